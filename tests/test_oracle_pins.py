@@ -1,0 +1,394 @@
+"""Pins of the CPU oracle to things other than itself (CPU only).
+
+Each test checks an oracle step against a closed form, an invariant, a library
+routine on a special case, a brute-force restatement with a different structure,
+or finite differences - chosen so that a dropped term, a wrong sign or index or
+a transposed operand fails at least one of them.  Citations are to the paper's
+sections / equations.
+"""
+import os
+
+import numpy as np
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------------------
+# Router (Sec. 1.1 definition; Sec. 2.1.2 item 2)
+# ---------------------------------------------------------------------------
+def test_router_closed_form_golden(oracle):
+    """Worked closed-form cases stored in tests/golden/router_closed_form.txt."""
+    path = os.path.join(HERE, "golden", "router_closed_form.txt")
+    cases = []
+    with open(path) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            score, norm, k, ratios, idx, w = [s.strip() for s in line.split("|")]
+            cases.append((int(score), int(norm), int(k), [float(v) for v in ratios.split()],
+                          [int(v) for v in idx.split()], [float(v) for v in w.split()]))
+    assert len(cases) >= 4
+    for score, norm, k, ratios, idx_exp, w_exp in cases:
+        r = np.array(ratios, np.float64)
+        # softmax rows are given as odds e^l (l = ln r); sigmoid rows as odds s/(1-s) (l = ln r)
+        logits = np.log(r).astype(np.float32)[None, :]
+        idx, w, counts = oracle.route_topk(logits, k, score, bool(norm))
+        assert idx[0].tolist() == idx_exp
+        np.testing.assert_allclose(w[0], w_exp, rtol=2e-7)  # fp32 logits carry ~6e-8 relative error
+        assert counts.sum() == k
+
+
+@pytest.mark.parametrize("score", [0, 1])
+@pytest.mark.parametrize("norm", [False, True])
+def test_router_vs_bruteforce_sort(oracle, score, norm):
+    g = _rng(3)
+    T, E, k = 200, 37, 5
+    logits = g.standard_normal((T, E)).astype(np.float32)
+    idx, w, counts = oracle.route_topk(logits, k, score, norm, scale=2.5)
+    l64 = logits.astype(np.float64)
+    if score == 0:
+        s = np.exp(l64 - l64.max(1, keepdims=True))
+        s /= s.sum(1, keepdims=True)
+        np.testing.assert_allclose(s.sum(1), 1.0, rtol=1e-14)
+    else:
+        s = 1.0 / (1.0 + np.exp(-l64))
+    # selection on the scores (what the paper states) == selection on the logits (what the oracle does)
+    order = np.argsort(-s, axis=1, kind="stable")[:, :k]
+    assert np.array_equal(order, idx)
+    ws = np.take_along_axis(s, order, 1)
+    if norm:
+        ws = ws / ws.sum(1, keepdims=True)
+        np.testing.assert_allclose(w.sum(1), 2.5, rtol=1e-13)
+    np.testing.assert_allclose(w, 2.5 * ws, rtol=1e-12)
+    assert np.all(w >= 0)
+    assert np.array_equal(counts, np.bincount(order.ravel(), minlength=E))
+    assert counts.sum() == T * k
+    # descending slot order
+    assert np.all(np.diff(np.take_along_axis(l64, idx.astype(np.int64), 1), axis=1) <= 0)
+
+
+def test_router_k_equals_E_and_ties(oracle):
+    g = _rng(4)
+    logits = g.standard_normal((16, 6)).astype(np.float32)
+    idx, w, counts = oracle.route_topk(logits, 6, 0, False)
+    assert np.all(np.sort(idx, 1) == np.arange(6))
+    np.testing.assert_allclose(w.sum(1), 1.0, rtol=1e-14)      # softmax over all experts sums to one
+    assert np.all(counts == 16)
+    # ties: equal logits -> lower expert index first
+    t = np.array([[1.0, 3.0, 3.0, 0.5, 3.0, 1.0]], np.float32)
+    idx, w, _ = oracle.route_topk(t, 4, 1, True)
+    assert idx[0].tolist() == [1, 2, 4, 0]
+    np.testing.assert_allclose(w.sum(), 1.0, rtol=1e-14)
+    assert w[0, 0] == w[0, 1] == w[0, 2]
+    # f32 instantiation selects the same experts
+    idx32, w32, _ = oracle.route_topk(logits, 3, 0, False, prec="f32")
+    idx64, w64, _ = oracle.route_topk(logits, 3, 0, False, prec="f64")
+    assert np.array_equal(idx32, idx64)
+    np.testing.assert_allclose(w32, w64, rtol=1e-6)
+
+
+# ---------------------------------------------------------------------------
+# Row-ID map and permute (Sec. 4.3.3 "Preprocessing", "Permute"; Sec. 5.4.1 padding)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("align", [1, 16, 128])
+def test_maps_equal_stable_sort(oracle, align):
+    g = _rng(5)
+    T, k, E = 333, 3, 7
+    idx = g.integers(-1, E + 1, size=(T, k)).astype(np.int32)   # includes -1 and E: "not on this GPU"
+    idx[:, 0] = np.where(idx[:, 0] == 5, 4, idx[:, 0])           # make expert 5 rarer
+    idx[idx == 3] = 2                                            # expert 3 gets no rows at all
+    m = oracle.permute_maps(idx, E, align)
+    flat = idx.ravel()
+    valid = (flat >= 0) & (flat < E)
+    counts = np.bincount(flat[valid], minlength=E)
+    assert np.array_equal(m.counts, counts) and counts[3] == 0
+    pad = (counts + align - 1) // align * align
+    assert np.array_equal(m.offsets, np.concatenate([[0], np.cumsum(pad)]))
+    assert m.Rtot == pad.sum()
+    # textbook: stable sort of the flattened ids by expert
+    order = np.argsort(np.where(valid, flat, E + 1), kind="stable")[: valid.sum()]
+    pos = 0
+    for e in range(E):
+        seg = m.src_of[m.offsets[e]: m.offsets[e] + counts[e]]
+        assert np.array_equal(seg, order[pos: pos + counts[e]])
+        assert np.all(flat[seg] == e)
+        assert np.all(np.diff(seg) > 0)
+        assert np.all(m.src_of[m.offsets[e] + counts[e]: m.offsets[e + 1]] == -1)   # pad rows
+        pos += counts[e]
+    assert np.all(m.src_of[m.Rtot:] == -1)
+    ro = m.row_of.ravel()
+    assert np.all(ro[~valid] == -1)
+    assert np.array_equal(m.src_of[ro[valid]], np.nonzero(valid)[0])
+    # rows: copies of the source token, pad rows zero
+    X = g.standard_normal((T, 10))
+    Xp = oracle.permute_rows(X, m.src_of[: m.Rtot], k)
+    live = m.src_of[: m.Rtot] >= 0
+    assert np.array_equal(Xp[live], X[m.src_of[: m.Rtot][live] // k])
+    assert np.all(Xp[~live] == 0)
+    with pytest.raises(ValueError):
+        oracle.permute_maps(idx, E, align, Rcap=m.Rtot - 1)
+
+
+def test_permute_combine_round_trip(oracle):
+    """Unpermute is the inverse of permute and sums the k copies (Sec. 4.3.3): w = 1/k returns X exactly."""
+    g = _rng(6)
+    T, k, E, h = 100, 4, 9, 24
+    idx = np.stack([g.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    X = g.standard_normal((T, h))
+    m = oracle.permute_maps(idx, E, 8)
+    Xp = oracle.permute_rows(X, m.src_of[: m.Rtot], k)
+    Y = oracle.combine(Xp, m.row_of, np.full((T, k), 0.25), None)
+    assert np.array_equal(Y, X)
+    res = g.standard_normal((T, h))
+    Y1 = oracle.combine(Xp, m.row_of, None, res)            # w == 1, residual (shared expert slot) added
+    np.testing.assert_allclose(Y1, 4 * X + res, rtol=1e-14, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------
+# Expert GEMMs (Sec. 2.1.4, 4.3.2) against numpy on special cases
+# ---------------------------------------------------------------------------
+def _offsets(counts):
+    return np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+
+
+@pytest.mark.parametrize("prec,tol", [("f64", 1e-13), ("f32", 2e-5)])
+def test_grouped_gemms_vs_numpy(oracle, prec, tol):
+    g = _rng(7)
+    counts = np.array([5, 0, 17, 1, 9])
+    E, N, K = len(counts), 11, 13
+    R = counts.sum()
+    off = _offsets(counts)
+    A = g.standard_normal((R, K))
+    B = g.standard_normal((E, N, K))
+    dC = g.standard_normal((R, N))
+    Cm = oracle.grouped_gemm_nt(A, B, off, prec=prec)
+    dA = oracle.grouped_gemm_nn(dC, B, off, prec=prec)
+    dB = oracle.grouped_gemm_tn(dC, A, off, prec=prec)
+    for e in range(E):
+        s = slice(off[e], off[e + 1])
+        np.testing.assert_allclose(Cm[s], A[s] @ B[e].T, rtol=tol, atol=tol)
+        np.testing.assert_allclose(dA[s], dC[s] @ B[e], rtol=tol, atol=tol)
+        np.testing.assert_allclose(dB[e], dC[s].T @ A[s], rtol=tol, atol=tol)
+    assert np.all(dB[1] == 0)                                   # zero-token expert: exact zero gradient
+    # row subset and output window agree with the full result
+    rows = np.array([0, 4, 5, 21, 22, 31], np.int32)
+    np.testing.assert_array_equal(oracle.grouped_gemm_nt(A, B, off, rows=rows, prec=prec), Cm[rows])
+    np.testing.assert_array_equal(oracle.grouped_gemm_nn(dC, B, off, rows=rows, prec=prec), dA[rows])
+    np.testing.assert_array_equal(oracle.grouped_gemm_tn(dC, A, off, window=(3, 4, 2, 7), prec=prec),
+                                  dB[:, 3:7, 2:9])
+    # E == 1 is an ordinary dense GEMM
+    one = np.array([0, R], np.int32)
+    np.testing.assert_allclose(oracle.grouped_gemm_nt(A, B[:1], one, prec=prec), A @ B[0].T, rtol=tol, atol=tol)
+
+
+def test_swiglu_closed_form(oracle):
+    # silu(0) = 0; silu(g) -> g for large g; silu(-g) = -g * sigmoid(-g); odd/even parts
+    Z = np.array([[0.0, 40.0, -40.0, np.log(3.0), 7.0, 2.0, 3.0, -5.0]])
+    A = oracle.swiglu(Z)
+    np.testing.assert_allclose(A[0], [0.0, 80.0, -40.0 * np.exp(-40.0) / (1 + np.exp(-40.0)) * 3.0,
+                                      np.log(3.0) * 0.75 * -5.0], rtol=1e-14, atol=0)
+    g = _rng(8)
+    Z = g.standard_normal((6, 10))
+    gate, up = Z[:, :5], Z[:, 5:]
+    np.testing.assert_allclose(oracle.swiglu(Z), gate / (1 + np.exp(-gate)) * up, rtol=1e-14)
+    # silu(g) - silu(-g) = g
+    Zm = Z.copy()
+    Zm[:, :5] *= -1
+    np.testing.assert_allclose(oracle.swiglu(Z) - oracle.swiglu(Zm), gate * up, rtol=1e-12, atol=1e-15)
+
+
+# ---------------------------------------------------------------------------
+# The whole layer against the definition written another way (Sec. 1.1; Sec. 4.1.2 eq. (1), (2))
+# ---------------------------------------------------------------------------
+def _dense_definition(X, idx, prob, W1, W2):
+    """MoE(x) = sum_{i in TopK} p_i E_i(x): every expert applied to every token, then masked."""
+    T, k = idx.shape
+    E, f2, h = W1.shape
+    f = f2 // 2
+    Y = np.zeros((T, h))
+    for e in range(E):
+        Zd = X @ W1[e].T
+        Ad = Zd[:, :f] / (1 + np.exp(-Zd[:, :f])) * Zd[:, f:]
+        Od = Ad @ W2[e].T
+        gatew = np.where(idx == e, prob, 0.0).sum(1)
+        Y += gatew[:, None] * Od
+    return Y
+
+
+def _tiny_layer(seed, T=40, h=12, f=10, E=5, k=2, shared=True):
+    g = _rng(seed)
+    X = g.standard_normal((T, h))
+    logits = g.standard_normal((T, E)).astype(np.float32)
+    W1 = g.standard_normal((E, 2 * f, h)) * 0.4
+    W2 = g.standard_normal((E, h, f)) * 0.4
+    Ws1 = g.standard_normal((2 * 6, h)) * 0.4 if shared else None
+    Ws2 = g.standard_normal((h, 6)) * 0.4 if shared else None
+    dY = g.standard_normal((T, h))
+    return X, logits, W1, W2, Ws1, Ws2, dY
+
+
+@pytest.mark.parametrize("align", [1, 16])
+def test_layer_equals_dense_definition(oracle, align):
+    X, logits, W1, W2, Ws1, Ws2, _ = _tiny_layer(9)
+    E = W1.shape[0]
+    idx, prob, _ = oracle.route_topk(logits, 2, 1, True)
+    fw = oracle.layer_forward(X, idx, prob, W1, W2, E, align)
+    np.testing.assert_allclose(fw.Y, _dense_definition(X, idx, prob, W1, W2), rtol=1e-12, atol=1e-13)
+    # shared expert: plain dense SwiGLU MLP of every token, added at the combine stage (Sec. 2.1.1 stage 4)
+    fws = oracle.layer_forward(X, idx, prob, W1, W2, E, align, Ws1, Ws2)
+    Zs = X @ Ws1.T
+    fs = Ws1.shape[0] // 2
+    S = (Zs[:, :fs] / (1 + np.exp(-Zs[:, :fs])) * Zs[:, fs:]) @ Ws2.T
+    np.testing.assert_allclose(fws.Y, fw.Y + S, rtol=1e-12, atol=1e-13)
+    # eq. (1) == eq. (2): weights applied before W2 with a plain-sum combine
+    m = fw.maps
+    p_row = np.zeros(fw.R)
+    p_row[m.row_of.ravel()] = prob.ravel()
+    O2 = oracle.grouped_gemm_nt(fw.A * p_row[:, None], W2, m.offsets)
+    Y2 = oracle.combine(O2, m.row_of, None, None)
+    np.testing.assert_allclose(Y2, fw.Y, rtol=1e-12, atol=1e-13)
+
+
+def test_k1_p1_is_plain_mlp(oracle):
+    X, logits, W1, W2, *_ = _tiny_layer(10)
+    E, f2, _ = W1.shape
+    idx, _, _ = oracle.route_topk(logits, 1, 0, False)
+    fw = oracle.layer_forward(X, idx, np.ones_like(idx, dtype=np.float64), W1, W2, E)
+    for t in range(X.shape[0]):
+        e = idx[t, 0]
+        z = W1[e] @ X[t]
+        a = z[: f2 // 2] / (1 + np.exp(-z[: f2 // 2])) * z[f2 // 2:]
+        np.testing.assert_allclose(fw.Y[t], W2[e] @ a, rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------
+# Backward by central finite differences in double (routing frozen)
+# ---------------------------------------------------------------------------
+def test_backward_finite_differences(oracle):
+    X, logits, W1, W2, Ws1, Ws2, dY = _tiny_layer(11, T=12, h=6, f=5, E=4, k=2)
+    E = W1.shape[0]
+    idx, prob, _ = oracle.route_topk(logits, 2, 0, False)
+    # make one expert empty to cover the zero-token gradient
+    idx[idx == 2] = 0
+    idx[:, 1] = np.where(idx[:, 1] == idx[:, 0], (idx[:, 0] + 1) % 2, idx[:, 1])
+
+    def loss(X_, p_, W1_, W2_, Ws1_, Ws2_):
+        return float((oracle.layer_forward(X_, idx, p_, W1_, W2_, E, 4, Ws1_, Ws2_).Y * dY).sum())
+
+    fw = oracle.layer_forward(X, idx, prob, W1, W2, E, 4, Ws1, Ws2)
+    bw = oracle.layer_backward(fw, X, prob, W1, W2, dY, Ws1, Ws2)
+    assert np.all(bw.dW1[2] == 0) and np.all(bw.dW2[2] == 0)
+    args = [X, prob, W1, W2, Ws1, Ws2]
+    grads = [bw.dX + bw.dX_shared, bw.dprob, bw.dW1, bw.dW2, bw.dWs1, bw.dWs2]
+    g = _rng(12)
+    eps = 1e-6
+    for ai, (a, gr) in enumerate(zip(args, grads)):
+        assert gr.shape == a.shape
+        for _ in range(25):
+            pos = tuple(g.integers(s) for s in a.shape)
+            ap, am = a.copy(), a.copy()
+            ap[pos] += eps
+            am[pos] -= eps
+            lp = loss(*[ap if j == ai else args[j] for j in range(6)])
+            lm = loss(*[am if j == ai else args[j] for j in range(6)])
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - gr[pos]) <= 1e-6 * max(1.0, abs(fd)), (ai, pos, fd, gr[pos])
+
+
+def test_swiglu_bwd_and_combine_bwd_closed_forms(oracle):
+    g = _rng(13)
+    # d/dg silu(g) at g = 0 is 1/2; dZ_up = silu(g)
+    Z = np.array([[0.0, 2.0, 3.0, 5.0]])
+    dZ = oracle.swiglu_bwd(np.array([[1.0, 1.0]]), Z)
+    s2 = 1 / (1 + np.exp(-2.0))
+    np.testing.assert_allclose(dZ[0], [0.5 * 3.0, 5.0 * s2 * (1 + 2.0 * (1 - s2)), 0.0, 2.0 * s2], rtol=1e-14)
+    # combine backward: dO = w * dY gathered, dprob = <dY, O>
+    T, k, h, R = 7, 2, 5, 20
+    row_of = g.permutation(R)[: T * k].reshape(T, k).astype(np.int32)
+    row_of[2, 1] = -1
+    O = g.standard_normal((R, h))
+    dY = g.standard_normal((T, h))
+    p = g.random((T, k))
+    dO, dp = oracle.combine_bwd(dY, O, row_of, p, R)
+    for t in range(T):
+        for s in range(k):
+            r = row_of[t, s]
+            if r < 0:
+                assert dp[t, s] == 0
+                continue
+            np.testing.assert_allclose(dO[r], p[t, s] * dY[t], rtol=1e-15)
+            np.testing.assert_allclose(dp[t, s], dY[t] @ O[r], rtol=1e-13)
+    untouched = np.setdiff1d(np.arange(R), row_of.ravel())
+    assert np.all(dO[untouched] == 0)
+
+
+# ---------------------------------------------------------------------------
+# Blockwise FP8 (Sec. 5.3.2)
+# ---------------------------------------------------------------------------
+def test_e4m3_table(oracle):
+    """All 256 codes against the OCP E4M3 definition and against torch's float8_e4m3fn."""
+    vals = np.array([oracle.e4m3_decode(c) for c in range(256)])
+    assert vals[0x7E] == 448.0 and vals[0xFE] == -448.0
+    assert np.isnan(vals[0x7F]) and np.isnan(vals[0xFF])
+    assert not np.any(np.isinf(vals))
+    assert vals[0x01] == 2.0 ** -9 and vals[0x08] == 2.0 ** -6 and vals[0x38] == 1.0
+    fin = vals[:0x7F]
+    assert np.all(np.diff(fin) > 0)                              # codes are monotone in value
+    torch = pytest.importorskip("torch")
+    if hasattr(torch, "float8_e4m3fn"):
+        tv = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+        assert np.array_equal(np.nan_to_num(tv, nan=-1.0), np.nan_to_num(vals, nan=-1.0).astype(np.float32))
+    # idempotence and rounding
+    for c in list(range(0x7F)) + list(range(0x81, 0xFF)):
+        assert oracle.e4m3_encode(vals[c]) == c
+    assert oracle.e4m3_encode(1e9) == 0x7E and oracle.e4m3_encode(-1e9) == 0xFE      # saturating
+    assert oracle.e4m3_encode(float("nan")) == 0x7F
+    # ties to even: halfway between 1.0 (0x38) and 1.125 (0x39) -> 0x38; between 1.125 and 1.25 (0x3A) -> 0x3A
+    assert oracle.e4m3_encode(1.0625) == 0x38 and oracle.e4m3_encode(1.1875) == 0x3A
+    assert oracle.e4m3_encode(2.0 ** -10) == 0x00 and oracle.e4m3_encode(3 * 2.0 ** -10) == 0x02
+    g = _rng(14)
+    x = (g.standard_normal(4000) * np.exp(g.uniform(-6, 5, 4000))).astype(np.float32)
+    x = x[np.abs(x) <= 448]
+    codes = np.array([oracle.e4m3_encode(v) for v in x], np.uint8)
+    if hasattr(torch, "float8_e4m3fn"):
+        tc = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        assert np.array_equal(tc & 0x7F, codes & 0x7F)
+        nz = (codes & 0x7F) != 0
+        assert np.array_equal(tc[nz], codes[nz])
+    normal = np.abs(x) >= 2.0 ** -6
+    rel = np.abs(vals[codes][normal] - x[normal]) / np.abs(x[normal])
+    assert rel.max() <= 2.0 ** -4
+
+
+def test_fp8_block_quantisers(oracle):
+    g = _rng(15)
+    X = (g.standard_normal((256, 384)) * np.exp(g.uniform(-3, 3, (256, 1)))).astype(np.float32)
+    X[5, 128:256] = 0.0                                           # an all-zero tile: scale 1, codes 0
+    for mode, fn in (("1x128", oracle.fp8_quant_1x128), ("128x1", oracle.fp8_quant_128x1)):
+        q, s = fn(X)
+        blocks = X.reshape(256, 3, 128) if mode == "1x128" else X.reshape(2, 128, 384).transpose(0, 2, 1)
+        amax = np.abs(blocks).max(-1)
+        np.testing.assert_array_equal(s, np.where(amax > 0, amax / np.float32(448), np.float32(1)))
+        qb = q.reshape(256, 3, 128) if mode == "1x128" else q.reshape(2, 128, 384).transpose(0, 2, 1)
+        assert np.all(((qb & 0x7F).max(-1) == 0x7E) | (amax == 0))   # the block's amax maps to +-448
+        D = oracle.fp8_dequant(q, s, mode)
+        sfull = np.repeat(s, 128, axis=1) if mode == "1x128" else np.repeat(s, 128, axis=0)
+        assert np.all(np.abs(D - X) <= 2.0 ** -4 * np.abs(X) + sfull * 2.0 ** -10)
+    q, s = oracle.fp8_quant_1x128(X)
+    assert s[5, 1] == 1.0 and np.all(q[5, 128:256] == 0)
+    W = g.standard_normal((2, 256, 128)).astype(np.float32)
+    qw, sw = oracle.fp8_quant_128x128(W)
+    amax = np.abs(W.reshape(2, 2, 128, 1, 128)).max((2, 4))
+    np.testing.assert_array_equal(sw, amax / np.float32(448))
+    Dw = oracle.fp8_dequant(qw, sw, "128x128")
+    assert np.abs(Dw - W).max() <= 2.0 ** -4 * np.abs(W).max()
+    # a transposed 1x128 quantisation equals the 128x1 quantisation
+    qt, st = oracle.fp8_quant_1x128(np.ascontiguousarray(X.T))
+    qc, sc = oracle.fp8_quant_128x1(X)
+    assert np.array_equal(qt.T, qc) and np.array_equal(st.T, sc)
