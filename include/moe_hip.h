@@ -1,0 +1,230 @@
+/*
+ * moe_hip.h - C ABI of the MI355X (gfx950) MoE expert-layer library.
+ *
+ * The calls follow the paper's statement of the layer: Route -> Dispatch
+ * (permute) -> Expert computation (Grouped GEMM) -> Combine (Sec. 2.1.1), with
+ * the backward MLP split into a data-gradient and a weight-gradient call
+ * (Sec. 4.2.3, "W/D split") and every dynamic shape left on the device
+ * (Sec. 4.3.7, "device-initiated kernels").
+ *
+ * Conventions that hold for every call unless the call says otherwise
+ *   - Pointers are DEVICE pointers owned by the caller, except the ones marked
+ *     "host".  The library allocates nothing in these calls; its only memory is
+ *     the context workspace (moe_ctx_create).
+ *   - Tensors are row-major with the innermost dimension contiguous and the
+ *     base address 16-byte aligned.  bf16 = 16-bit brain float, fp8 = OCP E4M3
+ *     (bias 7, no infinities, max 448) stored one code per byte.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work: no host synchronisation, no device-to-host copy
+ *     of the per-expert counts (Sec. 4.3.7, challenge 1).  Launch sizes come from
+ *     the static arguments (T, k, E, Rcap ...); the kernels read the actual
+ *     extents from `offsets` on the device and skip what lies beyond them.
+ *   - Return value: MOE_OK or a negative moe_status.  Argument errors are found
+ *     on the host before anything is launched; nothing is written then.
+ *     moe_last_error gives a host string describing the last failure on a context.
+ *   - Calls on one context from several host threads at once are not supported.
+ *   - Same inputs give bit-identical outputs from run to run (no floating-point
+ *     atomics anywhere; integer atomics only where the result is order-free).
+ */
+#ifndef MOE_HIP_H
+#define MOE_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx; /* opaque: device id, workspace, last error */
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_ARG = -1,         /* NULL pointer, size out of range, misaligned size */
+    MOE_ERR_UNSUPPORTED = -2, /* valid request the library has no kernel for */
+    MOE_ERR_WORKSPACE = -3,   /* context workspace too small for this call */
+    MOE_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
+} moe_status;
+
+typedef enum { MOE_BF16 = 0, MOE_FP8_E4M3 = 1, MOE_F32 = 2 } moe_dtype;
+typedef enum { MOE_SCORE_SOFTMAX = 0, MOE_SCORE_SIGMOID = 1 } moe_score;
+typedef enum { MOE_EPI_NONE = 0, MOE_EPI_SWIGLU = 1 } moe_epilogue;
+
+/* ------------------------------------------------------------------------- */
+/* Context                                                                   */
+/* ------------------------------------------------------------------------- */
+
+/* Bytes of workspace the calls below need for problems up to the given sizes
+ * (host, pure function).  T tokens, k slots per token, E experts, h hidden,
+ * f_max the largest expert width used with this context. */
+size_t moe_workspace_bytes(int T, int k, int E, int h, int f_max);
+
+/* Create a context on `device` and allocate `workspace_bytes` of device memory
+ * for it (hipMalloc; the only allocation the library ever makes).  *out is
+ * written only on success.  Host call; synchronises the device. */
+moe_status moe_ctx_create(moe_ctx** out, int device, size_t workspace_bytes);
+
+/* Free the workspace and the context.  Pending work that uses the context
+ * must have finished.  NULL is accepted. */
+moe_status moe_ctx_destroy(moe_ctx* ctx);
+
+/* Host string for the last error recorded on ctx ("" if none); owned by ctx. */
+const char* moe_last_error(const moe_ctx* ctx);
+
+/* Kernels that find a device-side inconsistency (offsets[E] > Rcap) skip the
+ * work and set a device error word instead of writing out of bounds.  This
+ * call waits for `stream`, copies the word to *device_error (host; 0 = none)
+ * and clears it.  It is the only call that synchronises. */
+moe_status moe_ctx_poll_error(moe_ctx* ctx, void* stream, int* device_error);
+
+/* ------------------------------------------------------------------------- */
+/* Stage 1: Route (Sec. 2.1.1 stage 1; Sec. 2.1.2 item 2; fused as in Sec. 4.3.4)*/
+/* ------------------------------------------------------------------------- */
+/*
+ * Per token: score function over the E logits, the k highest experts, their
+ * combine weights, and the per-expert histogram, in one fused kernel.  The gate
+ * projection x*W_r is not part of this call (Sec. 4.3.4 leaves the GEMM outside
+ * the fused router): `logits` [T,E] fp32 is the input.
+ *
+ *   fn = SOFTMAX : p_i = exp(l_i) / sum over all E;   fn = SIGMOID : p_i = 1/(1+exp(-l_i)).
+ *   Selection: the k largest logits (both score functions are strictly
+ *   increasing, so this is the set with the k highest scores); equal logits go
+ *   to the lower expert index; slot 0 holds the largest.
+ *   Weights: w = p_i, divided by the sum of the k selected p when norm_topk != 0,
+ *   then multiplied by `scale`.
+ * Outputs: topk_idx [T,k] int32, topk_prob [T,k] fp32, counts [E] int32
+ * (counts may be NULL).  Limits: 1 <= k <= 32, k <= E <= 1024.  NaN logits are
+ * not supported (selection is then unspecified, nothing faults).
+ */
+moe_status moe_route_topk(moe_ctx* ctx, void* stream, const float* logits, int T, int E, int k,
+                          moe_score fn, int norm_topk, float scale,
+                          int32_t* topk_idx, float* topk_prob, int32_t* counts);
+
+/* ------------------------------------------------------------------------- */
+/* Stage 2: Dispatch = permute (Sec. 4.3.3 "Preprocessing" + "Permute")      */
+/* ------------------------------------------------------------------------- */
+/*
+ * Builds the row-ID map once (a stable counting sort of the T*k (token, slot)
+ * pairs by expert) and moves the token rows into expert-contiguous order, each
+ * token copied once per slot.  Per-expert zero padding to a multiple of `align`
+ * rows is fused into the move (Sec. 5.4.1).
+ *
+ *   idx [T,k] int32: expert of each slot; values < 0 or >= E mean "not on this
+ *       GPU" and produce no row.
+ *   X [T,h] of dtype dt (MOE_BF16 or MOE_F32), or NULL to build the maps only.
+ *   Xp [Rcap,h]: rows [offsets[e], offsets[e]+counts[e]) hold expert e's tokens in
+ *       increasing flattened index t*k+s; rows up to offsets[e+1] are zero;
+ *       rows >= offsets[E] are left untouched.
+ *   row_of [T,k]: row of each slot, -1 if skipped.  src_of [Rcap]: t*k+s of each
+ *       row, -1 for padding and for rows >= offsets[E].
+ *   offsets [E+1]: padded group starts (offsets[0] = 0).  counts [E]: unpadded.
+ *   Rcap must be >= T*k + E*(align-1) (checked on the host, so the device can
+ *   never overflow it); align >= 1; h*sizeof(dt) must be a multiple of 16.
+ * Uses the context workspace (moe_workspace_bytes).
+ */
+moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe_dtype dt,
+                       const int32_t* idx, int T, int k, int h, int E, int align,
+                       void* Xp, int64_t Rcap,
+                       int32_t* row_of, int32_t* src_of, int32_t* offsets, int32_t* counts);
+
+/* ------------------------------------------------------------------------- */
+/* Stage 3: Expert computation = Grouped GEMM (Sec. 2.1.4, 4.3.2, 4.3.7)      */
+/* ------------------------------------------------------------------------- */
+/*
+ * All three calls run every expert's GEMM in one persistent launch.  Rows
+ * [offsets[e], offsets[e+1]) of the row-indexed operands belong to expert e;
+ * `offsets` [E+1] int32 stays on the device.  Rows >= offsets[E] are neither
+ * read nor written.  Weights are B [E,N,K] ("out, in" per expert: the layout of
+ * an expert's Linear weight), no bias (Sec. 4.1.2 needs bias-free experts).
+ * dt is the operand type: MOE_BF16 (fp32 accumulation, bf16 result) or
+ * MOE_FP8_E4M3 (blockwise recipe of Sec. 5.3.2: operands are E4M3 codes with
+ * fp32 scales, fp32 accumulation, bf16 result).  N and K must be multiples of
+ * 128 (fp8) / 16 (bf16: K % 32 == 0 for the contraction dimension).
+ *
+ * fwd:   C[r,n] = sum_k A[r,k] * B[e(r),n,k]                    A [Rcap,K], C [Rcap,N]
+ *        epi = MOE_EPI_SWIGLU (N = 2f): C holds the pre-activation Z = [gate | up]
+ *        (kept for backward) and C_act [Rcap,f] = silu(gate) * up, computed from
+ *        the fp32 accumulators.  C may be NULL with SWIGLU to skip storing Z.
+ *        fp8: a_scale [Rcap,K/128] (1x128 tiles along K), b_scale [E,N/128,K/128].
+ */
+moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const void* A, const void* B,
+                                const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                moe_dtype dt, moe_epilogue epi,
+                                const float* a_scale, const float* b_scale,
+                                void* C, void* C_act);
+
+/*
+ * dgrad: dA[r,k] = sum_n dC[r,n] * B[e(r),n,k]                  dC [Rcap,N], dA [Rcap,K]
+ *        Z_saved != NULL (the fc2 data gradient, K = f): Z_saved [Rcap,2K] is the
+ *        pre-activation fc1 stored; the SwiGLU backward is fused into the epilogue
+ *        and the output is dZ [Rcap,2K] = [dA*up*silu'(gate) | dA*silu(gate)].
+ *        fp8: dc_scale [Rcap,N/128] (1x128 tiles along N), b_scale as in fwd.
+ */
+moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const void* dC, const void* B,
+                                  const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                  moe_dtype dt, const void* Z_saved,
+                                  const float* dc_scale, const float* b_scale, void* dA);
+
+/*
+ * wgrad: dB[e,n,k] = sum over rows r of expert e of dC[r,n] * A[r,k]
+ *        The contraction length is the expert's (padded) row count, read from
+ *        `offsets`; an expert with no rows gets dB_e = 0 (accumulate = 0) or is
+ *        left as it is (accumulate != 0: dB += ...).  out_dt: MOE_BF16 or MOE_F32.
+ *        fp8: both operands are quantised in 128x1 tiles down the token dimension
+ *        (dc_scale [Rcap/128,N], a_scale [Rcap/128,K]); every offsets[e] must then
+ *        be a multiple of 128 (moe_permute with align = 128).
+ */
+moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, const void* dC,
+                                  const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                  moe_dtype dt, const float* a_scale, const float* dc_scale,
+                                  int accumulate, moe_dtype out_dt, void* dB);
+
+/* ------------------------------------------------------------------------- */
+/* Stage 4: Combine = unpermute + weighted sum (Sec. 4.3.3 "Unpermute"; eq. (1))*/
+/* ------------------------------------------------------------------------- */
+/*
+ * Y[t,:] = sum_s prob[t,s] * O[row_of[t,s],:]  (+ residual[t,:]),  accumulated in
+ * fp32 and rounded once to dt.  prob == NULL means weight 1 (the plain sum used
+ * for the backward of permute and for eq. (2)); residual [T,h] is the shared
+ * expert's output, added here (Sec. 2.1.1 stage 4), or NULL.  Slots with
+ * row_of < 0 contribute nothing.  dt: MOE_BF16 or MOE_F32 (O, residual and Y).
+ */
+moe_status moe_unpermute_combine(moe_ctx* ctx, void* stream, const void* O, moe_dtype dt,
+                                 const int32_t* row_of, const float* prob, const void* residual,
+                                 int T, int k, int h, void* Y);
+
+/*
+ * Backward of the combine for L = <dY, Y>:
+ *   dO[r,:] = prob[t,s] * dY[t,:] for the slot (t,s) = src_of[r], zero for padding
+ *   rows (src_of[r] < 0);  dprob[t,s] = <dY[t,:], O[row_of[t,s],:]> in fp32 (0 for
+ *   skipped slots).  O may be NULL together with dprob to skip the dot products.
+ *   dO is written for all Rcap rows.
+ */
+moe_status moe_unpermute_combine_bwd(moe_ctx* ctx, void* stream, const void* dY, const void* O,
+                                     moe_dtype dt, const int32_t* row_of, const int32_t* src_of,
+                                     const float* prob, int T, int k, int h, int64_t Rcap,
+                                     void* dO, float* dprob);
+
+/* ------------------------------------------------------------------------- */
+/* Blockwise FP8 quantisation (Sec. 5.3.2; grouped, shapes on device: Sec. 5.4.2)*/
+/* ------------------------------------------------------------------------- */
+/*
+ * X bf16 -> E4M3 codes q (same shape, one byte each) + fp32 scales.
+ *   scale = amax(block) / 448 (1 if the block is all zero), code = nearest E4M3
+ *   to clamp(x / scale, +-448), division and rounding in fp32, ties to even.
+ *   block = MOE_Q_1x128  : 128 consecutive elements of a row;   scale [rows, cols/128]
+ *           MOE_Q_128x1  : 128 consecutive rows of a column;    scale [rows/128, cols]
+ *           MOE_Q_128x128: square blocks of each [rows,cols] matrix of a stack of
+ *                          `groups` matrices;                   scale [groups, rows/128, cols/128]
+ *   rows_dev: optional device int32 holding the number of rows actually in use
+ *   (e.g. &offsets[E]); rows beyond it are skipped.  NULL = all `rows`.
+ */
+typedef enum { MOE_Q_1x128 = 0, MOE_Q_128x1 = 1, MOE_Q_128x128 = 2 } moe_qblock;
+moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X, moe_qblock block,
+                            int groups, int64_t rows, int cols, const int32_t* rows_dev,
+                            void* q, float* scale);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HIP_H */

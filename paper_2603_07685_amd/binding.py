@@ -1,0 +1,156 @@
+"""ctypes binding of libmoe_hip.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+include/moe_hip.h.  Tensors are torch CUDA tensors used as device memory; the
+current torch stream is passed as the HIP stream.  Nothing here computes: if
+the library is missing the import of `lib()` raises, there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmoe_hip.so")
+_lib = None
+
+BF16, FP8_E4M3, F32 = 0, 1, 2
+SOFTMAX, SIGMOID = 0, 1
+EPI_NONE, EPI_SWIGLU = 0, 1
+Q_1x128, Q_128x1, Q_128x128 = 0, 1, 2
+
+EXPORTS = [
+    "moe_workspace_bytes", "moe_ctx_create", "moe_ctx_destroy", "moe_last_error", "moe_ctx_poll_error",
+    "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
+    "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
+]
+
+_vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
+
+
+class MoeError(RuntimeError):
+    pass
+
+
+def lib() -> C.CDLL:
+    """Load libmoe_hip.so (built by paper_2603_07685_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise MoeError(f"{LIB_PATH} is not built: run `python -m paper_2603_07685_amd.build` first "
+                           "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        L.moe_workspace_bytes.restype = C.c_size_t
+        L.moe_workspace_bytes.argtypes = [_i] * 5
+        L.moe_ctx_create.argtypes = [C.POINTER(_vp), _i, C.c_size_t]
+        L.moe_ctx_destroy.argtypes = [_vp]
+        L.moe_last_error.restype = C.c_char_p
+        L.moe_last_error.argtypes = [_vp]
+        L.moe_ctx_poll_error.argtypes = [_vp, _vp, C.POINTER(_i)]
+        L.moe_route_topk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp]
+        L.moe_permute.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _vp, _i64, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_dgrad.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_wgrad.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _i, _i, _vp]
+        L.moe_unpermute_combine.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _vp]
+        L.moe_unpermute_combine_bwd.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i64, _vp, _vp]
+        L.moe_fp8_quantize.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _vp]
+        for name in EXPORTS:
+            if name not in ("moe_workspace_bytes", "moe_last_error"):
+                getattr(L, name).restype = _i
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Context:
+    """Owns a moe_ctx (device workspace + error state)."""
+
+    def __init__(self, T, k, E, h, f_max, device=0):
+        L = lib()
+        self.bytes = int(L.moe_workspace_bytes(T, k, E, h, f_max))
+        h_ = _vp()
+        st = L.moe_ctx_create(C.byref(h_), device, self.bytes)
+        if st != 0:
+            raise MoeError(f"moe_ctx_create failed with status {st}")
+        self.h = h_
+
+    def check(self, st, what):
+        if st != 0:
+            raise MoeError(f"{what}: status {st}: {lib().moe_last_error(self.h).decode()}")
+
+    def poll_error(self) -> int:
+        v = _i(0)
+        self.check(lib().moe_ctx_poll_error(self.h, _stream(), C.byref(v)), "moe_ctx_poll_error")
+        return v.value
+
+    def close(self):
+        if self.h:
+            lib().moe_ctx_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_workspace_bytes(T, k, E, h, f_max):
+    return int(lib().moe_workspace_bytes(T, k, E, h, f_max))
+
+
+def moe_route_topk(ctx, logits, T, E, k, fn, norm_topk, scale, topk_idx, topk_prob, counts):
+    ctx.check(lib().moe_route_topk(ctx.h, _stream(), _ptr(logits), T, E, k, fn, int(norm_topk), scale,
+                                   _ptr(topk_idx), _ptr(topk_prob), _ptr(counts)), "moe_route_topk")
+
+
+def moe_permute(ctx, X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts):
+    ctx.check(lib().moe_permute(ctx.h, _stream(), _ptr(X), dt, _ptr(idx), T, k, h, E, align, _ptr(Xp), Rcap,
+                                _ptr(row_of), _ptr(src_of), _ptr(offsets), _ptr(counts)), "moe_permute")
+
+
+def moe_grouped_gemm_fwd(ctx, A, B, offsets, E, N, K, Rcap, dt, epi, a_scale, b_scale, Cout, C_act):
+    ctx.check(lib().moe_grouped_gemm_fwd(ctx.h, _stream(), _ptr(A), _ptr(B), _ptr(offsets), E, N, K, Rcap, dt, epi,
+                                         _ptr(a_scale), _ptr(b_scale), _ptr(Cout), _ptr(C_act)),
+              "moe_grouped_gemm_fwd")
+
+
+def moe_grouped_gemm_dgrad(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_saved, dc_scale, b_scale, dA):
+    ctx.check(lib().moe_grouped_gemm_dgrad(ctx.h, _stream(), _ptr(dC), _ptr(B), _ptr(offsets), E, N, K, Rcap, dt,
+                                           _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(dA)),
+              "moe_grouped_gemm_dgrad")
+
+
+def moe_grouped_gemm_wgrad(ctx, A, dC, offsets, E, N, K, Rcap, dt, a_scale, dc_scale, accumulate, out_dt, dB):
+    ctx.check(lib().moe_grouped_gemm_wgrad(ctx.h, _stream(), _ptr(A), _ptr(dC), _ptr(offsets), E, N, K, Rcap, dt,
+                                           _ptr(a_scale), _ptr(dc_scale), int(accumulate), out_dt, _ptr(dB)),
+              "moe_grouped_gemm_wgrad")
+
+
+def moe_unpermute_combine(ctx, O, dt, row_of, prob, residual, T, k, h, Y):
+    ctx.check(lib().moe_unpermute_combine(ctx.h, _stream(), _ptr(O), dt, _ptr(row_of), _ptr(prob), _ptr(residual),
+                                          T, k, h, _ptr(Y)), "moe_unpermute_combine")
+
+
+def moe_unpermute_combine_bwd(ctx, dY, O, dt, row_of, src_of, prob, T, k, h, Rcap, dO, dprob):
+    ctx.check(lib().moe_unpermute_combine_bwd(ctx.h, _stream(), _ptr(dY), _ptr(O), dt, _ptr(row_of), _ptr(src_of),
+                                              _ptr(prob), T, k, h, Rcap, _ptr(dO), _ptr(dprob)),
+              "moe_unpermute_combine_bwd")
+
+
+def moe_fp8_quantize(ctx, X, block, groups, rows, cols, rows_dev, q, scale):
+    ctx.check(lib().moe_fp8_quantize(ctx.h, _stream(), _ptr(X), block, groups, rows, cols, _ptr(rows_dev), _ptr(q),
+                                     _ptr(scale)), "moe_fp8_quantize")

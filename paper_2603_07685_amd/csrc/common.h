@@ -1,0 +1,64 @@
+// Internal definitions shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "moe_hip.h"
+
+struct moe_ctx {
+    int device;
+    void* ws;          // device workspace
+    size_t ws_bytes;
+    int* dev_err;      // device error word (first 256 bytes of ws are reserved for it)
+    int num_cu;
+    char err[512];
+};
+
+#define MOE_WS_RESERVED 256  // bytes at the head of the workspace kept for the error word
+
+#define MOE_FAIL(ctx, code, ...)                                   \
+    do {                                                           \
+        if (ctx) snprintf((ctx)->err, sizeof((ctx)->err), __VA_ARGS__); \
+        return (code);                                             \
+    } while (0)
+
+#define MOE_HIP_CHECK(ctx, expr)                                                        \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess) MOE_FAIL(ctx, MOE_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+#define MOE_LAUNCH_CHECK(ctx, name)                                                     \
+    do {                                                                                \
+        hipError_t e_ = hipGetLastError();                                              \
+        if (e_ != hipSuccess) MOE_FAIL(ctx, MOE_ERR_HIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+static inline size_t moe_dtype_size(moe_dtype dt) { return dt == MOE_F32 ? 4 : (dt == MOE_BF16 ? 2 : 1); }
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// --- device helpers --------------------------------------------------------
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// two fp32 -> packed bf16 pair, round to nearest even (hardware conversion on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    bf16x2_t v;
+    v[0] = (bf16_t)lo;
+    v[1] = (bf16_t)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// shared by the fill launches of several files
+void moe_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s);

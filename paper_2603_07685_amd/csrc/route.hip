@@ -1,0 +1,127 @@
+// moe_route_topk: fused score function + top-k + weights + histogram (Sec. 2.1.2 item 2, Sec. 4.3.4).
+//
+// One 64-lane wavefront owns one token.  Lane l holds the logits of experts
+// l, l+64, l+128, ... in registers; the max / sum of the score function and each
+// of the k arg-max rounds are butterfly reductions over the wavefront, so a
+// token costs one coalesced read of its E logits and no LDS traffic.  Selection
+// is done on the raw logits (lower index wins ties), weights are computed for
+// the k winners only.  A workgroup accumulates its tokens' histogram in LDS and
+// adds it to the global counts once.
+#include "common.h"
+
+#define ROUTE_MAX_VPL 16          // values per lane -> E <= 1024
+#define ROUTE_WAVES 4
+#define ROUTE_TOKENS_PER_WAVE 8
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+template <int VPL>
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void route_topk_kernel(
+    const float* __restrict__ logits, int T, int E, int k, int fn, int norm_topk, float scale,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_prob, int32_t* __restrict__ counts) {
+    extern __shared__ int32_t hist[];  // [E]
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) hist[e] = 0;
+    __syncthreads();
+
+    const int t0 = (blockIdx.x * ROUTE_WAVES + wave) * ROUTE_TOKENS_PER_WAVE;
+    for (int tt = 0; tt < ROUTE_TOKENS_PER_WAVE; ++tt) {
+        const int t = t0 + tt;
+        if (t >= T) break;  // uniform per wave
+        const float* l = logits + (int64_t)t * E;
+        float v[VPL];
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+            int e = lane + 64 * j;
+            v[j] = e < E ? l[e] : -INFINITY;
+        }
+        float mx = 0.f, den = 1.f;
+        if (fn == MOE_SCORE_SOFTMAX) {
+            float m = v[0];
+#pragma unroll
+            for (int j = 1; j < VPL; ++j) m = fmaxf(m, v[j]);
+            mx = wave_max(m);
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) s += (lane + 64 * j < E) ? expf(v[j] - mx) : 0.f;
+            den = wave_sum(s);
+        }
+        // k rounds of arg-max over (logit desc, index asc)
+        uint32_t taken = 0;
+        float my_logit = 0.f;
+        int my_idx = 0;
+        for (int it = 0; it < k; ++it) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) {
+                int e = lane + 64 * j;
+                bool ok = e < E && !((taken >> j) & 1u);
+                if (ok && (bi == 0x7fffffff || v[j] > bv)) { bv = v[j]; bi = e; }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                float ov = __shfl_xor(bv, o);
+                int oi = __shfl_xor(bi, o);
+                bool take = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+                if (take) { bv = ov; bi = oi; }
+            }
+            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+            if (lane == it) { my_logit = bv; my_idx = bi; }
+        }
+        float p = 0.f;
+        if (lane < k) p = fn == MOE_SCORE_SOFTMAX ? expf(my_logit - mx) / den : 1.f / (1.f + expf(-my_logit));
+        if (norm_topk) {
+            float tot = wave_sum(lane < k ? p : 0.f);
+            p = p / tot;
+        }
+        if (lane < k) {
+            topk_idx[(int64_t)t * k + lane] = my_idx;
+            topk_prob[(int64_t)t * k + lane] = p * scale;
+            atomicAdd(&hist[my_idx], 1);
+        }
+    }
+    __syncthreads();
+    if (counts)
+        for (int e = threadIdx.x; e < E; e += blockDim.x)
+            if (hist[e]) atomicAdd(&counts[e], hist[e]);
+}
+
+extern "C" moe_status moe_route_topk(moe_ctx* ctx, void* stream, const float* logits, int T, int E, int k,
+                                     moe_score fn, int norm_topk, float scale,
+                                     int32_t* topk_idx, float* topk_prob, int32_t* counts) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!logits || !topk_idx || !topk_prob) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk: NULL pointer");
+    if (T < 0 || E < 1 || E > 64 * ROUTE_MAX_VPL || k < 1 || k > 32 || k > E)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk: need T>=0, 1<=k<=min(E,32), E<=%d (T=%d E=%d k=%d)",
+                 64 * ROUTE_MAX_VPL, T, E, k);
+    if (fn != MOE_SCORE_SOFTMAX && fn != MOE_SCORE_SIGMOID) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk: bad score fn");
+    hipStream_t s = (hipStream_t)stream;
+    if (counts) moe_launch_fill_i32(counts, E, 0, s);
+    if (T == 0) return MOE_OK;
+    const int per_block = ROUTE_WAVES * ROUTE_TOKENS_PER_WAVE;
+    dim3 grid((T + per_block - 1) / per_block), block(ROUTE_WAVES * 64);
+    size_t shm = (size_t)E * sizeof(int32_t);
+    const int vpl = (E + 63) / 64;
+#define ROUTE_LAUNCH(V)                                                                                     \
+    hipLaunchKernelGGL(route_topk_kernel<V>, grid, block, shm, s, logits, T, E, k, (int)fn, norm_topk, scale, \
+                       topk_idx, topk_prob, counts)
+    if (vpl <= 1) ROUTE_LAUNCH(1);
+    else if (vpl <= 2) ROUTE_LAUNCH(2);
+    else if (vpl <= 4) ROUTE_LAUNCH(4);
+    else if (vpl <= 8) ROUTE_LAUNCH(8);
+    else ROUTE_LAUNCH(16);
+#undef ROUTE_LAUNCH
+    MOE_LAUNCH_CHECK(ctx, "route_topk_kernel");
+    return MOE_OK;
+}

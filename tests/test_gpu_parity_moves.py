@@ -1,0 +1,179 @@
+"""GPU parity: router, row-ID map, permute, combine and its backward against the CPU oracle."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_07685_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(B):
+    c = B.Context(T=16384, k=8, E=256, h=7168, f_max=14336)
+    yield c
+    c.close()
+
+
+def _route(B, ctx, logits, k, fn, norm, scale=1.0):
+    from gpu_util import dev
+    T, E = logits.shape
+    d_log = dev(logits)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    prob = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    counts = torch.empty(E, dtype=torch.int32, device="cuda")
+    B.moe_route_topk(ctx, d_log, T, E, k, fn, norm, scale, idx, prob, counts)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), prob.cpu().numpy(), counts.cpu().numpy()
+
+
+@pytest.mark.parametrize("T,E,k,fn,norm,scale", [
+    (256, 8, 2, 0, False, 1.0),        # C1
+    (8192, 8, 2, 0, False, 1.0),       # C2
+    (16384, 128, 8, 0, False, 1.0),    # C3 router at its global shape
+    (16384, 256, 8, 1, True, 1.0),     # C4/C5 router: sigmoid, normalised top-k
+    (1000, 37, 5, 1, False, 2.5),      # ragged: E not a multiple of 64, T not a multiple of the block
+    (333, 1024, 32, 0, True, 1.0),     # maximum E and k
+    (64, 5, 5, 0, False, 1.0),         # k == E
+])
+def test_route_topk(B, ctx, oracle, T, E, k, fn, norm, scale):
+    from paper_2603_07685_amd import workloads as wl
+    _, _, logits = wl.router_logits(T, 64, E, 0.3, 77 + T + E)
+    idx, prob, counts = _route(B, ctx, logits, k, fn, norm, scale)
+    o_idx, o_prob, o_counts = oracle.route_topk(logits, k, fn, norm, scale)
+    assert np.array_equal(idx, o_idx)            # bit-exact indices, slot order included
+    assert np.array_equal(counts, o_counts)
+    np.testing.assert_allclose(prob, o_prob, rtol=2e-6, atol=1e-9)
+
+
+def test_route_topk_ties_and_errors(B, ctx, oracle):
+    g = np.random.default_rng(5)
+    logits = g.integers(-2, 3, size=(512, 16)).astype(np.float32)     # many exact ties
+    idx, prob, counts = _route(B, ctx, logits, 4, 1, True)
+    o_idx, o_prob, o_counts = oracle.route_topk(logits, 4, 1, True)
+    assert np.array_equal(idx, o_idx) and np.array_equal(counts, o_counts)
+    np.testing.assert_allclose(prob, o_prob, rtol=2e-6)
+    with pytest.raises(B.MoeError):
+        _route(B, ctx, logits, 17, 0, False)                         # k > E
+
+
+def _permute(B, ctx, X, idx, E, align, dt):
+    from gpu_util import dev
+    T, k = idx.shape
+    h = X.shape[1]
+    Rcap = T * k + E * (align - 1)
+    Xp = torch.full((Rcap, h), float("nan"), dtype=X.dtype, device="cuda")
+    row_of = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    src_of = torch.empty(Rcap, dtype=torch.int32, device="cuda")
+    offsets = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    counts = torch.empty(E, dtype=torch.int32, device="cuda")
+    B.moe_permute(ctx, X, dt, dev(idx), T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts)
+    torch.cuda.synchronize()
+    return Xp, row_of, src_of, offsets, counts, Rcap
+
+
+@pytest.mark.parametrize("T,k,E,h,align,f32", [
+    (256, 2, 8, 128, 1, False),       # C1
+    (256, 2, 8, 128, 1, True),
+    (3000, 3, 7, 264, 16, False),     # ragged sizes, skipped ids, an empty expert
+    (4096, 8, 32, 1024, 128, False),  # fp8-style padding
+    (1, 1, 1, 8, 1, False),           # degenerate
+    (2500, 8, 256, 72, 1, False),     # many experts, several chunks
+])
+def test_permute_maps_and_rows(B, ctx, oracle, T, k, E, h, align, f32):
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(T + E)
+    idx = g.integers(-1 if E > 1 else 0, E + (1 if E > 1 else 0), size=(T, k)).astype(np.int32)
+    if E > 4:
+        idx[idx == 3] = 2                                             # expert 3 receives nothing
+    Xh = wl.gaussian_bf16((T, h), 1.0, 11, T)
+    X = dev(Xh) if f32 else dev_bf16(Xh)
+    Xp, row_of, src_of, offsets, counts, Rcap = _permute(B, ctx, X, idx, E, align, B.F32 if f32 else B.BF16)
+    m = oracle.permute_maps(idx, E, align, Rcap)
+    assert np.array_equal(row_of.cpu().numpy(), m.row_of)
+    assert np.array_equal(src_of.cpu().numpy(), m.src_of)
+    assert np.array_equal(offsets.cpu().numpy(), m.offsets)
+    assert np.array_equal(counts.cpu().numpy(), m.counts)
+    ref = oracle.permute_rows(Xh, m.src_of[: m.Rtot], k, prec="f32")
+    got = Xp[: m.Rtot].float().cpu().numpy()
+    assert np.array_equal(got, ref)                                   # copies and zero padding are exact
+    assert torch.isnan(Xp[m.Rtot:].float()).all()                     # rows beyond offsets[E] untouched
+
+
+def test_permute_errors(B, ctx):
+    from gpu_util import dev
+    idx = dev(np.zeros((4, 2), np.int32))
+    X = torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda")
+    Xp = torch.zeros((8, 8), dtype=torch.bfloat16, device="cuda")
+    i32 = lambda n: torch.zeros(n, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.MoeError):   # Rcap too small for align = 4
+        B.moe_permute(ctx, X, B.BF16, idx, 4, 2, 8, 2, 4, Xp, 8, i32(8), i32(8), i32(3), i32(2))
+    with pytest.raises(B.MoeError):   # row size not a multiple of 16 bytes
+        B.moe_permute(ctx, X, B.BF16, idx, 4, 2, 4, 2, 1, Xp, 8, i32(8), i32(8), i32(3), i32(2))
+
+
+@pytest.mark.parametrize("T,k,E,h,align,f32,res", [
+    (256, 2, 8, 128, 1, False, False),
+    (256, 2, 8, 128, 1, True, True),
+    (1500, 8, 32, 7168, 128, False, True),    # C4 row width, ragged tail of the 16-byte chunks
+    (777, 5, 9, 200, 1, False, False),        # k not a multiple of 4
+    (300, 1, 4, 64, 1, False, True),
+])
+def test_combine_and_backward(B, ctx, oracle, T, k, E, h, align, f32, res):
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(T * 3 + k)
+    idx = g.integers(-1, E, size=(T, k)).astype(np.int32)            # some slots not on this GPU
+    m = oracle.permute_maps(idx, E, align)
+    Rcap = T * k + E * (align - 1)
+    Oh = wl.gaussian_bf16((Rcap, h), 1.0, 12, T)
+    Sh = wl.gaussian_bf16((T, h), 1.0, 13, T) if res else None
+    dYh = wl.gaussian_bf16((T, h), 1.0, 14, T)
+    prob = wl.forced_probs(T, k, 15)
+    mk = dev if f32 else dev_bf16
+    dt = B.F32 if f32 else B.BF16
+    tdt = torch.float32 if f32 else torch.bfloat16
+    O, dY = mk(Oh), mk(dYh)
+    S = mk(Sh) if res else None
+    row_of, src_of, dprob_in = dev(m.row_of), dev(m.src_of), dev(prob)
+    Y = torch.empty((T, h), dtype=tdt, device="cuda")
+    B.moe_unpermute_combine(ctx, O, dt, row_of, dprob_in, S, T, k, h, Y)
+    Yref = oracle.combine(Oh, m.row_of, prob, Sh)
+    tol = 1e-5 if f32 else BF16_TOL
+    assert rel_fro(host_f64(Y), Yref) <= tol
+    # plain-sum form (prob == NULL): the backward of permute
+    B.moe_unpermute_combine(ctx, O, dt, row_of, None, None, T, k, h, Y)
+    assert rel_fro(host_f64(Y), oracle.combine(Oh, m.row_of, None, None)) <= tol
+    # backward
+    dO = torch.full((Rcap, h), float("nan"), dtype=tdt, device="cuda")
+    dprob = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_unpermute_combine_bwd(ctx, dY, O, dt, row_of, src_of, dprob_in, T, k, h, Rcap, dO, dprob)
+    torch.cuda.synchronize()
+    dOref, dpref = oracle.combine_bwd(dYh, Oh, m.row_of, prob, Rcap)
+    assert rel_fro(host_f64(dO), dOref) <= tol                        # includes exact zeros on padding rows
+    assert np.all(host_f64(dO)[m.src_of < 0] == 0)
+    assert rel_fro(host_f64(dprob), dpref) <= (1e-5 if f32 else 1e-4)
+
+
+def test_round_trip_is_identity(B, ctx, oracle):
+    """permute then combine with w = 1/k returns X bit-exactly (k a power of two)."""
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    T, k, E, h = 2048, 4, 16, 512
+    g = np.random.default_rng(3)
+    idx = np.stack([g.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    X = dev_bf16(wl.gaussian_bf16((T, h), 1.0, 16, 0))
+    Xp, row_of, src_of, offsets, counts, Rcap = _permute(B, ctx, X, idx, E, 1, B.BF16)
+    assert int(counts.sum()) == T * k
+    Y = torch.empty_like(X)
+    w = torch.full((T, k), 0.25, dtype=torch.float32, device="cuda")
+    B.moe_unpermute_combine(ctx, Xp, B.BF16, row_of, w, None, T, k, h, Y)
+    torch.cuda.synchronize()
+    assert torch.equal(Y.view(torch.int16), X.view(torch.int16))
