@@ -16,7 +16,8 @@ struct moe_ctx {
     char err[512];
 };
 
-#define MOE_WS_RESERVED 256  // bytes at the head of the workspace kept for the error word
+#define MOE_WS_RESERVED 256  // bytes at the head of the workspace: error word at 0, ...
+#define MOE_WS_ZEROS 128     // ... and 128 bytes that stay zero for the whole life of the context
 
 #define MOE_FAIL(ctx, code, ...)                                   \
     do {                                                           \

@@ -1,0 +1,151 @@
+"""One MoE expert layer as a fixed sequence of C-ABI calls on preallocated device buffers.
+
+No arithmetic happens here: this module only allocates torch tensors as device
+memory and issues the library calls in the order of the paper's four stages
+(Sec. 2.1.1) and of the backward pass with the weight-/data-gradient split
+(Sec. 4.2.3).  It is what the tests, the smoke check and the benchmark drive.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as wl
+
+
+def host_inputs(cfg: wl.MoEConfig, shared_f: int | None = None) -> dict:
+    """Seeded host inputs (fp32 arrays whose values are bf16-representable) for the small configs."""
+    sf = cfg.shared_f if shared_f is None else shared_f
+    s = cfg.seed
+    _, _, logits = wl.router_logits(cfg.T, cfg.h, cfg.E_router, cfg.std, s)
+    d = {
+        "logits": logits,
+        "X": wl.gaussian_bf16((cfg.T, cfg.h), cfg.std, s, 1),
+        "W1": wl.gaussian_bf16((cfg.E, 2 * cfg.f, cfg.h), cfg.std, s, 2),
+        "W2": wl.gaussian_bf16((cfg.E, cfg.h, cfg.f), cfg.std, s, 3),
+        "dY": wl.gaussian_bf16((cfg.T, cfg.h), 1.0, s, 4),
+    }
+    if sf:
+        d["Ws1"] = wl.gaussian_bf16((2 * sf, cfg.h), cfg.std, s, 5)
+        d["Ws2"] = wl.gaussian_bf16((cfg.h, sf), cfg.std, s, 6)
+    return d
+
+
+def _dev_bf16(x: np.ndarray) -> torch.Tensor:
+    bits = wl.f32_to_bf16_bits(np.ascontiguousarray(x, np.float32))
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+class LayerState:
+    """Device buffers of one layer + the forward / backward call sequences."""
+
+    def __init__(self, cfg: wl.MoEConfig, hin: dict | None = None, shared_f: int | None = None,
+                 variant: str | None = None, wgrad_f32: bool = False):
+        self.cfg = cfg
+        T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
+        self.sf = sf = cfg.shared_f if shared_f is None else shared_f
+        self.align = cfg.align
+        self.Rcap = Rcap = T * k + E * (cfg.align - 1)
+        self.ctx = B.Context(T, k, max(E, cfg.E_router), h, max(f, sf))
+        bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+        dev = "cuda"
+        s = cfg.seed
+        if hin is not None:
+            self.logits = torch.from_numpy(hin["logits"]).cuda()
+            self.X, self.W1, self.W2, self.dY = (_dev_bf16(hin[n]) for n in ("X", "W1", "W2", "dY"))
+            if sf:
+                self.Ws1, self.Ws2 = _dev_bf16(hin["Ws1"]), _dev_bf16(hin["Ws2"])
+        else:  # large configs: draw on the device
+            g = torch.Generator(device=dev)
+            g.manual_seed(s)
+            self.logits = torch.empty((T, cfg.E_router), dtype=f32, device=dev).normal_(0.0, 0.03, generator=g)
+            self.X = wl.device_gaussian_bf16((T, h), cfg.std, s, 1)
+            self.W1 = wl.device_gaussian_bf16((E, 2 * f, h), cfg.std, s, 2)
+            self.W2 = wl.device_gaussian_bf16((E, h, f), cfg.std, s, 3)
+            self.dY = wl.device_gaussian_bf16((T, h), 1.0, s, 4)
+            if sf:
+                self.Ws1 = wl.device_gaussian_bf16((2 * sf, h), cfg.std, s, 5)
+                self.Ws2 = wl.device_gaussian_bf16((h, sf), cfg.std, s, 6)
+        # forced routing map (None: the router's own top-k drives the permute)
+        forced = wl.routing_map(cfg, variant)
+        self.forced_idx = None if forced is None else torch.from_numpy(forced).cuda()
+
+        self.topk_idx = torch.empty((T, k), dtype=i32, device=dev)
+        self.topk_prob = torch.empty((T, k), dtype=f32, device=dev)
+        self.route_counts = torch.empty(cfg.E_router, dtype=i32, device=dev)
+        self.row_of = torch.empty((T, k), dtype=i32, device=dev)
+        self.src_of = torch.empty(Rcap, dtype=i32, device=dev)
+        self.offsets = torch.empty(E + 1, dtype=i32, device=dev)
+        self.counts = torch.empty(E, dtype=i32, device=dev)
+        self.Xp = torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.Z = torch.empty((Rcap, 2 * f), dtype=bf, device=dev)
+        self.A = torch.empty((Rcap, f), dtype=bf, device=dev)
+        self.O = torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.Y = torch.empty((T, h), dtype=bf, device=dev)
+        # backward
+        wdt = f32 if wgrad_f32 else bf
+        self.wgrad_dt = B.F32 if wgrad_f32 else B.BF16
+        self.dO = torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.dprob = torch.empty((T, k), dtype=f32, device=dev)
+        self.dZ = torch.empty((Rcap, 2 * f), dtype=bf, device=dev)
+        self.dXp = torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.dX = torch.empty((T, h), dtype=bf, device=dev)
+        self.dW1 = torch.empty((E, 2 * f, h), dtype=wdt, device=dev)
+        self.dW2 = torch.empty((E, h, f), dtype=wdt, device=dev)
+        if sf:
+            self.off_shared = torch.tensor([0, T], dtype=i32, device=dev)
+            self.Zs = torch.empty((T, 2 * sf), dtype=bf, device=dev)
+            self.As = torch.empty((T, sf), dtype=bf, device=dev)
+            self.S = torch.empty((T, h), dtype=bf, device=dev)
+            self.dZs = torch.empty((T, 2 * sf), dtype=bf, device=dev)
+            self.dXs = torch.empty((T, h), dtype=bf, device=dev)
+            self.dWs1 = torch.empty((2 * sf, h), dtype=wdt, device=dev)
+            self.dWs2 = torch.empty((h, sf), dtype=wdt, device=dev)
+
+    # ---- the four forward stages --------------------------------------------------------------
+    def forward(self):
+        c, cfg = self.ctx, self.cfg
+        T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
+        B.moe_route_topk(c, self.logits, T, cfg.E_router, k, cfg.score, cfg.norm_topk, 1.0,
+                         self.topk_idx, self.topk_prob, self.route_counts)
+        idx = self.topk_idx if self.forced_idx is None else self.forced_idx
+        B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
+                      self.row_of, self.src_of, self.offsets, self.counts)
+        B.moe_grouped_gemm_fwd(c, self.Xp, self.W1, self.offsets, E, 2 * f, h, Rcap, B.BF16, B.EPI_SWIGLU,
+                               None, None, self.Z, self.A)
+        B.moe_grouped_gemm_fwd(c, self.A, self.W2, self.offsets, E, h, f, Rcap, B.BF16, B.EPI_NONE,
+                               None, None, self.O, None)
+        if sf:
+            B.moe_grouped_gemm_fwd(c, self.X, self.Ws1, self.off_shared, 1, 2 * sf, h, T, B.BF16, B.EPI_SWIGLU,
+                                   None, None, self.Zs, self.As)
+            B.moe_grouped_gemm_fwd(c, self.As, self.Ws2, self.off_shared, 1, h, sf, T, B.BF16, B.EPI_NONE,
+                                   None, None, self.S, None)
+        B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, self.topk_prob, self.S if sf else None,
+                                T, k, h, self.Y)
+
+    # ---- backward: combine, fc2 (wgrad, dgrad + SwiGLU'), fc1 (wgrad, dgrad), permute ---------
+    def backward(self):
+        c, cfg = self.ctx, self.cfg
+        T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
+        wdt = self.wgrad_dt
+        B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
+                                    T, k, h, Rcap, self.dO, self.dprob)
+        B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt, self.dW2)
+        B.moe_grouped_gemm_dgrad(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, B.BF16, self.Z, None, None, self.dZ)
+        B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, wdt,
+                                 self.dW1)
+        B.moe_grouped_gemm_dgrad(c, self.dZ, self.W1, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, None,
+                                 self.dXp)
+        if sf:
+            o1 = self.off_shared
+            B.moe_grouped_gemm_wgrad(c, self.As, self.dY, o1, 1, h, sf, T, B.BF16, None, None, 0, wdt, self.dWs2)
+            B.moe_grouped_gemm_dgrad(c, self.dY, self.Ws2, o1, 1, h, sf, T, B.BF16, self.Zs, None, None, self.dZs)
+            B.moe_grouped_gemm_wgrad(c, self.X, self.dZs, o1, 1, 2 * sf, h, T, B.BF16, None, None, 0, wdt, self.dWs1)
+            B.moe_grouped_gemm_dgrad(c, self.dZs, self.Ws1, o1, 1, 2 * sf, h, T, B.BF16, None, None, None, self.dXs)
+        # dX[t] = sum of the k permuted-row gradients (+ the shared expert's dX): the plain-sum unpermute
+        B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
+
+    def step(self):
+        self.forward()
+        self.backward()

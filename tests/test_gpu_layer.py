@@ -1,0 +1,55 @@
+"""GPU parity of the whole layer (route -> permute -> fc1+SwiGLU -> fc2 -> combine, then the backward
+chain) against the oracle's composition, every element, at the tiny config and a mid-size one."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.mark.parametrize("name,shared_f", [("C1", 0), ("C1", 64), ("MID", 0)])
+def test_layer_forward_backward_every_element(oracle, name, shared_f):
+    from gpu_util import host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    from paper_2603_07685_amd import layer as L
+    cfg = wl.CONFIGS[name]
+    hin = L.host_inputs(cfg, shared_f=shared_f)
+    st = L.LayerState(cfg, hin, shared_f=shared_f)
+    st.forward()
+    st.backward()
+    torch.cuda.synchronize()
+    assert st.ctx.poll_error() == 0
+
+    # oracle: same bf16-rounded input bits, fp64 arithmetic
+    o_idx, o_prob, o_counts = oracle.route_topk(hin["logits"], cfg.k, cfg.score, cfg.norm_topk)
+    assert np.array_equal(st.topk_idx.cpu().numpy(), o_idx)
+    assert np.array_equal(st.route_counts.cpu().numpy(), o_counts)
+    np.testing.assert_allclose(st.topk_prob.cpu().numpy(), o_prob, rtol=2e-6)
+    fw = oracle.layer_forward(hin["X"], o_idx, o_prob, hin["W1"], hin["W2"], cfg.E, cfg.align,
+                              hin.get("Ws1"), hin.get("Ws2"))
+    m = fw.maps
+    assert np.array_equal(st.row_of.cpu().numpy(), m.row_of)
+    assert np.array_equal(st.src_of.cpu().numpy(), m.src_of)
+    assert np.array_equal(st.offsets.cpu().numpy(), m.offsets)
+    assert np.array_equal(st.counts.cpu().numpy(), m.counts)
+    R = fw.R
+    assert np.array_equal(host_f64(st.Xp)[:R], fw.Xp)
+    errs = {
+        "Z": rel_fro(host_f64(st.Z)[:R], fw.Z), "A": rel_fro(host_f64(st.A)[:R], fw.A),
+        "O": rel_fro(host_f64(st.O)[:R], fw.O), "Y": rel_fro(host_f64(st.Y), fw.Y),
+    }
+    bw = oracle.layer_backward(fw, hin["X"], o_prob, hin["W1"], hin["W2"], hin["dY"], hin.get("Ws1"), hin.get("Ws2"))
+    errs.update({
+        "dO": rel_fro(host_f64(st.dO)[:R], bw.dO), "dprob": rel_fro(host_f64(st.dprob), bw.dprob),
+        "dW2": rel_fro(host_f64(st.dW2), bw.dW2), "dZ": rel_fro(host_f64(st.dZ)[:R], bw.dZ),
+        "dW1": rel_fro(host_f64(st.dW1), bw.dW1), "dXp": rel_fro(host_f64(st.dXp)[:R], bw.dXp),
+        "dX": rel_fro(host_f64(st.dX), bw.dX + (bw.dX_shared if shared_f else 0.0)),
+    })
+    if shared_f:
+        errs.update({"S": rel_fro(host_f64(st.S), fw.S), "dWs1": rel_fro(host_f64(st.dWs1), bw.dWs1),
+                     "dWs2": rel_fro(host_f64(st.dWs2), bw.dWs2),
+                     "dX_shared": rel_fro(host_f64(st.dXs), bw.dX_shared)})
+    print(name, {k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= BF16_TOL, (k, v)

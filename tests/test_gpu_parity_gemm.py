@@ -97,3 +97,95 @@ def test_grouped_gemm_bad_offsets_sets_error_word(B, ctx):
     assert ctx.poll_error() == 1
     assert ctx.poll_error() == 0
     assert (C == 7.0).all()
+
+
+DG_CASES = [
+    # counts, N (contraction), K (output columns)
+    ([300, 0, 257, 1, 700], 128, 512),
+    ([256, 256], 64, 256),
+    ([5], 256, 128),                       # K smaller than a tile
+    ([1000, 3, 0, 0, 513, 64], 192, 768),
+]
+
+
+@pytest.mark.parametrize("counts,N,K", DG_CASES)
+def test_grouped_gemm_dgrad_plain(B, ctx, oracle, counts, N, K):
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets(counts)
+    R = int(off[-1])
+    Rcap = R + 3
+    dCh = wl.gaussian_bf16((Rcap, N), 1.0, 31, N)
+    Bh = wl.gaussian_bf16((E, N, K), 1.0, 32, K)
+    dC, W = dev_bf16(dCh), dev_bf16(Bh)
+    dA = torch.full((Rcap, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_dgrad(ctx, dC, W, dev(off), E, N, K, Rcap, B.BF16, None, None, None, dA)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    ref = oracle.grouped_gemm_nn(dCh[:R], Bh, off)
+    got = host_f64(dA)
+    assert rel_fro(got[:R], ref) <= BF16_TOL
+    assert np.abs(got[:R] - ref).max() <= 0.02 * np.abs(ref).max() + 1e-6
+    assert np.isnan(got[R:]).all()
+
+
+@pytest.mark.parametrize("counts,N,f", [([300, 0, 257, 1, 700], 128, 256), ([130, 90], 64, 128),
+                                         ([513], 320, 384)])
+def test_grouped_gemm_dgrad_swiglu_bwd(B, ctx, oracle, counts, N, f):
+    """fc2 data gradient with the SwiGLU backward fused: dZ from dO, W2 and the saved pre-activation."""
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets(counts)
+    R = int(off[-1])
+    dOh = wl.gaussian_bf16((R, N), 1.0, 33, N)
+    W2h = wl.gaussian_bf16((E, N, f), 0.1, 34, f)
+    Zh = wl.gaussian_bf16((R, 2 * f), 1.5, 35, f)
+    dZ = torch.full((R, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_dgrad(ctx, dev_bf16(dOh), dev_bf16(W2h), dev(off), E, N, f, R, B.BF16, dev_bf16(Zh), None, None,
+                             dZ)
+    torch.cuda.synchronize()
+    dAref = oracle.grouped_gemm_nn(dOh, W2h, off)
+    dZref = oracle.swiglu_bwd(dAref, Zh)
+    assert rel_fro(host_f64(dZ), dZref) <= BF16_TOL
+
+
+WG_CASES = [
+    # counts, N, K
+    ([300, 0, 257, 1, 700], 256, 512),
+    ([64, 128], 256, 256),
+    ([5, 70], 128, 64),                    # output smaller than a tile in both directions
+    ([1000, 3, 0, 0, 513, 64], 320, 264),  # ragged output tiles
+]
+
+
+@pytest.mark.parametrize("counts,N,K", WG_CASES)
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_grouped_gemm_wgrad(B, ctx, oracle, counts, N, K, out_f32):
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets(counts)
+    R = int(off[-1])
+    Rcap = R + 5
+    dCh = wl.gaussian_bf16((Rcap, N), 1.0, 41, N)
+    Ah = wl.gaussian_bf16((Rcap, K), 1.0, 42, K)
+    tdt = torch.float32 if out_f32 else torch.bfloat16
+    dB = torch.full((E, N, K), float("nan"), dtype=tdt, device="cuda")
+    odt = B.F32 if out_f32 else B.BF16
+    A, dC, doff = dev_bf16(Ah), dev_bf16(dCh), dev(off)
+    B.moe_grouped_gemm_wgrad(ctx, A, dC, doff, E, N, K, Rcap, B.BF16, None, None, 0, odt, dB)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    ref = oracle.grouped_gemm_tn(dCh[:R], Ah[:R], off)
+    got = host_f64(dB)
+    tol = 1e-5 if out_f32 else BF16_TOL
+    assert rel_fro(got, ref) <= tol
+    for e, c in enumerate(counts):
+        if c == 0:
+            assert np.all(got[e] == 0)                              # zero-token expert: exact zeros
+    # accumulate: dB += result
+    B.moe_grouped_gemm_wgrad(ctx, A, dC, doff, E, N, K, Rcap, B.BF16, None, None, 1, odt, dB)
+    torch.cuda.synchronize()
+    assert rel_fro(host_f64(dB), 2 * ref) <= (1e-5 if out_f32 else BF16_TOL)
