@@ -217,6 +217,20 @@ def main():
                      "traffic": None},
         "kernels": breakdown,
     }
+    # context only: the vendor dense bf16 GEMM through torch on this very box (boxes differ by +-20 %)
+    a_ref = torch.randn((16384, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
+    b_ref = torch.randn((4096, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
+    for _ in range(3):
+        a_ref @ b_ref.T
+    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    r0.record()
+    for _ in range(10):
+        a_ref @ b_ref.T
+    r1.record()
+    torch.cuda.synchronize()
+    out["box_reference"] = {"what": f"torch.matmul bf16 16384x4096x{cfg.h} (dense, hipBLASLt) on this box",
+                            "tflops": round(2.0 * 16384 * 4096 * cfg.h * 10 / r0.elapsed_time(r1) / 1e9, 1)}
+    del a_ref, b_ref
     if not args.no_cpu_baseline:
         v, cores, desc = cpu_baseline(st, torch)
         out["cpu_baseline"] = {"value": round(v, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle", "sample": desc}

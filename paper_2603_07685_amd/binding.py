@@ -13,7 +13,7 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libmoe_hip.so")
+LIB_PATH = os.environ.get("MOE_HIP_LIB") or os.path.join(_PKG, "libmoe_hip.so")
 _lib = None
 
 BF16, FP8_E4M3, F32 = 0, 1, 2

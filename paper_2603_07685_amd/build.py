@@ -19,10 +19,12 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, jobs: int = 8) -> str:
-    """Compile every csrc/*.hip to an object (in parallel) and link libmoe_hip.so."""
+def build_library(verbose: bool = False, jobs: int = 8, extra_flags=(), out: str | None = None) -> str:
+    """Compile every csrc/*.hip to an object (in parallel) and link libmoe_hip.so.
+
+    extra_flags / out build a variant library elsewhere (used for kernel tuning experiments)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    bdir = os.path.join(PKG, "_build")
+    bdir = os.path.join(PKG, "_build" if out is None else "_build_" + os.path.basename(out))
     os.makedirs(bdir, exist_ok=True)
     procs = []
     objs = []
@@ -32,16 +34,17 @@ def build_library(verbose: bool = False, jobs: int = 8) -> str:
             continue
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", path, "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-c", path, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         if len(procs) >= jobs:
             _drain(procs, verbose)
     _drain(procs, verbose)
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    lib = out or LIB
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     subprocess.check_call(cmd)
-    return LIB
+    return lib
 
 
 def _drain(procs, verbose):
