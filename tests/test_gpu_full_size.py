@@ -1,0 +1,139 @@
+"""GPU parity at the full benchmark sizes (C2, C3, C4 and the degenerate C4 load patterns), in the
+launch configuration bench.py times.
+
+Integer results (routing indices, counts, row maps, offsets) are compared in full and bit-exactly.
+Floating-point results are checked per library call on sampled outputs the oracle computes one by
+one from the same bf16 input bits: rows of every forward / data-gradient tensor for a handful of
+experts (first / last / largest / smallest / two more, rows at tile boundaries and the ragged
+tail), 64x64 windows of every weight gradient contracted over all rows of the expert, and sampled
+tokens of the combine and its backward.  Bound: relative Frobenius error <= 2e-2 on the sample.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+CASES = [("C2", None), ("C3", None), ("C4", None), ("C4", "zeros"), ("C4", "hot")]
+
+
+def _f64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def _sample_rows(lo, hi, g, n=10):
+    """Rows of [lo, hi): both ends, the 256-row tile boundaries near them, and a few random ones."""
+    m = hi - lo
+    cand = {lo, hi - 1, lo + min(255, m - 1), lo + min(256, m - 1), lo + (m - 1) // 256 * 256, lo + m // 2}
+    cand |= {int(lo + v) for v in g.integers(0, m, size=n)}
+    return np.array(sorted(c for c in cand if lo <= c < hi), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name,variant", CASES)
+def test_full_size_sampled(oracle, name, variant):
+    from gpu_util import rel_fro, BF16_TOL
+    from paper_2603_07685_amd import layer as L
+    from paper_2603_07685_amd import workloads as wl
+    cfg = wl.CONFIGS[name]
+    g = np.random.default_rng(cfg.seed + (0 if variant is None else len(variant)))
+    st = L.LayerState(cfg, None, variant=variant)
+    st.step()
+    torch.cuda.synchronize()
+    assert st.ctx.poll_error() == 0
+    T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
+
+    # ---- integer parts, in full ----
+    logits = st.logits.cpu().numpy()
+    o_idx, o_prob, o_counts = oracle.route_topk(logits, k, cfg.score, cfg.norm_topk)
+    assert np.array_equal(st.topk_idx.cpu().numpy(), o_idx)
+    assert np.array_equal(st.route_counts.cpu().numpy(), o_counts)
+    np.testing.assert_allclose(st.topk_prob.cpu().numpy(), o_prob, rtol=3e-6, atol=1e-9)
+    idx = o_idx if st.forced_idx is None else st.forced_idx.cpu().numpy()
+    m = oracle.permute_maps(idx, E, cfg.align, st.Rcap)
+    assert np.array_equal(st.row_of.cpu().numpy(), m.row_of)
+    assert np.array_equal(st.src_of.cpu().numpy(), m.src_of)
+    assert np.array_equal(st.offsets.cpu().numpy(), m.offsets)
+    assert np.array_equal(st.counts.cpu().numpy(), m.counts)
+    assert int(m.counts.sum()) == T * k
+    if variant == "zeros":
+        assert int((m.counts == 0).sum()) == 4
+    if variant == "hot":
+        assert m.counts.max() >= 0.39 * T * k
+    off = m.offsets
+
+    # ---- per-expert sampled rows and weight-gradient windows ----
+    live = [e for e in range(E) if m.counts[e] > 0]
+    pick = {live[0], live[-1], max(live, key=lambda e: m.counts[e]), min(live, key=lambda e: m.counts[e])}
+    pick |= {int(e) for e in g.choice(live, size=min(2, len(live)), replace=False)}
+    errs = {}
+
+    def acc(key, got, ref):
+        num, den = errs.get(key, (0.0, 0.0))
+        errs[key] = (num + float(((got - ref) ** 2).sum()), den + float((ref ** 2).sum()))
+
+    one = lambda n: np.array([0, n], np.int32)
+    for e in sorted(pick):
+        lo, hi = int(off[e]), int(off[e]) + int(m.counts[e])
+        rows = _sample_rows(lo, hi, g)
+        rt = torch.from_numpy(rows).cuda()
+        n = len(rows)
+        W1 = _f64(st.W1[e])[None]
+        W2 = _f64(st.W2[e])[None]
+        src_tok = m.src_of[rows] // k
+        Xrows = _f64(st.X[torch.from_numpy(src_tok).cuda()])
+        assert np.array_equal(_f64(st.Xp[rt]), Xrows)                       # permuted rows are exact copies
+        Zref = oracle.grouped_gemm_nt(Xrows, W1, one(n))
+        acc("Z", _f64(st.Z[rt]), Zref)
+        acc("A", _f64(st.A[rt]), oracle.swiglu(Zref))
+        Ag = _f64(st.A[rt])
+        acc("O", _f64(st.O[rt]), oracle.grouped_gemm_nt(Ag, W2, one(n)))
+        dOg, Zg = _f64(st.dO[rt]), _f64(st.Z[rt])
+        acc("dZ", _f64(st.dZ[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, one(n)), Zg))
+        acc("dXp", _f64(st.dXp[rt]), oracle.grouped_gemm_nn(_f64(st.dZ[rt]), W1, one(n)))
+        # weight-gradient windows, contracted over every row of the expert
+        n0, k0 = int(g.integers(0, h - 63)), int(g.integers(0, f - 63))
+        ref = oracle.grouped_gemm_tn(_f64(st.dO[lo:hi, n0:n0 + 64]), _f64(st.A[lo:hi, k0:k0 + 64]), one(hi - lo))[0]
+        acc("dW2", _f64(st.dW2[e, n0:n0 + 64, k0:k0 + 64]), ref)
+        n1, k1 = int(g.integers(0, 2 * f - 63)), int(g.integers(0, h - 63))
+        ref = oracle.grouped_gemm_tn(_f64(st.dZ[lo:hi, n1:n1 + 64]), _f64(st.Xp[lo:hi, k1:k1 + 64]), one(hi - lo))[0]
+        acc("dW1", _f64(st.dW1[e, n1:n1 + 64, k1:k1 + 64]), ref)
+    for e in range(E):                                                       # zero-token experts: exact zero gradients
+        if m.counts[e] == 0:
+            assert not st.dW1[e].any() and not st.dW2[e].any()
+
+    # ---- shared expert (one group of T rows on the unpermuted tokens) ----
+    if st.sf:
+        rows = _sample_rows(0, T, g)
+        rt = torch.from_numpy(rows).cuda()
+        n = len(rows)
+        Ws1, Ws2 = _f64(st.Ws1)[None], _f64(st.Ws2)[None]
+        Zs = oracle.grouped_gemm_nt(_f64(st.X[rt]), Ws1, one(n))
+        acc("Zs", _f64(st.Zs[rt]), Zs)
+        acc("S", _f64(st.S[rt]), oracle.grouped_gemm_nt(_f64(st.As[rt]), Ws2, one(n)))
+        acc("dZs", _f64(st.dZs[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(_f64(st.dY[rt]), Ws2, one(n)), _f64(st.Zs[rt])))
+        acc("dXs", _f64(st.dXs[rt]), oracle.grouped_gemm_nn(_f64(st.dZs[rt]), Ws1, one(n)))
+        n0, k0 = int(g.integers(0, h - 63)), int(g.integers(0, st.sf - 63))
+        acc("dWs2", _f64(st.dWs2[n0:n0 + 64, k0:k0 + 64]),
+            oracle.grouped_gemm_tn(_f64(st.dY[:, n0:n0 + 64]), _f64(st.As[:, k0:k0 + 64]), one(T))[0])
+
+    # ---- combine, its backward and the permute backward on sampled tokens ----
+    toks = np.unique(np.concatenate([[0, T - 1], g.integers(0, T, size=64)]))
+    tt = torch.from_numpy(toks).cuda()
+    r_of = m.row_of[toks]                                                    # [n, k]
+    flat = torch.from_numpy(r_of.reshape(-1).astype(np.int64)).cuda()
+    Osub = _f64(st.O[flat])
+    dXpsub = _f64(st.dXp[flat])
+    local_rows = np.arange(len(toks) * k, dtype=np.int32).reshape(len(toks), k)
+    prob = st.topk_prob.cpu().numpy().astype(np.float64)[toks]
+    S = _f64(st.S[tt]) if st.sf else None
+    acc("Y", _f64(st.Y[tt]), oracle.combine(Osub, local_rows, prob, S))
+    dOref, dpref = oracle.combine_bwd(_f64(st.dY[tt]), Osub, local_rows, prob, len(toks) * k)
+    acc("dO", _f64(st.dO[flat]), dOref)
+    acc("dprob", st.dprob.cpu().numpy().astype(np.float64)[toks], dpref)
+    acc("dX", _f64(st.dX[tt]), oracle.combine(dXpsub, local_rows, None, _f64(st.dXs[tt]) if st.sf else None))
+
+    rel = {k_: (np.sqrt(n_ / d_) if d_ > 0 else (0.0 if n_ == 0 else np.inf)) for k_, (n_, d_) in errs.items()}
+    print(name, variant, {k_: f"{v:.2e}" for k_, v in rel.items()})
+    for k_, v in rel.items():
+        assert v <= BF16_TOL, (k_, v)
