@@ -1,9 +1,185 @@
-// Blockwise FP8 quantisation (Sec. 5.3.2).
+// Blockwise FP8 quantisation (Sec. 5.3.2): E4M3 codes + fp32 block scales, grouped over all experts
+// in one launch with the live row count read from the device (Sec. 5.4.2).
+//
+//   scale = amax(block) / 448   (1 for an all-zero block)
+//   code  = nearest E4M3 to clamp(x / scale, +-448): fp32 division, hardware round-to-nearest-even
+//           conversion (v_cvt_pk_fp8_f32; gfx950 implements the OCP "fn" format: no inf, max 448)
+// All three kernels are bandwidth-bound: 2 bytes read + 1 byte written per element.
+//   1x128   : 16 lanes own one block (8 elements per lane), amax by butterfly over those 16 lanes.
+//   128x1   : a wave owns a 128-row x 512-column panel, 8 columns per lane; first pass keeps the running
+//             column amax in registers, second pass re-reads the panel (from L2) and converts.
+//   128x128 : a 256-thread workgroup owns one block, 64 elements per thread held in registers.
 #include "common.h"
+
+__device__ __forceinline__ float block_scale(float amax) { return amax > 0.0f ? amax / 448.0f : 1.0f; }
+
+// four fp32 -> four E4M3 codes packed in a dword
+__device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d, float scale) {
+    a = __builtin_fminf(__builtin_fmaxf(a / scale, -448.0f), 448.0f);
+    b = __builtin_fminf(__builtin_fmaxf(b / scale, -448.0f), 448.0f);
+    c = __builtin_fminf(__builtin_fmaxf(c / scale, -448.0f), 448.0f);
+    d = __builtin_fminf(__builtin_fmaxf(d / scale, -448.0f), 448.0f);
+    int w = 0;
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, w, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+    return (uint32_t)w;
+}
+
+__device__ __forceinline__ float amax8(u32x4_t v) {
+    float m = fabsf(bf16_lo(v.x));
+    m = fmaxf(m, fabsf(bf16_hi(v.x)));
+    m = fmaxf(m, fmaxf(fabsf(bf16_lo(v.y)), fabsf(bf16_hi(v.y))));
+    m = fmaxf(m, fmaxf(fabsf(bf16_lo(v.z)), fabsf(bf16_hi(v.z))));
+    m = fmaxf(m, fmaxf(fabsf(bf16_lo(v.w)), fabsf(bf16_hi(v.w))));
+    return m;
+}
+
+__device__ __forceinline__ u32x2_t cvt8_e4m3(u32x4_t v, float scale) {
+    u32x2_t o;
+    o.x = cvt4_e4m3(bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y), scale);
+    o.y = cvt4_e4m3(bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w), scale);
+    return o;
+}
+
+// ---- 1x128 ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void quant_1x128_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
+                                                          const int32_t* __restrict__ rows_dev,
+                                                          u32x2_t* __restrict__ q, float* __restrict__ scale) {
+    const int64_t live = rows_dev ? min((int64_t)*rows_dev, rows) : rows;
+    const int bpr = cols / 128;                       // blocks per row
+    const int64_t nblocks = live * bpr;
+    const int sub = threadIdx.x & 15;                 // lane inside its 16-lane block group
+    int64_t b = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int64_t stride = ((int64_t)gridDim.x * blockDim.x) >> 4;
+    for (; b < nblocks; b += stride) {                // uniform inside a 16-lane group
+        const int64_t vec = b * 16 + sub;             // 16-byte vector index (row-major, 16 per block)
+        const u32x4_t v = X[vec];
+        float m = amax8(v);
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+        const float s = block_scale(m);
+        q[vec] = cvt8_e4m3(v, s);
+        if (sub == 0) scale[b] = s;
+    }
+}
+
+// ---- 128x1 ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void quant_128x1_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
+                                                          const int32_t* __restrict__ rows_dev,
+                                                          u32x2_t* __restrict__ q, float* __restrict__ scale) {
+    const int64_t live = rows_dev ? min((int64_t)*rows_dev, rows) : rows;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int vpr = cols / 8;                          // 16-byte vectors per row
+    const int panels_c = (vpr + 63) / 64;              // 512-column panels per row block
+    const int64_t npanels = (live / 128) * panels_c;
+    for (int64_t p = (int64_t)blockIdx.x * 4 + wave; p < npanels; p += (int64_t)gridDim.x * 4) {
+        const int64_t rb = p / panels_c;
+        const int vc = (int)(p % panels_c) * 64 + lane;
+        if (vc >= vpr) continue;
+        const u32x4_t* src = X + rb * 128 * vpr + vc;
+        float m[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < 128; ++r) {
+            const u32x4_t v = src[(int64_t)r * vpr];
+            m[0] = fmaxf(m[0], fabsf(bf16_lo(v.x))); m[1] = fmaxf(m[1], fabsf(bf16_hi(v.x)));
+            m[2] = fmaxf(m[2], fabsf(bf16_lo(v.y))); m[3] = fmaxf(m[3], fabsf(bf16_hi(v.y)));
+            m[4] = fmaxf(m[4], fabsf(bf16_lo(v.z))); m[5] = fmaxf(m[5], fabsf(bf16_hi(v.z)));
+            m[6] = fmaxf(m[6], fabsf(bf16_lo(v.w))); m[7] = fmaxf(m[7], fabsf(bf16_hi(v.w)));
+        }
+        float s[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s[i] = block_scale(m[i]);
+        f32x4_t* sd = (f32x4_t*)(scale + rb * cols + (int64_t)vc * 8);
+        sd[0] = f32x4_t{s[0], s[1], s[2], s[3]};
+        sd[1] = f32x4_t{s[4], s[5], s[6], s[7]};
+        u32x2_t* dst = q + rb * 128 * vpr + vc;
+        for (int r = 0; r < 128; ++r) {
+            const u32x4_t v = src[(int64_t)r * vpr];
+            float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                          bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = __builtin_fminf(__builtin_fmaxf(x[i] / s[i], -448.0f), 448.0f);
+            int w0 = 0, w1 = 0;
+            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w0, false);
+            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w0, true);
+            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], w1, false);
+            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], w1, true);
+            dst[(int64_t)r * vpr] = u32x2_t{(uint32_t)w0, (uint32_t)w1};
+        }
+    }
+}
+
+// ---- 128x128 -------------------------------------------------------------------------------
+// grid = groups * (rows/128) * (cols/128) workgroups of 256 threads
+__global__ __launch_bounds__(256) void quant_128x128_kernel(const u32x4_t* __restrict__ W, int rows, int cols,
+                                                            u32x2_t* __restrict__ q, float* __restrict__ scale) {
+    __shared__ float part[4];
+    const int nbr = rows / 128, nbc = cols / 128;
+    const int b = blockIdx.x;
+    const int g = b / (nbr * nbc), rb = (b / nbc) % nbr, cb = b % nbc;
+    const int vpr = cols / 8;
+    const int tr = threadIdx.x >> 4, tc = threadIdx.x & 15;   // 16 rows x 16 vectors per pass
+    const int64_t base = ((int64_t)g * rows + rb * 128) * vpr + cb * 16 + tc;
+    u32x4_t v[8];
+    float m = 0.f;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        v[it] = W[base + (int64_t)(it * 16 + tr) * vpr];
+        m = fmaxf(m, amax8(v[it]));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+    const float s = block_scale(m);
+    if (threadIdx.x == 0) scale[b] = s;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) q[base + (int64_t)(it * 16 + tr) * vpr] = cvt8_e4m3(v[it], s);
+}
 
 extern "C" moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X, moe_qblock block,
                                        int groups, int64_t rows, int cols, const int32_t* rows_dev,
                                        void* q, float* scale) {
     if (!ctx) return MOE_ERR_ARG;
-    MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_fp8_quantize: not built yet");
+    if (!X || !q || !scale) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize: NULL pointer");
+    if (rows < 0 || cols < 1 || groups < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize: bad sizes");
+    if (cols % 8) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize: cols must be a multiple of 8");
+    hipStream_t s = (hipStream_t)stream;
+    const int cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
+    if (rows == 0) return MOE_OK;
+    switch (block) {
+        case MOE_Q_1x128: {
+            if (cols % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(1x128): cols %% 128 != 0");
+            if (groups != 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(1x128): groups must be 1");
+            const int64_t nb = rows * (cols / 128);
+            int64_t grid = ceil_div64(nb * 16, 256);
+            if (grid > (int64_t)cu * 32) grid = (int64_t)cu * 32;
+            hipLaunchKernelGGL(quant_1x128_kernel, dim3((unsigned)grid), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
+                               rows_dev, (u32x2_t*)q, scale);
+            break;
+        }
+        case MOE_Q_128x1: {
+            if (rows % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(128x1): rows %% 128 != 0");
+            if (groups != 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(128x1): groups must be 1");
+            const int64_t npanels = (rows / 128) * ceil_div64(cols / 8, 64);
+            int64_t grid = ceil_div64(npanels, 4);
+            if (grid > (int64_t)cu * 16) grid = (int64_t)cu * 16;
+            hipLaunchKernelGGL(quant_128x1_kernel, dim3((unsigned)grid), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
+                               rows_dev, (u32x2_t*)q, scale);
+            break;
+        }
+        case MOE_Q_128x128: {
+            if (rows % 128 || cols % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(128x128): rows, cols %% 128 != 0");
+            if (rows_dev) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(128x128): rows_dev is not used for weights");
+            const int64_t nb = (int64_t)groups * (rows / 128) * (cols / 128);
+            if (nb > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(128x128): too many blocks");
+            hipLaunchKernelGGL(quant_128x128_kernel, dim3((unsigned)nb), dim3(256), 0, s, (const u32x4_t*)X, (int)rows, cols,
+                               (u32x2_t*)q, scale);
+            break;
+        }
+        default:
+            MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize: bad block kind");
+    }
+    MOE_LAUNCH_CHECK(ctx, "moe_fp8_quantize");
+    return MOE_OK;
 }

@@ -1,61 +1,70 @@
-// Grouped GEMM for the expert MLP (Sec. 2.1.4, 4.3.2), device-initiated (Sec. 4.3.7):
-// one persistent launch per call, every expert's extent is read from `offsets` on the
-// device; forward, data-gradient and weight-gradient (Sec. 4.2.3 "W/D split") are three
-// instantiations of one kernel.
+// Grouped GEMM for the expert MLP (Sec. 2.1.4, 4.3.2), device-initiated (Sec. 4.3.7): one
+// persistent launch per call, every expert's extent is read from `offsets` on the device;
+// forward, data-gradient and weight-gradient (Sec. 4.2.3 "W/D split") in bf16, forward and
+// data-gradient also in blockwise fp8 (Sec. 5.3.2), are instantiations of one kernel.
 //
-// The kernel computes OUT[i,j] = sum_c P[i,c] * Q[j,c] on a 256x256 output tile per
-// workgroup (8 wavefronts, 2 x 4), walking the contraction index c in steps of 64:
+// The kernel computes OUT[i,j] = sum_c P[i,c] * Q[j,c] on a 256x256 output tile per workgroup
+// (8 wavefronts as 2 x 4, wave tile 128x64 = 4x2 MFMA blocks of 32x32):
 //     forward : P = activations [rows,K]   Q = W_e [N,K]        OUT = C[rows,N]
 //     dgrad   : P = dC [rows,N]            Q = W_e as [K,N]^T   OUT = dA[rows,K]
 //     wgrad   : P = dC as [N,rows]^T       Q = A as [K,rows]^T  OUT = dW_e[N,K]
-// Operand tiles (32 KB each) are fetched by direct global->LDS loads, 16 B per lane,
-// into two LDS stages, so step s+1 streams in while the MFMAs of step s run.
-// An operand whose contraction index is contiguous in memory ("k-major", tile
-// [256][64]) is read for the 32x32x16 bf16 MFMA with ds_read_b128; one whose
-// contraction index is the memory row ("c-major", tile [64][256]: the weight in dgrad,
-// both operands in wgrad) is read with the transposing ds_read_b64_tr_b16, so no
-// transposed copy of weights or activations is ever made.  Both tile layouts XOR-swizzle
-// their 16-byte slots so the operand reads spread over the LDS banks; the swizzle is
-// applied on the global side of the DMA (each lane picks which 16 bytes it fetches).
-// A wave's two 32-column sub-tiles are 128 columns apart: with the SwiGLU epilogue they
-// are the gate and up columns of the same features, so the activation (forward) and its
-// derivative (fc2 dgrad) are applied to the fp32 accumulators in registers.
+//
+// Operand stream.  The contraction is walked in stages of 64 bytes per operand row (32 bf16 or
+// 64 fp8 elements).  Each stage's two 16 KB operand tiles are fetched by direct global->LDS
+// loads (16 B per lane) into one of GG_NS LDS stages; up to GG_NS-2 later stages are in flight
+// while one is consumed.  Every stage is its own LDS object so that the compiler can see that
+// the DMA writes of a later stage do not alias the operand reads of the current one.
+//
+// LDS layouts.  An operand whose contraction index is contiguous in memory ("k-major", tile
+// [256 rows][64 B]) is read with ds_read_b128; one whose contraction index is the memory row
+// ("c-major", tile [32 or 64 rows][256 columns]: the weight in dgrad, both operands in wgrad) is
+// read with the transposing ds_read_b64_tr_b16 / _b8, so no transposed copy of weights or
+// activations is ever made.  The 16-byte slots of every tile are XOR-swizzled with the row so the
+// operand reads are free of bank conflicts; the swizzle is applied on the global side of the DMA
+// (each lane chooses which 16 bytes it fetches; the LDS side of a DMA is always lane-linear).
+//
+// Schedule ("ping-pong").  The two waves that share a SIMD (wave w and w+4) run one phase apart:
+// while one issues the MFMAs of a stage with all operands already in registers, the other fetches
+// its next operands from LDS; they swap at fence-free workgroup barriers.  The DMA instructions
+// that refill a stage are slipped in between the MFMAs, so memory requests are spread over time
+// instead of bursting after a barrier.
+//   per stage s:   A_s: LDS -> registers      barrier      B_s: MFMAs (+ DMA of stage s+NS-1)      barrier
+//   group 1 (waves 4-7) takes one extra barrier up front, group 0 one at the end.
+// Buffer (s-1) % NS was last read in A_{s-1} of group 1, which ends one barrier before B_s of
+// group 0 begins, so refilling it during B_s is safe; each wave waits for its own loads of stage
+// s+1 at the end of A_s, before the barrier that precedes the first read of that stage.
+//
+// MFMAs are issued as (Q fragment, P fragment): a lane's 16 accumulators of a block are one
+// output row and 4 groups of 4 consecutive columns (8-byte stores), and the wave's two column
+// sub-tiles are 128 columns apart, i.e. the gate and up columns of the same features when the
+// SwiGLU epilogue is on: the activation (forward) and its derivative (fc2 dgrad) are applied to
+// the fp32 accumulators in registers.
+//
+// fp8: operands are E4M3 codes; a stage is one v_mfma_scale_f32_32x32x64_f8f6f4 per block with unit
+// hardware scales.  The fp32 block scales (1x128 per activation row, 128x128 per weight block) are
+// applied in software: a lane's accumulators of one block all share the factor
+// s = a_scale[row, kb] * b_scale[block], so the accumulator is kept in units of the current
+// factor: at every 128-wide contraction block it is multiplied by s_prev / s_new before the raw
+// products are added, and by the last factor in the epilogue.  No second set of accumulators.
 #include "common.h"
 
 #define GG_BM 256
 #define GG_BN 256
-#ifndef GG_PINGPONG
-#define GG_PINGPONG 1  // 1: ping-pong schedule; 0: plain multi-stage pipeline
-#endif
-#ifndef GG_SPREAD
-#define GG_SPREAD 1  // 1: DMA instructions are interleaved with the MFMAs of the compute phase
-#endif
-#ifndef GG_PFD
-#define GG_PFD 0   // L2 prefetch distance in stages (0 = off)
-#endif
-#ifndef GG_BK
-#define GG_BK 32   // contraction elements per pipeline stage (32 or 64)
-#endif
 #ifndef GG_NS
-#define GG_NS 4    // LDS pipeline stages (2..4); GG_NS * 2 * GG_STAGE_BYTES must fit in 160 KB
+#define GG_NS 4  // LDS stages (3 or 4)
+#endif
+#ifndef GG_BAND
+#define GG_BAND 4  // row-tiles per band of the tile order
 #endif
 #define GG_THREADS 512
 #define GG_MAX_E 1024
-#define GG_STAGE_BYTES (GG_BM * GG_BK * 2)  // one operand tile per stage
-#define GG_ROWB (GG_BK * 2)                 // bytes of a k-major tile row
-#define GG_KM_SLOTS (GG_ROWB / 16)          // 16-byte slots per k-major row
-#define GG_KM_ROWS (1024 / GG_ROWB)         // k-major rows per 1 KB DMA chunk
-#define GG_CH (GG_BM / GG_KM_ROWS / 8)      // DMA chunks per wave per operand per stage
-#define GG_KK (GG_BK / 16)                  // 16-wide MFMA sub-steps per stage
-#ifndef GG_BAND
-#define GG_BAND 4                           // row-tiles per band of the tile order
-#endif
-// k-major tile swizzle: 16-byte slot ^= KM_SWZ(row).  256 / GG_ROWB rows share one 256-byte
-// bank line; XOR-ing the slot with the row bits above that makes 16 consecutive rows hit 16
-// different (position in line, slot) pairs: a conflict-free ds_read_b128 for 16 lanes at a time
-// (measured: SQ_LDS_BANK_CONFLICT = 0).
-#define GG_KM_SHIFT (GG_BK == 64 ? 1 : 2)
-#define KM_SWZ(row) (((row) >> GG_KM_SHIFT) & (GG_KM_SLOTS - 1))
+#define GG_ROWB 64                      // bytes of a k-major tile row per stage
+#define GG_STAGE_BYTES (GG_BM * GG_ROWB)  // one operand tile per stage: 16 KB
+#define GG_CH 2                         // 1 KB DMA chunks per wave per operand per stage
+#define GG_DMA_PER_STAGE (2 * GG_CH)
+// k-major swizzle: four 64-byte rows share a 256-byte bank line; slot ^= bits 2..3 of the row makes
+// 16 consecutive rows hit 16 different (position in line, slot) pairs (SQ_LDS_BANK_CONFLICT = 0)
+#define KM_SWZ(row) (((row) >> 2) & 3)
 
 enum { GG_FWD = 0, GG_DGRAD = 1, GG_WGRAD = 2 };
 enum { GG_EPI_STORE = 0, GG_EPI_SWIGLU = 1, GG_EPI_SWIGLU_BWD = 2 };
@@ -63,49 +72,62 @@ enum { GG_EPI_STORE = 0, GG_EPI_SWIGLU = 1, GG_EPI_SWIGLU_BWD = 2 };
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef const __attribute__((address_space(1))) void gbl_void_t;
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef int i32x2_t __attribute__((ext_vector_type(2)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+typedef __attribute__((address_space(3))) i32x2_t lds_i32x2_t;
+
+static_assert(GG_NS == 3 || GG_NS == 4, "the schedule needs a third stage for the interleaved DMA to land in");
+static_assert(2 * GG_NS * GG_STAGE_BYTES <= 144 * 1024, "pipeline stages exceed the LDS budget");
 
 __device__ __forceinline__ void dma16(const void* g, void* lds_wave_base) {
     // each lane moves 16 bytes: LDS destination = wave-uniform base + lane * 16
     __builtin_amdgcn_global_load_lds((gbl_void_t*)g, (lds_void_t*)lds_wave_base, 16, 0, 0);
 }
 
-// s_waitcnt vmcnt(0) only (gfx9 encoding: expcnt and lgkmcnt fields left at their maxima)
-__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-// Workgroup barrier without the memory fence __syncthreads() carries: the fence would drain
-// every DMA load in flight (vmcnt(0)) and serialise the pipeline.  The wave has already waited
-// for its own loads of the stage being published (wait_stage); LDS reads after the barrier are
-// ordered by the hardware.  The empty asm statements keep the compiler from moving memory
-// operations across the barrier.
+// Workgroup barrier without the memory fence __syncthreads() carries: the fence would drain every
+// DMA load in flight (vmcnt(0)) and serialise the pipeline.  The wave has already waited for its own
+// loads of the stage being published; LDS reads after the barrier are ordered by the hardware.
+// The empty asm statements and sched_barriers keep the compiler from moving anything across.
 __device__ __forceinline__ void stage_barrier() {
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);  // nothing (MFMAs included) is scheduled across
+    __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
 }
-__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }       // lgkmcnt(0)
-__device__ __forceinline__ void wait_vm0_lgkm0() { __builtin_amdgcn_s_waitcnt(0x0070); }   // vmcnt(0) lgkmcnt(0)
-
-// wait until at most `newer` * GG_CH * 2 of this wave's DMA loads are still in flight
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0)
+// s_waitcnt vmcnt(n) only (gfx9 encoding, other counters at their maxima): at most `newer` younger
+// stages of this wave's DMA loads may still be in flight
 __device__ __forceinline__ void wait_stage(int newer) {
     if (newer <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);
-    else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * GG_CH));
-    else __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * GG_CH));
+    else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | GG_DMA_PER_STAGE);
+    else __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * GG_DMA_PER_STAGE));
 }
 
 __device__ __forceinline__ float sigmoid_f(float g) { return 1.0f / (1.0f + __expf(-g)); }
 
-// ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the address of
-// 4 consecutive 16-bit elements (row i/4, columns 4*(i%4)..+3 of a 4x16 block) and
-// receives column i of that block (rows 0..3).  Two of them give the 8 contraction
-// values per lane that the 32x32x16 MFMA operand needs.
-__device__ __forceinline__ bf16x8_t lds_read_tr8(const char* p_lo, const char* p_hi) {
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the address of 4 consecutive
+// 16-bit elements (row i/4, columns 4*(i%4)..+3 of a 4x16 block) and receives column i of that block
+// (rows 0..3).  Two of them give the 8 contraction values a lane feeds to the 32x32x16 MFMA.
+__device__ __forceinline__ bf16x8_t lds_read_tr16x8(const char* p_lo, const char* p_hi) {
     s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p_lo);
     s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p_hi);
-    typedef short s16x8_t __attribute__((ext_vector_type(8)));
     s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8_t, v);
+}
+// ds_read_b64_tr_b8: lane i of a 16-lane group supplies the address of 8 consecutive bytes (row i/2,
+// columns 8*(i%2)..+7 of an 8x16 block) and receives column i (rows 0..7).  Four reads, 8 rows apart,
+// give the 32 contraction values a lane feeds to the 32x32x64 fp8 MFMA.
+__device__ __forceinline__ i32x8_t lds_read_tr8x32(const char* p) {
+    i32x2_t r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)p);
+    i32x2_t r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + 8 * 256));
+    i32x2_t r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + 16 * 256));
+    i32x2_t r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + 24 * 256));
+    i32x8_t v = {r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
+    return v;
 }
 
 // 4 consecutive bf16 <-> 4 floats, one 8-byte access
@@ -122,45 +144,44 @@ __device__ __forceinline__ void ld4_bf16(const bf16_t* p, float* v) {
 }
 
 struct gg_args {
-    const bf16_t* P;      // fwd: A, dgrad: dC, wgrad: dC
-    const bf16_t* Q;      // fwd/dgrad: W [E,N,K], wgrad: A
+    const void* P;         // fwd: A, dgrad: dC, wgrad: dC   (bf16, or E4M3 codes)
+    const void* Q;         // fwd/dgrad: W [E,N,K], wgrad: A
+    const float* p_scale;  // fp8: [rows, C/128] for the row-indexed operand (C = contraction length)
+    const float* q_scale;  // fp8: [E, N/128, K/128] for the weights
     const int32_t* offsets;
     int E, N, K;
     int64_t Rcap;
-    void* out;            // fwd: C (may be NULL with SWIGLU), dgrad: dA or dZ, wgrad: dW
-    bf16_t* out_act;      // fwd SWIGLU: activation output
-    const bf16_t* Zsaved; // dgrad SWIGLU_BWD: saved pre-activation [rows, 2K]
-    const char* zeros;    // >= 16 zero bytes (feeds the wgrad contraction tail)
+    void* out;             // fwd: C (may be NULL with SWIGLU), dgrad: dA or dZ, wgrad: dW
+    bf16_t* out_act;       // fwd SWIGLU: activation output
+    const bf16_t* Zsaved;  // dgrad SWIGLU_BWD: saved pre-activation [rows, 2K]
+    const char* zeros;     // >= 16 zero bytes (feeds the wgrad contraction tail)
     int* dev_err;
-    int accumulate;       // wgrad: out += result
+    int accumulate;        // wgrad: out += result
 };
 
 // MODE: GG_FWD / GG_DGRAD / GG_WGRAD.  EPI: see enum.  OUT_F32: fp32 output (wgrad only).
-static_assert(!(GG_PINGPONG && GG_SPREAD) || (GG_NS >= 3 && GG_BK == 32), "interleaved DMA needs a third stage to land in");
-static_assert(GG_NS >= 2 && GG_NS <= 4 && (GG_BK == 32 || GG_BK == 64), "unsupported pipeline shape");
-static_assert(2 * (GG_NS - 2) * GG_CH < 16, "wait_stage immediate must fit the 4-bit vmcnt field");
-static_assert(2 * GG_NS * GG_STAGE_BYTES <= 144 * 1024, "pipeline stages exceed the LDS budget");
-
-template <int MODE, int EPI, bool OUT_F32>
+// FP8: operands are E4M3 codes with block scales (fwd and dgrad only).
+template <int MODE, int EPI, bool OUT_F32, bool FP8>
 __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
-    // one LDS object per stage and operand: distinct objects let the compiler see that the
-    // DMA writes of a later stage do not alias the operand reads of the current one
     __shared__ __attribute__((aligned(1024))) char ldsP0[GG_STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsP1[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsP2[GG_NS > 2 ? GG_STAGE_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char ldsP2[GG_STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsP3[GG_NS > 3 ? GG_STAGE_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) char ldsQ0[GG_STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsQ1[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsQ2[GG_NS > 2 ? GG_STAGE_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char ldsQ2[GG_STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsQ3[GG_NS > 3 ? GG_STAGE_BYTES : 16];
-#if GG_PFD > 0
-    __shared__ __attribute__((aligned(256))) char pf_dummy[8 * 256];
-#endif
     __shared__ int offs[GG_MAX_E + 1];
     __shared__ int tile_start[GG_MAX_E + 1];
 
+    static_assert(!(FP8 && MODE == GG_WGRAD), "fp8 weight gradients are not built");
     constexpr bool P_CMAJ = (MODE == GG_WGRAD);
     constexpr bool Q_CMAJ = (MODE != GG_FWD);
+    constexpr int ES = FP8 ? 1 : 2;            // operand element size
+    constexpr int BKE = GG_ROWB / ES;           // contraction elements per stage: 32 bf16 / 64 fp8
+    constexpr int CM_ROWS = 1024 / (256 * ES);  // c-major rows per 1 KB DMA chunk: 2 bf16 / 4 fp8
+    constexpr int CM_SLOTS = 256 * ES / 16;     // 16-byte slots per c-major row: 32 bf16 / 16 fp8
+    constexpr int EPS = 16 / ES;                // elements per 16-byte slot
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -204,37 +225,42 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     const int q = (G & 7) ? (int)blockIdx.x : ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3);
 
     // ---- per-lane constants: DMA side ----
-    // k-major tile: a 1 KB DMA chunk = 8 rows x 128 B; lane -> (row l/8, slot l%8), slot ^= KM_SWZ(row)
-    const int km_row = lane / GG_KM_SLOTS;
-    // c-major tile: a 1 KB chunk = 2 rows x 512 B; lane -> (row l/32, slot l%32), slot ^= 4*(row%4)
-    const int cm_row = lane >> 5;
+    // k-major tile: a 1 KB chunk = 16 rows x 64 B; lane -> (row l/4, slot l%4), slot ^= KM_SWZ(row)
+    const int km_row = lane >> 2;
+    // c-major tile: a 1 KB chunk = CM_ROWS rows; lane -> (row l / CM_SLOTS, slot l % CM_SLOTS)
+    //   bf16: slot ^= 4 * (row % 4);  fp8: slot ^= 2 * (row % 8)
+    const int cm_row = lane / CM_SLOTS;
     // ---- per-lane constants: fragment side ----
     const int fr_row = lane & 31;
     const int fr_khalf = lane >> 5;
     const int fr_swz = KM_SWZ(lane & 31);
     const int tr_i = lane & 15;
     const int tr_blk = lane >> 4;
-    // c-major read: row = kk*16 + 8*(blk>>1) + 4*hh + (i>>2); slot = (colblock/8 ^ 4*(i>>2)) + 2*(blk&1) + ((i&3)>>1)
-    const int tr_rowoff = (8 * (tr_blk >> 1) + (tr_i >> 2)) * 512;
-    const int tr_low = 2 * (tr_blk & 1) + ((tr_i & 3) >> 1);
-    const int tr_xor = 4 * (tr_i >> 2);
+    // c-major read of a 32-column operand block at column block cb (a multiple of 32):
+    //   bf16 (row pitch 512 B): row = 16 kk + 8 (blk >> 1) + 4 hh + (i >> 2),
+    //        slot = (cb / 8 ^ 4 (i >> 2)) + 2 (blk & 1) + ((i & 3) >> 1), byte (i & 1) * 8
+    //   fp8  (row pitch 256 B): row = 32 (blk >> 1) + 8 g + (i >> 1),
+    //        slot = (cb / 16 ^ 2 (i >> 1)) + (blk & 1), byte (i & 1) * 8
+    const int tr_rowoff = FP8 ? (32 * (tr_blk >> 1) + (tr_i >> 1)) * 256 : (8 * (tr_blk >> 1) + (tr_i >> 2)) * 512;
+    const int tr_low = FP8 ? (tr_blk & 1) : 2 * (tr_blk & 1) + ((tr_i & 3) >> 1);
+    const int tr_xor = FP8 ? 2 * (tr_i >> 1) : 4 * (tr_i >> 2);
     const int tr_byte = (tr_i & 1) * 8;
 
     int p_rd[4], q_rd[2];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        if (P_CMAJ) p_rd[i] = tr_rowoff + ((((wm * 128 + i * 32) >> 3) ^ tr_xor) + tr_low) * 16 + tr_byte;
+        if (P_CMAJ) p_rd[i] = tr_rowoff + ((((wm * 128 + i * 32) / EPS) ^ tr_xor) + tr_low) * 16 + tr_byte;
         else p_rd[i] = (wm * 128 + i * 32 + fr_row) * GG_ROWB;
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        if (Q_CMAJ) q_rd[j] = tr_rowoff + ((((j * 128 + wn * 32) >> 3) ^ tr_xor) + tr_low) * 16 + tr_byte;
+        if (Q_CMAJ) q_rd[j] = tr_rowoff + ((((j * 128 + wn * 32) / EPS) ^ tr_xor) + tr_low) * 16 + tr_byte;
         else q_rd[j] = (j * 128 + wn * 32 + fr_row) * GG_ROWB;
     }
 
     int e_hint = 0;
     for (int t = q; t < total_tiles; t += G) {
-        // ---- locate the tile ----
+        // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
         int e = e_hint;
         while (e + 1 < E && t >= tile_start[e + 1]) ++e;
         e_hint = e;
@@ -258,117 +284,104 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         // contraction range
         const int c_lo = (MODE == GG_WGRAD) ? row_lo : 0;
         const int c_hi = (MODE == GG_WGRAD) ? row_hi : (MODE == GG_FWD ? K : N);
-        const int KT = (c_hi - c_lo + GG_BK - 1) / GG_BK;
+        const int KT = (c_hi - c_lo + BKE - 1) / BKE;
 
-        // ---- DMA source pointers (4 chunks per operand per lane) ----
+        // ---- DMA source pointers (GG_CH chunks per operand per lane) ----
         const char* pg[GG_CH];
         const char* qg[GG_CH];
-        int64_t p_step, q_step;  // byte advance per contraction step
+        int64_t p_step, q_step;  // byte advance per stage
         if (P_CMAJ) {
             // P = dC [rows, N]: contraction row c, columns i0..i0+255
-            p_step = (int64_t)GG_BK * N * 2;
+            p_step = (int64_t)BKE * N * ES;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
-                const int row = (wave * GG_CH + i) * 2 + cm_row;
-                const int slot = (lane & 31) ^ (4 * (row & 3));
-                int col = i0 + slot * 8;
-                col = col <= N - 8 ? col : N - 8;
-                pg[i] = (const char*)a.P + ((int64_t)(c_lo + row) * N + col) * 2;
+                const int row = (wave * GG_CH + i) * CM_ROWS + cm_row;
+                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
+                int col = i0 + slot * EPS;
+                col = col <= N - EPS ? col : N - EPS;
+                pg[i] = (const char*)a.P + ((int64_t)(c_lo + row) * N + col) * ES;
             }
         } else {
             const int ldp = (MODE == GG_FWD) ? K : N;
-            p_step = GG_BK * 2;
+            p_step = GG_ROWB;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
-                const int p = (wave * GG_CH + i) * GG_KM_ROWS + km_row;  // tile row 0..255
+                const int p = (wave * GG_CH + i) * 16 + km_row;  // tile row 0..255
                 int64_t r = (int64_t)i0 + p;
                 r = r < a.Rcap ? r : a.Rcap - 1;
-                const int km_gslot = (lane & (GG_KM_SLOTS - 1)) ^ KM_SWZ(p);
-                pg[i] = (const char*)a.P + (r * ldp + km_gslot * 8) * 2;
+                const int gslot = (lane & 3) ^ KM_SWZ(p);
+                pg[i] = (const char*)a.P + r * ldp * ES + gslot * 16;
             }
         }
         if (Q_CMAJ) {
             // dgrad: Q = W_e [N,K]: contraction row n, columns (k) j0.. ; wgrad: Q = A [rows,K]
-            q_step = (int64_t)GG_BK * K * 2;
-            const char* qbase = (MODE == GG_DGRAD) ? (const char*)a.Q + (int64_t)e * N * K * 2 : (const char*)a.Q;
+            q_step = (int64_t)BKE * K * ES;
+            const char* qbase = (MODE == GG_DGRAD) ? (const char*)a.Q + (int64_t)e * N * K * ES : (const char*)a.Q;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
-                const int row = (wave * GG_CH + i) * 2 + cm_row;
-                const int slot = (lane & 31) ^ (4 * (row & 3));
-                int col = (slot < 16 ? j0 : j1 - 128) + slot * 8;
-                col = col <= K - 8 ? col : K - 8;
-                qg[i] = qbase + ((int64_t)(c_lo + row) * K + col) * 2;
+                const int row = (wave * GG_CH + i) * CM_ROWS + cm_row;
+                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
+                int col = (slot < CM_SLOTS / 2 ? j0 : j1 - 128) + slot * EPS;
+                col = col <= K - EPS ? col : K - EPS;
+                qg[i] = qbase + ((int64_t)(c_lo + row) * K + col) * ES;
             }
         } else {
-            q_step = GG_BK * 2;
+            q_step = GG_ROWB;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
-                const int p = (wave * GG_CH + i) * GG_KM_ROWS + km_row;  // tile row 0..255
+                const int p = (wave * GG_CH + i) * 16 + km_row;  // tile row 0..255
                 int n = (p < 128 ? j0 : j1 - 128) + p;
                 n = n < N ? n : N - 1;
-                const int km_gslot = (lane & (GG_KM_SLOTS - 1)) ^ KM_SWZ(p);
-                qg[i] = (const char*)a.Q + (((int64_t)e * N + n) * K + km_gslot * 8) * 2;
+                const int gslot = (lane & 3) ^ KM_SWZ(p);
+                qg[i] = (const char*)a.Q + ((int64_t)e * N + n) * K * ES + gslot * 16;
             }
         }
 
-#if GG_PFD > 0
-        const char* pf_ptr;
-        {
-            const int prow = wave * 32 + (lane & 31);  // tile row 0..255 of P (lanes 0-31) or Q (lanes 32-63)
-            if (lane < 32) {
-                int64_t r = (int64_t)i0 + prow;
-                r = r < a.Rcap ? r : a.Rcap - 1;
-                pf_ptr = (const char*)a.P + r * K * 2;
-            } else {
-                int n = (prow < 128 ? j0 : j1 - 128) + prow;
-                n = n < N ? n : N - 1;
-                pf_ptr = (const char*)a.Q + ((int64_t)e * N + n) * K * 2;
-            }
-        }
-#endif
-#ifdef GG_KROT
-        const int krot = KT > 0 ? (int)(((unsigned)q * GG_KROT) % (unsigned)KT) : 0;
-#endif
-        auto issue = [&](int kt, char* sp, char* sq) {
-#ifdef GG_DBG_NODMA
-            if (kt > 0) return;
-#endif
-#ifdef GG_KROT
-            // contraction steps taken in a rotated order that differs between workgroups, so the
-            // workgroups of an XCD do not all ask the same L2 channels for the same k at once
-            kt = (kt + krot) % KT;
-#endif
-#pragma unroll
-            for (int i = 0; i < GG_CH; ++i) {
-                const char* ps = pg[i] + kt * p_step;
-                const char* qs = qg[i] + kt * q_step;
-                if (MODE == GG_WGRAD) {  // contraction tail of the expert: feed zeros
-                    const int row = c_lo + kt * GG_BK + (wave * GG_CH + i) * 2 + cm_row;
-                    ps = row < c_hi ? ps : a.zeros;
-                    qs = row < c_hi ? qs : a.zeros;
-                }
-                dma16(ps, sp + (wave * GG_CH + i) * 1024);
-                dma16(qs, sq + (wave * GG_CH + i) * 1024);
-            }
-#if GG_PFD > 0
-            // L2 prefetch: touch one dword of every 128-byte line of the stage GG_PFD steps ahead
-            // (into a dummy LDS word), so that the later DMA finds the line already filled in L2
-            if (MODE == GG_FWD && kt + GG_PFD < KT && ((kt + GG_PFD) * GG_ROWB) % 128 == 0)
-                __builtin_amdgcn_global_load_lds((gbl_void_t*)(pf_ptr + (int64_t)(kt + GG_PFD) * GG_ROWB),
-                                                 (lds_void_t*)(pf_dummy + wave * 256), 4, 0, 0);
-#endif
-        };
-
-        // one of the 2 * GG_CH DMA instructions of a stage (idx: operand = idx & 1, chunk = idx >> 1)
+        // one of the GG_DMA_PER_STAGE DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
         auto issue_one = [&](int kt, char* sp, char* sq, int idx) {
             const int i = idx >> 1;
             const char* src = (idx & 1) ? qg[i] + kt * q_step : pg[i] + kt * p_step;
-            if (MODE == GG_WGRAD) {
-                const int row = c_lo + kt * GG_BK + (wave * GG_CH + i) * 2 + cm_row;
+            if (MODE == GG_WGRAD) {  // contraction tail of the expert: feed zeros
+                const int row = c_lo + kt * BKE + (wave * GG_CH + i) * CM_ROWS + cm_row;
                 src = row < c_hi ? src : a.zeros;
             }
             dma16(src, ((idx & 1) ? sq : sp) + (wave * GG_CH + i) * 1024);
         };
+
+        // ---- fp8 block scales: s = p_scale[row, kb] * q_scale[block]; per lane 4 rows x 2 column blocks ----
+        const float* ps_ptr[4];
+        const float* qs_ptr[2];
+        int64_t qs_step = 0;
+        float s_cur[4][2], ps_nxt[4], qs_nxt[2];
+        const int CB = (c_hi - c_lo) / 128;  // contraction blocks
+        if (FP8) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int64_t r = (int64_t)i0 + wm * 128 + i * 32 + fr_row;
+                r = r < a.Rcap ? r : a.Rcap - 1;
+                ps_ptr[i] = a.p_scale + r * CB;
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                int col = (j ? j1 : j0) + wn * 32;
+                col = col < J ? col : J - 1;
+                if (MODE == GG_FWD) {  // q_scale[e, col/128, kb]
+                    qs_ptr[j] = a.q_scale + ((int64_t)e * (N / 128) + col / 128) * (K / 128);
+                    qs_step = 1;
+                } else {               // dgrad: contraction over N: q_scale[e, kb, col/128]
+                    qs_ptr[j] = a.q_scale + (int64_t)e * (N / 128) * (K / 128) + col / 128;
+                    qs_step = K / 128;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ps_nxt[i] = CB > 0 ? ps_ptr[i][0] : 1.0f;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) qs_nxt[j] = CB > 0 ? qs_ptr[j][0] : 1.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) s_cur[i][j] = 1.0f;
+        }
 
         f32x16_t acc[4][2];
 #pragma unroll
@@ -378,91 +391,111 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 #pragma unroll
                 for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
 
-        auto compute = [&](const char* sp, const char* sq) {
-#pragma unroll
-            for (int kk = 0; kk < GG_KK; ++kk) {
-                const int km_slot = ((kk * 2 + fr_khalf) ^ fr_swz) * 16;
-                bf16x8_t pf[4], qf[2];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (P_CMAJ) pf[i] = lds_read_tr8(sp + p_rd[i] + kk * 8192, sp + p_rd[i] + kk * 8192 + 2048);
-                    else pf[i] = *(const bf16x8_t*)(sp + p_rd[i] + km_slot);
-                }
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    if (Q_CMAJ) qf[j] = lds_read_tr8(sq + q_rd[j] + kk * 8192, sq + q_rd[j] + kk * 8192 + 2048);
-                    else qf[j] = *(const bf16x8_t*)(sq + q_rd[j] + km_slot);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[j], pf[i], acc[i][j], 0, 0, 0);
-            }
-        };
-
-#if GG_PINGPONG
-        // Ping-pong schedule.  The two waves that share a SIMD (wave w and w+4) run one phase apart:
-        // while one issues the 16 MFMAs of a phase with all operands already in registers, the other
-        // fetches its next operands from LDS (and issues the DMA of a later stage); they swap at a
-        // workgroup barrier.  The matrix pipe always has a wave with a full queue of independent MFMAs.
-        //   per phase h:   A_h: LDS -> registers      barrier      B_h: 16 MFMAs      barrier
-        //   group 1 (waves 4-7) takes one extra barrier up front, group 0 one at the end.
-        // A phase covers 32 contraction elements: a whole stage when BK = 32 (GG_NS stages, up to
-        // GG_NS-1 stages of DMA in flight to cover the L2-miss latency), half a stage when BK = 64.
-        // The DMA that refills a buffer is issued at the start of the A phase that follows the last A
-        // phase reading it in the other group (one barrier later), and each wave waits for its own
-        // loads of the next stage at the end of the A phase before that stage's first read.
         {
             char* const SP[4] = {ldsP0, ldsP1, ldsP2, ldsP3};
             char* const SQ[4] = {ldsQ0, ldsQ1, ldsQ2, ldsQ3};
+            // operand fragments of one stage: bf16 2 x (4 + 2) x 4 VGPRs, fp8 (4 + 2) x 8 VGPRs
             bf16x8_t pf[2][4], qf[2][2];
-            auto fetch = [&](const char* sp, const char* sq, int half) {
-#ifdef GG_DBG_NOMMA
-                return;
-#endif
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {
-                    const int kk = half * 2 + k2;
-                    const int km_slot = ((kk * 2 + fr_khalf) ^ fr_swz) * 16;
+            i32x8_t pf8[4], qf8[2];
+
+            auto fetch = [&](const char* sp, const char* sq) {
+                if (FP8) {
+                    const int s0 = ((2 * fr_khalf) ^ fr_swz) * 16, s1 = ((2 * fr_khalf + 1) ^ fr_swz) * 16;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        if (P_CMAJ) pf[k2][i] = lds_read_tr8(sp + p_rd[i] + kk * 8192, sp + p_rd[i] + kk * 8192 + 2048);
-                        else pf[k2][i] = *(const bf16x8_t*)(sp + p_rd[i] + km_slot);
+                        const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i] + s0), hi = *(const i32x4_t*)(sp + p_rd[i] + s1);
+                        pf8[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     }
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        if (Q_CMAJ) qf[k2][j] = lds_read_tr8(sq + q_rd[j] + kk * 8192, sq + q_rd[j] + kk * 8192 + 2048);
-                        else qf[k2][j] = *(const bf16x8_t*)(sq + q_rd[j] + km_slot);
+                        if (Q_CMAJ) {
+                            qf8[j] = lds_read_tr8x32(sq + q_rd[j]);
+                        } else {
+                            const i32x4_t lo = *(const i32x4_t*)(sq + q_rd[j] + s0), hi = *(const i32x4_t*)(sq + q_rd[j] + s1);
+                            qf8[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < 2; ++kk) {
+                        const int km_slot = ((kk * 2 + fr_khalf) ^ fr_swz) * 16;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (P_CMAJ) pf[kk][i] = lds_read_tr16x8(sp + p_rd[i] + kk * 8192, sp + p_rd[i] + kk * 8192 + 2048);
+                            else pf[kk][i] = *(const bf16x8_t*)(sp + p_rd[i] + km_slot);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            if (Q_CMAJ) qf[kk][j] = lds_read_tr16x8(sq + q_rd[j] + kk * 8192, sq + q_rd[j] + kk * 8192 + 2048);
+                            else qf[kk][j] = *(const bf16x8_t*)(sq + q_rd[j] + km_slot);
+                        }
                     }
                 }
             };
-            // 16 MFMAs; with GG_SPREAD the DMA instructions idx0 .. idx0+3 of stage `kt_dma` are slipped
-            // in after every fourth MFMA so the memory requests are spread over the phase
-            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq, int idx0) {
-#ifdef GG_DBG_NOMMA
-                return;
-#endif
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
+            // the MFMAs of one stage, with the GG_DMA_PER_STAGE DMA instructions of stage kt_dma slipped in
+            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq) {
+                if (FP8) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
 #pragma unroll
                         for (int j = 0; j < 2; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[k2][j], pf[k2][i], acc[i][j], 0, 0, 0);
-#if GG_SPREAD
-                        if ((i & 1) == 1) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (do_dma) issue_one(kt_dma, dp, dq, idx0 + k2 * 2 + (i >> 1));
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-#endif
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 0, 127, 0, 127);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (do_dma) issue_one(kt_dma, dp, dq, i);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                            for (int j = 0; j < 2; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk][j], pf[kk][i], acc[i][j], 0, 0, 0);
+                            if ((i & 1) == 1) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                if (do_dma) issue_one(kt_dma, dp, dq, kk * 2 + (i >> 1));
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                }
             };
+            // fp8: entering contraction block kb, bring the accumulators to the new block's units
+            auto rescale = [&](int kb) {
+                float s_new[4][2];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) s_new[i][j] = ps_nxt[i] * qs_nxt[j];
+                if (kb > 0) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const float ratio = s_cur[i][j] / s_new[i][j];
+#pragma unroll
+                            for (int x = 0; x < 16; ++x) acc[i][j][x] *= ratio;
+                        }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) s_cur[i][j] = s_new[i][j];
+                if (kb + 1 < CB) {  // next block's scales, needed two stages from now
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) ps_nxt[i] = ps_ptr[i][kb + 1];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) qs_nxt[j] = qs_ptr[j][(int64_t)(kb + 1) * qs_step];
+                }
+            };
+
             if (KT > 0) {
 #pragma unroll
                 for (int s = 0; s < GG_NS - 1; ++s)
-                    if (s < KT) issue(s, SP[s], SQ[s]);
+                    if (s < KT) {
+#pragma unroll
+                        for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(s, SP[s], SQ[s], x);
+                    }
                 wait_stage(min(GG_NS - 2, KT - 1));
                 stage_barrier();
                 if (wm == 1) stage_barrier();  // group 1 starts one phase later
@@ -471,26 +504,13 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     for (int s = 0; s < GG_NS; ++s) {
                         const int j = kt + s;
                         if (j < KT) {  // uniform
-                            const bool more = j + GG_NS - 1 < KT;
-                            char* const dp = SP[(s + GG_NS - 1) % GG_NS];
-                            char* const dq = SQ[(s + GG_NS - 1) % GG_NS];
-#if !GG_SPREAD
-                            if (more) issue(j + GG_NS - 1, dp, dq);
-#endif
-#if GG_BK == 64
-                            fetch(SP[s], SQ[s], 0);
+                            if (FP8 && (j & 1) == 0) rescale(j >> 1);
+                            fetch(SP[s], SQ[s]);
                             wait_lgkm0();
+                            // stage j+1 (issued during B_{j+2-NS}) must have landed; stage j+2 may be in flight
+                            if (j + 1 < KT) wait_stage(min(GG_NS - 3, KT - 2 - j));
                             stage_barrier();
-                            mma(more, j + GG_NS - 1, dp, dq, 0);
-                            stage_barrier();
-                            fetch(SP[s], SQ[s], 1);
-#else
-                            fetch(SP[s], SQ[s], 0);
-#endif
-                            wait_lgkm0();
-                            if (j + 1 < KT) wait_stage(min(GG_NS - 2 - (GG_SPREAD ? 1 : 0), KT - 2 - j));
-                            stage_barrier();
-                            mma(more, j + GG_NS - 1, dp, dq, GG_BK == 64 ? 4 : 0);
+                            mma(j + GG_NS - 1 < KT, j + GG_NS - 1, SP[(s + GG_NS - 1) % GG_NS], SQ[(s + GG_NS - 1) % GG_NS]);
                             stage_barrier();
                         }
                     }
@@ -498,37 +518,10 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 if (wm == 0) stage_barrier();  // re-align the two groups
             }
         }
-#else
-        {
-            char* const SP[4] = {ldsP0, ldsP1, ldsP2, ldsP3};
-            char* const SQ[4] = {ldsQ0, ldsQ1, ldsQ2, ldsQ3};
-            // prologue: stages 0 .. NS-2 in flight
-#pragma unroll
-            for (int s = 0; s < GG_NS - 1; ++s)
-                if (s < KT) issue(s, SP[s], SQ[s]);
-            for (int kt = 0; kt < KT; kt += GG_NS) {
-#pragma unroll
-                for (int s = 0; s < GG_NS; ++s) {
-                    const int j = kt + s;
-                    if (j < KT) {  // uniform
-                        // stage j must have landed; up to NS-2 younger stages may stay in flight
-                        wait_stage(min(GG_NS - 2, KT - 1 - j));
-                        stage_barrier();  // everyone's stage j is in LDS, everyone is done with stage j-1
-                        if (j + GG_NS - 1 < KT)
-                            issue(j + GG_NS - 1, SP[(s + GG_NS - 1) % GG_NS], SQ[(s + GG_NS - 1) % GG_NS]);
-                        compute(SP[s], SQ[s]);
-                    }
-                }
-            }
-        }
-
-#endif
 
         // ---- epilogue ----
-        // The MFMAs were issued as (Q fragment, P fragment), so a lane's 16 accumulators of a 32x32
-        // block are one output row (P index = lane % 32) and four groups of 4 consecutive output
-        // columns (Q index = 8 g + 4 (lane / 32) + 0..3): every store is 8 contiguous bytes of bf16
-        // (16 of fp32) and the SwiGLU partners sit in the same lane.
+        // A lane holds, per 32x32 block, one output row (P index = lane % 32) and four groups of 4
+        // consecutive output columns (Q index = 8 g + 4 (lane / 32) + 0..3).
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = i0 + wm * 128 + i * 32 + fr_row;
@@ -542,6 +535,10 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 for (int x = 0; x < 4; ++x) {
                     v0[x] = acc[i][0][4 * g + x];
                     v1[x] = acc[i][1][4 * g + x];
+                    if (FP8) {
+                        v0[x] *= s_cur[i][0];
+                        v1[x] *= s_cur[i][1];
+                    }
                 }
                 if (EPI == GG_EPI_SWIGLU) {
                     if (c0 < half_cols) {
@@ -604,7 +601,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
             }
         }
-        __syncthreads();  // stage 0 is refilled by the next tile's prologue
+        __syncthreads();  // the LDS stages are refilled by the next tile's prologue
     }
 }
 
@@ -616,10 +613,11 @@ static moe_status gg_check_common(moe_ctx* ctx, const char* who, const void* p, 
     if (!p || !q || !offsets) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: NULL pointer", who);
     if (E < 1 || E > GG_MAX_E || N < 1 || K < 1 || Rcap < 1 || Rcap > 0x7fffffffLL)
         MOE_FAIL(ctx, MOE_ERR_ARG, "%s: need 1<=E<=%d, N,K>=1, 1<=Rcap<2^31", who, GG_MAX_E);
-    if (N % 8 || K % 8) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: N and K must be multiples of 8 (16-byte rows)", who);
     if (dt == MOE_F32) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "%s: fp32 operands are not supported", who);
-    if (dt == MOE_FP8_E4M3) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "%s: fp8 path not built yet", who);
-    if (dt != MOE_BF16) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: bad dtype", who);
+    if (dt != MOE_BF16 && dt != MOE_FP8_E4M3) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: bad dtype", who);
+    if (dt == MOE_FP8_E4M3 && (N % 128 || K % 128))
+        MOE_FAIL(ctx, MOE_ERR_ARG, "%s: fp8 needs N and K to be multiples of 128 (block scales)", who);
+    if (N % 8 || K % 8) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: N and K must be multiples of 8 (16-byte rows)", who);
     return MOE_OK;
 }
 
@@ -627,8 +625,8 @@ static gg_args gg_make(moe_ctx* ctx, const void* P, const void* Q, const int32_t
                        int64_t Rcap, void* out) {
     gg_args a;
     memset(&a, 0, sizeof(a));
-    a.P = (const bf16_t*)P;
-    a.Q = (const bf16_t*)Q;
+    a.P = P;
+    a.Q = Q;
     a.offsets = offsets;
     a.E = E;
     a.N = N;
@@ -640,6 +638,10 @@ static gg_args gg_make(moe_ctx* ctx, const void* P, const void* Q, const int32_t
     return a;
 }
 
+#define GG_LAUNCH(MODE, EPI, F32, FP8)                                                                          \
+    hipLaunchKernelGGL((gg_kernel<MODE, EPI, F32, FP8>), dim3(ctx->num_cu > 0 ? ctx->num_cu : 256), dim3(GG_THREADS), \
+                       0, (hipStream_t)stream, a)
+
 extern "C" moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const void* A, const void* B,
                                            const int32_t* offsets, int E, int N, int K, int64_t Rcap,
                                            moe_dtype dt, moe_epilogue epi,
@@ -648,25 +650,29 @@ extern "C" moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const voi
     if (!ctx) return MOE_ERR_ARG;
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_fwd", A, B, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
-    (void)a_scale;
-    (void)b_scale;
     if (epi == MOE_EPI_SWIGLU) {
         if (!C_act) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: SWIGLU needs C_act");
         if (N % 16) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: SWIGLU needs N %% 16 == 0");
+        if (dt == MOE_FP8_E4M3 && N % 256) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: fp8 SWIGLU needs N %% 256 == 0");
     } else if (epi == MOE_EPI_NONE) {
         if (!C) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: C is NULL");
     } else {
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: bad epilogue");
     }
-    if (K % GG_BK) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd: K=%d must be a multiple of %d", K, GG_BK);
+    const bool fp8 = dt == MOE_FP8_E4M3;
+    if (fp8 && (!a_scale || !b_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: fp8 needs a_scale and b_scale");
+    if (!fp8 && K % 32) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd: K=%d must be a multiple of 32", K);
     gg_args a = gg_make(ctx, A, B, offsets, E, N, K, Rcap, C);
     a.out_act = (bf16_t*)C_act;
-    hipStream_t s = (hipStream_t)stream;
-    const int grid = ctx->num_cu > 0 ? ctx->num_cu : 256;
-    if (epi == MOE_EPI_SWIGLU)
-        hipLaunchKernelGGL((gg_kernel<GG_FWD, GG_EPI_SWIGLU, false>), dim3(grid), dim3(GG_THREADS), 0, s, a);
-    else
-        hipLaunchKernelGGL((gg_kernel<GG_FWD, GG_EPI_STORE, false>), dim3(grid), dim3(GG_THREADS), 0, s, a);
+    a.p_scale = a_scale;
+    a.q_scale = b_scale;
+    if (epi == MOE_EPI_SWIGLU) {
+        if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, true);
+        else GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, false);
+    } else {
+        if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_STORE, false, true);
+        else GG_LAUNCH(GG_FWD, GG_EPI_STORE, false, false);
+    }
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<fwd>");
     return MOE_OK;
 }
@@ -678,18 +684,21 @@ extern "C" moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const v
     if (!ctx) return MOE_ERR_ARG;
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_dgrad", dC, B, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
-    (void)dc_scale;
-    (void)b_scale;
     if (!dA) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: dA is NULL");
-    if (N % GG_BK) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad: N=%d must be a multiple of %d", N, GG_BK);
+    const bool fp8 = dt == MOE_FP8_E4M3;
+    if (fp8 && (!dc_scale || !b_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: fp8 needs dc_scale and b_scale");
+    if (!fp8 && N % 32) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad: N=%d must be a multiple of 32", N);
     gg_args a = gg_make(ctx, dC, B, offsets, E, N, K, Rcap, dA);
     a.Zsaved = (const bf16_t*)Z_saved;
-    hipStream_t s = (hipStream_t)stream;
-    const int grid = ctx->num_cu > 0 ? ctx->num_cu : 256;
-    if (Z_saved)
-        hipLaunchKernelGGL((gg_kernel<GG_DGRAD, GG_EPI_SWIGLU_BWD, false>), dim3(grid), dim3(GG_THREADS), 0, s, a);
-    else
-        hipLaunchKernelGGL((gg_kernel<GG_DGRAD, GG_EPI_STORE, false>), dim3(grid), dim3(GG_THREADS), 0, s, a);
+    a.p_scale = dc_scale;
+    a.q_scale = b_scale;
+    if (Z_saved) {
+        if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, true);
+        else GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, false);
+    } else {
+        if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_STORE, false, true);
+        else GG_LAUNCH(GG_DGRAD, GG_EPI_STORE, false, false);
+    }
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<dgrad>");
     return MOE_OK;
 }
@@ -703,16 +712,14 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     if (st != MOE_OK) return st;
     (void)a_scale;
     (void)dc_scale;
+    if (dt == MOE_FP8_E4M3)
+        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wgrad: fp8 operands are not built; pass the bf16 tensors");
     if (!dB) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: dB is NULL");
     if (out_dt != MOE_BF16 && out_dt != MOE_F32) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: out_dt must be bf16 or f32");
     gg_args a = gg_make(ctx, dC, A, offsets, E, N, K, Rcap, dB);
     a.accumulate = accumulate ? 1 : 0;
-    hipStream_t s = (hipStream_t)stream;
-    const int grid = ctx->num_cu > 0 ? ctx->num_cu : 256;
-    if (out_dt == MOE_F32)
-        hipLaunchKernelGGL((gg_kernel<GG_WGRAD, GG_EPI_STORE, true>), dim3(grid), dim3(GG_THREADS), 0, s, a);
-    else
-        hipLaunchKernelGGL((gg_kernel<GG_WGRAD, GG_EPI_STORE, false>), dim3(grid), dim3(GG_THREADS), 0, s, a);
+    if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, false);
+    else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, false);
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<wgrad>");
     return MOE_OK;
 }
