@@ -93,6 +93,32 @@ class LayerState:
         self.dX = torch.empty((T, h), dtype=bf, device=dev)
         self.dW1 = torch.empty((E, 2 * f, h), dtype=wdt, device=dev)
         self.dW2 = torch.empty((E, h, f), dtype=wdt, device=dev)
+        self.fp8 = bool(cfg.fp8)
+        if self.fp8:
+            u8 = torch.uint8
+
+            def codes(rows, cols):   # E4M3 codes + 1x128 scales of a row-indexed tensor
+                return (torch.empty((rows, cols), dtype=u8, device=dev),
+                        torch.empty((rows, cols // 128), dtype=f32, device=dev))
+
+            def wcodes(g, rows, cols):  # E4M3 codes + 128x128 scales of a weight stack
+                return (torch.empty((g, rows, cols), dtype=u8, device=dev),
+                        torch.empty((g, rows // 128, cols // 128), dtype=f32, device=dev))
+
+            self.qXp, self.sXp = codes(Rcap, h)
+            self.qA, self.sA = codes(Rcap, f)
+            self.qdO, self.sdO = codes(Rcap, h)
+            self.qdZ, self.sdZ = codes(Rcap, 2 * f)
+            self.qW1, self.sW1 = wcodes(E, 2 * f, h)
+            self.qW2, self.sW2 = wcodes(E, h, f)
+            self.live_rows = self.offsets[E:E + 1]   # device int32: offsets[E]
+            if sf:
+                self.qX, self.sX = codes(T, h)
+                self.qAs, self.sAs = codes(T, sf)
+                self.qdY, self.sdY = codes(T, h)
+                self.qdZs, self.sdZs = codes(T, 2 * sf)
+                self.qWs1, self.sWs1 = wcodes(1, 2 * sf, h)
+                self.qWs2, self.sWs2 = wcodes(1, h, sf)
         if sf:
             self.off_shared = torch.tensor([0, T], dtype=i32, device=dev)
             self.Zs = torch.empty((T, 2 * sf), dtype=bf, device=dev)
@@ -103,8 +129,22 @@ class LayerState:
             self.dWs1 = torch.empty((2 * sf, h), dtype=wdt, device=dev)
             self.dWs2 = torch.empty((h, sf), dtype=wdt, device=dev)
 
-    # ---- the four forward stages --------------------------------------------------------------
+    # ---- fp8 helpers: quantise a row-indexed tensor (1x128) / a weight stack (128x128) ----------
+    def _q_rows(self, X, q, s, rows, cols, live=None):
+        B.moe_fp8_quantize(self.ctx, X, B.Q_1x128, 1, rows, cols, live, q, s)
+
+    def _q_weight(self, W, q, s):
+        g, rows, cols = q.shape
+        B.moe_fp8_quantize(self.ctx, W, B.Q_128x128, g, rows, cols, None, q, s)
+
     def forward(self):
+        return self._forward_fp8() if self.fp8 else self._forward_bf16()
+
+    def backward(self):
+        return self._backward_fp8() if self.fp8 else self._backward_bf16()
+
+    # ---- the four forward stages --------------------------------------------------------------
+    def _forward_bf16(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         B.moe_route_topk(c, self.logits, T, cfg.E_router, k, cfg.score, cfg.norm_topk, 1.0,
@@ -125,7 +165,7 @@ class LayerState:
                                 T, k, h, self.Y)
 
     # ---- backward: combine, fc2 (wgrad, dgrad + SwiGLU'), fc1 (wgrad, dgrad), permute ---------
-    def backward(self):
+    def _backward_bf16(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         wdt = self.wgrad_dt
@@ -144,6 +184,64 @@ class LayerState:
             B.moe_grouped_gemm_wgrad(c, self.X, self.dZs, o1, 1, 2 * sf, h, T, B.BF16, None, None, 0, wdt, self.dWs1)
             B.moe_grouped_gemm_dgrad(c, self.dZs, self.Ws1, o1, 1, 2 * sf, h, T, B.BF16, None, None, None, self.dXs)
         # dX[t] = sum of the k permuted-row gradients (+ the shared expert's dX): the plain-sum unpermute
+        B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
+
+    # ---- blockwise fp8 (Sec. 5.3.2): forward and data-gradient GEMMs on E4M3 codes; weights are
+    # re-quantised every step; the weight gradients use the bf16 tensors (fp8 wgrad is not built) ----
+    def _forward_fp8(self):
+        c, cfg = self.ctx, self.cfg
+        T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
+        F8 = B.FP8_E4M3
+        B.moe_route_topk(c, self.logits, T, cfg.E_router, k, cfg.score, cfg.norm_topk, 1.0,
+                         self.topk_idx, self.topk_prob, self.route_counts)
+        idx = self.topk_idx if self.forced_idx is None else self.forced_idx
+        B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
+                      self.row_of, self.src_of, self.offsets, self.counts)
+        self._q_weight(self.W1, self.qW1, self.sW1)
+        self._q_weight(self.W2, self.qW2, self.sW2)
+        self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows)
+        B.moe_grouped_gemm_fwd(c, self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, B.EPI_SWIGLU,
+                               self.sXp, self.sW1, self.Z, self.A)
+        self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows)
+        B.moe_grouped_gemm_fwd(c, self.qA, self.qW2, self.offsets, E, h, f, Rcap, F8, B.EPI_NONE,
+                               self.sA, self.sW2, self.O, None)
+        if sf:
+            o1 = self.off_shared
+            self._q_weight(self.Ws1.view(1, 2 * sf, h), self.qWs1, self.sWs1)
+            self._q_weight(self.Ws2.view(1, h, sf), self.qWs2, self.sWs2)
+            self._q_rows(self.X, self.qX, self.sX, T, h)
+            B.moe_grouped_gemm_fwd(c, self.qX, self.qWs1, o1, 1, 2 * sf, h, T, F8, B.EPI_SWIGLU,
+                                   self.sX, self.sWs1, self.Zs, self.As)
+            self._q_rows(self.As, self.qAs, self.sAs, T, sf)
+            B.moe_grouped_gemm_fwd(c, self.qAs, self.qWs2, o1, 1, h, sf, T, F8, B.EPI_NONE,
+                                   self.sAs, self.sWs2, self.S, None)
+        B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, self.topk_prob, self.S if sf else None,
+                                T, k, h, self.Y)
+
+    def _backward_fp8(self):
+        c, cfg = self.ctx, self.cfg
+        T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
+        F8, wdt = B.FP8_E4M3, self.wgrad_dt
+        B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
+                                    T, k, h, Rcap, self.dO, self.dprob)
+        B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt, self.dW2)
+        self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows)
+        B.moe_grouped_gemm_dgrad(c, self.qdO, self.qW2, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO, self.sW2,
+                                 self.dZ)
+        B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, wdt,
+                                 self.dW1)
+        self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows)
+        B.moe_grouped_gemm_dgrad(c, self.qdZ, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, None, self.sdZ, self.sW1,
+                                 self.dXp)
+        if sf:
+            o1 = self.off_shared
+            B.moe_grouped_gemm_wgrad(c, self.As, self.dY, o1, 1, h, sf, T, B.BF16, None, None, 0, wdt, self.dWs2)
+            self._q_rows(self.dY, self.qdY, self.sdY, T, h)
+            B.moe_grouped_gemm_dgrad(c, self.qdY, self.qWs2, o1, 1, h, sf, T, F8, self.Zs, self.sdY, self.sWs2, self.dZs)
+            B.moe_grouped_gemm_wgrad(c, self.X, self.dZs, o1, 1, 2 * sf, h, T, B.BF16, None, None, 0, wdt, self.dWs1)
+            self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf)
+            B.moe_grouped_gemm_dgrad(c, self.qdZs, self.qWs1, o1, 1, 2 * sf, h, T, F8, None, self.sdZs, self.sWs1,
+                                     self.dXs)
         B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
 
     def step(self):

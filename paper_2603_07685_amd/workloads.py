@@ -91,6 +91,8 @@ CONFIGS = {
                     norm_topk=False, load="zipf", load_param=1.2, seed=1237),
     "C4": MoEConfig("C4-dsv3-share", T=16384, h=7168, f=2048, E=32, k=8, E_router=256, score=SIGMOID,
                     norm_topk=True, load="cv", load_param=0.3, shared_f=2048, seed=1238),
+    "C5S": MoEConfig("C5-small-fp8", T=1024, h=512, f=256, E=8, k=4, E_router=32, score=SIGMOID,
+                     norm_topk=True, load="cv", load_param=0.3, shared_f=256, fp8=True, align=128, seed=1241),
     "C5": MoEConfig("C5-dsv3-share-fp8", T=16384, h=7168, f=2048, E=32, k=8, E_router=256, score=SIGMOID,
                     norm_topk=True, load="cv", load_param=0.3, shared_f=2048, fp8=True, align=128, seed=1239),
 }
