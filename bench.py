@@ -19,6 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+FP8_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 
 
@@ -27,70 +28,83 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C4", help="C1 | MID | C2 | C3 | C4 (default: the metric's config)")
+    ap.add_argument("--workload", default="C4", help="C1 | MID | C2 | C3 | C4 | C5 (default: the metric's config, C4)")
     ap.add_argument("--variant", default=None, help="load pattern override: uniform | zeros | hot | cv | zipf")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad-f32", action="store_true", help="fp32 weight gradients (default bf16)")
     return ap.parse_args()
 
 
-def call_table(st):
-    """(name, flops or None, bytes or None) for every library call of one step, in issue order."""
+def describe_call(name, args, st):
+    """(label, flops or None, bytes or None) of one library call, from its own arguments."""
     cfg = st.cfg
-    T, k, h, f, sf = cfg.T, cfg.k, cfg.h, cfg.f, st.sf
-    R = T * k  # routed rows (unpadded)
-    b = 2
-    calls = [
-        ("route_topk", None, T * cfg.E_router * 4 + T * k * 8 + cfg.E_router * 4),
-        ("permute", None, (T + R) * h * b + T * k * 12),
-        ("fc1_fwd_swiglu", 2.0 * R * 2 * f * h, None),
-        ("fc2_fwd", 2.0 * R * f * h, None),
-    ]
-    if sf:
-        calls += [("shared_fc1_fwd_swiglu", 2.0 * T * 2 * sf * h, None), ("shared_fc2_fwd", 2.0 * T * sf * h, None)]
-    calls += [
-        ("combine", None, (R + T) * h * b + T * k * 8 + (T * h * b if sf else 0)),
-        ("combine_bwd", None, (T + 2 * R) * h * b),
-        ("fc2_wgrad", 2.0 * R * f * h, None),
-        ("fc2_dgrad_swiglu_bwd", 2.0 * R * f * h, None),
-        ("fc1_wgrad", 2.0 * R * 2 * f * h, None),
-        ("fc1_dgrad", 2.0 * R * 2 * f * h, None),
-    ]
-    if sf:
-        calls += [("shared_fc2_wgrad", 2.0 * T * sf * h, None), ("shared_fc2_dgrad_swiglu_bwd", 2.0 * T * sf * h, None),
-                  ("shared_fc1_wgrad", 2.0 * T * 2 * sf * h, None), ("shared_fc1_dgrad", 2.0 * T * 2 * sf * h, None)]
-    calls += [("unpermute_sum_dx", None, (R + T) * h * b + (T * h * b if sf else 0))]
-    return calls
+    T, k = cfg.T, cfg.k
+    R = T * k  # routed rows (unpadded): the algorithmic row count of the grouped calls
+    if name in ("moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad"):
+        E, N, K, dt = args[4], args[5], args[6], args[8]
+        rows = R if E > 1 else T
+        kind = name.rsplit("_", 1)[1]
+        tag = "fp8" if dt == 1 else "bf16"
+        if kind == "fwd":
+            extra = "_swiglu" if args[9] == 1 else ""
+        elif kind == "dgrad":
+            extra = "_swiglu_bwd" if args[9] is not None else ""
+        else:
+            extra = ""
+        which = ("fc1" if (kind == "fwd" and K == cfg.h) or (kind != "fwd" and K == cfg.h) else "fc2")
+        label = f"{'shared_' if E == 1 else ''}{which}_{kind}{extra}_{tag}"
+        return label, 2.0 * rows * N * K, None
+    if name == "moe_route_topk":
+        Tn, E = args[2], args[3]
+        return "route_topk", None, Tn * E * 4 + Tn * args[4] * 8 + E * 4
+    if name == "moe_permute":
+        h = args[6]
+        return "permute", None, (T + R) * h * 2 + T * k * 12
+    if name == "moe_unpermute_combine":
+        h = args[8]
+        res = args[5] is not None
+        return ("combine" if args[4] is not None else "unpermute_sum_dx"), None, (R + T) * h * 2 + T * k * 8 + (T * h * 2 if res else 0)
+    if name == "moe_unpermute_combine_bwd":
+        h = args[9]
+        return "combine_bwd", None, (T + 2 * R) * h * 2
+    if name == "moe_fp8_quantize":
+        block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
+        rows_alg = R if live is not None else rows          # grouped row tensors: only the routed rows count
+        n = groups * rows_alg * cols
+        return f"quantize_{['1x128', '128x1', '128x128'][block]}[{rows}x{cols}]", None, n * 3 + n // 128 * 4
+    return name, None, None
+
+
+HOOKED = ["moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
+          "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize"]
 
 
 def timed_step_with_events(st, torch):
-    """One step with an event after every library call; returns per-call milliseconds."""
+    """One step with an event after every library call; returns [(label, flops, bytes, ms)] in issue order."""
     from paper_2603_07685_amd import binding as B
-    names = [c[0] for c in call_table(st)]
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
-    it = iter(evs)
-    orig = {}
+    recs, evs, orig = [], [torch.cuda.Event(enable_timing=True)], {}
 
-    def wrap(fn):
+    def wrap(name, fn):
         def inner(*a, **kw):
             r = fn(*a, **kw)
-            next(it).record()
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record()
+            evs.append(ev)
+            recs.append(describe_call(name, a, st))
             return r
         return inner
 
-    hooked = ["moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad",
-              "moe_grouped_gemm_wgrad", "moe_unpermute_combine", "moe_unpermute_combine_bwd"]
-    next(it).record()
-    for n in hooked:
+    evs[0].record()
+    for n in HOOKED:
         orig[n] = getattr(B, n)
-        setattr(B, n, wrap(orig[n]))
+        setattr(B, n, wrap(n, orig[n]))
     try:
         st.step()
     finally:
-        for n in hooked:
+        for n in HOOKED:
             setattr(B, n, orig[n])
     torch.cuda.synchronize()
-    return [evs[i].elapsed_time(evs[i + 1]) for i in range(len(names))]
+    return [(lab, fl, by, evs[i].elapsed_time(evs[i + 1])) for i, (lab, fl, by) in enumerate(recs)]
 
 
 def cpu_baseline(st, torch):
@@ -175,25 +189,29 @@ def main():
 
     # per-call durations (events on the same stream, extra instrumented steps after the timed region)
     reps = max(3, min(10, args.steps))
-    per = None
+    calls = None
     for _ in range(reps):
         cur = timed_step_with_events(st, torch)
-        per = cur if per is None else [a + b for a, b in zip(per, cur)]
-    per = [p / reps for p in per]
-    calls = call_table(st)
+        calls = cur if calls is None else [(a[0], a[1], a[2], a[3] + b[3]) for a, b in zip(calls, cur)]
+    calls = [(lab, fl, by, t / reps) for lab, fl, by, t in calls]
     breakdown = {}
-    for (name, fl, by), t in zip(calls, per):
+    for lab, fl, by, t in calls:
         d = {"ms": round(t, 4)}
         if fl:
             d["tflops"] = round(fl / t / 1e9, 1)
         if by:
             d["gbs"] = round(by / t / 1e6, 1)
-        breakdown[name] = d
-    gemm = [(t, name, fl) for (name, fl, by), t in zip(calls, per) if fl]
+        key, n = lab, 2
+        while key in breakdown:
+            key = f"{lab}#{n}"
+            n += 1
+        breakdown[key] = d
+    gemm = [(t, lab, fl) for lab, fl, by, t in calls if fl]
     t_dom, n_dom, fl_dom = max(gemm)
     achieved = fl_dom / t_dom / 1e9
     gemm_ms = sum(t for t, _, _ in gemm)
     gemm_fl = sum(fl for _, _, fl in gemm)
+    peak = FP8_PEAK_TFLOPS if n_dom.endswith("fp8") else BF16_PEAK_TFLOPS
 
     flops = cfg.model_flops()
     out = {
@@ -204,7 +222,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "wall_ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "fp8_e4m3 (fwd/dgrad GEMMs) + bf16" if cfg.fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} h={cfg.h} f={cfg.f} E_local={cfg.E} top{cfg.k} "
                                f"shared_f={cfg.shared_f} load={args.variant or cfg.load} "
                                f"wgrad_out={'f32' if args.wgrad_f32 else 'bf16'}",
@@ -213,7 +231,7 @@ def main():
         "gemm_only": {"tflops": round(gemm_fl / gemm_ms / 1e9, 1),
                       "pct_peak": round(100.0 * gemm_fl / gemm_ms / 1e9 / BF16_PEAK_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "kernel": f"gg_kernel ({n_dom})", "achieved": round(achieved, 1),
-                     "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / BF16_PEAK_TFLOPS, 4),
+                     "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                      "traffic": None},
         "kernels": breakdown,
     }

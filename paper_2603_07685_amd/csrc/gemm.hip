@@ -185,7 +185,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps wave-derived values in SGPRs
     const int wm = wave >> 2;  // 0..1 : 128-row half of the tile
     const int wn = wave & 3;   // 0..3 : 32-column strip inside each 128-column half
     const int E = a.E, N = a.N, K = a.K;
@@ -349,38 +349,39 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         };
 
         // ---- fp8 block scales: s = p_scale[row, kb] * q_scale[block]; per lane 4 rows x 2 column blocks ----
-        const float* ps_ptr[4];
-        const float* qs_ptr[2];
-        int64_t qs_step = 0;
-        float s_cur[4][2], ps_nxt[4], qs_nxt[2];
+        // kept as the two factors (4 per-lane row scales, 2 wave-uniform block scales), current and next
         const int CB = (c_hi - c_lo) / 128;  // contraction blocks
+        const int ps_row0 = i0 + wm * 128 + fr_row;
+        int64_t qs_off[2] = {0, 0}, qs_step = 0;
+        float ps_cur[4], ps_nxt[4], qs_cur[2], qs_nxt[2];
+        auto ps_load = [&](int i, int kb) -> float {
+            int64_t r = (int64_t)ps_row0 + i * 32;
+            r = r < a.Rcap ? r : a.Rcap - 1;
+            return a.p_scale[r * CB + kb];
+        };
         if (FP8) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int64_t r = (int64_t)i0 + wm * 128 + i * 32 + fr_row;
-                r = r < a.Rcap ? r : a.Rcap - 1;
-                ps_ptr[i] = a.p_scale + r * CB;
-            }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 int col = (j ? j1 : j0) + wn * 32;
                 col = col < J ? col : J - 1;
                 if (MODE == GG_FWD) {  // q_scale[e, col/128, kb]
-                    qs_ptr[j] = a.q_scale + ((int64_t)e * (N / 128) + col / 128) * (K / 128);
+                    qs_off[j] = ((int64_t)e * (N / 128) + col / 128) * (K / 128);
                     qs_step = 1;
                 } else {               // dgrad: contraction over N: q_scale[e, kb, col/128]
-                    qs_ptr[j] = a.q_scale + (int64_t)e * (N / 128) * (K / 128) + col / 128;
+                    qs_off[j] = (int64_t)e * (N / 128) * (K / 128) + col / 128;
                     qs_step = K / 128;
                 }
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ps_nxt[i] = CB > 0 ? ps_ptr[i][0] : 1.0f;
+            for (int i = 0; i < 4; ++i) {
+                ps_nxt[i] = CB > 0 ? ps_load(i, 0) : 1.0f;
+                ps_cur[i] = 1.0f;
+            }
 #pragma unroll
-            for (int j = 0; j < 2; ++j) qs_nxt[j] = CB > 0 ? qs_ptr[j][0] : 1.0f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) s_cur[i][j] = 1.0f;
+            for (int j = 0; j < 2; ++j) {
+                qs_nxt[j] = CB > 0 ? a.q_scale[qs_off[j]] : 1.0f;
+                qs_cur[j] = 1.0f;
+            }
         }
 
         f32x16_t acc[4][2];
@@ -462,30 +463,30 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             };
             // fp8: entering contraction block kb, bring the accumulators to the new block's units
             auto rescale = [&](int kb) {
-                float s_new[4][2];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) s_new[i][j] = ps_nxt[i] * qs_nxt[j];
                 if (kb > 0) {
+                    float pr[4], qr[2];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pr[i] = ps_cur[i] / ps_nxt[i];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) qr[j] = qs_cur[j] / qs_nxt[j];
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            const float ratio = s_cur[i][j] / s_new[i][j];
+                            const float ratio = pr[i] * qr[j];
 #pragma unroll
                             for (int x = 0; x < 16; ++x) acc[i][j][x] *= ratio;
                         }
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i) ps_cur[i] = ps_nxt[i];
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) s_cur[i][j] = s_new[i][j];
+                for (int j = 0; j < 2; ++j) qs_cur[j] = qs_nxt[j];
                 if (kb + 1 < CB) {  // next block's scales, needed two stages from now
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) ps_nxt[i] = ps_ptr[i][kb + 1];
+                    for (int i = 0; i < 4; ++i) ps_nxt[i] = ps_load(i, kb + 1);
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) qs_nxt[j] = qs_ptr[j][(int64_t)(kb + 1) * qs_step];
+                    for (int j = 0; j < 2; ++j) qs_nxt[j] = a.q_scale[qs_off[j] + (int64_t)(kb + 1) * qs_step];
                 }
             };
 
@@ -536,8 +537,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     v0[x] = acc[i][0][4 * g + x];
                     v1[x] = acc[i][1][4 * g + x];
                     if (FP8) {
-                        v0[x] *= s_cur[i][0];
-                        v1[x] *= s_cur[i][1];
+                        v0[x] *= ps_cur[i] * qs_cur[0];
+                        v1[x] *= ps_cur[i] * qs_cur[1];
                     }
                 }
                 if (EPI == GG_EPI_SWIGLU) {
