@@ -9,11 +9,13 @@
 //     dgrad   : P = dC [rows,N]            Q = W_e as [K,N]^T   OUT = dA[rows,K]
 //     wgrad   : P = dC as [N,rows]^T       Q = A as [K,rows]^T  OUT = dW_e[N,K]
 //
-// Operand stream.  The contraction is walked in stages of 64 bytes per operand row (32 bf16 or
-// 64 fp8 elements).  Each stage's two 16 KB operand tiles are fetched by direct global->LDS
-// loads (16 B per lane) into one of GG_NS LDS stages; up to GG_NS-2 later stages are in flight
-// while one is consumed.  Every stage is its own LDS object so that the compiler can see that
-// the DMA writes of a later stage do not alias the operand reads of the current one.
+// Operand stream.  The contraction is walked in stages of 128 bytes per operand row (64 bf16 or
+// 128 fp8 elements): every global request of the DMA is then a whole 128-byte cache line, which
+// the L1/L2 path serves at about twice the rate of half-line requests (measured: 20 vs 10 TB/s on
+// a GEMM-like sharing pattern).  Each stage's two 32 KB operand tiles are fetched by direct
+// global->LDS loads (16 B per lane) into one of two LDS stages.  Every stage is its own LDS object
+// so that the compiler can see that the DMA writes of the next stage do not alias the operand
+// reads of the current one.
 //
 // LDS layouts.  An operand whose contraction index is contiguous in memory ("k-major", tile
 // [256 rows][64 B]) is read with ds_read_b128; one whose contraction index is the memory row
@@ -23,16 +25,19 @@
 // operand reads are free of bank conflicts; the swizzle is applied on the global side of the DMA
 // (each lane chooses which 16 bytes it fetches; the LDS side of a DMA is always lane-linear).
 //
-// Schedule ("ping-pong").  The two waves that share a SIMD (wave w and w+4) run one phase apart:
-// while one issues the MFMAs of a stage with all operands already in registers, the other fetches
-// its next operands from LDS; they swap at fence-free workgroup barriers.  The DMA instructions
-// that refill a stage are slipped in between the MFMAs, so memory requests are spread over time
-// instead of bursting after a barrier.
-//   per stage s:   A_s: LDS -> registers      barrier      B_s: MFMAs (+ DMA of stage s+NS-1)      barrier
-//   group 1 (waves 4-7) takes one extra barrier up front, group 0 one at the end.
-// Buffer (s-1) % NS was last read in A_{s-1} of group 1, which ends one barrier before B_s of
-// group 0 begins, so refilling it during B_s is safe; each wave waits for its own loads of stage
-// s+1 at the end of A_s, before the barrier that precedes the first read of that stage.
+// Schedule ("ping-pong").  A stage is consumed in two halves.  The two waves that share a SIMD
+// (wave w and w+4) run one phase apart: while one issues the MFMAs of a half-stage with all
+// operands already in registers, the other fetches its next operands from LDS; they swap at
+// fence-free workgroup barriers.  The DMA instructions that refill the other buffer are slipped in
+// between the MFMAs, so memory requests are spread over time instead of bursting after a barrier.
+//   per stage s:  A(s,0) | B(s,0) | A(s,1) | B(s,1)    A: LDS -> registers,  B: MFMAs,  '|' = barrier
+//   group 1 (waves 4-7) takes one extra barrier up front, group 0 one at the end; in time:
+//     group 0:  A(s,0)   B(s,0)*  A(s,1)   B(s,1)   A(s+1,0) ...
+//     group 1:  B(s-1,1)* A(s,0)  B(s,0)   A(s,1)   B(s,1)*  ...        (* = issues DMA of stage s+1 / s+2)
+// Buffer (s+1)%2 was last read in A(s-1,1); group 1 finishes that phase one barrier before group 0
+// enters A(s,0), so group 0 refills it during B(s,0) and group 1 during its B(s-1,1).  Each wave waits
+// for its own loads of stage s+1 before the barrier that precedes group 0's A(s+1,0): group 0 at the end
+// of B(s,1), group 1 at the end of A(s,1).
 //
 // MFMAs are issued as (Q fragment, P fragment): a lane's 16 accumulators of a block are one
 // output row and 4 groups of 4 consecutive columns (8-byte stores), and the wave's two column
@@ -40,31 +45,28 @@
 // SwiGLU epilogue is on: the activation (forward) and its derivative (fc2 dgrad) are applied to
 // the fp32 accumulators in registers.
 //
-// fp8: operands are E4M3 codes; a stage is one v_mfma_scale_f32_32x32x64_f8f6f4 per block with unit
+// fp8: operands are E4M3 codes; a half-stage is one v_mfma_scale_f32_32x32x64_f8f6f4 per block with unit
 // hardware scales.  The fp32 block scales (1x128 per activation row, 128x128 per weight block) are
 // applied in software: a lane's accumulators of one block all share the factor
 // s = a_scale[row, kb] * b_scale[block], so the accumulator is kept in units of the current
-// factor: at every 128-wide contraction block it is multiplied by s_prev / s_new before the raw
+// factor: at every 128-wide contraction block (= stage) it is multiplied by s_prev / s_new before the raw
 // products are added, and by the last factor in the epilogue.  No second set of accumulators.
 #include "common.h"
 
 #define GG_BM 256
 #define GG_BN 256
-#ifndef GG_NS
-#define GG_NS 4  // LDS stages (3 or 4)
-#endif
 #ifndef GG_BAND
 #define GG_BAND 4  // row-tiles per band of the tile order
 #endif
 #define GG_THREADS 512
 #define GG_MAX_E 1024
-#define GG_ROWB 64                      // bytes of a k-major tile row per stage
-#define GG_STAGE_BYTES (GG_BM * GG_ROWB)  // one operand tile per stage: 16 KB
-#define GG_CH 2                         // 1 KB DMA chunks per wave per operand per stage
+#define GG_ROWB 128                     // bytes of a k-major tile row per stage: one cache line
+#define GG_STAGE_BYTES (GG_BM * GG_ROWB)  // one operand tile per stage: 32 KB
+#define GG_CH 4                         // 1 KB DMA chunks per wave per operand per stage
 #define GG_DMA_PER_STAGE (2 * GG_CH)
-// k-major swizzle: four 64-byte rows share a 256-byte bank line; slot ^= bits 2..3 of the row makes
+// k-major swizzle: two 128-byte rows share a 256-byte bank line; slot ^= bits 1..3 of the row makes
 // 16 consecutive rows hit 16 different (position in line, slot) pairs (SQ_LDS_BANK_CONFLICT = 0)
-#define KM_SWZ(row) (((row) >> 2) & 3)
+#define KM_SWZ(row) (((row) >> 1) & 7)
 
 enum { GG_FWD = 0, GG_DGRAD = 1, GG_WGRAD = 2 };
 enum { GG_EPI_STORE = 0, GG_EPI_SWIGLU = 1, GG_EPI_SWIGLU_BWD = 2 };
@@ -79,8 +81,7 @@ typedef int i32x8_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 typedef __attribute__((address_space(3))) i32x2_t lds_i32x2_t;
 
-static_assert(GG_NS == 3 || GG_NS == 4, "the schedule needs a third stage for the interleaved DMA to land in");
-static_assert(2 * GG_NS * GG_STAGE_BYTES <= 144 * 1024, "pipeline stages exceed the LDS budget");
+static_assert(2 * 2 * GG_STAGE_BYTES <= 144 * 1024, "pipeline stages exceed the LDS budget");
 
 __device__ __forceinline__ void dma16(const void* g, void* lds_wave_base) {
     // each lane moves 16 bytes: LDS destination = wave-uniform base + lane * 16
@@ -99,13 +100,8 @@ __device__ __forceinline__ void stage_barrier() {
     asm volatile("" ::: "memory");
 }
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0)
-// s_waitcnt vmcnt(n) only (gfx9 encoding, other counters at their maxima): at most `newer` younger
-// stages of this wave's DMA loads may still be in flight
-__device__ __forceinline__ void wait_stage(int newer) {
-    if (newer <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);
-    else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | GG_DMA_PER_STAGE);
-    else __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * GG_DMA_PER_STAGE));
-}
+// s_waitcnt vmcnt(0) only (gfx9 encoding, other counters at their maxima): this wave's DMA loads landed
+__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 __device__ __forceinline__ float sigmoid_f(float g) { return 1.0f / (1.0f + __expf(-g)); }
 
@@ -165,12 +161,8 @@ template <int MODE, int EPI, bool OUT_F32, bool FP8>
 __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     __shared__ __attribute__((aligned(1024))) char ldsP0[GG_STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsP1[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsP2[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsP3[GG_NS > 3 ? GG_STAGE_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) char ldsQ0[GG_STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsQ1[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsQ2[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsQ3[GG_NS > 3 ? GG_STAGE_BYTES : 16];
     __shared__ int offs[GG_MAX_E + 1];
     __shared__ int tile_start[GG_MAX_E + 1];
 
@@ -178,7 +170,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     constexpr bool P_CMAJ = (MODE == GG_WGRAD);
     constexpr bool Q_CMAJ = (MODE != GG_FWD);
     constexpr int ES = FP8 ? 1 : 2;            // operand element size
-    constexpr int BKE = GG_ROWB / ES;           // contraction elements per stage: 32 bf16 / 64 fp8
+    constexpr int BKE = GG_ROWB / ES;           // contraction elements per stage: 64 bf16 / 128 fp8
     constexpr int CM_ROWS = 1024 / (256 * ES);  // c-major rows per 1 KB DMA chunk: 2 bf16 / 4 fp8
     constexpr int CM_SLOTS = 256 * ES / 16;     // 16-byte slots per c-major row: 32 bf16 / 16 fp8
     constexpr int EPS = 16 / ES;                // elements per 16-byte slot
@@ -218,15 +210,17 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         }
     }
     __syncthreads();
-    const int total_tiles = tile_start[E];
+    // values read back from LDS are the same in every lane: say so, so that everything derived from
+    // them (tile origin, operand bases, trip counts) lives in scalar registers
+    const int total_tiles = __builtin_amdgcn_readfirstlane(tile_start[E]);
 
     // workgroups land on the 8 XCDs round-robin; give each XCD a contiguous run of tiles
     const int G = gridDim.x;
     const int q = (G & 7) ? (int)blockIdx.x : ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3);
 
     // ---- per-lane constants: DMA side ----
-    // k-major tile: a 1 KB chunk = 16 rows x 64 B; lane -> (row l/4, slot l%4), slot ^= KM_SWZ(row)
-    const int km_row = lane >> 2;
+    // k-major tile: a 1 KB chunk = 8 rows x 128 B; lane -> (row l/8, slot l%8), slot ^= KM_SWZ(row)
+    const int km_row = lane >> 3;
     // c-major tile: a 1 KB chunk = CM_ROWS rows; lane -> (row l / CM_SLOTS, slot l % CM_SLOTS)
     //   bf16: slot ^= 4 * (row % 4);  fp8: slot ^= 2 * (row % 8)
     const int cm_row = lane / CM_SLOTS;
@@ -237,9 +231,9 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     const int tr_i = lane & 15;
     const int tr_blk = lane >> 4;
     // c-major read of a 32-column operand block at column block cb (a multiple of 32):
-    //   bf16 (row pitch 512 B): row = 16 kk + 8 (blk >> 1) + 4 hh + (i >> 2),
+    //   bf16 (row pitch 512 B, 64 rows): row = 16 kk + 8 (blk >> 1) + 4 hh + (i >> 2),
     //        slot = (cb / 8 ^ 4 (i >> 2)) + 2 (blk & 1) + ((i & 3) >> 1), byte (i & 1) * 8
-    //   fp8  (row pitch 256 B): row = 32 (blk >> 1) + 8 g + (i >> 1),
+    //   fp8  (row pitch 256 B, 128 rows): row = 64 half + 32 (blk >> 1) + 8 g + (i >> 1),
     //        slot = (cb / 16 ^ 2 (i >> 1)) + (blk & 1), byte (i & 1) * 8
     const int tr_rowoff = FP8 ? (32 * (tr_blk >> 1) + (tr_i >> 1)) * 256 : (8 * (tr_blk >> 1) + (tr_i >> 2)) * 512;
     const int tr_low = FP8 ? (tr_blk & 1) : 2 * (tr_blk & 1) + ((tr_i & 3) >> 1);
@@ -262,10 +256,10 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     for (int t = q; t < total_tiles; t += G) {
         // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
         int e = e_hint;
-        while (e + 1 < E && t >= tile_start[e + 1]) ++e;
+        while (e + 1 < E && t >= __builtin_amdgcn_readfirstlane(tile_start[e + 1])) ++e;
         e_hint = e;
-        const int u = t - tile_start[e];
-        const int row_lo = offs[e], row_hi = offs[e + 1];
+        const int u = t - __builtin_amdgcn_readfirstlane(tile_start[e]);
+        const int row_lo = __builtin_amdgcn_readfirstlane(offs[e]), row_hi = __builtin_amdgcn_readfirstlane(offs[e + 1]);
         int ti, tj;
         {
             const int tiles_i = (MODE == GG_WGRAD) ? tiles_i_w : (row_hi - row_lo + GG_BM - 1) / GG_BM;
@@ -286,61 +280,72 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         const int c_hi = (MODE == GG_WGRAD) ? row_hi : (MODE == GG_FWD ? K : N);
         const int KT = (c_hi - c_lo + BKE - 1) / BKE;
 
-        // ---- DMA source pointers (GG_CH chunks per operand per lane) ----
-        const char* pg[GG_CH];
-        const char* qg[GG_CH];
+        // ---- DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus
+        //      GG_CH 32-bit per-lane offsets; offsets stay below 2^32 because they are tile-relative ----
+        const char* p_base;
+        const char* q_base;
+        uint32_t po[GG_CH], qo[GG_CH];
         int64_t p_step, q_step;  // byte advance per stage
         if (P_CMAJ) {
             // P = dC [rows, N]: contraction row c, columns i0..i0+255
             p_step = (int64_t)BKE * N * ES;
+            p_base = (const char*)a.P + (int64_t)c_lo * N * ES;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
                 const int row = (wave * GG_CH + i) * CM_ROWS + cm_row;
                 const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
                 int col = i0 + slot * EPS;
                 col = col <= N - EPS ? col : N - EPS;
-                pg[i] = (const char*)a.P + ((int64_t)(c_lo + row) * N + col) * ES;
+                po[i] = (uint32_t)((row * N + col) * ES);
             }
         } else {
             const int ldp = (MODE == GG_FWD) ? K : N;
             p_step = GG_ROWB;
+            p_base = (const char*)a.P + (int64_t)i0 * ldp * ES;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
-                const int p = (wave * GG_CH + i) * 16 + km_row;  // tile row 0..255
+                const int p = (wave * GG_CH + i) * 8 + km_row;  // tile row 0..255
                 int64_t r = (int64_t)i0 + p;
-                r = r < a.Rcap ? r : a.Rcap - 1;
-                const int gslot = (lane & 3) ^ KM_SWZ(p);
-                pg[i] = (const char*)a.P + r * ldp * ES + gslot * 16;
+                r = r < a.Rcap ? r : a.Rcap - 1;                // i0 < Rcap, so r - i0 >= 0
+                const int gslot = (lane & 7) ^ KM_SWZ(p);
+                po[i] = (uint32_t)((r - i0) * ldp * ES + gslot * 16);
             }
         }
         if (Q_CMAJ) {
             // dgrad: Q = W_e [N,K]: contraction row n, columns (k) j0.. ; wgrad: Q = A [rows,K]
             q_step = (int64_t)BKE * K * ES;
-            const char* qbase = (MODE == GG_DGRAD) ? (const char*)a.Q + (int64_t)e * N * K * ES : (const char*)a.Q;
+            q_base = (MODE == GG_DGRAD ? (const char*)a.Q + (int64_t)e * N * K * ES : (const char*)a.Q) + (int64_t)c_lo * K * ES;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
                 const int row = (wave * GG_CH + i) * CM_ROWS + cm_row;
                 const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
                 int col = (slot < CM_SLOTS / 2 ? j0 : j1 - 128) + slot * EPS;
                 col = col <= K - EPS ? col : K - EPS;
-                qg[i] = qbase + ((int64_t)(c_lo + row) * K + col) * ES;
+                qo[i] = (uint32_t)((row * K + col) * ES);
             }
         } else {
             q_step = GG_ROWB;
+            q_base = (const char*)a.Q + (int64_t)e * N * K * ES;
 #pragma unroll
             for (int i = 0; i < GG_CH; ++i) {
-                const int p = (wave * GG_CH + i) * 16 + km_row;  // tile row 0..255
+                const int p = (wave * GG_CH + i) * 8 + km_row;  // tile row 0..255
                 int n = (p < 128 ? j0 : j1 - 128) + p;
                 n = n < N ? n : N - 1;
-                const int gslot = (lane & 3) ^ KM_SWZ(p);
-                qg[i] = (const char*)a.Q + ((int64_t)e * N + n) * K * ES + gslot * 16;
+                const int gslot = (lane & 7) ^ KM_SWZ(p);
+                qo[i] = (uint32_t)(((int64_t)n * K) * ES + gslot * 16);
             }
         }
 
         // one of the GG_DMA_PER_STAGE DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
         auto issue_one = [&](int kt, char* sp, char* sq, int idx) {
             const int i = idx >> 1;
-            const char* src = (idx & 1) ? qg[i] + kt * q_step : pg[i] + kt * p_step;
+            // the empty asm makes the lane offset opaque here, so that base + offset is not hoisted out of
+            // the stage loop as a 64-bit per-lane pointer: the load then takes the scalar-base form
+            uint32_t off = (idx & 1) ? qo[i] : po[i];
+            asm volatile("" : "+v"(off));
+            const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;
+            asm volatile("" : "+s"(base));  // the stage's operand base, complete, in scalar registers
+            const char* src = base + off;
             if (MODE == GG_WGRAD) {  // contraction tail of the expert: feed zeros
                 const int row = c_lo + kt * BKE + (wave * GG_CH + i) * CM_ROWS + cm_row;
                 src = row < c_hi ? src : a.zeros;
@@ -355,9 +360,10 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         int64_t qs_off[2] = {0, 0}, qs_step = 0;
         float ps_cur[4], ps_nxt[4], qs_cur[2], qs_nxt[2];
         auto ps_load = [&](int i, int kb) -> float {
-            int64_t r = (int64_t)ps_row0 + i * 32;
+            int r = ps_row0 + i * 32;
+            asm volatile("" : "+v"(r));  // recompute the address at each use instead of carrying four of them
             r = r < a.Rcap ? r : a.Rcap - 1;
-            return a.p_scale[r * CB + kb];
+            return a.p_scale[(int64_t)r * CB + kb];
         };
         if (FP8) {
 #pragma unroll
@@ -393,24 +399,32 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
 
         {
-            char* const SP[4] = {ldsP0, ldsP1, ldsP2, ldsP3};
-            char* const SQ[4] = {ldsQ0, ldsQ1, ldsQ2, ldsQ3};
-            // operand fragments of one stage: bf16 2 x (4 + 2) x 4 VGPRs, fp8 (4 + 2) x 8 VGPRs
+            char* const SP[2] = {ldsP0, ldsP1};
+            char* const SQ[2] = {ldsQ0, ldsQ1};
+            // operand fragments of one half-stage: bf16 2 x (4 + 2) x 4 VGPRs, fp8 (4 + 2) x 8 VGPRs
             bf16x8_t pf[2][4], qf[2][2];
-            i32x8_t pf8[4], qf8[2];
+            i32x8_t pf8[2], qf8[2];
 
-            auto fetch = [&](const char* sp, const char* sq) {
+            // MFMAs (and the fp8 rescaling multiplies) have no side effects, so nothing else stops the
+            // compiler from sinking them past DMA issues, LDS reads and barriers towards the next use of
+            // the accumulators, which keeps two half-stages of fragments alive and undoes the schedule.
+            // An empty asm that "modifies" a block of accumulators pins its producer in program order.
+            auto pin = [](f32x16_t& v) { asm volatile("" : "+v"(v)::"memory"); };
+
+            auto fetch = [&](const char* sp, const char* sq, int half) {
                 if (FP8) {
-                    const int s0 = ((2 * fr_khalf) ^ fr_swz) * 16, s1 = ((2 * fr_khalf + 1) ^ fr_swz) * 16;
+                    // Q blocks and the first two P blocks; P blocks 2 and 3 are fetched during the MFMA phase
+                    // into the registers of blocks 0 and 1 once those have been consumed (see mma)
+                    const int s0 = ((4 * half + 2 * fr_khalf) ^ fr_swz) * 16, s1 = ((4 * half + 2 * fr_khalf + 1) ^ fr_swz) * 16;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
+                    for (int i = 0; i < 2; ++i) {
                         const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i] + s0), hi = *(const i32x4_t*)(sp + p_rd[i] + s1);
                         pf8[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     }
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         if (Q_CMAJ) {
-                            qf8[j] = lds_read_tr8x32(sq + q_rd[j]);
+                            qf8[j] = lds_read_tr8x32(sq + q_rd[j] + half * 64 * 256);
                         } else {
                             const i32x4_t lo = *(const i32x4_t*)(sq + q_rd[j] + s0), hi = *(const i32x4_t*)(sq + q_rd[j] + s1);
                             qf8[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -418,71 +432,93 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     }
                 } else {
 #pragma unroll
-                    for (int kk = 0; kk < 2; ++kk) {
+                    for (int k2 = 0; k2 < 2; ++k2) {
+                        const int kk = half * 2 + k2;
                         const int km_slot = ((kk * 2 + fr_khalf) ^ fr_swz) * 16;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            if (P_CMAJ) pf[kk][i] = lds_read_tr16x8(sp + p_rd[i] + kk * 8192, sp + p_rd[i] + kk * 8192 + 2048);
-                            else pf[kk][i] = *(const bf16x8_t*)(sp + p_rd[i] + km_slot);
+                            if (P_CMAJ) pf[k2][i] = lds_read_tr16x8(sp + p_rd[i] + kk * 8192, sp + p_rd[i] + kk * 8192 + 2048);
+                            else pf[k2][i] = *(const bf16x8_t*)(sp + p_rd[i] + km_slot);
                         }
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            if (Q_CMAJ) qf[kk][j] = lds_read_tr16x8(sq + q_rd[j] + kk * 8192, sq + q_rd[j] + kk * 8192 + 2048);
-                            else qf[kk][j] = *(const bf16x8_t*)(sq + q_rd[j] + km_slot);
+                            if (Q_CMAJ) qf[k2][j] = lds_read_tr16x8(sq + q_rd[j] + kk * 8192, sq + q_rd[j] + kk * 8192 + 2048);
+                            else qf[k2][j] = *(const bf16x8_t*)(sq + q_rd[j] + km_slot);
                         }
                     }
                 }
             };
-            // the MFMAs of one stage, with the GG_DMA_PER_STAGE DMA instructions of stage kt_dma slipped in
-            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq) {
+            // the MFMAs of one half-stage, with the GG_DMA_PER_STAGE DMA instructions of stage kt_dma slipped in
+            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq, const char* sp, int half) {
                 if (FP8) {
+                    const int s0 = ((4 * half + 2 * fr_khalf) ^ fr_swz) * 16, s1 = ((4 * half + 2 * fr_khalf + 1) ^ fr_swz) * 16;
+                    // blocks 0 and 1 from the registers fetched in the A phase; each is refilled with block
+                    // i+2 as soon as its two MFMAs are issued (P is k-major in both fp8 modes)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
+                    for (int i = 0; i < 2; ++i) {
 #pragma unroll
                         for (int j = 0; j < 2; ++j)
                             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 0, 127, 0, 127);
+                        pin(acc[i][0]);
+                        pin(acc[i][1]);
                         __builtin_amdgcn_sched_barrier(0);
-                        if (do_dma) issue_one(kt_dma, dp, dq, i);
+                        const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i + 2] + s0), hi = *(const i32x4_t*)(sp + p_rd[i + 2] + s1);
+                        pf8[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                         __builtin_amdgcn_sched_barrier(0);
                     }
+                    // the stage buffer is not read after this point: the DMA instructions follow
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            acc[i + 2][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i + 2][j], 0, 0, 0, 127, 0, 127);
+                            pin(acc[i + 2][j]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (do_dma) {
+                                issue_one(kt_dma, dp, dq, (i * 2 + j) * 2);
+                                issue_one(kt_dma, dp, dq, (i * 2 + j) * 2 + 1);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
                 } else {
 #pragma unroll
-                    for (int kk = 0; kk < 2; ++kk)
+                    for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
 #pragma unroll
                             for (int j = 0; j < 2; ++j)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk][j], pf[kk][i], acc[i][j], 0, 0, 0);
-                            if ((i & 1) == 1) {
-                                __builtin_amdgcn_sched_barrier(0);
-                                if (do_dma) issue_one(kt_dma, dp, dq, kk * 2 + (i >> 1));
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[k2][j], pf[k2][i], acc[i][j], 0, 0, 0);
+                            pin(acc[i][0]);
+                            pin(acc[i][1]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (do_dma) issue_one(kt_dma, dp, dq, k2 * 4 + i);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                 }
             };
             // fp8: entering contraction block kb, bring the accumulators to the new block's units
+            // (block 0 multiplies zeros by 1 / s_0, which is finite: scales are positive; no special case,
+            // so that the compiler does not peel the first stage off the loop)
             auto rescale = [&](int kb) {
-                if (kb > 0) {
-                    float pr[4], qr[2];
+                float qr[2];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) pr[i] = ps_cur[i] / ps_nxt[i];
+                for (int j = 0; j < 2; ++j) qr[j] = qs_cur[j] * __builtin_amdgcn_rcpf(qs_nxt[j]);
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) qr[j] = qs_cur[j] / qs_nxt[j];
+                for (int i = 0; i < 4; ++i) {
+                    const float pr = ps_cur[i] * __builtin_amdgcn_rcpf(ps_nxt[i]);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                    for (int j = 0; j < 2; ++j) {
+                        const float ratio = pr * qr[j];
 #pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            const float ratio = pr[i] * qr[j];
-#pragma unroll
-                            for (int x = 0; x < 16; ++x) acc[i][j][x] *= ratio;
-                        }
+                        for (int x = 0; x < 16; ++x) acc[i][j][x] *= ratio;
+                    }
+                    pin(acc[i][0]);
+                    pin(acc[i][1]);
+                    ps_cur[i] = ps_nxt[i];
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ps_cur[i] = ps_nxt[i];
-#pragma unroll
                 for (int j = 0; j < 2; ++j) qs_cur[j] = qs_nxt[j];
-                if (kb + 1 < CB) {  // next block's scales, needed two stages from now
+                if (kb + 1 < CB) {  // next block's scales, needed one stage from now
 #pragma unroll
                     for (int i = 0; i < 4; ++i) ps_nxt[i] = ps_load(i, kb + 1);
 #pragma unroll
@@ -492,26 +528,33 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 
             if (KT > 0) {
 #pragma unroll
-                for (int s = 0; s < GG_NS - 1; ++s)
-                    if (s < KT) {
+                for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(0, SP[0], SQ[0], x);
+                if (wm == 1 && KT > 1) {  // group 1 issues a stage one B phase earlier than group 0
 #pragma unroll
-                        for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(s, SP[s], SQ[s], x);
-                    }
-                wait_stage(min(GG_NS - 2, KT - 1));
+                    for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(1, SP[1], SQ[1], x);
+                    __builtin_amdgcn_s_waitcnt(0x0F70 | GG_DMA_PER_STAGE);  // stage 0 landed, stage 1 in flight
+                } else {
+                    wait_vm0();
+                }
                 stage_barrier();
                 if (wm == 1) stage_barrier();  // group 1 starts one phase later
-                for (int kt = 0; kt < KT; kt += GG_NS) {
+                for (int kt = 0; kt < KT; kt += 2) {
 #pragma unroll
-                    for (int s = 0; s < GG_NS; ++s) {
+                    for (int s = 0; s < 2; ++s) {
                         const int j = kt + s;
                         if (j < KT) {  // uniform
-                            if (FP8 && (j & 1) == 0) rescale(j >> 1);
-                            fetch(SP[s], SQ[s]);
+                            if (FP8) rescale(j);
+                            fetch(SP[s], SQ[s], 0);
                             wait_lgkm0();
-                            // stage j+1 (issued during B_{j+2-NS}) must have landed; stage j+2 may be in flight
-                            if (j + 1 < KT) wait_stage(min(GG_NS - 3, KT - 2 - j));
                             stage_barrier();
-                            mma(j + GG_NS - 1 < KT, j + GG_NS - 1, SP[(s + GG_NS - 1) % GG_NS], SQ[(s + GG_NS - 1) % GG_NS]);
+                            mma(wm == 0 && j + 1 < KT, j + 1, SP[s ^ 1], SQ[s ^ 1], SP[s], 0);   // group 0: stage j+1
+                            stage_barrier();
+                            fetch(SP[s], SQ[s], 1);
+                            wait_lgkm0();
+                            if (wm == 1) wait_vm0();                                    // group 1: stage j+1 landed
+                            stage_barrier();
+                            mma(wm == 1 && j + 2 < KT, j + 2, SP[s], SQ[s], SP[s], 1);        // group 1: stage j+2
+                            if (wm == 0) wait_vm0();                                    // group 0: stage j+1 landed
                             stage_barrier();
                         }
                     }
@@ -662,7 +705,7 @@ extern "C" moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const voi
     }
     const bool fp8 = dt == MOE_FP8_E4M3;
     if (fp8 && (!a_scale || !b_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: fp8 needs a_scale and b_scale");
-    if (!fp8 && K % 32) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd: K=%d must be a multiple of 32", K);
+    if (!fp8 && K % 64) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd: K=%d must be a multiple of 64", K);
     gg_args a = gg_make(ctx, A, B, offsets, E, N, K, Rcap, C);
     a.out_act = (bf16_t*)C_act;
     a.p_scale = a_scale;
@@ -688,7 +731,7 @@ extern "C" moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const v
     if (!dA) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: dA is NULL");
     const bool fp8 = dt == MOE_FP8_E4M3;
     if (fp8 && (!dc_scale || !b_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: fp8 needs dc_scale and b_scale");
-    if (!fp8 && N % 32) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad: N=%d must be a multiple of 32", N);
+    if (!fp8 && N % 64) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad: N=%d must be a multiple of 64", N);
     gg_args a = gg_make(ctx, dC, B, offsets, E, N, K, Rcap, dA);
     a.Zsaved = (const bf16_t*)Z_saved;
     a.p_scale = dc_scale;
