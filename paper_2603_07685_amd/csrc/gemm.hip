@@ -76,6 +76,7 @@ typedef const __attribute__((address_space(1))) void gbl_void_t;
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef int i32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
 typedef int i32x8_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
@@ -83,9 +84,39 @@ typedef __attribute__((address_space(3))) i32x2_t lds_i32x2_t;
 
 static_assert(2 * 2 * GG_STAGE_BYTES <= 144 * 1024, "pipeline stages exceed the LDS budget");
 
-__device__ __forceinline__ void dma16(const void* g, void* lds_wave_base) {
-    // each lane moves 16 bytes: LDS destination = wave-uniform base + lane * 16
-    __builtin_amdgcn_global_load_lds((gbl_void_t*)g, (lds_void_t*)lds_wave_base, 16, 0, 0);
+// Global -> LDS DMA: each lane moves 16 (or 4) bytes; LDS destination = M0 + lane * size.
+// Written as inline asm on purpose.  With the builtin, the compiler tracks every DMA as a pending LDS
+// write and decides on its own, per LDS read, whether to wait for it (s_waitcnt vmcnt); around a
+// software pipeline with conditional issue it cannot prove the buffers apart and puts vmcnt(0) in front
+// of fragment reads, which drains the pipeline every stage.  The kernel waits explicitly for exactly the
+// stage it is about to read (wait_vm0 + barrier), so the compiler needs to see only an opaque memory
+// write.  (Waits the compiler adds for its own global loads stay correct: the memory counter completes
+// in order, so extra older or younger entries only make such a wait longer.)
+// The LDS destination is passed as a wave-uniform register part plus a constant part (buffer + chunk).
+// The register part goes through an empty asm first: the sum is then formed at each use (one scalar add)
+// instead of sixteen loop-invariant sums each holding a scalar register across the stage loop.
+__device__ __forceinline__ uint32_t lds_addr(void* p) { return (uint32_t)(uintptr_t)(lds_void_t*)p; }
+__device__ __forceinline__ uint32_t m0_value(uint32_t lds_wave, uint32_t lds_const) {
+    asm volatile("" : "+s"(lds_wave));
+    return lds_wave + lds_const;
+}
+// scalar base + 32-bit lane offset (readfirstlane: a no-op for a value the compiler already keeps in
+// scalar registers, and the guarantee the "s" constraint needs where it does not)
+__device__ __forceinline__ void dma16(const char* base, uint32_t off, uint32_t lds_wave, uint32_t lds_const) {
+    const uint64_t b = (uint64_t)base;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    base = (const char*)(((uint64_t)hi << 32) | lo);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(m0_value(lds_wave, lds_const)), "v"(off), "s"(base) : "memory", "m0");
+}
+// per-lane 64-bit address
+__device__ __forceinline__ void dma16(const char* src, uint32_t lds_wave, uint32_t lds_const) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(m0_value(lds_wave, lds_const)), "v"(src) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(const void* src, uint32_t lds_wave, uint32_t lds_const) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                 :: "s"(m0_value(lds_wave, lds_const)), "v"(src) : "memory", "m0");
 }
 
 // Workgroup barrier without the memory fence __syncthreads() carries: the fence would drain every
@@ -159,8 +190,12 @@ struct gg_args {
 // FP8: operands are E4M3 codes with block scales (fwd and dgrad only).
 template <int MODE, int EPI, bool OUT_F32, bool FP8>
 __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
-    __shared__ __attribute__((aligned(1024))) char ldsP0[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsP1[GG_STAGE_BYTES];
+    // fp8: the block scales of a stage travel with it, behind the P tile: 256 row scales (position
+    // 4 * (row % 32) + row / 32 inside each 128-row half, so a lane finds its four rows in one 16-byte
+    // read) and, from position 256 on, the two column-block scales (replicated)
+    constexpr int SC_BYTES = FP8 ? 2048 : 0;
+    __shared__ __attribute__((aligned(1024))) char ldsP0[GG_STAGE_BYTES + SC_BYTES];
+    __shared__ __attribute__((aligned(1024))) char ldsP1[GG_STAGE_BYTES + SC_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsQ0[GG_STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char ldsQ1[GG_STAGE_BYTES];
     __shared__ int offs[GG_MAX_E + 1];
@@ -339,56 +374,52 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         // one of the GG_DMA_PER_STAGE DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
         auto issue_one = [&](int kt, char* sp, char* sq, int idx) {
             const int i = idx >> 1;
-            // the empty asm makes the lane offset opaque here, so that base + offset is not hoisted out of
-            // the stage loop as a 64-bit per-lane pointer: the load then takes the scalar-base form
-            uint32_t off = (idx & 1) ? qo[i] : po[i];
-            asm volatile("" : "+v"(off));
-            const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;
-            asm volatile("" : "+s"(base));  // the stage's operand base, complete, in scalar registers
-            const char* src = base + off;
+            const uint32_t off = (idx & 1) ? qo[i] : po[i];
+            const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
+            const uint32_t dst_wave = wave * (GG_CH * 1024), dst_const = lds_addr((idx & 1) ? sq : sp) + i * 1024;
             if (MODE == GG_WGRAD) {  // contraction tail of the expert: feed zeros
                 const int row = c_lo + kt * BKE + (wave * GG_CH + i) * CM_ROWS + cm_row;
-                src = row < c_hi ? src : a.zeros;
+                uint32_t o = off;
+                asm volatile("" : "+v"(o));  // opaque: keeps base + offset from being hoisted as 64-bit lane pointers
+                dma16(row < c_hi ? base + o : a.zeros, dst_wave, dst_const);
+            } else {
+                dma16(base, off, dst_wave, dst_const);
             }
-            dma16(src, ((idx & 1) ? sq : sp) + (wave * GG_CH + i) * 1024);
         };
 
         // ---- fp8 block scales: s = p_scale[row, kb] * q_scale[block]; per lane 4 rows x 2 column blocks ----
-        // kept as the two factors (4 per-lane row scales, 2 wave-uniform block scales), current and next
-        const int CB = (c_hi - c_lo) / 128;  // contraction blocks
-        const int ps_row0 = i0 + wm * 128 + fr_row;
-        int64_t qs_off[2] = {0, 0}, qs_step = 0;
-        float ps_cur[4], ps_nxt[4], qs_cur[2], qs_nxt[2];
-        auto ps_load = [&](int i, int kb) -> float {
-            int r = ps_row0 + i * 32;
-            asm volatile("" : "+v"(r));  // recompute the address at each use instead of carrying four of them
-            r = r < a.Rcap ? r : a.Rcap - 1;
-            return a.p_scale[(int64_t)r * CB + kb];
-        };
+        // The accumulators are kept in units of the current block's scale: entering block kb they are
+        // multiplied by s(kb-1) / s(kb), and by the last s in the epilogue.  The scales of block kb reach
+        // LDS with the operands of stage kb (one more 4-byte-per-lane DMA by waves 0..4).
+        const int CB = (c_hi - c_lo) / 128;  // contraction blocks = stages
+        const float* sc_src = nullptr;       // this lane's scale for block 0
+        int64_t sc_step = 0;                 // element advance per block
+        float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[2] = {1.f, 1.f};
         if (FP8) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                int col = (j ? j1 : j0) + wn * 32;
+            if (wave < 4) {  // row scales: LDS position p = 64 wave + lane holds tile row ...
+                const int pp = wave * 64 + lane;
+                int64_t r = (int64_t)i0 + (pp >> 7) * 128 + (pp & 3) * 32 + ((pp & 127) >> 2);
+                r = r < a.Rcap ? r : a.Rcap - 1;
+                sc_src = a.p_scale + r * CB;
+                sc_step = 1;
+            } else {         // column-block scales (issued by wave 4 only): even lanes block j0, odd lanes j1
+                int col = (lane & 1) ? j1 : j0;
                 col = col < J ? col : J - 1;
                 if (MODE == GG_FWD) {  // q_scale[e, col/128, kb]
-                    qs_off[j] = ((int64_t)e * (N / 128) + col / 128) * (K / 128);
-                    qs_step = 1;
-                } else {               // dgrad: contraction over N: q_scale[e, kb, col/128]
-                    qs_off[j] = (int64_t)e * (N / 128) * (K / 128) + col / 128;
-                    qs_step = K / 128;
+                    sc_src = a.q_scale + ((int64_t)e * (N / 128) + col / 128) * (K / 128);
+                    sc_step = 1;
+                } else {               // dgrad contracts over N: q_scale[e, kb, col/128]
+                    sc_src = a.q_scale + (int64_t)e * (N / 128) * (K / 128) + col / 128;
+                    sc_step = K / 128;
                 }
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                ps_nxt[i] = CB > 0 ? ps_load(i, 0) : 1.0f;
-                ps_cur[i] = 1.0f;
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                qs_nxt[j] = CB > 0 ? a.q_scale[qs_off[j]] : 1.0f;
-                qs_cur[j] = 1.0f;
-            }
         }
+        auto issue_scales = [&](int kb, float* ss) {
+            if (wave <= 4) {
+                const float* src = sc_src + kb * sc_step;
+                dma4(src, wave * 256, lds_addr(ss));
+            }
+        };
 
         f32x16_t acc[4][2];
 #pragma unroll
@@ -403,7 +434,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             char* const SQ[2] = {ldsQ0, ldsQ1};
             // operand fragments of one half-stage: bf16 2 x (4 + 2) x 4 VGPRs, fp8 (4 + 2) x 8 VGPRs
             bf16x8_t pf[2][4], qf[2][2];
-            i32x8_t pf8[2], qf8[2];
+            i32x8_t pf8[4], qf8[2];
 
             // MFMAs (and the fp8 rescaling multiplies) have no side effects, so nothing else stops the
             // compiler from sinking them past DMA issues, LDS reads and barriers towards the next use of
@@ -413,11 +444,9 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 
             auto fetch = [&](const char* sp, const char* sq, int half) {
                 if (FP8) {
-                    // Q blocks and the first two P blocks; P blocks 2 and 3 are fetched during the MFMA phase
-                    // into the registers of blocks 0 and 1 once those have been consumed (see mma)
                     const int s0 = ((4 * half + 2 * fr_khalf) ^ fr_swz) * 16, s1 = ((4 * half + 2 * fr_khalf + 1) ^ fr_swz) * 16;
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
+                    for (int i = 0; i < 4; ++i) {  // P is k-major in both fp8 modes
                         const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i] + s0), hi = *(const i32x4_t*)(sp + p_rd[i] + s1);
                         pf8[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     }
@@ -449,35 +478,16 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
             };
             // the MFMAs of one half-stage, with the GG_DMA_PER_STAGE DMA instructions of stage kt_dma slipped in
-            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq, const char* sp, int half) {
+            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq) {
                 if (FP8) {
-                    const int s0 = ((4 * half + 2 * fr_khalf) ^ fr_swz) * 16, s1 = ((4 * half + 2 * fr_khalf + 1) ^ fr_swz) * 16;
-                    // blocks 0 and 1 from the registers fetched in the A phase; each is refilled with block
-                    // i+2 as soon as its two MFMAs are issued (P is k-major in both fp8 modes)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-#pragma unroll
-                        for (int j = 0; j < 2; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 0, 127, 0, 127);
-                        pin(acc[i][0]);
-                        pin(acc[i][1]);
-                        __builtin_amdgcn_sched_barrier(0);
-                        const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i + 2] + s0), hi = *(const i32x4_t*)(sp + p_rd[i + 2] + s1);
-                        pf8[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    // the stage buffer is not read after this point: the DMA instructions follow
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
+                    for (int i = 0; i < 4; ++i)
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            acc[i + 2][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i + 2][j], 0, 0, 0, 127, 0, 127);
-                            pin(acc[i + 2][j]);
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 0, 127, 0, 127);
+                            pin(acc[i][j]);
                             __builtin_amdgcn_sched_barrier(0);
-                            if (do_dma) {
-                                issue_one(kt_dma, dp, dq, (i * 2 + j) * 2);
-                                issue_one(kt_dma, dp, dq, (i * 2 + j) * 2 + 1);
-                            }
+                            if (do_dma) issue_one(kt_dma, dp, dq, i * 2 + j);
                             __builtin_amdgcn_sched_barrier(0);
                         }
                 } else {
@@ -499,13 +509,24 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             // fp8: entering contraction block kb, bring the accumulators to the new block's units
             // (block 0 multiplies zeros by 1 / s_0, which is finite: scales are positive; no special case,
             // so that the compiler does not peel the first stage off the loop)
-            auto rescale = [&](int kb) {
-                float qr[2];
+            f32x4_t pn;
+            float qn[2];
+            auto read_scales = [&](const float* ss) {
+                pn = *(const f32x4_t*)(ss + wm * 128 + fr_row * 4);
+                qn[0] = ss[256];
+                qn[1] = ss[257];
+            };
+            auto rescale = [&]() {
+                float qs_nxt[2], qr[2];
 #pragma unroll
-                for (int j = 0; j < 2; ++j) qr[j] = qs_cur[j] * __builtin_amdgcn_rcpf(qs_nxt[j]);
+                for (int j = 0; j < 2; ++j) {
+                    qs_nxt[j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, qn[j])));
+                    qr[j] = qs_cur[j] * __builtin_amdgcn_rcpf(qs_nxt[j]);
+                    qs_cur[j] = qs_nxt[j];
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float pr = ps_cur[i] * __builtin_amdgcn_rcpf(ps_nxt[i]);
+                    const float pr = ps_cur[i] * __builtin_amdgcn_rcpf(pn[i]);
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         const float ratio = pr * qr[j];
@@ -514,52 +535,92 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     }
                     pin(acc[i][0]);
                     pin(acc[i][1]);
-                    ps_cur[i] = ps_nxt[i];
-                }
-#pragma unroll
-                for (int j = 0; j < 2; ++j) qs_cur[j] = qs_nxt[j];
-                if (kb + 1 < CB) {  // next block's scales, needed one stage from now
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) ps_nxt[i] = ps_load(i, kb + 1);
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) qs_nxt[j] = a.q_scale[qs_off[j] + (int64_t)(kb + 1) * qs_step];
+                    ps_cur[i] = pn[i];
                 }
             };
 
-            if (KT > 0) {
+            // The two wave groups (wm = 0 / 1) run the same stages one slot apart: while one group issues
+            // MFMAs the other reads fragments.  Each group has its own copy of the loop, so that every wait
+            // is unconditional inside it (the compiler's own wait insertion then sees exactly which DMA is
+            // outstanding at each LDS read and adds nothing).  Both copies execute the same number of
+            // barriers: 2 + 4 KT.
+            //   slot:      1        2        3        4        5 ...
+            //   group 0:   A(j,0)   B(j,0)   A(j,1)   B(j,1)   A(j+1,0)
+            //   group 1:   B(j-1,1) A(j,0)   B(j,0)   A(j,1)   B(j,1)
+            // A = fragment reads of a half-stage (+ fp8 rescale), B = its MFMAs.  Stage j+1 goes into the
+            // buffer stage j-1 used, whose last reader is group 1's A(j-1,1) in the slot before slot 1:
+            // group 0 issues its share of stage j+1 at the start of A(j,0), group 1 during B(j-1,1), both in
+            // slot 1, and both wait for their share in slot 4.
+            float* const SS[2] = {(float*)(ldsP0 + GG_STAGE_BYTES), (float*)(ldsP1 + GG_STAGE_BYTES)};
+            auto half_a = [&](int s, int half) {
+                if (FP8 && half == 0) {
+                    read_scales(SS[s]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                fetch(SP[s], SQ[s], half);
+                __builtin_amdgcn_sched_barrier(0);
+                if (FP8 && half == 0) rescale();  // after the fragment reads in program order: overlaps them
+                wait_lgkm0();
+            };
+            if (KT > 0 && wm == 0) {
 #pragma unroll
                 for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(0, SP[0], SQ[0], x);
-                if (wm == 1 && KT > 1) {  // group 1 issues a stage one B phase earlier than group 0
+                if (FP8) issue_scales(0, SS[0]);
+                wait_vm0();
+                stage_barrier();
+                auto stage0 = [&](int j, int s) {
+                    if (j + 1 < KT) {
+#pragma unroll
+                        for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(j + 1, SP[s ^ 1], SQ[s ^ 1], x);
+                        if (FP8) issue_scales(j + 1, SS[s ^ 1]);
+                    }
+                    half_a(s, 0);
+                    stage_barrier();
+                    mma(false, 0, nullptr, nullptr);
+                    stage_barrier();
+                    half_a(s, 1);
+                    stage_barrier();
+                    mma(false, 0, nullptr, nullptr);
+                    wait_vm0();  // stage j+1 landed
+                    stage_barrier();
+                };
+                // (an odd stage count leaves through an exit edge, not a skipped block: the compiler then sees
+                // that no path re-enters the loop with a DMA into the buffer about to be read still pending)
+                for (int j = 0; j < KT; j += 2) {
+                    stage0(j, 0);
+                    if (j + 1 >= KT) break;
+                    stage0(j + 1, 1);
+                }
+                stage_barrier();  // group 1's last slot
+            } else if (KT > 0) {
+#pragma unroll
+                for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(0, SP[0], SQ[0], x);
+                if (FP8) issue_scales(0, SS[0]);
+                wait_vm0();
+                stage_barrier();
+                if (KT > 1) {  // slot 1: group 0 reads stage 0, both groups issue their share of stage 1
 #pragma unroll
                     for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(1, SP[1], SQ[1], x);
-                    __builtin_amdgcn_s_waitcnt(0x0F70 | GG_DMA_PER_STAGE);  // stage 0 landed, stage 1 in flight
-                } else {
-                    wait_vm0();
+                    if (FP8) issue_scales(1, SS[1]);
                 }
-                stage_barrier();
-                if (wm == 1) stage_barrier();  // group 1 starts one phase later
-                for (int kt = 0; kt < KT; kt += 2) {
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        const int j = kt + s;
-                        if (j < KT) {  // uniform
-                            if (FP8) rescale(j);
-                            fetch(SP[s], SQ[s], 0);
-                            wait_lgkm0();
-                            stage_barrier();
-                            mma(wm == 0 && j + 1 < KT, j + 1, SP[s ^ 1], SQ[s ^ 1], SP[s], 0);   // group 0: stage j+1
-                            stage_barrier();
-                            fetch(SP[s], SQ[s], 1);
-                            wait_lgkm0();
-                            if (wm == 1) wait_vm0();                                    // group 1: stage j+1 landed
-                            stage_barrier();
-                            mma(wm == 1 && j + 2 < KT, j + 2, SP[s], SQ[s], SP[s], 1);        // group 1: stage j+2
-                            if (wm == 0) wait_vm0();                                    // group 0: stage j+1 landed
-                            stage_barrier();
-                        }
-                    }
+                stage_barrier();  // group 0's first slot
+                auto stage1 = [&](int j, int s) {
+                    half_a(s, 0);
+                    stage_barrier();
+                    mma(false, 0, nullptr, nullptr);
+                    stage_barrier();
+                    half_a(s, 1);
+                    wait_vm0();  // stage j+1 landed
+                    stage_barrier();
+                    mma(j + 2 < KT, j + 2, SP[s], SQ[s]);
+                    if (FP8 && j + 2 < KT) issue_scales(j + 2, SS[s]);
+                    stage_barrier();
+                };
+                for (int j = 0; j < KT; j += 2) {
+                    stage1(j, 0);
+                    if (j + 1 >= KT) break;
+                    stage1(j + 1, 1);
                 }
-                if (wm == 0) stage_barrier();  // re-align the two groups
             }
         }
 
