@@ -287,10 +287,21 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         else q_rd[j] = (j * 128 + wn * 32 + fr_row) * GG_ROWB;
     }
 
+    // ---- state of the tile being set up / multiplied (assigned by setup_tile) ----
+    int e = 0, i0 = 0, i_end = 0, j0 = 0, j1 = 0;  // expert, output row origin and end, column origins of the two halves
+    int c_lo = 0, c_hi = 0, KT = 0;                // contraction range and its stage count
+    // DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus GG_CH 32-bit
+    // per-lane offsets; offsets stay below 2^32 because they are tile-relative
+    const char* p_base = nullptr;
+    const char* q_base = nullptr;
+    uint32_t po[GG_CH], qo[GG_CH];
+    int64_t p_step = 0, q_step = 0;  // byte advance per stage
+    const float* sc_src = nullptr;   // fp8: this lane's scale for block 0
+    int64_t sc_step = 0;             // fp8: element advance per block
     int e_hint = 0;
-    for (int t = q; t < total_tiles; t += G) {
+    auto setup_tile = [&](int t) {
         // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
-        int e = e_hint;
+        e = e_hint;
         while (e + 1 < E && t >= __builtin_amdgcn_readfirstlane(tile_start[e + 1])) ++e;
         e_hint = e;
         const int u = t - __builtin_amdgcn_readfirstlane(tile_start[e]);
@@ -306,21 +317,17 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             tj = in_band / band_rows;
         }
         // output row/column origin of the two 128-column halves
-        const int i0 = (MODE == GG_WGRAD) ? ti * GG_BM : row_lo + ti * GG_BM;
-        const int i_end = (MODE == GG_WGRAD) ? N : row_hi;
-        const int j0 = (EPI == GG_EPI_SWIGLU) ? tj * 128 : tj * GG_BN;
-        const int j1 = (EPI == GG_EPI_SWIGLU) ? half_cols + tj * 128 : tj * GG_BN + 128;
+        i0 = (MODE == GG_WGRAD) ? ti * GG_BM : row_lo + ti * GG_BM;
+        i_end = (MODE == GG_WGRAD) ? N : row_hi;
+        j0 = (EPI == GG_EPI_SWIGLU) ? tj * 128 : tj * GG_BN;
+        j1 = (EPI == GG_EPI_SWIGLU) ? half_cols + tj * 128 : tj * GG_BN + 128;
         // contraction range
-        const int c_lo = (MODE == GG_WGRAD) ? row_lo : 0;
-        const int c_hi = (MODE == GG_WGRAD) ? row_hi : (MODE == GG_FWD ? K : N);
-        const int KT = (c_hi - c_lo + BKE - 1) / BKE;
+        c_lo = (MODE == GG_WGRAD) ? row_lo : 0;
+        c_hi = (MODE == GG_WGRAD) ? row_hi : (MODE == GG_FWD ? K : N);
+        KT = (c_hi - c_lo + BKE - 1) / BKE;
 
         // ---- DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus
         //      GG_CH 32-bit per-lane offsets; offsets stay below 2^32 because they are tile-relative ----
-        const char* p_base;
-        const char* q_base;
-        uint32_t po[GG_CH], qo[GG_CH];
-        int64_t p_step, q_step;  // byte advance per stage
         if (P_CMAJ) {
             // P = dC [rows, N]: contraction row c, columns i0..i0+255
             p_step = (int64_t)BKE * N * ES;
@@ -371,30 +378,11 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             }
         }
 
-        // one of the GG_DMA_PER_STAGE DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
-        auto issue_one = [&](int kt, char* sp, char* sq, int idx) {
-            const int i = idx >> 1;
-            const uint32_t off = (idx & 1) ? qo[i] : po[i];
-            const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
-            const uint32_t dst_wave = wave * (GG_CH * 1024), dst_const = lds_addr((idx & 1) ? sq : sp) + i * 1024;
-            if (MODE == GG_WGRAD) {  // contraction tail of the expert: feed zeros
-                const int row = c_lo + kt * BKE + (wave * GG_CH + i) * CM_ROWS + cm_row;
-                uint32_t o = off;
-                asm volatile("" : "+v"(o));  // opaque: keeps base + offset from being hoisted as 64-bit lane pointers
-                dma16(row < c_hi ? base + o : a.zeros, dst_wave, dst_const);
-            } else {
-                dma16(base, off, dst_wave, dst_const);
-            }
-        };
-
         // ---- fp8 block scales: s = p_scale[row, kb] * q_scale[block]; per lane 4 rows x 2 column blocks ----
         // The accumulators are kept in units of the current block's scale: entering block kb they are
         // multiplied by s(kb-1) / s(kb), and by the last s in the epilogue.  The scales of block kb reach
         // LDS with the operands of stage kb (one more 4-byte-per-lane DMA by waves 0..4).
         const int CB = (c_hi - c_lo) / 128;  // contraction blocks = stages
-        const float* sc_src = nullptr;       // this lane's scale for block 0
-        int64_t sc_step = 0;                 // element advance per block
-        float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[2] = {1.f, 1.f};
         if (FP8) {
             if (wave < 4) {  // row scales: LDS position p = 64 wave + lane holds tile row ...
                 const int pp = wave * 64 + lane;
@@ -414,6 +402,24 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
             }
         }
+    };
+
+        // one of the GG_DMA_PER_STAGE DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
+        auto issue_one = [&](int kt, char* sp, char* sq, int idx) {
+            const int i = idx >> 1;
+            const uint32_t off = (idx & 1) ? qo[i] : po[i];
+            const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
+            const uint32_t dst_wave = wave * (GG_CH * 1024), dst_const = lds_addr((idx & 1) ? sq : sp) + i * 1024;
+            if (MODE == GG_WGRAD) {  // contraction tail of the expert: feed zeros
+                const int row = c_lo + kt * BKE + (wave * GG_CH + i) * CM_ROWS + cm_row;
+                uint32_t o = off;
+                asm volatile("" : "+v"(o));  // opaque: keeps base + offset from being hoisted as 64-bit lane pointers
+                dma16(row < c_hi ? base + o : a.zeros, dst_wave, dst_const);
+            } else {
+                dma16(base, off, dst_wave, dst_const);
+            }
+        };
+
         auto issue_scales = [&](int kb, float* ss) {
             if (wave <= 4) {
                 const float* src = sc_src + kb * sc_step;
@@ -421,6 +427,25 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             }
         };
 
+    char* const SP[2] = {ldsP0, ldsP1};
+    char* const SQ[2] = {ldsQ0, ldsQ1};
+    float* const SS[2] = {(float*)(ldsP0 + GG_STAGE_BYTES), (float*)(ldsP1 + GG_STAGE_BYTES)};
+    // stage 0 of a tile: every wave issues its share.  It is issued before the epilogue of the previous tile,
+    // so that the first fetch of a tile overlaps the output phase of the one before
+    auto issue_stage0 = [&]() {
+        if (KT > 0) {
+#pragma unroll
+            for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(0, SP[0], SQ[0], x);
+            if (FP8) issue_scales(0, SS[0]);
+        }
+    };
+
+    if (q < total_tiles) {
+        setup_tile(q);
+        issue_stage0();
+    }
+    for (int t = q; t < total_tiles; t += G) {
+        float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[2] = {1.f, 1.f};
         f32x16_t acc[4][2];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -430,8 +455,6 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
 
         {
-            char* const SP[2] = {ldsP0, ldsP1};
-            char* const SQ[2] = {ldsQ0, ldsQ1};
             // operand fragments of one half-stage: bf16 2 x (4 + 2) x 4 VGPRs, fp8 (4 + 2) x 8 VGPRs
             bf16x8_t pf[2][4], qf[2][2];
             i32x8_t pf8[4], qf8[2];
@@ -551,7 +574,6 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             // buffer stage j-1 used, whose last reader is group 1's A(j-1,1) in the slot before slot 1:
             // group 0 issues its share of stage j+1 at the start of A(j,0), group 1 during B(j-1,1), both in
             // slot 1, and both wait for their share in slot 4.
-            float* const SS[2] = {(float*)(ldsP0 + GG_STAGE_BYTES), (float*)(ldsP1 + GG_STAGE_BYTES)};
             auto half_a = [&](int s, int half) {
                 if (FP8 && half == 0) {
                     read_scales(SS[s]);
@@ -563,10 +585,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 wait_lgkm0();
             };
             if (KT > 0 && wm == 0) {
-#pragma unroll
-                for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(0, SP[0], SQ[0], x);
-                if (FP8) issue_scales(0, SS[0]);
-                wait_vm0();
+                wait_vm0();  // stage 0, issued before the previous tile's epilogue
                 stage_barrier();
                 auto stage0 = [&](int j, int s) {
                     if (j + 1 < KT) {
@@ -593,9 +612,6 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
                 stage_barrier();  // group 1's last slot
             } else if (KT > 0) {
-#pragma unroll
-                for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(0, SP[0], SQ[0], x);
-                if (FP8) issue_scales(0, SS[0]);
                 wait_vm0();
                 stage_barrier();
                 if (KT > 1) {  // slot 1: group 0 reads stage 0, both groups issue their share of stage 1
@@ -624,17 +640,26 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             }
         }
 
+        // ---- next tile: set it up and start its first stage, then write this tile out ----
+        // (every wave is past its last LDS read here: the stage loop ends with a barrier after the last
+        // fragment reads of both groups)
+        const int ep_e = e, ep_i0 = i0, ep_i_end = i_end, ep_j0 = j0, ep_j1 = j1;
+        if (t + G < total_tiles) {
+            setup_tile(t + G);
+            issue_stage0();
+        }
+
         // ---- epilogue ----
         // A lane holds, per 32x32 block, one output row (P index = lane % 32) and four groups of 4
         // consecutive output columns (Q index = 8 g + 4 (lane / 32) + 0..3).
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = i0 + wm * 128 + i * 32 + fr_row;
-            if (r >= i_end) continue;
+            const int r = ep_i0 + wm * 128 + i * 32 + fr_row;
+            if (r >= ep_i_end) continue;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int c0 = j0 + wn * 32 + 8 * g + 4 * fr_khalf;
-                const int c1 = j1 + wn * 32 + 8 * g + 4 * fr_khalf;
+                const int c0 = ep_j0 + wn * 32 + 8 * g + 4 * fr_khalf;
+                const int c1 = ep_j1 + wn * 32 + 8 * g + 4 * fr_khalf;
                 float v0[4], v1[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
@@ -680,7 +705,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                         }
                     }
                 } else {
-                    const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)e * N + r) * K : (int64_t)r * J;
+                    const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r) * K : (int64_t)r * J;
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) {
                         const int c = h2 ? c1 : c0;
@@ -706,7 +731,6 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
             }
         }
-        __syncthreads();  // the LDS stages are refilled by the next tile's prologue
     }
 }
 
