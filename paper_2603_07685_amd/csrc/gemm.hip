@@ -194,10 +194,17 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     // 4 * (row % 32) + row / 32 inside each 128-row half, so a lane finds its four rows in one 16-byte
     // read) and, from position 256 on, the two column-block scales (replicated)
     constexpr int SC_BYTES = FP8 ? 2048 : 0;
-    __shared__ __attribute__((aligned(1024))) char ldsP0[GG_STAGE_BYTES + SC_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsP1[GG_STAGE_BYTES + SC_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsQ0[GG_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsQ1[GG_STAGE_BYTES];
+    // One LDS array: [P0 | scales0 | Q0 | P1 | scales1 | Q1 | pad].  Buffer 1 (from P1 on) doubles as the
+    // staging area of the epilogue: 64 tile rows x 260 floats.
+    constexpr int BUF_BYTES = 2 * GG_STAGE_BYTES + SC_BYTES;
+    constexpr int STG_PITCH = 260;                       // floats per staged row: 256 + 4 (bank rotation)
+    constexpr int STG_BYTES = 64 * STG_PITCH * 4;
+    constexpr int LDS_BYTES = BUF_BYTES + (BUF_BYTES > STG_BYTES ? BUF_BYTES : STG_BYTES);
+    __shared__ __attribute__((aligned(1024))) char lds_buf[LDS_BYTES];
+    char* const ldsP0 = lds_buf;
+    char* const ldsQ0 = lds_buf + GG_STAGE_BYTES + SC_BYTES;
+    char* const ldsP1 = lds_buf + BUF_BYTES;
+    char* const ldsQ1 = ldsP1 + GG_STAGE_BYTES + SC_BYTES;
     __shared__ int offs[GG_MAX_E + 1];
     __shared__ int tile_start[GG_MAX_E + 1];
 
@@ -650,86 +657,100 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         }
 
         // ---- epilogue ----
-        // A lane holds, per 32x32 block, one output row (P index = lane % 32) and four groups of 4
-        // consecutive output columns (Q index = 8 g + 4 (lane / 32) + 0..3).
+        // A lane holds, per 32x32 block, one output row (P index = lane % 32) and four groups of 4 consecutive
+        // output columns (Q index = 8 g + 4 (lane / 32) + 0..3): written out directly, a store instruction
+        // would touch 32 rows x 16 bytes.  Instead the accumulators go through LDS (fp32), one 32-row block
+        // of both wave groups (64 tile rows) per pass, and come back one whole tile row per wave and
+        // instruction: lane l owns columns 4 l .. 4 l + 3 of the 256, so every global access is 256-512
+        // contiguous bytes.  Buffer 1 is free here: the next tile's stage 0 went to buffer 0, its stage 1 is
+        // issued after the barrier that follows this epilogue.
+        float* const stg = (float*)ldsP1;
+        const int cl = lane * 4;                                          // column inside the 256-wide tile
+        const int c = cl < 128 ? ep_j0 + cl : ep_j1 + cl - 128;           // output column of this lane
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = ep_i0 + wm * 128 + i * 32 + fr_row;
-            if (r >= ep_i_end) continue;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int c0 = ep_j0 + wn * 32 + 8 * g + 4 * fr_khalf;
-                const int c1 = ep_j1 + wn * 32 + 8 * g + 4 * fr_khalf;
-                float v0[4], v1[4];
+            for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    v0[x] = acc[i][0][4 * g + x];
-                    v1[x] = acc[i][1][4 * g + x];
-                    if (FP8) {
-                        v0[x] *= ps_cur[i] * qs_cur[0];
-                        v1[x] *= ps_cur[i] * qs_cur[1];
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    f32x4_t v;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        v[x] = acc[i][h2][4 * g + x];
+                        if (FP8) v[x] *= ps_cur[i] * qs_cur[h2];
                     }
+                    *(f32x4_t*)(stg + (wm * 32 + fr_row) * STG_PITCH + h2 * 128 + wn * 32 + 8 * g + 4 * fr_khalf) = v;
                 }
-                if (EPI == GG_EPI_SWIGLU) {
-                    if (c0 < half_cols) {
-                        bf16_t* C = (bf16_t*)a.out;
-                        if (C) {
-                            st4_bf16(C + (int64_t)r * N + c0, v0);
-                            st4_bf16(C + (int64_t)r * N + c1, v1);
-                        }
-                        float act[4];
+            wait_lgkm0();
+            stage_barrier();
 #pragma unroll
-                        for (int x = 0; x < 4; ++x) act[x] = v0[x] * sigmoid_f(v0[x]) * v1[x];
-                        st4_bf16(a.out_act + (int64_t)r * half_cols + c0, act);
+            for (int x8 = 0; x8 < 8; ++x8) {
+                const int rr = wave * 8 + x8;                             // staged row 0..63
+                const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
+                if (r >= ep_i_end) continue;                              // wave-uniform
+                const f32x4_t v = *(const f32x4_t*)(stg + rr * STG_PITCH + cl);
+                if (EPI == GG_EPI_SWIGLU) {
+                    bf16_t* C = (bf16_t*)a.out;                           // [gate | up] pre-activations
+                    if (C && ep_j0 + (cl & 127) < half_cols) {
+                        const float t4[4] = {v[0], v[1], v[2], v[3]};
+                        st4_bf16(C + (int64_t)r * N + c, t4);
                     }
                 } else if (EPI == GG_EPI_SWIGLU_BWD) {
                     // dZ[r, c] = dA * up * s (1 + g (1 - s)),  dZ[r, K + c] = dA * g * s,  s = sigmoid(g)
-                    bf16_t* dZ = (bf16_t*)a.out;
-                    const int64_t zr = (int64_t)r * 2 * K;
+                    if (c < K) {
+                        bf16_t* dZ = (bf16_t*)a.out;
+                        const int64_t zr = (int64_t)r * 2 * K;
+                        float gt[4], up[4], dg[4], du[4];
+                        ld4_bf16(a.Zsaved + zr + c, gt);
+                        ld4_bf16(a.Zsaved + zr + K + c, up);
 #pragma unroll
-                    for (int h2 = 0; h2 < 2; ++h2) {
-                        const int c = h2 ? c1 : c0;
-                        const float* v = h2 ? v1 : v0;
-                        if (c < K) {
-                            float gt[4], up[4], dg[4], du[4];
-                            ld4_bf16(a.Zsaved + zr + c, gt);
-                            ld4_bf16(a.Zsaved + zr + K + c, up);
-#pragma unroll
-                            for (int x = 0; x < 4; ++x) {
-                                const float sg = sigmoid_f(gt[x]);
-                                dg[x] = v[x] * up[x] * sg * (1.0f + gt[x] * (1.0f - sg));
-                                du[x] = v[x] * gt[x] * sg;
-                            }
-                            st4_bf16(dZ + zr + c, dg);
-                            st4_bf16(dZ + zr + K + c, du);
+                        for (int x = 0; x < 4; ++x) {
+                            const float sg = sigmoid_f(gt[x]);
+                            dg[x] = v[x] * up[x] * sg * (1.0f + gt[x] * (1.0f - sg));
+                            du[x] = v[x] * gt[x] * sg;
                         }
+                        st4_bf16(dZ + zr + c, dg);
+                        st4_bf16(dZ + zr + K + c, du);
                     }
-                } else {
+                } else if (c < J) {
                     const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r) * K : (int64_t)r * J;
+                    if (OUT_F32) {
+                        f32x4_t* o = (f32x4_t*)((float*)a.out + base + c);
+                        f32x4_t w = v;
+                        if (a.accumulate) w += *o;
+                        *o = w;
+                    } else {
+                        bf16_t* o = (bf16_t*)a.out + base + c;
+                        float t4[4] = {v[0], v[1], v[2], v[3]};
+                        if (a.accumulate) {
+                            float old[4];
+                            ld4_bf16(o, old);
 #pragma unroll
-                    for (int h2 = 0; h2 < 2; ++h2) {
-                        const int c = h2 ? c1 : c0;
-                        float* v = h2 ? v1 : v0;
-                        if (c < J) {
-                            if (OUT_F32) {
-                                f32x4_t* o = (f32x4_t*)((float*)a.out + base + c);
-                                f32x4_t w = {v[0], v[1], v[2], v[3]};
-                                if (a.accumulate) w += *o;
-                                *o = w;
-                            } else {
-                                bf16_t* o = (bf16_t*)a.out + base + c;
-                                if (a.accumulate) {
-                                    float old[4];
-                                    ld4_bf16(o, old);
-#pragma unroll
-                                    for (int x = 0; x < 4; ++x) v[x] += old[x];
-                                }
-                                st4_bf16(o, v);
-                            }
+                            for (int x = 0; x < 4; ++x) t4[x] += old[x];
                         }
+                        st4_bf16(o, t4);
                     }
                 }
             }
+            if (EPI == GG_EPI_SWIGLU) {
+                // activation: a lane pairs gate and up of 4 features; two tile rows per instruction
+                const int fl = (lane & 31) * 4;
+#pragma unroll
+                for (int x4 = 0; x4 < 4; ++x4) {
+                    const int rr = wave * 8 + 2 * x4 + (lane >> 5);
+                    const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
+                    if (r < ep_i_end && ep_j0 + fl < half_cols) {
+                        const f32x4_t gt = *(const f32x4_t*)(stg + rr * STG_PITCH + fl);
+                        const f32x4_t up = *(const f32x4_t*)(stg + rr * STG_PITCH + 128 + fl);
+                        float act[4];
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) act[x] = gt[x] * sigmoid_f(gt[x]) * up[x];
+                        st4_bf16(a.out_act + (int64_t)r * half_cols + ep_j0 + fl, act);
+                    }
+                }
+            }
+            wait_lgkm0();
+            stage_barrier();  // the staging rows are rewritten by the next pass (or the next tile's stage 1)
         }
     }
 }
