@@ -23,6 +23,18 @@ FP8_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 CAL_COPY_BYTES = 1 << 30    # size of the calibration copy (read 1 GiB, write 1 GiB)
 
+# HBM-side bytes per launch (GB read, GB written) of the grouped-GEMM call sites, from two rocprofv3 counter
+# passes over this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same
+# counter read for the 1 GiB calibration copy above (FETCH_SIZE 0.5 x, WRITE_SIZE 1.0 x of the known size).
+# Summaries and commands: profiles/gg_kernel_c4_hbm_traffic.txt, profiles/gg_kernel_c5_hbm_traffic.txt.
+# Offline measurements: they describe the committed kernels at the default load pattern, not this run.
+MEASURED_TRAFFIC_GB = {
+    "C4": {"fc1_fwd_swiglu_bf16": (13.33, 1.61), "fc2_fwd_bf16": (6.73, 1.88), "fc2_wgrad_bf16": (11.43, 0.94),
+           "fc2_dgrad_swiglu_bwd_bf16": (9.26, 1.07), "fc1_wgrad_bf16": (18.53, 1.88), "fc1_dgrad_bf16": (15.21, 1.88)},
+    "C5": {"fc1_fwd_swiglu_fp8": (7.16, 1.65), "fc2_fwd_fp8": (3.86, 1.92), "fc2_wgrad_bf16": (12.05, 0.94),
+           "fc2_dgrad_swiglu_bwd_fp8": (4.99, 1.10), "fc1_wgrad_bf16": (19.29, 1.88), "fc1_dgrad_fp8": (7.07, 1.91)},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -54,7 +66,14 @@ def describe_call(name, args, st):
             extra = ""
         which = ("fc1" if (kind == "fwd" and K == cfg.h) or (kind != "fwd" and K == cfg.h) else "fc2")
         label = f"{'shared_' if E == 1 else ''}{which}_{kind}{extra}_{tag}"
-        return label, 2.0 * rows * N * K, None
+        es = 1 if dt == 1 else 2
+        if kind == "fwd":      # read A and the weights once, write C (SwiGLU: pre-activations + activation)
+            by = rows * K * es + E * N * K * es + rows * N * 2 + (rows * (N // 2) * 2 if extra else 0)
+        elif kind == "dgrad":  # read dC and the weights once, write dA (SwiGLU-bwd: read Z, write dZ, both [rows, 2K])
+            by = rows * N * es + E * N * K * es + (rows * 2 * K * 2 * 2 if extra else rows * K * 2)
+        else:                  # read A and dC once, write the weight gradients
+            by = rows * (N + K) * 2 + E * N * K * (4 if args[12] == 2 else 2)
+        return label, 2.0 * rows * N * K, by
     if name == "moe_route_topk":
         Tn, E = args[2], args[3]
         return "route_topk", None, Tn * E * 4 + Tn * args[4] * 8 + E * 4
@@ -216,6 +235,9 @@ def main():
         breakdown[key] = d
     gemm = [(t, lab, fl) for lab, fl, by, t in calls if fl]
     t_dom, n_dom, fl_dom = max(gemm)
+    by_dom = next(by for lab, fl, by, t in calls if lab == n_dom)
+    rw = MEASURED_TRAFFIC_GB.get(args.workload, {}).get(n_dom) if args.variant is None else None
+    traffic = round(sum(rw), 2) if rw else None
     achieved = fl_dom / t_dom / 1e9
     gemm_ms = sum(t for t, _, _ in gemm)
     gemm_fl = sum(fl for _, _, fl in gemm)
@@ -240,7 +262,9 @@ def main():
                       "pct_peak": round(100.0 * gemm_fl / gemm_ms / 1e9 / BF16_PEAK_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "kernel": f"gg_kernel ({n_dom})", "achieved": round(achieved, 1),
                      "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": None},
+                     "traffic": traffic, "traffic_unit": "GB per launch (HBM-side read + write, offline counters)",
+                     "traffic_read_write_gb": list(rw) if rw else None,
+                     "algorithmic_gb": round(by_dom / 1e9, 2) if by_dom else None},
         "kernels": breakdown,
     }
     # context only: the vendor dense bf16 GEMM through torch on this very box (boxes differ by +-20 %)

@@ -139,7 +139,11 @@ moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe_dtype dt,
  * dt is the operand type: MOE_BF16 (fp32 accumulation, bf16 result) or
  * MOE_FP8_E4M3 (blockwise recipe of Sec. 5.3.2: operands are E4M3 codes with
  * fp32 scales, fp32 accumulation, bf16 result).  N and K must be multiples of
- * 128 (fp8) / 16 (bf16: K % 32 == 0 for the contraction dimension).
+ * 128 (fp8) / 16 (bf16); in bf16 the contraction dimension of fwd (K) and of
+ * dgrad (N) must also be a multiple of 64 (one 128-byte operand row per stage);
+ * wgrad contracts over the expert's rows, any count.  Sizes outside these limits
+ * return MOE_ERR_UNSUPPORTED and touch nothing.  wgrad with dt = MOE_FP8_E4M3 is
+ * not built and returns MOE_ERR_UNSUPPORTED.
  *
  * fwd:   C[r,n] = sum_k A[r,k] * B[e(r),n,k]                    A [Rcap,K], C [Rcap,N]
  *        epi = MOE_EPI_SWIGLU (N = 2f): C holds the pre-activation Z = [gate | up]
