@@ -123,11 +123,24 @@ __global__ __launch_bounds__(MOVE_THREADS) void permute_rows_kernel(
         for (int s = threadIdx.x; s < k; s += MOVE_THREADS) rows[s] = row_of[(int64_t)b * k + s];
         __syncthreads();
         const u32x4_t* src = X + (int64_t)b * vec_per_row;
-        for (int c = threadIdx.x; c < vec_per_row; c += MOVE_THREADS) {
-            u32x4_t v = src[c];
+        // four 16-byte pieces of the source row per thread are loaded before the first copy is written, so a
+        // row of up to 16 KB is in flight at once instead of one piece per thread
+        for (int c0 = threadIdx.x; c0 < vec_per_row; c0 += 4 * MOVE_THREADS) {
+            u32x4_t v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * MOVE_THREADS;
+                if (c < vec_per_row) v[u] = src[c];
+            }
             for (int s = 0; s < k; ++s) {
-                int r = rows[s];
-                if (r >= 0) __builtin_nontemporal_store(v, &Xp[(int64_t)r * vec_per_row + c]);
+                const int r = rows[s];
+                if (r < 0) continue;
+                u32x4_t* dst = Xp + (int64_t)r * vec_per_row;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u * MOVE_THREADS;
+                    if (c < vec_per_row) __builtin_nontemporal_store(v[u], &dst[c]);
+                }
             }
         }
     } else {
@@ -176,6 +189,16 @@ __global__ __launch_bounds__(MOVE_THREADS) void combine_kernel(
         float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if (residual) acc_vec<F32>(a, residual[(int64_t)t * vec_per_row + c], 1.0f);
         int s = 0;
+        for (; s + 8 <= k; s += 8) {  // eight independent row reads in flight
+            u32x4_t v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = rows[s + j];
+                v[j] = r >= 0 ? __builtin_nontemporal_load(&O[(int64_t)r * vec_per_row + c]) : mk4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc_vec<F32>(a, v[j], wts[s + j]);
+        }
         for (; s + 4 <= k; s += 4) {  // four independent row reads in flight
             int r0 = rows[s], r1 = rows[s + 1], r2 = rows[s + 2], r3 = rows[s + 3];
             u32x4_t z = mk4(0, 0, 0, 0);
@@ -247,21 +270,42 @@ __global__ __launch_bounds__(MOVE_THREADS) void combine_bwd_kernel(
     }
     __syncthreads();
     const bool want_dot = dprob != nullptr && O != nullptr;
-    for (int s = 0; s < k; ++s) {
-        const int r = rows[s];
-        float acc = 0.f;
-        if (r >= 0) {
-            const float w = wts[s];
-            for (int c = threadIdx.x; c < vec_per_row; c += MOVE_THREADS) {
-                u32x4_t g = dY[(int64_t)t * vec_per_row + c];
-                if (want_dot) acc += dot_vec<F32>(g, __builtin_nontemporal_load(&O[(int64_t)r * vec_per_row + c]));
-                __builtin_nontemporal_store(scale_vec<F32>(g, w), &dO[(int64_t)r * vec_per_row + c]);
+    // slots in chunks of 8: per 16-byte piece of dY[t] the 8 expert rows are read together (9 loads in flight per
+    // thread) and the 8 scaled copies written; a slot's partial dot product stays in one register, summed over
+    // the pieces in increasing order
+    for (int s0 = 0; s0 < k; s0 += 8) {
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        for (int c = threadIdx.x; c < vec_per_row; c += MOVE_THREADS) {
+            const u32x4_t g = dY[(int64_t)t * vec_per_row + c];
+            u32x4_t o[8];
+            if (want_dot) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int r = s0 + j < k ? rows[s0 + j] : -1;
+                    if (r >= 0) o[j] = __builtin_nontemporal_load(&O[(int64_t)r * vec_per_row + c]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = s0 + j < k ? rows[s0 + j] : -1;
+                if (r >= 0) {
+                    if (want_dot) acc[j] += dot_vec<F32>(g, o[j]);
+                    __builtin_nontemporal_store(scale_vec<F32>(g, wts[s0 + j]), &dO[(int64_t)r * vec_per_row + c]);
+                }
             }
         }
         if (dprob) {
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-            if (lane == 0) part[s][wave] = acc;
+            for (int j = 0; j < 8; ++j) {
+                if (s0 + j < k) {
+                    float a = acc[j];
+#pragma unroll
+                    for (int o2 = 32; o2 > 0; o2 >>= 1) a += __shfl_xor(a, o2);
+                    if (lane == 0) part[s0 + j][wave] = a;
+                }
+            }
         }
     }
     if (dprob) {
