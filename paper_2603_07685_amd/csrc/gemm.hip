@@ -13,37 +13,36 @@
 // 128 fp8 elements): every global request of the DMA is then a whole 128-byte cache line, which
 // the L1/L2 path serves at about twice the rate of half-line requests (measured: 20 vs 10 TB/s on
 // a GEMM-like sharing pattern).  Each stage's two 32 KB operand tiles are fetched by direct
-// global->LDS loads (16 B per lane) into one of two LDS stages.  Every stage is its own LDS object
-// so that the compiler can see that the DMA writes of the next stage do not alias the operand
-// reads of the current one.
+// global->LDS loads (16 B per lane) into one of two stage buffers.  The DMA is issued through
+// inline asm and synchronised by the kernel's own waits (see dma16 below).
 //
 // LDS layouts.  An operand whose contraction index is contiguous in memory ("k-major", tile
-// [256 rows][64 B]) is read with ds_read_b128; one whose contraction index is the memory row
-// ("c-major", tile [32 or 64 rows][256 columns]: the weight in dgrad, both operands in wgrad) is
+// [256 rows][128 B]) is read with ds_read_b128; one whose contraction index is the memory row
+// ("c-major", tile [64 or 128 rows][256 columns]: the weight in dgrad, both operands in wgrad) is
 // read with the transposing ds_read_b64_tr_b16 / _b8, so no transposed copy of weights or
 // activations is ever made.  The 16-byte slots of every tile are XOR-swizzled with the row so the
 // operand reads are free of bank conflicts; the swizzle is applied on the global side of the DMA
 // (each lane chooses which 16 bytes it fetches; the LDS side of a DMA is always lane-linear).
 //
 // Schedule ("ping-pong").  A stage is consumed in two halves.  The two waves that share a SIMD
-// (wave w and w+4) run one phase apart: while one issues the MFMAs of a half-stage with all
-// operands already in registers, the other fetches its next operands from LDS; they swap at
-// fence-free workgroup barriers.  The DMA instructions that refill the other buffer are slipped in
-// between the MFMAs, so memory requests are spread over time instead of bursting after a barrier.
+// (wave w and w+4) belong to two groups that run one phase apart: while one issues the MFMAs of a
+// half-stage with all operands already in registers, the other fetches its next operands from
+// LDS; they swap at fence-free workgroup barriers.  Each group has its own copy of the stage loop.
 //   per stage s:  A(s,0) | B(s,0) | A(s,1) | B(s,1)    A: LDS -> registers,  B: MFMAs,  '|' = barrier
 //   group 1 (waves 4-7) takes one extra barrier up front, group 0 one at the end; in time:
-//     group 0:  A(s,0)   B(s,0)*  A(s,1)   B(s,1)   A(s+1,0) ...
-//     group 1:  B(s-1,1)* A(s,0)  B(s,0)   A(s,1)   B(s,1)*  ...        (* = issues DMA of stage s+1 / s+2)
+//     group 0:  A(s,0)*   B(s,0)   A(s,1)   B(s,1)   A(s+1,0)* ...
+//     group 1:  B(s-1,1)* A(s,0)   B(s,0)   A(s,1)   B(s,1)*   ...      (* = issues its half of stage s+1)
 // Buffer (s+1)%2 was last read in A(s-1,1); group 1 finishes that phase one barrier before group 0
-// enters A(s,0), so group 0 refills it during B(s,0) and group 1 during its B(s-1,1).  Each wave waits
-// for its own loads of stage s+1 before the barrier that precedes group 0's A(s+1,0): group 0 at the end
-// of B(s,1), group 1 at the end of A(s,1).
+// enters A(s,0), so group 0 refills it at the start of A(s,0) and group 1, in the same slot, between
+// the MFMAs of its B(s-1,1).  Each wave waits for its own loads of stage s+1 before the barrier that
+// precedes group 0's A(s+1,0): group 0 at the end of B(s,1), group 1 at the end of A(s,1).
+// The first stage of a tile is issued before the epilogue of the tile before it.
 //
 // MFMAs are issued as (Q fragment, P fragment): a lane's 16 accumulators of a block are one
-// output row and 4 groups of 4 consecutive columns (8-byte stores), and the wave's two column
-// sub-tiles are 128 columns apart, i.e. the gate and up columns of the same features when the
-// SwiGLU epilogue is on: the activation (forward) and its derivative (fc2 dgrad) are applied to
-// the fp32 accumulators in registers.
+// output row and 4 groups of 4 consecutive columns, and the wave's two column sub-tiles are 128
+// columns apart, i.e. the gate and up columns of the same features when the SwiGLU epilogue is
+// on.  The epilogue stages the fp32 accumulators through LDS and writes whole tile rows; the
+// activation (forward) and its derivative (fc2 dgrad) are applied to the fp32 values there.
 //
 // fp8: operands are E4M3 codes; a half-stage is one v_mfma_scale_f32_32x32x64_f8f6f4 per block with unit
 // hardware scales.  The fp32 block scales (1x128 per activation row, 128x128 per weight block) are
@@ -51,6 +50,7 @@
 // s = a_scale[row, kb] * b_scale[block], so the accumulator is kept in units of the current
 // factor: at every 128-wide contraction block (= stage) it is multiplied by s_prev / s_new before the raw
 // products are added, and by the last factor in the epilogue.  No second set of accumulators.
+// The scales of a block reach LDS with the operands of its stage.
 #include "common.h"
 
 #define GG_BM 256
