@@ -47,29 +47,46 @@ __global__ __launch_bounds__(64) void permute_hist_kernel(const int32_t* __restr
 // ---------------------------------------------------------------------------
 // 2. scans: chunk bases per expert, counts, padded offsets
 // ---------------------------------------------------------------------------
+#define SCAN_LDS_INTS 12288  // chunk histograms staged per pass (48 KB)
 __global__ __launch_bounds__(1024) void permute_scan_kernel(int32_t* __restrict__ chunk_hist, int nchunks, int E,
                                                             int align, int32_t* __restrict__ counts,
                                                             int32_t* __restrict__ offsets) {
+    // One workgroup.  The [nchunks][E] histogram table is brought into LDS with coalesced loads, a block of
+    // chunks at a time; thread e then runs the exclusive scan of expert e down the block in LDS (the serial
+    // chain is over LDS latency, not over dependent global loads) and the block is written back coalesced.
+    __shared__ int32_t tab[SCAN_LDS_INTS];
     __shared__ int32_t tot[1024];
-    const int e = threadIdx.x;
-    if (e < E) {
-        int32_t run = 0;
-        for (int c = 0; c < nchunks; ++c) {
-            int32_t v = chunk_hist[(int64_t)c * E + e];
-            chunk_hist[(int64_t)c * E + e] = run;
-            run += v;
+    const int tid = threadIdx.x;
+    const int per_pass = SCAN_LDS_INTS / E;  // chunks per pass (E <= 1024 is checked by the caller)
+    int32_t run = 0;
+    for (int c0 = 0; c0 < nchunks; c0 += per_pass) {
+        const int nc = min(per_pass, nchunks - c0);
+        int32_t* g = chunk_hist + (int64_t)c0 * E;
+        for (int i = tid; i < nc * E; i += 1024) tab[i] = g[i];
+        __syncthreads();
+        if (tid < E) {
+            for (int c = 0; c < nc; ++c) {
+                const int32_t v = tab[c * E + tid];
+                tab[c * E + tid] = run;
+                run += v;
+            }
         }
-        tot[e] = run;
-        if (counts) counts[e] = run;
+        __syncthreads();
+        for (int i = tid; i < nc * E; i += 1024) g[i] = tab[i];
+        __syncthreads();
+    }
+    if (tid < E) {
+        tot[tid] = run;
+        if (counts) counts[tid] = run;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int64_t run = 0;
+    if (tid == 0) {
+        int64_t r = 0;
         for (int i = 0; i < E; ++i) {
-            offsets[i] = (int32_t)run;
-            run += ((int64_t)tot[i] + align - 1) / align * align;
+            offsets[i] = (int32_t)r;
+            r += ((int64_t)tot[i] + align - 1) / align * align;
         }
-        offsets[E] = (int32_t)run;
+        offsets[E] = (int32_t)r;
     }
 }
 
