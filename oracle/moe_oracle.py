@@ -293,3 +293,59 @@ def layer_backward(fw, X, prob, W1, W2, dY, Ws1=None, Ws2=None, prec="f64"):
         out.dX_shared = grouped_gemm_nn(dZs, Ws1[None], off1, prec=prec)
         out.dZs = dZs
     return out
+
+
+# ----------------------------------------------------------------------------
+# the same layer with the routing weight absorbed into the activation (Sec. 4.2.1, eq. (2))
+# ----------------------------------------------------------------------------
+def gather_row_prob(prob, src_of):
+    """row_prob[r] = prob[t,s] of the slot that row r holds; 0 for padding rows."""
+    flat = np.asarray(prob, np.float64).reshape(-1)
+    src = np.asarray(src_of)
+    return np.where(src >= 0, flat[np.maximum(src, 0)], 0.0)
+
+
+def layer_forward_eq2(X, idx, prob, W1, W2, E, align=1, Ws1=None, Ws2=None, prec="f64"):
+    """y = sum_i W2_i (p_i * phi(W1_i x)): weights applied before fc2, plain-sum combine."""
+    m = permute_maps(idx, E, align)
+    R = m.Rtot
+    Xp = permute_rows(X, m.src_of[:R], m.k, prec)
+    Z = grouped_gemm_nt(Xp, W1, m.offsets, prec=prec)
+    row_p = gather_row_prob(prob, m.src_of[:R])
+    A = swiglu(Z, prec) * row_p[:, None]
+    O = grouped_gemm_nt(A, W2, m.offsets, prec=prec)
+    S = Zs = As = None
+    if Ws1 is not None:
+        off1 = np.array([0, X.shape[0]], np.int32)
+        Zs = grouped_gemm_nt(X, Ws1[None], off1, prec=prec)
+        As = swiglu(Zs, prec)
+        S = grouped_gemm_nt(As, Ws2[None], off1, prec=prec)
+    Y = combine(O, m.row_of, None, S, prec)
+    return SimpleNamespace(maps=m, R=R, Xp=Xp, Z=Z, A=A, O=O, S=S, Zs=Zs, As=As, Y=Y, row_prob=row_p)
+
+
+def layer_backward_eq2(fw, X, prob, W1, W2, dY, Ws1=None, Ws2=None, prec="f64"):
+    """Backward of L = <dY, Y> for eq. (2): dL/dp comes from the saved pre-activations, not from O."""
+    m, R = fw.maps, fw.R
+    dO = permute_rows(dY, m.src_of[:R], m.k, prec)              # plain copies of dY, zero rows for padding
+    dW2 = grouped_gemm_tn(dO, fw.A, m.offsets, prec=prec)       # A already carries the weight
+    dA = grouped_gemm_nn(dO, W2, m.offsets, prec=prec)          # gradient w.r.t. p * phi(z)
+    act = swiglu(fw.Z, prec)                                    # phi(z), recomputed
+    dprob_row = (dA * act).sum(axis=1)
+    dZ = swiglu_bwd(dA, fw.Z, prec) * fw.row_prob[:, None]
+    dW1 = grouped_gemm_tn(dZ, fw.Xp, m.offsets, prec=prec)
+    dXp = grouped_gemm_nn(dZ, W1, m.offsets, prec=prec)
+    dX = combine(dXp, m.row_of, None, None, prec)
+    row_of = np.asarray(m.row_of)
+    dprob = np.where(row_of >= 0, dprob_row[np.maximum(row_of, 0)], 0.0)
+    out = SimpleNamespace(dO=dO, dprob=dprob, dprob_row=dprob_row, dW2=dW2, dA=dA, dZ=dZ, dW1=dW1, dXp=dXp, dX=dX,
+                          dWs1=None, dWs2=None, dX_shared=None)
+    if Ws1 is not None:
+        off1 = np.array([0, X.shape[0]], np.int32)
+        out.dWs2 = grouped_gemm_tn(dY, fw.As, off1, prec=prec)[0]
+        dAs = grouped_gemm_nn(dY, Ws2[None], off1, prec=prec)
+        dZs = swiglu_bwd(dAs, fw.Zs, prec)
+        out.dWs1 = grouped_gemm_tn(dZs, X, off1, prec=prec)[0]
+        out.dX_shared = grouped_gemm_nn(dZs, Ws1[None], off1, prec=prec)
+        out.dZs = dZs
+    return out

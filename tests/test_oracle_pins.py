@@ -301,6 +301,40 @@ def test_backward_finite_differences(oracle):
             assert abs(fd - gr[pos]) <= 1e-6 * max(1.0, abs(fd)), (ai, pos, fd, gr[pos])
 
 
+def test_eq2_layer_matches_eq1_and_finite_differences(oracle):
+    """Memory-efficient permutation (Sec. 4.2.1): eq. (2) is an algebraic rearrangement of eq. (1), so its
+    forward output and every gradient must equal eq. (1)'s (themselves pinned above), and its own loss must
+    reproduce its dprob by central differences (dprob is the one gradient computed by a different formula)."""
+    X, logits, W1, W2, Ws1, Ws2, dY = _tiny_layer(21, T=12, h=6, f=5, E=4, k=2)
+    E = W1.shape[0]
+    idx, prob, _ = oracle.route_topk(logits, 2, 1, True)
+    idx[idx == 3] = 1
+    idx[:, 1] = np.where(idx[:, 1] == idx[:, 0], (idx[:, 0] + 1) % 3, idx[:, 1])
+    for align in (1, 4):
+        f1 = oracle.layer_forward(X, idx, prob, W1, W2, E, align, Ws1, Ws2)
+        b1 = oracle.layer_backward(f1, X, prob, W1, W2, dY, Ws1, Ws2)
+        f2 = oracle.layer_forward_eq2(X, idx, prob, W1, W2, E, align, Ws1, Ws2)
+        b2 = oracle.layer_backward_eq2(f2, X, prob, W1, W2, dY, Ws1, Ws2)
+        np.testing.assert_allclose(f2.Y, f1.Y, rtol=1e-12, atol=1e-14)
+        for name in ("dX", "dprob", "dW1", "dW2", "dWs1", "dWs2", "dX_shared"):
+            np.testing.assert_allclose(getattr(b2, name), getattr(b1, name), rtol=1e-11, atol=1e-14, err_msg=name)
+        assert np.all(b2.dW1[3] == 0) and np.all(b2.dW2[3] == 0)
+        # padding rows: zero weight, zero gradient rows
+        pad = f2.maps.src_of[:f2.R] < 0
+        assert np.all(f2.row_prob[pad] == 0) and np.all(b2.dZ[pad] == 0) and np.all(f2.A[pad] == 0)
+    g = _rng(22)
+    eps = 1e-6
+    for _ in range(20):
+        pos = tuple(g.integers(s) for s in prob.shape)
+        pp, pm = prob.copy(), prob.copy()
+        pp[pos] += eps
+        pm[pos] -= eps
+        lp = float((oracle.layer_forward_eq2(X, idx, pp, W1, W2, E, 4, Ws1, Ws2).Y * dY).sum())
+        lm = float((oracle.layer_forward_eq2(X, idx, pm, W1, W2, E, 4, Ws1, Ws2).Y * dY).sum())
+        fd = (lp - lm) / (2 * eps)
+        assert abs(fd - b2.dprob[pos]) <= 1e-6 * max(1.0, abs(fd)), (pos, fd, b2.dprob[pos])
+
+
 def test_swiglu_bwd_and_combine_bwd_closed_forms(oracle):
     g = _rng(13)
     # d/dg silu(g) at g = 0 is 1/2; dZ_up = silu(g)
