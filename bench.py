@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--variant", default=None, help="load pattern override: uniform | zeros | hot | cv | zipf")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad-f32", action="store_true", help="fp32 weight gradients (default bf16)")
+    ap.add_argument("--eq2", action="store_true",
+                    help="memory-efficient permutation: routing weights applied in the fc1 epilogue, plain-sum combine")
     return ap.parse_args()
 
 
@@ -53,6 +55,12 @@ def describe_call(name, args, st):
     cfg = st.cfg
     T, k = cfg.T, cfg.k
     R = T * k  # routed rows (unpadded): the algorithmic row count of the grouped calls
+    if name == "moe_gather_row_prob":
+        return "gather_row_prob", None, args[3] * 12
+    if name == "moe_scatter_row_dprob":
+        return "scatter_row_dprob", None, T * k * (8 + 4 * args[2])
+    if name.endswith("_weighted"):
+        name = name[:-len("_weighted")]
     if name in ("moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad"):
         E, N, K, dt = args[4], args[5], args[6], args[8]
         rows = R if E > 1 else T
@@ -86,7 +94,7 @@ def describe_call(name, args, st):
         return ("combine" if args[4] is not None else "unpermute_sum_dx"), None, (R + T) * h * 2 + T * k * 8 + (T * h * 2 if res else 0)
     if name == "moe_unpermute_combine_bwd":
         h = args[9]
-        return "combine_bwd", None, (T + 2 * R) * h * 2
+        return "combine_bwd", None, (T + (2 if args[2] is not None else 1) * R) * h * 2
     if name == "moe_fp8_quantize":
         block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
         rows_alg = R if live is not None else rows          # grouped row tensors: only the routed rows count
@@ -96,7 +104,9 @@ def describe_call(name, args, st):
 
 
 HOOKED = ["moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
-          "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize"]
+          "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
+          "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob",
+          "moe_scatter_row_dprob"]
 
 
 def timed_step_with_events(st, torch, sync=True):
@@ -192,7 +202,7 @@ def main():
     cfg = wl.CONFIGS[args.workload]
     small = cfg.T * cfg.h <= 4 * 1024 * 1024
     hin = L.host_inputs(cfg) if small else None
-    st = L.LayerState(cfg, hin, variant=args.variant, wgrad_f32=args.wgrad_f32)
+    st = L.LayerState(cfg, hin, variant=args.variant, wgrad_f32=args.wgrad_f32, eq2=args.eq2)
 
     # one plain device copy of known size, outside the timed region: the reference dispatch the HBM byte
     # counters (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by
@@ -255,7 +265,8 @@ def main():
         "dtype": "fp8_e4m3 (fwd/dgrad GEMMs) + bf16" if cfg.fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} h={cfg.h} f={cfg.f} E_local={cfg.E} top{cfg.k} "
                                f"shared_f={cfg.shared_f} load={args.variant or cfg.load} "
-                               f"wgrad_out={'f32' if args.wgrad_f32 else 'bf16'}",
+                               f"wgrad_out={'f32' if args.wgrad_f32 else 'bf16'}"
+                               f"{' weights-in-fc1 (eq. 2)' if args.eq2 else ''}",
                    "model_tflop_per_step": round(flops / 1e12, 3)},
         "pct_bf16_mfma_peak": round(100.0 * flops / ms / 1e9 / BF16_PEAK_TFLOPS, 2),
         "gemm_only": {"tflops": round(gemm_fl / gemm_ms / 1e9, 1),

@@ -183,6 +183,45 @@ moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, con
                                   moe_dtype dt, const float* a_scale, const float* dc_scale,
                                   int accumulate, moe_dtype out_dt, void* dB);
 
+/*
+ * Memory-efficient permutation (Sec. 4.2.1, eq. (2)): the routing weight multiplies the
+ * activation before fc2, the combine is then a plain sum (moe_unpermute_combine with
+ * prob = NULL), and dL/dp needs only the saved pre-activations, not the expert outputs.
+ *
+ * fwd_weighted:   as moe_grouped_gemm_fwd; with epi = MOE_EPI_SWIGLU and row_prob != NULL
+ *                 (fp32 [Rcap], one weight per permuted row, see moe_gather_row_prob)
+ *                 C_act[r,:] = row_prob[r] * silu(gate) * up.  C (the pre-activation) is
+ *                 not weighted.  row_prob = NULL is exactly moe_grouped_gemm_fwd.
+ * dgrad_weighted: as moe_grouped_gemm_dgrad with Z_saved; the output is
+ *                 dZ[r,:] = row_prob[r] * SwiGLU-backward(dA[r,:], Z_saved[r,:]) and, if
+ *                 dprob_part != NULL (fp32 [Rcap, ceil(K/256)]), dprob_part[r,j] =
+ *                 sum over the 256 columns c of column tile j of dA[r,c] * silu(gate)*up:
+ *                 the partial sums of dL/d row_prob[r], in fp32, written once each (no
+ *                 atomics; moe_scatter_row_dprob adds them in a fixed order).  Rows of
+ *                 padding get a partial of 0; rows >= offsets[E] are not written.
+ */
+moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, const void* A, const void* B,
+                                         const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                         moe_dtype dt, moe_epilogue epi,
+                                         const float* a_scale, const float* b_scale,
+                                         const float* row_prob, void* C, void* C_act);
+moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream, const void* dC, const void* B,
+                                           const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                           moe_dtype dt, const void* Z_saved,
+                                           const float* dc_scale, const float* b_scale,
+                                           const float* row_prob, void* dA, float* dprob_part);
+
+/*
+ * Row-indexed view of the routing weights for eq. (2) and its inverse:
+ *   gather:  row_prob[r] = prob[src_of[r]] for r < Rcap, 0 where src_of[r] < 0 (padding).
+ *   scatter: dprob[t,s] = sum_j dprob_part[row_of[t,s], j], j = 0..parts-1 in increasing
+ *            order; 0 for skipped slots (row_of < 0).
+ */
+moe_status moe_gather_row_prob(moe_ctx* ctx, void* stream, const float* prob, const int32_t* src_of,
+                               int64_t Rcap, float* row_prob);
+moe_status moe_scatter_row_dprob(moe_ctx* ctx, void* stream, const float* dprob_part, int parts,
+                                 const int32_t* row_of, int T, int k, float* dprob);
+
 /* ------------------------------------------------------------------------- */
 /* Stage 4: Combine = unpermute + weighted sum (Sec. 4.3.3 "Unpermute"; eq. (1))*/
 /* ------------------------------------------------------------------------- */

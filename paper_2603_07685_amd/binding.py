@@ -25,6 +25,7 @@ EXPORTS = [
     "moe_workspace_bytes", "moe_ctx_create", "moe_ctx_destroy", "moe_last_error", "moe_ctx_poll_error",
     "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
+    "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -57,6 +58,10 @@ def lib() -> C.CDLL:
         L.moe_unpermute_combine.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _vp]
         L.moe_unpermute_combine_bwd.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i64, _vp, _vp]
         L.moe_fp8_quantize.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _vp]
+        L.moe_grouped_gemm_fwd_weighted.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_dgrad_weighted.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
+        L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
         for name in EXPORTS:
             if name not in ("moe_workspace_bytes", "moe_last_error"):
                 getattr(L, name).restype = _i
@@ -132,6 +137,31 @@ def moe_grouped_gemm_dgrad(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_saved, dc_s
     ctx.check(lib().moe_grouped_gemm_dgrad(ctx.h, _stream(), _ptr(dC), _ptr(B), _ptr(offsets), E, N, K, Rcap, dt,
                                            _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(dA)),
               "moe_grouped_gemm_dgrad")
+
+
+def moe_grouped_gemm_fwd_weighted(ctx, A, B, offsets, E, N, K, Rcap, dt, epi, a_scale, b_scale, row_prob, Cout, C_act):
+    ctx.check(lib().moe_grouped_gemm_fwd_weighted(ctx.h, _stream(), _ptr(A), _ptr(B), _ptr(offsets), E, N, K, Rcap, dt,
+                                                  epi, _ptr(a_scale), _ptr(b_scale), _ptr(row_prob), _ptr(Cout),
+                                                  _ptr(C_act)),
+              "moe_grouped_gemm_fwd_weighted")
+
+
+def moe_grouped_gemm_dgrad_weighted(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_saved, dc_scale, b_scale, row_prob, dA,
+                                    dprob_part):
+    ctx.check(lib().moe_grouped_gemm_dgrad_weighted(ctx.h, _stream(), _ptr(dC), _ptr(B), _ptr(offsets), E, N, K, Rcap,
+                                                    dt, _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(row_prob),
+                                                    _ptr(dA), _ptr(dprob_part)),
+              "moe_grouped_gemm_dgrad_weighted")
+
+
+def moe_gather_row_prob(ctx, prob, src_of, Rcap, row_prob):
+    ctx.check(lib().moe_gather_row_prob(ctx.h, _stream(), _ptr(prob), _ptr(src_of), Rcap, _ptr(row_prob)),
+              "moe_gather_row_prob")
+
+
+def moe_scatter_row_dprob(ctx, dprob_part, parts, row_of, T, k, dprob):
+    ctx.check(lib().moe_scatter_row_dprob(ctx.h, _stream(), _ptr(dprob_part), parts, _ptr(row_of), T, k, _ptr(dprob)),
+              "moe_scatter_row_dprob")
 
 
 def moe_grouped_gemm_wgrad(ctx, A, dC, offsets, E, N, K, Rcap, dt, a_scale, dc_scale, accumulate, out_dt, dB):

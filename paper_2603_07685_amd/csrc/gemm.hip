@@ -184,6 +184,9 @@ struct gg_args {
     const char* zeros;     // >= 16 zero bytes (feeds the wgrad contraction tail)
     int* dev_err;
     int accumulate;        // wgrad: out += result
+    const float* row_prob; // eq. (2): routing weight of each row (fwd SWIGLU: scales the activation;
+                           //   dgrad SWIGLU_BWD: scales dZ); NULL = 1
+    float* dprob_part;     // eq. (2), dgrad SWIGLU_BWD: [Rcap, ceil(K/256)] partial <dA, act(Z)> per row and column tile
 };
 
 // MODE: GG_FWD / GG_DGRAD / GG_WGRAD.  EPI: see enum.  OUT_F32: fp32 output (wgrad only).
@@ -697,20 +700,28 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     }
                 } else if (EPI == GG_EPI_SWIGLU_BWD) {
                     // dZ[r, c] = dA * up * s (1 + g (1 - s)),  dZ[r, K + c] = dA * g * s,  s = sigmoid(g)
+                    float dot = 0.f;
                     if (c < K) {
                         bf16_t* dZ = (bf16_t*)a.out;
                         const int64_t zr = (int64_t)r * 2 * K;
                         float gt[4], up[4], dg[4], du[4];
                         ld4_bf16(a.Zsaved + zr + c, gt);
                         ld4_bf16(a.Zsaved + zr + K + c, up);
+                        const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
                             const float sg = sigmoid_f(gt[x]);
-                            dg[x] = v[x] * up[x] * sg * (1.0f + gt[x] * (1.0f - sg));
-                            du[x] = v[x] * gt[x] * sg;
+                            dg[x] = pr * v[x] * up[x] * sg * (1.0f + gt[x] * (1.0f - sg));
+                            du[x] = pr * v[x] * gt[x] * sg;
+                            dot += v[x] * (gt[x] * sg * up[x]);  // <dA, silu(gate) * up>: the row's share of dL/dp
                         }
                         st4_bf16(dZ + zr + c, dg);
                         st4_bf16(dZ + zr + K + c, du);
+                    }
+                    if (a.dprob_part) {  // the wave holds the 256 columns of this row and tile: one partial sum
+#pragma unroll
+                        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+                        if (lane == 0) a.dprob_part[(int64_t)r * tiles_j + ep_j0 / GG_BN] = dot;
                     }
                 } else if (c < J) {
                     const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r) * K : (int64_t)r * J;
@@ -743,8 +754,9 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                         const f32x4_t gt = *(const f32x4_t*)(stg + rr * STG_PITCH + fl);
                         const f32x4_t up = *(const f32x4_t*)(stg + rr * STG_PITCH + 128 + fl);
                         float act[4];
+                        const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
 #pragma unroll
-                        for (int x = 0; x < 4; ++x) act[x] = gt[x] * sigmoid_f(gt[x]) * up[x];
+                        for (int x = 0; x < 4; ++x) act[x] = pr * (gt[x] * sigmoid_f(gt[x]) * up[x]);
                         st4_bf16(a.out_act + (int64_t)r * half_cols + ep_j0 + fl, act);
                     }
                 }
@@ -797,7 +809,18 @@ extern "C" moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const voi
                                            moe_dtype dt, moe_epilogue epi,
                                            const float* a_scale, const float* b_scale,
                                            void* C, void* C_act) {
+    return moe_grouped_gemm_fwd_weighted(ctx, stream, A, B, offsets, E, N, K, Rcap, dt, epi, a_scale, b_scale, nullptr,
+                                         C, C_act);
+}
+
+extern "C" moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, const void* A, const void* B,
+                                                    const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                                    moe_dtype dt, moe_epilogue epi,
+                                                    const float* a_scale, const float* b_scale,
+                                                    const float* row_prob, void* C, void* C_act) {
     if (!ctx) return MOE_ERR_ARG;
+    if (row_prob && epi != MOE_EPI_SWIGLU)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_weighted: row weights go with the SwiGLU epilogue");
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_fwd", A, B, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
     if (epi == MOE_EPI_SWIGLU) {
@@ -816,6 +839,7 @@ extern "C" moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const voi
     a.out_act = (bf16_t*)C_act;
     a.p_scale = a_scale;
     a.q_scale = b_scale;
+    a.row_prob = row_prob;
     if (epi == MOE_EPI_SWIGLU) {
         if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, true);
         else GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, false);
@@ -831,7 +855,18 @@ extern "C" moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const v
                                              const int32_t* offsets, int E, int N, int K, int64_t Rcap,
                                              moe_dtype dt, const void* Z_saved,
                                              const float* dc_scale, const float* b_scale, void* dA) {
+    return moe_grouped_gemm_dgrad_weighted(ctx, stream, dC, B, offsets, E, N, K, Rcap, dt, Z_saved, dc_scale, b_scale,
+                                           nullptr, dA, nullptr);
+}
+
+extern "C" moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream, const void* dC, const void* B,
+                                                      const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                                      moe_dtype dt, const void* Z_saved,
+                                                      const float* dc_scale, const float* b_scale,
+                                                      const float* row_prob, void* dA, float* dprob_part) {
     if (!ctx) return MOE_ERR_ARG;
+    if ((row_prob || dprob_part) && !Z_saved)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_weighted: row weights / dprob_part need Z_saved");
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_dgrad", dC, B, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
     if (!dA) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: dA is NULL");
@@ -842,6 +877,8 @@ extern "C" moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const v
     a.Zsaved = (const bf16_t*)Z_saved;
     a.p_scale = dc_scale;
     a.q_scale = b_scale;
+    a.row_prob = row_prob;
+    a.dprob_part = dprob_part;
     if (Z_saved) {
         if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, true);
         else GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, false);

@@ -443,3 +443,52 @@ extern "C" moe_status moe_unpermute_combine_bwd(moe_ctx* ctx, void* stream, cons
     MOE_LAUNCH_CHECK(ctx, "combine_bwd kernels");
     return MOE_OK;
 }
+
+// ---------------------------------------------------------------------------
+// eq. (2) helpers: routing weights per permuted row, and the way back for their gradients
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_row_prob_kernel(const float* __restrict__ prob,
+                                                              const int32_t* __restrict__ src_of, int64_t Rcap,
+                                                              float* __restrict__ row_prob) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= Rcap) return;
+    const int32_t j = src_of[r];
+    row_prob[r] = j >= 0 ? prob[j] : 0.0f;
+}
+
+__global__ __launch_bounds__(256) void scatter_row_dprob_kernel(const float* __restrict__ part, int parts,
+                                                                const int32_t* __restrict__ row_of, int64_t pairs,
+                                                                float* __restrict__ dprob) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= pairs) return;
+    const int32_t r = row_of[j];
+    float acc = 0.f;
+    if (r >= 0)
+        for (int q = 0; q < parts; ++q) acc += part[(int64_t)r * parts + q];
+    dprob[j] = acc;
+}
+
+extern "C" moe_status moe_gather_row_prob(moe_ctx* ctx, void* stream, const float* prob, const int32_t* src_of,
+                                          int64_t Rcap, float* row_prob) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!prob || !src_of || !row_prob) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_gather_row_prob: NULL pointer");
+    if (Rcap < 0 || Rcap > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_gather_row_prob: need 0 <= Rcap < 2^31");
+    if (Rcap == 0) return MOE_OK;
+    hipLaunchKernelGGL(gather_row_prob_kernel, dim3((unsigned)ceil_div64(Rcap, 256)), dim3(256), 0, (hipStream_t)stream,
+                       prob, src_of, Rcap, row_prob);
+    MOE_LAUNCH_CHECK(ctx, "gather_row_prob_kernel");
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_scatter_row_dprob(moe_ctx* ctx, void* stream, const float* dprob_part, int parts,
+                                            const int32_t* row_of, int T, int k, float* dprob) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!dprob_part || !row_of || !dprob) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_scatter_row_dprob: NULL pointer");
+    if (parts < 1 || T < 0 || k < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_scatter_row_dprob: need parts >= 1, T >= 0, k >= 1");
+    const int64_t pairs = (int64_t)T * k;
+    if (pairs == 0) return MOE_OK;
+    hipLaunchKernelGGL(scatter_row_dprob_kernel, dim3((unsigned)ceil_div64(pairs, 256)), dim3(256), 0, (hipStream_t)stream,
+                       dprob_part, parts, row_of, pairs, dprob);
+    MOE_LAUNCH_CHECK(ctx, "scatter_row_dprob_kernel");
+    return MOE_OK;
+}

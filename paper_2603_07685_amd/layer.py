@@ -41,8 +41,9 @@ class LayerState:
     """Device buffers of one layer + the forward / backward call sequences."""
 
     def __init__(self, cfg: wl.MoEConfig, hin: dict | None = None, shared_f: int | None = None,
-                 variant: str | None = None, wgrad_f32: bool = False):
+                 variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False):
         self.cfg = cfg
+        self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.2.1): weights applied before fc2
         T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
         self.sf = sf = cfg.shared_f if shared_f is None else shared_f
         self.align = cfg.align
@@ -93,6 +94,10 @@ class LayerState:
         self.dX = torch.empty((T, h), dtype=bf, device=dev)
         self.dW1 = torch.empty((E, 2 * f, h), dtype=wdt, device=dev)
         self.dW2 = torch.empty((E, h, f), dtype=wdt, device=dev)
+        if self.eq2:
+            self.row_prob = torch.empty(Rcap, dtype=f32, device=dev)
+            self.dprob_parts = (f + 255) // 256
+            self.dprob_part = torch.empty((Rcap, self.dprob_parts), dtype=f32, device=dev)
         self.fp8 = bool(cfg.fp8)
         if self.fp8:
             u8 = torch.uint8
@@ -152,8 +157,12 @@ class LayerState:
         idx = self.topk_idx if self.forced_idx is None else self.forced_idx
         B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
                       self.row_of, self.src_of, self.offsets, self.counts)
-        B.moe_grouped_gemm_fwd(c, self.Xp, self.W1, self.offsets, E, 2 * f, h, Rcap, B.BF16, B.EPI_SWIGLU,
-                               None, None, self.Z, self.A)
+        row_prob = None
+        if self.eq2:  # eq. (2): A = p * silu(gate) * up, plain-sum combine
+            B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
+            row_prob = self.row_prob
+        B.moe_grouped_gemm_fwd_weighted(c, self.Xp, self.W1, self.offsets, E, 2 * f, h, Rcap, B.BF16, B.EPI_SWIGLU,
+                                        None, None, row_prob, self.Z, self.A)
         B.moe_grouped_gemm_fwd(c, self.A, self.W2, self.offsets, E, h, f, Rcap, B.BF16, B.EPI_NONE,
                                None, None, self.O, None)
         if sf:
@@ -161,18 +170,30 @@ class LayerState:
                                    None, None, self.Zs, self.As)
             B.moe_grouped_gemm_fwd(c, self.As, self.Ws2, self.off_shared, 1, h, sf, T, B.BF16, B.EPI_NONE,
                                    None, None, self.S, None)
-        B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, self.topk_prob, self.S if sf else None,
-                                T, k, h, self.Y)
+        B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, None if self.eq2 else self.topk_prob,
+                                self.S if sf else None, T, k, h, self.Y)
 
     # ---- backward: combine, fc2 (wgrad, dgrad + SwiGLU'), fc1 (wgrad, dgrad), permute ---------
     def _backward_bf16(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         wdt = self.wgrad_dt
-        B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
-                                    T, k, h, Rcap, self.dO, self.dprob)
-        B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt, self.dW2)
-        B.moe_grouped_gemm_dgrad(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, B.BF16, self.Z, None, None, self.dZ)
+        if self.eq2:
+            # dO = plain copies of dY (no weight, O is not read); dprob comes out of the fc2 data gradient
+            B.moe_unpermute_combine_bwd(c, self.dY, None, B.BF16, self.row_of, self.src_of, None,
+                                        T, k, h, Rcap, self.dO, None)
+            B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt,
+                                     self.dW2)
+            B.moe_grouped_gemm_dgrad_weighted(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, B.BF16, self.Z, None,
+                                              None, self.row_prob, self.dZ, self.dprob_part)
+            B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
+        else:
+            B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
+                                        T, k, h, Rcap, self.dO, self.dprob)
+            B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt,
+                                     self.dW2)
+            B.moe_grouped_gemm_dgrad(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, B.BF16, self.Z, None, None,
+                                     self.dZ)
         B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, wdt,
                                  self.dW1)
         B.moe_grouped_gemm_dgrad(c, self.dZ, self.W1, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, None,
@@ -200,8 +221,12 @@ class LayerState:
         self._q_weight(self.W1, self.qW1, self.sW1)
         self._q_weight(self.W2, self.qW2, self.sW2)
         self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows)
-        B.moe_grouped_gemm_fwd(c, self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, B.EPI_SWIGLU,
-                               self.sXp, self.sW1, self.Z, self.A)
+        row_prob = None
+        if self.eq2:
+            B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
+            row_prob = self.row_prob
+        B.moe_grouped_gemm_fwd_weighted(c, self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, B.EPI_SWIGLU,
+                                        self.sXp, self.sW1, row_prob, self.Z, self.A)
         self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows)
         B.moe_grouped_gemm_fwd(c, self.qA, self.qW2, self.offsets, E, h, f, Rcap, F8, B.EPI_NONE,
                                self.sA, self.sW2, self.O, None)
@@ -215,19 +240,28 @@ class LayerState:
             self._q_rows(self.As, self.qAs, self.sAs, T, sf)
             B.moe_grouped_gemm_fwd(c, self.qAs, self.qWs2, o1, 1, h, sf, T, F8, B.EPI_NONE,
                                    self.sAs, self.sWs2, self.S, None)
-        B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, self.topk_prob, self.S if sf else None,
-                                T, k, h, self.Y)
+        B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, None if self.eq2 else self.topk_prob,
+                                self.S if sf else None, T, k, h, self.Y)
 
     def _backward_fp8(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         F8, wdt = B.FP8_E4M3, self.wgrad_dt
-        B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
-                                    T, k, h, Rcap, self.dO, self.dprob)
+        if self.eq2:
+            B.moe_unpermute_combine_bwd(c, self.dY, None, B.BF16, self.row_of, self.src_of, None,
+                                        T, k, h, Rcap, self.dO, None)
+        else:
+            B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
+                                        T, k, h, Rcap, self.dO, self.dprob)
         B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt, self.dW2)
         self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows)
-        B.moe_grouped_gemm_dgrad(c, self.qdO, self.qW2, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO, self.sW2,
-                                 self.dZ)
+        if self.eq2:
+            B.moe_grouped_gemm_dgrad_weighted(c, self.qdO, self.qW2, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
+                                              self.sW2, self.row_prob, self.dZ, self.dprob_part)
+            B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
+        else:
+            B.moe_grouped_gemm_dgrad(c, self.qdO, self.qW2, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
+                                     self.sW2, self.dZ)
         B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, wdt,
                                  self.dW1)
         self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows)

@@ -78,3 +78,44 @@ def test_fp8_layer_every_element(oracle, variant):
     fw = oracle.layer_forward(hin["X"], idx, o_prob, W1, W2, E, 128, hin["Ws1"], hin["Ws2"])
     print("end-to-end Y vs full-precision oracle:", f"{rel_fro(_f64(st.Y), fw.Y):.2e}")
     assert rel_fro(_f64(st.Y), fw.Y) <= 0.1
+
+
+def test_fp8_layer_eq2_per_call(oracle):
+    """C5S in the memory-efficient permutation form (eq. (2)) with the fp8 GEMMs: the calls that differ from the
+    standard form, each against the oracle on the tensors the GPU actually fed it."""
+    from gpu_util import rel_fro, BF16_TOL, FP8_TOL
+    from paper_2603_07685_amd import layer as L
+    from paper_2603_07685_amd import workloads as wl
+    cfg = wl.CONFIGS["C5S"]
+    hin = L.host_inputs(cfg)
+    st = L.LayerState(cfg, hin, eq2=True)
+    st.step()
+    torch.cuda.synchronize()
+    assert st.ctx.poll_error() == 0
+    T, k, E = cfg.T, cfg.k, cfg.E
+    idx = st.forced_idx.cpu().numpy()
+    m = oracle.permute_maps(idx, E, 128, st.Rcap)
+    R, off = m.Rtot, m.offsets
+    prob = st.topk_prob.cpu().numpy().astype(np.float64)
+    row_p = oracle.gather_row_prob(prob, m.src_of[:R])
+    np.testing.assert_array_equal(st.row_prob.cpu().numpy()[:R], row_p.astype(np.float32))
+    Xp = oracle.permute_rows(hin["X"], m.src_of[:R], k)
+    Zref = oracle.grouped_gemm_nt(Xp, hin["W1"], off)
+    e8 = {"Z": rel_fro(_f64(st.Z)[:R], Zref),
+          "A": rel_fro(_f64(st.A)[:R], oracle.swiglu(Zref) * row_p[:, None])}
+    assert np.all(_f64(st.A)[:R][m.src_of[:R] < 0] == 0)                  # padding rows carry weight 0
+    Y = oracle.combine(_f64(st.O)[:R], m.row_of, None, _f64(st.S))
+    e16 = {"Y": rel_fro(_f64(st.Y), Y)}
+    dOref = oracle.permute_rows(hin["dY"], m.src_of[:R], k)
+    assert np.array_equal(_f64(st.dO)[:R], dOref)
+    dA = oracle.grouped_gemm_nn(dOref, hin["W2"], off)
+    Zg = _f64(st.Z)[:R]
+    e8["dZ"] = rel_fro(_f64(st.dZ)[:R], oracle.swiglu_bwd(dA, Zg) * row_p[:, None])
+    dp_row = (dA * oracle.swiglu(Zg)).sum(axis=1)
+    dp = np.where(m.row_of >= 0, dp_row[np.maximum(m.row_of, 0)], 0.0)
+    e8["dprob"] = rel_fro(st.dprob.cpu().numpy(), dp)
+    print("eq2 fp8:", {k_: f"{v:.2e}" for k_, v in e8.items()}, "bf16:", {k_: f"{v:.2e}" for k_, v in e16.items()})
+    for k_, v in e8.items():
+        assert v <= FP8_TOL, (k_, v)
+    for k_, v in e16.items():
+        assert v <= BF16_TOL, (k_, v)

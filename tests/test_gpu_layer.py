@@ -53,3 +53,39 @@ def test_layer_forward_backward_every_element(oracle, name, shared_f):
     print(name, {k: f"{v:.2e}" for k, v in errs.items()})
     for k, v in errs.items():
         assert v <= BF16_TOL, (k, v)
+
+
+@pytest.mark.parametrize("name,shared_f", [("C1", 64), ("MID", 0)])
+def test_layer_eq2_every_element(oracle, name, shared_f):
+    """The memory-efficient permutation variant (Sec. 4.2.1, eq. (2)) of the whole layer, every element:
+    weights applied in the fc1 epilogue, plain-sum combine, dprob from the fused fc2 data gradient."""
+    from gpu_util import host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    from paper_2603_07685_amd import layer as L
+    cfg = wl.CONFIGS[name]
+    hin = L.host_inputs(cfg, shared_f=shared_f)
+    st = L.LayerState(cfg, hin, shared_f=shared_f, eq2=True)
+    st.forward()
+    st.backward()
+    torch.cuda.synchronize()
+    assert st.ctx.poll_error() == 0
+    o_idx, o_prob, _ = oracle.route_topk(hin["logits"], cfg.k, cfg.score, cfg.norm_topk)
+    assert np.array_equal(st.topk_idx.cpu().numpy(), o_idx)
+    fw = oracle.layer_forward_eq2(hin["X"], o_idx, o_prob, hin["W1"], hin["W2"], cfg.E, cfg.align,
+                                  hin.get("Ws1"), hin.get("Ws2"))
+    bw = oracle.layer_backward_eq2(fw, hin["X"], o_prob, hin["W1"], hin["W2"], hin["dY"], hin.get("Ws1"), hin.get("Ws2"))
+    R = fw.R
+    assert np.array_equal(st.row_of.cpu().numpy(), fw.maps.row_of)
+    np.testing.assert_allclose(st.row_prob.cpu().numpy()[:R], fw.row_prob, rtol=2e-6)
+    errs = {
+        "Z": rel_fro(host_f64(st.Z)[:R], fw.Z), "A": rel_fro(host_f64(st.A)[:R], fw.A),
+        "O": rel_fro(host_f64(st.O)[:R], fw.O), "Y": rel_fro(host_f64(st.Y), fw.Y),
+        "dO": rel_fro(host_f64(st.dO)[:R], bw.dO), "dprob": rel_fro(host_f64(st.dprob), bw.dprob),
+        "dW2": rel_fro(host_f64(st.dW2), bw.dW2), "dZ": rel_fro(host_f64(st.dZ)[:R], bw.dZ),
+        "dW1": rel_fro(host_f64(st.dW1), bw.dW1), "dXp": rel_fro(host_f64(st.dXp)[:R], bw.dXp),
+        "dX": rel_fro(host_f64(st.dX), bw.dX + (bw.dX_shared if shared_f else 0.0)),
+    }
+    assert np.array_equal(host_f64(st.dO)[:R], bw.dO)      # plain copies of dY
+    print(name, "eq2", {k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= BF16_TOL, (k, v)

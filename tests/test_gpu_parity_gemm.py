@@ -151,6 +151,75 @@ def test_grouped_gemm_dgrad_swiglu_bwd(B, ctx, oracle, counts, N, f):
     assert rel_fro(host_f64(dZ), dZref) <= BF16_TOL
 
 
+@pytest.mark.parametrize("counts,N,f", [([300, 0, 257, 1, 700], 128, 256), ([130, 90], 64, 128),
+                                         ([513], 320, 384), ([700, 40], 192, 640)])
+def test_weighted_swiglu_forward_and_backward(B, ctx, oracle, counts, N, f):
+    """Memory-efficient permutation (eq. (2)): the row weight multiplies the activation in the fc1 epilogue
+    (the pre-activation stays unweighted); the fused fc2 data gradient scales dZ by it and emits the partial
+    sums of <dA, silu(gate) * up> per row, which moe_scatter_row_dprob adds up per (token, slot)."""
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets(counts)
+    R = int(off[-1])
+    g = np.random.default_rng(R + f)
+    ph = g.uniform(0.05, 1.0, size=R).astype(np.float32)
+    p = dev(ph)
+    # forward: Z = X W1^T, A = p * swiglu(Z)
+    K = N
+    Xh = wl.gaussian_bf16((R, K), 1.0, 51, K)
+    W1h = wl.gaussian_bf16((E, 2 * f, K), 0.1, 52, f)
+    Z = torch.full((R, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    A = torch.full((R, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_fwd_weighted(ctx, dev_bf16(Xh), dev_bf16(W1h), dev(off), E, 2 * f, K, R, B.BF16, B.EPI_SWIGLU,
+                                    None, None, p, Z, A)
+    torch.cuda.synchronize()
+    Zref = oracle.grouped_gemm_nt(Xh, W1h, off)
+    assert rel_fro(host_f64(Z), Zref) <= BF16_TOL                       # not weighted
+    assert rel_fro(host_f64(A), oracle.swiglu(Zref) * ph.astype(np.float64)[:, None]) <= BF16_TOL
+    # backward: dZ = p * swiglu_bwd(dO W2, Z); partials of <dA, swiglu(Z)>
+    dOh = wl.gaussian_bf16((R, N), 1.0, 53, N)
+    W2h = wl.gaussian_bf16((E, N, f), 0.1, 54, f)
+    Zh = wl.gaussian_bf16((R, 2 * f), 1.5, 55, f)
+    parts = (f + 255) // 256
+    dZ = torch.full((R, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    part = torch.full((R, parts), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_grouped_gemm_dgrad_weighted(ctx, dev_bf16(dOh), dev_bf16(W2h), dev(off), E, N, f, R, B.BF16, dev_bf16(Zh),
+                                      None, None, p, dZ, part)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    dAref = oracle.grouped_gemm_nn(dOh, W2h, off)
+    assert rel_fro(host_f64(dZ), oracle.swiglu_bwd(dAref, Zh) * ph.astype(np.float64)[:, None]) <= BF16_TOL
+    dp_ref = (dAref * oracle.swiglu(Zh)).sum(axis=1)
+    got = part.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    # per column tile, then summed
+    tiles = (dAref * oracle.swiglu(Zh)).reshape(R, -1)
+    for j in range(parts):
+        ref_j = tiles[:, 256 * j:256 * (j + 1)].sum(axis=1)
+        assert rel_fro(got[:, j], ref_j) <= 1e-5, j
+    assert rel_fro(got.sum(axis=1), dp_ref) <= 1e-5
+    # scatter back to (token, slot): a synthetic map that visits the rows in reverse, with one skipped slot
+    k = 2
+    T = (R + k - 1) // k
+    row_of = np.full((T, k), -1, np.int32)
+    rows = np.arange(R - 1, -1, -1, dtype=np.int32)
+    row_of.reshape(-1)[:R] = rows
+    dprob = torch.full((T, k), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_scatter_row_dprob(ctx, part, parts, dev(row_of), T, k, dprob)
+    torch.cuda.synchronize()
+    ref = np.where(row_of >= 0, got.astype(np.float32).astype(np.float64)[np.maximum(row_of, 0)].sum(axis=-1), 0.0)
+    np.testing.assert_allclose(dprob.cpu().numpy(), ref, rtol=1e-6, atol=1e-7)
+    # gather: row weights from (token, slot) weights, zero for padding rows
+    src_of = np.full(R + 3, -1, np.int32)
+    src_of[:R] = g.permutation(T * k)[:R]
+    probs = g.uniform(0, 1, size=(T, k)).astype(np.float32)
+    rp = torch.full((R + 3,), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_gather_row_prob(ctx, dev(probs), dev(src_of), R + 3, rp)
+    torch.cuda.synchronize()
+    assert np.array_equal(rp.cpu().numpy(), oracle.gather_row_prob(probs, src_of).astype(np.float32))
+
+
 WG_CASES = [
     # counts, N, K
     ([300, 0, 257, 1, 700], 256, 512),
