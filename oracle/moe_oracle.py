@@ -349,3 +349,37 @@ def layer_backward_eq2(fw, X, prob, W1, W2, dY, Ws1=None, Ws2=None, prec="f64"):
         out.dX_shared = grouped_gemm_nn(dZs, Ws1[None], off1, prec=prec)
         out.dZs = dZs
     return out
+
+
+# ----------------------------------------------------------------------------
+# router score function backward (Sec. 2.1.2 item 2): dL/dlogits from dL/dweights, selection frozen
+# ----------------------------------------------------------------------------
+def route_topk_bwd(logits, topk_idx, dprob, score=SOFTMAX, norm_topk=False, scale=1.0):
+    """Weights are w_s = scale * q_s / D with q_s the score of the s-th selected expert and D = sum of the
+    selected scores (norm_topk) or 1.  Chain rule through D, then through softmax (all E logits move every
+    score) or sigmoid (a logit moves only its own score).  fp64, one token at a time."""
+    L = np.asarray(logits, np.float64)
+    T, E = L.shape
+    out = np.zeros((T, E))
+    for t in range(T):
+        l = L[t]
+        idx = np.asarray(topk_idx[t], np.int64)
+        dw = np.asarray(dprob[t], np.float64)
+        if score == SOFTMAX:
+            ex = np.exp(l - l.max())
+            sc = ex / ex.sum()
+        else:
+            sc = 1.0 / (1.0 + np.exp(-l))
+        q = sc[idx]
+        if norm_topk:
+            D = q.sum()
+            dq = scale * (dw / D - np.dot(dw, q) / (D * D))
+        else:
+            dq = scale * dw
+        if score == SOFTMAX:
+            g = np.zeros(E)
+            g[idx] = dq
+            out[t] = sc * (g - np.dot(dq, q))
+        else:
+            out[t, idx] = dq * q * (1.0 - q)
+    return out

@@ -301,6 +301,47 @@ def test_backward_finite_differences(oracle):
             assert abs(fd - gr[pos]) <= 1e-6 * max(1.0, abs(fd)), (ai, pos, fd, gr[pos])
 
 
+@pytest.mark.parametrize("score,norm", [(0, False), (0, True), (1, True), (1, False)])
+def test_router_backward_finite_differences(oracle, score, norm):
+    """dL/dlogits of the routing weights with the selection frozen, against central differences of the weight
+    formula written out here (softmax over all experts / sigmoid, optional normalisation over the selected k),
+    which is itself tied to the oracle's forward."""
+    g = _rng(31 + 2 * score + norm)
+    T, E, k, scale = 9, 11, 3, 1.7
+    logits = g.normal(size=(T, E)).astype(np.float32)
+    idx, prob, _ = oracle.route_topk(logits, k, score, norm, scale)
+    dw = g.normal(size=(T, k))
+
+    def weights(l):
+        l = l.astype(np.float64)
+        if score == 0:
+            e = np.exp(l - l.max(axis=1, keepdims=True))
+            sc = e / e.sum(axis=1, keepdims=True)
+        else:
+            sc = 1 / (1 + np.exp(-l))
+        q = np.take_along_axis(sc, idx.astype(np.int64), axis=1)
+        if norm:
+            q = q / q.sum(axis=1, keepdims=True)
+        return scale * q
+
+    np.testing.assert_allclose(weights(logits), prob, rtol=1e-12, atol=1e-15)
+    got = oracle.route_topk_bwd(logits, idx, dw, score, norm, scale)
+    eps = 1e-5
+    L64 = logits.astype(np.float64)
+    for t in range(T):
+        for e in range(E):
+            lp, lm = L64.copy(), L64.copy()
+            lp[t, e] += eps
+            lm[t, e] -= eps
+            fd = ((weights(lp) - weights(lm)) * dw).sum() / (2 * eps)
+            assert abs(fd - got[t, e]) <= 1e-8 * max(1.0, abs(fd)) + 1e-9, (t, e, fd, got[t, e])
+    if score == 0:   # softmax: a constant shift of the logits changes nothing
+        np.testing.assert_allclose(got.sum(axis=1), 0.0, atol=1e-12)
+    if norm:         # normalised weights sum to `scale`: a common factor on dw-direction 1 gives zero gradient
+        ones = oracle.route_topk_bwd(logits, idx, np.ones((T, k)), score, norm, scale)
+        np.testing.assert_allclose(ones, 0.0, atol=1e-12)
+
+
 def test_eq2_layer_matches_eq1_and_finite_differences(oracle):
     """Memory-efficient permutation (Sec. 4.2.1): eq. (2) is an algebraic rearrangement of eq. (1), so its
     forward output and every gradient must equal eq. (1)'s (themselves pinned above), and its own loss must
