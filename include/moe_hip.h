@@ -100,6 +100,17 @@ moe_status moe_route_topk(moe_ctx* ctx, void* stream, const float* logits, int T
                           moe_score fn, int norm_topk, float scale,
                           int32_t* topk_idx, float* topk_prob, int32_t* counts);
 
+/*
+ * Backward of the routing weights (Sec. 2.1.2 item 2) with the selection frozen:
+ * dlogits[t,:] = sum_s dprob[t,s] * d topk_prob[t,s] / d logits[t,:], for the same score function,
+ * normalisation and scale as the forward call.  logits [T,E] fp32, topk_idx [T,k] as returned by
+ * moe_route_topk, dprob [T,k] fp32, dlogits [T,E] fp32 (every element is written; experts that
+ * were not selected get a non-zero gradient only through the softmax denominator).
+ */
+moe_status moe_route_topk_bwd(moe_ctx* ctx, void* stream, const float* logits, const int32_t* topk_idx,
+                              const float* dprob, int T, int E, int k, moe_score fn, int norm_topk,
+                              float scale, float* dlogits);
+
 /* ------------------------------------------------------------------------- */
 /* Stage 2: Dispatch = permute (Sec. 4.3.3 "Preprocessing" + "Permute")      */
 /* ------------------------------------------------------------------------- */

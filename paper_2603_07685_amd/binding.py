@@ -26,6 +26,7 @@ EXPORTS = [
     "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
+    "moe_route_topk_bwd",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -60,6 +61,7 @@ def lib() -> C.CDLL:
         L.moe_fp8_quantize.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _vp]
         L.moe_grouped_gemm_fwd_weighted.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_dgrad_weighted.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
         L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
         for name in EXPORTS:
@@ -152,6 +154,11 @@ def moe_grouped_gemm_dgrad_weighted(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_sa
                                                     dt, _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(row_prob),
                                                     _ptr(dA), _ptr(dprob_part)),
               "moe_grouped_gemm_dgrad_weighted")
+
+
+def moe_route_topk_bwd(ctx, logits, topk_idx, dprob, T, E, k, fn, norm_topk, scale, dlogits):
+    ctx.check(lib().moe_route_topk_bwd(ctx.h, _stream(), _ptr(logits), _ptr(topk_idx), _ptr(dprob), T, E, k, fn,
+                                       int(norm_topk), float(scale), _ptr(dlogits)), "moe_route_topk_bwd")
 
 
 def moe_gather_row_prob(ctx, prob, src_of, Rcap, row_prob):

@@ -125,3 +125,113 @@ extern "C" moe_status moe_route_topk(moe_ctx* ctx, void* stream, const float* lo
     MOE_LAUNCH_CHECK(ctx, "route_topk_kernel");
     return MOE_OK;
 }
+
+// ---------------------------------------------------------------------------
+// moe_route_topk_bwd: dL/dlogits from dL/dweights with the selection frozen (Sec. 2.1.2 item 2).
+//   w_s = scale * q_s / D,  q_s = score of the s-th selected expert,  D = sum_s q_s (norm_topk) or 1
+//   dq_s = scale * (dw_s / D - [norm] <dw, q> / D^2)
+//   softmax: dl_j = p_j * ([j selected] dq_j - <dq, q>)      sigmoid: dl_j = [j selected] dq_j * q_j (1 - q_j)
+// One wavefront per token, same register layout as the forward kernel; lane s < k holds slot s.
+// ---------------------------------------------------------------------------
+template <int VPL>
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void route_topk_bwd_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ topk_idx, const float* __restrict__ dprob,
+    int T, int E, int k, int fn, int norm_topk, float scale, float* __restrict__ dlogits) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int t0 = (blockIdx.x * ROUTE_WAVES + wave) * ROUTE_TOKENS_PER_WAVE;
+    for (int tt = 0; tt < ROUTE_TOKENS_PER_WAVE; ++tt) {
+        const int t = t0 + tt;
+        if (t >= T) break;  // uniform per wave
+        const float* l = logits + (int64_t)t * E;
+        float v[VPL];
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+            const int e = lane + 64 * j;
+            v[j] = e < E ? l[e] : -INFINITY;
+        }
+        float mx = 0.f, den = 1.f;
+        if (fn == MOE_SCORE_SOFTMAX) {
+            float m = v[0];
+#pragma unroll
+            for (int j = 1; j < VPL; ++j) m = fmaxf(m, v[j]);
+            mx = wave_max(m);
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) s += (lane + 64 * j < E) ? expf(v[j] - mx) : 0.f;
+            den = wave_sum(s);
+        }
+        // slot s lives in lane s: its expert, its score q_s and the incoming gradient
+        int my_idx = lane < k ? topk_idx[(int64_t)t * k + lane] : -1;
+        if (my_idx < 0 || my_idx >= E) my_idx = -1;  // a slot that names no expert of this router contributes nothing
+        const float dw = my_idx >= 0 ? dprob[(int64_t)t * k + lane] : 0.f;
+        float q = 0.f;
+        if (my_idx >= 0) {
+            const float lg = l[my_idx];
+            q = fn == MOE_SCORE_SOFTMAX ? expf(lg - mx) / den : 1.f / (1.f + expf(-lg));
+        }
+        float dq = scale * dw;
+        if (norm_topk) {
+            const float D = wave_sum(q);
+            const float dwq = wave_sum(dw * q);
+            dq = my_idx >= 0 ? scale * (dw / D - dwq / (D * D)) : 0.f;
+        }
+        const float dqq = wave_sum(dq * q);  // <dq, q>
+        // every lane collects the dq of the selected experts it owns
+        float gsel[VPL];
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) gsel[j] = 0.f;
+        for (int s = 0; s < k; ++s) {
+            const int e = __shfl(my_idx, s);
+            const float d = __shfl(dq, s);
+            if (e >= 0 && (e & 63) == lane) {
+#pragma unroll
+                for (int j = 0; j < VPL; ++j)
+                    if ((e >> 6) == j) gsel[j] += d;
+            }
+        }
+        float* o = dlogits + (int64_t)t * E;
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+            const int e = lane + 64 * j;
+            if (e < E) {
+                float r;
+                if (fn == MOE_SCORE_SOFTMAX) {
+                    const float p = expf(v[j] - mx) / den;
+                    r = p * (gsel[j] - dqq);
+                } else {
+                    const float sg = 1.f / (1.f + expf(-v[j]));
+                    r = gsel[j] * sg * (1.f - sg);
+                }
+                o[e] = r;
+            }
+        }
+    }
+}
+
+extern "C" moe_status moe_route_topk_bwd(moe_ctx* ctx, void* stream, const float* logits, const int32_t* topk_idx,
+                                         const float* dprob, int T, int E, int k, moe_score fn, int norm_topk,
+                                         float scale, float* dlogits) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!logits || !topk_idx || !dprob || !dlogits) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk_bwd: NULL pointer");
+    if (T < 0 || E < 1 || E > 64 * ROUTE_MAX_VPL || k < 1 || k > 32 || k > E)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk_bwd: need T>=0, 1<=k<=min(E,32), E<=%d (T=%d E=%d k=%d)",
+                 64 * ROUTE_MAX_VPL, T, E, k);
+    if (fn != MOE_SCORE_SOFTMAX && fn != MOE_SCORE_SIGMOID) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk_bwd: bad score fn");
+    if (T == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const int per_block = ROUTE_WAVES * ROUTE_TOKENS_PER_WAVE;
+    dim3 grid((T + per_block - 1) / per_block), block(ROUTE_WAVES * 64);
+    const int vpl = (E + 63) / 64;
+#define ROUTE_BWD_LAUNCH(V)                                                                                       \
+    hipLaunchKernelGGL(route_topk_bwd_kernel<V>, grid, block, 0, s, logits, topk_idx, dprob, T, E, k, (int)fn, norm_topk, \
+                       scale, dlogits)
+    if (vpl <= 1) ROUTE_BWD_LAUNCH(1);
+    else if (vpl <= 2) ROUTE_BWD_LAUNCH(2);
+    else if (vpl <= 4) ROUTE_BWD_LAUNCH(4);
+    else if (vpl <= 8) ROUTE_BWD_LAUNCH(8);
+    else ROUTE_BWD_LAUNCH(16);
+#undef ROUTE_BWD_LAUNCH
+    MOE_LAUNCH_CHECK(ctx, "route_topk_bwd_kernel");
+    return MOE_OK;
+}

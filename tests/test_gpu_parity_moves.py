@@ -52,6 +52,33 @@ def test_route_topk(B, ctx, oracle, T, E, k, fn, norm, scale):
     np.testing.assert_allclose(prob, o_prob, rtol=2e-6, atol=1e-9)
 
 
+@pytest.mark.parametrize("T,E,k,fn,norm,scale", [
+    (256, 8, 2, 0, False, 1.0),
+    (1000, 128, 8, 0, True, 2.5),
+    (4096, 256, 8, 1, True, 1.0),      # C4/C5 router
+    (777, 300, 6, 1, False, 0.5),      # E not a multiple of 64
+])
+def test_route_topk_backward(B, ctx, oracle, T, E, k, fn, norm, scale):
+    """dlogits from dweights with the selection frozen, every element, against the fp64 oracle."""
+    from gpu_util import dev
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(T + E)
+    logits = (g.normal(size=(T, E)) * 1.5).astype(np.float32)
+    idx, _, _ = oracle.route_topk(logits, k, fn, norm, scale)
+    dw = g.normal(size=(T, k)).astype(np.float32)
+    out = torch.full((T, E), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_route_topk_bwd(ctx, dev(logits), dev(idx), dev(dw), T, E, k, fn, norm, scale, out)
+    torch.cuda.synchronize()
+    ref = oracle.route_topk_bwd(logits, idx, dw, fn, norm, scale)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max() + 1e-9
+    if fn == 1:      # sigmoid: only the selected experts receive a gradient
+        mask = np.zeros((T, E), bool)
+        np.put_along_axis(mask, idx.astype(np.int64), True, axis=1)
+        assert np.all(got[~mask] == 0)
+
+
 def test_route_topk_ties_and_errors(B, ctx, oracle):
     g = np.random.default_rng(5)
     logits = g.integers(-2, 3, size=(512, 16)).astype(np.float32)     # many exact ties
