@@ -130,3 +130,78 @@ int orc_fp8_dequant(const uint8_t* q, const float* scale, int mode, int G, int64
             }
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* MXFP8 (Sec. 5.3.3): E4M3 elements, 1x32 blocks, E8M0 (power-of-two) scales */
+/* ------------------------------------------------------------------------ */
+/*
+ * The paper fixes the block (1x32 along the contraction dimension of the consuming GEMM,
+ * hence a row-wise and a column-wise quantised copy), the element format and the scale
+ * format, not how the scale is chosen.  Reading taken here: the scale is the smallest
+ * power of two that brings the block's largest magnitude inside the E4M3 range,
+ *     e = ceil(log2(amax / 448)),  scale = 2^e,  E8M0 byte = e + 127  (clamped to 0..254),
+ * so no element saturates; an all-zero block gets scale 1 (byte 127).  Elements are
+ * code = nearest E4M3 value to x / 2^e (exact division), ties to even.
+ * The exponent is computed exactly from the binary representation: amax = m * 2^x with
+ * m in [0.5, 1) and 448 = 0.875 * 2^9 give e = x - 9 if m <= 0.875, else x - 8.
+ */
+static int mx_exponent(float amax) {
+    if (!(amax > 0.0f)) return 0;
+    int x;
+    float m = frexpf(amax, &x);
+    int e = (m <= 0.875f) ? x - 9 : x - 8;
+    if (e < -127) e = -127;
+    if (e > 127) e = 127;
+    return e;
+}
+uint8_t orc_e8m0_from_amax(float amax) { return (uint8_t)(mx_exponent(amax) + 127); }
+double orc_e8m0_decode(uint8_t b) { return ldexp(1.0, (int)b - 127); }
+
+/* row-wise: X[rows,K] -> q[rows,K], e8[rows,K/32]; blocks of 32 along each row.  K % 32 == 0. */
+int orc_mx_quant_1x32(const float* X, int64_t rows, int K, uint8_t* q, uint8_t* e8) {
+    if (K % 32) return -1;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int b = 0; b < K / 32; ++b) {
+            const float* x = X + r * K + b * 32;
+            float amax = 0.0f;
+            for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(x[i]));
+            int e = mx_exponent(amax);
+            e8[r * (K / 32) + b] = (uint8_t)(e + 127);
+            for (int i = 0; i < 32; ++i) q[r * K + b * 32 + i] = orc_e4m3_encode(ldexpf(x[i], -e));
+        }
+    return 0;
+}
+
+/* column-wise, for a weight stack W[G,N,K] read with N as the contraction dimension (dgrad):
+ * blocks of 32 consecutive n for a fixed k; q[G,N,K] keeps W's layout, e8[G,K,N/32] is laid out
+ * so that the scales of one output column k are contiguous.  N % 32 == 0. */
+int orc_mx_quant_32x1(const float* W, int G, int N, int K, uint8_t* q, uint8_t* e8) {
+    if (N % 32) return -1;
+    for (int g = 0; g < G; ++g)
+        for (int k = 0; k < K; ++k)
+            for (int b = 0; b < N / 32; ++b) {
+                float amax = 0.0f;
+                for (int i = 0; i < 32; ++i)
+                    amax = fmaxf(amax, fabsf(W[((int64_t)g * N + b * 32 + i) * K + k]));
+                int e = mx_exponent(amax);
+                e8[((int64_t)g * K + k) * (N / 32) + b] = (uint8_t)(e + 127);
+                for (int i = 0; i < 32; ++i) {
+                    int64_t at = ((int64_t)g * N + b * 32 + i) * K + k;
+                    q[at] = orc_e4m3_encode(ldexpf(W[at], -e));
+                }
+            }
+    return 0;
+}
+
+/* dequantise to double.  mode 0: row-wise (G = 1, e8[rows,K/32]); mode 1: column-wise stack
+ * (rows = N, e8[G,K,N/32]). */
+int orc_mx_dequant(const uint8_t* q, const uint8_t* e8, int mode, int G, int64_t rows, int K, double* out) {
+    for (int g = 0; g < G; ++g)
+        for (int64_t r = 0; r < rows; ++r)
+            for (int k = 0; k < K; ++k) {
+                int64_t at = ((int64_t)g * rows + r) * K + k;
+                uint8_t b = mode == 0 ? e8[r * (K / 32) + k / 32] : e8[((int64_t)g * K + k) * (rows / 32) + r / 32];
+                out[at] = (double)orc_e4m3_decode(q[at]) * orc_e8m0_decode(b);
+            }
+    return 0;
+}

@@ -51,6 +51,8 @@ def lib():
         _lib.orc_e4m3_decode.argtypes = [C.c_uint8]
         _lib.orc_e4m3_encode.restype = C.c_uint8
         _lib.orc_e4m3_encode.argtypes = [C.c_float]
+        _lib.orc_e8m0_from_amax.restype = C.c_uint8
+        _lib.orc_e8m0_from_amax.argtypes = [C.c_float]
     return _lib
 
 
@@ -383,3 +385,46 @@ def route_topk_bwd(logits, topk_idx, dprob, score=SOFTMAX, norm_topk=False, scal
         else:
             out[t, idx] = dq * q * (1.0 - q)
     return out
+
+
+# ----------------------------------------------------------------------------
+# MXFP8 (Sec. 5.3.3): E4M3 elements, 1x32 blocks, E8M0 scales
+# ----------------------------------------------------------------------------
+def mx_quant_1x32(X):
+    """Row-wise: blocks of 32 along the last dimension.  Returns (codes [rows,K] u8, e8m0 [rows,K/32] u8)."""
+    X = _arr(X, np.float32)
+    rows, K = X.shape
+    q = np.empty((rows, K), np.uint8)
+    e = np.empty((rows, K // 32), np.uint8)
+    if lib().orc_mx_quant_1x32(_p(X), C.c_int64(rows), K, _p(q), _p(e)) != 0:
+        raise ValueError("K must be a multiple of 32")
+    return q, e
+
+
+def mx_quant_32x1(W):
+    """Column-wise for a weight stack [G,N,K]: blocks of 32 along N.  Returns (codes [G,N,K], e8m0 [G,K,N/32])."""
+    W = _arr(W, np.float32)
+    G, N, K = W.shape
+    q = np.empty((G, N, K), np.uint8)
+    e = np.empty((G, K, N // 32), np.uint8)
+    if lib().orc_mx_quant_32x1(_p(W), G, N, K, _p(q), _p(e)) != 0:
+        raise ValueError("N must be a multiple of 32")
+    return q, e
+
+
+def mx_dequant(q, e, mode):
+    """mode "1x32": q [rows,K], e [rows,K/32];  mode "32x1": q [G,N,K], e [G,K,N/32].  Returns float64."""
+    q = _arr(q, np.uint8)
+    e = _arr(e, np.uint8)
+    out = np.empty(q.shape, np.float64)
+    if mode == "1x32":
+        rows, K = q.shape
+        lib().orc_mx_dequant(_p(q), _p(e), 0, 1, C.c_int64(rows), K, _p(out))
+    else:
+        G, N, K = q.shape
+        lib().orc_mx_dequant(_p(q), _p(e), 1, G, C.c_int64(N), K, _p(out))
+    return out
+
+
+def e8m0_from_amax(a: float) -> int:
+    return int(lib().orc_e8m0_from_amax(C.c_float(a)))

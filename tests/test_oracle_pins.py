@@ -467,3 +467,59 @@ def test_fp8_block_quantisers(oracle):
     qt, st = oracle.fp8_quant_1x128(np.ascontiguousarray(X.T))
     qc, sc = oracle.fp8_quant_128x1(X)
     assert np.array_equal(qt.T, qc) and np.array_equal(st.T, sc)
+
+
+def test_mxfp8_quantisers(oracle):
+    """MXFP8 (Sec. 5.3.3): E8M0 scale = smallest power of two that brings the block maximum inside +-448;
+    1x32 blocks along the row (and along N for the column-wise weight copy)."""
+    # scale exponent against the definition evaluated in exact rational arithmetic
+    from fractions import Fraction
+    g = _rng(41)
+    for a in list(g.uniform(1e-6, 1e4, size=200)) + [448.0, 224.0, 448.0 * 2 ** -20, 449.0, 3.5, 1.75 * 2 ** -3, 1e-30, 3e38]:
+        a32 = np.float32(a)
+        e = oracle.e8m0_from_amax(float(a32)) - 127
+        ratio = Fraction(float(a32)) / 448
+        if -127 < e < 127:
+            assert ratio <= Fraction(2) ** e and ratio > Fraction(2) ** (e - 1), (a, e)
+    assert oracle.e8m0_from_amax(0.0) == 127
+    # row-wise quantiser: per block amax/scale in (224, 448], no saturation, dequantisation error <= 2^-4 relative
+    X = (g.normal(size=(7, 96)) * np.exp(g.normal(size=(7, 96)) * 3)).astype(np.float32)
+    X[2, 32:64] = 0.0
+    X[3, 5] = 448.0 * 2 ** 10                                   # block maximum exactly at the top of the range
+    q, e8 = oracle.mx_quant_1x32(X)
+    assert q.shape == X.shape and e8.shape == (7, 3)
+    assert e8[2, 1] == 127 and not q[2, 32:64].any()
+    dq = oracle.mx_dequant(q, e8, "1x32")
+    for r in range(7):
+        for b in range(3):
+            blk = X[r, 32 * b:32 * b + 32].astype(np.float64)
+            am = np.abs(blk).max()
+            if am == 0:
+                continue
+            sc = 2.0 ** (int(e8[r, b]) - 127)
+            assert 224 < am / sc <= 448, (r, b, am, sc)
+            err = np.abs(dq[r, 32 * b:32 * b + 32] - blk)
+            # normal E4M3 values: half an ulp = 2^-4 relative; below 2^-6 * scale: half the subnormal step
+            assert np.all(err <= np.maximum(np.abs(blk) * 2.0 ** -4, sc * 2.0 ** -10) + 1e-300)
+    assert q[3, 5] == 0x7E and e8[3, 0] == 127 + 10             # 448 * 2^10 -> largest code, scale 2^10
+    # idempotence at the value level: representable values survive a second pass unchanged (codes may differ:
+    # a block maximum that rounded down to exactly 224 * scale moves to the next smaller scale with doubled codes)
+    q2, e2 = oracle.mx_quant_1x32(dq.astype(np.float32))
+    big = np.abs(dq) >= np.repeat(2.0 ** (e8.astype(np.float64) - 127 - 5), 32, axis=1)   # not in the subnormal tail
+    np.testing.assert_array_equal(oracle.mx_dequant(q2, e2, "1x32")[big], dq[big])
+    # powers of two are exact
+    P = (2.0 ** g.integers(-20, 20, size=(4, 64))).astype(np.float32)
+    # (a block spanning more than 2^17 in magnitude underflows its small members: keep each block within range)
+    P = (P.reshape(4, 2, 32) / P.reshape(4, 2, 32).max(axis=2, keepdims=True) * 2.0 ** g.integers(-5, 5, size=(4, 2, 1))).astype(np.float32)
+    P = np.maximum(P, P.max(axis=2, keepdims=True) * 2.0 ** -12).reshape(4, 64)
+    qp, ep = oracle.mx_quant_1x32(P)
+    np.testing.assert_array_equal(oracle.mx_dequant(qp, ep, "1x32"), P.astype(np.float64))
+    # column-wise copy of a weight stack == row-wise quantisation of the transposed matrices
+    W = g.normal(size=(2, 64, 8)).astype(np.float32)
+    qc, ec = oracle.mx_quant_32x1(W)
+    assert qc.shape == W.shape and ec.shape == (2, 8, 2)
+    for gi in range(2):
+        qt, et = oracle.mx_quant_1x32(np.ascontiguousarray(W[gi].T))
+        assert np.array_equal(qc[gi], qt.T) and np.array_equal(ec[gi], et)
+    np.testing.assert_array_equal(oracle.mx_dequant(qc, ec, "32x1")[1],
+                                  oracle.mx_dequant(*oracle.mx_quant_1x32(np.ascontiguousarray(W[1].T)), "1x32").T)
