@@ -46,7 +46,7 @@ typedef enum {
     MOE_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
 } moe_status;
 
-typedef enum { MOE_BF16 = 0, MOE_FP8_E4M3 = 1, MOE_F32 = 2 } moe_dtype;
+typedef enum { MOE_BF16 = 0, MOE_FP8_E4M3 = 1, MOE_F32 = 2, MOE_MXFP8_E4M3 = 3 } moe_dtype;
 typedef enum { MOE_SCORE_SOFTMAX = 0, MOE_SCORE_SIGMOID = 1 } moe_score;
 typedef enum { MOE_EPI_NONE = 0, MOE_EPI_SWIGLU = 1 } moe_epilogue;
 
@@ -277,6 +277,33 @@ typedef enum { MOE_Q_1x128 = 0, MOE_Q_128x1 = 1, MOE_Q_128x128 = 2 } moe_qblock;
 moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X, moe_qblock block,
                             int groups, int64_t rows, int cols, const int32_t* rows_dev,
                             void* q, float* scale);
+
+/* ------------------------------------------------------------------------- */
+/* MXFP8 quantisation (Sec. 5.3.3): E4M3 elements, 1x32 blocks, E8M0 scales    */
+/* ------------------------------------------------------------------------- */
+/*
+ * X bf16 -> E4M3 codes q (same shape, one byte each) + one E8M0 byte per block of 32
+ * elements along the contraction dimension of the GEMM that will read the tensor.
+ *   scale = 2^e, e = ceil(log2(amax(block) / 448)) clamped to +-127 (no element
+ *   saturates), e8m0 byte = e + 127, an all-zero block gets 127;
+ *   code = nearest E4M3 to x / 2^e, ties to even.
+ *   block = MOE_MX_1x32: 32 consecutive elements of a row; X [rows,cols], groups = 1
+ *                        (a weight stack [E,N,K] is passed as rows = E*N); e8m0 [rows, cols/32].
+ *           MOE_MX_32x1: 32 consecutive rows of a column, for the copy of a weight stack
+ *                        [groups, rows = N, cols = K] that the data-gradient GEMM reads with N
+ *                        as its contraction; q keeps the [groups,N,K] layout, e8m0 is
+ *                        [groups, K, N/32] (the scales of one output column are contiguous).
+ *   rows_dev: as in moe_fp8_quantize (1x32 only).
+ * The grouped GEMMs take these with dt = MOE_MXFP8_E4M3: the scale arguments then point to
+ * the E8M0 bytes (a_scale / dc_scale: [Rcap, C/32] of the row operand, C its contraction
+ * length; b_scale: fwd [E*N, K/32] from MOE_MX_1x32, dgrad [E, K, N/32] from MOE_MX_32x1, together
+ * with the matching code tensor), and the scaling is done by the matrix instruction itself.
+ * N and K must be multiples of 128.  wgrad is not built for this type.
+ */
+typedef enum { MOE_MX_1x32 = 0, MOE_MX_32x1 = 1 } moe_mxblock;
+moe_status moe_mx_quantize(moe_ctx* ctx, void* stream, const void* X, moe_mxblock block,
+                           int groups, int64_t rows, int cols, const int32_t* rows_dev,
+                           void* q, uint8_t* e8m0);
 
 #ifdef __cplusplus
 }

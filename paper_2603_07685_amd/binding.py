@@ -16,17 +16,18 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MOE_HIP_LIB") or os.path.join(_PKG, "libmoe_hip.so")
 _lib = None
 
-BF16, FP8_E4M3, F32 = 0, 1, 2
+BF16, FP8_E4M3, F32, MXFP8_E4M3 = 0, 1, 2, 3
 SOFTMAX, SIGMOID = 0, 1
 EPI_NONE, EPI_SWIGLU = 0, 1
 Q_1x128, Q_128x1, Q_128x128 = 0, 1, 2
+MX_1x32, MX_32x1 = 0, 1
 
 EXPORTS = [
     "moe_workspace_bytes", "moe_ctx_create", "moe_ctx_destroy", "moe_last_error", "moe_ctx_poll_error",
     "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
-    "moe_route_topk_bwd",
+    "moe_route_topk_bwd", "moe_mx_quantize",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -61,6 +62,7 @@ def lib() -> C.CDLL:
         L.moe_fp8_quantize.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _vp]
         L.moe_grouped_gemm_fwd_weighted.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_dgrad_weighted.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.moe_mx_quantize.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _vp]
         L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
         L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
@@ -186,6 +188,11 @@ def moe_unpermute_combine_bwd(ctx, dY, O, dt, row_of, src_of, prob, T, k, h, Rca
     ctx.check(lib().moe_unpermute_combine_bwd(ctx.h, _stream(), _ptr(dY), _ptr(O), dt, _ptr(row_of), _ptr(src_of),
                                               _ptr(prob), T, k, h, Rcap, _ptr(dO), _ptr(dprob)),
               "moe_unpermute_combine_bwd")
+
+
+def moe_mx_quantize(ctx, X, block, groups, rows, cols, rows_dev, q, e8m0):
+    ctx.check(lib().moe_mx_quantize(ctx.h, _stream(), _ptr(X), block, groups, rows, cols, _ptr(rows_dev), _ptr(q),
+                                    _ptr(e8m0)), "moe_mx_quantize")
 
 
 def moe_fp8_quantize(ctx, X, block, groups, rows, cols, rows_dev, q, scale):

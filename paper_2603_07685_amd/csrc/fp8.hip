@@ -183,3 +183,120 @@ extern "C" moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X
     MOE_LAUNCH_CHECK(ctx, "moe_fp8_quantize");
     return MOE_OK;
 }
+
+// ---------------------------------------------------------------------------
+// MXFP8 (Sec. 5.3.3): E4M3 elements in 1x32 blocks with E8M0 (power-of-two) scales.
+//   e = ceil(log2(amax / 448)) from the bits of amax = 1.f * 2^(E-127): e = E - 127 - 8 (+1 if 1.f > 1.75),
+//   clamped to +-127; an all-zero block gets e = 0.  code = nearest E4M3 to x * 2^-e (exact scaling).
+//   1x32 : 4 lanes own one block (8 elements each); a wave reads 1 KB and writes 512 B contiguous.
+//   32x1 : for a weight stack [G,N,K] read with N as the contraction: a lane owns 4 consecutive k of one
+//          32-row block, holds the 32 rows in registers; scales go to [G,K,N/32].
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int mx_exponent(float amax) {
+    if (!(amax > 0.0f)) return 0;
+    const uint32_t b = __float_as_uint(amax);
+    int e = (int)((b >> 23) & 0xFF) - 127 - 8 + ((b & 0x7FFFFFu) > 0x600000u ? 1 : 0);
+    if (((b >> 23) & 0xFF) == 0) e = -127;  // subnormal maximum: far below the clamp
+    return e < -127 ? -127 : (e > 127 ? 127 : e);
+}
+__device__ __forceinline__ uint32_t mx_cvt4(float a, float b, float c, float d, int e) {
+    int w = 0;
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(a, -e), ldexpf(b, -e), w, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(c, -e), ldexpf(d, -e), w, true);
+    return (uint32_t)w;
+}
+
+__global__ __launch_bounds__(256) void mx_quant_1x32_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
+                                                            const int32_t* __restrict__ rows_dev,
+                                                            u32x2_t* __restrict__ q, uint8_t* __restrict__ e8) {
+    const int64_t live = rows_dev ? min((int64_t)*rows_dev, rows) : rows;
+    const int64_t nvec = live * (cols / 8);            // 16-byte vectors; 4 per block, blocks never straddle rows
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; v < ((nvec + 3) & ~(int64_t)3); v += stride) {  // whole 4-lane groups stay together
+        const bool in = v < nvec;
+        const u32x4_t x = in ? X[v] : u32x4_t{0, 0, 0, 0};
+        float m = amax8(x);
+        m = fmaxf(m, __shfl_xor(m, 1));
+        m = fmaxf(m, __shfl_xor(m, 2));
+        const int e = mx_exponent(m);
+        if (in) {
+            u32x2_t o;
+            o.x = mx_cvt4(bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y), e);
+            o.y = mx_cvt4(bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w), e);
+            q[v] = o;
+            if ((v & 3) == 0) e8[v >> 2] = (uint8_t)(e + 127);
+        }
+    }
+}
+
+// grid.x covers (G * N/32) row blocks x ceil(K/4 / 256) column groups
+__global__ __launch_bounds__(256) void mx_quant_32x1_kernel(const u32x2_t* __restrict__ W, int G, int N, int K,
+                                                            uint32_t* __restrict__ q, uint8_t* __restrict__ e8) {
+    const int kq = K / 4;                               // 4-column groups per row
+    const int cgroups = (kq + 255) / 256;
+    const int64_t blk = blockIdx.x / cgroups;           // (g, n-block)
+    const int c4 = (blockIdx.x % cgroups) * 256 + threadIdx.x;
+    if (c4 >= kq) return;
+    const int nb = N / 32;
+    const int g = (int)(blk / nb), b = (int)(blk % nb);
+    const int64_t row0 = (int64_t)g * N + b * 32;
+    u32x2_t v[32];
+    float m[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        v[r] = W[(row0 + r) * kq + c4];
+        m[0] = fmaxf(m[0], fabsf(bf16_lo(v[r].x)));
+        m[1] = fmaxf(m[1], fabsf(bf16_hi(v[r].x)));
+        m[2] = fmaxf(m[2], fabsf(bf16_lo(v[r].y)));
+        m[3] = fmaxf(m[3], fabsf(bf16_hi(v[r].y)));
+    }
+    int e[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        e[i] = mx_exponent(m[i]);
+        e8[((int64_t)g * K + c4 * 4 + i) * nb + b] = (uint8_t)(e[i] + 127);
+    }
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        int w = 0;
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(v[r].x), -e[0]), ldexpf(bf16_hi(v[r].x), -e[1]), w, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(v[r].y), -e[2]), ldexpf(bf16_hi(v[r].y), -e[3]), w, true);
+        q[(row0 + r) * kq + c4] = (uint32_t)w;
+    }
+}
+
+extern "C" moe_status moe_mx_quantize(moe_ctx* ctx, void* stream, const void* X, moe_mxblock block,
+                                      int groups, int64_t rows, int cols, const int32_t* rows_dev,
+                                      void* q, uint8_t* e8m0) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!X || !q || !e8m0) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize: NULL pointer");
+    if (rows < 0 || cols < 1 || groups < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize: bad sizes");
+    hipStream_t s = (hipStream_t)stream;
+    const int cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
+    if (rows == 0) return MOE_OK;
+    switch (block) {
+        case MOE_MX_1x32: {
+            if (cols % 32) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(1x32): cols %% 32 != 0");
+            if (groups != 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(1x32): groups must be 1 (fold them into rows)");
+            int64_t grid = ceil_div64(rows * (cols / 8), 256);
+            if (grid > (int64_t)cu * 32) grid = (int64_t)cu * 32;
+            hipLaunchKernelGGL(mx_quant_1x32_kernel, dim3((unsigned)grid), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
+                               rows_dev, (u32x2_t*)q, e8m0);
+            break;
+        }
+        case MOE_MX_32x1: {
+            if (rows % 32 || cols % 4) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): rows %% 32 or cols %% 4 != 0");
+            if (rows_dev) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): rows_dev is not used for weights");
+            const int64_t nblk = (int64_t)groups * (rows / 32) * ceil_div64(cols / 4, 256);
+            if (nblk > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): too many blocks");
+            hipLaunchKernelGGL(mx_quant_32x1_kernel, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x2_t*)X, groups,
+                               (int)rows, cols, (uint32_t*)q, e8m0);
+            break;
+        }
+        default:
+            MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize: bad block kind");
+    }
+    MOE_LAUNCH_CHECK(ctx, "moe_mx_quantize");
+    return MOE_OK;
+}

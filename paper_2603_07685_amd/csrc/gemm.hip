@@ -148,11 +148,12 @@ __device__ __forceinline__ bf16x8_t lds_read_tr16x8(const char* p_lo, const char
 // ds_read_b64_tr_b8: lane i of a 16-lane group supplies the address of 8 consecutive bytes (row i/2,
 // columns 8*(i%2)..+7 of an 8x16 block) and receives column i (rows 0..7).  Four reads, 8 rows apart,
 // give the 32 contraction values a lane feeds to the 32x32x64 fp8 MFMA.
-__device__ __forceinline__ i32x8_t lds_read_tr8x32(const char* p) {
+// `second` is the row distance between the lane's first and second group of 16 contraction values.
+__device__ __forceinline__ i32x8_t lds_read_tr8x32(const char* p, int second = 16) {
     i32x2_t r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)p);
     i32x2_t r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + 8 * 256));
-    i32x2_t r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + 16 * 256));
-    i32x2_t r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + 24 * 256));
+    i32x2_t r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + second * 256));
+    i32x2_t r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2_t*)(p + (second + 8) * 256));
     i32x8_t v = {r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
     return v;
 }
@@ -190,9 +191,13 @@ struct gg_args {
 };
 
 // MODE: GG_FWD / GG_DGRAD / GG_WGRAD.  EPI: see enum.  OUT_F32: fp32 output (wgrad only).
-// FP8: operands are E4M3 codes with block scales (fwd and dgrad only).
-template <int MODE, int EPI, bool OUT_F32, bool FP8>
+// F8 (fwd and dgrad only): 0 = bf16 operands; 1 = E4M3 codes with fp32 block scales applied in software
+// (blockwise recipe); 2 = E4M3 codes with one E8M0 scale per 32 contraction elements, applied by the matrix
+// instruction itself (MXFP8, Sec. 5.3.3).
+template <int MODE, int EPI, bool OUT_F32, int F8>
 __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
+    constexpr bool FP8 = F8 != 0;  // one-byte operands
+    constexpr bool MX = F8 == 2;   // hardware block scales
     // fp8: the block scales of a stage travel with it, behind the P tile: 256 row scales (position
     // 4 * (row % 32) + row / 32 inside each 128-row half, so a lane finds its four rows in one 16-byte
     // read) and, from position 256 on, the two column-block scales (replicated)
@@ -280,7 +285,12 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     //        slot = (cb / 8 ^ 4 (i >> 2)) + 2 (blk & 1) + ((i & 3) >> 1), byte (i & 1) * 8
     //   fp8  (row pitch 256 B, 128 rows): row = 64 half + 32 (blk >> 1) + 8 g + (i >> 1),
     //        slot = (cb / 16 ^ 2 (i >> 1)) + (blk & 1), byte (i & 1) * 8
-    const int tr_rowoff = FP8 ? (32 * (tr_blk >> 1) + (tr_i >> 1)) * 256 : (8 * (tr_blk >> 1) + (tr_i >> 2)) * 512;
+    // (MX: the scaled MFMA takes K 0..31 of a 64-step, the first scale block, from bytes 0..15 of both lane
+    // halves and K 32..63 from bytes 16..31, so a lane of half h holds K 16 h + 0..15 and 32 + 16 h + 0..15;
+    // without block scales the order inside the step does not matter and a lane holds 32 consecutive K)
+    const int tr_rowoff = MX    ? (16 * (tr_blk >> 1) + (tr_i >> 1)) * 256
+                          : FP8 ? (32 * (tr_blk >> 1) + (tr_i >> 1)) * 256
+                                : (8 * (tr_blk >> 1) + (tr_i >> 2)) * 512;
     const int tr_low = FP8 ? (tr_blk & 1) : 2 * (tr_blk & 1) + ((tr_i & 3) >> 1);
     const int tr_xor = FP8 ? 2 * (tr_i >> 1) : 4 * (tr_i >> 2);
     const int tr_byte = (tr_i & 1) * 8;
@@ -393,7 +403,26 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         // multiplied by s(kb-1) / s(kb), and by the last s in the epilogue.  The scales of block kb reach
         // LDS with the operands of stage kb (one more 4-byte-per-lane DMA by waves 0..4).
         const int CB = (c_hi - c_lo) / 128;  // contraction blocks = stages
-        if (FP8) {
+        if (MX) {
+            // one dword = the four E8M0 bytes of a row for this stage (128 contraction elements).  Waves 0..3
+            // fetch the 256 P rows (position layout as below), waves 4..7 the 256 Q rows: position
+            // p' = 64 (wave - 4) + lane holds Q tile row 128 (p' & 1) + (p' >> 1), so a lane finds the rows of its
+            // two column blocks in one 8-byte read.
+            if (wave < 4) {
+                const int pp = wave * 64 + lane;
+                int64_t r = (int64_t)i0 + (pp >> 7) * 128 + (pp & 3) * 32 + ((pp & 127) >> 2);
+                r = r < a.Rcap ? r : a.Rcap - 1;
+                sc_src = a.p_scale + r * CB;
+            } else {
+                const int pp = (wave - 4) * 64 + lane;
+                const int rho = 128 * (pp & 1) + (pp >> 1);
+                int col = (rho < 128 ? j0 : j1 - 128) + rho;  // output column = weight row (fwd) / weight column (dgrad)
+                col = col < J ? col : J - 1;
+                // fwd: e8m0 [E*N, K/32];  dgrad: e8m0 [E, K, N/32]: in both a row of CB dwords per output column
+                sc_src = a.q_scale + ((int64_t)e * J + col) * CB;
+            }
+            sc_step = 1;
+        } else if (FP8) {
             if (wave < 4) {  // row scales: LDS position p = 64 wave + lane holds tile row ...
                 const int pp = wave * 64 + lane;
                 int64_t r = (int64_t)i0 + (pp >> 7) * 128 + (pp & 3) * 32 + ((pp & 127) >> 2);
@@ -431,7 +460,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         };
 
         auto issue_scales = [&](int kb, float* ss) {
-            if (wave <= 4) {
+            if (MX || wave <= 4) {
                 const float* src = sc_src + kb * sc_step;
                 dma4(src, wave * 256, lds_addr(ss));
             }
@@ -477,7 +506,9 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 
             auto fetch = [&](const char* sp, const char* sq, int half) {
                 if (FP8) {
-                    const int s0 = ((4 * half + 2 * fr_khalf) ^ fr_swz) * 16, s1 = ((4 * half + 2 * fr_khalf + 1) ^ fr_swz) * 16;
+                    const int sl0 = MX ? 4 * half + fr_khalf : 4 * half + 2 * fr_khalf;  // 16-byte slot of the lane's first 16 K
+                    const int sl1 = MX ? sl0 + 2 : sl0 + 1;
+                    const int s0 = (sl0 ^ fr_swz) * 16, s1 = (sl1 ^ fr_swz) * 16;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {  // P is k-major in both fp8 modes
                         const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i] + s0), hi = *(const i32x4_t*)(sp + p_rd[i] + s1);
@@ -486,7 +517,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         if (Q_CMAJ) {
-                            qf8[j] = lds_read_tr8x32(sq + q_rd[j] + half * 64 * 256);
+                            qf8[j] = lds_read_tr8x32(sq + q_rd[j] + half * 64 * 256, MX ? 32 : 16);
                         } else {
                             const i32x4_t lo = *(const i32x4_t*)(sq + q_rd[j] + s0), hi = *(const i32x4_t*)(sq + q_rd[j] + s1);
                             qf8[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -511,13 +542,18 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
             };
             // the MFMAs of one half-stage, with the GG_DMA_PER_STAGE DMA instructions of stage kt_dma slipped in
-            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq) {
+            int psr[4] = {127, 127, 127, 127}, qsr[2] = {127, 127};  // MX: scale bytes of the current stage
+            auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq, int half) {
                 if (FP8) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 0, 127, 0, 127);
+                            // MX: the lane's 32 contraction elements are one scale block; its E8M0 byte sits in byte 0
+                            // (first half-stage) / byte 2 (second) of the pre-shifted scale registers
+                            if (!MX) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 0, 127, 0, 127);
+                            else if (half == 0) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 0, qsr[j], 0, psr[i]);
+                            else acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qf8[j], pf8[i], acc[i][j], 0, 0, 2, qsr[j], 2, psr[i]);
                             pin(acc[i][j]);
                             __builtin_amdgcn_sched_barrier(0);
                             if (do_dma) issue_one(kt_dma, dp, dq, i * 2 + j);
@@ -545,6 +581,16 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             f32x4_t pn;
             float qn[2];
             auto read_scales = [&](const float* ss) {
+                if (MX) {
+                    const i32x4_t pw = *(const i32x4_t*)(ss + wm * 128 + fr_row * 4);
+                    const i32x2_t qw = *(const i32x2_t*)(ss + 256 + (wn * 32 + fr_row) * 2);
+                    const int sh = 8 * fr_khalf;  // this lane's 32 elements are block khalf (first half) / 2 + khalf (second)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) psr[i] = (int)((uint32_t)pw[i] >> sh);
+                    qsr[0] = (int)((uint32_t)qw.x >> sh);
+                    qsr[1] = (int)((uint32_t)qw.y >> sh);
+                    return;
+                }
                 pn = *(const f32x4_t*)(ss + wm * 128 + fr_row * 4);
                 qn[0] = ss[256];
                 qn[1] = ss[257];
@@ -591,7 +637,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
                 fetch(SP[s], SQ[s], half);
                 __builtin_amdgcn_sched_barrier(0);
-                if (FP8 && half == 0) rescale();  // after the fragment reads in program order: overlaps them
+                if (FP8 && !MX && half == 0) rescale();  // after the fragment reads in program order: overlaps them
                 wait_lgkm0();
             };
             if (KT > 0 && wm == 0) {
@@ -605,11 +651,11 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     }
                     half_a(s, 0);
                     stage_barrier();
-                    mma(false, 0, nullptr, nullptr);
+                    mma(false, 0, nullptr, nullptr, 0);
                     stage_barrier();
                     half_a(s, 1);
                     stage_barrier();
-                    mma(false, 0, nullptr, nullptr);
+                    mma(false, 0, nullptr, nullptr, 1);
                     wait_vm0();  // stage j+1 landed
                     stage_barrier();
                 };
@@ -633,12 +679,12 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 auto stage1 = [&](int j, int s) {
                     half_a(s, 0);
                     stage_barrier();
-                    mma(false, 0, nullptr, nullptr);
+                    mma(false, 0, nullptr, nullptr, 0);
                     stage_barrier();
                     half_a(s, 1);
                     wait_vm0();  // stage j+1 landed
                     stage_barrier();
-                    mma(j + 2 < KT, j + 2, SP[s], SQ[s]);
+                    mma(j + 2 < KT, j + 2, SP[s], SQ[s], 1);
                     if (FP8 && j + 2 < KT) issue_scales(j + 2, SS[s]);
                     stage_barrier();
                 };
@@ -680,7 +726,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
                         v[x] = acc[i][h2][4 * g + x];
-                        if (FP8) v[x] *= ps_cur[i] * qs_cur[h2];
+                        if (FP8 && !MX) v[x] *= ps_cur[i] * qs_cur[h2];
                     }
                     *(f32x4_t*)(stg + (wm * 32 + fr_row) * STG_PITCH + h2 * 128 + wn * 32 + 8 * g + 4 * fr_khalf) = v;
                 }
@@ -776,8 +822,8 @@ static moe_status gg_check_common(moe_ctx* ctx, const char* who, const void* p, 
     if (E < 1 || E > GG_MAX_E || N < 1 || K < 1 || Rcap < 1 || Rcap > 0x7fffffffLL)
         MOE_FAIL(ctx, MOE_ERR_ARG, "%s: need 1<=E<=%d, N,K>=1, 1<=Rcap<2^31", who, GG_MAX_E);
     if (dt == MOE_F32) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "%s: fp32 operands are not supported", who);
-    if (dt != MOE_BF16 && dt != MOE_FP8_E4M3) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: bad dtype", who);
-    if (dt == MOE_FP8_E4M3 && (N % 128 || K % 128))
+    if (dt != MOE_BF16 && dt != MOE_FP8_E4M3 && dt != MOE_MXFP8_E4M3) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: bad dtype", who);
+    if (dt != MOE_BF16 && (N % 128 || K % 128))
         MOE_FAIL(ctx, MOE_ERR_ARG, "%s: fp8 needs N and K to be multiples of 128 (block scales)", who);
     if (N % 8 || K % 8) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: N and K must be multiples of 8 (16-byte rows)", who);
     return MOE_OK;
@@ -826,13 +872,13 @@ extern "C" moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, 
     if (epi == MOE_EPI_SWIGLU) {
         if (!C_act) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: SWIGLU needs C_act");
         if (N % 16) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: SWIGLU needs N %% 16 == 0");
-        if (dt == MOE_FP8_E4M3 && N % 256) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: fp8 SWIGLU needs N %% 256 == 0");
+        if (dt != MOE_BF16 && N % 256) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: fp8 SWIGLU needs N %% 256 == 0");
     } else if (epi == MOE_EPI_NONE) {
         if (!C) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: C is NULL");
     } else {
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: bad epilogue");
     }
-    const bool fp8 = dt == MOE_FP8_E4M3;
+    const bool fp8 = dt != MOE_BF16, mx = dt == MOE_MXFP8_E4M3;
     if (fp8 && (!a_scale || !b_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: fp8 needs a_scale and b_scale");
     if (!fp8 && K % 64) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd: K=%d must be a multiple of 64", K);
     gg_args a = gg_make(ctx, A, B, offsets, E, N, K, Rcap, C);
@@ -841,11 +887,13 @@ extern "C" moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, 
     a.q_scale = b_scale;
     a.row_prob = row_prob;
     if (epi == MOE_EPI_SWIGLU) {
-        if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, true);
-        else GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, false);
+        if (mx) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, 2);
+        else if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, 1);
+        else GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, 0);
     } else {
-        if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_STORE, false, true);
-        else GG_LAUNCH(GG_FWD, GG_EPI_STORE, false, false);
+        if (mx) GG_LAUNCH(GG_FWD, GG_EPI_STORE, false, 2);
+        else if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_STORE, false, 1);
+        else GG_LAUNCH(GG_FWD, GG_EPI_STORE, false, 0);
     }
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<fwd>");
     return MOE_OK;
@@ -870,7 +918,7 @@ extern "C" moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_dgrad", dC, B, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
     if (!dA) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: dA is NULL");
-    const bool fp8 = dt == MOE_FP8_E4M3;
+    const bool fp8 = dt != MOE_BF16, mx = dt == MOE_MXFP8_E4M3;
     if (fp8 && (!dc_scale || !b_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: fp8 needs dc_scale and b_scale");
     if (!fp8 && N % 64) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad: N=%d must be a multiple of 64", N);
     gg_args a = gg_make(ctx, dC, B, offsets, E, N, K, Rcap, dA);
@@ -880,11 +928,13 @@ extern "C" moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream
     a.row_prob = row_prob;
     a.dprob_part = dprob_part;
     if (Z_saved) {
-        if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, true);
-        else GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, false);
+        if (mx) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 2);
+        else if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 1);
+        else GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 0);
     } else {
-        if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_STORE, false, true);
-        else GG_LAUNCH(GG_DGRAD, GG_EPI_STORE, false, false);
+        if (mx) GG_LAUNCH(GG_DGRAD, GG_EPI_STORE, false, 2);
+        else if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_STORE, false, 1);
+        else GG_LAUNCH(GG_DGRAD, GG_EPI_STORE, false, 0);
     }
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<dgrad>");
     return MOE_OK;
@@ -899,14 +949,14 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     if (st != MOE_OK) return st;
     (void)a_scale;
     (void)dc_scale;
-    if (dt == MOE_FP8_E4M3)
+    if (dt != MOE_BF16)
         MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wgrad: fp8 operands are not built; pass the bf16 tensors");
     if (!dB) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: dB is NULL");
     if (out_dt != MOE_BF16 && out_dt != MOE_F32) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: out_dt must be bf16 or f32");
     gg_args a = gg_make(ctx, dC, A, offsets, E, N, K, Rcap, dB);
     a.accumulate = accumulate ? 1 : 0;
-    if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, false);
-    else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, false);
+    if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 0);
+    else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 0);
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<wgrad>");
     return MOE_OK;
 }

@@ -1,0 +1,162 @@
+"""GPU parity of the MXFP8 path (Sec. 5.3.3): E4M3 elements, 1x32 blocks, E8M0 scales applied by the matrix
+instruction.  Quantisers bit-exact against the oracle; grouped GEMMs against the oracle's own
+quantise-dequantise emulation (tight: accumulation order and bf16 output rounding only) and against the
+full-precision result (6e-2)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+EMU_TOL = 4e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_07685_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(B):
+    c = B.Context(T=16384, k=8, E=256, h=7168, f_max=14336)
+    yield c
+    c.close()
+
+
+def _mxq(B, ctx, X, kind, rows_dev=None):
+    """X: device bf16 [rows, cols] (1x32) or [G, N, K] (32x1).  Returns (codes, e8m0) device tensors."""
+    if kind == B.MX_1x32:
+        rows, cols = X.shape
+        q = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+        e = torch.zeros((rows, cols // 32), dtype=torch.uint8, device="cuda")
+        B.moe_mx_quantize(ctx, X, kind, 1, rows, cols, rows_dev, q, e)
+    else:
+        G, N, K = X.shape
+        q = torch.zeros((G, N, K), dtype=torch.uint8, device="cuda")
+        e = torch.zeros((G, K, N // 32), dtype=torch.uint8, device="cuda")
+        B.moe_mx_quantize(ctx, X, kind, G, N, K, None, q, e)
+    return q, e
+
+
+@pytest.mark.parametrize("rows,cols", [(256, 384), (1000, 32), (77, 7168)])
+def test_mx_quantize_1x32_bit_exact(B, ctx, oracle, rows, cols):
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(rows + cols)
+    Xh = wl.bf16_round((g.standard_normal((rows, cols)) * np.exp(g.normal(size=(rows, cols)) * 2)).astype(np.float32))
+    Xh[3, :32] = 0.0
+    Xh[5, 0] = 448.0
+    Xh[5, 1:32] = 1.0
+    q, e = _mxq(B, ctx, dev_bf16(Xh), B.MX_1x32)
+    torch.cuda.synchronize()
+    qo, eo = oracle.mx_quant_1x32(Xh)
+    assert np.array_equal(e.cpu().numpy(), eo)
+    assert np.array_equal(q.cpu().numpy(), qo)
+    # live-row count on the device: rows beyond it are left alone
+    live = torch.tensor([rows // 2], dtype=torch.int32, device="cuda")
+    q2, e2 = _mxq(B, ctx, dev_bf16(Xh), B.MX_1x32, live)
+    torch.cuda.synchronize()
+    assert np.array_equal(q2.cpu().numpy()[:rows // 2], qo[:rows // 2]) and not q2[rows // 2:].any()
+
+
+def test_mx_quantize_32x1_bit_exact(B, ctx, oracle):
+    from gpu_util import dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    Wh = wl.gaussian_bf16((3, 128, 1028), 0.02, 5, 1)      # K not a multiple of the 1024 columns a workgroup covers
+    Wh[1, 32:64, :100] = 0.0
+    q, e = _mxq(B, ctx, dev_bf16(Wh), B.MX_32x1)
+    torch.cuda.synchronize()
+    qo, eo = oracle.mx_quant_32x1(Wh)
+    assert np.array_equal(e.cpu().numpy(), eo) and np.array_equal(q.cpu().numpy(), qo)
+
+
+def _offsets128(counts):
+    pad = (np.asarray(counts) + 127) // 128 * 128
+    return np.concatenate([[0], np.cumsum(pad)]).astype(np.int32)
+
+
+@pytest.mark.parametrize("counts,N,K,swiglu", [
+    ([300, 0, 257, 1, 700], 512, 256, False),
+    ([130, 90], 256, 128, False),
+    ([513, 128, 5], 768, 384, True),
+    ([300, 0, 257, 1, 700], 512, 256, True),
+])
+def test_mx_grouped_gemm_fwd(B, ctx, oracle, counts, N, K, swiglu):
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, FP8_TOL
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets128(counts)
+    R = int(off[-1])
+    g = np.random.default_rng(N + K)
+    # per-element magnitudes spread over a few octaves so that neighbouring 32-blocks get different scales
+    Ah = wl.bf16_round((g.standard_normal((R, K)) * np.exp(g.uniform(-2, 2, (R, K // 32)).repeat(32, axis=1))).astype(np.float32))
+    for e, c in enumerate(counts):
+        Ah[off[e] + c: off[e + 1]] = 0.0
+    Wh = wl.bf16_round((g.standard_normal((E, N, K)) * 0.05 * np.exp(g.uniform(-2, 2, (E, N, K // 32)).repeat(32, axis=2))).astype(np.float32))
+    qa, ea = _mxq(B, ctx, dev_bf16(Ah), B.MX_1x32)
+    qw, ew = _mxq(B, ctx, dev_bf16(Wh.reshape(E * N, K)), B.MX_1x32)
+    C = torch.full((R, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    Act = torch.full((R, N // 2), float("nan"), dtype=torch.bfloat16, device="cuda") if swiglu else None
+    B.moe_grouped_gemm_fwd(ctx, qa, qw, dev(off), E, N, K, R, B.MXFP8_E4M3, B.EPI_SWIGLU if swiglu else B.EPI_NONE,
+                           ea, ew, C, Act)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    Ad = oracle.mx_dequant(qa.cpu().numpy(), ea.cpu().numpy(), "1x32")
+    Wd = oracle.mx_dequant(qw.cpu().numpy(), ew.cpu().numpy(), "1x32").reshape(E, N, K)
+    emu = oracle.grouped_gemm_nt(Ad, Wd, off)
+    full = oracle.grouped_gemm_nt(Ah, Wh, off)
+    got = host_f64(C)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, emu) <= EMU_TOL
+    assert rel_fro(got, full) <= FP8_TOL
+    if swiglu:
+        assert rel_fro(host_f64(Act), oracle.swiglu(emu)) <= 2 * EMU_TOL
+        assert rel_fro(host_f64(Act), oracle.swiglu(full)) <= FP8_TOL
+
+
+@pytest.mark.parametrize("counts,N,K,bwd", [
+    ([300, 0, 257, 1, 700], 256, 512, False),
+    ([130, 90], 128, 256, False),
+    ([513, 128, 5], 384, 384, True),
+])
+def test_mx_grouped_gemm_dgrad(B, ctx, oracle, counts, N, K, bwd):
+    """Data gradient: dC quantised along N (row-wise), the weights along N too (the column-wise copy)."""
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, FP8_TOL
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets128(counts)
+    R = int(off[-1])
+    g = np.random.default_rng(N * 3 + K)
+    dCh = wl.bf16_round((g.standard_normal((R, N)) * np.exp(g.uniform(-2, 2, (R, N // 32)).repeat(32, axis=1))).astype(np.float32))
+    for e, c in enumerate(counts):
+        dCh[off[e] + c: off[e + 1]] = 0.0
+    Wh = wl.bf16_round((g.standard_normal((E, N, K)) * 0.05 * np.exp(g.uniform(-2, 2, (E, N // 32, K)).repeat(32, axis=1))).astype(np.float32))
+    qd, ed = _mxq(B, ctx, dev_bf16(dCh), B.MX_1x32)
+    qw, ew = _mxq(B, ctx, dev_bf16(Wh), B.MX_32x1)
+    Zh = wl.gaussian_bf16((R, 2 * K), 1.5, 35, K) if bwd else None
+    out = torch.full((R, 2 * K if bwd else K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_dgrad(ctx, qd, qw, dev(off), E, N, K, R, B.MXFP8_E4M3, dev_bf16(Zh) if bwd else None, ed, ew, out)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    dCd = oracle.mx_dequant(qd.cpu().numpy(), ed.cpu().numpy(), "1x32")
+    Wd = oracle.mx_dequant(qw.cpu().numpy(), ew.cpu().numpy(), "32x1")
+    emu = oracle.grouped_gemm_nn(dCd, Wd, off)
+    full = oracle.grouped_gemm_nn(dCh, Wh, off)
+    if bwd:
+        emu, full = oracle.swiglu_bwd(emu, Zh), oracle.swiglu_bwd(full, Zh)
+    got = host_f64(out)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, emu) <= EMU_TOL
+    assert rel_fro(got, full) <= FP8_TOL
+
+
+def test_mx_wgrad_is_refused(B, ctx):
+    from gpu_util import dev
+    A = torch.zeros((128, 128), dtype=torch.uint8, device="cuda")
+    dW = torch.zeros((1, 128, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.MoeError):
+        B.moe_grouped_gemm_wgrad(ctx, A, A, dev(np.array([0, 128], np.int32)), 1, 128, 128, 128, B.MXFP8_E4M3, None, None,
+                                 0, B.BF16, dW)
