@@ -41,7 +41,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C4", help="C1 | MID | C2 | C3 | C4 | C5 (default: the metric's config, C4)")
+    ap.add_argument("--workload", default="C4",
+                    help="C1 | MID | C2 | C3 | C4 | C5 (blockwise fp8) | C6 (MXFP8) (default: the metric's config, C4)")
     ap.add_argument("--variant", default=None, help="load pattern override: uniform | zeros | hot | cv | zipf")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad-f32", action="store_true", help="fp32 weight gradients (default bf16)")
@@ -65,7 +66,7 @@ def describe_call(name, args, st):
         E, N, K, dt = args[4], args[5], args[6], args[8]
         rows = R if E > 1 else T
         kind = name.rsplit("_", 1)[1]
-        tag = "fp8" if dt == 1 else "bf16"
+        tag = {1: "fp8", 3: "mxfp8"}.get(dt, "bf16")
         if kind == "fwd":
             extra = "_swiglu" if args[9] == 1 else ""
         elif kind == "dgrad":
@@ -74,7 +75,7 @@ def describe_call(name, args, st):
             extra = ""
         which = ("fc1" if (kind == "fwd" and K == cfg.h) or (kind != "fwd" and K == cfg.h) else "fc2")
         label = f"{'shared_' if E == 1 else ''}{which}_{kind}{extra}_{tag}"
-        es = 1 if dt == 1 else 2
+        es = 1 if dt in (1, 3) else 2
         if kind == "fwd":      # read A and the weights once, write C (SwiGLU: pre-activations + activation)
             by = rows * K * es + E * N * K * es + rows * N * 2 + (rows * (N // 2) * 2 if extra else 0)
         elif kind == "dgrad":  # read dC and the weights once, write dA (SwiGLU-bwd: read Z, write dZ, both [rows, 2K])
@@ -95,6 +96,11 @@ def describe_call(name, args, st):
     if name == "moe_unpermute_combine_bwd":
         h = args[9]
         return "combine_bwd", None, (T + (2 if args[2] is not None else 1) * R) * h * 2
+    if name == "moe_mx_quantize":
+        block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
+        rows_alg = R if live is not None else rows
+        n = groups * rows_alg * cols
+        return f"mx_quantize_{['1x32', '32x1'][block]}[{groups * rows}x{cols}]", None, n * 3 + n // 32
     if name == "moe_fp8_quantize":
         block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
         rows_alg = R if live is not None else rows          # grouped row tensors: only the routed rows count
@@ -103,7 +109,7 @@ def describe_call(name, args, st):
     return name, None, None
 
 
-HOOKED = ["moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
+HOOKED = ["moe_mx_quantize", "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
           "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
           "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob",
           "moe_scatter_row_dprob"]
@@ -251,7 +257,7 @@ def main():
     achieved = fl_dom / t_dom / 1e9
     gemm_ms = sum(t for t, _, _ in gemm)
     gemm_fl = sum(fl for _, _, fl in gemm)
-    peak = FP8_PEAK_TFLOPS if n_dom.endswith("fp8") else BF16_PEAK_TFLOPS
+    peak = FP8_PEAK_TFLOPS if n_dom.endswith("fp8") else BF16_PEAK_TFLOPS  # ("..._fp8" and "..._mxfp8")
 
     flops = cfg.model_flops()
     out = {
@@ -262,7 +268,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "wall_ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp8_e4m3 (fwd/dgrad GEMMs) + bf16" if cfg.fp8 else "bf16", "data": "synthetic",
+        "dtype": ("mxfp8_e4m3 (fwd/dgrad GEMMs) + bf16" if cfg.mx else
+                  "fp8_e4m3 (fwd/dgrad GEMMs) + bf16" if cfg.fp8 else "bf16"), "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} h={cfg.h} f={cfg.f} E_local={cfg.E} top{cfg.k} "
                                f"shared_f={cfg.shared_f} load={args.variant or cfg.load} "
                                f"wgrad_out={'f32' if args.wgrad_f32 else 'bf16'}"

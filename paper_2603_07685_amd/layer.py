@@ -98,17 +98,26 @@ class LayerState:
             self.row_prob = torch.empty(Rcap, dtype=f32, device=dev)
             self.dprob_parts = (f + 255) // 256
             self.dprob_part = torch.empty((Rcap, self.dprob_parts), dtype=f32, device=dev)
-        self.fp8 = bool(cfg.fp8)
+        self.mx = bool(cfg.mx)                    # MXFP8: 1x32 blocks, E8M0 scales, scaling by the matrix instruction
+        self.fp8 = bool(cfg.fp8) or self.mx       # one-byte operands in the forward / data-gradient GEMMs
+        self.f8dt = B.MXFP8_E4M3 if self.mx else B.FP8_E4M3
         if self.fp8:
             u8 = torch.uint8
+            mx = self.mx
 
-            def codes(rows, cols):   # E4M3 codes + 1x128 scales of a row-indexed tensor
+            def codes(rows, cols):   # E4M3 codes + scales of a row-indexed tensor (1x128 fp32 / 1x32 E8M0)
                 return (torch.empty((rows, cols), dtype=u8, device=dev),
+                        torch.empty((rows, cols // 32), dtype=u8, device=dev) if mx else
                         torch.empty((rows, cols // 128), dtype=f32, device=dev))
 
-            def wcodes(g, rows, cols):  # E4M3 codes + 128x128 scales of a weight stack
+            def wcodes(g, rows, cols):  # codes + scales of a weight stack read along its last dimension (forward)
                 return (torch.empty((g, rows, cols), dtype=u8, device=dev),
+                        torch.empty((g * rows, cols // 32), dtype=u8, device=dev) if mx else
                         torch.empty((g, rows // 128, cols // 128), dtype=f32, device=dev))
+
+            def wcodes_col(g, rows, cols):  # MXFP8 only: the copy quantised along `rows` for the data gradient
+                return (torch.empty((g, rows, cols), dtype=u8, device=dev),
+                        torch.empty((g, cols, rows // 32), dtype=u8, device=dev))
 
             self.qXp, self.sXp = codes(Rcap, h)
             self.qA, self.sA = codes(Rcap, f)
@@ -116,6 +125,9 @@ class LayerState:
             self.qdZ, self.sdZ = codes(Rcap, 2 * f)
             self.qW1, self.sW1 = wcodes(E, 2 * f, h)
             self.qW2, self.sW2 = wcodes(E, h, f)
+            # data-gradient copies: the 128x128 blocks serve both directions; MXFP8 needs a second copy
+            self.qW1d, self.sW1d = wcodes_col(E, 2 * f, h) if mx else (self.qW1, self.sW1)
+            self.qW2d, self.sW2d = wcodes_col(E, h, f) if mx else (self.qW2, self.sW2)
             self.live_rows = self.offsets[E:E + 1]   # device int32: offsets[E]
             if sf:
                 self.qX, self.sX = codes(T, h)
@@ -124,6 +136,8 @@ class LayerState:
                 self.qdZs, self.sdZs = codes(T, 2 * sf)
                 self.qWs1, self.sWs1 = wcodes(1, 2 * sf, h)
                 self.qWs2, self.sWs2 = wcodes(1, h, sf)
+                self.qWs1d, self.sWs1d = wcodes_col(1, 2 * sf, h) if mx else (self.qWs1, self.sWs1)
+                self.qWs2d, self.sWs2d = wcodes_col(1, h, sf) if mx else (self.qWs2, self.sWs2)
         if sf:
             self.off_shared = torch.tensor([0, T], dtype=i32, device=dev)
             self.Zs = torch.empty((T, 2 * sf), dtype=bf, device=dev)
@@ -136,11 +150,19 @@ class LayerState:
 
     # ---- fp8 helpers: quantise a row-indexed tensor (1x128) / a weight stack (128x128) ----------
     def _q_rows(self, X, q, s, rows, cols, live=None):
-        B.moe_fp8_quantize(self.ctx, X, B.Q_1x128, 1, rows, cols, live, q, s)
+        if self.mx:
+            B.moe_mx_quantize(self.ctx, X, B.MX_1x32, 1, rows, cols, live, q, s)
+        else:
+            B.moe_fp8_quantize(self.ctx, X, B.Q_1x128, 1, rows, cols, live, q, s)
 
-    def _q_weight(self, W, q, s):
+    def _q_weight(self, W, q, s, qd=None, sd=None):
+        """Quantise a weight stack for the forward GEMM (and, MXFP8, the second copy for the data gradient)."""
         g, rows, cols = q.shape
-        B.moe_fp8_quantize(self.ctx, W, B.Q_128x128, g, rows, cols, None, q, s)
+        if self.mx:
+            B.moe_mx_quantize(self.ctx, W, B.MX_1x32, 1, g * rows, cols, None, q, s)
+            B.moe_mx_quantize(self.ctx, W, B.MX_32x1, g, rows, cols, None, qd, sd)
+        else:
+            B.moe_fp8_quantize(self.ctx, W, B.Q_128x128, g, rows, cols, None, q, s)
 
     def forward(self):
         return self._forward_fp8() if self.fp8 else self._forward_bf16()
@@ -207,19 +229,20 @@ class LayerState:
         # dX[t] = sum of the k permuted-row gradients (+ the shared expert's dX): the plain-sum unpermute
         B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
 
-    # ---- blockwise fp8 (Sec. 5.3.2): forward and data-gradient GEMMs on E4M3 codes; weights are
-    # re-quantised every step; the weight gradients use the bf16 tensors (fp8 wgrad is not built) ----
+    # ---- fp8 (blockwise, Sec. 5.3.2, or MXFP8, Sec. 5.3.3): forward and data-gradient GEMMs on E4M3 codes;
+    # weights are re-quantised every step (MXFP8: in both directions); the weight gradients use the bf16
+    # tensors (fp8 wgrad is not built) ----
     def _forward_fp8(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
-        F8 = B.FP8_E4M3
+        F8 = self.f8dt
         B.moe_route_topk(c, self.logits, T, cfg.E_router, k, cfg.score, cfg.norm_topk, 1.0,
                          self.topk_idx, self.topk_prob, self.route_counts)
         idx = self.topk_idx if self.forced_idx is None else self.forced_idx
         B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
                       self.row_of, self.src_of, self.offsets, self.counts)
-        self._q_weight(self.W1, self.qW1, self.sW1)
-        self._q_weight(self.W2, self.qW2, self.sW2)
+        self._q_weight(self.W1, self.qW1, self.sW1, self.qW1d, self.sW1d)
+        self._q_weight(self.W2, self.qW2, self.sW2, self.qW2d, self.sW2d)
         self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows)
         row_prob = None
         if self.eq2:
@@ -232,8 +255,8 @@ class LayerState:
                                self.sA, self.sW2, self.O, None)
         if sf:
             o1 = self.off_shared
-            self._q_weight(self.Ws1.view(1, 2 * sf, h), self.qWs1, self.sWs1)
-            self._q_weight(self.Ws2.view(1, h, sf), self.qWs2, self.sWs2)
+            self._q_weight(self.Ws1.view(1, 2 * sf, h), self.qWs1, self.sWs1, self.qWs1d, self.sWs1d)
+            self._q_weight(self.Ws2.view(1, h, sf), self.qWs2, self.sWs2, self.qWs2d, self.sWs2d)
             self._q_rows(self.X, self.qX, self.sX, T, h)
             B.moe_grouped_gemm_fwd(c, self.qX, self.qWs1, o1, 1, 2 * sf, h, T, F8, B.EPI_SWIGLU,
                                    self.sX, self.sWs1, self.Zs, self.As)
@@ -246,7 +269,7 @@ class LayerState:
     def _backward_fp8(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
-        F8, wdt = B.FP8_E4M3, self.wgrad_dt
+        F8, wdt = self.f8dt, self.wgrad_dt
         if self.eq2:
             B.moe_unpermute_combine_bwd(c, self.dY, None, B.BF16, self.row_of, self.src_of, None,
                                         T, k, h, Rcap, self.dO, None)
@@ -256,25 +279,25 @@ class LayerState:
         B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt, self.dW2)
         self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows)
         if self.eq2:
-            B.moe_grouped_gemm_dgrad_weighted(c, self.qdO, self.qW2, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
-                                              self.sW2, self.row_prob, self.dZ, self.dprob_part)
+            B.moe_grouped_gemm_dgrad_weighted(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
+                                              self.sW2d, self.row_prob, self.dZ, self.dprob_part)
             B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
         else:
-            B.moe_grouped_gemm_dgrad(c, self.qdO, self.qW2, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
-                                     self.sW2, self.dZ)
+            B.moe_grouped_gemm_dgrad(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
+                                     self.sW2d, self.dZ)
         B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, wdt,
                                  self.dW1)
         self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows)
-        B.moe_grouped_gemm_dgrad(c, self.qdZ, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, None, self.sdZ, self.sW1,
+        B.moe_grouped_gemm_dgrad(c, self.qdZ, self.qW1d, self.offsets, E, 2 * f, h, Rcap, F8, None, self.sdZ, self.sW1d,
                                  self.dXp)
         if sf:
             o1 = self.off_shared
             B.moe_grouped_gemm_wgrad(c, self.As, self.dY, o1, 1, h, sf, T, B.BF16, None, None, 0, wdt, self.dWs2)
             self._q_rows(self.dY, self.qdY, self.sdY, T, h)
-            B.moe_grouped_gemm_dgrad(c, self.qdY, self.qWs2, o1, 1, h, sf, T, F8, self.Zs, self.sdY, self.sWs2, self.dZs)
+            B.moe_grouped_gemm_dgrad(c, self.qdY, self.qWs2d, o1, 1, h, sf, T, F8, self.Zs, self.sdY, self.sWs2d, self.dZs)
             B.moe_grouped_gemm_wgrad(c, self.X, self.dZs, o1, 1, 2 * sf, h, T, B.BF16, None, None, 0, wdt, self.dWs1)
             self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf)
-            B.moe_grouped_gemm_dgrad(c, self.qdZs, self.qWs1, o1, 1, 2 * sf, h, T, F8, None, self.sdZs, self.sWs1,
+            B.moe_grouped_gemm_dgrad(c, self.qdZs, self.qWs1d, o1, 1, 2 * sf, h, T, F8, None, self.sdZs, self.sWs1d,
                                      self.dXs)
         B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
 

@@ -61,7 +61,8 @@ class MoEConfig:
     load: str              # "router" | "zipf" | "cv" | "zeros" | "hot"
     load_param: float = 0.0
     shared_f: int = 0      # width of the always-on shared expert (0: none)
-    fp8: bool = False
+    fp8: bool = False      # blockwise fp8 (1x128 / 128x128, fp32 scales) forward and data-gradient GEMMs
+    mx: bool = False       # MXFP8 (1x32, E8M0 scales) forward and data-gradient GEMMs
     align: int = 1         # per-expert row padding (fp8 wgrad: 128)
     std: float = 0.02
     seed: int = 1234
@@ -93,6 +94,10 @@ CONFIGS = {
                     norm_topk=True, load="cv", load_param=0.3, shared_f=2048, seed=1238),
     "C5S": MoEConfig("C5-small-fp8", T=1024, h=512, f=256, E=8, k=4, E_router=32, score=SIGMOID,
                      norm_topk=True, load="cv", load_param=0.3, shared_f=256, fp8=True, align=128, seed=1241),
+    "C6S": MoEConfig("C6-small-mxfp8", T=1024, h=512, f=256, E=8, k=4, E_router=32, score=SIGMOID,
+                     norm_topk=True, load="cv", load_param=0.3, shared_f=256, mx=True, align=128, seed=1242),
+    "C6": MoEConfig("C6-dsv3-share-mxfp8", T=16384, h=7168, f=2048, E=32, k=8, E_router=256, score=SIGMOID,
+                    norm_topk=True, load="cv", load_param=0.3, shared_f=2048, mx=True, align=128, seed=1239),
     "C5": MoEConfig("C5-dsv3-share-fp8", T=16384, h=7168, f=2048, E=32, k=8, E_router=256, score=SIGMOID,
                     norm_topk=True, load="cv", load_param=0.3, shared_f=2048, fp8=True, align=128, seed=1239),
 }

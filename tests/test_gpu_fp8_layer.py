@@ -119,3 +119,55 @@ def test_fp8_layer_eq2_per_call(oracle):
         assert v <= FP8_TOL, (k_, v)
     for k_, v in e16.items():
         assert v <= BF16_TOL, (k_, v)
+
+
+def test_mxfp8_layer_per_call(oracle):
+    """C6S: the layer with MXFP8 (1x32, E8M0) forward / data-gradient GEMMs, every element, per call: each GPU
+    result against the oracle applied to the tensors the GPU fed that call (bound 6e-2 for the fp8 calls)."""
+    from gpu_util import rel_fro, BF16_TOL, FP8_TOL
+    from paper_2603_07685_amd import layer as L
+    from paper_2603_07685_amd import workloads as wl
+    cfg = wl.CONFIGS["C6S"]
+    hin = L.host_inputs(cfg)
+    st = L.LayerState(cfg, hin)
+    assert st.mx and st.fp8
+    st.step()
+    torch.cuda.synchronize()
+    assert st.ctx.poll_error() == 0
+    T, k, E = cfg.T, cfg.k, cfg.E
+    idx = st.forced_idx.cpu().numpy()
+    m = oracle.permute_maps(idx, E, 128, st.Rcap)
+    R, off = m.Rtot, m.offsets
+    Xp = oracle.permute_rows(hin["X"], m.src_of[:R], k)
+    assert np.array_equal(_f64(st.Xp)[:R], Xp)
+    # the quantised operands the GEMMs read, bit for bit
+    qo, eo = oracle.mx_quant_1x32(Xp)
+    assert np.array_equal(st.qXp.cpu().numpy()[:R], qo) and np.array_equal(st.sXp.cpu().numpy()[:R], eo)
+    qo, eo = oracle.mx_quant_32x1(hin["W1"])
+    assert np.array_equal(st.qW1d.cpu().numpy(), qo) and np.array_equal(st.sW1d.cpu().numpy(), eo)
+    W1, W2, Ws1, Ws2 = hin["W1"], hin["W2"], hin["Ws1"][None], hin["Ws2"][None]
+    o1 = np.array([0, T], np.int32)
+    prob = st.topk_prob.cpu().numpy().astype(np.float64)
+    Zref = oracle.grouped_gemm_nt(Xp, W1, off)
+    dOg, Zg, dZg = _f64(st.dO)[:R], _f64(st.Z)[:R], _f64(st.dZ)[:R]
+    e8 = {
+        "Z": rel_fro(_f64(st.Z)[:R], Zref), "A": rel_fro(_f64(st.A)[:R], oracle.swiglu(Zref)),
+        "O": rel_fro(_f64(st.O)[:R], oracle.grouped_gemm_nt(_f64(st.A)[:R], W2, off)),
+        "Zs": rel_fro(_f64(st.Zs), oracle.grouped_gemm_nt(hin["X"], Ws1, o1)),
+        "S": rel_fro(_f64(st.S), oracle.grouped_gemm_nt(_f64(st.As), Ws2, o1)),
+        "dZ": rel_fro(dZg, oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, off), Zg)),
+        "dXp": rel_fro(_f64(st.dXp)[:R], oracle.grouped_gemm_nn(dZg, W1, off)),
+        "dZs": rel_fro(_f64(st.dZs), oracle.swiglu_bwd(oracle.grouped_gemm_nn(hin["dY"], Ws2, o1), _f64(st.Zs))),
+        "dXs": rel_fro(_f64(st.dXs), oracle.grouped_gemm_nn(_f64(st.dZs), Ws1, o1)),
+    }
+    e16 = {
+        "Y": rel_fro(_f64(st.Y), oracle.combine(_f64(st.O)[:R], m.row_of, prob, _f64(st.S))),
+        "dW2": rel_fro(_f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off)),
+        "dW1": rel_fro(_f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off)),
+        "dX": rel_fro(_f64(st.dX), oracle.combine(_f64(st.dXp)[:R], m.row_of, None, _f64(st.dXs))),
+    }
+    print("mxfp8:", {k_: f"{v:.2e}" for k_, v in e8.items()}, "bf16:", {k_: f"{v:.2e}" for k_, v in e16.items()})
+    for k_, v in e8.items():
+        assert v <= FP8_TOL, (k_, v)
+    for k_, v in e16.items():
+        assert v <= BF16_TOL, (k_, v)

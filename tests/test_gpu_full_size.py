@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 CASES = [("C2", None), ("C3", None), ("C4", None), ("C4", "zeros"), ("C4", "hot"),
-         ("C5", None), ("C5", "zeros"), ("C5", "hot")]
+         ("C5", None), ("C5", "zeros"), ("C5", "hot"), ("C6", None)]
 
 
 def _f64(t):
@@ -136,6 +136,6 @@ def test_full_size_sampled(oracle, name, variant):
 
     rel = {k_: (np.sqrt(n_ / d_) if d_ > 0 else (0.0 if n_ == 0 else np.inf)) for k_, (n_, d_) in errs.items()}
     print(name, variant, {k_: f"{v:.2e}" for k_, v in rel.items()})
-    fp8_keys = {"Z", "A", "O", "dZ", "dXp", "Zs", "S", "dZs", "dXs"} if cfg.fp8 else set()
+    fp8_keys = {"Z", "A", "O", "dZ", "dXp", "Zs", "S", "dZs", "dXs"} if (cfg.fp8 or cfg.mx) else set()
     for k_, v in rel.items():
         assert v <= (FP8_TOL if k_ in fp8_keys else BF16_TOL), (k_, v)
