@@ -81,7 +81,7 @@ def describe_call(name, args, st):
         elif kind == "dgrad":  # read dC and the weights once, write dA (SwiGLU-bwd: read Z, write dZ, both [rows, 2K])
             by = rows * N * es + E * N * K * es + (rows * 2 * K * 2 * 2 if extra else rows * K * 2)
         else:                  # read A and dC once, write the weight gradients
-            by = rows * (N + K) * 2 + E * N * K * (4 if args[12] == 2 else 2)
+            by = rows * (N + K) * es + E * N * K * (4 if args[12] == 2 else 2)
         return label, 2.0 * rows * N * K, by
     if name == "moe_route_topk":
         Tn, E = args[2], args[3]
@@ -101,6 +101,10 @@ def describe_call(name, args, st):
         rows_alg = R if live is not None else rows
         n = groups * rows_alg * cols
         return f"mx_quantize_{['1x32', '32x1'][block]}[{groups * rows}x{cols}]", None, n * 3 + n // 32
+    if name == "moe_mx_quantize_rowcol":  # read bf16 once, write two one-byte copies and their scales
+        rows, cols, live = args[2], args[3], args[4]
+        n = (R if live is not None else rows) * cols
+        return f"mx_quantize_rowcol[{rows}x{cols}]", None, n * 4 + n // 16
     if name == "moe_fp8_quantize":
         block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
         rows_alg = R if live is not None else rows          # grouped row tensors: only the routed rows count
@@ -109,7 +113,7 @@ def describe_call(name, args, st):
     return name, None, None
 
 
-HOOKED = ["moe_mx_quantize", "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
+HOOKED = ["moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
           "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
           "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob",
           "moe_scatter_row_dprob"]

@@ -154,7 +154,8 @@ moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe_dtype dt,
  * dgrad (N) must also be a multiple of 64 (one 128-byte operand row per stage);
  * wgrad contracts over the expert's rows, any count.  Sizes outside these limits
  * return MOE_ERR_UNSUPPORTED and touch nothing.  wgrad with dt = MOE_FP8_E4M3 is
- * not built and returns MOE_ERR_UNSUPPORTED.
+ * not built and returns MOE_ERR_UNSUPPORTED.  dt = MOE_MXFP8_E4M3 (Sec. 5.3.3) is
+ * described with moe_mx_quantize below; all three calls take it.
  *
  * fwd:   C[r,n] = sum_k A[r,k] * B[e(r),n,k]                    A [Rcap,K], C [Rcap,N]
  *        epi = MOE_EPI_SWIGLU (N = 2f): C holds the pre-activation Z = [gate | up]
@@ -185,9 +186,9 @@ moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const void* dC, co
  *        The contraction length is the expert's (padded) row count, read from
  *        `offsets`; an expert with no rows gets dB_e = 0 (accumulate = 0) or is
  *        left as it is (accumulate != 0: dB += ...).  out_dt: MOE_BF16 or MOE_F32.
- *        fp8: both operands are quantised in 128x1 tiles down the token dimension
- *        (dc_scale [Rcap/128,N], a_scale [Rcap/128,K]); every offsets[e] must then
- *        be a multiple of 128 (moe_permute with align = 128).
+ *        MXFP8: both operands are quantised in 32x1 blocks down the token dimension
+ *        (see moe_mx_quantize); every offsets[e] must then be a multiple of 128
+ *        (moe_permute with align = 128).  Blockwise fp8 is not built for this call.
  */
 moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, const void* dC,
                                   const int32_t* offsets, int E, int N, int K, int64_t Rcap,
@@ -289,21 +290,35 @@ moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X, moe_qbloc
  *   code = nearest E4M3 to x / 2^e, ties to even.
  *   block = MOE_MX_1x32: 32 consecutive elements of a row; X [rows,cols], groups = 1
  *                        (a weight stack [E,N,K] is passed as rows = E*N); e8m0 [rows, cols/32].
- *           MOE_MX_32x1: 32 consecutive rows of a column, for the copy of a weight stack
- *                        [groups, rows = N, cols = K] that the data-gradient GEMM reads with N
- *                        as its contraction; q keeps the [groups,N,K] layout, e8m0 is
- *                        [groups, K, N/32] (the scales of one output column are contiguous).
- *   rows_dev: as in moe_fp8_quantize (1x32 only).
+ *           MOE_MX_32x1: 32 consecutive rows of a column, for a tensor that a GEMM reads with its
+ *                        row index as the contraction: the copy of a weight stack [groups, rows = N,
+ *                        cols = K] for the data gradient, and both operands of the weight gradient
+ *                        (groups = 1, rows = Rcap).  q keeps the layout of X; the scales are stored in
+ *                        units of 128 rows, the step in which the GEMMs walk such a contraction:
+ *                        e8m0 [groups*rows/128, cols, 4], byte j of entry (R, c) = block of rows
+ *                        128 R + 32 j .. + 31 of column c.  rows and cols must be multiples of 128.
+ *   rows_dev: as in moe_fp8_quantize (groups = 1 only).  With 32x1 blocks, whole tiles of 128 rows
+ *   that start below *rows_dev are quantised.
+ * moe_mx_quantize_rowcol makes both copies of X [rows,cols] in one pass over it (Sec. 5.3.3: a
+ * tensor used in two GEMMs with different contraction dimensions needs both; Sec. 5.4.2: one grouped
+ * launch for all experts): (q_row, e8m0_row) as MOE_MX_1x32, (q_col, e8m0_col) as MOE_MX_32x1, bit
+ * for bit.  rows and cols must be multiples of 128.
  * The grouped GEMMs take these with dt = MOE_MXFP8_E4M3: the scale arguments then point to
- * the E8M0 bytes (a_scale / dc_scale: [Rcap, C/32] of the row operand, C its contraction
- * length; b_scale: fwd [E*N, K/32] from MOE_MX_1x32, dgrad [E, K, N/32] from MOE_MX_32x1, together
- * with the matching code tensor), and the scaling is done by the matrix instruction itself.
- * N and K must be multiples of 128.  wgrad is not built for this type.
+ * the E8M0 bytes and the scaling is done by the matrix instruction itself:
+ *   fwd  : A 1x32 codes, a_scale [Rcap, K/32];  B 1x32 codes of [E*N, K], b_scale [E*N, K/32]
+ *   dgrad: dC 1x32 codes, dc_scale [Rcap, N/32]; B 32x1 codes, b_scale [E*N/128, K, 4]
+ *   wgrad: A and dC 32x1 codes, a_scale [Rcap/128, K, 4], dc_scale [Rcap/128, N, 4]; every expert's
+ *          row range must start and end on a multiple of 128 (moe_permute with align = 128),
+ *          otherwise the error word is raised and dB is left untouched.
+ * N and K must be multiples of 128.
  */
 typedef enum { MOE_MX_1x32 = 0, MOE_MX_32x1 = 1 } moe_mxblock;
 moe_status moe_mx_quantize(moe_ctx* ctx, void* stream, const void* X, moe_mxblock block,
                            int groups, int64_t rows, int cols, const int32_t* rows_dev,
                            void* q, uint8_t* e8m0);
+moe_status moe_mx_quantize_rowcol(moe_ctx* ctx, void* stream, const void* X, int64_t rows, int cols,
+                                  const int32_t* rows_dev, void* q_row, uint8_t* e8m0_row,
+                                  void* q_col, uint8_t* e8m0_col);
 
 #ifdef __cplusplus
 }

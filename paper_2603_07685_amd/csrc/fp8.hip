@@ -189,8 +189,9 @@ extern "C" moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X
 //   e = ceil(log2(amax / 448)) from the bits of amax = 1.f * 2^(E-127): e = E - 127 - 8 (+1 if 1.f > 1.75),
 //   clamped to +-127; an all-zero block gets e = 0.  code = nearest E4M3 to x * 2^-e (exact scaling).
 //   1x32 : 4 lanes own one block (8 elements each); a wave reads 1 KB and writes 512 B contiguous.
-//   32x1 : for a weight stack [G,N,K] read with N as the contraction: a lane owns 4 consecutive k of one
-//          32-row block, holds the 32 rows in registers; scales go to [G,K,N/32].
+//   32x1 : blocks of 32 consecutive rows of a column, for a tensor read with its row index as the contraction
+//          (weights in the data gradient, both operands of the weight gradient); made alone or together with
+//          the 1x32 copy in one pass over the input (mx_quant_rowcol_kernel).
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ int mx_exponent(float amax) {
     if (!(amax > 0.0f)) return 0;
@@ -230,40 +231,95 @@ __global__ __launch_bounds__(256) void mx_quant_1x32_kernel(const u32x4_t* __res
     }
 }
 
-// grid.x covers (G * N/32) row blocks x ceil(K/4 / 256) column groups
-__global__ __launch_bounds__(256) void mx_quant_32x1_kernel(const u32x2_t* __restrict__ W, int G, int N, int K,
-                                                            uint32_t* __restrict__ q, uint8_t* __restrict__ e8) {
-    const int kq = K / 4;                               // 4-column groups per row
-    const int cgroups = (kq + 255) / 256;
-    const int64_t blk = blockIdx.x / cgroups;           // (g, n-block)
-    const int c4 = (blockIdx.x % cgroups) * 256 + threadIdx.x;
-    if (c4 >= kq) return;
-    const int nb = N / 32;
-    const int g = (int)(blk / nb), b = (int)(blk % nb);
-    const int64_t row0 = (int64_t)g * N + b * 32;
-    u32x2_t v[32];
-    float m[4] = {0.f, 0.f, 0.f, 0.f};
+// Row- and column-wise copies in one pass (either may be switched off).  A 256-thread workgroup owns a tile of
+// 128 rows x 128 columns; wave w owns its rows 32 w .. 32 w + 31, i.e. one 32-row block of every column.  A lane
+// reads eight 16-byte pieces: piece i is row 4 i + lane / 16, columns 8 (lane % 16) .. + 7.
+//   row-wise  : a 1x32 block is 4 adjacent lanes of one piece (two butterfly steps);
+//   col-wise  : a 32x1 block is the same element of the lane's 8 pieces and of the 4 lanes 16 apart.
+// The column scales of the four waves meet in LDS and leave as one dword per column:
+// e8_col[(row / 128) * cols + col] holds the four 32-row blocks of rows 128 (row / 128) .. + 127, the unit in
+// which the GEMMs walk a contraction over rows.
+__global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
+                                                              const int32_t* __restrict__ rows_dev,
+                                                              u32x2_t* __restrict__ q_row, uint32_t* __restrict__ e8_row,
+                                                              u32x2_t* __restrict__ q_col, uint32_t* __restrict__ e8_col) {
+    __shared__ uint8_t sc[4][128];
+    const int64_t live = rows_dev ? min((int64_t)*rows_dev, rows) : rows;
+    const int ctiles = cols / 128;
+    const int64_t rt = blockIdx.x / ctiles;
+    const int ct = blockIdx.x % ctiles;
+    const int64_t row0 = rt * 128;
+    if (row0 >= live) return;  // uniform over the workgroup
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int vpr = cols / 8;                                       // 16-byte pieces per row
+    const int64_t v0 = (row0 + wave * 32 + (lane >> 4)) * vpr + ct * 16 + (lane & 15);
+    u32x4_t x[8];
 #pragma unroll
-    for (int r = 0; r < 32; ++r) {
-        v[r] = W[(row0 + r) * kq + c4];
-        m[0] = fmaxf(m[0], fabsf(bf16_lo(v[r].x)));
-        m[1] = fmaxf(m[1], fabsf(bf16_hi(v[r].x)));
-        m[2] = fmaxf(m[2], fabsf(bf16_lo(v[r].y)));
-        m[3] = fmaxf(m[3], fabsf(bf16_hi(v[r].y)));
-    }
-    int e[4];
+    for (int i = 0; i < 8; ++i) x[i] = X[v0 + (int64_t)i * 4 * vpr];
+    if (q_row) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        e[i] = mx_exponent(m[i]);
-        e8[((int64_t)g * K + c4 * 4 + i) * nb + b] = (uint8_t)(e[i] + 127);
+        for (int i = 0; i < 8; ++i) {
+            float m = amax8(x[i]);
+            m = fmaxf(m, __shfl_xor(m, 1));
+            m = fmaxf(m, __shfl_xor(m, 2));
+            const int e = mx_exponent(m);
+            u32x2_t o;
+            o.x = mx_cvt4(bf16_lo(x[i].x), bf16_hi(x[i].x), bf16_lo(x[i].y), bf16_hi(x[i].y), e);
+            o.y = mx_cvt4(bf16_lo(x[i].z), bf16_hi(x[i].z), bf16_lo(x[i].w), bf16_hi(x[i].w), e);
+            q_row[v0 + (int64_t)i * 4 * vpr] = o;
+            // the row's four block bytes of this tile, gathered into the first of its 16 lanes
+            const int b = e + 127, base = lane & 48;
+            const uint32_t w = (uint32_t)__shfl(b, base) | ((uint32_t)__shfl(b, base + 4) << 8) |
+                               ((uint32_t)__shfl(b, base + 8) << 16) | ((uint32_t)__shfl(b, base + 12) << 24);
+            if ((lane & 15) == 0) e8_row[((row0 + wave * 32 + 4 * i + (lane >> 4)) * (cols / 32) + ct * 4) >> 2] = w;
+        }
     }
+    if (q_col) {
+        float m[8];
 #pragma unroll
-    for (int r = 0; r < 32; ++r) {
-        int w = 0;
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(v[r].x), -e[0]), ldexpf(bf16_hi(v[r].x), -e[1]), w, false);
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(v[r].y), -e[2]), ldexpf(bf16_hi(v[r].y), -e[3]), w, true);
-        q[(row0 + r) * kq + c4] = (uint32_t)w;
+        for (int c = 0; c < 8; ++c) m[c] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            m[0] = fmaxf(m[0], fabsf(bf16_lo(x[i].x))); m[1] = fmaxf(m[1], fabsf(bf16_hi(x[i].x)));
+            m[2] = fmaxf(m[2], fabsf(bf16_lo(x[i].y))); m[3] = fmaxf(m[3], fabsf(bf16_hi(x[i].y)));
+            m[4] = fmaxf(m[4], fabsf(bf16_lo(x[i].z))); m[5] = fmaxf(m[5], fabsf(bf16_hi(x[i].z)));
+            m[6] = fmaxf(m[6], fabsf(bf16_lo(x[i].w))); m[7] = fmaxf(m[7], fabsf(bf16_hi(x[i].w)));
+        }
+        int e[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            m[c] = fmaxf(m[c], __shfl_xor(m[c], 16));
+            m[c] = fmaxf(m[c], __shfl_xor(m[c], 32));
+            e[c] = mx_exponent(m[c]);
+            if (lane < 16) sc[wave][8 * lane + c] = (uint8_t)(e[c] + 127);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int w0 = 0, w1 = 0;
+            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].x), -e[0]), ldexpf(bf16_hi(x[i].x), -e[1]), w0, false);
+            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].y), -e[2]), ldexpf(bf16_hi(x[i].y), -e[3]), w0, true);
+            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].z), -e[4]), ldexpf(bf16_hi(x[i].z), -e[5]), w1, false);
+            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].w), -e[6]), ldexpf(bf16_hi(x[i].w), -e[7]), w1, true);
+            u32x2_t o = {(uint32_t)w0, (uint32_t)w1};
+            q_col[v0 + (int64_t)i * 4 * vpr] = o;
+        }
+        __syncthreads();
+        if (threadIdx.x < 128) {
+            const int c = threadIdx.x;
+            e8_col[rt * cols + ct * 128 + c] = (uint32_t)sc[0][c] | ((uint32_t)sc[1][c] << 8) | ((uint32_t)sc[2][c] << 16) |
+                                               ((uint32_t)sc[3][c] << 24);
+        }
     }
+}
+
+static moe_status mx_rowcol_launch(moe_ctx* ctx, hipStream_t s, const char* who, const void* X, int64_t rows, int cols,
+                                   const int32_t* rows_dev, void* q_row, uint8_t* e8_row, void* q_col, uint8_t* e8_col) {
+    if (rows % 128 || cols % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: rows and cols must be multiples of 128", who);
+    const int64_t nblk = (rows / 128) * (cols / 128);
+    if (nblk > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: too many tiles", who);
+    hipLaunchKernelGGL(mx_quant_rowcol_kernel, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols, rows_dev,
+                       (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col, (uint32_t*)e8_col);
+    return MOE_OK;
 }
 
 extern "C" moe_status moe_mx_quantize(moe_ctx* ctx, void* stream, const void* X, moe_mxblock block,
@@ -286,17 +342,30 @@ extern "C" moe_status moe_mx_quantize(moe_ctx* ctx, void* stream, const void* X,
             break;
         }
         case MOE_MX_32x1: {
-            if (rows % 32 || cols % 4) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): rows %% 32 or cols %% 4 != 0");
-            if (rows_dev) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): rows_dev is not used for weights");
-            const int64_t nblk = (int64_t)groups * (rows / 32) * ceil_div64(cols / 4, 256);
-            if (nblk > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): too many blocks");
-            hipLaunchKernelGGL(mx_quant_32x1_kernel, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x2_t*)X, groups,
-                               (int)rows, cols, (uint32_t*)q, e8m0);
+            if (rows % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): rows %% 128 != 0");
+            if (groups != 1 && rows_dev) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize(32x1): rows_dev needs groups == 1");
+            moe_status st = mx_rowcol_launch(ctx, s, "moe_mx_quantize(32x1)", X, (int64_t)groups * rows, cols, rows_dev, nullptr,
+                                             nullptr, q, e8m0);
+            if (st != MOE_OK) return st;
             break;
         }
         default:
             MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize: bad block kind");
     }
     MOE_LAUNCH_CHECK(ctx, "moe_mx_quantize");
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_mx_quantize_rowcol(moe_ctx* ctx, void* stream, const void* X, int64_t rows, int cols,
+                                             const int32_t* rows_dev, void* q_row, uint8_t* e8m0_row,
+                                             void* q_col, uint8_t* e8m0_col) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!X || !q_row || !e8m0_row || !q_col || !e8m0_col) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize_rowcol: NULL pointer");
+    if (rows < 0 || cols < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize_rowcol: bad sizes");
+    if (rows == 0) return MOE_OK;
+    moe_status st = mx_rowcol_launch(ctx, (hipStream_t)stream, "moe_mx_quantize_rowcol", X, rows, cols, rows_dev, q_row,
+                                     e8m0_row, q_col, e8m0_col);
+    if (st != MOE_OK) return st;
+    MOE_LAUNCH_CHECK(ctx, "moe_mx_quantize_rowcol");
     return MOE_OK;
 }

@@ -1,7 +1,7 @@
 // Grouped GEMM for the expert MLP (Sec. 2.1.4, 4.3.2), device-initiated (Sec. 4.3.7): one
 // persistent launch per call, every expert's extent is read from `offsets` on the device;
-// forward, data-gradient and weight-gradient (Sec. 4.2.3 "W/D split") in bf16, forward and
-// data-gradient also in blockwise fp8 (Sec. 5.3.2), are instantiations of one kernel.
+// forward, data-gradient and weight-gradient (Sec. 4.2.3 "W/D split") in bf16 and MXFP8 (Sec. 5.3.3),
+// forward and data-gradient also in blockwise fp8 (Sec. 5.3.2), are instantiations of one kernel.
 //
 // The kernel computes OUT[i,j] = sum_c P[i,c] * Q[j,c] on a 256x256 output tile per workgroup
 // (8 wavefronts as 2 x 4, wave tile 128x64 = 4x2 MFMA blocks of 32x32):
@@ -191,8 +191,8 @@ struct gg_args {
 };
 
 // MODE: GG_FWD / GG_DGRAD / GG_WGRAD.  EPI: see enum.  OUT_F32: fp32 output (wgrad only).
-// F8 (fwd and dgrad only): 0 = bf16 operands; 1 = E4M3 codes with fp32 block scales applied in software
-// (blockwise recipe); 2 = E4M3 codes with one E8M0 scale per 32 contraction elements, applied by the matrix
+// F8: 0 = bf16 operands; 1 = E4M3 codes with fp32 block scales applied in software
+// (blockwise recipe, fwd and dgrad only); 2 = E4M3 codes with one E8M0 scale per 32 contraction elements, applied by the matrix
 // instruction itself (MXFP8, Sec. 5.3.3).
 template <int MODE, int EPI, bool OUT_F32, int F8>
 __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     __shared__ int offs[GG_MAX_E + 1];
     __shared__ int tile_start[GG_MAX_E + 1];
 
-    static_assert(!(FP8 && MODE == GG_WGRAD), "fp8 weight gradients are not built");
+    static_assert(!(F8 == 1 && MODE == GG_WGRAD), "blockwise fp8 weight gradients are not built");
     constexpr bool P_CMAJ = (MODE == GG_WGRAD);
     constexpr bool Q_CMAJ = (MODE != GG_FWD);
     constexpr int ES = FP8 ? 1 : 2;            // operand element size
@@ -250,6 +250,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             tile_start[e] = run;
             const int rows = offs[e + 1] - offs[e];
             bad |= rows < 0;
+            // MXFP8 wgrad: a 32-row scale block (and the 128-row stage) must not straddle two experts
+            if (MX && MODE == GG_WGRAD) bad |= (rows & 127) != 0 || (offs[e] & 127) != 0;
             if (MODE == GG_WGRAD) run += tiles_i_w * tiles_j;
             else run += rows > 0 ? ((rows + GG_BM - 1) / GG_BM) * tiles_j : 0;
         }
@@ -404,24 +406,40 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         // LDS with the operands of stage kb (one more 4-byte-per-lane DMA by waves 0..4).
         const int CB = (c_hi - c_lo) / 128;  // contraction blocks = stages
         if (MX) {
-            // one dword = the four E8M0 bytes of a row for this stage (128 contraction elements).  Waves 0..3
-            // fetch the 256 P rows (position layout as below), waves 4..7 the 256 Q rows: position
-            // p' = 64 (wave - 4) + lane holds Q tile row 128 (p' & 1) + (p' >> 1), so a lane finds the rows of its
-            // two column blocks in one 8-byte read.
+            // one dword = the four E8M0 bytes (32-element blocks) of one tile row for this stage of 128 contraction
+            // elements.  Waves 0..3 fetch the 256 P rows (position layout as below), waves 4..7 the 256 Q rows:
+            // position p' = 64 (wave - 4) + lane holds Q tile row 128 (p' & 1) + (p' >> 1), so a lane finds the rows
+            // of its two column blocks in one 8-byte read.
+            // 1x32 copies (contraction along the memory row): [row, C/128] dwords, one step per stage;
+            // 32x1 copies (contraction along the rows): [c/128, columns] dwords, `columns` per stage.
             if (wave < 4) {
                 const int pp = wave * 64 + lane;
                 int64_t r = (int64_t)i0 + (pp >> 7) * 128 + (pp & 3) * 32 + ((pp & 127) >> 2);
-                r = r < a.Rcap ? r : a.Rcap - 1;
-                sc_src = a.p_scale + r * CB;
+                if (MODE == GG_WGRAD) {  // P tile row = output row n
+                    r = r < N ? r : N - 1;
+                    sc_src = a.p_scale + (int64_t)(c_lo >> 7) * N + r;
+                    sc_step = N;
+                } else {
+                    r = r < a.Rcap ? r : a.Rcap - 1;
+                    sc_src = a.p_scale + r * CB;
+                    sc_step = 1;
+                }
             } else {
                 const int pp = (wave - 4) * 64 + lane;
                 const int rho = 128 * (pp & 1) + (pp >> 1);
                 int col = (rho < 128 ? j0 : j1 - 128) + rho;  // output column = weight row (fwd) / weight column (dgrad)
                 col = col < J ? col : J - 1;
-                // fwd: e8m0 [E*N, K/32];  dgrad: e8m0 [E, K, N/32]: in both a row of CB dwords per output column
-                sc_src = a.q_scale + ((int64_t)e * J + col) * CB;
+                if (MODE == GG_FWD) {         // e8m0 [E*N, K/32]
+                    sc_src = a.q_scale + ((int64_t)e * N + col) * CB;
+                    sc_step = 1;
+                } else if (MODE == GG_DGRAD) {  // e8m0 [E*N/128, K, 4]
+                    sc_src = a.q_scale + (int64_t)e * (N >> 7) * K + col;
+                    sc_step = K;
+                } else {                      // e8m0 [Rcap/128, K, 4]
+                    sc_src = a.q_scale + (int64_t)(c_lo >> 7) * K + col;
+                    sc_step = K;
+                }
             }
-            sc_step = 1;
         } else if (FP8) {
             if (wave < 4) {  // row scales: LDS position p = 64 wave + lane holds tile row ...
                 const int pp = wave * 64 + lane;
@@ -449,7 +467,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             const uint32_t off = (idx & 1) ? qo[i] : po[i];
             const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
             const uint32_t dst_wave = wave * (GG_CH * 1024), dst_const = lds_addr((idx & 1) ? sq : sp) + i * 1024;
-            if (MODE == GG_WGRAD) {  // contraction tail of the expert: feed zeros
+            if (MODE == GG_WGRAD && !MX) {  // contraction tail of the expert: feed zeros
                 const int row = c_lo + kt * BKE + (wave * GG_CH + i) * CM_ROWS + cm_row;
                 uint32_t o = off;
                 asm volatile("" : "+v"(o));  // opaque: keeps base + offset from being hoisted as 64-bit lane pointers
@@ -510,9 +528,13 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     const int sl1 = MX ? sl0 + 2 : sl0 + 1;
                     const int s0 = (sl0 ^ fr_swz) * 16, s1 = (sl1 ^ fr_swz) * 16;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {  // P is k-major in both fp8 modes
-                        const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i] + s0), hi = *(const i32x4_t*)(sp + p_rd[i] + s1);
-                        pf8[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    for (int i = 0; i < 4; ++i) {
+                        if (P_CMAJ) {
+                            pf8[i] = lds_read_tr8x32(sp + p_rd[i] + half * 64 * 256, MX ? 32 : 16);
+                        } else {
+                            const i32x4_t lo = *(const i32x4_t*)(sp + p_rd[i] + s0), hi = *(const i32x4_t*)(sp + p_rd[i] + s1);
+                            pf8[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        }
                     }
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
@@ -947,16 +969,23 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     if (!ctx) return MOE_ERR_ARG;
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_wgrad", dC, A, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
-    (void)a_scale;
-    (void)dc_scale;
-    if (dt != MOE_BF16)
-        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wgrad: fp8 operands are not built; pass the bf16 tensors");
+    if (dt == MOE_FP8_E4M3)
+        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wgrad: blockwise fp8 operands are not built; pass the bf16 tensors");
+    const bool mx = dt == MOE_MXFP8_E4M3;
+    if (mx && (!a_scale || !dc_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: MXFP8 needs a_scale and dc_scale");
     if (!dB) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: dB is NULL");
     if (out_dt != MOE_BF16 && out_dt != MOE_F32) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: out_dt must be bf16 or f32");
     gg_args a = gg_make(ctx, dC, A, offsets, E, N, K, Rcap, dB);
     a.accumulate = accumulate ? 1 : 0;
-    if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 0);
-    else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 0);
+    a.p_scale = dc_scale;
+    a.q_scale = a_scale;
+    if (mx) {
+        if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 2);
+        else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 2);
+    } else {
+        if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 0);
+        else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 0);
+    }
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<wgrad>");
     return MOE_OK;
 }

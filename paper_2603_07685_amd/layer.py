@@ -47,7 +47,10 @@ class LayerState:
         T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
         self.sf = sf = cfg.shared_f if shared_f is None else shared_f
         self.align = cfg.align
-        self.Rcap = Rcap = T * k + E * (cfg.align - 1)
+        Rcap = T * k + E * (cfg.align - 1)
+        if cfg.mx:  # the column-wise quantiser and the weight-gradient GEMM walk the rows in steps of 128
+            Rcap = (Rcap + 127) // 128 * 128
+        self.Rcap = Rcap
         self.ctx = B.Context(T, k, max(E, cfg.E_router), h, max(f, sf))
         bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
         dev = "cuda"
@@ -117,12 +120,24 @@ class LayerState:
 
             def wcodes_col(g, rows, cols):  # MXFP8 only: the copy quantised along `rows` for the data gradient
                 return (torch.empty((g, rows, cols), dtype=u8, device=dev),
-                        torch.empty((g, cols, rows // 32), dtype=u8, device=dev))
+                        torch.empty((g * rows // 128, cols, 4), dtype=u8, device=dev))
+
+            def codes_col(rows, cols):  # MXFP8 only: the copy quantised down the rows for the weight gradient
+                if not mx:
+                    return None, None
+                return (torch.empty((rows, cols), dtype=u8, device=dev),
+                        torch.empty((rows // 128, cols, 4), dtype=u8, device=dev))
 
             self.qXp, self.sXp = codes(Rcap, h)
             self.qA, self.sA = codes(Rcap, f)
             self.qdO, self.sdO = codes(Rcap, h)
             self.qdZ, self.sdZ = codes(Rcap, 2 * f)
+            if mx:
+                assert Rcap % 128 == 0 and T % 128 == 0, "MXFP8 weight gradients walk the rows in steps of 128"
+            self.qXpc, self.sXpc = codes_col(Rcap, h)
+            self.qAc, self.sAc = codes_col(Rcap, f)
+            self.qdOc, self.sdOc = codes_col(Rcap, h)
+            self.qdZc, self.sdZc = codes_col(Rcap, 2 * f)
             self.qW1, self.sW1 = wcodes(E, 2 * f, h)
             self.qW2, self.sW2 = wcodes(E, h, f)
             # data-gradient copies: the 128x128 blocks serve both directions; MXFP8 needs a second copy
@@ -134,6 +149,10 @@ class LayerState:
                 self.qAs, self.sAs = codes(T, sf)
                 self.qdY, self.sdY = codes(T, h)
                 self.qdZs, self.sdZs = codes(T, 2 * sf)
+                self.qXc, self.sXc = codes_col(T, h)
+                self.qAsc, self.sAsc = codes_col(T, sf)
+                self.qdYc, self.sdYc = codes_col(T, h)
+                self.qdZsc, self.sdZsc = codes_col(T, 2 * sf)
                 self.qWs1, self.sWs1 = wcodes(1, 2 * sf, h)
                 self.qWs2, self.sWs2 = wcodes(1, h, sf)
                 self.qWs1d, self.sWs1d = wcodes_col(1, 2 * sf, h) if mx else (self.qWs1, self.sWs1)
@@ -149,9 +168,11 @@ class LayerState:
             self.dWs2 = torch.empty((h, sf), dtype=wdt, device=dev)
 
     # ---- fp8 helpers: quantise a row-indexed tensor (1x128) / a weight stack (128x128) ----------
-    def _q_rows(self, X, q, s, rows, cols, live=None):
+    def _q_rows(self, X, q, s, rows, cols, live=None, qc=None, sc=None):
+        """Quantise a row-indexed tensor for the GEMM that contracts along its rows' elements (and, MXFP8, in the
+        same pass the second copy, quantised down the rows, for the weight gradient)."""
         if self.mx:
-            B.moe_mx_quantize(self.ctx, X, B.MX_1x32, 1, rows, cols, live, q, s)
+            B.moe_mx_quantize_rowcol(self.ctx, X, rows, cols, live, q, s, qc, sc)
         else:
             B.moe_fp8_quantize(self.ctx, X, B.Q_1x128, 1, rows, cols, live, q, s)
 
@@ -159,8 +180,7 @@ class LayerState:
         """Quantise a weight stack for the forward GEMM (and, MXFP8, the second copy for the data gradient)."""
         g, rows, cols = q.shape
         if self.mx:
-            B.moe_mx_quantize(self.ctx, W, B.MX_1x32, 1, g * rows, cols, None, q, s)
-            B.moe_mx_quantize(self.ctx, W, B.MX_32x1, g, rows, cols, None, qd, sd)
+            B.moe_mx_quantize_rowcol(self.ctx, W, g * rows, cols, None, q, s, qd, sd)
         else:
             B.moe_fp8_quantize(self.ctx, W, B.Q_128x128, g, rows, cols, None, q, s)
 
@@ -230,8 +250,9 @@ class LayerState:
         B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
 
     # ---- fp8 (blockwise, Sec. 5.3.2, or MXFP8, Sec. 5.3.3): forward and data-gradient GEMMs on E4M3 codes;
-    # weights are re-quantised every step (MXFP8: in both directions); the weight gradients use the bf16
-    # tensors (fp8 wgrad is not built) ----
+    # weights are re-quantised every step (MXFP8: in both directions, one pass); MXFP8 also runs the weight
+    # gradients on one-byte operands, quantised down the token dimension in the same pass as the row-wise
+    # copy; blockwise weight gradients use the bf16 tensors ----
     def _forward_fp8(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
@@ -243,24 +264,24 @@ class LayerState:
                       self.row_of, self.src_of, self.offsets, self.counts)
         self._q_weight(self.W1, self.qW1, self.sW1, self.qW1d, self.sW1d)
         self._q_weight(self.W2, self.qW2, self.sW2, self.qW2d, self.sW2d)
-        self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows)
+        self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows, self.qXpc, self.sXpc)
         row_prob = None
         if self.eq2:
             B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
             row_prob = self.row_prob
         B.moe_grouped_gemm_fwd_weighted(c, self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, B.EPI_SWIGLU,
                                         self.sXp, self.sW1, row_prob, self.Z, self.A)
-        self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows)
+        self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows, self.qAc, self.sAc)
         B.moe_grouped_gemm_fwd(c, self.qA, self.qW2, self.offsets, E, h, f, Rcap, F8, B.EPI_NONE,
                                self.sA, self.sW2, self.O, None)
         if sf:
             o1 = self.off_shared
             self._q_weight(self.Ws1.view(1, 2 * sf, h), self.qWs1, self.sWs1, self.qWs1d, self.sWs1d)
             self._q_weight(self.Ws2.view(1, h, sf), self.qWs2, self.sWs2, self.qWs2d, self.sWs2d)
-            self._q_rows(self.X, self.qX, self.sX, T, h)
+            self._q_rows(self.X, self.qX, self.sX, T, h, None, self.qXc, self.sXc)
             B.moe_grouped_gemm_fwd(c, self.qX, self.qWs1, o1, 1, 2 * sf, h, T, F8, B.EPI_SWIGLU,
                                    self.sX, self.sWs1, self.Zs, self.As)
-            self._q_rows(self.As, self.qAs, self.sAs, T, sf)
+            self._q_rows(self.As, self.qAs, self.sAs, T, sf, None, self.qAsc, self.sAsc)
             B.moe_grouped_gemm_fwd(c, self.qAs, self.qWs2, o1, 1, h, sf, T, F8, B.EPI_NONE,
                                    self.sAs, self.sWs2, self.S, None)
         B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, None if self.eq2 else self.topk_prob,
@@ -276,8 +297,8 @@ class LayerState:
         else:
             B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
                                         T, k, h, Rcap, self.dO, self.dprob)
-        B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt, self.dW2)
-        self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows)
+        self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows, self.qdOc, self.sdOc)
+        self._wgrad(self.A, self.dO, self.qAc, self.sAc, self.qdOc, self.sdOc, self.offsets, E, h, f, Rcap, self.dW2)
         if self.eq2:
             B.moe_grouped_gemm_dgrad_weighted(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
                                               self.sW2d, self.row_prob, self.dZ, self.dprob_part)
@@ -285,21 +306,28 @@ class LayerState:
         else:
             B.moe_grouped_gemm_dgrad(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
                                      self.sW2d, self.dZ)
-        B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, wdt,
-                                 self.dW1)
-        self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows)
+        self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows, self.qdZc, self.sdZc)
+        self._wgrad(self.Xp, self.dZ, self.qXpc, self.sXpc, self.qdZc, self.sdZc, self.offsets, E, 2 * f, h, Rcap, self.dW1)
         B.moe_grouped_gemm_dgrad(c, self.qdZ, self.qW1d, self.offsets, E, 2 * f, h, Rcap, F8, None, self.sdZ, self.sW1d,
                                  self.dXp)
         if sf:
             o1 = self.off_shared
-            B.moe_grouped_gemm_wgrad(c, self.As, self.dY, o1, 1, h, sf, T, B.BF16, None, None, 0, wdt, self.dWs2)
-            self._q_rows(self.dY, self.qdY, self.sdY, T, h)
+            self._q_rows(self.dY, self.qdY, self.sdY, T, h, None, self.qdYc, self.sdYc)
+            self._wgrad(self.As, self.dY, self.qAsc, self.sAsc, self.qdYc, self.sdYc, o1, 1, h, sf, T, self.dWs2)
             B.moe_grouped_gemm_dgrad(c, self.qdY, self.qWs2d, o1, 1, h, sf, T, F8, self.Zs, self.sdY, self.sWs2d, self.dZs)
-            B.moe_grouped_gemm_wgrad(c, self.X, self.dZs, o1, 1, 2 * sf, h, T, B.BF16, None, None, 0, wdt, self.dWs1)
-            self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf)
+            self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf, None, self.qdZsc, self.sdZsc)
+            self._wgrad(self.X, self.dZs, self.qXc, self.sXc, self.qdZsc, self.sdZsc, o1, 1, 2 * sf, h, T, self.dWs1)
             B.moe_grouped_gemm_dgrad(c, self.qdZs, self.qWs1d, o1, 1, 2 * sf, h, T, F8, None, self.sdZs, self.sWs1d,
                                      self.dXs)
         B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
+
+    def _wgrad(self, A, dC, qA, sA, qdC, sdC, offsets, E, N, K, rows, dW):
+        """dW = dC^T A per expert: on the copies quantised down the rows (MXFP8) or on the bf16 tensors (the
+        blockwise recipe has no weight-gradient GEMM here)."""
+        if self.mx:
+            B.moe_grouped_gemm_wgrad(self.ctx, qA, qdC, offsets, E, N, K, rows, B.MXFP8_E4M3, sA, sdC, 0, self.wgrad_dt, dW)
+        else:
+            B.moe_grouped_gemm_wgrad(self.ctx, A, dC, offsets, E, N, K, rows, B.BF16, None, None, 0, self.wgrad_dt, dW)
 
     def step(self):
         self.forward()

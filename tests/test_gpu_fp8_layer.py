@@ -122,7 +122,7 @@ def test_fp8_layer_eq2_per_call(oracle):
 
 
 def test_mxfp8_layer_per_call(oracle):
-    """C6S: the layer with MXFP8 (1x32, E8M0) forward / data-gradient GEMMs, every element, per call: each GPU
+    """C6S: the layer with MXFP8 (1x32, E8M0) forward / data-gradient / weight-gradient GEMMs, every element, per call: each GPU
     result against the oracle applied to the tensors the GPU fed that call (bound 6e-2 for the fp8 calls)."""
     from gpu_util import rel_fro, BF16_TOL, FP8_TOL
     from paper_2603_07685_amd import layer as L
@@ -144,7 +144,12 @@ def test_mxfp8_layer_per_call(oracle):
     qo, eo = oracle.mx_quant_1x32(Xp)
     assert np.array_equal(st.qXp.cpu().numpy()[:R], qo) and np.array_equal(st.sXp.cpu().numpy()[:R], eo)
     qo, eo = oracle.mx_quant_32x1(hin["W1"])
-    assert np.array_equal(st.qW1d.cpu().numpy(), qo) and np.array_equal(st.sW1d.cpu().numpy(), eo)
+    f2, h_ = hin["W1"].shape[1:]
+    col = lambda s_, G, N, K: s_.cpu().numpy().reshape(G, N // 128, K, 4).transpose(0, 2, 1, 3).reshape(G, K, N // 32)
+    assert np.array_equal(st.qW1d.cpu().numpy(), qo) and np.array_equal(col(st.sW1d, E, f2, h_), eo)
+    qo, eo = oracle.mx_quant_32x1(Xp[None])                   # the weight-gradient copy of the permuted tokens
+    assert np.array_equal(st.qXpc.cpu().numpy()[:R], qo[0])
+    assert np.array_equal(col(st.sXpc, 1, st.Rcap, h_)[0, :, :R // 32], eo[0])
     W1, W2, Ws1, Ws2 = hin["W1"], hin["W2"], hin["Ws1"][None], hin["Ws2"][None]
     o1 = np.array([0, T], np.int32)
     prob = st.topk_prob.cpu().numpy().astype(np.float64)
@@ -159,11 +164,13 @@ def test_mxfp8_layer_per_call(oracle):
         "dXp": rel_fro(_f64(st.dXp)[:R], oracle.grouped_gemm_nn(dZg, W1, off)),
         "dZs": rel_fro(_f64(st.dZs), oracle.swiglu_bwd(oracle.grouped_gemm_nn(hin["dY"], Ws2, o1), _f64(st.Zs))),
         "dXs": rel_fro(_f64(st.dXs), oracle.grouped_gemm_nn(_f64(st.dZs), Ws1, o1)),
+        "dW2": rel_fro(_f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off)),
+        "dW1": rel_fro(_f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off)),
+        "dWs2": rel_fro(_f64(st.dWs2), oracle.grouped_gemm_tn(hin["dY"], _f64(st.As), o1)[0]),
+        "dWs1": rel_fro(_f64(st.dWs1), oracle.grouped_gemm_tn(_f64(st.dZs), hin["X"], o1)[0]),
     }
     e16 = {
         "Y": rel_fro(_f64(st.Y), oracle.combine(_f64(st.O)[:R], m.row_of, prob, _f64(st.S))),
-        "dW2": rel_fro(_f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off)),
-        "dW1": rel_fro(_f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off)),
         "dX": rel_fro(_f64(st.dX), oracle.combine(_f64(st.dXp)[:R], m.row_of, None, _f64(st.dXs))),
     }
     print("mxfp8:", {k_: f"{v:.2e}" for k_, v in e8.items()}, "bf16:", {k_: f"{v:.2e}" for k_, v in e16.items()})

@@ -137,5 +137,7 @@ def test_full_size_sampled(oracle, name, variant):
     rel = {k_: (np.sqrt(n_ / d_) if d_ > 0 else (0.0 if n_ == 0 else np.inf)) for k_, (n_, d_) in errs.items()}
     print(name, variant, {k_: f"{v:.2e}" for k_, v in rel.items()})
     fp8_keys = {"Z", "A", "O", "dZ", "dXp", "Zs", "S", "dZs", "dXs"} if (cfg.fp8 or cfg.mx) else set()
+    if cfg.mx:  # MXFP8 runs the weight gradients on one-byte operands too
+        fp8_keys |= {"dW1", "dW2", "dWs2"}
     for k_, v in rel.items():
         assert v <= (FP8_TOL if k_ in fp8_keys else BF16_TOL), (k_, v)

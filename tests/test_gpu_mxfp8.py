@@ -26,6 +26,12 @@ def ctx(B):
     c.close()
 
 
+def _col_scales(e, G, N, K):
+    """Column-wise E8M0 scales as the library stores them, [G*N/128, K, 4], in the oracle's order [G, K, N/32]."""
+    e = e.cpu().numpy() if hasattr(e, "cpu") else e
+    return np.ascontiguousarray(e.reshape(G, N // 128, K, 4).transpose(0, 2, 1, 3).reshape(G, K, N // 32))
+
+
 def _mxq(B, ctx, X, kind, rows_dev=None):
     """X: device bf16 [rows, cols] (1x32) or [G, N, K] (32x1).  Returns (codes, e8m0) device tensors."""
     if kind == B.MX_1x32:
@@ -36,8 +42,8 @@ def _mxq(B, ctx, X, kind, rows_dev=None):
     else:
         G, N, K = X.shape
         q = torch.zeros((G, N, K), dtype=torch.uint8, device="cuda")
-        e = torch.zeros((G, K, N // 32), dtype=torch.uint8, device="cuda")
-        B.moe_mx_quantize(ctx, X, kind, G, N, K, None, q, e)
+        e = torch.zeros((G * N // 128, K, 4), dtype=torch.uint8, device="cuda")
+        B.moe_mx_quantize(ctx, X, kind, G, N, K, rows_dev, q, e)
     return q, e
 
 
@@ -65,12 +71,40 @@ def test_mx_quantize_1x32_bit_exact(B, ctx, oracle, rows, cols):
 def test_mx_quantize_32x1_bit_exact(B, ctx, oracle):
     from gpu_util import dev_bf16
     from paper_2603_07685_amd import workloads as wl
-    Wh = wl.gaussian_bf16((3, 128, 1028), 0.02, 5, 1)      # K not a multiple of the 1024 columns a workgroup covers
+    Wh = wl.gaussian_bf16((3, 256, 1152), 0.02, 5, 1)
     Wh[1, 32:64, :100] = 0.0
     q, e = _mxq(B, ctx, dev_bf16(Wh), B.MX_32x1)
     torch.cuda.synchronize()
     qo, eo = oracle.mx_quant_32x1(Wh)
-    assert np.array_equal(e.cpu().numpy(), eo) and np.array_equal(q.cpu().numpy(), qo)
+    assert np.array_equal(_col_scales(e, 3, 256, 1152), eo) and np.array_equal(q.cpu().numpy(), qo)
+
+
+@pytest.mark.parametrize("rows,cols", [(128, 128), (640, 384), (256, 7168)])
+def test_mx_quantize_rowcol_bit_exact(B, ctx, oracle, rows, cols):
+    """Both copies from one pass over the input: each equal, bit for bit, to the oracle's separate quantisers; with a
+    live-row count on the device, whole 128-row tiles beyond it are left alone."""
+    from gpu_util import dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(rows * 7 + cols)
+    Xh = wl.bf16_round((g.standard_normal((rows, cols)) * np.exp(g.normal(size=(rows, cols)) * 2)).astype(np.float32))
+    Xh[3, :32] = 0.0
+    Xh[32:64, 5] = 0.0
+    Xh[70, 40] = 448.0
+    qr_o, er_o = oracle.mx_quant_1x32(Xh)
+    qc_o, ec_o = oracle.mx_quant_32x1(Xh[None])
+    for live_rows in (None, (rows // 256) * 128):
+        qr = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+        er = torch.zeros((rows, cols // 32), dtype=torch.uint8, device="cuda")
+        qc = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+        ec = torch.zeros((rows // 128, cols, 4), dtype=torch.uint8, device="cuda")
+        live = None if live_rows is None else torch.tensor([live_rows], dtype=torch.int32, device="cuda")
+        B.moe_mx_quantize_rowcol(ctx, dev_bf16(Xh), rows, cols, live, qr, er, qc, ec)
+        torch.cuda.synchronize()
+        n = rows if live_rows is None else live_rows
+        assert np.array_equal(qr.cpu().numpy()[:n], qr_o[:n]) and np.array_equal(er.cpu().numpy()[:n], er_o[:n])
+        assert np.array_equal(qc.cpu().numpy()[:n], qc_o[0, :n])
+        assert np.array_equal(_col_scales(ec, 1, rows, cols)[0, :, :n // 32], ec_o[0, :, :n // 32])
+        assert not qr[n:].any() and not qc[n:].any() and not er[n:].any() and not ec[n // 128:].any()
 
 
 def _offsets128(counts):
@@ -142,7 +176,7 @@ def test_mx_grouped_gemm_dgrad(B, ctx, oracle, counts, N, K, bwd):
     torch.cuda.synchronize()
     assert ctx.poll_error() == 0
     dCd = oracle.mx_dequant(qd.cpu().numpy(), ed.cpu().numpy(), "1x32")
-    Wd = oracle.mx_dequant(qw.cpu().numpy(), ew.cpu().numpy(), "32x1")
+    Wd = oracle.mx_dequant(qw.cpu().numpy(), _col_scales(ew, E, N, K), "32x1")
     emu = oracle.grouped_gemm_nn(dCd, Wd, off)
     full = oracle.grouped_gemm_nn(dCh, Wh, off)
     if bwd:
@@ -153,10 +187,69 @@ def test_mx_grouped_gemm_dgrad(B, ctx, oracle, counts, N, K, bwd):
     assert rel_fro(got, full) <= FP8_TOL
 
 
-def test_mx_wgrad_is_refused(B, ctx):
+@pytest.mark.parametrize("counts,N,K,out_f32,acc", [
+    ([300, 0, 257, 1, 700], 256, 512, False, False),
+    ([130, 90], 128, 256, True, True),
+    ([513, 128, 5], 384, 640, False, True),
+    ([0, 0, 1024], 512, 128, True, False),
+])
+def test_mx_grouped_gemm_wgrad(B, ctx, oracle, counts, N, K, out_f32, acc):
+    """Weight gradient: both operands quantised down the token dimension (32x1), every expert's range a multiple
+    of 128 rows.  An expert without rows gets zeros (or keeps its old value when accumulating)."""
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, FP8_TOL
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets128(counts)
+    R = int(off[-1])
+    g = np.random.default_rng(N * 5 + K)
+    Ah = wl.bf16_round((g.standard_normal((R, K)) * np.exp(g.uniform(-2, 2, (R // 32, K)).repeat(32, axis=0))).astype(np.float32))
+    dCh = wl.bf16_round((g.standard_normal((R, N)) * np.exp(g.uniform(-2, 2, (R // 32, N)).repeat(32, axis=0))).astype(np.float32))
+    for e, c in enumerate(counts):
+        Ah[off[e] + c: off[e + 1]] = 0.0
+        dCh[off[e] + c: off[e + 1]] = 0.0
+    qa, ea = _mxq(B, ctx, dev_bf16(Ah[None]), B.MX_32x1)
+    qd, ed = _mxq(B, ctx, dev_bf16(dCh[None]), B.MX_32x1)
+    odt = torch.float32 if out_f32 else torch.bfloat16
+    old = wl.gaussian_bf16((E, N, K), 1.0, 77, N)
+    dW = torch.tensor(old, dtype=odt, device="cuda") if acc else torch.full((E, N, K), float("nan"), dtype=odt, device="cuda")
+    B.moe_grouped_gemm_wgrad(ctx, qa[0], qd[0], dev(off), E, N, K, R, B.MXFP8_E4M3, ea, ed, int(acc),
+                             B.F32 if out_f32 else B.BF16, dW)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    Ad = oracle.mx_dequant(qa.cpu().numpy(), _col_scales(ea, 1, R, K), "32x1")[0]
+    dCd = oracle.mx_dequant(qd.cpu().numpy(), _col_scales(ed, 1, R, N), "32x1")[0]
+    emu = oracle.grouped_gemm_tn(dCd, Ad, off)
+    full = oracle.grouped_gemm_tn(dCh, Ah, off)
+    got = host_f64(dW)
+    assert np.isfinite(got).all()
+    if acc:
+        got = got - old.astype(np.float64)
+        for e in range(E):
+            if off[e + 1] == off[e]:
+                assert not got[e].any()
+    assert rel_fro(got, emu) <= (EMU_TOL if not acc or out_f32 else 2e-2)   # bf16 accumulate rounds old + new
+    assert rel_fro(got, full) <= FP8_TOL
+
+
+def test_mx_wgrad_rejects_ranges_off_the_block_grid(B, ctx):
+    """Expert ranges that do not start and end on multiples of 128 rows: the call raises the error word and leaves
+    dB alone (a scale block would straddle two experts)."""
+    from gpu_util import dev
+    R = 512
+    q = torch.zeros((R, 128), dtype=torch.uint8, device="cuda")
+    e = torch.full((R // 128, 128, 4), 127, dtype=torch.uint8, device="cuda")
+    dW = torch.full((2, 128, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_wgrad(ctx, q, q, dev(np.array([0, 200, 512], np.int32)), 2, 128, 128, R, B.MXFP8_E4M3, e, e, 0,
+                             B.BF16, dW)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() != 0
+    assert (dW == 3.0).all()
+
+
+def test_blockwise_fp8_wgrad_is_refused(B, ctx):
     from gpu_util import dev
     A = torch.zeros((128, 128), dtype=torch.uint8, device="cuda")
     dW = torch.zeros((1, 128, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(B.MoeError):
-        B.moe_grouped_gemm_wgrad(ctx, A, A, dev(np.array([0, 128], np.int32)), 1, 128, 128, 128, B.MXFP8_E4M3, None, None,
+        B.moe_grouped_gemm_wgrad(ctx, A, A, dev(np.array([0, 128], np.int32)), 1, 128, 128, 128, B.FP8_E4M3, None, None,
                                  0, B.BF16, dW)
