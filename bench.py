@@ -272,8 +272,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "wall_ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("mxfp8_e4m3 (fwd/dgrad GEMMs) + bf16" if cfg.mx else
-                  "fp8_e4m3 (fwd/dgrad GEMMs) + bf16" if cfg.fp8 else "bf16"), "data": "synthetic",
+        "dtype": ("mxfp8_e4m3 (fwd/dgrad/wgrad GEMMs) + bf16 moves" if cfg.mx else
+                  "fp8_e4m3 (fwd/dgrad GEMMs) + bf16 (wgrad, moves)" if cfg.fp8 else "bf16"), "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} h={cfg.h} f={cfg.f} E_local={cfg.E} top{cfg.k} "
                                f"shared_f={cfg.shared_f} load={args.variant or cfg.load} "
                                f"wgrad_out={'f32' if args.wgrad_f32 else 'bf16'}"
