@@ -740,6 +740,23 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         const int c = cl < 128 ? ep_j0 + cl : ep_j1 + cl - 128;           // output column of this lane
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            // SwiGLU backward: the saved pre-activations of the 8 rows this wave writes in this pass are requested
+            // before the accumulators go to LDS, so their latency overlaps the staging and its barrier
+            // (bf16 only: the one-byte variants have no registers to spare for it)
+            constexpr bool Z_EARLY = EPI == GG_EPI_SWIGLU_BWD && !FP8;
+            u32x2_t zg[8], zu[8];
+            if (Z_EARLY) {
+#pragma unroll
+                for (int x8 = 0; x8 < 8; ++x8) {
+                    const int rr = wave * 8 + x8;
+                    const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
+                    if (r < ep_i_end && c < K) {
+                        const int64_t zr = (int64_t)r * 2 * K;
+                        zg[x8] = *(const u32x2_t*)(a.Zsaved + zr + c);
+                        zu[x8] = *(const u32x2_t*)(a.Zsaved + zr + K + c);
+                    }
+                }
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -772,9 +789,13 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     if (c < K) {
                         bf16_t* dZ = (bf16_t*)a.out;
                         const int64_t zr = (int64_t)r * 2 * K;
-                        float gt[4], up[4], dg[4], du[4];
-                        ld4_bf16(a.Zsaved + zr + c, gt);
-                        ld4_bf16(a.Zsaved + zr + K + c, up);
+                        if (!Z_EARLY) {
+                            zg[x8] = *(const u32x2_t*)(a.Zsaved + zr + c);
+                            zu[x8] = *(const u32x2_t*)(a.Zsaved + zr + K + c);
+                        }
+                        const float gt[4] = {bf16_lo(zg[x8].x), bf16_hi(zg[x8].x), bf16_lo(zg[x8].y), bf16_hi(zg[x8].y)};
+                        const float up[4] = {bf16_lo(zu[x8].x), bf16_hi(zu[x8].x), bf16_lo(zu[x8].y), bf16_hi(zu[x8].y)};
+                        float dg[4], du[4];
                         const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
