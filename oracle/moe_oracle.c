@@ -16,6 +16,7 @@
  * What each function follows:
  *   route_topk        Sec. 1.1 (p = Softmax(W_r x), sum over TopK) and Sec. 2.1.2
  *                     item 2 (softmax or sigmoid score, k highest per token).
+ *   route_topk_grouped  Sec. 4.3.4 item 1 (group top-k, scaling) + Sec. 7 (expert bias); see its comment.
  *   permute_maps      Sec. 4.3.3 "Preprocessing": the row-ID map.
  *   permute_rows      Sec. 4.3.3 "Permute" (+ Sec. 5.4.1: zero padding fused in).
  *   grouped_gemm_nt   Sec. 2.1.4 / 4.3.2: one independent GEMM per expert over its
@@ -92,6 +93,92 @@ int FN(orc_route_topk)(const float* logits, int T, int E, int k, int score, int 
     }
     free(s);
     free(taken);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Router, the branches Sec. 4.3.4 item 1 lists for the fused score kernel:  */
+/* group-limited top-k, the load-balancing expert bias (Sec. 7, "auxiliary-  */
+/* loss-free balancing"), score scaling.                                     */
+/* ------------------------------------------------------------------------ */
+/* The paper names these branches and cites their sources; it does not restate them.  Reading taken (the
+ * published DeepSeek-V3 router):
+ *   s_e  = score function of the logits over all E experts (softmax or sigmoid);
+ *   c_e  = s_e + bias_e decides the routing only; the combine weights use s_e;
+ *   the E experts form n_group contiguous groups of E / n_group; a group's score is the sum of its
+ *   k / topk_group largest c; the topk_group best groups stay, all other experts are excluded;
+ *   the k largest c among the remaining experts are selected (slots in selection order);
+ *   weight = s_e of the selected (divided by their sum when norm_topk) * scale.
+ * Ties go to the lower index, for experts and for groups.  n_group = 1 (then topk_group = 1) and
+ * bias = NULL reduce to the plain router.
+ * Precision: the routing decisions are taken on fp32 values, as a fp32 router would (Sec. 5.1 keeps the
+ * router in FP32): s_e is computed in double and rounded to fp32, c_e and the group sums are fp32
+ * additions (group sums in descending order of c).  The weights are then formed in REAL from the fp32
+ * scores. */
+int FN(orc_route_topk_grouped)(const float* logits, const float* bias, int T, int E, int k, int n_group, int topk_group,
+                               int score, int norm_topk, double scale,
+                               int32_t* topk_idx, REAL* topk_prob, int32_t* counts) {
+    if (T < 0 || E < 1 || k < 1 || k > E || n_group < 1 || E % n_group || topk_group < 1 || topk_group > n_group ||
+        k % topk_group || k / topk_group > E / n_group || k > topk_group * (E / n_group))
+        return -1;
+    const int gs = E / n_group, m = k / topk_group;
+    for (int e = 0; e < E; ++e) counts[e] = 0;
+    float* s = (float*)malloc(sizeof(float) * (size_t)E);
+    float* c = (float*)malloc(sizeof(float) * (size_t)E);
+    float* gscore = (float*)malloc(sizeof(float) * (size_t)n_group);
+    char* taken = (char*)malloc((size_t)E);
+    char* gkeep = (char*)malloc((size_t)n_group);
+    for (int t = 0; t < T; ++t) {
+        const float* l = logits + (int64_t)t * E;
+        if (score == 0) {
+            double mx = l[0], den = 0;
+            for (int e = 1; e < E; ++e) if (l[e] > mx) mx = l[e];
+            for (int e = 0; e < E; ++e) den += exp((double)l[e] - mx);
+            for (int e = 0; e < E; ++e) s[e] = (float)(exp((double)l[e] - mx) / den);
+        } else {
+            for (int e = 0; e < E; ++e) s[e] = (float)(1.0 / (1.0 + exp(-(double)l[e])));
+        }
+        for (int e = 0; e < E; ++e) c[e] = bias ? s[e] + bias[e] : s[e];
+        /* group scores: sum of the m largest c of the group, largest first */
+        memset(taken, 0, (size_t)E);
+        for (int g = 0; g < n_group; ++g) {
+            float sum = 0.0f;
+            for (int j = 0; j < m; ++j) {
+                int best = -1;
+                for (int e = g * gs; e < (g + 1) * gs; ++e)
+                    if (!taken[e] && (best < 0 || c[e] > c[best])) best = e;
+                taken[best] = 1;
+                sum = j == 0 ? c[best] : sum + c[best];
+            }
+            gscore[g] = sum;
+        }
+        /* the topk_group best groups */
+        memset(gkeep, 0, (size_t)n_group);
+        for (int j = 0; j < topk_group; ++j) {
+            int best = -1;
+            for (int g = 0; g < n_group; ++g)
+                if (!gkeep[g] && (best < 0 || gscore[g] > gscore[best])) best = g;
+            gkeep[best] = 1;
+        }
+        /* k largest c among the experts of the kept groups */
+        memset(taken, 0, (size_t)E);
+        REAL sel_sum = 0;
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            for (int e = 0; e < E; ++e)
+                if (gkeep[e / gs] && !taken[e] && (best < 0 || c[e] > c[best])) best = e;
+            taken[best] = 1;
+            topk_idx[(int64_t)t * k + j] = best;
+            sel_sum += (REAL)s[best];
+            counts[best] += 1;
+        }
+        for (int j = 0; j < k; ++j) {
+            REAL w = (REAL)s[topk_idx[(int64_t)t * k + j]];
+            if (norm_topk) w /= sel_sum;
+            topk_prob[(int64_t)t * k + j] = w * (REAL)scale;
+        }
+    }
+    free(s); free(c); free(gscore); free(taken); free(gkeep);
     return 0;
 }
 

@@ -96,6 +96,23 @@ def route_topk(logits, k, score=SOFTMAX, norm_topk=False, scale=1.0, prec="f64")
     return idx, prob, counts
 
 
+def route_topk_grouped(logits, k, n_group=1, topk_group=1, bias=None, score=SIGMOID, norm_topk=False, scale=1.0,
+                       prec="f64"):
+    """Group-limited top-k with an optional load-balancing expert bias (Sec. 4.3.4 item 1; Sec. 7)."""
+    logits = _arr(logits, np.float32)
+    T, E = logits.shape
+    b = None if bias is None else _arr(bias, np.float32)
+    idx = np.empty((T, k), np.int32)
+    prob = np.empty((T, k), _dt(prec))
+    counts = np.empty(E, np.int32)
+    rc = _fn("orc_route_topk_grouped", prec)(_p(logits), None if b is None else _p(b), T, E, k, int(n_group),
+                                             int(topk_group), int(score), int(bool(norm_topk)), C.c_double(scale),
+                                             _p(idx), _p(prob), _p(counts))
+    if rc != 0:
+        raise ValueError("orc_route_topk_grouped: bad arguments")
+    return idx, prob, counts
+
+
 def permute_maps(idx, E, align=1, Rcap=None):
     idx = _arr(idx, np.int32)
     T, k = idx.shape

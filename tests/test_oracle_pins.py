@@ -94,6 +94,112 @@ def test_router_k_equals_E_and_ties(oracle):
 
 
 # ---------------------------------------------------------------------------
+# Router branches: group-limited top-k, expert bias, scaling (Sec. 4.3.4 item 1; Sec. 7)
+# ---------------------------------------------------------------------------
+def test_grouped_router_worked_examples(oracle):
+    """Cases small enough to do by hand.  Sigmoid of ln(r) is r / (1 + r): logits ln 1, ln 3, ln(1/3), ln 9 give
+    scores 1/2, 3/4, 1/4, 9/10."""
+    ln = lambda r: float(np.log(r))
+    # E = 4, two groups {0,1} and {2,3}, keep one group, k = 1: group scores (best single) 1/2 and 3/4 -> group 1
+    lg = np.array([[ln(1), ln(1), ln(3), ln(1 / 3)]], np.float32)
+    idx, w, cnt = oracle.route_topk_grouped(lg, 1, 2, 1, None, 1, False, 1.0)
+    assert idx.tolist() == [[2]] and cnt.tolist() == [0, 0, 1, 0]
+    np.testing.assert_allclose(w, [[0.75]], rtol=1e-7)
+    # k = 2 from one group: group scores are sums of two: 1/2 + 1/2 = 1 = 3/4 + 1/4: the tie goes to group 0
+    idx, w, _ = oracle.route_topk_grouped(lg, 2, 2, 1, None, 1, True, 2.0)
+    assert idx.tolist() == [[0, 1]]
+    np.testing.assert_allclose(w, [[1.0, 1.0]], rtol=1e-7)                 # (1/2) / 1 * 2
+    # without the group limit the two best experts are 2 (3/4) and then 0 (1/2, lower index of the tie)
+    idx, w, _ = oracle.route_topk_grouped(lg, 2, 1, 1, None, 1, True, 1.0)
+    assert idx.tolist() == [[2, 0]]
+    np.testing.assert_allclose(w, [[0.6, 0.4]], rtol=1e-7)
+    # the group limit excludes the single best expert when its group loses: scores 9/10, 0 | 1/2, 1/2 with
+    # two per group: sums 0.9 + ~0 < 1
+    lg2 = np.array([[ln(9), -40.0, ln(1), ln(1)]], np.float32)
+    idx, w, _ = oracle.route_topk_grouped(lg2, 2, 2, 1, None, 1, False, 1.0)
+    assert idx.tolist() == [[2, 3]]
+    # a bias decides the selection but not the weight: +1 on expert 3 (score 1/4) makes it the winner, weight 1/4
+    b = np.array([0, 0, 0, 1], np.float32)
+    idx, w, _ = oracle.route_topk_grouped(lg, 1, 1, 1, b, 1, False, 1.0)
+    assert idx.tolist() == [[3]]
+    np.testing.assert_allclose(w, [[0.25]], rtol=1e-7)
+    # ... and moves the group choice too: {2,3} now scores 1.25 + 0.75
+    idx, w, _ = oracle.route_topk_grouped(lg, 2, 2, 1, b, 1, True, 1.0)
+    assert idx.tolist() == [[3, 2]]
+    np.testing.assert_allclose(w, [[0.25, 0.75]], rtol=1e-7)
+    # softmax: odds 1 : 2 : 3 : 4 -> probabilities 0.1 .. 0.4; groups {0,1} = 0.2 (best single), {2,3} = 0.4
+    lg3 = np.log(np.array([[1, 2, 3, 4]], np.float64)).astype(np.float32)
+    idx, w, _ = oracle.route_topk_grouped(lg3, 1, 2, 1, None, 0, False, 1.0)
+    assert idx.tolist() == [[3]]
+    np.testing.assert_allclose(w, [[0.4]], rtol=1e-6)
+    with pytest.raises(ValueError):
+        oracle.route_topk_grouped(lg, 3, 2, 1)          # k not a multiple of topk_group / more than the groups hold
+    with pytest.raises(ValueError):
+        oracle.route_topk_grouped(lg, 2, 3, 1)          # E not divisible into the groups
+
+
+@pytest.mark.parametrize("score", [0, 1])
+def test_grouped_router_reduces_to_plain_router(oracle, score):
+    """One group and no bias (or a constant bias) is the plain router, which has its own pins."""
+    g = _rng(41 + score)
+    logits = g.standard_normal((300, 48)).astype(np.float32)
+    i0, w0, c0 = oracle.route_topk(logits, 6, score, True, 2.5)
+    i1, w1, c1 = oracle.route_topk_grouped(logits, 6, 1, 1, None, score, True, 2.5)
+    assert np.array_equal(i0, i1) and np.array_equal(c0, c1)
+    np.testing.assert_allclose(w1, w0, rtol=3e-7)       # grouped variant rounds the scores to fp32 first
+    # all groups kept: the limit excludes nothing
+    i2, w2, _ = oracle.route_topk_grouped(logits, 6, 6, 6, None, score, True, 2.5)
+    assert np.array_equal(i0, i2)
+    np.testing.assert_array_equal(w1, w2)
+
+
+@pytest.mark.parametrize("score,E,ng,tg,k", [(1, 256, 8, 4, 8), (0, 64, 4, 2, 6), (1, 32, 8, 3, 3), (1, 16, 4, 1, 2)])
+def test_grouped_router_vs_sort_based_statement(oracle, score, E, ng, tg, k):
+    """The same selection stated with library sorts on the same fp32 decision values (independent of the oracle's
+    loops): group score = sum of the k/tg largest c per group, keep the tg best groups, take the k largest c there."""
+    g = _rng(E + k)
+    T = 500
+    logits = (g.standard_normal((T, E)) * 1.5).astype(np.float32)
+    bias = (g.standard_normal(E) * 0.1).astype(np.float32)
+    idx, w, counts = oracle.route_topk_grouped(logits, k, ng, tg, bias, score, True, 2.5)
+    l64 = logits.astype(np.float64)
+    if score == 0:
+        ex = np.exp(l64 - l64.max(1, keepdims=True))
+        s = (ex / ex.sum(1, keepdims=True)).astype(np.float32)
+    else:
+        s = (1.0 / (1.0 + np.exp(-l64))).astype(np.float32)
+    c = s + bias[None, :]                                              # fp32 + fp32
+    gs, m = E // ng, k // tg
+    cg = c.reshape(T, ng, gs)
+    top = -np.sort(-cg, axis=2)[:, :, :m]                              # descending
+    gscore = top[:, :, 0].copy()
+    for j in range(1, m):
+        gscore = gscore + top[:, :, j]                                 # fp32, largest first
+    keep = np.argsort(-gscore, axis=1, kind="stable")[:, :tg]
+    mask = np.zeros((T, ng), bool)
+    np.put_along_axis(mask, keep, True, 1)
+    cm = np.where(np.repeat(mask, gs, axis=1), c, -np.inf)
+    order = np.argsort(-cm, axis=1, kind="stable")[:, :k]
+    assert np.array_equal(order, idx)
+    assert np.all(np.take_along_axis(np.repeat(mask, gs, axis=1), idx.astype(np.int64), 1))
+    assert max(len(set(r)) for r in (idx // gs).tolist()) <= tg          # at most tg groups per token
+    ws = np.take_along_axis(s.astype(np.float64), order, 1)
+    np.testing.assert_allclose(w, 2.5 * ws / ws.sum(1, keepdims=True), rtol=1e-12)
+    np.testing.assert_allclose(w.sum(1), 2.5, rtol=1e-13)
+    assert np.array_equal(counts, np.bincount(order.ravel(), minlength=E)) and counts.sum() == T * k
+    # the bias steers the load: a large bias on one expert puts it into every token's selection, at its unbiased weight
+    big = bias.copy()
+    big[5] += 10.0
+    idx_b, w_b, cnt_b = oracle.route_topk_grouped(logits, k, ng, tg, big, score, False, 1.0)
+    assert cnt_b[5] == T and np.all(idx_b[:, 0] == 5)
+    np.testing.assert_allclose(w_b[:, 0], s[:, 5].astype(np.float64), rtol=1e-12)
+    # f32 instantiation: same decisions
+    idx32, w32, _ = oracle.route_topk_grouped(logits, k, ng, tg, bias, score, True, 2.5, prec="f32")
+    assert np.array_equal(idx32, idx)
+    np.testing.assert_allclose(w32, w, rtol=1e-6)
+
+
+# ---------------------------------------------------------------------------
 # Row-ID map and permute (Sec. 4.3.3 "Preprocessing", "Permute"; Sec. 5.4.1 padding)
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("align", [1, 16, 128])
