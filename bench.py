@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4",
-                    help="C1 | MID | C2 | C3 | C4 | C5 (blockwise fp8) | C6 (MXFP8) (default: the metric's config, C4)")
+                    help="C1 | MID | C2 | C3 | C4 | C4G (C4 behind the group-limited, bias-corrected router) | C5 (blockwise fp8) | C6 (MXFP8) (default: the metric's config, C4)")
     ap.add_argument("--variant", default=None, help="load pattern override: uniform | zeros | hot | cv | zipf")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad-f32", action="store_true", help="fp32 weight gradients (default bf16)")
@@ -83,6 +83,9 @@ def describe_call(name, args, st):
         else:                  # read A and dC once, write the weight gradients
             by = rows * (N + K) * es + E * N * K * (4 if args[12] == 2 else 2)
         return label, 2.0 * rows * N * K, by
+    if name == "moe_route_topk_grouped":
+        Tn, E = args[3], args[4]
+        return "route_topk_grouped", None, Tn * E * 4 + Tn * args[5] * 8 + E * 8
     if name == "moe_route_topk":
         Tn, E = args[2], args[3]
         return "route_topk", None, Tn * E * 4 + Tn * args[4] * 8 + E * 4
@@ -113,7 +116,7 @@ def describe_call(name, args, st):
     return name, None, None
 
 
-HOOKED = ["moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_route_topk", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
+HOOKED = ["moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_route_topk", "moe_route_topk_grouped", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
           "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
           "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob",
           "moe_scatter_row_dprob"]

@@ -101,6 +101,29 @@ moe_status moe_route_topk(moe_ctx* ctx, void* stream, const float* logits, int T
                           int32_t* topk_idx, float* topk_prob, int32_t* counts);
 
 /*
+ * Router with the branches Sec. 4.3.4 item 1 lists for the fused score kernel: group-limited
+ * top-k, the load-balancing expert bias of the auxiliary-loss-free strategy (Sec. 7) and score
+ * scaling.  The paper names them and cites their source; the published DeepSeek-V3 router is taken
+ * as their definition:
+ *   s = score function of the logits over all E experts; c = s + expert_bias (expert_bias [E] fp32
+ *   or NULL) decides the routing, the weights use s; the experts form n_group contiguous groups of
+ *   E / n_group; a group scores the sum of its k / topk_group largest c; only experts of the
+ *   topk_group best groups can be selected; the k largest c among them are selected, slots in
+ *   selection order; topk_prob = s of the selected (/ their sum when norm_topk) * scale.
+ *   Ties go to the lower index (experts and groups).  n_group = topk_group = 1 with no bias selects
+ *   what moe_route_topk selects.
+ * The decisions are taken on fp32 values: s is evaluated in double and rounded to fp32 once, the
+ * bias add and the group sums (largest first) are fp32 additions.
+ * Limits: as moe_route_topk, and n_group <= 64, E % n_group == 0, topk_group <= n_group,
+ * k % topk_group == 0, k / topk_group <= E / n_group.  moe_route_topk_bwd is its backward too (the
+ * bias does not enter the weights).
+ */
+moe_status moe_route_topk_grouped(moe_ctx* ctx, void* stream, const float* logits, const float* expert_bias,
+                                  int T, int E, int k, int n_group, int topk_group,
+                                  moe_score fn, int norm_topk, float scale,
+                                  int32_t* topk_idx, float* topk_prob, int32_t* counts);
+
+/*
  * Backward of the routing weights (Sec. 2.1.2 item 2) with the selection frozen:
  * dlogits[t,:] = sum_s dprob[t,s] * d topk_prob[t,s] / d logits[t,:], for the same score function,
  * normalisation and scale as the forward call.  logits [T,E] fp32, topk_idx [T,k] as returned by

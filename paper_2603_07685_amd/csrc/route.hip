@@ -127,6 +127,192 @@ extern "C" moe_status moe_route_topk(moe_ctx* ctx, void* stream, const float* lo
 }
 
 // ---------------------------------------------------------------------------
+// moe_route_topk_grouped: the other branches of the fused score kernel (Sec. 4.3.4 item 1): group-limited
+// top-k, the load-balancing expert bias (Sec. 7) and score scaling.
+//   s_e = score(logits)_e;  c_e = s_e + bias_e decides, s_e weighs;
+//   group score = sum of the k / topk_group largest c of the group; keep the topk_group best groups;
+//   select the k largest c among the kept groups' experts; ties to the lower index throughout.
+// Same wave-per-token layout as the plain kernel.  The decisions are taken on fp32 values that do not depend
+// on the precision of a fast exponential: the score is evaluated in double and rounded to fp32 once, the bias
+// add and the group sums (largest first) are single fp32 additions.  The group scores are formed by one lane
+// per group from the wave's c values in LDS (each wave has its own region, so program order is all the
+// synchronisation needed); groups and experts are then chosen by the same butterfly arg-max rounds.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+// one round of arg-max over (value desc, index asc) across the wave; idx 0x7fffffff = no candidate
+__device__ __forceinline__ void wave_argmax(float& bv, int& bi) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o);
+        const int oi = __shfl_xor(bi, o);
+        const bool take = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+        if (take) { bv = ov; bi = oi; }
+    }
+}
+
+template <int VPL>
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void route_topk_grouped_kernel(
+    const float* __restrict__ logits, const float* __restrict__ bias, int T, int E, int k, int n_group, int topk_group,
+    int fn, int norm_topk, float scale,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_prob, int32_t* __restrict__ counts) {
+    extern __shared__ int32_t hist[];  // [E] histogram, then ROUTE_WAVES x [E] floats
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    float* cw = (float*)(hist + E) + wave * E;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) hist[e] = 0;
+    __syncthreads();
+    const int gs = E / n_group, m = k / topk_group;
+
+    const int t0 = (blockIdx.x * ROUTE_WAVES + wave) * ROUTE_TOKENS_PER_WAVE;
+    for (int tt = 0; tt < ROUTE_TOKENS_PER_WAVE; ++tt) {
+        const int t = t0 + tt;
+        if (t >= T) break;  // uniform per wave
+        const float* l = logits + (int64_t)t * E;
+        float v[VPL], sc[VPL], c[VPL];
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+            const int e = lane + 64 * j;
+            v[j] = e < E ? l[e] : -INFINITY;
+        }
+        if (fn == MOE_SCORE_SOFTMAX) {
+            float mf = v[0];
+#pragma unroll
+            for (int j = 1; j < VPL; ++j) mf = fmaxf(mf, v[j]);
+            const double mx = (double)wave_max(mf);
+            double part = 0.0;
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) part += (lane + 64 * j < E) ? exp((double)v[j] - mx) : 0.0;
+            const double den = wave_sum_f64(part);
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) sc[j] = (float)(exp((double)v[j] - mx) / den);
+        } else {
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) sc[j] = (float)(1.0 / (1.0 + exp(-(double)v[j])));
+        }
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+            const int e = lane + 64 * j;
+            c[j] = (bias && e < E) ? sc[j] + bias[e] : sc[j];
+        }
+
+        // ---- groups to keep ----
+        uint64_t keep = ~0ull;
+        if (n_group > 1) {
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) {
+                const int e = lane + 64 * j;
+                if (e < E) cw[e] = c[j];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            // lane g: sum of the m largest c of group g, largest first; round r takes the best element that
+            // comes after round r-1's pick in (value desc, index asc) order
+            float gsum = -INFINITY;
+            int gi = 0x7fffffff;
+            if (lane < n_group) {
+                float pv = INFINITY;
+                int pi = -1;
+                gsum = 0.f;
+                for (int r = 0; r < m; ++r) {
+                    float bv = -INFINITY;
+                    int bi = 0x7fffffff;
+                    for (int x = 0; x < gs; ++x) {
+                        const float cv = cw[lane * gs + x];
+                        const bool after = cv < pv || (cv == pv && x > pi);
+                        if (after && (bi == 0x7fffffff || cv > bv)) { bv = cv; bi = x; }
+                    }
+                    gsum = r == 0 ? bv : gsum + bv;
+                    pv = bv;
+                    pi = bi;
+                }
+                gi = lane;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            bool kept = false;
+            for (int r = 0; r < topk_group; ++r) {
+                float bv = kept ? -INFINITY : gsum;
+                int bi = kept ? 0x7fffffff : gi;
+                wave_argmax(bv, bi);
+                if (bi == lane) kept = true;
+            }
+            keep = __ballot(kept);
+        }
+
+        // ---- k rounds of arg-max over c among the kept groups ----
+        uint32_t taken = 0;
+        float my_s = 0.f;
+        int my_idx = 0;
+        for (int it = 0; it < k; ++it) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) {
+                const int e = lane + 64 * j;
+                const bool ok = e < E && !((taken >> j) & 1u) && ((keep >> (e / gs)) & 1ull);
+                if (ok && (bi == 0x7fffffff || c[j] > bv)) { bv = c[j]; bi = e; }
+            }
+            wave_argmax(bv, bi);
+            float sv = 0.f;
+#pragma unroll
+            for (int j = 0; j < VPL; ++j)
+                if (j == (bi >> 6)) sv = sc[j];
+            sv = __shfl(sv, bi & 63);  // the winner's unbiased score
+            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+            if (lane == it) { my_s = sv; my_idx = bi; }
+        }
+        float p = lane < k ? my_s : 0.f;
+        if (norm_topk) p = p / wave_sum(p);
+        if (lane < k) {
+            topk_idx[(int64_t)t * k + lane] = my_idx;
+            topk_prob[(int64_t)t * k + lane] = p * scale;
+            atomicAdd(&hist[my_idx], 1);
+        }
+    }
+    __syncthreads();
+    if (counts)
+        for (int e = threadIdx.x; e < E; e += blockDim.x)
+            if (hist[e]) atomicAdd(&counts[e], hist[e]);
+}
+
+extern "C" moe_status moe_route_topk_grouped(moe_ctx* ctx, void* stream, const float* logits, const float* expert_bias,
+                                             int T, int E, int k, int n_group, int topk_group,
+                                             moe_score fn, int norm_topk, float scale,
+                                             int32_t* topk_idx, float* topk_prob, int32_t* counts) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!logits || !topk_idx || !topk_prob) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk_grouped: NULL pointer");
+    if (T < 0 || E < 1 || E > 64 * ROUTE_MAX_VPL || k < 1 || k > 32 || k > E)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk_grouped: need T>=0, 1<=k<=min(E,32), E<=%d (T=%d E=%d k=%d)",
+                 64 * ROUTE_MAX_VPL, T, E, k);
+    if (n_group < 1 || n_group > 64 || E % n_group || topk_group < 1 || topk_group > n_group || k % topk_group ||
+        k / topk_group > E / n_group)
+        MOE_FAIL(ctx, MOE_ERR_ARG,
+                 "moe_route_topk_grouped: need 1<=topk_group<=n_group<=64, E %% n_group == 0, k %% topk_group == 0 and "
+                 "k/topk_group <= E/n_group (E=%d k=%d n_group=%d topk_group=%d)", E, k, n_group, topk_group);
+    if (fn != MOE_SCORE_SOFTMAX && fn != MOE_SCORE_SIGMOID) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_route_topk_grouped: bad score fn");
+    hipStream_t s = (hipStream_t)stream;
+    if (counts) moe_launch_fill_i32(counts, E, 0, s);
+    if (T == 0) return MOE_OK;
+    const int per_block = ROUTE_WAVES * ROUTE_TOKENS_PER_WAVE;
+    dim3 grid((T + per_block - 1) / per_block), block(ROUTE_WAVES * 64);
+    size_t shm = (size_t)E * sizeof(int32_t) * (1 + ROUTE_WAVES);
+    const int vpl = (E + 63) / 64;
+#define ROUTE_LAUNCH(V)                                                                                            \
+    hipLaunchKernelGGL(route_topk_grouped_kernel<V>, grid, block, shm, s, logits, expert_bias, T, E, k, n_group,   \
+                       topk_group, (int)fn, norm_topk, scale, topk_idx, topk_prob, counts)
+    if (vpl <= 1) ROUTE_LAUNCH(1);
+    else if (vpl <= 2) ROUTE_LAUNCH(2);
+    else if (vpl <= 4) ROUTE_LAUNCH(4);
+    else if (vpl <= 8) ROUTE_LAUNCH(8);
+    else ROUTE_LAUNCH(16);
+#undef ROUTE_LAUNCH
+    MOE_LAUNCH_CHECK(ctx, "route_topk_grouped_kernel");
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------
 // moe_route_topk_bwd: dL/dlogits from dL/dweights with the selection frozen (Sec. 2.1.2 item 2).
 //   w_s = scale * q_s / D,  q_s = score of the s-th selected expert,  D = sum_s q_s (norm_topk) or 1
 //   dq_s = scale * (dw_s / D - [norm] <dw, q> / D^2)

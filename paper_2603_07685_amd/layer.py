@@ -71,6 +71,8 @@ class LayerState:
             if sf:
                 self.Ws1 = wl.device_gaussian_bf16((2 * sf, h), cfg.std, s, 5)
                 self.Ws2 = wl.device_gaussian_bf16((h, sf), cfg.std, s, 6)
+        b = wl.expert_bias(cfg)
+        self.expert_bias = None if b is None else torch.from_numpy(b).cuda()
         # forced routing map (None: the router's own top-k drives the permute)
         forced = wl.routing_map(cfg, variant)
         self.forced_idx = None if forced is None else torch.from_numpy(forced).cuda()
@@ -184,6 +186,16 @@ class LayerState:
         else:
             B.moe_fp8_quantize(self.ctx, W, B.Q_128x128, g, rows, cols, None, q, s)
 
+    def _route(self):
+        cfg = self.cfg
+        if cfg.grouped_router:
+            B.moe_route_topk_grouped(self.ctx, self.logits, self.expert_bias, cfg.T, cfg.E_router, cfg.k, cfg.n_group,
+                                     cfg.topk_group, cfg.score, cfg.norm_topk, cfg.route_scale,
+                                     self.topk_idx, self.topk_prob, self.route_counts)
+        else:
+            B.moe_route_topk(self.ctx, self.logits, cfg.T, cfg.E_router, cfg.k, cfg.score, cfg.norm_topk,
+                             cfg.route_scale, self.topk_idx, self.topk_prob, self.route_counts)
+
     def forward(self):
         return self._forward_fp8() if self.fp8 else self._forward_bf16()
 
@@ -194,8 +206,7 @@ class LayerState:
     def _forward_bf16(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
-        B.moe_route_topk(c, self.logits, T, cfg.E_router, k, cfg.score, cfg.norm_topk, 1.0,
-                         self.topk_idx, self.topk_prob, self.route_counts)
+        self._route()
         idx = self.topk_idx if self.forced_idx is None else self.forced_idx
         B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
                       self.row_of, self.src_of, self.offsets, self.counts)
@@ -257,8 +268,7 @@ class LayerState:
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         F8 = self.f8dt
-        B.moe_route_topk(c, self.logits, T, cfg.E_router, k, cfg.score, cfg.norm_topk, 1.0,
-                         self.topk_idx, self.topk_prob, self.route_counts)
+        self._route()
         idx = self.topk_idx if self.forced_idx is None else self.forced_idx
         B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
                       self.row_of, self.src_of, self.offsets, self.counts)

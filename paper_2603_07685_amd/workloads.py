@@ -66,6 +66,15 @@ class MoEConfig:
     align: int = 1         # per-expert row padding (fp8 wgrad: 128)
     std: float = 0.02
     seed: int = 1234
+    # router branches (group-limited top-k, load-balancing bias, score scaling); the defaults are the plain router
+    n_group: int = 1       # expert groups of E_router / n_group
+    topk_group: int = 1    # groups a token may draw its experts from
+    route_scale: float = 1.0
+    bias_std: float = 0.0  # > 0: a seeded N(0, bias_std^2) per-expert selection bias
+
+    @property
+    def grouped_router(self) -> bool:
+        return self.n_group > 1 or self.bias_std > 0.0
 
     @property
     def R(self) -> int:
@@ -92,6 +101,13 @@ CONFIGS = {
                     norm_topk=False, load="zipf", load_param=1.2, seed=1237),
     "C4": MoEConfig("C4-dsv3-share", T=16384, h=7168, f=2048, E=32, k=8, E_router=256, score=SIGMOID,
                     norm_topk=True, load="cv", load_param=0.3, shared_f=2048, seed=1238),
+    # the C4 layer behind the published DeepSeek-V3 router: 8 groups of 32, 4 kept, bias, weights scaled by 2.5
+    "C4G": MoEConfig("C4-dsv3-share-grouped-router", T=16384, h=7168, f=2048, E=32, k=8, E_router=256, score=SIGMOID,
+                     norm_topk=True, load="cv", load_param=0.3, shared_f=2048, seed=1238,
+                     n_group=8, topk_group=4, route_scale=2.5, bias_std=0.1),
+    "C7S": MoEConfig("C7-small-grouped-router", T=1024, h=512, f=256, E=32, k=4, E_router=32, score=SIGMOID,
+                     norm_topk=True, load="router", shared_f=256, seed=1243,
+                     n_group=4, topk_group=2, route_scale=2.5, bias_std=0.1),
     "C5S": MoEConfig("C5-small-fp8", T=1024, h=512, f=256, E=8, k=4, E_router=32, score=SIGMOID,
                      norm_topk=True, load="cv", load_param=0.3, shared_f=256, fp8=True, align=128, seed=1241),
     "C6S": MoEConfig("C6-small-mxfp8", T=1024, h=512, f=256, E=8, k=4, E_router=32, score=SIGMOID,
@@ -101,6 +117,13 @@ CONFIGS = {
     "C5": MoEConfig("C5-dsv3-share-fp8", T=16384, h=7168, f=2048, E=32, k=8, E_router=256, score=SIGMOID,
                     norm_topk=True, load="cv", load_param=0.3, shared_f=2048, fp8=True, align=128, seed=1239),
 }
+
+
+def expert_bias(cfg: "MoEConfig"):
+    """The seeded selection bias of a config (None when it has none)."""
+    if cfg.bias_std <= 0.0:
+        return None
+    return (rng(cfg.seed, 9).standard_normal(cfg.E_router, dtype=np.float32) * np.float32(cfg.bias_std)).astype(np.float32)
 
 
 def rng(seed: int, stream: int = 0) -> np.random.Generator:

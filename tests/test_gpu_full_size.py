@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 CASES = [("C2", None), ("C3", None), ("C4", None), ("C4", "zeros"), ("C4", "hot"),
-         ("C5", None), ("C5", "zeros"), ("C5", "hot"), ("C6", None)]
+         ("C5", None), ("C5", "zeros"), ("C5", "hot"), ("C6", None), ("C4G", None)]
 
 
 def _f64(t):
@@ -46,7 +46,11 @@ def test_full_size_sampled(oracle, name, variant):
 
     # ---- integer parts, in full ----
     logits = st.logits.cpu().numpy()
-    o_idx, o_prob, o_counts = oracle.route_topk(logits, k, cfg.score, cfg.norm_topk)
+    if cfg.grouped_router:
+        o_idx, o_prob, o_counts = oracle.route_topk_grouped(logits, k, cfg.n_group, cfg.topk_group, wl.expert_bias(cfg),
+                                                            cfg.score, cfg.norm_topk, cfg.route_scale)
+    else:
+        o_idx, o_prob, o_counts = oracle.route_topk(logits, k, cfg.score, cfg.norm_topk, cfg.route_scale)
     assert np.array_equal(st.topk_idx.cpu().numpy(), o_idx)
     assert np.array_equal(st.route_counts.cpu().numpy(), o_counts)
     np.testing.assert_allclose(st.topk_prob.cpu().numpy(), o_prob, rtol=3e-6, atol=1e-9)

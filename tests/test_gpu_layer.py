@@ -8,12 +8,22 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-@pytest.mark.parametrize("name,shared_f", [("C1", 0), ("C1", 64), ("MID", 0)])
+def _oracle_route(oracle, cfg, logits):
+    from paper_2603_07685_amd import workloads as wl
+    if cfg.grouped_router:
+        return oracle.route_topk_grouped(logits, cfg.k, cfg.n_group, cfg.topk_group, wl.expert_bias(cfg), cfg.score,
+                                         cfg.norm_topk, cfg.route_scale)
+    return oracle.route_topk(logits, cfg.k, cfg.score, cfg.norm_topk, cfg.route_scale)
+
+
+@pytest.mark.parametrize("name,shared_f", [("C1", 0), ("C1", 64), ("MID", 0), ("C7S", None)])
 def test_layer_forward_backward_every_element(oracle, name, shared_f):
     from gpu_util import host_f64, rel_fro, BF16_TOL
     from paper_2603_07685_amd import workloads as wl
     from paper_2603_07685_amd import layer as L
     cfg = wl.CONFIGS[name]
+    if shared_f is None:
+        shared_f = cfg.shared_f
     hin = L.host_inputs(cfg, shared_f=shared_f)
     st = L.LayerState(cfg, hin, shared_f=shared_f)
     st.forward()
@@ -22,7 +32,7 @@ def test_layer_forward_backward_every_element(oracle, name, shared_f):
     assert st.ctx.poll_error() == 0
 
     # oracle: same bf16-rounded input bits, fp64 arithmetic
-    o_idx, o_prob, o_counts = oracle.route_topk(hin["logits"], cfg.k, cfg.score, cfg.norm_topk)
+    o_idx, o_prob, o_counts = _oracle_route(oracle, cfg, hin["logits"])
     assert np.array_equal(st.topk_idx.cpu().numpy(), o_idx)
     assert np.array_equal(st.route_counts.cpu().numpy(), o_counts)
     np.testing.assert_allclose(st.topk_prob.cpu().numpy(), o_prob, rtol=2e-6)

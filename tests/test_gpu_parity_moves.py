@@ -90,6 +90,56 @@ def test_route_topk_ties_and_errors(B, ctx, oracle):
         _route(B, ctx, logits, 17, 0, False)                         # k > E
 
 
+@pytest.mark.parametrize("T,E,k,ng,tg,fn,norm,scale,with_bias", [
+    (16384, 256, 8, 8, 4, 1, True, 2.5, True),     # the published DeepSeek-V3 router at the C4 token count
+    (4096, 128, 8, 8, 2, 0, True, 1.0, True),      # softmax scores, 16 experts per group, 4 per kept group
+    (1000, 64, 6, 4, 2, 0, False, 1.0, False),
+    (777, 96, 3, 8, 3, 1, False, 0.5, True),       # 12 per group: groups straddle lanes and register slots
+    (500, 1024, 32, 64, 16, 1, True, 1.0, True),   # maximum E, k and group count
+    (300, 40, 5, 1, 1, 1, True, 1.0, True),        # one group: only the bias differs from the plain router
+    (64, 8, 8, 2, 2, 0, False, 1.0, False),        # k == E
+])
+def test_route_topk_grouped(B, ctx, oracle, T, E, k, ng, tg, fn, norm, scale, with_bias):
+    """Group-limited, bias-corrected selection: indices (slot order included) and counts bit-exact."""
+    from gpu_util import dev
+    g = np.random.default_rng(T + E + k)
+    logits = (g.normal(size=(T, E)) * 1.5).astype(np.float32)
+    bias = (g.normal(size=E) * 0.1).astype(np.float32) if with_bias else None
+    idx = torch.full((T, k), -7, dtype=torch.int32, device="cuda")
+    prob = torch.full((T, k), float("nan"), dtype=torch.float32, device="cuda")
+    counts = torch.full((E,), -7, dtype=torch.int32, device="cuda")
+    B.moe_route_topk_grouped(ctx, dev(logits), None if bias is None else dev(bias), T, E, k, ng, tg, fn, norm, scale,
+                             idx, prob, counts)
+    torch.cuda.synchronize()
+    o_idx, o_prob, o_counts = oracle.route_topk_grouped(logits, k, ng, tg, bias, fn, norm, scale)
+    assert np.array_equal(idx.cpu().numpy(), o_idx)
+    assert np.array_equal(counts.cpu().numpy(), o_counts)
+    np.testing.assert_allclose(prob.cpu().numpy(), o_prob, rtol=2e-6, atol=1e-9)
+
+
+def test_route_topk_grouped_ties_plain_equivalence_and_errors(B, ctx, oracle):
+    from gpu_util import dev
+    g = np.random.default_rng(6)
+    T, E, k = 512, 32, 4
+    logits = g.integers(-2, 3, size=(T, E)).astype(np.float32)          # many exact ties, in experts and in groups
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    prob = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    counts = torch.empty(E, dtype=torch.int32, device="cuda")
+    B.moe_route_topk_grouped(ctx, dev(logits), None, T, E, k, 4, 2, 1, True, 1.0, idx, prob, counts)
+    torch.cuda.synchronize()
+    o_idx, o_prob, o_counts = oracle.route_topk_grouped(logits, k, 4, 2, None, 1, True, 1.0)
+    assert np.array_equal(idx.cpu().numpy(), o_idx) and np.array_equal(counts.cpu().numpy(), o_counts)
+    # one group, no bias: the plain router's selection
+    B.moe_route_topk_grouped(ctx, dev(logits), None, T, E, k, 1, 1, 1, True, 1.0, idx, prob, counts)
+    torch.cuda.synchronize()
+    p_idx, p_prob, p_counts = _route(B, ctx, logits, k, 1, True)
+    assert np.array_equal(idx.cpu().numpy(), p_idx) and np.array_equal(counts.cpu().numpy(), p_counts)
+    np.testing.assert_allclose(prob.cpu().numpy(), p_prob, rtol=2e-6)
+    for bad in [(3, 2), (4, 5), (64, 1)]:                                # E % n_group, topk_group > n_group, k/tg > E/ng
+        with pytest.raises(B.MoeError):
+            B.moe_route_topk_grouped(ctx, dev(logits), None, T, E, k, bad[0], bad[1], 1, True, 1.0, idx, prob, counts)
+
+
 def _permute(B, ctx, X, idx, E, align, dt):
     from gpu_util import dev
     T, k = idx.shape
