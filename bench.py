@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--variant", default=None, help="load pattern override: uniform | zeros | hot | cv | zipf")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad-f32", action="store_true", help="fp32 weight gradients (default bf16)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture the step in a HIP graph and report the time of its replays (field 'graph')")
     ap.add_argument("--eq2", action="store_true",
                     help="memory-efficient permutation: routing weights applied in the fc1 epilogue, plain-sum combine")
     return ap.parse_args()
@@ -292,6 +294,24 @@ def main():
                      "algorithmic_gb": round(by_dom / 1e9, 2) if by_dom else None},
         "kernels": breakdown,
     }
+    if args.graph:
+        # the same step captured once in a HIP graph (no allocation, copy or host sync inside it: every extent is read
+        # on the device) and replayed K times; launch overhead is what differs from the eager figure above
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            st.step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        gms = g0.elapsed_time(g1) / args.steps
+        assert st.ctx.poll_error() == 0
+        out["graph"] = {"ms_per_step": round(gms, 4), "tflops": round(cfg.model_flops() / gms / 1e9, 2)}
     # context only: the vendor dense bf16 GEMM through torch on this very box (boxes differ by +-20 %)
     a_ref = torch.randn((16384, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
     b_ref = torch.randn((4096, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
