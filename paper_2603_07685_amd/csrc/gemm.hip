@@ -133,6 +133,8 @@ __device__ __forceinline__ void stage_barrier() {
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0)
 // s_waitcnt vmcnt(0) only (gfx9 encoding, other counters at their maxima): this wave's DMA loads landed
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// vmcnt(1): everything but the wave's youngest vector-memory operation (the L2 warm-up load, see PF below)
+__device__ __forceinline__ void wait_vm1() { __builtin_amdgcn_s_waitcnt(0x0F71); }
 
 __device__ __forceinline__ float sigmoid_f(float g) { return 1.0f / (1.0f + __expf(-g)); }
 
@@ -198,6 +200,13 @@ template <int MODE, int EPI, bool OUT_F32, int F8>
 __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     constexpr bool FP8 = F8 != 0;  // one-byte operands
     constexpr bool MX = F8 == 2;   // hardware block scales
+#ifndef GG_PF
+#define GG_PF 0
+#endif
+    // L2 warm-up loads (bf16 variants), off by default: measured at the DeepSeek-V3-style shape they gain 3-17 % per
+    // call on all-zero operands (clock not power-limited) and lose 1.5-4.5 % on N(0, 0.02^2) operands, where the
+    // sustained clock is set by power and the extra requests only add to it
+    constexpr bool PF = GG_PF && !FP8;
     // fp8: the block scales of a stage travel with it, behind the P tile: 256 row scales (position
     // 4 * (row % 32) + row / 32 inside each 128-row half, so a lane finds its four rows in one 16-byte
     // read) and, from position 256 on, the two column-block scales (replicated)
@@ -320,6 +329,10 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     int64_t p_step = 0, q_step = 0;  // byte advance per stage
     const float* sc_src = nullptr;   // fp8: this lane's scale for block 0
     int64_t sc_step = 0;             // fp8: element advance per block
+    // L2 warm-up (bf16): see PF below
+    uint32_t pf_off = 0;
+    bool pf_on = false, pf_q = false;
+    int KT_pf = 0;
     int e_hint = 0;
     auto setup_tile = [&](int t) {
         // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
@@ -398,6 +411,18 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 const int gslot = (lane & 7) ^ KM_SWZ(p);
                 qo[i] = (uint32_t)(((int64_t)n * K) * ES + gslot * 16);
             }
+        }
+
+        // ---- L2 warm-up share of this wave (see PF): lanes 8x of DMA chunk (ti & 3) of Q, lanes 8x + 1 of half a
+        //      chunk of P; lanes 8x .. 8x + 7 of a chunk fetch from one 128-byte line ----
+        if (PF) {
+            const int a_in = ti & 3, b_in = tj & 7;
+            const uint32_t qsel = a_in == 0 ? qo[0] : a_in == 1 ? qo[1] : a_in == 2 ? qo[2] : qo[3];
+            const uint32_t psel = (b_in >> 1) == 0 ? po[0] : (b_in >> 1) == 1 ? po[1] : (b_in >> 1) == 2 ? po[2] : po[3];
+            pf_q = (lane & 7) == 0;
+            pf_on = pf_q || ((lane & 7) == 1 && (lane >> 5) == (b_in & 1));
+            pf_off = pf_q ? qsel : psel;
+            KT_pf = (MODE == GG_WGRAD) ? (c_hi - c_lo) / BKE : KT;  // wgrad: only stages that lie wholly inside the expert
         }
 
         // ---- fp8 block scales: s = p_scale[row, kb] * q_scale[block]; per lane 4 rows x 2 column blocks ----
@@ -483,6 +508,23 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 dma4(src, wave * 256, lds_addr(ss));
             }
         };
+
+    // PF: L2 warm-up.  With two stage buffers a stage's DMA can be issued only 3/4 of a stage before it is needed,
+    // less than the latency of an L2 miss, and about one line in five misses (first touch by the XCD).  The
+    // workgroups that run together on an XCD share each P tile 8 ways and each Q tile 4 ways, so each takes
+    // 1/8 and 1/4 of the lines of the stage after next (12 lines per wave) and touches them with one 4-byte
+    // load into a dummy LDS word; the load is the wave's youngest vector-memory operation when the wave waits
+    // for its DMA (wait_vm1), so it never delays the stage being waited for.
+    uint32_t pf_lds = lds_addr(lds_buf + 2 * BUF_BYTES);  // dummy word: the pad behind the two stage buffers
+    asm volatile("" : "+s"(pf_lds));                      // (formed here, in uniform code, not where it is used)
+    auto prefetch = [&](int kt) {
+        if (pf_on) {
+            uint64_t src = (uint64_t)(pf_q ? q_base + kt * q_step : p_base + kt * p_step) + pf_off;
+            asm volatile("" : "+v"(src));  // a per-lane address in vector registers, whatever the compiler can prove
+            const uint32_t m0v = __builtin_amdgcn_readfirstlane(pf_lds);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(m0v), "v"(src) : "memory", "m0");
+        }
+    };
 
     char* const SP[2] = {ldsP0, ldsP1};
     char* const SQ[2] = {ldsQ0, ldsQ1};
@@ -671,6 +713,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                         for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(j + 1, SP[s ^ 1], SQ[s ^ 1], x);
                         if (FP8) issue_scales(j + 1, SS[s ^ 1]);
                     }
+                    const bool pf = PF && j + 2 < KT_pf;
+                    if (pf) prefetch(j + 2);
                     half_a(s, 0);
                     stage_barrier();
                     mma(false, 0, nullptr, nullptr, 0);
@@ -678,7 +722,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     half_a(s, 1);
                     stage_barrier();
                     mma(false, 0, nullptr, nullptr, 1);
-                    wait_vm0();  // stage j+1 landed
+                    if (pf) wait_vm1();  // stage j+1 landed (the warm-up load may still be in flight)
+                    else wait_vm0();
                     stage_barrier();
                 };
                 // (an odd stage count leaves through an exit edge, not a skipped block: the compiler then sees
@@ -697,6 +742,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(1, SP[1], SQ[1], x);
                     if (FP8) issue_scales(1, SS[1]);
                 }
+                if (PF && 2 < KT_pf) prefetch(2);
                 stage_barrier();  // group 0's first slot
                 auto stage1 = [&](int j, int s) {
                     half_a(s, 0);
@@ -704,10 +750,12 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     mma(false, 0, nullptr, nullptr, 0);
                     stage_barrier();
                     half_a(s, 1);
-                    wait_vm0();  // stage j+1 landed
+                    if (PF && j + 2 < KT_pf) wait_vm1();  // stage j+1 landed (issued before the warm-up load of stage j+2)
+                    else wait_vm0();
                     stage_barrier();
                     mma(j + 2 < KT, j + 2, SP[s], SQ[s], 1);
                     if (FP8 && j + 2 < KT) issue_scales(j + 2, SS[s]);
+                    if (PF && j + 3 < KT_pf) prefetch(j + 3);
                     stage_barrier();
                 };
                 for (int j = 0; j < KT; j += 2) {
