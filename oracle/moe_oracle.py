@@ -113,6 +113,36 @@ def route_topk_grouped(logits, k, n_group=1, topk_group=1, bias=None, score=SIGM
     return idx, prob, counts
 
 
+def aux_loss(logits, counts, k, score=SOFTMAX, coeff=1.0):
+    """Load-balancing auxiliary loss and its gradient w.r.t. the logits (Sec. 4.3.4 items 2-3).
+
+    The paper fuses the computation and cites the Switch-Transformer loss without restating it; that published
+    form is taken: loss = coeff * E * sum_e f_e * P_e with f_e = counts[e] / (T k) the fraction of routed
+    (token, slot) pairs that went to expert e and P_e = mean over tokens of p[t, e], where p is the score function
+    over all E experts as Sec. 2.1.2 item 2 defines it (softmax, or sigmoid divided by its sum over the E experts).
+    The counts are constants of the differentiation.  fp64 throughout.  Returns (loss, dloss/dlogits [T,E])."""
+    l = np.asarray(logits, np.float64)
+    c = np.asarray(counts, np.float64)
+    T, E = l.shape
+    if score == SOFTMAX:
+        ex = np.exp(l - l.max(axis=1, keepdims=True))
+        p = ex / ex.sum(axis=1, keepdims=True)
+    else:
+        sg = 1.0 / (1.0 + np.exp(-l))
+        p = sg / sg.sum(axis=1, keepdims=True)
+    f = c / (T * k)
+    P = p.mean(axis=0)
+    loss = coeff * E * float((f * P).sum())
+    # d loss / d p[t,e] = coeff E f_e / T =: w_e, and p depends on the logits of its own token only
+    w = coeff * E * f / T
+    wp = (p * w[None, :]).sum(axis=1, keepdims=True)
+    if score == SOFTMAX:
+        grad = p * (w[None, :] - wp)                       # dp_e/dl_j = p_e ([e = j] - p_j)
+    else:
+        grad = (1.0 - sg) * p * (w[None, :] - wp)          # dp_e/dl_j = sg_j (1 - sg_j) ([e = j] - p_e) / S
+    return loss, grad
+
+
 def permute_maps(idx, E, align=1, Rcap=None):
     idx = _arr(idx, np.int32)
     T, k = idx.shape

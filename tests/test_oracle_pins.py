@@ -200,6 +200,55 @@ def test_grouped_router_vs_sort_based_statement(oracle, score, E, ng, tg, k):
 
 
 # ---------------------------------------------------------------------------
+# Load-balancing auxiliary loss (Sec. 4.3.4 items 2-3)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("score", [0, 1])
+def test_aux_loss_closed_forms_and_gradient(oracle, score):
+    g = _rng(60 + score)
+    T, E, k, coeff = 96, 12, 3, 0.01
+    logits = g.standard_normal((T, E)) * 2.0
+    counts = g.multinomial(T * k, np.ones(E) / E)
+    # 1. equal logits: every probability is 1/E, so sum_e f_e P_e = 1/E whatever the load: loss = coeff
+    loss, grad = oracle.aux_loss(np.full((T, E), 0.7), counts, k, score, coeff)
+    np.testing.assert_allclose(loss, coeff, rtol=1e-13)
+    np.testing.assert_allclose(grad.sum(axis=1), 0.0, atol=1e-18)
+    # 2. perfectly balanced load: f_e = 1/E and the probabilities of a token sum to one: loss = coeff for any logits,
+    #    and the gradient vanishes (the loss does not depend on the logits at all)
+    loss, grad = oracle.aux_loss(logits, np.full(E, T * k // E), k, score, coeff)
+    np.testing.assert_allclose(loss, coeff, rtol=1e-13)
+    np.testing.assert_allclose(grad, 0.0, atol=1e-17)
+    # 3. collapse: every pair on expert 0 and (softmax) all probability there: f_0 = P_0 = 1, loss = coeff E
+    if score == 0:
+        hot = np.zeros((T, E))
+        hot[:, 0] = 60.0
+        c0 = np.zeros(E, np.int64)
+        c0[0] = T * k
+        np.testing.assert_allclose(oracle.aux_loss(hot, c0, k, score, coeff)[0], coeff * E, rtol=1e-12)
+    # 4. the definition written as loops
+    loss, grad = oracle.aux_loss(logits, counts, k, score, coeff)
+    acc = 0.0
+    for e in range(E):
+        Pe = 0.0
+        for t in range(T):
+            v = np.exp(logits[t]) if score == 0 else 1.0 / (1.0 + np.exp(-logits[t]))
+            Pe += v[e] / v.sum()
+        acc += (counts[e] / (T * k)) * (Pe / T)
+    np.testing.assert_allclose(loss, coeff * E * acc, rtol=1e-12)
+    # 5. gradient by central differences (counts held fixed)
+    for _ in range(12):
+        t, e = int(g.integers(T)), int(g.integers(E))
+        d = 1e-5
+        lp, lm = logits.copy(), logits.copy()
+        lp[t, e] += d
+        lm[t, e] -= d
+        fd = (oracle.aux_loss(lp, counts, k, score, coeff)[0] - oracle.aux_loss(lm, counts, k, score, coeff)[0]) / (2 * d)
+        np.testing.assert_allclose(grad[t, e], fd, rtol=2e-6, atol=1e-12)
+    # the most loaded expert has the largest weight w_e, above the p-weighted mean of the weights: descending the
+    # loss lowers its logit for every token
+    assert (grad[:, int(np.argmax(counts))] > 0).all()
+
+
+# ---------------------------------------------------------------------------
 # Row-ID map and permute (Sec. 4.3.3 "Preprocessing", "Permute"; Sec. 5.4.1 padding)
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("align", [1, 16, 128])
