@@ -124,6 +124,25 @@ moe_status moe_route_topk_grouped(moe_ctx* ctx, void* stream, const float* logit
                                   int32_t* topk_idx, float* topk_prob, int32_t* counts);
 
 /*
+ * Load-balancing auxiliary loss and its gradient (Sec. 4.3.4 items 2 and 3: the score computation for the
+ * loss and the loss itself, here one pass over the logits).  The paper cites the loss without restating it;
+ * the Switch-Transformer form is taken:
+ *   p[t,:] = softmax(logits[t,:]), or sigmoid(logits[t,:]) divided by its sum over the E experts
+ *            (the probabilities of Sec. 2.1.2 item 2);
+ *   loss   = coeff * E * sum_e f_e * P_e,  f_e = counts[e] / (T k),  P_e = (1/T) sum_t p[t,e];
+ *   dlogits[t,:] = dloss * d loss / d logits[t,:] with the counts held constant (written, or added to
+ *            what dlogits holds when accumulate != 0, e.g. the result of moe_route_topk_bwd);
+ *            dlogits may be NULL to get the loss only.
+ * counts [E] int32 is the routing histogram the loss balances (the router's counts output), loss one
+ * fp32 on the device.  fp32 arithmetic per token, per-token terms summed in double in a fixed order
+ * (run-to-run identical).  Uses the context's workspace (8 bytes per 32 tokens); calls on one context
+ * must not overlap with each other or with moe_permute.  Limits: T >= 1, E <= 1024.
+ */
+moe_status moe_aux_loss(moe_ctx* ctx, void* stream, const float* logits, const int32_t* counts,
+                        int T, int E, int k, moe_score fn, float coeff, float dloss, int accumulate,
+                        float* loss, float* dlogits);
+
+/*
  * Backward of the routing weights (Sec. 2.1.2 item 2) with the selection frozen:
  * dlogits[t,:] = sum_s dprob[t,s] * d topk_prob[t,s] / d logits[t,:], for the same score function,
  * normalisation and scale as the forward call.  logits [T,E] fp32, topk_idx [T,k] as returned by

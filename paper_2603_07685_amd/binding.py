@@ -28,7 +28,7 @@ EXPORTS = [
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
     "moe_route_topk_bwd", "moe_mx_quantize", "moe_mx_quantize_rowcol",
-    "moe_route_topk_grouped",
+    "moe_route_topk_grouped", "moe_aux_loss",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -66,6 +66,7 @@ def lib() -> C.CDLL:
         L.moe_mx_quantize.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _vp]
         L.moe_mx_quantize_rowcol.argtypes = [_vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_route_topk_grouped.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp]
+        L.moe_aux_loss.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _f, _i, _vp, _vp]
         L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
         L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
@@ -134,6 +135,11 @@ def moe_route_topk_grouped(ctx, logits, expert_bias, T, E, k, n_group, topk_grou
     ctx.check(lib().moe_route_topk_grouped(ctx.h, _stream(), _ptr(logits), _ptr(expert_bias), T, E, k, n_group,
                                            topk_group, fn, int(norm_topk), float(scale), _ptr(topk_idx),
                                            _ptr(topk_prob), _ptr(counts)), "moe_route_topk_grouped")
+
+
+def moe_aux_loss(ctx, logits, counts, T, E, k, fn, coeff, dloss, accumulate, loss, dlogits):
+    ctx.check(lib().moe_aux_loss(ctx.h, _stream(), _ptr(logits), _ptr(counts), T, E, k, fn, float(coeff), float(dloss),
+                                 int(bool(accumulate)), _ptr(loss), _ptr(dlogits)), "moe_aux_loss")
 
 
 def moe_permute(ctx, X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts):

@@ -421,3 +421,116 @@ extern "C" moe_status moe_route_topk_bwd(moe_ctx* ctx, void* stream, const float
     MOE_LAUNCH_CHECK(ctx, "route_topk_bwd_kernel");
     return MOE_OK;
 }
+
+// ---------------------------------------------------------------------------
+// moe_aux_loss: load-balancing auxiliary loss and its gradient (Sec. 4.3.4 items 2 and 3, fused here into one
+// pass over the logits; the Switch-Transformer form the paper cites):
+//   p[t,:] = softmax(l[t,:]) or sigmoid(l[t,:]) / sum_j sigmoid(l[t,j])           (Sec. 2.1.2 item 2)
+//   loss   = coeff E sum_e f_e P_e,  f_e = counts[e] / (T k),  P_e = (1/T) sum_t p[t,e]
+//          = sum_t <w, p[t,:]>,      w_e = coeff E counts[e] / (T^2 k)
+//   dl[t,j] = g p_j (w_j - <w, p>) (softmax),  g (1 - sg_j) p_j (w_j - <w, p>) (sigmoid),  g = dloss
+// so both the loss and the gradient need only per-token quantities: one wavefront per token in the router's
+// register layout; the per-token terms are summed in double, per workgroup, into the context's workspace and a
+// one-wave kernel adds the partial sums in a fixed order (run-to-run identical, no floating-point atomics).
+// ---------------------------------------------------------------------------
+template <int VPL>
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void aux_loss_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ counts, int T, int E, int fn, float wscale, float g,
+    int accumulate, float* __restrict__ dlogits, double* __restrict__ partial) {
+    extern __shared__ float wsh[];  // [E] weights, then ROUTE_WAVES doubles
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) wsh[e] = wscale * (float)counts[e];
+    __syncthreads();
+    float w[VPL];
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) w[j] = lane + 64 * j < E ? wsh[lane + 64 * j] : 0.f;
+    double acc = 0.0;
+    const int t0 = (blockIdx.x * ROUTE_WAVES + wave) * ROUTE_TOKENS_PER_WAVE;
+    for (int tt = 0; tt < ROUTE_TOKENS_PER_WAVE; ++tt) {
+        const int t = t0 + tt;
+        if (t >= T) break;  // uniform per wave
+        const float* l = logits + (int64_t)t * E;
+        float v[VPL], p[VPL], sg[VPL];
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) v[j] = lane + 64 * j < E ? l[lane + 64 * j] : -INFINITY;
+        float part = 0.f;
+        if (fn == MOE_SCORE_SOFTMAX) {
+            float m = v[0];
+#pragma unroll
+            for (int j = 1; j < VPL; ++j) m = fmaxf(m, v[j]);
+            m = wave_max(m);
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) { p[j] = lane + 64 * j < E ? expf(v[j] - m) : 0.f; part += p[j]; }
+        } else {
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) { sg[j] = lane + 64 * j < E ? 1.f / (1.f + expf(-v[j])) : 0.f; p[j] = sg[j]; part += p[j]; }
+        }
+        const float inv = 1.f / wave_sum(part);
+        float d = 0.f;
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) { p[j] *= inv; d += w[j] * p[j]; }
+        d = wave_sum(d);  // <w, p[t,:]>
+        acc += (double)d;
+        if (dlogits) {
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) {
+                const int e = lane + 64 * j;
+                if (e < E) {
+                    float gr = g * p[j] * (w[j] - d);
+                    if (fn != MOE_SCORE_SOFTMAX) gr *= 1.f - sg[j];
+                    float* o = dlogits + (int64_t)t * E + e;
+                    *o = accumulate ? *o + gr : gr;
+                }
+            }
+        }
+    }
+    double* wpart = (double*)(wsh + ((E + 1) & ~1));
+    if (lane == 0) wpart[wave] = acc;  // every lane holds the same sum
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double sum = 0.0;
+        for (int i = 0; i < ROUTE_WAVES; ++i) sum += wpart[i];
+        partial[blockIdx.x] = sum;
+    }
+}
+
+__global__ __launch_bounds__(64) void aux_loss_sum_kernel(const double* __restrict__ partial, int n, float* __restrict__ loss) {
+    double a = 0.0;
+    for (int i = threadIdx.x; i < n; i += 64) a += partial[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+    if (threadIdx.x == 0) *loss = (float)a;
+}
+
+extern "C" moe_status moe_aux_loss(moe_ctx* ctx, void* stream, const float* logits, const int32_t* counts,
+                                   int T, int E, int k, moe_score fn, float coeff, float dloss, int accumulate,
+                                   float* loss, float* dlogits) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!logits || !counts || !loss) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_aux_loss: NULL pointer");
+    if (T < 1 || E < 1 || E > 64 * ROUTE_MAX_VPL || k < 1)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_aux_loss: need T>=1, 1<=E<=%d, k>=1 (T=%d E=%d k=%d)", 64 * ROUTE_MAX_VPL, T, E, k);
+    if (fn != MOE_SCORE_SOFTMAX && fn != MOE_SCORE_SIGMOID) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_aux_loss: bad score fn");
+    const int per_block = ROUTE_WAVES * ROUTE_TOKENS_PER_WAVE;
+    const int nblocks = (T + per_block - 1) / per_block;
+    if (MOE_WS_RESERVED + (size_t)nblocks * sizeof(double) > ctx->ws_bytes)
+        MOE_FAIL(ctx, MOE_ERR_WORKSPACE, "moe_aux_loss: workspace %zu B < %zu B", ctx->ws_bytes,
+                 MOE_WS_RESERVED + (size_t)nblocks * sizeof(double));
+    hipStream_t s = (hipStream_t)stream;
+    double* partial = (double*)((char*)ctx->ws + MOE_WS_RESERVED);
+    const float wscale = (float)((double)coeff * E / ((double)T * T * k));
+    const size_t shm = (size_t)((E + 1) & ~1) * sizeof(float) + ROUTE_WAVES * sizeof(double);
+    const int vpl = (E + 63) / 64;
+#define AUX_LAUNCH(V)                                                                                                \
+    hipLaunchKernelGGL(aux_loss_kernel<V>, dim3(nblocks), dim3(ROUTE_WAVES * 64), shm, s, logits, counts, T, E, (int)fn, \
+                       wscale, dloss, accumulate, dlogits, partial)
+    if (vpl <= 1) AUX_LAUNCH(1);
+    else if (vpl <= 2) AUX_LAUNCH(2);
+    else if (vpl <= 4) AUX_LAUNCH(4);
+    else if (vpl <= 8) AUX_LAUNCH(8);
+    else AUX_LAUNCH(16);
+#undef AUX_LAUNCH
+    hipLaunchKernelGGL(aux_loss_sum_kernel, dim3(1), dim3(64), 0, s, partial, nblocks, loss);
+    MOE_LAUNCH_CHECK(ctx, "aux_loss_kernel");
+    return MOE_OK;
+}

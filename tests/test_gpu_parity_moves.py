@@ -140,6 +140,49 @@ def test_route_topk_grouped_ties_plain_equivalence_and_errors(B, ctx, oracle):
             B.moe_route_topk_grouped(ctx, dev(logits), None, T, E, k, bad[0], bad[1], 1, True, 1.0, idx, prob, counts)
 
 
+@pytest.mark.parametrize("T,E,k,fn", [
+    (16384, 256, 8, 1),      # C4 router shape
+    (16384, 128, 8, 0),      # C3
+    (1000, 37, 5, 0),        # ragged
+    (333, 1024, 32, 1),      # maximum E
+    (1, 8, 2, 0),            # a single token
+])
+def test_aux_loss_and_gradient(B, ctx, oracle, T, E, k, fn):
+    """Loss and d loss / d logits against the fp64 oracle; the gradient also accumulated onto an existing tensor;
+    two runs give identical bits (fixed summation order)."""
+    from gpu_util import dev
+    g = np.random.default_rng(T + E + k)
+    logits = (g.normal(size=(T, E)) * 1.5).astype(np.float32)
+    counts = g.multinomial(T * k, g.dirichlet(np.ones(E) * 2.0)).astype(np.int32)
+    coeff, dloss = 1e-2, 0.7
+    ref_loss, ref_grad = oracle.aux_loss(logits, counts, k, fn, coeff)
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    dl = torch.full((T, E), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_aux_loss(ctx, dev(logits), dev(counts), T, E, k, fn, coeff, dloss, 0, loss, dl)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    got = dl.cpu().numpy().astype(np.float64)
+    assert abs(loss.item() - ref_loss) <= 2e-6 * abs(ref_loss)
+    assert np.abs(got - dloss * ref_grad).max() <= 2e-5 * np.abs(dloss * ref_grad).max() + 1e-12
+    # accumulate onto an existing gradient; loss only (dlogits NULL); bit-identical repeat
+    base = g.normal(size=(T, E)).astype(np.float32)
+    dl2 = dev(base)
+    loss2 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.moe_aux_loss(ctx, dev(logits), dev(counts), T, E, k, fn, coeff, dloss, 1, loss2, dl2)
+    loss3 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.moe_aux_loss(ctx, dev(logits), dev(counts), T, E, k, fn, coeff, dloss, 0, loss3, None)
+    torch.cuda.synchronize()
+    assert torch.equal(loss2, loss) and torch.equal(loss3, loss)
+    np.testing.assert_allclose(dl2.cpu().numpy(), base + dl.cpu().numpy(), rtol=1e-6, atol=1e-9)   # fused multiply-add allowed
+    # balanced load: the loss is coeff whatever the logits, the gradient vanishes
+    if (T * k) % E == 0:
+        bal = np.full(E, T * k // E, np.int32)
+        B.moe_aux_loss(ctx, dev(logits), dev(bal), T, E, k, fn, coeff, 1.0, 0, loss, dl)
+        torch.cuda.synchronize()
+        assert abs(loss.item() - coeff) <= 2e-6 * coeff
+        assert dl.abs().max().item() <= 1e-9
+
+
 def _permute(B, ctx, X, idx, E, align, dt):
     from gpu_util import dev
     T, k = idx.shape
