@@ -100,7 +100,8 @@ def describe_call(name, args, st):
         return ("combine" if args[4] is not None else "unpermute_sum_dx"), None, (R + T) * h * 2 + T * k * 8 + (T * h * 2 if res else 0)
     if name == "moe_unpermute_combine_bwd":
         h = args[9]
-        return "combine_bwd", None, (T + (2 if args[2] is not None else 1) * R) * h * 2
+        # read dY, read O (when dprob is wanted), write dO (unless only dprob is wanted)
+        return "combine_bwd", None, (T + ((args[2] is not None) + (args[11] is not None)) * R) * h * 2
     if name == "moe_mx_quantize":
         block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
         rows_alg = R if live is not None else rows
@@ -110,6 +111,11 @@ def describe_call(name, args, st):
         rows, cols, live = args[2], args[3], args[4]
         n = (R if live is not None else rows) * cols
         return f"mx_quantize_rowcol[{rows}x{cols}]", None, n * 4 + n // 16
+    if name == "moe_mx_quantize_rowcol_gather":  # read the source rows, write two one-byte copies and their scales
+        cols = args[7]
+        n = R * cols
+        src = "tokens" if args[1] is st.X else "dY"
+        return f"mx_quantize_gather_{src}[{args[6]}x{cols}]", None, T * cols * 2 + n * 2 + n // 16 + R * 4
     if name == "moe_fp8_quantize":
         block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
         rows_alg = R if live is not None else rows          # grouped row tensors: only the routed rows count
@@ -118,7 +124,7 @@ def describe_call(name, args, st):
     return name, None, None
 
 
-HOOKED = ["moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_route_topk", "moe_route_topk_grouped", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
+HOOKED = ["moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_mx_quantize_rowcol_gather", "moe_route_topk", "moe_route_topk_grouped", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
           "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
           "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob",
           "moe_scatter_row_dprob"]
@@ -154,6 +160,21 @@ def timed_step_with_events(st, torch, sync=True):
     return recs, evs
 
 
+def _rows_of(st, torch, which, rows):
+    """Rows of the permuted tokens / of the combine's backward for the CPU baseline's inputs: as stored, or, when the
+    layer quantises them straight from X / dY and keeps no bf16 copy, gathered here through the row map."""
+    t = getattr(st, which)
+    if t is not None:
+        return t[rows]
+    s = st.src_of[rows].long()
+    tok = torch.div(s.clamp(min=0), st.cfg.k, rounding_mode="floor")
+    x = (st.X if which == "Xp" else st.dY)[tok].float()
+    if which == "dO" and not st.eq2:
+        x = x * st.topk_prob.reshape(-1)[s.clamp(min=0)][:, None]
+    x[s < 0] = 0
+    return x.to(torch.bfloat16)
+
+
 def cpu_baseline(st, torch):
     """The fp32 CPU oracle on a bounded sample of the same workload: 16 experts x 512 rows through
     fc1+SwiGLU+fc2 forward and both data gradients, and 512x512 weight-gradient windows contracted over
@@ -172,17 +193,18 @@ def cpu_baseline(st, torch):
         rows = np.unique(np.linspace(lo, hi - 1, num=min(nrow, hi - lo)).astype(np.int64))
         n = len(rows)
         ridx = torch.from_numpy(rows).cuda()
-        xp = st.Xp[ridx].float().cpu().numpy()
-        do = st.dO[ridx].float().cpu().numpy()
+        xp = _rows_of(st, torch, "Xp", ridx).float().cpu().numpy()
+        do = _rows_of(st, torch, "dO", ridx).float().cpu().numpy()
         w1 = st.W1[e].float().cpu().numpy()[None]
         w2 = st.W2[e].float().cpu().numpy()[None]
         o1 = np.array([0, n], np.int32)
         # wgrad windows over all rows of the expert
         wn, wk = min(win, h), min(win, f)
-        dO_all = st.dO[lo:hi, :wn].float().cpu().numpy()
+        allr = torch.arange(lo, hi, device="cuda")
+        dO_all = _rows_of(st, torch, "dO", allr)[:, :wn].float().cpu().numpy()
         A_all = st.A[lo:hi, :wk].float().cpu().numpy()
         dZ_all = st.dZ[lo:hi, :min(win, 2 * f)].float().cpu().numpy()
-        Xp_all = st.Xp[lo:hi, :min(win, h)].float().cpu().numpy()
+        Xp_all = _rows_of(st, torch, "Xp", allr)[:, :min(win, h)].float().cpu().numpy()
         oall = np.array([0, hi - lo], np.int32)
         t0 = time.perf_counter()
         z = orc.grouped_gemm_nt(xp, w1, o1, prec="f32")

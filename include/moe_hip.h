@@ -295,7 +295,8 @@ moe_status moe_unpermute_combine(moe_ctx* ctx, void* stream, const void* O, moe_
  *   dO[r,:] = prob[t,s] * dY[t,:] for the slot (t,s) = src_of[r], zero for padding
  *   rows (src_of[r] < 0);  dprob[t,s] = <dY[t,:], O[row_of[t,s],:]> in fp32 (0 for
  *   skipped slots).  O may be NULL together with dprob to skip the dot products.
- *   dO is written for all Rcap rows.
+ *   dO is written for all Rcap rows; dO may be NULL to get dprob only (when the rows of dO are
+ *   produced elsewhere, e.g. quantised straight from dY by moe_mx_quantize_rowcol_gather).
  */
 moe_status moe_unpermute_combine_bwd(moe_ctx* ctx, void* stream, const void* dY, const void* O,
                                      moe_dtype dt, const int32_t* row_of, const int32_t* src_of,
@@ -361,6 +362,22 @@ moe_status moe_mx_quantize(moe_ctx* ctx, void* stream, const void* X, moe_mxbloc
 moe_status moe_mx_quantize_rowcol(moe_ctx* ctx, void* stream, const void* X, int64_t rows, int cols,
                                   const int32_t* rows_dev, void* q_row, uint8_t* e8m0_row,
                                   void* q_col, uint8_t* e8m0_col);
+/*
+ * The same two copies of a tensor that is never stored in bf16 (quantisation fused into the permute,
+ * padding included: Sec. 5.4.1, 5.4.2, and into the backward of the combine):
+ *   V[r,:] = X[s / k, :] with s = src_of[r]                         (pair_scale == NULL: the permuted tokens)
+ *   V[r,:] = bf16(pair_scale[s] * X[s / k, :]), product in fp32     (pair_scale [T*k]: dO = p * dY)
+ *   V[r,:] = 0 where src_of[r] < 0 (padding rows)
+ * X [T,cols] bf16, src_of [rows] as moe_permute returns it (call it with X = Xp = NULL for the maps
+ * alone), rows = Rcap, k <= 32.  `groups` (>= 1, normally E) only steers the order in which the row
+ * tiles are visited (expert-interleaved, so that the k copies of a token are read close together in
+ * time); any value gives the same result.  Outputs and limits as moe_mx_quantize_rowcol, bit for bit
+ * what it gives on V.
+ */
+moe_status moe_mx_quantize_rowcol_gather(moe_ctx* ctx, void* stream, const void* X, const int32_t* src_of, int k,
+                                         const float* pair_scale, int groups, int64_t rows, int cols,
+                                         const int32_t* rows_dev, void* q_row, uint8_t* e8m0_row,
+                                         void* q_col, uint8_t* e8m0_col);
 
 #ifdef __cplusplus
 }

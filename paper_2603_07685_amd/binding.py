@@ -28,7 +28,7 @@ EXPORTS = [
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
     "moe_route_topk_bwd", "moe_mx_quantize", "moe_mx_quantize_rowcol",
-    "moe_route_topk_grouped", "moe_aux_loss",
+    "moe_route_topk_grouped", "moe_aux_loss", "moe_mx_quantize_rowcol_gather",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         L.moe_mx_quantize_rowcol.argtypes = [_vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_route_topk_grouped.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp]
         L.moe_aux_loss.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _f, _i, _vp, _vp]
+        L.moe_mx_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
         L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
@@ -214,6 +215,13 @@ def moe_mx_quantize(ctx, X, block, groups, rows, cols, rows_dev, q, e8m0):
 def moe_mx_quantize_rowcol(ctx, X, rows, cols, rows_dev, q_row, e8m0_row, q_col, e8m0_col):
     ctx.check(lib().moe_mx_quantize_rowcol(ctx.h, _stream(), _ptr(X), rows, cols, _ptr(rows_dev), _ptr(q_row),
                                            _ptr(e8m0_row), _ptr(q_col), _ptr(e8m0_col)), "moe_mx_quantize_rowcol")
+
+
+def moe_mx_quantize_rowcol_gather(ctx, X, src_of, k, pair_scale, groups, rows, cols, rows_dev, q_row, e8m0_row, q_col,
+                                  e8m0_col):
+    ctx.check(lib().moe_mx_quantize_rowcol_gather(ctx.h, _stream(), _ptr(X), _ptr(src_of), k, _ptr(pair_scale), groups, rows, cols,
+                                                  _ptr(rows_dev), _ptr(q_row), _ptr(e8m0_row), _ptr(q_col),
+                                                  _ptr(e8m0_col)), "moe_mx_quantize_rowcol_gather")
 
 
 def moe_fp8_quantize(ctx, X, block, groups, rows, cols, rows_dev, q, scale):

@@ -239,23 +239,56 @@ __global__ __launch_bounds__(256) void mx_quant_1x32_kernel(const u32x4_t* __res
 // The column scales of the four waves meet in LDS and leave as one dword per column:
 // e8_col[(row / 128) * cols + col] holds the four 32-row blocks of rows 128 (row / 128) .. + 127, the unit in
 // which the GEMMs walk a contraction over rows.
+// GATHER: the input is not stored in row order: row r of it is pair_scale[s] * X[s / k, :] rounded to bf16
+// (no scale, no rounding when pair_scale is NULL) with s = src_of[r], and zero where s < 0 -- the permuted
+// tokens (Sec. 4.3.3) or the combine's backward, quantised without ever being written out in bf16.
+__device__ __forceinline__ uint32_t scale2_bf16(uint32_t w, float sc) { return pack_bf16(sc * bf16_lo(w), sc * bf16_hi(w)); }
+
+template <bool GATHER>
 __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
                                                               const int32_t* __restrict__ rows_dev,
+                                                              const int32_t* __restrict__ src_of, uint64_t k_magic,
+                                                              const float* __restrict__ pair_scale, int groups,
                                                               u32x2_t* __restrict__ q_row, uint32_t* __restrict__ e8_row,
                                                               u32x2_t* __restrict__ q_col, uint32_t* __restrict__ e8_col) {
     __shared__ uint8_t sc[4][128];
     const int64_t live = rows_dev ? min((int64_t)*rows_dev, rows) : rows;
     const int ctiles = cols / 128;
-    const int64_t rt = blockIdx.x / ctiles;
+    int64_t rt = blockIdx.x / ctiles;
     const int ct = blockIdx.x % ctiles;
+    if (GATHER && groups > 1) {
+        // Visit the row tiles expert-interleaved: with `groups` experts of roughly equal extent, consecutive
+        // workgroups take the same relative position in different experts, which (stable order inside an expert)
+        // is roughly the same window of source tokens, so the k copies of a token are read while it is cached.
+        // Only the order changes: rt -> (rt % groups) * S + rt / groups is one-to-one onto [0, groups * S).
+        const int64_t S = (rows / 128 + groups - 1) / groups;
+        rt = (rt % groups) * S + rt / groups;
+    }
     const int64_t row0 = rt * 128;
-    if (row0 >= live) return;  // uniform over the workgroup
+    if (row0 >= live || row0 >= rows) return;  // uniform over the workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int vpr = cols / 8;                                       // 16-byte pieces per row
     const int64_t v0 = (row0 + wave * 32 + (lane >> 4)) * vpr + ct * 16 + (lane & 15);
     u32x4_t x[8];
+    if (GATHER) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = X[v0 + (int64_t)i * 4 * vpr];
+        for (int i = 0; i < 8; ++i) {
+            const int32_t sidx = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
+            x[i] = u32x4_t{0, 0, 0, 0};
+            if (sidx >= 0) {
+                const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx * k_magic) >> 40);  // sidx / k, exact below 2^31
+                x[i] = X[tok * vpr + ct * 16 + (lane & 15)];
+                if (pair_scale) {
+                    const float sc = pair_scale[sidx];
+                    x[i] = u32x4_t{scale2_bf16(x[i].x, sc), scale2_bf16(x[i].y, sc), scale2_bf16(x[i].z, sc),
+                                   scale2_bf16(x[i].w, sc)};
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = X[v0 + (int64_t)i * 4 * vpr];
+    }
     if (q_row) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -313,12 +346,22 @@ __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __r
 }
 
 static moe_status mx_rowcol_launch(moe_ctx* ctx, hipStream_t s, const char* who, const void* X, int64_t rows, int cols,
-                                   const int32_t* rows_dev, void* q_row, uint8_t* e8_row, void* q_col, uint8_t* e8_col) {
+                                   const int32_t* rows_dev, void* q_row, uint8_t* e8_row, void* q_col, uint8_t* e8_col,
+                                   const int32_t* src_of = nullptr, int k = 1, const float* pair_scale = nullptr,
+                                   int groups = 1) {
     if (rows % 128 || cols % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: rows and cols must be multiples of 128", who);
-    const int64_t nblk = (rows / 128) * (cols / 128);
+    if (groups < 1) groups = 1;
+    const int64_t tiles_r = src_of ? (rows / 128 + groups - 1) / groups * groups : rows / 128;
+    const int64_t nblk = tiles_r * (cols / 128);
     if (nblk > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: too many tiles", who);
-    hipLaunchKernelGGL(mx_quant_rowcol_kernel, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols, rows_dev,
-                       (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col, (uint32_t*)e8_col);
+    if (src_of)
+        hipLaunchKernelGGL(mx_quant_rowcol_kernel<true>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
+                           rows_dev, src_of, ((1ull << 40) + k - 1) / k, pair_scale, groups, (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col,
+                           (uint32_t*)e8_col);
+    else
+        hipLaunchKernelGGL(mx_quant_rowcol_kernel<false>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
+                           rows_dev, nullptr, 0, nullptr, 1, (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col,
+                           (uint32_t*)e8_col);
     return MOE_OK;
 }
 
@@ -367,5 +410,21 @@ extern "C" moe_status moe_mx_quantize_rowcol(moe_ctx* ctx, void* stream, const v
                                      e8m0_row, q_col, e8m0_col);
     if (st != MOE_OK) return st;
     MOE_LAUNCH_CHECK(ctx, "moe_mx_quantize_rowcol");
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_mx_quantize_rowcol_gather(moe_ctx* ctx, void* stream, const void* X, const int32_t* src_of, int k,
+                                                    const float* pair_scale, int groups, int64_t rows, int cols,
+                                                    const int32_t* rows_dev, void* q_row, uint8_t* e8m0_row,
+                                                    void* q_col, uint8_t* e8m0_col) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!X || !src_of || !q_row || !e8m0_row || !q_col || !e8m0_col)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize_rowcol_gather: NULL pointer");
+    if (rows < 0 || cols < 1 || k < 1 || k > 32 || groups < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_mx_quantize_rowcol_gather: bad sizes");
+    if (rows == 0) return MOE_OK;
+    moe_status st = mx_rowcol_launch(ctx, (hipStream_t)stream, "moe_mx_quantize_rowcol_gather", X, rows, cols, rows_dev, q_row,
+                                     e8m0_row, q_col, e8m0_col, src_of, k, pair_scale, groups);
+    if (st != MOE_OK) return st;
+    MOE_LAUNCH_CHECK(ctx, "moe_mx_quantize_rowcol_gather");
     return MOE_OK;
 }

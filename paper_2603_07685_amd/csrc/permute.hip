@@ -309,7 +309,7 @@ __global__ __launch_bounds__(MOVE_THREADS) void combine_bwd_kernel(
                 const int r = s0 + j < k ? rows[s0 + j] : -1;
                 if (r >= 0) {
                     if (want_dot) acc[j] += dot_vec<F32>(g, o[j]);
-                    __builtin_nontemporal_store(scale_vec<F32>(g, wts[s0 + j]), &dO[(int64_t)r * vec_per_row + c]);
+                    if (dO) __builtin_nontemporal_store(scale_vec<F32>(g, wts[s0 + j]), &dO[(int64_t)r * vec_per_row + c]);
                 }
             }
         }
@@ -420,7 +420,8 @@ extern "C" moe_status moe_unpermute_combine_bwd(moe_ctx* ctx, void* stream, cons
                                                 const float* prob, int T, int k, int h, int64_t Rcap,
                                                 void* dO, float* dprob) {
     if (!ctx) return MOE_ERR_ARG;
-    if (!dY || !row_of || !src_of || !dO) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_unpermute_combine_bwd: NULL pointer");
+    if (!dY || !row_of || !src_of) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_unpermute_combine_bwd: NULL pointer");
+    if (!dO && !dprob) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_unpermute_combine_bwd: neither dO nor dprob requested");
     if (dprob && !O) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_unpermute_combine_bwd: dprob needs O");
     if (T < 0 || k < 1 || k > COMBINE_MAX_K || h < 1 || Rcap < 0)
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_unpermute_combine_bwd: need T>=0, 1<=k<=32, h>=1, Rcap>=0");
@@ -429,7 +430,7 @@ extern "C" moe_status moe_unpermute_combine_bwd(moe_ctx* ctx, void* stream, cons
     if (row_bytes % 16) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_unpermute_combine_bwd: row size %zu B is not a multiple of 16", row_bytes);
     hipStream_t s = (hipStream_t)stream;
     const int vec = (int)(row_bytes / 16);
-    if (Rcap > 0)
+    if (Rcap > 0 && dO)
         hipLaunchKernelGGL(zero_pad_rows_kernel, dim3((unsigned)ceil_div64(Rcap, MOVE_THREADS / 64)), dim3(MOVE_THREADS), 0,
                            s, src_of, Rcap, vec, (u32x4_t*)dO);
     if (T > 0) {

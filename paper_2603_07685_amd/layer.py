@@ -41,9 +41,14 @@ class LayerState:
     """Device buffers of one layer + the forward / backward call sequences."""
 
     def __init__(self, cfg: wl.MoEConfig, hin: dict | None = None, shared_f: int | None = None,
-                 variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False):
+                 variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False,
+                 fused_quant: bool | None = None):
         self.cfg = cfg
         self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.2.1): weights applied before fc2
+        # MXFP8 only (default there): the permuted tokens and the combine's backward are quantised straight from
+        # X / dY through the row map, padding included (Sec. 5.4.1, 5.4.2); Xp and dO are never stored in bf16
+        self.fused_quant = bool(cfg.mx) if fused_quant is None else bool(fused_quant)
+        assert not self.fused_quant or cfg.mx, "fused quantisation is built for the MXFP8 path"
         T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
         self.sf = sf = cfg.shared_f if shared_f is None else shared_f
         self.align = cfg.align
@@ -84,7 +89,7 @@ class LayerState:
         self.src_of = torch.empty(Rcap, dtype=i32, device=dev)
         self.offsets = torch.empty(E + 1, dtype=i32, device=dev)
         self.counts = torch.empty(E, dtype=i32, device=dev)
-        self.Xp = torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.Xp = None if self.fused_quant else torch.empty((Rcap, h), dtype=bf, device=dev)
         self.Z = torch.empty((Rcap, 2 * f), dtype=bf, device=dev)
         self.A = torch.empty((Rcap, f), dtype=bf, device=dev)
         self.O = torch.empty((Rcap, h), dtype=bf, device=dev)
@@ -92,7 +97,7 @@ class LayerState:
         # backward
         wdt = f32 if wgrad_f32 else bf
         self.wgrad_dt = B.F32 if wgrad_f32 else B.BF16
-        self.dO = torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.dO = None if self.fused_quant else torch.empty((Rcap, h), dtype=bf, device=dev)
         self.dprob = torch.empty((T, k), dtype=f32, device=dev)
         self.dZ = torch.empty((Rcap, 2 * f), dtype=bf, device=dev)
         self.dXp = torch.empty((Rcap, h), dtype=bf, device=dev)
@@ -270,11 +275,15 @@ class LayerState:
         F8 = self.f8dt
         self._route()
         idx = self.topk_idx if self.forced_idx is None else self.forced_idx
-        B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
+        B.moe_permute(c, None if self.fused_quant else self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
                       self.row_of, self.src_of, self.offsets, self.counts)
         self._q_weight(self.W1, self.qW1, self.sW1, self.qW1d, self.sW1d)
         self._q_weight(self.W2, self.qW2, self.sW2, self.qW2d, self.sW2d)
-        self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows, self.qXpc, self.sXpc)
+        if self.fused_quant:
+            B.moe_mx_quantize_rowcol_gather(c, self.X, self.src_of, k, None, E, Rcap, h, self.live_rows,
+                                            self.qXp, self.sXp, self.qXpc, self.sXpc)
+        else:
+            self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows, self.qXpc, self.sXpc)
         row_prob = None
         if self.eq2:
             B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
@@ -301,13 +310,21 @@ class LayerState:
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         F8, wdt = self.f8dt, self.wgrad_dt
-        if self.eq2:
-            B.moe_unpermute_combine_bwd(c, self.dY, None, B.BF16, self.row_of, self.src_of, None,
-                                        T, k, h, Rcap, self.dO, None)
+        if self.fused_quant:
+            # dO = p * dY (eq. (2): plain copies of dY) goes from dY to its two quantised copies in one pass
+            if not self.eq2:
+                B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
+                                            T, k, h, Rcap, None, self.dprob)
+            B.moe_mx_quantize_rowcol_gather(c, self.dY, self.src_of, k, None if self.eq2 else self.topk_prob, E, Rcap, h,
+                                            self.live_rows, self.qdO, self.sdO, self.qdOc, self.sdOc)
         else:
-            B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
-                                        T, k, h, Rcap, self.dO, self.dprob)
-        self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows, self.qdOc, self.sdOc)
+            if self.eq2:
+                B.moe_unpermute_combine_bwd(c, self.dY, None, B.BF16, self.row_of, self.src_of, None,
+                                            T, k, h, Rcap, self.dO, None)
+            else:
+                B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
+                                            T, k, h, Rcap, self.dO, self.dprob)
+            self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows, self.qdOc, self.sdOc)
         self._wgrad(self.A, self.dO, self.qAc, self.sAc, self.qdOc, self.sdOc, self.offsets, E, h, f, Rcap, self.dW2)
         if self.eq2:
             B.moe_grouped_gemm_dgrad_weighted(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,

@@ -32,3 +32,28 @@ def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
 
 BF16_TOL = 2e-2   # relative Frobenius bound for bf16 outputs and gradients (fp32 accumulation)
 FP8_TOL = 6e-2    # same for the blockwise fp8 path
+
+
+def permuted_rows(st, rows: torch.Tensor, cols=slice(None)) -> torch.Tensor:
+    """Rows of the permuted-token tensor Xp: as stored, or, when the layer quantises straight from X (no bf16 Xp
+    exists), what they are by definition: exact copies of the source tokens, zero for padding rows."""
+    if st.Xp is not None:
+        return st.Xp[rows][:, cols]
+    s = st.src_of[rows].long()
+    x = st.X[torch.div(s.clamp(min=0), st.cfg.k, rounding_mode="floor")][:, cols].clone()
+    x[s < 0] = 0
+    return x
+
+
+def combine_bwd_rows(st, rows: torch.Tensor, cols=slice(None)) -> torch.Tensor:
+    """Rows of dO = bf16(p * dY) (eq. (2): copies of dY): as stored, or rebuilt from dY when only its quantised
+    copies exist (fp32 product rounded to bf16, the value the fused quantiser is defined on)."""
+    if st.dO is not None:
+        return st.dO[rows][:, cols]
+    s = st.src_of[rows].long()
+    x = st.dY[torch.div(s.clamp(min=0), st.cfg.k, rounding_mode="floor")][:, cols].float()
+    if not st.eq2:
+        x = x * st.topk_prob.reshape(-1)[s.clamp(min=0)][:, None]
+    x = x.to(torch.bfloat16)
+    x[s < 0] = 0
+    return x

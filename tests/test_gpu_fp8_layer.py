@@ -129,7 +129,7 @@ def test_mxfp8_layer_per_call(oracle):
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS["C6S"]
     hin = L.host_inputs(cfg)
-    st = L.LayerState(cfg, hin)
+    st = L.LayerState(cfg, hin, fused_quant=False)
     assert st.mx and st.fp8
     st.step()
     torch.cuda.synchronize()
@@ -178,3 +178,46 @@ def test_mxfp8_layer_per_call(oracle):
         assert v <= FP8_TOL, (k_, v)
     for k_, v in e16.items():
         assert v <= BF16_TOL, (k_, v)
+
+
+@pytest.mark.parametrize("eq2", [False, True])
+def test_mxfp8_fused_quantisation_is_bit_identical(oracle, eq2):
+    """C6S: quantising the permuted tokens and the combine's backward straight from X / dY through the row map
+    (no bf16 Xp or dO) gives the GEMMs the very same codes and scales, so every output of the step is bit-identical
+    to the unfused path; the codes themselves are checked against the oracle."""
+    from paper_2603_07685_amd import layer as L
+    from paper_2603_07685_amd import workloads as wl
+    cfg = wl.CONFIGS["C6S"]
+    hin = L.host_inputs(cfg)
+    a = L.LayerState(cfg, hin, eq2=eq2, fused_quant=False)
+    b = L.LayerState(cfg, hin, eq2=eq2, fused_quant=True)
+    assert b.Xp is None and b.dO is None
+    for st in (a, b):
+        st.step()
+    torch.cuda.synchronize()
+    assert a.ctx.poll_error() == 0 and b.ctx.poll_error() == 0
+    R = int(a.offsets[-1].item())
+    for n in ["qXp", "sXp", "qXpc", "qdO", "sdO", "qdOc"]:
+        assert torch.equal(getattr(a, n)[:R], getattr(b, n)[:R]), n
+    for n in ["sXpc", "sdOc"]:
+        assert torch.equal(getattr(a, n)[:R // 128], getattr(b, n)[:R // 128]), n
+    for n in ["Y", "dX", "dW1", "dW2", "dprob", "dWs1", "dWs2", "Z", "dZ"]:
+        x, y = getattr(a, n), getattr(b, n)
+        assert torch.equal(x[:R] if n in ("Z", "dZ") else x, y[:R] if n in ("Z", "dZ") else y), n
+    # against the oracle: codes of the permuted tokens (padding rows included) and of dO = bf16(p * dY)
+    idx = b.forced_idx.cpu().numpy()
+    m = oracle.permute_maps(idx, cfg.E, 128, b.Rcap)
+    Xp = oracle.permute_rows(hin["X"], m.src_of[:R], cfg.k)
+    qo, eo = oracle.mx_quant_1x32(Xp)
+    assert np.array_equal(b.qXp.cpu().numpy()[:R], qo) and np.array_equal(b.sXp.cpu().numpy()[:R], eo)
+    src = m.src_of[:R]
+    dO = hin["dY"].astype(np.float32)[np.maximum(src, 0) // cfg.k]
+    if not eq2:
+        dO = wl.bf16_round(dO * b.topk_prob.cpu().numpy().reshape(-1)[np.maximum(src, 0)][:, None])
+    dO[src < 0] = 0
+    qo, eo = oracle.mx_quant_1x32(dO)
+    assert np.array_equal(b.qdO.cpu().numpy()[:R], qo) and np.array_equal(b.sdO.cpu().numpy()[:R], eo)
+    qc, ec = oracle.mx_quant_32x1(dO[None])
+    assert np.array_equal(b.qdOc.cpu().numpy()[:R], qc[0])
+    ecg = b.sdOc.cpu().numpy().reshape(1, b.Rcap // 128, cfg.h, 4).transpose(0, 2, 1, 3).reshape(cfg.h, b.Rcap // 32)
+    assert np.array_equal(ecg[:, :R // 32], ec[0])

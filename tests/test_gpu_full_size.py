@@ -33,7 +33,7 @@ def _sample_rows(lo, hi, g, n=10):
 
 @pytest.mark.parametrize("name,variant", CASES)
 def test_full_size_sampled(oracle, name, variant):
-    from gpu_util import rel_fro, BF16_TOL, FP8_TOL
+    from gpu_util import rel_fro, BF16_TOL, FP8_TOL, permuted_rows, combine_bwd_rows
     from paper_2603_07685_amd import layer as L
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS[name]
@@ -87,21 +87,31 @@ def test_full_size_sampled(oracle, name, variant):
         W2 = _f64(st.W2[e])[None]
         src_tok = m.src_of[rows] // k
         Xrows = _f64(st.X[torch.from_numpy(src_tok).cuda()])
-        assert np.array_equal(_f64(st.Xp[rt]), Xrows)                       # permuted rows are exact copies
+        if st.Xp is not None:
+            assert np.array_equal(_f64(st.Xp[rt]), Xrows)                   # permuted rows are exact copies
+        else:                                                               # quantised straight from X: the codes are exact
+            qo, eo = oracle.mx_quant_1x32(Xrows)
+            assert np.array_equal(st.qXp[rt].cpu().numpy(), qo) and np.array_equal(st.sXp[rt].cpu().numpy(), eo)
         Zref = oracle.grouped_gemm_nt(Xrows, W1, one(n))
         acc("Z", _f64(st.Z[rt]), Zref)
         acc("A", _f64(st.A[rt]), oracle.swiglu(Zref))
         Ag = _f64(st.A[rt])
         acc("O", _f64(st.O[rt]), oracle.grouped_gemm_nt(Ag, W2, one(n)))
-        dOg, Zg = _f64(st.dO[rt]), _f64(st.Z[rt])
+        dOg, Zg = _f64(combine_bwd_rows(st, rt)), _f64(st.Z[rt])
+        if st.dO is None:
+            qo, eo = oracle.mx_quant_1x32(dOg)
+            assert np.array_equal(st.qdO[rt].cpu().numpy(), qo) and np.array_equal(st.sdO[rt].cpu().numpy(), eo)
         acc("dZ", _f64(st.dZ[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, one(n)), Zg))
         acc("dXp", _f64(st.dXp[rt]), oracle.grouped_gemm_nn(_f64(st.dZ[rt]), W1, one(n)))
         # weight-gradient windows, contracted over every row of the expert
         n0, k0 = int(g.integers(0, h - 63)), int(g.integers(0, f - 63))
-        ref = oracle.grouped_gemm_tn(_f64(st.dO[lo:hi, n0:n0 + 64]), _f64(st.A[lo:hi, k0:k0 + 64]), one(hi - lo))[0]
+        allr = torch.arange(lo, hi, device="cuda")
+        ref = oracle.grouped_gemm_tn(_f64(combine_bwd_rows(st, allr, slice(n0, n0 + 64))), _f64(st.A[lo:hi, k0:k0 + 64]),
+                                     one(hi - lo))[0]
         acc("dW2", _f64(st.dW2[e, n0:n0 + 64, k0:k0 + 64]), ref)
         n1, k1 = int(g.integers(0, 2 * f - 63)), int(g.integers(0, h - 63))
-        ref = oracle.grouped_gemm_tn(_f64(st.dZ[lo:hi, n1:n1 + 64]), _f64(st.Xp[lo:hi, k1:k1 + 64]), one(hi - lo))[0]
+        ref = oracle.grouped_gemm_tn(_f64(st.dZ[lo:hi, n1:n1 + 64]), _f64(permuted_rows(st, allr, slice(k1, k1 + 64))),
+                                     one(hi - lo))[0]
         acc("dW1", _f64(st.dW1[e, n1:n1 + 64, k1:k1 + 64]), ref)
     for e in range(E):                                                       # zero-token experts: exact zero gradients
         if m.counts[e] == 0:
@@ -134,7 +144,7 @@ def test_full_size_sampled(oracle, name, variant):
     S = _f64(st.S[tt]) if st.sf else None
     acc("Y", _f64(st.Y[tt]), oracle.combine(Osub, local_rows, prob, S))
     dOref, dpref = oracle.combine_bwd(_f64(st.dY[tt]), Osub, local_rows, prob, len(toks) * k)
-    acc("dO", _f64(st.dO[flat]), dOref)
+    acc("dO", _f64(combine_bwd_rows(st, flat)), dOref)
     acc("dprob", st.dprob.cpu().numpy().astype(np.float64)[toks], dpref)
     acc("dX", _f64(st.dX[tt]), oracle.combine(dXpsub, local_rows, None, _f64(st.dXs[tt]) if st.sf else None))
 

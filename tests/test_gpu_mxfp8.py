@@ -107,6 +107,43 @@ def test_mx_quantize_rowcol_bit_exact(B, ctx, oracle, rows, cols):
         assert not qr[n:].any() and not qc[n:].any() and not er[n:].any() and not ec[n // 128:].any()
 
 
+@pytest.mark.parametrize("with_scale", [False, True])
+def test_mx_quantize_rowcol_gather_bit_exact(B, ctx, oracle, with_scale):
+    """Quantisation fused into the permute (padding rows included) and into the combine's backward: the virtual
+    tensor V[r] = (bf16(p[s] *)) X[s / k], s = src_of[r], zero where s < 0, quantised both ways without being stored."""
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(11 + with_scale)
+    T, k, E, cols = 300, 3, 5, 384
+    idx = g.integers(0, E, size=(T, k)).astype(np.int32)
+    m = oracle.permute_maps(idx, E, 128, None)
+    Rcap = (T * k + E * 127 + 127) // 128 * 128
+    src = np.full(Rcap, -1, np.int32)
+    src[:len(m.src_of)] = m.src_of
+    R = int(m.offsets[-1])
+    Xh = wl.bf16_round((g.standard_normal((T, cols)) * np.exp(g.normal(size=(T, cols)))).astype(np.float32))
+    p = g.uniform(0.05, 1.0, size=T * k).astype(np.float32)
+    V = Xh[np.maximum(src, 0) // k]
+    if with_scale:
+        V = wl.bf16_round(p[np.maximum(src, 0)][:, None] * V)
+    V[src < 0] = 0
+    qr = torch.zeros((Rcap, cols), dtype=torch.uint8, device="cuda")
+    er = torch.zeros((Rcap, cols // 32), dtype=torch.uint8, device="cuda")
+    qc = torch.zeros((Rcap, cols), dtype=torch.uint8, device="cuda")
+    ec = torch.zeros((Rcap // 128, cols, 4), dtype=torch.uint8, device="cuda")
+    live = torch.tensor([R], dtype=torch.int32, device="cuda")
+    B.moe_mx_quantize_rowcol_gather(ctx, dev_bf16(Xh), dev(src), k, dev(p) if with_scale else None, E if with_scale else 1,
+                                    Rcap, cols, live, qr, er, qc, ec)
+    torch.cuda.synchronize()
+    qr_o, er_o = oracle.mx_quant_1x32(V)
+    qc_o, ec_o = oracle.mx_quant_32x1(V[None])
+    assert np.array_equal(qr.cpu().numpy()[:R], qr_o[:R]) and np.array_equal(er.cpu().numpy()[:R], er_o[:R])
+    assert np.array_equal(qc.cpu().numpy()[:R], qc_o[0, :R])
+    assert np.array_equal(_col_scales(ec, 1, Rcap, cols)[0, :, :R // 32], ec_o[0, :, :R // 32])
+    assert (src[:R] < 0).any() and not qr.cpu().numpy()[:R][src[:R] < 0].any()      # padding rows: zero codes
+    assert not qr[R:].any() and not qc[R:].any()                                     # beyond the live rows: untouched
+
+
 def _offsets128(counts):
     pad = (np.asarray(counts) + 127) // 128 * 128
     return np.concatenate([[0], np.cumsum(pad)]).astype(np.int32)
