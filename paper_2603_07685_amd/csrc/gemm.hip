@@ -203,10 +203,11 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 #ifndef GG_PF
 #define GG_PF 0
 #endif
-    // L2 warm-up loads (bf16 variants), off by default: measured at the DeepSeek-V3-style shape they gain 3-17 % per
-    // call on all-zero operands (clock not power-limited) and lose 1.5-4.5 % on N(0, 0.02^2) operands, where the
-    // sustained clock is set by power and the extra requests only add to it
-    constexpr bool PF = GG_PF && !FP8;
+    // L2 warm-up loads (GG_PF bit 0: bf16 variants, bit 1: one-byte variants), off by default: measured at the
+    // DeepSeek-V3-style shape they gain 3-17 % per bf16 call on all-zero operands (clock not power-limited) and lose
+    // 1.5-4.5 % on N(0, 0.02^2) operands, where the sustained clock is set by power and the extra requests only add
+    // to it; the one-byte variants change by -5 .. +3 % per call, no net gain
+    constexpr bool PF = FP8 ? (GG_PF & 2) != 0 : (GG_PF & 1) != 0;
     // fp8: the block scales of a stage travel with it, behind the P tile: 256 row scales (position
     // 4 * (row % 32) + row / 32 inside each 128-row half, so a lane finds its four rows in one 16-byte
     // read) and, from position 256 on, the two column-block scales (replicated)
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     constexpr int BUF_BYTES = 2 * GG_STAGE_BYTES + SC_BYTES;
     constexpr int STG_PITCH = 260;                       // floats per staged row: 256 + 4 (bank rotation)
     constexpr int STG_BYTES = 64 * STG_PITCH * 4;
-    constexpr int LDS_BYTES = BUF_BYTES + (BUF_BYTES > STG_BYTES ? BUF_BYTES : STG_BYTES);
+    constexpr int LDS_BYTES = BUF_BYTES + (BUF_BYTES > STG_BYTES ? BUF_BYTES : STG_BYTES) + 256;  // + a dummy word row
     __shared__ __attribute__((aligned(1024))) char lds_buf[LDS_BYTES];
     char* const ldsP0 = lds_buf;
     char* const ldsQ0 = lds_buf + GG_STAGE_BYTES + SC_BYTES;
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     // 1/8 and 1/4 of the lines of the stage after next (12 lines per wave) and touches them with one 4-byte
     // load into a dummy LDS word; the load is the wave's youngest vector-memory operation when the wave waits
     // for its DMA (wait_vm1), so it never delays the stage being waited for.
-    uint32_t pf_lds = lds_addr(lds_buf + 2 * BUF_BYTES);  // dummy word: the pad behind the two stage buffers
+    uint32_t pf_lds = lds_addr(lds_buf + LDS_BYTES - 256);  // dummy words behind everything else
     asm volatile("" : "+s"(pf_lds));                      // (formed here, in uniform code, not where it is used)
     auto prefetch = [&](int kt) {
         if (pf_on) {
