@@ -253,11 +253,26 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     // ---- tile schedule, computed by every workgroup from the device-resident offsets ----
     for (int e = tid; e <= E; e += GG_THREADS) offs[e] = a.offsets[e];
     __syncthreads();
+    // wgrad: every expert has the same number of output tiles but a tile costs its expert's row count, so the
+    // experts are walked in descending order of rows (rank sort, ties by index; tile_start[i] = i-th largest
+    // expert) and the tile list is dealt to the XCDs in a snake (see tile_of): equal work per workgroup
+    // whatever the load skew.  Only the order of the tiles changes, never what a tile computes.
+    if (MODE == GG_WGRAD) {
+        for (int e = tid; e < E; e += GG_THREADS) {
+            const int re = offs[e + 1] - offs[e];
+            int rank = 0;
+            for (int o = 0; o < E; ++o) {
+                const int ro = offs[o + 1] - offs[o];
+                rank += (ro > re) || (ro == re && o < e);
+            }
+            tile_start[rank] = e;
+        }
+    }
     if (tid == 0) {
         int run = 0;
         bool bad = offs[0] < 0 || offs[E] > a.Rcap;
         for (int e = 0; e < E; ++e) {
-            tile_start[e] = run;
+            if (MODE != GG_WGRAD) tile_start[e] = run;
             const int rows = offs[e + 1] - offs[e];
             bad |= rows < 0;
             // MXFP8 wgrad: a 32-row scale block (and the 128-row stage) must not straddle two experts
@@ -337,10 +352,18 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     int e_hint = 0;
     auto setup_tile = [&](int t) {
         // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
-        e = e_hint;
-        while (e + 1 < E && t >= __builtin_amdgcn_readfirstlane(tile_start[e + 1])) ++e;
-        e_hint = e;
-        const int u = t - __builtin_amdgcn_readfirstlane(tile_start[e]);
+        int u;
+        if (MODE == GG_WGRAD) {
+            const int tpe = tiles_i_w * tiles_j;
+            const int es = t / tpe;
+            e = __builtin_amdgcn_readfirstlane(tile_start[es]);
+            u = t - es * tpe;
+        } else {
+            e = e_hint;
+            while (e + 1 < E && t >= __builtin_amdgcn_readfirstlane(tile_start[e + 1])) ++e;
+            e_hint = e;
+            u = t - __builtin_amdgcn_readfirstlane(tile_start[e]);
+        }
         const int row_lo = __builtin_amdgcn_readfirstlane(offs[e]), row_hi = __builtin_amdgcn_readfirstlane(offs[e + 1]);
         int ti, tj;
         {
@@ -540,11 +563,21 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         }
     };
 
-    if (q < total_tiles) {
-        setup_tile(q);
+    // n-th tile of this workgroup.  Forward / data gradient: q, q + G, ... (equal-cost tiles).  Weight gradient: the
+    // list is in descending cost; chunks of G / 8 consecutive tiles go to the XCDs in a snake (0..7, 7..0, ...),
+    // the i-th workgroup of an XCD takes the i-th tile of each of its chunks.
+    auto tile_of = [&](int n) -> int {
+        if (MODE == GG_WGRAD && !(G & 7)) {
+            const int x = (int)blockIdx.x & 7, i = (int)blockIdx.x >> 3;
+            return (8 * n + ((n & 1) ? 7 - x : x)) * (G >> 3) + i;
+        }
+        return q + n * G;
+    };
+    if (tile_of(0) < total_tiles) {
+        setup_tile(tile_of(0));
         issue_stage0();
     }
-    for (int t = q; t < total_tiles; t += G) {
+    for (int n_tile = 0, t = tile_of(0); t < total_tiles; ++n_tile, t = tile_of(n_tile)) {
         float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[2] = {1.f, 1.f};
         f32x16_t acc[4][2];
 #pragma unroll
@@ -771,8 +804,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         // (every wave is past its last LDS read here: the stage loop ends with a barrier after the last
         // fragment reads of both groups)
         const int ep_e = e, ep_i0 = i0, ep_i_end = i_end, ep_j0 = j0, ep_j1 = j1;
-        if (t + G < total_tiles) {
-            setup_tile(t + G);
+        if (tile_of(n_tile + 1) < total_tiles) {
+            setup_tile(tile_of(n_tile + 1));
             issue_stage0();
         }
 
