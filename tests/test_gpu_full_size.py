@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 CASES = [("C2", None), ("C3", None), ("C4", None), ("C4", "zeros"), ("C4", "hot"),
-         ("C5", None), ("C5", "zeros"), ("C5", "hot"), ("C6", None), ("C4G", None)]
+         ("C5", None), ("C5", "zeros"), ("C5", "hot"), ("C6", None), ("C6", "zeros"), ("C6", "hot"), ("C4G", None)]
 
 
 def _f64(t):
