@@ -64,8 +64,9 @@ def describe_call(name, args, st):
         return "gather_row_prob", None, args[3] * 12
     if name == "moe_scatter_row_dprob":
         return "scatter_row_dprob", None, T * k * (8 + 4 * args[2])
-    if name.endswith("_weighted"):
-        name = name[:-len("_weighted")]
+    for sfx in ("_weighted", "_quant"):
+        if name.endswith(sfx):
+            name = name[:-len(sfx)]
     if name in ("moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad"):
         E, N, K, dt = args[4], args[5], args[6], args[8]
         rows = R if E > 1 else T
@@ -128,7 +129,8 @@ def describe_call(name, args, st):
 
 HOOKED = ["moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_mx_quantize_rowcol_gather", "moe_route_topk", "moe_route_topk_grouped", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
           "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
-          "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob",
+          "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted",
+          "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gather_row_prob",
           "moe_scatter_row_dprob"]
 
 

@@ -266,6 +266,28 @@ moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream, const voi
                                            const float* row_prob, void* dA, float* dprob_part);
 
 /*
+ * Quantisation of a GEMM's output fused into its epilogue (Sec. 5.4.2; the activation + quantisation
+ * epilogue of Sec. 4.3.2), blockwise recipe (dt = MOE_FP8_E4M3) only.  The calls are the _weighted ones
+ * with two more outputs, which receive the 1x128 codes and scales of the bf16 tensor the epilogue
+ * stores, bit for bit what moe_fp8_quantize(MOE_Q_1x128) would make of it:
+ *   fwd  (epi = MOE_EPI_SWIGLU): act_q [Rcap, N/2] codes, act_q_scale [Rcap, N/256] of C_act;
+ *   dgrad (Z_saved != NULL)    : dz_q  [Rcap, 2K] codes,  dz_q_scale [Rcap, 2K/128] of dZ.
+ * Both NULL = the _weighted call.  Rows >= offsets[E] are not written.
+ */
+moe_status moe_grouped_gemm_fwd_quant(moe_ctx* ctx, void* stream, const void* A, const void* B,
+                                      const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                      moe_dtype dt, moe_epilogue epi,
+                                      const float* a_scale, const float* b_scale,
+                                      const float* row_prob, void* C, void* C_act,
+                                      void* act_q, float* act_q_scale);
+moe_status moe_grouped_gemm_dgrad_quant(moe_ctx* ctx, void* stream, const void* dC, const void* B,
+                                        const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                        moe_dtype dt, const void* Z_saved,
+                                        const float* dc_scale, const float* b_scale,
+                                        const float* row_prob, void* dA, float* dprob_part,
+                                        void* dz_q, float* dz_q_scale);
+
+/*
  * Row-indexed view of the routing weights for eq. (2) and its inverse:
  *   gather:  row_prob[r] = prob[src_of[r]] for r < Rcap, 0 where src_of[r] < 0 (padding).
  *   scatter: dprob[t,s] = sum_j dprob_part[row_of[t,s], j], j = 0..parts-1 in increasing

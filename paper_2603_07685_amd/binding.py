@@ -29,6 +29,7 @@ EXPORTS = [
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
     "moe_route_topk_bwd", "moe_mx_quantize", "moe_mx_quantize_rowcol",
     "moe_route_topk_grouped", "moe_aux_loss", "moe_mx_quantize_rowcol_gather",
+    "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -68,6 +69,8 @@ def lib() -> C.CDLL:
         L.moe_route_topk_grouped.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp]
         L.moe_aux_loss.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _f, _i, _vp, _vp]
         L.moe_mx_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_fwd_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_dgrad_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
         L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
@@ -173,6 +176,21 @@ def moe_grouped_gemm_dgrad_weighted(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_sa
                                                     dt, _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(row_prob),
                                                     _ptr(dA), _ptr(dprob_part)),
               "moe_grouped_gemm_dgrad_weighted")
+
+
+def moe_grouped_gemm_fwd_quant(ctx, A, B, offsets, E, N, K, Rcap, dt, epi, a_scale, b_scale, row_prob, Cout, C_act,
+                               act_q, act_q_scale):
+    ctx.check(lib().moe_grouped_gemm_fwd_quant(ctx.h, _stream(), _ptr(A), _ptr(B), _ptr(offsets), E, N, K, Rcap, dt, epi,
+                                               _ptr(a_scale), _ptr(b_scale), _ptr(row_prob), _ptr(Cout), _ptr(C_act),
+                                               _ptr(act_q), _ptr(act_q_scale)), "moe_grouped_gemm_fwd_quant")
+
+
+def moe_grouped_gemm_dgrad_quant(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_saved, dc_scale, b_scale, row_prob, dA,
+                                 dprob_part, dz_q, dz_q_scale):
+    ctx.check(lib().moe_grouped_gemm_dgrad_quant(ctx.h, _stream(), _ptr(dC), _ptr(B), _ptr(offsets), E, N, K, Rcap, dt,
+                                                 _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(row_prob), _ptr(dA),
+                                                 _ptr(dprob_part), _ptr(dz_q), _ptr(dz_q_scale)),
+              "moe_grouped_gemm_dgrad_quant")
 
 
 def moe_route_topk_bwd(ctx, logits, topk_idx, dprob, T, E, k, fn, norm_topk, scale, dlogits):

@@ -61,5 +61,20 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// blockwise fp8 (Sec. 5.3.2): scale of a block from its amax, and four fp32 -> four E4M3 codes packed in a dword
+// (fp32 division, clamp to +-448, hardware round-to-nearest-even conversion).  Shared by the quantiser kernels and
+// the GEMM epilogues that quantise their own output, so both produce the same bits.
+__device__ __forceinline__ float block_scale(float amax) { return amax > 0.0f ? amax / 448.0f : 1.0f; }
+__device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d, float scale) {
+    a = __builtin_fminf(__builtin_fmaxf(a / scale, -448.0f), 448.0f);
+    b = __builtin_fminf(__builtin_fmaxf(b / scale, -448.0f), 448.0f);
+    c = __builtin_fminf(__builtin_fmaxf(c / scale, -448.0f), 448.0f);
+    d = __builtin_fminf(__builtin_fmaxf(d / scale, -448.0f), 448.0f);
+    int w = 0;
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, w, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+    return (uint32_t)w;
+}
+
 // shared by the fill launches of several files
 void moe_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s);

@@ -11,20 +11,6 @@
 //   128x128 : a 256-thread workgroup owns one block, 64 elements per thread held in registers.
 #include "common.h"
 
-__device__ __forceinline__ float block_scale(float amax) { return amax > 0.0f ? amax / 448.0f : 1.0f; }
-
-// four fp32 -> four E4M3 codes packed in a dword
-__device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d, float scale) {
-    a = __builtin_fminf(__builtin_fmaxf(a / scale, -448.0f), 448.0f);
-    b = __builtin_fminf(__builtin_fmaxf(b / scale, -448.0f), 448.0f);
-    c = __builtin_fminf(__builtin_fmaxf(c / scale, -448.0f), 448.0f);
-    d = __builtin_fminf(__builtin_fmaxf(d / scale, -448.0f), 448.0f);
-    int w = 0;
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, w, false);
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
-    return (uint32_t)w;
-}
-
 __device__ __forceinline__ float amax8(u32x4_t v) {
     float m = fabsf(bf16_lo(v.x));
     m = fmaxf(m, fabsf(bf16_hi(v.x)));

@@ -189,6 +189,10 @@ struct gg_args {
     int accumulate;        // wgrad: out += result
     const float* row_prob; // eq. (2): routing weight of each row (fwd SWIGLU: scales the activation;
                            //   dgrad SWIGLU_BWD: scales dZ); NULL = 1
+    // blockwise fp8 only: the epilogue also emits the 1x128 codes and scales of its bf16 output (fwd SWIGLU: of the
+    // activation [rows, N/2]; dgrad SWIGLU_BWD: of dZ [rows, 2K]), the operand of the next GEMM (Sec. 5.4.2)
+    uint8_t* out_q;
+    float* out_q_scale;
     float* dprob_part;     // eq. (2), dgrad SWIGLU_BWD: [Rcap, ceil(K/256)] partial <dA, act(Z)> per row and column tile
 };
 
@@ -853,11 +857,10 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 }
             wait_lgkm0();
             stage_barrier();
-#pragma unroll
-            for (int x8 = 0; x8 < 8; ++x8) {
+            auto out_row = [&](int x8) {
                 const int rr = wave * 8 + x8;                             // staged row 0..63
                 const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
-                if (r >= ep_i_end) continue;                              // wave-uniform
+                if (r >= ep_i_end) return;                                // wave-uniform
                 const f32x4_t v = *(const f32x4_t*)(stg + rr * STG_PITCH + cl);
                 if (EPI == GG_EPI_SWIGLU) {
                     bf16_t* C = (bf16_t*)a.out;                           // [gate | up] pre-activations
@@ -888,6 +891,29 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                         }
                         st4_bf16(dZ + zr + c, dg);
                         st4_bf16(dZ + zr + K + c, du);
+                        if (F8 == 1 && a.out_q) {
+                            // the 32 lanes of a half-wave hold one 1x128 block of the gate part and one of the up
+                            // part of this row (K % 128 == 0: a half is inside K or outside as a whole); quantise
+                            // the values as they were just stored (bf16), as the stand-alone quantiser would
+                            const uint32_t g01 = pack_bf16(dg[0], dg[1]), g23 = pack_bf16(dg[2], dg[3]);
+                            const uint32_t u01 = pack_bf16(du[0], du[1]), u23 = pack_bf16(du[2], du[3]);
+                            float mg = fmaxf(fmaxf(fabsf(bf16_lo(g01)), fabsf(bf16_hi(g01))), fmaxf(fabsf(bf16_lo(g23)), fabsf(bf16_hi(g23))));
+                            float mu = fmaxf(fmaxf(fabsf(bf16_lo(u01)), fabsf(bf16_hi(u01))), fmaxf(fabsf(bf16_lo(u23)), fabsf(bf16_hi(u23))));
+#pragma unroll
+                            for (int o = 16; o > 0; o >>= 1) {
+                                mg = fmaxf(mg, __shfl_xor(mg, o));
+                                mu = fmaxf(mu, __shfl_xor(mu, o));
+                            }
+                            const float sgs = block_scale(mg), sus = block_scale(mu);
+                            uint32_t* q = (uint32_t*)(a.out_q + zr);
+                            q[c >> 2] = cvt4_e4m3(bf16_lo(g01), bf16_hi(g01), bf16_lo(g23), bf16_hi(g23), sgs);
+                            q[(K + c) >> 2] = cvt4_e4m3(bf16_lo(u01), bf16_hi(u01), bf16_lo(u23), bf16_hi(u23), sus);
+                            if ((lane & 31) == 0) {
+                                float* sc = a.out_q_scale + (int64_t)r * (2 * K / 128);
+                                sc[c >> 7] = sgs;
+                                sc[(K + c) >> 7] = sus;
+                            }
+                        }
                     }
                     if (a.dprob_part) {  // the wave holds the 256 columns of this row and tile: one partial sum
 #pragma unroll
@@ -913,15 +939,27 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                         st4_bf16(o, t4);
                     }
                 }
+            };
+            // (the pass loop must unroll completely: the accumulators are indexed by it.  The compiler gives up on
+            // that above a size limit, so the row loops stay rolled where nothing is indexed by them)
+            if (Z_EARLY) {
+#pragma unroll
+                for (int x8 = 0; x8 < 8; ++x8) out_row(x8);
+            } else if (FP8) {
+#pragma unroll 1
+                for (int x8 = 0; x8 < 8; ++x8) out_row(x8);
+            } else {
+#pragma unroll
+                for (int x8 = 0; x8 < 8; ++x8) out_row(x8);
             }
             if (EPI == GG_EPI_SWIGLU) {
                 // activation: a lane pairs gate and up of 4 features; two tile rows per instruction
                 const int fl = (lane & 31) * 4;
-#pragma unroll
+#pragma unroll(FP8 ? 1 : 4)
                 for (int x4 = 0; x4 < 4; ++x4) {
                     const int rr = wave * 8 + 2 * x4 + (lane >> 5);
                     const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
-                    if (r < ep_i_end && ep_j0 + fl < half_cols) {
+                    if (r < ep_i_end && ep_j0 + fl < half_cols) {  // uniform over a half-wave when N % 256 == 0 (fp8)
                         const f32x4_t gt = *(const f32x4_t*)(stg + rr * STG_PITCH + fl);
                         const f32x4_t up = *(const f32x4_t*)(stg + rr * STG_PITCH + 128 + fl);
                         float act[4];
@@ -929,6 +967,18 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 #pragma unroll
                         for (int x = 0; x < 4; ++x) act[x] = pr * (gt[x] * sigmoid_f(gt[x]) * up[x]);
                         st4_bf16(a.out_act + (int64_t)r * half_cols + ep_j0 + fl, act);
+                        if (F8 == 1 && a.out_q) {
+                            // the half-wave holds the row's 128 activations of this tile = one 1x128 block of fc2's
+                            // input: quantise the values as stored (bf16), as the stand-alone quantiser would
+                            const uint32_t a01 = pack_bf16(act[0], act[1]), a23 = pack_bf16(act[2], act[3]);
+                            float m = fmaxf(fmaxf(fabsf(bf16_lo(a01)), fabsf(bf16_hi(a01))), fmaxf(fabsf(bf16_lo(a23)), fabsf(bf16_hi(a23))));
+#pragma unroll
+                            for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+                            const float sa = block_scale(m);
+                            ((uint32_t*)(a.out_q + (int64_t)r * half_cols))[(ep_j0 + fl) >> 2] =
+                                cvt4_e4m3(bf16_lo(a01), bf16_hi(a01), bf16_lo(a23), bf16_hi(a23), sa);
+                            if ((lane & 31) == 0) a.out_q_scale[(int64_t)r * (half_cols / 128) + ep_j0 / 128] = sa;
+                        }
                     }
                 }
             }
@@ -989,7 +1039,21 @@ extern "C" moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, 
                                                     moe_dtype dt, moe_epilogue epi,
                                                     const float* a_scale, const float* b_scale,
                                                     const float* row_prob, void* C, void* C_act) {
+    return moe_grouped_gemm_fwd_quant(ctx, stream, A, B, offsets, E, N, K, Rcap, dt, epi, a_scale, b_scale, row_prob, C,
+                                      C_act, nullptr, nullptr);
+}
+
+extern "C" moe_status moe_grouped_gemm_fwd_quant(moe_ctx* ctx, void* stream, const void* A, const void* B,
+                                                 const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                                 moe_dtype dt, moe_epilogue epi,
+                                                 const float* a_scale, const float* b_scale,
+                                                 const float* row_prob, void* C, void* C_act,
+                                                 void* act_q, float* act_q_scale) {
     if (!ctx) return MOE_ERR_ARG;
+    if ((act_q == nullptr) != (act_q_scale == nullptr))
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_quant: act_q and act_q_scale go together");
+    if (act_q && (dt != MOE_FP8_E4M3 || epi != MOE_EPI_SWIGLU))
+        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd_quant: quantised output needs dt = MOE_FP8_E4M3 and the SwiGLU epilogue");
     if (row_prob && epi != MOE_EPI_SWIGLU)
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_weighted: row weights go with the SwiGLU epilogue");
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_fwd", A, B, offsets, E, N, K, Rcap, dt);
@@ -1011,6 +1075,8 @@ extern "C" moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, 
     a.p_scale = a_scale;
     a.q_scale = b_scale;
     a.row_prob = row_prob;
+    a.out_q = (uint8_t*)act_q;
+    a.out_q_scale = act_q_scale;
     if (epi == MOE_EPI_SWIGLU) {
         if (mx) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, 2);
         else if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, 1);
@@ -1037,7 +1103,21 @@ extern "C" moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream
                                                       moe_dtype dt, const void* Z_saved,
                                                       const float* dc_scale, const float* b_scale,
                                                       const float* row_prob, void* dA, float* dprob_part) {
+    return moe_grouped_gemm_dgrad_quant(ctx, stream, dC, B, offsets, E, N, K, Rcap, dt, Z_saved, dc_scale, b_scale, row_prob,
+                                        dA, dprob_part, nullptr, nullptr);
+}
+
+extern "C" moe_status moe_grouped_gemm_dgrad_quant(moe_ctx* ctx, void* stream, const void* dC, const void* B,
+                                                   const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                                   moe_dtype dt, const void* Z_saved,
+                                                   const float* dc_scale, const float* b_scale,
+                                                   const float* row_prob, void* dA, float* dprob_part,
+                                                   void* dz_q, float* dz_q_scale) {
     if (!ctx) return MOE_ERR_ARG;
+    if ((dz_q == nullptr) != (dz_q_scale == nullptr))
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_quant: dz_q and dz_q_scale go together");
+    if (dz_q && (dt != MOE_FP8_E4M3 || !Z_saved))
+        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad_quant: quantised output needs dt = MOE_FP8_E4M3 and Z_saved");
     if ((row_prob || dprob_part) && !Z_saved)
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_weighted: row weights / dprob_part need Z_saved");
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_dgrad", dC, B, offsets, E, N, K, Rcap, dt);
@@ -1052,6 +1132,8 @@ extern "C" moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream
     a.q_scale = b_scale;
     a.row_prob = row_prob;
     a.dprob_part = dprob_part;
+    a.out_q = (uint8_t*)dz_q;
+    a.out_q_scale = dz_q_scale;
     if (Z_saved) {
         if (mx) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 2);
         else if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 1);

@@ -42,13 +42,17 @@ class LayerState:
 
     def __init__(self, cfg: wl.MoEConfig, hin: dict | None = None, shared_f: int | None = None,
                  variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False,
-                 fused_quant: bool | None = None):
+                 fused_quant: bool | None = None, epilogue_quant: bool | None = None):
         self.cfg = cfg
         self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.2.1): weights applied before fc2
         # MXFP8 only (default there): the permuted tokens and the combine's backward are quantised straight from
         # X / dY through the row map, padding included (Sec. 5.4.1, 5.4.2); Xp and dO are never stored in bf16
         self.fused_quant = bool(cfg.mx) if fused_quant is None else bool(fused_quant)
         assert not self.fused_quant or cfg.mx, "fused quantisation is built for the MXFP8 path"
+        # blockwise fp8 (default there): the SwiGLU / SwiGLU-backward epilogues also emit the 1x128 codes of their
+        # output, the next GEMM's operand (Sec. 5.4.2); off = stand-alone quantiser launches
+        self.epilogue_quant = bool(cfg.fp8) and not cfg.mx if epilogue_quant is None else bool(epilogue_quant)
+        assert not self.epilogue_quant or (cfg.fp8 and not cfg.mx), "epilogue quantisation is built for the blockwise path"
         T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
         self.sf = sf = cfg.shared_f if shared_f is None else shared_f
         self.align = cfg.align
@@ -288,9 +292,12 @@ class LayerState:
         if self.eq2:
             B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
             row_prob = self.row_prob
-        B.moe_grouped_gemm_fwd_weighted(c, self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, B.EPI_SWIGLU,
-                                        self.sXp, self.sW1, row_prob, self.Z, self.A)
-        self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows, self.qAc, self.sAc)
+        eq = self.epilogue_quant
+        B.moe_grouped_gemm_fwd_quant(c, self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, B.EPI_SWIGLU,
+                                     self.sXp, self.sW1, row_prob, self.Z, self.A,
+                                     self.qA if eq else None, self.sA if eq else None)
+        if not eq:
+            self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows, self.qAc, self.sAc)
         B.moe_grouped_gemm_fwd(c, self.qA, self.qW2, self.offsets, E, h, f, Rcap, F8, B.EPI_NONE,
                                self.sA, self.sW2, self.O, None)
         if sf:
@@ -298,9 +305,11 @@ class LayerState:
             self._q_weight(self.Ws1.view(1, 2 * sf, h), self.qWs1, self.sWs1, self.qWs1d, self.sWs1d)
             self._q_weight(self.Ws2.view(1, h, sf), self.qWs2, self.sWs2, self.qWs2d, self.sWs2d)
             self._q_rows(self.X, self.qX, self.sX, T, h, None, self.qXc, self.sXc)
-            B.moe_grouped_gemm_fwd(c, self.qX, self.qWs1, o1, 1, 2 * sf, h, T, F8, B.EPI_SWIGLU,
-                                   self.sX, self.sWs1, self.Zs, self.As)
-            self._q_rows(self.As, self.qAs, self.sAs, T, sf, None, self.qAsc, self.sAsc)
+            B.moe_grouped_gemm_fwd_quant(c, self.qX, self.qWs1, o1, 1, 2 * sf, h, T, F8, B.EPI_SWIGLU,
+                                         self.sX, self.sWs1, None, self.Zs, self.As,
+                                         self.qAs if eq else None, self.sAs if eq else None)
+            if not eq:
+                self._q_rows(self.As, self.qAs, self.sAs, T, sf, None, self.qAsc, self.sAsc)
             B.moe_grouped_gemm_fwd(c, self.qAs, self.qWs2, o1, 1, h, sf, T, F8, B.EPI_NONE,
                                    self.sAs, self.sWs2, self.S, None)
         B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, None if self.eq2 else self.topk_prob,
@@ -326,14 +335,15 @@ class LayerState:
                                             T, k, h, Rcap, self.dO, self.dprob)
             self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows, self.qdOc, self.sdOc)
         self._wgrad(self.A, self.dO, self.qAc, self.sAc, self.qdOc, self.sdOc, self.offsets, E, h, f, Rcap, self.dW2)
+        eq = self.epilogue_quant
+        B.moe_grouped_gemm_dgrad_quant(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
+                                       self.sW2d, self.row_prob if self.eq2 else None, self.dZ,
+                                       self.dprob_part if self.eq2 else None,
+                                       self.qdZ if eq else None, self.sdZ if eq else None)
         if self.eq2:
-            B.moe_grouped_gemm_dgrad_weighted(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
-                                              self.sW2d, self.row_prob, self.dZ, self.dprob_part)
             B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
-        else:
-            B.moe_grouped_gemm_dgrad(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
-                                     self.sW2d, self.dZ)
-        self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows, self.qdZc, self.sdZc)
+        if not eq:
+            self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows, self.qdZc, self.sdZc)
         self._wgrad(self.Xp, self.dZ, self.qXpc, self.sXpc, self.qdZc, self.sdZc, self.offsets, E, 2 * f, h, Rcap, self.dW1)
         B.moe_grouped_gemm_dgrad(c, self.qdZ, self.qW1d, self.offsets, E, 2 * f, h, Rcap, F8, None, self.sdZ, self.sW1d,
                                  self.dXp)
@@ -341,8 +351,10 @@ class LayerState:
             o1 = self.off_shared
             self._q_rows(self.dY, self.qdY, self.sdY, T, h, None, self.qdYc, self.sdYc)
             self._wgrad(self.As, self.dY, self.qAsc, self.sAsc, self.qdYc, self.sdYc, o1, 1, h, sf, T, self.dWs2)
-            B.moe_grouped_gemm_dgrad(c, self.qdY, self.qWs2d, o1, 1, h, sf, T, F8, self.Zs, self.sdY, self.sWs2d, self.dZs)
-            self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf, None, self.qdZsc, self.sdZsc)
+            B.moe_grouped_gemm_dgrad_quant(c, self.qdY, self.qWs2d, o1, 1, h, sf, T, F8, self.Zs, self.sdY, self.sWs2d,
+                                           None, self.dZs, None, self.qdZs if eq else None, self.sdZs if eq else None)
+            if not eq:
+                self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf, None, self.qdZsc, self.sdZsc)
             self._wgrad(self.X, self.dZs, self.qXc, self.sXc, self.qdZsc, self.sdZsc, o1, 1, 2 * sf, h, T, self.dWs1)
             B.moe_grouped_gemm_dgrad(c, self.qdZs, self.qWs1d, o1, 1, 2 * sf, h, T, F8, None, self.sdZs, self.sWs1d,
                                      self.dXs)

@@ -221,3 +221,27 @@ def test_mxfp8_fused_quantisation_is_bit_identical(oracle, eq2):
     assert np.array_equal(b.qdOc.cpu().numpy()[:R], qc[0])
     ecg = b.sdOc.cpu().numpy().reshape(1, b.Rcap // 128, cfg.h, 4).transpose(0, 2, 1, 3).reshape(cfg.h, b.Rcap // 32)
     assert np.array_equal(ecg[:, :R // 32], ec[0])
+
+
+@pytest.mark.parametrize("eq2", [False, True])
+def test_fp8_epilogue_quantisation_is_bit_identical(eq2):
+    """C5S: the codes and scales the SwiGLU / SwiGLU-backward epilogues emit (routed and shared expert) equal those of
+    the stand-alone 1x128 quantiser run on the stored bf16 tensor, so every output of the step is bit-identical."""
+    from paper_2603_07685_amd import layer as L
+    from paper_2603_07685_amd import workloads as wl
+    cfg = wl.CONFIGS["C5S"]
+    hin = L.host_inputs(cfg)
+    a = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=False)
+    b = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=True)
+    for st in (a, b):
+        for n in ("qA", "sA", "qdZ", "sdZ", "qAs", "sAs", "qdZs", "sdZs"):
+            getattr(st, n).zero_()
+        st.step()
+    torch.cuda.synchronize()
+    assert a.ctx.poll_error() == 0 and b.ctx.poll_error() == 0
+    R = int(a.offsets[-1].item())
+    for n in ("qA", "sA", "qdZ", "sdZ"):
+        assert torch.equal(getattr(a, n)[:R], getattr(b, n)[:R]), n
+    for n in ("qAs", "sAs", "qdZs", "sdZs", "Y", "dX", "dW1", "dW2", "dprob", "dWs1", "dWs2"):
+        assert torch.equal(getattr(a, n), getattr(b, n)), n
+    assert not b.qA[R:].any() and not b.qdZ[R:].any()          # rows beyond the live ones are not written
