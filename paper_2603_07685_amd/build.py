@@ -16,7 +16,13 @@ HIPCC_FLAGS = [
     # packed-fp32 VALU forms are kept off (known-unreliable on the test machines)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    # per-kernel register / scratch report on stderr, checked below
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+# A kernel that needs more scratch than a handful of spilled registers has had a register array demoted to
+# memory (e.g. a loop over the accumulators that silently failed to unroll): orders of magnitude slower and
+# reported nowhere else, so the build refuses it.
+MAX_SCRATCH_BYTES_PER_LANE = 256
 
 
 def build_library(verbose: bool = False, jobs: int = 8, extra_flags=(), out: str | None = None) -> str:
@@ -47,12 +53,29 @@ def build_library(verbose: bool = False, jobs: int = 8, extra_flags=(), out: str
     return lib
 
 
+def _max_scratch(log: str):
+    """(largest ScratchSize [bytes/lane], its kernel) from the compiler's resource-usage remarks."""
+    worst, name, cur = 0, "", ""
+    for line in log.splitlines():
+        if "Function Name:" in line:
+            cur = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line:
+            v = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+            if v > worst:
+                worst, name = v, cur
+    return worst, name
+
+
 def _drain(procs, verbose):
     for src, p in procs:
         out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and l.strip())
+        worst = _max_scratch(out)
+        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l and l.strip())
         if p.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+        if worst[0] > MAX_SCRATCH_BYTES_PER_LANE:
+            raise RuntimeError(f"{src}: kernel {worst[1]} uses {worst[0]} bytes of scratch per lane "
+                               f"(limit {MAX_SCRATCH_BYTES_PER_LANE}): a register array went to memory")
         if verbose and out:
             print(out, flush=True)
     procs.clear()
