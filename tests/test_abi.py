@@ -42,3 +42,16 @@ def test_host_only_calls():
     assert lib.moe_workspace_bytes(-1, 2, 8, 128, 256) == 0
     assert lib.moe_route_topk(None, None, None, 1, 1, 1, 0, 0, ctypes.c_float(1.0), None, None, None) == -1
     assert lib.moe_ctx_destroy(None) == 0
+
+
+def test_build_refuses_register_arrays_in_scratch():
+    """The build reads the compiler's per-kernel resource report and fails when a kernel needs more scratch than a
+    few spilled registers (a register array demoted to memory); the parser picks the largest figure and its kernel."""
+    from paper_2603_07685_amd import build as b
+    log = ("gemm.hip:1:1: remark: Function Name: kernel_a [-Rpass-analysis=kernel-resource-usage]\n"
+           "gemm.hip:1:1: remark:     ScratchSize [bytes/lane]: 44 [-Rpass-analysis=kernel-resource-usage]\n"
+           "gemm.hip:9:1: remark: Function Name: kernel_b [-Rpass-analysis=kernel-resource-usage]\n"
+           "gemm.hip:9:1: remark:     ScratchSize [bytes/lane]: 640 [-Rpass-analysis=kernel-resource-usage]\n")
+    assert b._max_scratch(log) == (640, "kernel_b")
+    assert b._max_scratch("no remarks here") == (0, "")
+    assert 0 < b.MAX_SCRATCH_BYTES_PER_LANE < 640
