@@ -101,6 +101,16 @@ moe_status moe_route_topk(moe_ctx* ctx, void* stream, const float* logits, int T
                           int32_t* topk_idx, float* topk_prob, int32_t* counts);
 
 /*
+ * Gate GEMM in front of the router (Sec. 2.1.2 item 1): logits[t,e] = sum_i X[t,i] * Wr[e,i].
+ * X [T,h] and Wr [E,h] bf16 (Wr is W_r of the paper stored expert-major, like an expert's Linear
+ * weight), fp32 accumulation, logits [T,E] fp32 (Sec. 5.1 keeps the router in FP32).  E must be a
+ * multiple of 8, h of 64.  Stream-ordered, no allocation or copy; uses 8 bytes of the context's
+ * reserved workspace (calls on one context must not overlap).
+ */
+moe_status moe_gate_gemm(moe_ctx* ctx, void* stream, const void* X, const void* Wr, int T, int E, int h,
+                         float* logits);
+
+/*
  * Router with the branches Sec. 4.3.4 item 1 lists for the fused score kernel: group-limited
  * top-k, the load-balancing expert bias of the auxiliary-loss-free strategy (Sec. 7) and score
  * scaling.  The paper names them and cites their source; the published DeepSeek-V3 router is taken

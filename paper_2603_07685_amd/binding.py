@@ -29,7 +29,7 @@ EXPORTS = [
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
     "moe_route_topk_bwd", "moe_mx_quantize", "moe_mx_quantize_rowcol",
     "moe_route_topk_grouped", "moe_aux_loss", "moe_mx_quantize_rowcol_gather",
-    "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant",
+    "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gate_gemm",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
         L.moe_mx_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_fwd_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_dgrad_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.moe_gate_gemm.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
         L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
         L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
@@ -191,6 +192,10 @@ def moe_grouped_gemm_dgrad_quant(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_saved
                                                  _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(row_prob), _ptr(dA),
                                                  _ptr(dprob_part), _ptr(dz_q), _ptr(dz_q_scale)),
               "moe_grouped_gemm_dgrad_quant")
+
+
+def moe_gate_gemm(ctx, X, Wr, T, E, h, logits):
+    ctx.check(lib().moe_gate_gemm(ctx.h, _stream(), _ptr(X), _ptr(Wr), T, E, h, _ptr(logits)), "moe_gate_gemm")
 
 
 def moe_route_topk_bwd(ctx, logits, topk_idx, dprob, T, E, k, fn, norm_topk, scale, dlogits):

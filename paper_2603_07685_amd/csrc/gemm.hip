@@ -1174,3 +1174,32 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<wgrad>");
     return MOE_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Gate GEMM (Sec. 2.1.2 item 1): logits[T,E] = X[T,h] * Wr[E,h]^T, bf16 operands, fp32 accumulation and fp32
+// output (the router works on fp32 logits, Sec. 5.1).  One group of T rows through the forward kernel with the
+// fp32 store; the two-entry offsets array lives in the context's reserved workspace and is written by a
+// one-thread kernel, so the call allocates and copies nothing.  With E <= 256 there is one column tile: T / 256
+// workgroups have work, which is a quarter of the chip at T = 16384 -- small next to the layer, not tuned.
+// ---------------------------------------------------------------------------
+#define MOE_WS_GATE_OFFSETS 32  // byte offset of {0, T} in the reserved head of the workspace
+__global__ void gate_offsets_kernel(int32_t* o, int T) {
+    o[0] = 0;
+    o[1] = T;
+}
+
+extern "C" moe_status moe_gate_gemm(moe_ctx* ctx, void* stream, const void* X, const void* Wr, int T, int E, int h,
+                                    float* logits) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!logits) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_gate_gemm: logits is NULL");
+    if (T < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_gate_gemm: T must be positive");
+    int32_t* offsets = (int32_t*)((char*)ctx->ws + MOE_WS_GATE_OFFSETS);
+    moe_status st = gg_check_common(ctx, "moe_gate_gemm", X, Wr, offsets, 1, E, h, T, MOE_BF16);
+    if (st != MOE_OK) return st;
+    if (h % 64) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_gate_gemm: h=%d must be a multiple of 64", h);
+    hipLaunchKernelGGL(gate_offsets_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, offsets, T);
+    gg_args a = gg_make(ctx, X, Wr, offsets, 1, E, h, T, logits);
+    GG_LAUNCH(GG_FWD, GG_EPI_STORE, true, 0);
+    MOE_LAUNCH_CHECK(ctx, "gg_kernel<gate>");
+    return MOE_OK;
+}

@@ -258,3 +258,28 @@ def test_grouped_gemm_wgrad(B, ctx, oracle, counts, N, K, out_f32):
     B.moe_grouped_gemm_wgrad(ctx, A, dC, doff, E, N, K, Rcap, B.BF16, None, None, 1, odt, dB)
     torch.cuda.synchronize()
     assert rel_fro(host_f64(dB), 2 * ref) <= (1e-5 if out_f32 else BF16_TOL)
+
+
+@pytest.mark.parametrize("T,E,h", [(16384, 256, 7168), (1000, 8, 128), (300, 128, 4096), (1, 40, 64)])
+def test_gate_gemm_and_router_on_its_logits(B, ctx, oracle, T, E, h):
+    """logits = X Wr^T in fp32 from bf16 operands against the fp64 oracle; the router then selects on those logits
+    exactly what the oracle selects on the same numbers."""
+    from gpu_util import dev_bf16, rel_fro
+    from paper_2603_07685_amd import workloads as wl
+    Xh = wl.gaussian_bf16((T, h), 1.0, 31, T)
+    Wh = wl.gaussian_bf16((E, h), 0.02, 32, E)
+    logits = torch.full((T, E), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_gate_gemm(ctx, dev_bf16(Xh), dev_bf16(Wh), T, E, h, logits)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    got = logits.cpu().numpy()
+    ref = oracle.grouped_gemm_nt(Xh, Wh[None], np.array([0, T], np.int32))
+    assert np.isfinite(got).all()
+    assert rel_fro(got, ref) <= 2e-6                        # fp32 accumulation of exact bf16 products
+    k = min(8, E)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    prob = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_route_topk(ctx, logits, T, E, k, 0, False, 1.0, idx, prob, None)
+    torch.cuda.synchronize()
+    o_idx, o_prob, _ = oracle.route_topk(got, k, 0, False)
+    assert np.array_equal(idx.cpu().numpy(), o_idx)
