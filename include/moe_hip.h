@@ -248,7 +248,7 @@ moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, con
                                   int accumulate, moe_dtype out_dt, void* dB);
 
 /*
- * Memory-efficient permutation (Sec. 4.2.1, eq. (2)): the routing weight multiplies the
+ * Memory-efficient permutation (Sec. 4.1.2, eq. (2)): the routing weight multiplies the
  * activation before fc2, the combine is then a plain sum (moe_unpermute_combine with
  * prob = NULL), and dL/dp needs only the saved pre-activations, not the expert outputs.
  *

@@ -345,7 +345,7 @@ def layer_backward(fw, X, prob, W1, W2, dY, Ws1=None, Ws2=None, prec="f64"):
 
 
 # ----------------------------------------------------------------------------
-# the same layer with the routing weight absorbed into the activation (Sec. 4.2.1, eq. (2))
+# the same layer with the routing weight absorbed into the activation (Sec. 4.1.2, eq. (2))
 # ----------------------------------------------------------------------------
 def gather_row_prob(prob, src_of):
     """row_prob[r] = prob[t,s] of the slot that row r holds; 0 for padding rows."""

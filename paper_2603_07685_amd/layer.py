@@ -44,7 +44,7 @@ class LayerState:
                  variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False,
                  fused_quant: bool | None = None, epilogue_quant: bool | None = None):
         self.cfg = cfg
-        self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.2.1): weights applied before fc2
+        self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.1.2): weights applied before fc2
         # MXFP8 only (default there): the permuted tokens and the combine's backward are quantised straight from
         # X / dY through the row map, padding included (Sec. 5.4.1, 5.4.2); Xp and dO are never stored in bf16
         self.fused_quant = bool(cfg.mx) if fused_quant is None else bool(fused_quant)

@@ -67,7 +67,7 @@ def test_layer_forward_backward_every_element(oracle, name, shared_f):
 
 @pytest.mark.parametrize("name,shared_f", [("C1", 64), ("MID", 0)])
 def test_layer_eq2_every_element(oracle, name, shared_f):
-    """The memory-efficient permutation variant (Sec. 4.2.1, eq. (2)) of the whole layer, every element:
+    """The memory-efficient permutation variant (Sec. 4.1.2, eq. (2)) of the whole layer, every element:
     weights applied in the fc1 epilogue, plain-sum combine, dprob from the fused fc2 data gradient."""
     from gpu_util import host_f64, rel_fro, BF16_TOL
     from paper_2603_07685_amd import workloads as wl

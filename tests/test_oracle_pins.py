@@ -498,7 +498,7 @@ def test_router_backward_finite_differences(oracle, score, norm):
 
 
 def test_eq2_layer_matches_eq1_and_finite_differences(oracle):
-    """Memory-efficient permutation (Sec. 4.2.1): eq. (2) is an algebraic rearrangement of eq. (1), so its
+    """Memory-efficient permutation (Sec. 4.1.2): eq. (2) is an algebraic rearrangement of eq. (1), so its
     forward output and every gradient must equal eq. (1)'s (themselves pinned above), and its own loss must
     reproduce its dprob by central differences (dprob is the one gradient computed by a different formula)."""
     X, logits, W1, W2, Ws1, Ws2, dY = _tiny_layer(21, T=12, h=6, f=5, E=4, k=2)
