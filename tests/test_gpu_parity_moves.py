@@ -297,3 +297,43 @@ def test_round_trip_is_identity(B, ctx, oracle):
     B.moe_unpermute_combine(ctx, Xp, B.BF16, row_of, w, None, T, k, h, Y)
     torch.cuda.synchronize()
     assert torch.equal(Y.view(torch.int16), X.view(torch.int16))
+
+
+def test_empty_batch_and_all_experts_empty(B, ctx, oracle):
+    """Degenerate extents end to end: T = 0 through route / permute / combine, and grouped GEMMs whose offsets say
+    that no expert has a row (forward and data gradient touch nothing, the weight gradient is exact zeros)."""
+    from gpu_util import dev
+    E, k, h, f = 4, 2, 64, 64
+    # T = 0: nothing to read; counts and offsets are still written (all zero).  (One-row buffers stand in for the
+    # empty tensors: torch gives a zero-size tensor a NULL data pointer, and a pointer must still be a pointer)
+    empty = lambda cols, dt: torch.zeros((1, cols), dtype=dt, device="cuda")
+    idx, prob = empty(k, torch.int32), empty(k, torch.float32)
+    counts = torch.full((E,), 7, dtype=torch.int32, device="cuda")
+    B.moe_route_topk(ctx, empty(E, torch.float32), 0, E, k, 0, False, 1.0, idx, prob, counts)
+    Rcap = 8
+    X = empty(h, torch.bfloat16)
+    Xp = torch.full((Rcap, h), 3.0, dtype=torch.bfloat16, device="cuda")
+    row_of = empty(k, torch.int32)
+    src_of = torch.full((Rcap,), 5, dtype=torch.int32, device="cuda")
+    offsets = torch.full((E + 1,), 9, dtype=torch.int32, device="cuda")
+    cnt2 = torch.full((E,), 9, dtype=torch.int32, device="cuda")
+    B.moe_permute(ctx, X, B.BF16, idx, 0, k, h, E, 1, Xp, Rcap, row_of, src_of, offsets, cnt2)
+    Y = empty(h, torch.bfloat16)
+    B.moe_unpermute_combine(ctx, Xp, B.BF16, row_of, prob, None, 0, k, h, Y)
+    torch.cuda.synchronize()
+    assert not counts.any() and not cnt2.any() and not offsets.any()
+    assert (src_of == -1).all() and (Xp == 3.0).all()
+    # all experts empty
+    W = torch.ones((E, 2 * f, h), dtype=torch.bfloat16, device="cuda")
+    A = torch.ones((Rcap, h), dtype=torch.bfloat16, device="cuda")
+    Z = torch.full((Rcap, 2 * f), 3.0, dtype=torch.bfloat16, device="cuda")
+    Act = torch.full((Rcap, f), 3.0, dtype=torch.bfloat16, device="cuda")
+    dA = torch.full((Rcap, h), 3.0, dtype=torch.bfloat16, device="cuda")
+    dW = torch.full((E, 2 * f, h), 3.0, dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_fwd(ctx, A, W, offsets, E, 2 * f, h, Rcap, B.BF16, B.EPI_SWIGLU, None, None, Z, Act)
+    B.moe_grouped_gemm_dgrad(ctx, Z, W, offsets, E, 2 * f, h, Rcap, B.BF16, None, None, None, dA)
+    B.moe_grouped_gemm_wgrad(ctx, A, Z, offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, B.BF16, dW)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    assert (Z == 3.0).all() and (Act == 3.0).all() and (dA == 3.0).all()
+    assert not dW.any()
