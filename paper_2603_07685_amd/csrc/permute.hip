@@ -16,7 +16,9 @@
 #include "common.h"
 #include "layout.h"
 
+#ifndef MOVE_THREADS
 #define MOVE_THREADS 256
+#endif
 
 __device__ __forceinline__ u32x4_t mk4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     u32x4_t v = {a, b, c, d};

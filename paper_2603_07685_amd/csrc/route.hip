@@ -437,7 +437,7 @@ template <int VPL>
 __global__ __launch_bounds__(ROUTE_WAVES * 64) void aux_loss_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ counts, int T, int E, int fn, float wscale, float g,
     int accumulate, float* __restrict__ dlogits, double* __restrict__ partial) {
-    extern __shared__ float wsh[];  // [E] weights, then ROUTE_WAVES doubles
+    extern __shared__ __attribute__((aligned(16))) float wsh[];  // [E] weights, then ROUTE_WAVES doubles
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     for (int e = threadIdx.x; e < E; e += blockDim.x) wsh[e] = wscale * (float)counts[e];
