@@ -283,3 +283,35 @@ def test_gate_gemm_and_router_on_its_logits(B, ctx, oracle, T, E, h):
     torch.cuda.synchronize()
     o_idx, o_prob, _ = oracle.route_topk(got, k, 0, False)
     assert np.array_equal(idx.cpu().numpy(), o_idx)
+
+
+@pytest.mark.parametrize("E", [700, 1024])
+def test_grouped_gemms_many_small_experts(B, ctx, oracle, E):
+    """Hundreds of experts with 0..300 rows each (about a third of them empty): the device-side tile schedule, the
+    expert search and the weight gradient's cost ordering beyond one pass of the workgroup's threads."""
+    from gpu_util import dev, dev_bf16, host_f64, rel_fro, BF16_TOL
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(E)
+    counts = g.integers(0, 301, size=E)
+    counts[g.random(E) < 0.33] = 0
+    counts[E // 2] = 1500                                            # one expert far above the rest
+    off = _offsets(counts)
+    R = int(off[-1])
+    N, K = 128, 64
+    Ah = wl.gaussian_bf16((R, K), 1.0, 51, E)
+    Wh = wl.gaussian_bf16((E, N, K), 1.0, 52, E)
+    dCh = wl.gaussian_bf16((R, N), 1.0, 53, E)
+    A, W, dC, doff = dev_bf16(Ah), dev_bf16(Wh), dev_bf16(dCh), dev(off)
+    C = torch.full((R, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dA = torch.full((R, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dW = torch.full((E, N, K), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_grouped_gemm_fwd(ctx, A, W, doff, E, N, K, R, B.BF16, B.EPI_NONE, None, None, C, None)
+    B.moe_grouped_gemm_dgrad(ctx, dC, W, doff, E, N, K, R, B.BF16, None, None, None, dA)
+    B.moe_grouped_gemm_wgrad(ctx, A, dC, doff, E, N, K, R, B.BF16, None, None, 0, B.F32, dW)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    assert rel_fro(host_f64(C), oracle.grouped_gemm_nt(Ah, Wh, off)) <= BF16_TOL
+    assert rel_fro(host_f64(dA), oracle.grouped_gemm_nn(dCh, Wh, off)) <= BF16_TOL
+    got = host_f64(dW)
+    assert rel_fro(got, oracle.grouped_gemm_tn(dCh, Ah, off)) <= 1e-5
+    assert not got[counts == 0].any()
