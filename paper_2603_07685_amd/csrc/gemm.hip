@@ -874,12 +874,16 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                     if (c < K) {
                         bf16_t* dZ = (bf16_t*)a.out;
                         const int64_t zr = (int64_t)r * 2 * K;
-                        if (!Z_EARLY) {
-                            zg[x8] = *(const u32x2_t*)(a.Zsaved + zr + c);
-                            zu[x8] = *(const u32x2_t*)(a.Zsaved + zr + K + c);
+                        u32x2_t zgv, zuv;  // (not through the arrays when the row loop is rolled: no runtime index)
+                        if (Z_EARLY) {
+                            zgv = zg[x8];
+                            zuv = zu[x8];
+                        } else {
+                            zgv = *(const u32x2_t*)(a.Zsaved + zr + c);
+                            zuv = *(const u32x2_t*)(a.Zsaved + zr + K + c);
                         }
-                        const float gt[4] = {bf16_lo(zg[x8].x), bf16_hi(zg[x8].x), bf16_lo(zg[x8].y), bf16_hi(zg[x8].y)};
-                        const float up[4] = {bf16_lo(zu[x8].x), bf16_hi(zu[x8].x), bf16_lo(zu[x8].y), bf16_hi(zu[x8].y)};
+                        const float gt[4] = {bf16_lo(zgv.x), bf16_hi(zgv.x), bf16_lo(zgv.y), bf16_hi(zgv.y)};
+                        const float up[4] = {bf16_lo(zuv.x), bf16_hi(zuv.x), bf16_lo(zuv.y), bf16_hi(zuv.y)};
                         float dg[4], du[4];
                         const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
 #pragma unroll
