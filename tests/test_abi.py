@@ -55,3 +55,11 @@ def test_build_refuses_register_arrays_in_scratch():
     assert b._max_scratch(log) == (640, "kernel_b")
     assert b._max_scratch("no remarks here") == (0, "")
     assert 0 < b.MAX_SCRATCH_BYTES_PER_LANE < 640
+
+
+def test_header_is_plain_c_and_cxx():
+    """The boundary is a C ABI: the header must compile on its own as C99 and as C++11, warnings included."""
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "moe_hip.h")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", hdr])
