@@ -45,7 +45,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4",
                     help="C1 | MID | C2 | C3 | C4 | C4G (C4 behind the group-limited, bias-corrected router) | C5 (blockwise fp8) | C6 (MXFP8) (default: the metric's config, C4)")
-    ap.add_argument("--variant", default=None, help="load pattern override: uniform | zeros | hot | cv | zipf")
+    ap.add_argument("--variant", default=None,
+                    help="load pattern override: uniform | zeros | hot | cv | zipf | router (the router's own top-k over "
+                         "the global experts; only hits on the local experts become rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad-f32", action="store_true", help="fp32 weight gradients (default bf16)")
     ap.add_argument("--graph", action="store_true",
@@ -59,7 +61,9 @@ def describe_call(name, args, st):
     """(label, flops or None, bytes or None) of one library call, from its own arguments."""
     cfg = st.cfg
     T, k = cfg.T, cfg.k
-    R = T * k  # routed rows (unpadded): the algorithmic row count of the grouped calls
+    # routed rows (unpadded): the algorithmic row count of the grouped calls.  With the router's own top-k over more
+    # experts than live on this GPU (--variant router) only the local hits are rows: counted after the warm-up
+    R = getattr(st, "R_live", None) or T * k
     if name == "moe_gather_row_prob":
         return "gather_row_prob", None, args[3] * 12
     if name == "moe_scatter_row_dprob":
@@ -255,6 +259,8 @@ def main():
     for _ in range(args.warmup):
         st.step()
     torch.cuda.synchronize()
+    if st.forced_idx is None and cfg.E_router > cfg.E:
+        st.R_live = int(st.counts.sum().item())   # rows whose expert lives here (outside the timed region)
     # timed region: K steps; every library call is followed by an event on the launch stream, so the
     # per-kernel durations come from the timed region itself (an event record costs about a microsecond)
     t0 = time.perf_counter()
@@ -295,6 +301,8 @@ def main():
     peak = FP8_PEAK_TFLOPS if n_dom.endswith("fp8") else BF16_PEAK_TFLOPS  # ("..._fp8" and "..._mxfp8")
 
     flops = cfg.model_flops()
+    if getattr(st, "R_live", None):
+        flops = 18.0 * st.R_live * cfg.h * cfg.f + 18.0 * cfg.T * cfg.h * st.sf
     out = {
         "metric": "MoE-layer fwd+bwd TFLOPS/GPU at DeepSeek-V3 local shape" if args.workload == "C4"
                   else f"MoE-layer fwd+bwd TFLOPS/GPU ({cfg.name})",
@@ -337,7 +345,7 @@ def main():
         torch.cuda.synchronize()
         gms = g0.elapsed_time(g1) / args.steps
         assert st.ctx.poll_error() == 0
-        out["graph"] = {"ms_per_step": round(gms, 4), "tflops": round(cfg.model_flops() / gms / 1e9, 2)}
+        out["graph"] = {"ms_per_step": round(gms, 4), "tflops": round(flops / gms / 1e9, 2)}
     # context only: the vendor dense bf16 GEMM through torch on this very box (boxes differ by +-20 %)
     a_ref = torch.randn((16384, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
     b_ref = torch.randn((4096, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
