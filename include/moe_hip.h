@@ -205,7 +205,10 @@ moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe_dtype dt,
  * 128 (fp8) / 16 (bf16); in bf16 the contraction dimension of fwd (K) and of
  * dgrad (N) must also be a multiple of 64 (one 128-byte operand row per stage);
  * wgrad contracts over the expert's rows, any count.  Sizes outside these limits
- * return MOE_ERR_UNSUPPORTED and touch nothing.  wgrad with dt = MOE_FP8_E4M3 is
+ * return MOE_ERR_UNSUPPORTED and touch nothing.  dt = MOE_F32: every operand and result is fp32
+ * (fp32 accumulation in increasing contraction index; wgrad needs out_dt = MOE_F32; any N, K >= 1);
+ * a plain one-thread-per-output path for parity runs at the 1e-5 level on small layers, not tuned.
+ * wgrad with dt = MOE_FP8_E4M3 is
  * not built and returns MOE_ERR_UNSUPPORTED.  dt = MOE_MXFP8_E4M3 (Sec. 5.3.3) is
  * described with moe_mx_quantize below; all three calls take it.
  *

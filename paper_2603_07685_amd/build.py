@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoe_hip.so")
-SOURCES = ["ctx.hip", "route.hip", "permute.hip", "gemm.hip", "fp8.hip"]  # missing files are skipped while the library grows
+SOURCES = ["ctx.hip", "route.hip", "permute.hip", "gemm.hip", "gemm_f32.hip", "fp8.hip"]  # missing files are skipped while the library grows
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -76,5 +76,13 @@ __device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d
     return (uint32_t)w;
 }
 
+// all-fp32 grouped GEMMs (gemm_f32.hip), reached from the public entry points with dt = MOE_F32
+moe_status moe_gg_f32_fwd(moe_ctx* ctx, hipStream_t s, const void* A, const void* B, const int32_t* offsets, int E, int N,
+                          int K, int64_t Rcap, int swiglu, const float* row_prob, void* C, void* C_act);
+moe_status moe_gg_f32_dgrad(moe_ctx* ctx, hipStream_t s, const void* dC, const void* B, const int32_t* offsets, int E, int N,
+                            int K, int64_t Rcap, const void* Z_saved, const float* row_prob, void* dA);
+moe_status moe_gg_f32_wgrad(moe_ctx* ctx, hipStream_t s, const void* A, const void* dC, const int32_t* offsets, int E, int N,
+                            int K, int64_t Rcap, int accumulate, void* dB);
+
 // shared by the fill launches of several files
 void moe_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s);

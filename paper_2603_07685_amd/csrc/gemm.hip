@@ -1058,6 +1058,13 @@ extern "C" moe_status moe_grouped_gemm_fwd_quant(moe_ctx* ctx, void* stream, con
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_quant: act_q and act_q_scale go together");
     if (act_q && (dt != MOE_FP8_E4M3 || epi != MOE_EPI_SWIGLU))
         MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd_quant: quantised output needs dt = MOE_FP8_E4M3 and the SwiGLU epilogue");
+    if (dt == MOE_F32) {  // all-fp32 path (gemm_f32.hip)
+        if (!A || !B || !offsets) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: NULL pointer");
+        if (E < 1 || N < 1 || K < 1 || Rcap < 1 || Rcap > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: bad sizes");
+        if (epi == MOE_EPI_SWIGLU ? (!C_act || N % 2) : (epi != MOE_EPI_NONE || !C || row_prob))
+            MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd(f32): bad epilogue arguments");
+        return moe_gg_f32_fwd(ctx, (hipStream_t)stream, A, B, offsets, E, N, K, Rcap, epi == MOE_EPI_SWIGLU, row_prob, C, C_act);
+    }
     if (row_prob && epi != MOE_EPI_SWIGLU)
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_weighted: row weights go with the SwiGLU epilogue");
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_fwd", A, B, offsets, E, N, K, Rcap, dt);
@@ -1122,6 +1129,13 @@ extern "C" moe_status moe_grouped_gemm_dgrad_quant(moe_ctx* ctx, void* stream, c
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_quant: dz_q and dz_q_scale go together");
     if (dz_q && (dt != MOE_FP8_E4M3 || !Z_saved))
         MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad_quant: quantised output needs dt = MOE_FP8_E4M3 and Z_saved");
+    if (dt == MOE_F32) {  // all-fp32 path (gemm_f32.hip)
+        if (!dC || !B || !offsets || !dA) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: NULL pointer");
+        if (E < 1 || N < 1 || K < 1 || Rcap < 1 || Rcap > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad: bad sizes");
+        if (dprob_part) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad(f32): dprob_part is not built for fp32 operands");
+        if (row_prob && !Z_saved) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad(f32): row weights need Z_saved");
+        return moe_gg_f32_dgrad(ctx, (hipStream_t)stream, dC, B, offsets, E, N, K, Rcap, Z_saved, row_prob, dA);
+    }
     if ((row_prob || dprob_part) && !Z_saved)
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_weighted: row weights / dprob_part need Z_saved");
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_dgrad", dC, B, offsets, E, N, K, Rcap, dt);
@@ -1156,6 +1170,12 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
                                              moe_dtype dt, const float* a_scale, const float* dc_scale,
                                              int accumulate, moe_dtype out_dt, void* dB) {
     if (!ctx) return MOE_ERR_ARG;
+    if (dt == MOE_F32) {  // all-fp32 path (gemm_f32.hip)
+        if (!A || !dC || !offsets || !dB) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: NULL pointer");
+        if (E < 1 || N < 1 || K < 1 || Rcap < 1 || Rcap > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: bad sizes");
+        if (out_dt != MOE_F32) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad(f32): out_dt must be MOE_F32");
+        return moe_gg_f32_wgrad(ctx, (hipStream_t)stream, A, dC, offsets, E, N, K, Rcap, accumulate, dB);
+    }
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_wgrad", dC, A, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
     if (dt == MOE_FP8_E4M3)

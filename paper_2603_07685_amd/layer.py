@@ -42,7 +42,7 @@ class LayerState:
 
     def __init__(self, cfg: wl.MoEConfig, hin: dict | None = None, shared_f: int | None = None,
                  variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False,
-                 fused_quant: bool | None = None, epilogue_quant: bool | None = None):
+                 fused_quant: bool | None = None, epilogue_quant: bool | None = None, f32: bool = False):
         self.cfg = cfg
         self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.1.2): weights applied before fc2
         # MXFP8 only (default there): the permuted tokens and the combine's backward are quantised straight from
@@ -61,14 +61,23 @@ class LayerState:
             Rcap = (Rcap + 127) // 128 * 128
         self.Rcap = Rcap
         self.ctx = B.Context(T, k, max(E, cfg.E_router), h, max(f, sf))
-        bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+        # all-fp32 run (small layers, host inputs): every tensor and every call in fp32, for parity at the 1e-5 level
+        self.f32 = bool(f32)
+        assert not self.f32 or (hin is not None and not cfg.fp8 and not cfg.mx and not self.eq2), \
+            "the all-fp32 run takes host inputs, eq. (1), no fp8"
+        self.dt = B.F32 if self.f32 else B.BF16
+        i32, f32 = torch.int32, torch.float32
+        bf = f32 if self.f32 else torch.bfloat16   # storage type of activations, weights and gradients
+        if self.f32:
+            wgrad_f32 = True
         dev = "cuda"
         s = cfg.seed
         if hin is not None:
+            put = (lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()) if self.f32 else _dev_bf16
             self.logits = torch.from_numpy(hin["logits"]).cuda()
-            self.X, self.W1, self.W2, self.dY = (_dev_bf16(hin[n]) for n in ("X", "W1", "W2", "dY"))
+            self.X, self.W1, self.W2, self.dY = (put(hin[n]) for n in ("X", "W1", "W2", "dY"))
             if sf:
-                self.Ws1, self.Ws2 = _dev_bf16(hin["Ws1"]), _dev_bf16(hin["Ws2"])
+                self.Ws1, self.Ws2 = put(hin["Ws1"]), put(hin["Ws2"])
         else:  # large configs: draw on the device
             g = torch.Generator(device=dev)
             g.manual_seed(s)
@@ -217,22 +226,22 @@ class LayerState:
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         self._route()
         idx = self.topk_idx if self.forced_idx is None else self.forced_idx
-        B.moe_permute(c, self.X, B.BF16, idx, T, k, h, E, self.align, self.Xp, Rcap,
+        B.moe_permute(c, self.X, self.dt, idx, T, k, h, E, self.align, self.Xp, Rcap,
                       self.row_of, self.src_of, self.offsets, self.counts)
         row_prob = None
         if self.eq2:  # eq. (2): A = p * silu(gate) * up, plain-sum combine
             B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
             row_prob = self.row_prob
-        B.moe_grouped_gemm_fwd_weighted(c, self.Xp, self.W1, self.offsets, E, 2 * f, h, Rcap, B.BF16, B.EPI_SWIGLU,
+        B.moe_grouped_gemm_fwd_weighted(c, self.Xp, self.W1, self.offsets, E, 2 * f, h, Rcap, self.dt, B.EPI_SWIGLU,
                                         None, None, row_prob, self.Z, self.A)
-        B.moe_grouped_gemm_fwd(c, self.A, self.W2, self.offsets, E, h, f, Rcap, B.BF16, B.EPI_NONE,
+        B.moe_grouped_gemm_fwd(c, self.A, self.W2, self.offsets, E, h, f, Rcap, self.dt, B.EPI_NONE,
                                None, None, self.O, None)
         if sf:
-            B.moe_grouped_gemm_fwd(c, self.X, self.Ws1, self.off_shared, 1, 2 * sf, h, T, B.BF16, B.EPI_SWIGLU,
+            B.moe_grouped_gemm_fwd(c, self.X, self.Ws1, self.off_shared, 1, 2 * sf, h, T, self.dt, B.EPI_SWIGLU,
                                    None, None, self.Zs, self.As)
-            B.moe_grouped_gemm_fwd(c, self.As, self.Ws2, self.off_shared, 1, h, sf, T, B.BF16, B.EPI_NONE,
+            B.moe_grouped_gemm_fwd(c, self.As, self.Ws2, self.off_shared, 1, h, sf, T, self.dt, B.EPI_NONE,
                                    None, None, self.S, None)
-        B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, None if self.eq2 else self.topk_prob,
+        B.moe_unpermute_combine(c, self.O, self.dt, self.row_of, None if self.eq2 else self.topk_prob,
                                 self.S if sf else None, T, k, h, self.Y)
 
     # ---- backward: combine, fc2 (wgrad, dgrad + SwiGLU'), fc1 (wgrad, dgrad), permute ---------
@@ -242,32 +251,32 @@ class LayerState:
         wdt = self.wgrad_dt
         if self.eq2:
             # dO = plain copies of dY (no weight, O is not read); dprob comes out of the fc2 data gradient
-            B.moe_unpermute_combine_bwd(c, self.dY, None, B.BF16, self.row_of, self.src_of, None,
+            B.moe_unpermute_combine_bwd(c, self.dY, None, self.dt, self.row_of, self.src_of, None,
                                         T, k, h, Rcap, self.dO, None)
-            B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt,
+            B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, self.dt, None, None, 0, wdt,
                                      self.dW2)
-            B.moe_grouped_gemm_dgrad_weighted(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, B.BF16, self.Z, None,
+            B.moe_grouped_gemm_dgrad_weighted(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, self.dt, self.Z, None,
                                               None, self.row_prob, self.dZ, self.dprob_part)
             B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
         else:
-            B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
+            B.moe_unpermute_combine_bwd(c, self.dY, self.O, self.dt, self.row_of, self.src_of, self.topk_prob,
                                         T, k, h, Rcap, self.dO, self.dprob)
-            B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, B.BF16, None, None, 0, wdt,
+            B.moe_grouped_gemm_wgrad(c, self.A, self.dO, self.offsets, E, h, f, Rcap, self.dt, None, None, 0, wdt,
                                      self.dW2)
-            B.moe_grouped_gemm_dgrad(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, B.BF16, self.Z, None, None,
+            B.moe_grouped_gemm_dgrad(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, self.dt, self.Z, None, None,
                                      self.dZ)
-        B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, 0, wdt,
+        B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, self.dt, None, None, 0, wdt,
                                  self.dW1)
-        B.moe_grouped_gemm_dgrad(c, self.dZ, self.W1, self.offsets, E, 2 * f, h, Rcap, B.BF16, None, None, None,
+        B.moe_grouped_gemm_dgrad(c, self.dZ, self.W1, self.offsets, E, 2 * f, h, Rcap, self.dt, None, None, None,
                                  self.dXp)
         if sf:
             o1 = self.off_shared
-            B.moe_grouped_gemm_wgrad(c, self.As, self.dY, o1, 1, h, sf, T, B.BF16, None, None, 0, wdt, self.dWs2)
-            B.moe_grouped_gemm_dgrad(c, self.dY, self.Ws2, o1, 1, h, sf, T, B.BF16, self.Zs, None, None, self.dZs)
-            B.moe_grouped_gemm_wgrad(c, self.X, self.dZs, o1, 1, 2 * sf, h, T, B.BF16, None, None, 0, wdt, self.dWs1)
-            B.moe_grouped_gemm_dgrad(c, self.dZs, self.Ws1, o1, 1, 2 * sf, h, T, B.BF16, None, None, None, self.dXs)
+            B.moe_grouped_gemm_wgrad(c, self.As, self.dY, o1, 1, h, sf, T, self.dt, None, None, 0, wdt, self.dWs2)
+            B.moe_grouped_gemm_dgrad(c, self.dY, self.Ws2, o1, 1, h, sf, T, self.dt, self.Zs, None, None, self.dZs)
+            B.moe_grouped_gemm_wgrad(c, self.X, self.dZs, o1, 1, 2 * sf, h, T, self.dt, None, None, 0, wdt, self.dWs1)
+            B.moe_grouped_gemm_dgrad(c, self.dZs, self.Ws1, o1, 1, 2 * sf, h, T, self.dt, None, None, None, self.dXs)
         # dX[t] = sum of the k permuted-row gradients (+ the shared expert's dX): the plain-sum unpermute
-        B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
+        B.moe_unpermute_combine(c, self.dXp, self.dt, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
 
     # ---- fp8 (blockwise, Sec. 5.3.2, or MXFP8, Sec. 5.3.3): forward and data-gradient GEMMs on E4M3 codes;
     # weights are re-quantised every step (MXFP8: in both directions, one pass); MXFP8 also runs the weight

@@ -99,3 +99,41 @@ def test_layer_eq2_every_element(oracle, name, shared_f):
     print(name, "eq2", {k: f"{v:.2e}" for k, v in errs.items()})
     for k, v in errs.items():
         assert v <= BF16_TOL, (k, v)
+
+
+@pytest.mark.parametrize("name,shared_f", [("C1", 0), ("C1", 64), ("MID", 0)])
+def test_layer_all_fp32_every_element(oracle, name, shared_f):
+    """The tiny config is generated in fp32: the whole layer with fp32 tensors and the fp32 GEMM path (dt = MOE_F32)
+    against the fp64 oracle at the 1e-5 level, every element of every tensor."""
+    from gpu_util import host_f64, rel_fro
+    from paper_2603_07685_amd import workloads as wl
+    from paper_2603_07685_amd import layer as L
+    TOL = 1e-5
+    cfg = wl.CONFIGS[name]
+    hin = L.host_inputs(cfg, shared_f=shared_f)
+    st = L.LayerState(cfg, hin, shared_f=shared_f, f32=True)
+    assert st.X.dtype == torch.float32 and st.dW1.dtype == torch.float32
+    st.step()
+    torch.cuda.synchronize()
+    assert st.ctx.poll_error() == 0
+    o_idx, o_prob, _ = oracle.route_topk(hin["logits"], cfg.k, cfg.score, cfg.norm_topk)
+    assert np.array_equal(st.topk_idx.cpu().numpy(), o_idx)
+    fw = oracle.layer_forward(hin["X"], o_idx, o_prob, hin["W1"], hin["W2"], cfg.E, cfg.align, hin.get("Ws1"), hin.get("Ws2"))
+    bw = oracle.layer_backward(fw, hin["X"], o_prob, hin["W1"], hin["W2"], hin["dY"], hin.get("Ws1"), hin.get("Ws2"))
+    R = fw.R
+    assert np.array_equal(st.row_of.cpu().numpy(), fw.maps.row_of)
+    assert np.array_equal(host_f64(st.Xp)[:R], fw.Xp)
+    errs = {
+        "Z": rel_fro(host_f64(st.Z)[:R], fw.Z), "A": rel_fro(host_f64(st.A)[:R], fw.A),
+        "O": rel_fro(host_f64(st.O)[:R], fw.O), "Y": rel_fro(host_f64(st.Y), fw.Y),
+        "dO": rel_fro(host_f64(st.dO)[:R], bw.dO), "dprob": rel_fro(host_f64(st.dprob), bw.dprob),
+        "dW2": rel_fro(host_f64(st.dW2), bw.dW2), "dZ": rel_fro(host_f64(st.dZ)[:R], bw.dZ),
+        "dW1": rel_fro(host_f64(st.dW1), bw.dW1), "dXp": rel_fro(host_f64(st.dXp)[:R], bw.dXp),
+        "dX": rel_fro(host_f64(st.dX), bw.dX + (bw.dX_shared if shared_f else 0.0)),
+    }
+    if shared_f:
+        errs.update({"S": rel_fro(host_f64(st.S), fw.S), "dWs1": rel_fro(host_f64(st.dWs1), bw.dWs1),
+                     "dWs2": rel_fro(host_f64(st.dWs2), bw.dWs2)})
+    print(name, "fp32", {k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= TOL, (k, v)
