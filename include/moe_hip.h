@@ -241,6 +241,9 @@ moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const void* dC, co
  *        The contraction length is the expert's (padded) row count, read from
  *        `offsets`; an expert with no rows gets dB_e = 0 (accumulate = 0) or is
  *        left as it is (accumulate != 0: dB += ...).  out_dt: MOE_BF16 or MOE_F32.
+ *        Under a skewed load the tiles are handed out through a counter in the context's
+ *        reserved workspace (results are unaffected): wgrad calls on one context must not
+ *        overlap in time.
  *        MXFP8: both operands are quantised in 32x1 blocks down the token dimension
  *        (see moe_mx_quantize); every offsets[e] must then be a multiple of 128
  *        (moe_permute with align = 128).  Blockwise fp8 is not built for this call.

@@ -193,6 +193,7 @@ struct gg_args {
     // activation [rows, N/2]; dgrad SWIGLU_BWD: of dZ [rows, 2K]), the operand of the next GEMM (Sec. 5.4.2)
     uint8_t* out_q;
     float* out_q_scale;
+    int* tile_counter;     // wgrad: zeroed device counter for the dynamic tile order under skewed loads (see the kernel)
     float* dprob_part;     // eq. (2), dgrad SWIGLU_BWD: [Rcap, ceil(K/256)] partial <dA, act(Z)> per row and column tile
 };
 
@@ -229,6 +230,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     char* const ldsQ1 = ldsP1 + GG_STAGE_BYTES + SC_BYTES;
     __shared__ int offs[GG_MAX_E + 1];
     __shared__ int tile_start[GG_MAX_E + 1];
+    __shared__ int dyn_next;
 
     static_assert(!(F8 == 1 && MODE == GG_WGRAD), "blockwise fp8 weight gradients are not built");
     constexpr bool P_CMAJ = (MODE == GG_WGRAD);
@@ -577,11 +579,36 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         }
         return q + n * G;
     };
-    if (tile_of(0) < total_tiles) {
-        setup_tile(tile_of(0));
+    // Weight gradient under a skewed load (largest expert above twice the mean): a static deal cannot balance when one
+    // tile of the largest expert is most of a workgroup's share, so the workgroups then draw tiles from a device
+    // counter in the same descending-cost order (longest-processing-time-first list scheduling): whoever finishes
+    // early takes the next tile.  Which workgroup computes a tile changes, what the tile computes does not.  The
+    // draw for the tile after this one is issued at the top of a tile and collected after its contraction.
+    bool dyn = false;
+    if (MODE == GG_WGRAD && a.tile_counter != nullptr && total_tiles > 0) {
+        const int emax = __builtin_amdgcn_readfirstlane(tile_start[0]);
+        const int64_t rows_max = __builtin_amdgcn_readfirstlane(offs[emax + 1]) - __builtin_amdgcn_readfirstlane(offs[emax]);
+        const int64_t rows_all = __builtin_amdgcn_readfirstlane(offs[E]) - __builtin_amdgcn_readfirstlane(offs[0]);
+        dyn = rows_max * E > 2 * rows_all;
+    }
+    auto draw = [&]() -> int {  // thread 0 only
+        return tid == 0 ? atomicAdd(a.tile_counter, 1) : 0;
+    };
+    auto publish = [&](int v) -> int {  // thread 0's value to every wave
+        if (tid == 0) dyn_next = v;
+        wait_lgkm0();
+        stage_barrier();
+        return __builtin_amdgcn_readfirstlane(dyn_next);
+    };
+    int t_first = tile_of(0);
+    if (dyn) t_first = publish(draw());
+    if (t_first < total_tiles) {
+        setup_tile(t_first);
         issue_stage0();
     }
-    for (int n_tile = 0, t = tile_of(0); t < total_tiles; ++n_tile, t = tile_of(n_tile)) {
+    for (int n_tile = 0, t = t_first; t < total_tiles; ++n_tile) {
+        int drawn = 0;
+        if (dyn) drawn = draw();
         float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[2] = {1.f, 1.f};
         f32x16_t acc[4][2];
 #pragma unroll
@@ -808,8 +835,9 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         // (every wave is past its last LDS read here: the stage loop ends with a barrier after the last
         // fragment reads of both groups)
         const int ep_e = e, ep_i0 = i0, ep_i_end = i_end, ep_j0 = j0, ep_j1 = j1;
-        if (tile_of(n_tile + 1) < total_tiles) {
-            setup_tile(tile_of(n_tile + 1));
+        const int t_next = dyn ? publish(drawn) : tile_of(n_tile + 1);
+        if (t_next < total_tiles) {
+            setup_tile(t_next);
             issue_stage0();
         }
 
@@ -989,6 +1017,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             wait_lgkm0();
             stage_barrier();  // the staging rows are rewritten by the next pass (or the next tile's stage 1)
         }
+        t = t_next;
     }
 }
 
@@ -1024,6 +1053,8 @@ static gg_args gg_make(moe_ctx* ctx, const void* P, const void* Q, const int32_t
     a.dev_err = ctx->dev_err;
     return a;
 }
+
+#define MOE_WS_TILE_COUNTER 48  // byte offset of the wgrad tile counter in the reserved head of the workspace
 
 #define GG_LAUNCH(MODE, EPI, F32, FP8)                                                                          \
     hipLaunchKernelGGL((gg_kernel<MODE, EPI, F32, FP8>), dim3(ctx->num_cu > 0 ? ctx->num_cu : 256), dim3(GG_THREADS), \
@@ -1186,6 +1217,8 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     if (out_dt != MOE_BF16 && out_dt != MOE_F32) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: out_dt must be bf16 or f32");
     gg_args a = gg_make(ctx, dC, A, offsets, E, N, K, Rcap, dB);
     a.accumulate = accumulate ? 1 : 0;
+    a.tile_counter = (int*)((char*)ctx->ws + MOE_WS_TILE_COUNTER);
+    moe_launch_fill_i32(a.tile_counter, 1, 0, (hipStream_t)stream);
     a.p_scale = dc_scale;
     a.q_scale = a_scale;
     if (mx) {
