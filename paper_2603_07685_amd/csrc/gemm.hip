@@ -62,8 +62,6 @@
 #define GG_MAX_E 1024
 #define GG_ROWB 128                     // bytes of a k-major tile row per stage: one cache line
 #define GG_STAGE_BYTES (GG_BM * GG_ROWB)  // one operand tile per stage: 32 KB
-#define GG_CH 4                         // 1 KB DMA chunks per wave per operand per stage
-#define GG_DMA_PER_STAGE (2 * GG_CH)
 // k-major swizzle: two 128-byte rows share a 256-byte bank line; slot ^= bits 1..3 of the row makes
 // 16 consecutive rows hit 16 different (position in line, slot) pairs (SQ_LDS_BANK_CONFLICT = 0)
 #define KM_SWZ(row) (((row) >> 1) & 7)
@@ -201,10 +199,19 @@ struct gg_args {
 // F8: 0 = bf16 operands; 1 = E4M3 codes with fp32 block scales applied in software
 // (blockwise recipe, fwd and dgrad only); 2 = E4M3 codes with one E8M0 scale per 32 contraction elements, applied by the matrix
 // instruction itself (MXFP8, Sec. 5.3.3).
-template <int MODE, int EPI, bool OUT_F32, int F8>
-__global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
+// NW: waves per workgroup.  8 = two groups of four waves (wave tile 128 x 64) that alternate between fragment reads
+// and MFMAs, operands by global -> LDS DMA; 4 = one wave per SIMD with 512 registers (wave tile 128 x 128), operands
+// staged through registers two stages ahead, fragment reads pipelined inside the wave (bf16 only).
+template <int MODE, int EPI, bool OUT_F32, int F8, int NW>
+__global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, NW == 4 ? 1 : 2))) void gg_kernel(const gg_args a) {
     constexpr bool FP8 = F8 != 0;  // one-byte operands
     constexpr bool MX = F8 == 2;   // hardware block scales
+    static_assert(NW == 8 || (NW == 4 && !FP8), "four-wave workgroups are built for bf16 operands only");
+    constexpr int THREADS = NW * 64;
+    constexpr int HW = NW / 2;     // waves per 128-row half of the tile
+    constexpr int NJ = 16 / NW;    // 32-column blocks per wave: NJ / 2 in each 128-column half
+    constexpr int CH = 32 / NW;    // 1 KB chunks per wave per operand per stage
+    constexpr int RPW = 64 / NW;   // staged output rows per wave and epilogue pass
 #ifndef GG_PF
 #define GG_PF 0
 #endif
@@ -244,8 +251,10 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps wave-derived values in SGPRs
-    const int wm = wave >> 2;  // 0..1 : 128-row half of the tile
-    const int wn = wave & 3;   // 0..3 : 32-column strip inside each 128-column half
+    const int wm = wave / HW;  // 0..1 : 128-row half of the tile
+    const int wn = wave % HW;  // strip of 16 NJ columns inside each 128-column half
+    // tile column of the wave's jb-th 32-column block
+    auto blk_col = [&](int jb) { return (jb / (NJ / 2)) * 128 + wn * (16 * NJ) + (jb % (NJ / 2)) * 32; };
     const int E = a.E, N = a.N, K = a.K;
 
     // Output geometry.  J = extent of j (output columns).
@@ -257,14 +266,14 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     const int tiles_i_w = (N + GG_BM - 1) / GG_BM;  // wgrad only
 
     // ---- tile schedule, computed by every workgroup from the device-resident offsets ----
-    for (int e = tid; e <= E; e += GG_THREADS) offs[e] = a.offsets[e];
+    for (int e = tid; e <= E; e += THREADS) offs[e] = a.offsets[e];
     __syncthreads();
     // wgrad: every expert has the same number of output tiles but a tile costs its expert's row count, so the
     // experts are walked in descending order of rows (rank sort, ties by index; tile_start[i] = i-th largest
     // expert) and the tile list is dealt to the XCDs in a snake (see tile_of): equal work per workgroup
     // whatever the load skew.  Only the order of the tiles changes, never what a tile computes.
     if (MODE == GG_WGRAD) {
-        for (int e = tid; e < E; e += GG_THREADS) {
+        for (int e = tid; e < E; e += THREADS) {
             const int re = offs[e + 1] - offs[e];
             int rank = 0;
             for (int o = 0; o < E; ++o) {
@@ -328,26 +337,26 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     const int tr_xor = FP8 ? 2 * (tr_i >> 1) : 4 * (tr_i >> 2);
     const int tr_byte = (tr_i & 1) * 8;
 
-    int p_rd[4], q_rd[2];
+    int p_rd[4], q_rd[NJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if (P_CMAJ) p_rd[i] = tr_rowoff + ((((wm * 128 + i * 32) / EPS) ^ tr_xor) + tr_low) * 16 + tr_byte;
         else p_rd[i] = (wm * 128 + i * 32 + fr_row) * GG_ROWB;
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        if (Q_CMAJ) q_rd[j] = tr_rowoff + ((((j * 128 + wn * 32) / EPS) ^ tr_xor) + tr_low) * 16 + tr_byte;
-        else q_rd[j] = (j * 128 + wn * 32 + fr_row) * GG_ROWB;
+    for (int j = 0; j < NJ; ++j) {
+        if (Q_CMAJ) q_rd[j] = tr_rowoff + (((blk_col(j) / EPS) ^ tr_xor) + tr_low) * 16 + tr_byte;
+        else q_rd[j] = (blk_col(j) + fr_row) * GG_ROWB;
     }
 
     // ---- state of the tile being set up / multiplied (assigned by setup_tile) ----
     int e = 0, i0 = 0, i_end = 0, j0 = 0, j1 = 0;  // expert, output row origin and end, column origins of the two halves
     int c_lo = 0, c_hi = 0, KT = 0;                // contraction range and its stage count
-    // DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus GG_CH 32-bit
+    // DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus CH 32-bit
     // per-lane offsets; offsets stay below 2^32 because they are tile-relative
     const char* p_base = nullptr;
     const char* q_base = nullptr;
-    uint32_t po[GG_CH], qo[GG_CH];
+    uint32_t po[CH], qo[CH];
     int64_t p_step = 0, q_step = 0;  // byte advance per stage
     const float* sc_src = nullptr;   // fp8: this lane's scale for block 0
     int64_t sc_step = 0;             // fp8: element advance per block
@@ -356,7 +365,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     bool pf_on = false, pf_q = false;
     int KT_pf = 0;
     int e_hint = 0;
-    auto setup_tile = [&](int t) {
+    auto setup_tile = [&](int t) __attribute__((always_inline)) {
         // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
         int u;
         if (MODE == GG_WGRAD) {
@@ -392,14 +401,14 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         KT = (c_hi - c_lo + BKE - 1) / BKE;
 
         // ---- DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus
-        //      GG_CH 32-bit per-lane offsets; offsets stay below 2^32 because they are tile-relative ----
+        //      CH 32-bit per-lane offsets; offsets stay below 2^32 because they are tile-relative ----
         if (P_CMAJ) {
             // P = dC [rows, N]: contraction row c, columns i0..i0+255
             p_step = (int64_t)BKE * N * ES;
             p_base = (const char*)a.P + (int64_t)c_lo * N * ES;
 #pragma unroll
-            for (int i = 0; i < GG_CH; ++i) {
-                const int row = (wave * GG_CH + i) * CM_ROWS + cm_row;
+            for (int i = 0; i < CH; ++i) {
+                const int row = (wave * CH + i) * CM_ROWS + cm_row;
                 const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
                 int col = i0 + slot * EPS;
                 col = col <= N - EPS ? col : N - EPS;
@@ -410,8 +419,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             p_step = GG_ROWB;
             p_base = (const char*)a.P + (int64_t)i0 * ldp * ES;
 #pragma unroll
-            for (int i = 0; i < GG_CH; ++i) {
-                const int p = (wave * GG_CH + i) * 8 + km_row;  // tile row 0..255
+            for (int i = 0; i < CH; ++i) {
+                const int p = (wave * CH + i) * 8 + km_row;  // tile row 0..255
                 int64_t r = (int64_t)i0 + p;
                 r = r < a.Rcap ? r : a.Rcap - 1;                // i0 < Rcap, so r - i0 >= 0
                 const int gslot = (lane & 7) ^ KM_SWZ(p);
@@ -423,8 +432,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             q_step = (int64_t)BKE * K * ES;
             q_base = (MODE == GG_DGRAD ? (const char*)a.Q + (int64_t)e * N * K * ES : (const char*)a.Q) + (int64_t)c_lo * K * ES;
 #pragma unroll
-            for (int i = 0; i < GG_CH; ++i) {
-                const int row = (wave * GG_CH + i) * CM_ROWS + cm_row;
+            for (int i = 0; i < CH; ++i) {
+                const int row = (wave * CH + i) * CM_ROWS + cm_row;
                 const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
                 int col = (slot < CM_SLOTS / 2 ? j0 : j1 - 128) + slot * EPS;
                 col = col <= K - EPS ? col : K - EPS;
@@ -434,8 +443,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             q_step = GG_ROWB;
             q_base = (const char*)a.Q + (int64_t)e * N * K * ES;
 #pragma unroll
-            for (int i = 0; i < GG_CH; ++i) {
-                const int p = (wave * GG_CH + i) * 8 + km_row;  // tile row 0..255
+            for (int i = 0; i < CH; ++i) {
+                const int p = (wave * CH + i) * 8 + km_row;  // tile row 0..255
                 int n = (p < 128 ? j0 : j1 - 128) + p;
                 n = n < N ? n : N - 1;
                 const int gslot = (lane & 7) ^ KM_SWZ(p);
@@ -516,14 +525,14 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
         }
     };
 
-        // one of the GG_DMA_PER_STAGE DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
+        // one of the 2 CH DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
         auto issue_one = [&](int kt, char* sp, char* sq, int idx) {
             const int i = idx >> 1;
             const uint32_t off = (idx & 1) ? qo[i] : po[i];
             const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
-            const uint32_t dst_wave = wave * (GG_CH * 1024), dst_const = lds_addr((idx & 1) ? sq : sp) + i * 1024;
+            const uint32_t dst_wave = wave * (CH * 1024), dst_const = lds_addr((idx & 1) ? sq : sp) + i * 1024;
             if (MODE == GG_WGRAD && !MX) {  // contraction tail of the expert: feed zeros
-                const int row = c_lo + kt * BKE + (wave * GG_CH + i) * CM_ROWS + cm_row;
+                const int row = c_lo + kt * BKE + (wave * CH + i) * CM_ROWS + cm_row;
                 uint32_t o = off;
                 asm volatile("" : "+v"(o));  // opaque: keeps base + offset from being hoisted as 64-bit lane pointers
                 dma16(row < c_hi ? base + o : a.zeros, dst_wave, dst_const);
@@ -538,6 +547,43 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 dma4(src, wave * 256, lds_addr(ss));
             }
         };
+
+    // NW == 4: the operands of two stages in flight, in registers (set = stage parity): 2 CH 16-byte loads per lane
+    // and stage, the same chunk -> lane mapping as the DMA.  Plain loads and LDS stores: the compiler counts the
+    // loads in flight itself and waits, before each store, for exactly the load that feeds it.
+    constexpr int NSET = 2;  // register sets = stages of look-ahead
+    u32x4_t R[NSET][NW == 4 ? 2 * CH : 1];
+    // Loads go through buffer descriptors (base = the operand at this stage, wave-uniform; 32-bit lane offset): a
+    // lane whose offset is not below the record count reads zeros, with no branch and no address arithmetic.
+    // Contraction-major operands count the bytes up to the end of the contraction range (the tail rows of an
+    // expert, and whole stages past the end, read zeros); row-major operands (rows clamped, always valid) get
+    // everything or, for a stage past the end, nothing.
+    auto load_one = [&](int kt, int set, int idx) __attribute__((always_inline)) {
+        const int i = idx >> 1;
+        const bool isq = idx & 1;
+        const uint32_t off = isq ? qo[i] : po[i];
+        const char* base = isq ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
+        const bool cmaj = isq ? Q_CMAJ : P_CMAJ;
+        uint32_t records;
+        if (cmaj) {
+            const int ld = (isq || MODE == GG_DGRAD) ? K : N;  // row length of the contraction-major operand
+            const int64_t bytes = (int64_t)max(c_hi - c_lo - kt * BKE, 0) * ld * ES;
+            records = bytes > 0xffffffffLL ? 0xffffffffu : (uint32_t)bytes;
+        } else {
+            records = kt < KT ? 0xffffffffu : 0u;
+        }
+        // (readfirstlane: free for values already in scalar registers, and the promise of uniformity the descriptor needs)
+        const uint64_t b = (uint64_t)base;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+        records = __builtin_amdgcn_readfirstlane(records);
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, (int)records, 0x00020000);
+        R[set][idx] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
+    };
+    auto store_one = [&](char* sp, char* sq, int set, int idx) __attribute__((always_inline)) {
+        asm volatile("" : "+v"(R[set][idx]));  // (held in ordinary vector registers: the accumulation registers are all taken)
+        *(u32x4_t*)(((idx & 1) ? sq : sp) + wave * (CH * 1024) + (idx >> 1) * 1024 + lane * 16) = R[set][idx];
+    };
 
     // PF: L2 warm-up.  With two stage buffers a stage's DMA can be issued only 3/4 of a stage before it is needed,
     // less than the latency of an L2 miss, and about one line in five misses (first touch by the XCD).  The
@@ -561,10 +607,19 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     float* const SS[2] = {(float*)(ldsP0 + GG_STAGE_BYTES), (float*)(ldsP1 + GG_STAGE_BYTES)};
     // stage 0 of a tile: every wave issues its share.  It is issued before the epilogue of the previous tile,
     // so that the first fetch of a tile overlaps the output phase of the one before
-    auto issue_stage0 = [&]() {
+    auto issue_stage0 = [&]() __attribute__((always_inline)) {
+        if (NW == 4) {  // stages 0 and 1 into the two register sets (a stage past the end repeats the last one, unused)
+            if (KT > 0) {
+#pragma unroll
+                for (int x = 0; x < 2 * CH; ++x) load_one(0, 0, x);
+#pragma unroll
+                for (int x = 0; x < 2 * CH; ++x) load_one(1, 1, x);
+            }
+            return;
+        }
         if (KT > 0) {
 #pragma unroll
-            for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(0, SP[0], SQ[0], x);
+            for (int x = 0; x < 2 * CH; ++x) issue_one(0, SP[0], SQ[0], x);
             if (FP8) issue_scales(0, SS[0]);
         }
     };
@@ -609,18 +664,20 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
     for (int n_tile = 0, t = t_first; t < total_tiles; ++n_tile) {
         int drawn = 0;
         if (dyn) drawn = draw();
-        float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[2] = {1.f, 1.f};
-        f32x16_t acc[4][2];
+        float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[NJ];
+        f32x16_t acc[4][NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) qs_cur[j] = 1.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
 
         {
             // operand fragments of one half-stage: bf16 2 x (4 + 2) x 4 VGPRs, fp8 (4 + 2) x 8 VGPRs
-            bf16x8_t pf[2][4], qf[2][2];
+            bf16x8_t pf[2][4], qf[2][NJ];
             i32x8_t pf8[4], qf8[2];
 
             // MFMAs (and the fp8 rescaling multiplies) have no side effects, so nothing else stops the
@@ -663,14 +720,14 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                             else pf[k2][i] = *(const bf16x8_t*)(sp + p_rd[i] + km_slot);
                         }
 #pragma unroll
-                        for (int j = 0; j < 2; ++j) {
+                        for (int j = 0; j < NJ; ++j) {
                             if (Q_CMAJ) qf[k2][j] = lds_read_tr16x8(sq + q_rd[j] + kk * 8192, sq + q_rd[j] + kk * 8192 + 2048);
                             else qf[k2][j] = *(const bf16x8_t*)(sq + q_rd[j] + km_slot);
                         }
                     }
                 }
             };
-            // the MFMAs of one half-stage, with the GG_DMA_PER_STAGE DMA instructions of stage kt_dma slipped in
+            // the MFMAs of one half-stage, with the 2 CH DMA instructions of stage kt_dma slipped in
             int psr[4] = {127, 127, 127, 127}, qsr[2] = {127, 127};  // MX: scale bytes of the current stage
             auto mma = [&](bool do_dma, int kt_dma, char* dp, char* dq, int half) {
                 if (FP8) {
@@ -769,13 +826,107 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 if (FP8 && !MX && half == 0) rescale();  // after the fragment reads in program order: overlaps them
                 wait_lgkm0();
             };
-            if (KT > 0 && wm == 0) {
+            if (NW == 4) {
+                // One wave per SIMD.  Per stage j (buffer s = j % 2) a wave runs four contraction steps of 16 MFMAs; the
+                // fragments of step kk + 1 are read during step kk, stage j + 1 moves from registers to buffer s ^ 1
+                // and the freed registers take stage j + 3.  One barrier per stage, at the end of step 2, when the
+                // reads of step 3 (the last of buffer s) have returned and the stores have landed: behind it stage
+                // j + 1 is readable and buffer s may be overwritten, and the MFMAs of step 3 run while the first
+                // fragments of stage j + 1 arrive.
+                if (KT > 0) {
+                    bf16x8_t pr[2][4], qr[2][NJ];
+                    // one fragment (32 rows x 16 contraction elements) of contraction step kk of buffer s: blocks 0..3 = P, 4.. = Q
+                    auto rd_one = [&](int s, int kk, int fs, int blk) __attribute__((always_inline)) {
+                        const char* sp = SP[s];
+                        const char* sq = SQ[s];
+                        const int km_slot = ((kk * 2 + fr_khalf) ^ fr_swz) * 16;
+                        if (blk < 4) {
+                            if (P_CMAJ) pr[fs][blk] = lds_read_tr16x8(sp + p_rd[blk] + kk * 8192, sp + p_rd[blk] + kk * 8192 + 2048);
+                            else pr[fs][blk] = *(const bf16x8_t*)(sp + p_rd[blk] + km_slot);
+                        } else {
+                            const int jb = blk - 4;
+                            if (Q_CMAJ) qr[fs][jb] = lds_read_tr16x8(sq + q_rd[jb] + kk * 8192, sq + q_rd[jb] + kk * 8192 + 2048);
+                            else qr[fs][jb] = *(const bf16x8_t*)(sq + q_rd[jb] + km_slot);
+                        }
+                    };
+                    // A stage is 64 MFMAs per wave and as many other instructions: 32 fragment reads, 16 LDS stores and 16
+                    // global loads.  A wave alone on its SIMD issues in order, so they are written one per MFMA: each
+                    // issues in the shadow of the MFMA before it, and the matrix pipe never waits for the instruction
+                    // stream.  Even gaps read the fragments of the next step in the order the MFMAs will want them;
+                    // odd gaps alternate store / load, so the LDS and the address unit of the memory pipe see one
+                    // request per wave every 128 cycles instead of bursts that fill their queues and stall the wave.
+                    // The store window of a stage's buffer runs from the barrier that frees it to the barrier that
+                    // publishes it: chunks 0..3 of stage j + 2 go out in step 3 of stage j, chunks 4..15 of stage
+                    // j + 1 in steps 0..2.  Each freed register takes the same chunk NSET stages further on.
+                    auto stage4 = [&](int j, int s) __attribute__((always_inline)) {
+                        // (nothing here is conditional: behind the last stage the moves and reads go on, unused)
+                        constexpr int NM = 4 * NJ, NF = 4 + NJ, MV = 2 * CH;
+                        static_assert(NW != 4 || (NM == 2 * NF && MV == 16), "the gap assignment below is for 16 MFMAs per step");
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) {
+                            const int fs = kk & 1;
+#pragma unroll
+                            for (int m = 0; m < NM; ++m) {
+                                const int i = m / NJ, jb = m % NJ;
+                                acc[i][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[fs][jb], pr[fs][i], acc[i][jb], 0, 0, 0);
+                                __builtin_amdgcn_sched_barrier(0);
+                                if ((m & 1) == 0) {
+                                    const int r = m >> 1;  // P0, Q0 .. Q3, P1 .. P3
+                                    const int blk = r == 0 ? 0 : r <= NJ ? 3 + r : r - NJ;
+                                    if (kk < 3) rd_one(s, kk + 1, fs ^ 1, blk);
+                                    else rd_one(s ^ 1, 0, fs ^ 1, blk);
+                                } else {
+                                    const int o = m >> 1;
+                                    const bool nxt = kk == 3;                          // behind the barrier: stage j + 2
+                                    const int x = nxt ? o >> 1 : 4 + ((kk * 8 + o) >> 1);
+                                    const int tgt = nxt ? j + 2 : j + 1;               // the stage stored
+                                    const int bs = nxt ? s : s ^ 1;                    // its buffer
+                                    const int rs = bs;                                 // and register set (= stage parity)
+                                    if ((o & 1) == 0) store_one(SP[bs], SQ[bs], rs, x);
+                                    else load_one(tgt + NSET, rs, x);
+                                }
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            // (the compiler waits for each fragment before its first use; the last reads of this
+                            // buffer must have returned, and the stores landed, only at the barrier)
+                            if (kk == 2) {
+                                wait_lgkm0();
+                                stage_barrier();
+                            }
+                        }
+                    };
+                    // stage 0 from the registers to buffer 0 (both register sets were requested before the previous
+                    // tile's epilogue), stage NSET into the freed set, the first fragments
+#pragma unroll
+                    for (int x = 0; x < 2 * CH; ++x) store_one(SP[0], SQ[0], 0, x);
+#pragma unroll
+                    for (int x = 0; x < 2 * CH; ++x) load_one(NSET, 0, x);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {  // (the part of stage 1 that step 3 of the stage before would have moved)
+                        store_one(SP[1], SQ[1], 1, x);
+                        load_one(1 + NSET, 1, x);
+                    }
+                    wait_lgkm0();
+                    stage_barrier();
+#pragma unroll
+                    for (int b = 0; b < 4 + NJ; ++b) rd_one(0, 0, 0, b);
+                    // (always pairs of stages, an odd count padded with a stage of zeros: with an exit between the two
+                    // halves, or an odd stage behind the loop, the register allocator no longer keeps the 256
+                    // accumulation registers in place and spills hundreds of them)
+                    for (int j = 0; j < KT; j += 2) {
+                        stage4(j, 0);
+                        stage4(j + 1, 1);
+                    }
+                    wait_lgkm0();     // (the unused stores of the last step: landed before buffer 1 becomes the staging area)
+                    stage_barrier();  // every wave is past its last fragment read
+                }
+            } else if (KT > 0 && wm == 0) {
                 wait_vm0();  // stage 0, issued before the previous tile's epilogue
                 stage_barrier();
                 auto stage0 = [&](int j, int s) {
                     if (j + 1 < KT) {
 #pragma unroll
-                        for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(j + 1, SP[s ^ 1], SQ[s ^ 1], x);
+                        for (int x = 0; x < 2 * CH; ++x) issue_one(j + 1, SP[s ^ 1], SQ[s ^ 1], x);
                         if (FP8) issue_scales(j + 1, SS[s ^ 1]);
                     }
                     const bool pf = PF && j + 2 < KT_pf;
@@ -804,7 +955,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
                 stage_barrier();
                 if (KT > 1) {  // slot 1: group 0 reads stage 0, both groups issue their share of stage 1
 #pragma unroll
-                    for (int x = 0; x < GG_DMA_PER_STAGE; ++x) issue_one(1, SP[1], SQ[1], x);
+                    for (int x = 0; x < 2 * CH; ++x) issue_one(1, SP[1], SQ[1], x);
                     if (FP8) issue_scales(1, SS[1]);
                 }
                 if (PF && 2 < KT_pf) prefetch(2);
@@ -857,12 +1008,12 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             // SwiGLU backward: the saved pre-activations of the 8 rows this wave writes in this pass are requested
             // before the accumulators go to LDS, so their latency overlaps the staging and its barrier
             // (bf16 only: the one-byte variants have no registers to spare for it)
-            constexpr bool Z_EARLY = EPI == GG_EPI_SWIGLU_BWD && !FP8;
-            u32x2_t zg[8], zu[8];
+            constexpr bool Z_EARLY = EPI == GG_EPI_SWIGLU_BWD && !FP8 && NW == 8;
+            u32x2_t zg[RPW], zu[RPW];
             if (Z_EARLY) {
 #pragma unroll
-                for (int x8 = 0; x8 < 8; ++x8) {
-                    const int rr = wave * 8 + x8;
+                for (int x8 = 0; x8 < RPW; ++x8) {
+                    const int rr = wave * RPW + x8;
                     const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
                     if (r < ep_i_end && c < K) {
                         const int64_t zr = (int64_t)r * 2 * K;
@@ -874,19 +1025,19 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) {
+                for (int h2 = 0; h2 < NJ; ++h2) {
                     f32x4_t v;
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
                         v[x] = acc[i][h2][4 * g + x];
                         if (FP8 && !MX) v[x] *= ps_cur[i] * qs_cur[h2];
                     }
-                    *(f32x4_t*)(stg + (wm * 32 + fr_row) * STG_PITCH + h2 * 128 + wn * 32 + 8 * g + 4 * fr_khalf) = v;
+                    *(f32x4_t*)(stg + (wm * 32 + fr_row) * STG_PITCH + blk_col(h2) + 8 * g + 4 * fr_khalf) = v;
                 }
             wait_lgkm0();
             stage_barrier();
             auto out_row = [&](int x8) {
-                const int rr = wave * 8 + x8;                             // staged row 0..63
+                const int rr = wave * RPW + x8;                           // staged row 0..63
                 const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
                 if (r >= ep_i_end) return;                                // wave-uniform
                 const f32x4_t v = *(const f32x4_t*)(stg + rr * STG_PITCH + cl);
@@ -976,20 +1127,20 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gg_kernel(const gg_args a) {
             // that above a size limit, so the row loops stay rolled where nothing is indexed by them)
             if (Z_EARLY) {
 #pragma unroll
-                for (int x8 = 0; x8 < 8; ++x8) out_row(x8);
+                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8);
             } else if (FP8) {
 #pragma unroll 1
-                for (int x8 = 0; x8 < 8; ++x8) out_row(x8);
-            } else {
-#pragma unroll
-                for (int x8 = 0; x8 < 8; ++x8) out_row(x8);
+                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8);
+            } else {  // (four waves, SwiGLU backward: 16 rows at once is past the size at which the pass loop still unrolls)
+#pragma unroll(NW == 4 && EPI == GG_EPI_SWIGLU_BWD ? 4 : RPW)
+                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8);
             }
             if (EPI == GG_EPI_SWIGLU) {
                 // activation: a lane pairs gate and up of 4 features; two tile rows per instruction
                 const int fl = (lane & 31) * 4;
 #pragma unroll(FP8 ? 1 : 4)
-                for (int x4 = 0; x4 < 4; ++x4) {
-                    const int rr = wave * 8 + 2 * x4 + (lane >> 5);
+                for (int x4 = 0; x4 < RPW / 2; ++x4) {
+                    const int rr = wave * RPW + 2 * x4 + (lane >> 5);
                     const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
                     if (r < ep_i_end && ep_j0 + fl < half_cols) {  // uniform over a half-wave when N % 256 == 0 (fp8)
                         const f32x4_t gt = *(const f32x4_t*)(stg + rr * STG_PITCH + fl);
@@ -1056,8 +1207,16 @@ static gg_args gg_make(moe_ctx* ctx, const void* P, const void* Q, const int32_t
 
 #define MOE_WS_TILE_COUNTER 48  // byte offset of the wgrad tile counter in the reserved head of the workspace
 
+#ifndef GG_BF16_NW
+#define GG_BF16_NW 4  // waves per workgroup of the bf16 variants (see the kernel)
+#endif
+#ifndef GG_BF16_WGRAD_NW
+#define GG_BF16_WGRAD_NW GG_BF16_NW
+#endif
+#define GG_NW_OF(MODE, FP8) ((FP8) ? 8 : (MODE) == GG_WGRAD ? GG_BF16_WGRAD_NW : GG_BF16_NW)
 #define GG_LAUNCH(MODE, EPI, F32, FP8)                                                                          \
-    hipLaunchKernelGGL((gg_kernel<MODE, EPI, F32, FP8>), dim3(ctx->num_cu > 0 ? ctx->num_cu : 256), dim3(GG_THREADS), \
+    hipLaunchKernelGGL((gg_kernel<MODE, EPI, F32, FP8, GG_NW_OF(MODE, FP8)>),                                   \
+                       dim3(ctx->num_cu > 0 ? ctx->num_cu : 256), dim3(GG_NW_OF(MODE, FP8) * 64),               \
                        0, (hipStream_t)stream, a)
 
 extern "C" moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const void* A, const void* B,
