@@ -346,19 +346,23 @@ def main():
         gms = g0.elapsed_time(g1) / args.steps
         assert st.ctx.poll_error() == 0
         out["graph"] = {"ms_per_step": round(gms, 4), "tflops": round(flops / gms / 1e9, 2)}
-    # context only: the vendor dense bf16 GEMM through torch on this very box (boxes differ by +-20 %)
-    a_ref = torch.randn((16384, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
+    # context only: the vendor dense bf16 GEMM through torch on this very box, at the size of one fc1 call of this
+    # workload (rows = routed tokens, capped), same operand distribution, output preallocated
+    m_ref = min(cfg.T * cfg.k, 131072)
+    a_ref = torch.randn((m_ref, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
     b_ref = torch.randn((4096, cfg.h), dtype=torch.bfloat16, device="cuda") * 0.02
+    o_ref = torch.empty((m_ref, 4096), dtype=torch.bfloat16, device="cuda")
     for _ in range(3):
-        a_ref @ b_ref.T
+        torch.matmul(a_ref, b_ref.T, out=o_ref)
     r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     r0.record()
     for _ in range(10):
-        a_ref @ b_ref.T
+        torch.matmul(a_ref, b_ref.T, out=o_ref)
     r1.record()
     torch.cuda.synchronize()
-    out["box_reference"] = {"what": f"torch.matmul bf16 16384x4096x{cfg.h} (dense, hipBLASLt) on this box",
-                            "tflops": round(2.0 * 16384 * 4096 * cfg.h * 10 / r0.elapsed_time(r1) / 1e9, 1)}
+    out["box_reference"] = {"what": f"torch.matmul bf16 {m_ref}x4096x{cfg.h} (dense, hipBLASLt) on this box",
+                            "tflops": round(2.0 * m_ref * 4096 * cfg.h * 10 / r0.elapsed_time(r1) / 1e9, 1)}
+    del o_ref
     del a_ref, b_ref
     if not args.no_cpu_baseline:
         v, cores, desc = cpu_baseline(st, torch)

@@ -1005,14 +1005,16 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         const int c = cl < 128 ? ep_j0 + cl : ep_j1 + cl - 128;           // output column of this lane
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            // SwiGLU backward: the saved pre-activations of the 8 rows this wave writes in this pass are requested
+            // SwiGLU backward: the saved pre-activations of the first 8 rows this wave writes in this pass are requested
             // before the accumulators go to LDS, so their latency overlaps the staging and its barrier
-            // (bf16 only: the one-byte variants have no registers to spare for it)
-            constexpr bool Z_EARLY = EPI == GG_EPI_SWIGLU_BWD && !FP8 && NW == 8;
-            u32x2_t zg[RPW], zu[RPW];
+            // (bf16 only: the one-byte variants have no registers to spare for it; with four waves a wave writes
+            // 16 rows per pass and has registers for half of them)
+            constexpr bool Z_EARLY = EPI == GG_EPI_SWIGLU_BWD && !FP8;
+            constexpr int ZE = 8;
+            u32x2_t zg[ZE], zu[ZE];
             if (Z_EARLY) {
 #pragma unroll
-                for (int x8 = 0; x8 < RPW; ++x8) {
+                for (int x8 = 0; x8 < ZE; ++x8) {
                     const int rr = wave * RPW + x8;
                     const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
                     if (r < ep_i_end && c < K) {
@@ -1036,7 +1038,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 }
             wait_lgkm0();
             stage_barrier();
-            auto out_row = [&](int x8) {
+            auto out_row = [&](int x8, bool early) {
                 const int rr = wave * RPW + x8;                           // staged row 0..63
                 const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
                 if (r >= ep_i_end) return;                                // wave-uniform
@@ -1054,9 +1056,9 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                         bf16_t* dZ = (bf16_t*)a.out;
                         const int64_t zr = (int64_t)r * 2 * K;
                         u32x2_t zgv, zuv;  // (not through the arrays when the row loop is rolled: no runtime index)
-                        if (Z_EARLY) {
-                            zgv = zg[x8];
-                            zuv = zu[x8];
+                        if (Z_EARLY && early) {
+                            zgv = zg[x8 < ZE ? x8 : 0];
+                            zuv = zu[x8 < ZE ? x8 : 0];
                         } else {
                             zgv = *(const u32x2_t*)(a.Zsaved + zr + c);
                             zuv = *(const u32x2_t*)(a.Zsaved + zr + K + c);
@@ -1127,13 +1129,15 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             // that above a size limit, so the row loops stay rolled where nothing is indexed by them)
             if (Z_EARLY) {
 #pragma unroll
-                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8);
+                for (int x8 = 0; x8 < ZE; ++x8) out_row(x8, true);
+#pragma unroll 4
+                for (int x8 = ZE; x8 < RPW; ++x8) out_row(x8, false);
             } else if (FP8) {
 #pragma unroll 1
-                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8);
-            } else {  // (four waves, SwiGLU backward: 16 rows at once is past the size at which the pass loop still unrolls)
-#pragma unroll(NW == 4 && EPI == GG_EPI_SWIGLU_BWD ? 4 : RPW)
-                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8);
+                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8, false);
+            } else {
+#pragma unroll
+                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8, false);
             }
             if (EPI == GG_EPI_SWIGLU) {
                 // activation: a lane pairs gate and up of 4 features; two tile rows per instruction
