@@ -200,8 +200,9 @@ struct gg_args {
 // (blockwise recipe, fwd and dgrad only); 2 = E4M3 codes with one E8M0 scale per 32 contraction elements, applied by the matrix
 // instruction itself (MXFP8, Sec. 5.3.3).
 // NW: waves per workgroup.  8 = two groups of four waves (wave tile 128 x 64) that alternate between fragment reads
-// and MFMAs, operands by global -> LDS DMA; 4 = one wave per SIMD with 512 registers (wave tile 128 x 128), operands
-// staged through registers two stages ahead, fragment reads pipelined inside the wave (bf16 only).
+// and MFMAs, operands by global -> LDS DMA; 4 = one wave per SIMD with 512 registers (wave tile 128 x 128 as 8 x 8
+// blocks of the 16x16x32 MFMA), operands staged through registers one stage ahead, fragment reads pipelined inside
+// the wave (bf16 only).
 template <int MODE, int EPI, bool OUT_F32, int F8, int NW>
 __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, NW == 4 ? 1 : 2))) void gg_kernel(const gg_args a) {
     constexpr bool FP8 = F8 != 0;  // one-byte operands
@@ -337,6 +338,23 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     const int tr_xor = FP8 ? 2 * (tr_i >> 1) : 4 * (tr_i >> 2);
     const int tr_byte = (tr_i & 1) * 8;
 
+    // four waves: 16 x 16 blocks.  Row-major: lane -> (row l % 16, 16-byte slot l / 16 of the step's 64 bytes), one
+    // slot offset per step (the swizzle depends on l % 16 only).  Contraction-major: lane group l / 16 covers the
+    // contraction rows 8 (l / 16) .. + 7 of a step in two transposing reads of 4 rows.
+    int p4[8], q4[8], km4[2];
+    if (NW == 4) {
+        const int l16 = lane & 15, kq = lane >> 4;
+        km4[0] = ((kq) ^ KM_SWZ(l16)) * 16;
+        km4[1] = ((4 + kq) ^ KM_SWZ(l16)) * 16;
+        const int cm_off = (8 * kq + (l16 >> 2)) * 512 + (l16 & 1) * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int prow = wm * 128 + 16 * i;                             // tile row of P block i
+            const int qrow = (i / 4) * 128 + wn * 64 + (i % 4) * 16;        // tile column of Q block i
+            p4[i] = P_CMAJ ? cm_off + (((prow / 8) ^ tr_xor) + ((l16 & 3) >> 1)) * 16 : (prow + l16) * GG_ROWB;
+            q4[i] = Q_CMAJ ? cm_off + (((qrow / 8) ^ tr_xor) + ((l16 & 3) >> 1)) * 16 : (qrow + l16) * GG_ROWB;
+        }
+    }
     int p_rd[4], q_rd[NJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -357,6 +375,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     const char* p_base = nullptr;
     const char* q_base = nullptr;
     uint32_t po[CH], qo[CH];
+    // four waves: chunk i of a wave sits (i / 2) x a fixed stride behind chunk i % 2 (the swizzle alternates with the
+    // parity of the chunk), so two lane offsets and a wave-uniform stride per operand replace 2 x 8 registers; rows are
+    // not clamped here, the record count of the buffer descriptor covers the end of the tensor
+    uint32_t po2[2] = {0, 0}, qo2[2] = {0, 0};
+    uint32_t p_cstride = 0, q_cstride = 0;
     int64_t p_step = 0, q_step = 0;  // byte advance per stage
     const float* sc_src = nullptr;   // fp8: this lane's scale for block 0
     int64_t sc_step = 0;             // fp8: element advance per block
@@ -406,49 +429,57 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             // P = dC [rows, N]: contraction row c, columns i0..i0+255
             p_step = (int64_t)BKE * N * ES;
             p_base = (const char*)a.P + (int64_t)c_lo * N * ES;
+            p_cstride = (uint32_t)(2 * CM_ROWS * N * ES);
 #pragma unroll
-            for (int i = 0; i < CH; ++i) {
+            for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
                 const int row = (wave * CH + i) * CM_ROWS + cm_row;
                 const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
                 int col = i0 + slot * EPS;
                 col = col <= N - EPS ? col : N - EPS;
-                po[i] = (uint32_t)((row * N + col) * ES);
+                if (NW == 4) po2[i] = (uint32_t)((row * N + col) * ES);
+                else po[i] = (uint32_t)((row * N + col) * ES);
             }
         } else {
             const int ldp = (MODE == GG_FWD) ? K : N;
             p_step = GG_ROWB;
             p_base = (const char*)a.P + (int64_t)i0 * ldp * ES;
+            p_cstride = (uint32_t)(16 * ldp * ES);
 #pragma unroll
-            for (int i = 0; i < CH; ++i) {
+            for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
                 const int p = (wave * CH + i) * 8 + km_row;  // tile row 0..255
                 int64_t r = (int64_t)i0 + p;
-                r = r < a.Rcap ? r : a.Rcap - 1;                // i0 < Rcap, so r - i0 >= 0
+                if (NW != 4) r = r < a.Rcap ? r : a.Rcap - 1;   // i0 < Rcap, so r - i0 >= 0
                 const int gslot = (lane & 7) ^ KM_SWZ(p);
-                po[i] = (uint32_t)((r - i0) * ldp * ES + gslot * 16);
+                if (NW == 4) po2[i] = (uint32_t)((r - i0) * ldp * ES + gslot * 16);
+                else po[i] = (uint32_t)((r - i0) * ldp * ES + gslot * 16);
             }
         }
         if (Q_CMAJ) {
             // dgrad: Q = W_e [N,K]: contraction row n, columns (k) j0.. ; wgrad: Q = A [rows,K]
             q_step = (int64_t)BKE * K * ES;
             q_base = (MODE == GG_DGRAD ? (const char*)a.Q + (int64_t)e * N * K * ES : (const char*)a.Q) + (int64_t)c_lo * K * ES;
+            q_cstride = (uint32_t)(2 * CM_ROWS * K * ES);
 #pragma unroll
-            for (int i = 0; i < CH; ++i) {
+            for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
                 const int row = (wave * CH + i) * CM_ROWS + cm_row;
                 const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
                 int col = (slot < CM_SLOTS / 2 ? j0 : j1 - 128) + slot * EPS;
                 col = col <= K - EPS ? col : K - EPS;
-                qo[i] = (uint32_t)((row * K + col) * ES);
+                if (NW == 4) qo2[i] = (uint32_t)((row * K + col) * ES);
+                else qo[i] = (uint32_t)((row * K + col) * ES);
             }
         } else {
             q_step = GG_ROWB;
             q_base = (const char*)a.Q + (int64_t)e * N * K * ES;
+            q_cstride = (uint32_t)(16 * K * ES);
 #pragma unroll
-            for (int i = 0; i < CH; ++i) {
+            for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
                 const int p = (wave * CH + i) * 8 + km_row;  // tile row 0..255
                 int n = (p < 128 ? j0 : j1 - 128) + p;
-                n = n < N ? n : N - 1;
+                if (NW != 4) n = n < N ? n : N - 1;
                 const int gslot = (lane & 7) ^ KM_SWZ(p);
-                qo[i] = (uint32_t)(((int64_t)n * K) * ES + gslot * 16);
+                if (NW == 4) qo2[i] = (uint32_t)(((int64_t)n * K) * ES + gslot * 16);
+                else qo[i] = (uint32_t)(((int64_t)n * K) * ES + gslot * 16);
             }
         }
 
@@ -548,41 +579,46 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             }
         };
 
-    // NW == 4: the operands of two stages in flight, in registers (set = stage parity): 2 CH 16-byte loads per lane
-    // and stage, the same chunk -> lane mapping as the DMA.  Plain loads and LDS stores: the compiler counts the
-    // loads in flight itself and waits, before each store, for exactly the load that feeds it.
-    constexpr int NSET = 2;  // register sets = stages of look-ahead
-    u32x4_t R[NSET][NW == 4 ? 2 * CH : 1];
+    // NW == 4: the operands of one stage in flight, in registers: 2 CH 16-byte loads per lane and stage, the same
+    // chunk -> lane mapping as the DMA.  Plain loads and LDS stores: the compiler counts the loads in flight itself
+    // and waits, before each store, for exactly the load that feeds it.  A register is stored (stage j + 1) and at
+    // once reloaded (stage j + 2), so every load has a full stage to arrive.  (A second register set, two stages
+    // ahead, measured 1-3 % slower: it leaves the register allocator no slack.)
+    u32x4_t R[NW == 4 ? 2 * CH : 1];
     // Loads go through buffer descriptors (base = the operand at this stage, wave-uniform; 32-bit lane offset): a
     // lane whose offset is not below the record count reads zeros, with no branch and no address arithmetic.
     // Contraction-major operands count the bytes up to the end of the contraction range (the tail rows of an
     // expert, and whole stages past the end, read zeros); row-major operands (rows clamped, always valid) get
     // everything or, for a stage past the end, nothing.
-    auto load_one = [&](int kt, int set, int idx) __attribute__((always_inline)) {
+    auto load_one = [&](int kt, int idx) __attribute__((always_inline)) {
         const int i = idx >> 1;
         const bool isq = idx & 1;
-        const uint32_t off = isq ? qo[i] : po[i];
+        const uint32_t off = (isq ? qo2[i & 1] : po2[i & 1]) + (uint32_t)(i >> 1) * (isq ? q_cstride : p_cstride);
         const char* base = isq ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
         const bool cmaj = isq ? Q_CMAJ : P_CMAJ;
-        uint32_t records;
+        int64_t bytes;  // from the base to the end of what may be read
         if (cmaj) {
             const int ld = (isq || MODE == GG_DGRAD) ? K : N;  // row length of the contraction-major operand
-            const int64_t bytes = (int64_t)max(c_hi - c_lo - kt * BKE, 0) * ld * ES;
-            records = bytes > 0xffffffffLL ? 0xffffffffu : (uint32_t)bytes;
-        } else {
-            records = kt < KT ? 0xffffffffu : 0u;
+            bytes = (int64_t)max(c_hi - c_lo - kt * BKE, 0) * ld * ES;
+        } else if (kt >= KT) {
+            bytes = 0;
+        } else if (isq) {  // weights of this expert: rows (output columns) up to N
+            bytes = (int64_t)N * K * ES - kt * GG_ROWB;
+        } else {           // rows of the activation tensor up to its capacity
+            bytes = (a.Rcap - i0) * (int64_t)((MODE == GG_FWD) ? K : N) * ES - kt * GG_ROWB;
         }
+        uint32_t records = bytes > 0xffffffffLL ? 0xffffffffu : (uint32_t)bytes;
         // (readfirstlane: free for values already in scalar registers, and the promise of uniformity the descriptor needs)
         const uint64_t b = (uint64_t)base;
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
         records = __builtin_amdgcn_readfirstlane(records);
         const __amdgpu_buffer_rsrc_t rsrc =
             __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, (int)records, 0x00020000);
-        R[set][idx] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
+        R[idx] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
     };
-    auto store_one = [&](char* sp, char* sq, int set, int idx) __attribute__((always_inline)) {
-        asm volatile("" : "+v"(R[set][idx]));  // (held in ordinary vector registers: the accumulation registers are all taken)
-        *(u32x4_t*)(((idx & 1) ? sq : sp) + wave * (CH * 1024) + (idx >> 1) * 1024 + lane * 16) = R[set][idx];
+    auto store_one = [&](char* sp, char* sq, int idx) __attribute__((always_inline)) {
+        asm volatile("" : "+v"(R[idx]));  // (held in ordinary vector registers: the accumulation registers are all taken)
+        *(u32x4_t*)(((idx & 1) ? sq : sp) + wave * (CH * 1024) + (idx >> 1) * 1024 + lane * 16) = R[idx];
     };
 
     // PF: L2 warm-up.  With two stage buffers a stage's DMA can be issued only 3/4 of a stage before it is needed,
@@ -608,12 +644,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // stage 0 of a tile: every wave issues its share.  It is issued before the epilogue of the previous tile,
     // so that the first fetch of a tile overlaps the output phase of the one before
     auto issue_stage0 = [&]() __attribute__((always_inline)) {
-        if (NW == 4) {  // stages 0 and 1 into the two register sets (a stage past the end repeats the last one, unused)
+        if (NW == 4) {  // into the registers
             if (KT > 0) {
 #pragma unroll
-                for (int x = 0; x < 2 * CH; ++x) load_one(0, 0, x);
-#pragma unroll
-                for (int x = 0; x < 2 * CH; ++x) load_one(1, 1, x);
+                for (int x = 0; x < 2 * CH; ++x) load_one(0, x);
             }
             return;
         }
@@ -665,7 +699,16 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         int drawn = 0;
         if (dyn) drawn = draw();
         float ps_cur[4] = {1.f, 1.f, 1.f, 1.f}, qs_cur[NJ];
-        f32x16_t acc[4][NJ];
+        f32x16_t acc[4][NJ];  // eight waves: 32 x 32 blocks
+        f32x4_t acc4[8][8];   // four waves: 16 x 16 blocks (P block i, Q block j)
+        if (NW == 4) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) acc4[i][j][x] = 0.f;
+        }
 #pragma unroll
         for (int j = 0; j < NJ; ++j) qs_cur[j] = 1.f;
 #pragma unroll
@@ -827,89 +870,93 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 wait_lgkm0();
             };
             if (NW == 4) {
-                // One wave per SIMD.  Per stage j (buffer s = j % 2) a wave runs four contraction steps of 16 MFMAs; the
-                // fragments of step kk + 1 are read during step kk, stage j + 1 moves from registers to buffer s ^ 1
-                // and the freed registers take stage j + 3.  One barrier per stage, at the end of step 2, when the
-                // reads of step 3 (the last of buffer s) have returned and the stores have landed: behind it stage
-                // j + 1 is readable and buffer s may be overwritten, and the MFMAs of step 3 run while the first
-                // fragments of stage j + 1 arrive.
+                // One wave per SIMD and 16x16x32 MFMAs (at equal peak rate they draw less power than the 32x32x16
+                // shape, and power sets the sustained clock): the wave tile is 8 x 8 blocks of 16 x 16.  A stage
+                // (buffer s = j % 2) is two contraction steps of 32; a step runs the P blocks i = 0..7 in turn against
+                // the 8 Q fragments of the step, 64 MFMAs of 16 cycles.  Q fragments are double-buffered by step, P
+                // fragments go round a ring of four (P block i + 2 is read while block i runs).
+                // A wave alone on its SIMD issues in order, so every other instruction is written into the gap behind
+                // one MFMA and issues in its shadow; the 64 of a stage (32 fragment reads, 16 LDS stores of stage
+                // j + 1, 16 global loads of stage j + 2 into the registers those stores free) are spread over the
+                // 128 gaps, so that the LDS and the address unit of the memory pipe see a steady trickle instead of
+                // bursts that fill their queues and stall the wave.
+                // One barrier per stage, 12 MFMAs before its end: by then the last fragments of buffer s have
+                // arrived and stage j + 1 is complete in buffer s ^ 1; behind it the first fragments of stage j + 1
+                // are read while the last MFMAs of stage j run.
                 if (KT > 0) {
-                    bf16x8_t pr[2][4], qr[2][NJ];
-                    // one fragment (32 rows x 16 contraction elements) of contraction step kk of buffer s: blocks 0..3 = P, 4.. = Q
-                    auto rd_one = [&](int s, int kk, int fs, int blk) __attribute__((always_inline)) {
-                        const char* sp = SP[s];
-                        const char* sq = SQ[s];
-                        const int km_slot = ((kk * 2 + fr_khalf) ^ fr_swz) * 16;
-                        if (blk < 4) {
-                            if (P_CMAJ) pr[fs][blk] = lds_read_tr16x8(sp + p_rd[blk] + kk * 8192, sp + p_rd[blk] + kk * 8192 + 2048);
-                            else pr[fs][blk] = *(const bf16x8_t*)(sp + p_rd[blk] + km_slot);
-                        } else {
-                            const int jb = blk - 4;
-                            if (Q_CMAJ) qr[fs][jb] = lds_read_tr16x8(sq + q_rd[jb] + kk * 8192, sq + q_rd[jb] + kk * 8192 + 2048);
-                            else qr[fs][jb] = *(const bf16x8_t*)(sq + q_rd[jb] + km_slot);
+                    bf16x8_t qr[2][8], pr[4];
+                    // row-major operands: one LDS address per buffer and step (lane row and swizzled slot folded in), the
+                    // block as an immediate offset
+                    typedef __attribute__((address_space(3))) bf16x8_t lds_bf16x8_t;
+                    uint32_t vbp[2][2], vbq[2][2];
+#pragma unroll
+                    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) {
+                            vbp[sb][ks] = lds_addr(SP[sb]) + (wm * 128 + (lane & 15)) * GG_ROWB + km4[ks];
+                            vbq[sb][ks] = lds_addr(SQ[sb]) + (wn * 64 + (lane & 15)) * GG_ROWB + km4[ks];
+                            asm volatile("" : "+v"(vbp[sb][ks]), "+v"(vbq[sb][ks]));
                         }
+                    auto rdP = [&](int sb, int ks, int i, int slot) __attribute__((always_inline)) {
+                        const char* sp = SP[sb] + p4[i];
+                        if (P_CMAJ) pr[slot] = lds_read_tr16x8(sp + ks * 16384, sp + ks * 16384 + 2048);
+                        else pr[slot] = *(const lds_bf16x8_t*)(uintptr_t)(vbp[sb][ks] + i * 16 * GG_ROWB);
                     };
-                    // A stage is 64 MFMAs per wave and as many other instructions: 32 fragment reads, 16 LDS stores and 16
-                    // global loads.  A wave alone on its SIMD issues in order, so they are written one per MFMA: each
-                    // issues in the shadow of the MFMA before it, and the matrix pipe never waits for the instruction
-                    // stream.  Even gaps read the fragments of the next step in the order the MFMAs will want them;
-                    // odd gaps alternate store / load, so the LDS and the address unit of the memory pipe see one
-                    // request per wave every 128 cycles instead of bursts that fill their queues and stall the wave.
-                    // The store window of a stage's buffer runs from the barrier that frees it to the barrier that
-                    // publishes it: chunks 0..3 of stage j + 2 go out in step 3 of stage j, chunks 4..15 of stage
-                    // j + 1 in steps 0..2.  Each freed register takes the same chunk NSET stages further on.
+                    auto rdQ = [&](int sb, int ks, int jq, int set) __attribute__((always_inline)) {
+                        const char* sq = SQ[sb] + q4[jq];
+                        if (Q_CMAJ) qr[set][jq] = lds_read_tr16x8(sq + ks * 16384, sq + ks * 16384 + 2048);
+                        else qr[set][jq] = *(const lds_bf16x8_t*)(uintptr_t)(vbq[sb][ks] + ((jq / 4) * 128 + (jq % 4) * 16) * GG_ROWB);
+                    };
                     auto stage4 = [&](int j, int s) __attribute__((always_inline)) {
                         // (nothing here is conditional: behind the last stage the moves and reads go on, unused)
-                        constexpr int NM = 4 * NJ, NF = 4 + NJ, MV = 2 * CH;
-                        static_assert(NW != 4 || (NM == 2 * NF && MV == 16), "the gap assignment below is for 16 MFMAs per step");
+                        static_assert(NW != 4 || CH == 8, "the gap assignment below is for 16 chunks per stage");
 #pragma unroll
-                        for (int kk = 0; kk < 4; ++kk) {
-                            const int fs = kk & 1;
+                        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                            for (int m = 0; m < NM; ++m) {
-                                const int i = m / NJ, jb = m % NJ;
-                                acc[i][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[fs][jb], pr[fs][i], acc[i][jb], 0, 0, 0);
-                                __builtin_amdgcn_sched_barrier(0);
-                                if ((m & 1) == 0) {
-                                    const int r = m >> 1;  // P0, Q0 .. Q3, P1 .. P3
-                                    const int blk = r == 0 ? 0 : r <= NJ ? 3 + r : r - NJ;
-                                    if (kk < 3) rd_one(s, kk + 1, fs ^ 1, blk);
-                                    else rd_one(s ^ 1, 0, fs ^ 1, blk);
-                                } else {
-                                    const int o = m >> 1;
-                                    const bool nxt = kk == 3;                          // behind the barrier: stage j + 2
-                                    const int x = nxt ? o >> 1 : 4 + ((kk * 8 + o) >> 1);
-                                    const int tgt = nxt ? j + 2 : j + 1;               // the stage stored
-                                    const int bs = nxt ? s : s ^ 1;                    // its buffer
-                                    const int rs = bs;                                 // and register set (= stage parity)
-                                    if ((o & 1) == 0) store_one(SP[bs], SQ[bs], rs, x);
-                                    else load_one(tgt + NSET, rs, x);
-                                }
-                                __builtin_amdgcn_sched_barrier(0);
+                        for (int i = 0; i < 8; ++i)
+#pragma unroll
+                        for (int jq = 0; jq < 8; ++jq) {
+                            const int b = 8 * ks + i, M = 8 * b + jq, off = jq;
+                            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc4[i][jq]) : "v"(qr[ks][jq]), "v"(pr[b & 3]));
+                            __builtin_amdgcn_sched_barrier(0);
+                            int mv = -1;  // move slot: 2 x chunk = store, 2 x chunk + 1 = load
+                            if (b < 8) {
+                                if (off == 5) mv = 2 * b;
+                                if (off == 7) mv = 2 * b + 1;
+                            } else if (b <= 13) {
+                                if (off == 3) mv = 16 + 3 * (b - 8);
+                                if (off == 5) mv = 17 + 3 * (b - 8);
+                                if (off == 7) mv = 18 + 3 * (b - 8);
                             }
-                            // (the compiler waits for each fragment before its first use; the last reads of this
-                            // buffer must have returned, and the stores landed, only at the barrier)
-                            if (kk == 2) {
+                            if (off == 1 && i <= 5) rdP(s, ks, i + 2, (b + 2) & 3);       // two blocks ahead
+                            else if (ks == 0 && off == 3) rdQ(s, 1, i, 1);                 // the Q fragments of step 1
+                            else if (M == 50) rdP(s, 1, 0, 0);                             // P blocks 0, 1 of step 1
+                            else if (M == 57) rdP(s, 1, 1, 1);
+                            else if (mv >= 0 && mv < 32 && (mv & 1) == 0) store_one(SP[s ^ 1], SQ[s ^ 1], mv >> 1);
+                            else if (mv >= 0 && mv < 32) load_one(j + 2, mv >> 1);
+                            else if (M == 115) {  // the last fragments of this buffer have arrived, stage j + 1 has landed
                                 wait_lgkm0();
                                 stage_barrier();
-                            }
+                            } else if (M == 117) rdP(s ^ 1, 0, 0, 0);                      // behind the barrier: the first
+                            else if (M == 125) rdP(s ^ 1, 0, 1, 1);                        // fragments of stage j + 1
+                            else if (M == 116) rdQ(s ^ 1, 0, 0, 0);
+                            else if (M >= 118 && M <= 124) rdQ(s ^ 1, 0, M - 117, 0);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     };
-                    // stage 0 from the registers to buffer 0 (both register sets were requested before the previous
-                    // tile's epilogue), stage NSET into the freed set, the first fragments
+                    // stage 0 from the registers to buffer 0 (it was requested before the previous tile's epilogue),
+                    // stage 1 into the freed registers, the first fragments
 #pragma unroll
-                    for (int x = 0; x < 2 * CH; ++x) store_one(SP[0], SQ[0], 0, x);
+                    for (int x = 0; x < 2 * CH; ++x) store_one(SP[0], SQ[0], x);
 #pragma unroll
-                    for (int x = 0; x < 2 * CH; ++x) load_one(NSET, 0, x);
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {  // (the part of stage 1 that step 3 of the stage before would have moved)
-                        store_one(SP[1], SQ[1], 1, x);
-                        load_one(1 + NSET, 1, x);
-                    }
+                    for (int x = 0; x < 2 * CH; ++x) load_one(1, x);
                     wait_lgkm0();
                     stage_barrier();
 #pragma unroll
-                    for (int b = 0; b < 4 + NJ; ++b) rd_one(0, 0, 0, b);
+                    for (int jq = 0; jq < 8; ++jq) rdQ(0, 0, jq, 0);
+                    rdP(0, 0, 0, 0);
+                    rdP(0, 0, 1, 1);
+                    asm volatile("s_nop 7" ::: "memory");  // (likewise: the zeroed accumulators, written by ordinary moves)
                     // (always pairs of stages, an odd count padded with a stage of zeros: with an exit between the two
                     // halves, or an odd stage behind the loop, the register allocator no longer keeps the 256
                     // accumulation registers in place and spills hundreds of them)
@@ -917,8 +964,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                         stage4(j, 0);
                         stage4(j + 1, 1);
                     }
-                    wait_lgkm0();     // (the unused stores of the last step: landed before buffer 1 becomes the staging area)
+                    wait_lgkm0();     // (the unused reads and stores of the last stage: landed before the buffers are reused)
                     stage_barrier();  // every wave is past its last fragment read
+                    // (the MFMAs are inline assembly: the compiler does not know that their results need 18 more cycles
+                    // before ordinary instructions may read them)
+                    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
                 }
             } else if (KT > 0 && wm == 0) {
                 wait_vm0();  // stage 0, issued before the previous tile's epilogue
@@ -1024,6 +1074,16 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     }
                 }
             }
+            if (NW == 4) {
+                // a lane holds, per 16 x 16 block, one output row (l % 16) and 4 consecutive columns (4 (l / 16) + 0..3);
+                // pass i stages the P blocks 2 i and 2 i + 1 of both wave rows
+#pragma unroll
+                for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+                    for (int jq = 0; jq < 8; ++jq)
+                        *(f32x4_t*)(stg + (wm * 32 + 16 * ib + (lane & 15)) * STG_PITCH + (jq / 4) * 128 + wn * 64 + (jq % 4) * 16 +
+                                    4 * (lane >> 4)) = acc4[2 * i + ib][jq];
+            } else
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
