@@ -134,7 +134,8 @@ __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70);
 // vmcnt(1): everything but the wave's youngest vector-memory operation (the L2 warm-up load, see PF below)
 __device__ __forceinline__ void wait_vm1() { __builtin_amdgcn_s_waitcnt(0x0F71); }
 
-__device__ __forceinline__ float sigmoid_f(float g) { return 1.0f / (1.0f + __expf(-g)); }
+// (hardware reciprocal, 1 ulp: an IEEE division is ten instructions per element in an epilogue one wave runs alone)
+__device__ __forceinline__ float sigmoid_f(float g) { return __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
 // ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the address of 4 consecutive
 // 16-bit elements (row i/4, columns 4*(i%4)..+3 of a 4x16 block) and receives column i of that block
@@ -1098,11 +1099,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 }
             wait_lgkm0();
             stage_barrier();
-            auto out_row = [&](int x8, bool early) {
+            auto out_row = [&](int x8, bool early, bool have, f32x4_t vin) {
                 const int rr = wave * RPW + x8;                           // staged row 0..63
                 const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
                 if (r >= ep_i_end) return;                                // wave-uniform
-                const f32x4_t v = *(const f32x4_t*)(stg + rr * STG_PITCH + cl);
+                const f32x4_t v = have ? vin : *(const f32x4_t*)(stg + rr * STG_PITCH + cl);
                 if (EPI == GG_EPI_SWIGLU) {
                     bf16_t* C = (bf16_t*)a.out;                           // [gate | up] pre-activations
                     if (C && ep_j0 + (cl & 127) < half_cols) {
@@ -1187,17 +1188,21 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             };
             // (the pass loop must unroll completely: the accumulators are indexed by it.  The compiler gives up on
             // that above a size limit, so the row loops stay rolled where nothing is indexed by them)
-            if (Z_EARLY) {
-#pragma unroll
-                for (int x8 = 0; x8 < ZE; ++x8) out_row(x8, true);
-#pragma unroll 4
-                for (int x8 = ZE; x8 < RPW; ++x8) out_row(x8, false);
-            } else if (FP8) {
+            const f32x4_t none = {0.f, 0.f, 0.f, 0.f};
+            if (FP8) {
 #pragma unroll 1
-                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8, false);
+                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8, false, false, none);
             } else {
+                // rows in batches of 8: all the staged values first (unconditional LDS reads, nothing between them),
+                // then the rows; read inside the rows, every LDS latency would be taken in turn
 #pragma unroll
-                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8, false);
+                for (int x0 = 0; x0 < RPW; x0 += 8) {
+                    f32x4_t vb[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) vb[u] = *(const f32x4_t*)(stg + (wave * RPW + x0 + u) * STG_PITCH + cl);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) out_row(x0 + u, Z_EARLY && x0 == 0, true, vb[u]);
+                }
             }
             if (EPI == GG_EPI_SWIGLU) {
                 // activation: a lane pairs gate and up of 4 features; two tile rows per instruction
