@@ -29,12 +29,12 @@ CAL_COPY_BYTES = 1 << 30    # size of the calibration copy (read 1 GiB, write 1 
 # Summaries and commands: profiles/gg_kernel_c4_hbm_traffic.txt, ..._c5_..., ..._c6_....
 # Offline measurements: they describe the committed kernels at the default load pattern, not this run.
 MEASURED_TRAFFIC_GB = {
-    "C4": {"fc1_fwd_swiglu_bf16": (13.22, 1.61), "fc2_fwd_bf16": (6.77, 1.88), "fc2_wgrad_bf16": (11.09, 0.94),
-           "fc2_dgrad_swiglu_bwd_bf16": (8.78, 1.07), "fc1_wgrad_bf16": (18.89, 1.88), "fc1_dgrad_bf16": (14.51, 1.88)},
-    "C5": {"fc1_fwd_swiglu_fp8": (7.18, 1.65), "fc2_fwd_fp8": (3.86, 1.92), "fc2_wgrad_bf16": (11.95, 0.94),
-           "fc2_dgrad_swiglu_bwd_fp8": (5.00, 1.10), "fc1_wgrad_bf16": (19.28, 1.88), "fc1_dgrad_fp8": (7.08, 1.91)},
-    "C6": {"fc1_fwd_swiglu_mxfp8": (7.46, 1.65), "fc2_fwd_mxfp8": (3.72, 1.91), "fc2_wgrad_mxfp8": (4.55, 0.94),
-           "fc2_dgrad_swiglu_bwd_mxfp8": (5.01, 1.09), "fc1_wgrad_mxfp8": (9.94, 1.88), "fc1_dgrad_mxfp8": (7.17, 1.91)},
+    "C4": {"fc1_fwd_swiglu_bf16": (13.76, 1.61), "fc2_fwd_bf16": (6.75, 1.88), "fc2_wgrad_bf16": (5.65, 0.94),
+           "fc2_dgrad_swiglu_bwd_bf16": (10.14, 1.07), "fc1_wgrad_bf16": (11.81, 1.88), "fc1_dgrad_bf16": (13.29, 1.88)},
+    "C5": {"fc1_fwd_swiglu_fp8": (7.13, 1.93), "fc2_fwd_fp8": (3.86, 1.92), "fc2_wgrad_bf16": (6.14, 0.94),
+           "fc2_dgrad_swiglu_bwd_fp8": (5.05, 1.66), "fc1_wgrad_bf16": (12.01, 1.88), "fc1_dgrad_fp8": (7.31, 1.91)},
+    "C6": {"fc1_fwd_swiglu_mxfp8": (7.38, 1.64), "fc2_fwd_mxfp8": (3.71, 1.91), "fc2_wgrad_mxfp8": (4.65, 0.94),
+           "fc2_dgrad_swiglu_bwd_mxfp8": (5.00, 1.09), "fc1_wgrad_mxfp8": (9.64, 1.88), "fc1_dgrad_mxfp8": (7.19, 1.91)},
 }
 
 
