@@ -221,7 +221,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // DeepSeek-V3-style shape they gain 3-17 % per bf16 call on all-zero operands (clock not power-limited) and lose
     // 1.5-4.5 % on N(0, 0.02^2) operands, where the sustained clock is set by power and the extra requests only add
     // to it; the one-byte variants change by -5 .. +3 % per call, no net gain
-    constexpr bool PF = FP8 ? (GG_PF & 2) != 0 : (GG_PF & 1) != 0;
+    constexpr bool PF = NW == 8 && (FP8 ? (GG_PF & 2) != 0 : (GG_PF & 1) != 0);
     // fp8: the block scales of a stage travel with it, behind the P tile: 256 row scales (position
     // 4 * (row % 32) + row / 32 inside each 128-row half, so a lane finds its four rows in one 16-byte
     // read) and, from position 256 on, the two column-block scales (replicated)
