@@ -1200,8 +1200,30 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     f32x4_t vb[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) vb[u] = *(const f32x4_t*)(stg + (wave * RPW + x0 + u) * STG_PITCH + cl);
+                    // plain store of 8 whole rows (the common case): no test or branch per row, one address chain
+                    const int rr0 = wave * RPW + x0;
+                    const int r0 = ep_i0 + (rr0 >> 5) * 128 + i * 32 + (rr0 & 31);  // the 8 rows are consecutive
+                    if (EPI == GG_EPI_STORE && !a.accumulate && r0 + 8 <= ep_i_end) {
+                        if (c < J) {
+                            const int64_t ld = (MODE == GG_WGRAD) ? K : J;
+                            const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r0) * K : (int64_t)r0 * J;
+                            if (OUT_F32) {
+                                float* o = (float*)a.out + base + c;
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) out_row(x0 + u, Z_EARLY && x0 == 0, true, vb[u]);
+                                for (int u = 0; u < 8; ++u) *(f32x4_t*)(o + u * ld) = vb[u];
+                            } else {
+                                bf16_t* o = (bf16_t*)a.out + base + c;
+#pragma unroll
+                                for (int u = 0; u < 8; ++u) {
+                                    const float t4[4] = {vb[u][0], vb[u][1], vb[u][2], vb[u][3]};
+                                    st4_bf16(o + u * ld, t4);
+                                }
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) out_row(x0 + u, Z_EARLY && x0 == 0, true, vb[u]);
+                    }
                 }
             }
             if (EPI == GG_EPI_SWIGLU) {
