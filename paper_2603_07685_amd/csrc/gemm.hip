@@ -3,8 +3,12 @@
 // forward, data-gradient and weight-gradient (Sec. 4.2.3 "W/D split") in bf16 and MXFP8 (Sec. 5.3.3),
 // forward and data-gradient also in blockwise fp8 (Sec. 5.3.2), are instantiations of one kernel.
 //
-// The kernel computes OUT[i,j] = sum_c P[i,c] * Q[j,c] on a 256x256 output tile per workgroup
-// (8 wavefronts as 2 x 4, wave tile 128x64 = 4x2 MFMA blocks of 32x32):
+// The kernel computes OUT[i,j] = sum_c P[i,c] * Q[j,c] on a 256x256 output tile per workgroup.  Two bodies share
+// the schedule, the tile set-up, the LDS layouts and the epilogue (template parameter NW):
+//   bf16:        4 wavefronts as 2 x 2, one per SIMD with 512 registers; wave tile 128x128 = 8x8 blocks of the
+//                16x16x32 MFMA; operands staged through registers (described at the stage loop)
+//   fp8 / MXFP8: 8 wavefronts as 2 x 4; wave tile 128x64 = 4x2 blocks of the 32x32x64 MFMA; operands by DMA, the
+//                "ping-pong" schedule below
 //     forward : P = activations [rows,K]   Q = W_e [N,K]        OUT = C[rows,N]
 //     dgrad   : P = dC [rows,N]            Q = W_e as [K,N]^T   OUT = dA[rows,K]
 //     wgrad   : P = dC as [N,rows]^T       Q = A as [K,rows]^T  OUT = dW_e[N,K]
@@ -12,9 +16,9 @@
 // Operand stream.  The contraction is walked in stages of 128 bytes per operand row (64 bf16 or
 // 128 fp8 elements): every global request of the DMA is then a whole 128-byte cache line, which
 // the L1/L2 path serves at about twice the rate of half-line requests (measured: 20 vs 10 TB/s on
-// a GEMM-like sharing pattern).  Each stage's two 32 KB operand tiles are fetched by direct
-// global->LDS loads (16 B per lane) into one of two stage buffers.  The DMA is issued through
-// inline asm and synchronised by the kernel's own waits (see dma16 below).
+// a GEMM-like sharing pattern).  Each stage's two 32 KB operand tiles go into one of two stage buffers: by direct
+// global->LDS loads (eight-wave body; 16 B per lane, issued through inline asm and synchronised by the kernel's
+// own waits, see dma16 below) or through registers (four-wave body), with the same chunk -> lane mapping.
 //
 // LDS layouts.  An operand whose contraction index is contiguous in memory ("k-major", tile
 // [256 rows][128 B]) is read with ds_read_b128; one whose contraction index is the memory row
@@ -24,7 +28,7 @@
 // operand reads are free of bank conflicts; the swizzle is applied on the global side of the DMA
 // (each lane chooses which 16 bytes it fetches; the LDS side of a DMA is always lane-linear).
 //
-// Schedule ("ping-pong").  A stage is consumed in two halves.  The two waves that share a SIMD
+// Schedule of the eight-wave body ("ping-pong").  A stage is consumed in two halves.  The two waves that share a SIMD
 // (wave w and w+4) belong to two groups that run one phase apart: while one issues the MFMAs of a
 // half-stage with all operands already in registers, the other fetches its next operands from
 // LDS; they swap at fence-free workgroup barriers.  Each group has its own copy of the stage loop.
@@ -38,10 +42,9 @@
 // precedes group 0's A(s+1,0): group 0 at the end of B(s,1), group 1 at the end of A(s,1).
 // The first stage of a tile is issued before the epilogue of the tile before it.
 //
-// MFMAs are issued as (Q fragment, P fragment): a lane's 16 accumulators of a block are one
-// output row and 4 groups of 4 consecutive columns, and the wave's two column sub-tiles are 128
-// columns apart, i.e. the gate and up columns of the same features when the SwiGLU epilogue is
-// on.  The epilogue stages the fp32 accumulators through LDS and writes whole tile rows; the
+// MFMAs are issued as (Q fragment, P fragment): a lane's accumulators of a block are one output row and 4
+// consecutive columns (16x16 blocks; four such groups in a 32x32 block), and the wave's column blocks come in two
+// halves 128 columns apart, i.e. the gate and up columns of the same features when the SwiGLU epilogue is on.  The epilogue stages the fp32 accumulators through LDS and writes whole tile rows; the
 // activation (forward) and its derivative (fc2 dgrad) are applied to the fp32 values there.
 //
 // fp8: operands are E4M3 codes; a half-stage is one v_mfma_scale_f32_32x32x64_f8f6f4 per block with unit
