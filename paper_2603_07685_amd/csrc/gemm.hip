@@ -1304,10 +1304,7 @@ static gg_args gg_make(moe_ctx* ctx, const void* P, const void* Q, const int32_t
 #ifndef GG_BF16_NW
 #define GG_BF16_NW 4  // waves per workgroup of the bf16 variants (see the kernel)
 #endif
-#ifndef GG_BF16_WGRAD_NW
-#define GG_BF16_WGRAD_NW GG_BF16_NW
-#endif
-#define GG_NW_OF(MODE, FP8) ((FP8) ? 8 : (MODE) == GG_WGRAD ? GG_BF16_WGRAD_NW : GG_BF16_NW)
+#define GG_NW_OF(MODE, FP8) ((FP8) ? 8 : GG_BF16_NW)
 #define GG_LAUNCH(MODE, EPI, F32, FP8)                                                                          \
     hipLaunchKernelGGL((gg_kernel<MODE, EPI, F32, FP8, GG_NW_OF(MODE, FP8)>),                                   \
                        dim3(ctx->num_cu > 0 ? ctx->num_cu : 256), dim3(GG_NW_OF(MODE, FP8) * 64),               \
