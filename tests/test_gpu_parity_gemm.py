@@ -315,3 +315,34 @@ def test_grouped_gemms_many_small_experts(B, ctx, oracle, E):
     got = host_f64(dW)
     assert rel_fro(got, oracle.grouped_gemm_tn(dCh, Ah, off)) <= 1e-5
     assert not got[counts == 0].any()
+
+
+def test_grouped_gemm_runs_are_bit_identical(B, ctx):
+    """No result depends on timing: every workgroup walks its tiles through two LDS buffers that four waves fill and
+    read under one barrier per stage, and no floating-point atomics are used, so two runs of a call must agree bit
+    for bit.  Many tiles per workgroup (odd and even stage counts, ragged experts, an empty one), all three modes."""
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    counts = [1500, 0, 777, 2049, 130, 4096, 3, 900]
+    E, N, K = len(counts), 1536, 1344          # K / 64 = 21 stages (odd), N / 64 = 24 (even)
+    off = _offsets(counts)
+    R = int(off[-1])
+    Rcap = R + 3
+    A = dev_bf16(wl.gaussian_bf16((Rcap, K), 1.0, 71, K))
+    W = dev_bf16(wl.gaussian_bf16((E, N, K), 0.05, 72, K))
+    dC = dev_bf16(wl.gaussian_bf16((Rcap, N), 1.0, 73, N))
+    doff = dev(off)
+    outs = []
+    for rep in range(3):
+        C = torch.zeros((Rcap, N), dtype=torch.bfloat16, device="cuda")
+        dA = torch.zeros((Rcap, K), dtype=torch.bfloat16, device="cuda")
+        dW = torch.zeros((E, N, K), dtype=torch.bfloat16, device="cuda")
+        B.moe_grouped_gemm_fwd(ctx, A, W, doff, E, N, K, Rcap, B.BF16, B.EPI_NONE, None, None, C, None)
+        B.moe_grouped_gemm_dgrad(ctx, dC, W, doff, E, N, K, Rcap, B.BF16, None, None, None, dA)
+        B.moe_grouped_gemm_wgrad(ctx, A, dC, doff, E, N, K, Rcap, B.BF16, None, None, 0, B.BF16, dW)
+        torch.cuda.synchronize()
+        assert ctx.poll_error() == 0
+        outs.append((C, dA, dW))
+    for rep in (1, 2):
+        for got, first in zip(outs[rep], outs[0]):
+            assert torch.equal(got.view(torch.int16), first.view(torch.int16))
