@@ -68,7 +68,8 @@ moe_status moe_ctx_create(moe_ctx** out, int device, size_t workspace_bytes);
  * must have finished.  NULL is accepted. */
 moe_status moe_ctx_destroy(moe_ctx* ctx);
 
-/* Host string for the last error recorded on ctx ("" if none); owned by ctx. */
+/* Host string for the last error recorded on ctx ("" if none); owned by ctx.  ctx = NULL: the message of the
+ * calling host thread's last failed call that takes no context (moe_permute_static). */
 const char* moe_last_error(const moe_ctx* ctx);
 
 /* Kernels that find a device-side inconsistency (offsets[E] > Rcap) skip the
@@ -189,6 +190,24 @@ moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe_dtype dt,
                        const int32_t* idx, int T, int k, int h, int E, int align,
                        void* Xp, int64_t Rcap,
                        int32_t* row_of, int32_t* src_of, int32_t* offsets, int32_t* counts);
+
+/*
+ * moe_permute for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It takes no context (moe_ctx_create allocates) and calls no
+ * hipMalloc / hipFree or allocating library routine: the per-chunk histograms that moe_permute keeps in the
+ * context workspace live in a file-scope device array of 1 MiB inside the library (each GPU the library runs on
+ * holds it until the process ends; its address is looked up once per device, on the first call made with that
+ * device current).  Arguments, results and limits are those of moe_permute, bit for bit, and in addition
+ *   ceil(T*k / 1024) * E * 4 bytes <= 1 MiB   (e.g. T*k <= 262144 pairs at E = 1024, 8.4 M pairs at E = 32);
+ * larger problems return MOE_ERR_WORKSPACE and launch nothing.  The device current on the calling thread must be
+ * the one that owns the buffers and `stream`.  The array needs no clearing between calls (every entry is written
+ * before it is read), but every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU
+ * (two streams, two host threads) race.  Failures: status as above, message through moe_last_error(NULL).
+ */
+moe_status moe_permute_static(void* stream, const void* X, moe_dtype dt,
+                              const int32_t* idx, int T, int k, int h, int E, int align,
+                              void* Xp, int64_t Rcap,
+                              int32_t* row_of, int32_t* src_of, int32_t* offsets, int32_t* counts);
 
 /* ------------------------------------------------------------------------- */
 /* Stage 3: Expert computation = Grouped GEMM (Sec. 2.1.4, 4.3.2, 4.3.7)      */

@@ -29,7 +29,7 @@ EXPORTS = [
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
     "moe_route_topk_bwd", "moe_mx_quantize", "moe_mx_quantize_rowcol",
     "moe_route_topk_grouped", "moe_aux_loss", "moe_mx_quantize_rowcol_gather",
-    "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gate_gemm",
+    "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gate_gemm", "moe_permute_static",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
         L.moe_ctx_poll_error.argtypes = [_vp, _vp, C.POINTER(_i)]
         L.moe_route_topk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp]
         L.moe_permute.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _vp, _i64, _vp, _vp, _vp, _vp]
+        L.moe_permute_static.argtypes = [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _vp, _i64, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_dgrad.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_wgrad.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _i, _i, _vp]
@@ -150,6 +151,13 @@ def moe_aux_loss(ctx, logits, counts, T, E, k, fn, coeff, dloss, accumulate, los
 def moe_permute(ctx, X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts):
     ctx.check(lib().moe_permute(ctx.h, _stream(), _ptr(X), dt, _ptr(idx), T, k, h, E, align, _ptr(Xp), Rcap,
                                 _ptr(row_of), _ptr(src_of), _ptr(offsets), _ptr(counts)), "moe_permute")
+
+
+def moe_permute_static(X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts):
+    st = lib().moe_permute_static(_stream(), _ptr(X), dt, _ptr(idx), T, k, h, E, align, _ptr(Xp), Rcap,
+                                  _ptr(row_of), _ptr(src_of), _ptr(offsets), _ptr(counts))
+    if st != 0:
+        raise MoeError(f"moe_permute_static: status {st}: {lib().moe_last_error(None).decode()}")
 
 
 def moe_grouped_gemm_fwd(ctx, A, B, offsets, E, N, K, Rcap, dt, epi, a_scale, b_scale, Cout, C_act):

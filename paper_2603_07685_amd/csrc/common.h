@@ -84,5 +84,8 @@ moe_status moe_gg_f32_dgrad(moe_ctx* ctx, hipStream_t s, const void* dC, const v
 moe_status moe_gg_f32_wgrad(moe_ctx* ctx, hipStream_t s, const void* A, const void* dC, const int32_t* offsets, int E, int N,
                             int K, int64_t Rcap, int accumulate, void* dB);
 
+// message buffer (512 bytes, one per host thread) of the calls that take no context; moe_last_error(NULL) returns it
+char* moe_ctxless_error();
+
 // shared by the fill launches of several files
 void moe_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s);

@@ -61,7 +61,10 @@ extern "C" moe_status moe_ctx_destroy(moe_ctx* ctx) {
     return e == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-extern "C" const char* moe_last_error(const moe_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+static thread_local char ctxless_err[512];
+char* moe_ctxless_error() { return ctxless_err; }
+
+extern "C" const char* moe_last_error(const moe_ctx* ctx) { return ctx ? ctx->err : ctxless_err; }
 
 extern "C" moe_status moe_ctx_poll_error(moe_ctx* ctx, void* stream, int* device_error) {
     if (!ctx || !device_error) return MOE_ERR_ARG;

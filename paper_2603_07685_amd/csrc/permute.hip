@@ -356,30 +356,38 @@ static int bits_for(int E) {
     return b;
 }
 
-extern "C" moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe_dtype dt,
-                                  const int32_t* idx, int T, int k, int h, int E, int align,
-                                  void* Xp, int64_t Rcap,
-                                  int32_t* row_of, int32_t* src_of, int32_t* offsets, int32_t* counts) {
-    if (!ctx) return MOE_ERR_ARG;
-    if (!idx || !row_of || !src_of || !offsets || !counts) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_permute: NULL map pointer");
-    if ((X == nullptr) != (Xp == nullptr)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_permute: X and Xp must both be given or both NULL");
+// Argument checks shared by moe_permute and moe_permute_static (err: where the message goes, 512 bytes, or NULL).
+static moe_status permute_check(char* err, const void* X, moe_dtype dt, const int32_t* idx, int T, int k, int h, int E,
+                                int align, const void* Xp, int64_t Rcap, const int32_t* row_of, const int32_t* src_of,
+                                const int32_t* offsets, const int32_t* counts) {
+#define PERMUTE_FAIL(code, ...)                        \
+    do {                                               \
+        if (err) snprintf(err, 512, __VA_ARGS__);      \
+        return (code);                                 \
+    } while (0)
+    if (!idx || !row_of || !src_of || !offsets || !counts) PERMUTE_FAIL(MOE_ERR_ARG, "moe_permute: NULL map pointer");
+    if ((X == nullptr) != (Xp == nullptr)) PERMUTE_FAIL(MOE_ERR_ARG, "moe_permute: X and Xp must both be given or both NULL");
     if (T < 0 || k < 1 || k > 32 || E < 1 || E > 1024 || align < 1 || h < 1)
-        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_permute: need T>=0, 1<=k<=32, 1<=E<=1024, align>=1, h>=1");
-    if (dt != MOE_BF16 && dt != MOE_F32) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_permute: dtype must be bf16 or f32");
+        PERMUTE_FAIL(MOE_ERR_ARG, "moe_permute: need T>=0, 1<=k<=32, 1<=E<=1024, align>=1, h>=1");
+    if (dt != MOE_BF16 && dt != MOE_F32) PERMUTE_FAIL(MOE_ERR_UNSUPPORTED, "moe_permute: dtype must be bf16 or f32");
     const size_t row_bytes = (size_t)h * moe_dtype_size(dt);
-    if (X && row_bytes % 16) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_permute: row size %zu B is not a multiple of 16", row_bytes);
+    if (X && row_bytes % 16) PERMUTE_FAIL(MOE_ERR_ARG, "moe_permute: row size %zu B is not a multiple of 16", row_bytes);
     const int64_t pairs = (int64_t)T * k;
     const int64_t need = pairs + (int64_t)E * (align - 1);
-    if (Rcap < need) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_permute: Rcap=%lld < T*k+E*(align-1)=%lld", (long long)Rcap, (long long)need);
-    if (Rcap > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_permute: Rcap exceeds int32");
-    if (MOE_WS_RESERVED + moe_permute_ws_bytes(pairs, E) > ctx->ws_bytes)
-        MOE_FAIL(ctx, MOE_ERR_WORKSPACE, "moe_permute: workspace %zu B < %zu B", ctx->ws_bytes,
-                 MOE_WS_RESERVED + moe_permute_ws_bytes(pairs, E));
-    hipStream_t s = (hipStream_t)stream;
-    int32_t* chunk_hist = (int32_t*)((char*)ctx->ws + MOE_WS_RESERVED);
+    if (Rcap < need) PERMUTE_FAIL(MOE_ERR_ARG, "moe_permute: Rcap=%lld < T*k+E*(align-1)=%lld", (long long)Rcap, (long long)need);
+    if (Rcap > 0x7fffffffLL) PERMUTE_FAIL(MOE_ERR_ARG, "moe_permute: Rcap exceeds int32");
+#undef PERMUTE_FAIL
+    return MOE_OK;
+}
+
+// The launches of one permute call; chunk_hist = int32 [chunks, E] of device scratch (every entry is written by the
+// histogram kernel before it is read: the buffer needs no clearing).
+static void permute_launch(hipStream_t s, const void* X, moe_dtype dt, const int32_t* idx, int T, int k, int h, int E,
+                           int align, void* Xp, int64_t Rcap, int32_t* row_of, int32_t* src_of, int32_t* offsets,
+                           int32_t* counts, int32_t* chunk_hist) {
+    const int64_t pairs = (int64_t)T * k;
     const int nchunks = (int)moe_permute_chunks(pairs);
     const size_t shm = (size_t)E * sizeof(int32_t);
-
     moe_launch_fill_i32(src_of, Rcap, -1, s);
     if (nchunks > 0) hipLaunchKernelGGL(permute_hist_kernel, dim3(nchunks), dim3(64), shm, s, idx, pairs, E, chunk_hist);
     hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, s, chunk_hist, nchunks, E, align, counts, offsets);
@@ -387,11 +395,77 @@ extern "C" moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe
         hipLaunchKernelGGL(permute_rank_kernel, dim3(nchunks), dim3(64), shm, s, idx, pairs, E, bits_for(E), chunk_hist,
                            offsets, row_of, src_of);
     if (X) {
-        const int vec = (int)(row_bytes / 16);
+        const int vec = (int)((size_t)h * moe_dtype_size(dt) / 16);
         hipLaunchKernelGGL(permute_rows_kernel, dim3(T + E), dim3(MOVE_THREADS), 0, s, (const u32x4_t*)X, row_of, offsets,
                            counts, T, k, E, vec, (u32x4_t*)Xp);
     }
+}
+
+extern "C" moe_status moe_permute(moe_ctx* ctx, void* stream, const void* X, moe_dtype dt,
+                                  const int32_t* idx, int T, int k, int h, int E, int align,
+                                  void* Xp, int64_t Rcap,
+                                  int32_t* row_of, int32_t* src_of, int32_t* offsets, int32_t* counts) {
+    if (!ctx) return MOE_ERR_ARG;
+    const moe_status st = permute_check(ctx->err, X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts);
+    if (st != MOE_OK) return st;
+    const int64_t pairs = (int64_t)T * k;
+    if (MOE_WS_RESERVED + moe_permute_ws_bytes(pairs, E) > ctx->ws_bytes)
+        MOE_FAIL(ctx, MOE_ERR_WORKSPACE, "moe_permute: workspace %zu B < %zu B", ctx->ws_bytes,
+                 MOE_WS_RESERVED + moe_permute_ws_bytes(pairs, E));
+    permute_launch((hipStream_t)stream, X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts,
+                   (int32_t*)((char*)ctx->ws + MOE_WS_RESERVED));
     MOE_LAUNCH_CHECK(ctx, "moe_permute kernels");
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------
+// moe_permute_static: moe_permute for callers that cannot allocate (no context, no hipMalloc anywhere on the path).
+// The per-chunk histograms live in a file-scope device array instead of a context workspace.  Every GPU the library
+// runs on holds its own copy of the array at its own address until the process ends; the address is looked up once
+// per device, on the first call made with that device current, and kept.
+// ---------------------------------------------------------------------------
+#define PERMUTE_STATIC_BYTES (1u << 20)
+#define PERMUTE_STATIC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[PERMUTE_STATIC_BYTES];
+static void* scratch_ptr_of_device[PERMUTE_STATIC_MAX_DEVICES];  // host copies of the per-device addresses (0 = not yet looked up)
+
+extern "C" moe_status moe_permute_static(void* stream, const void* X, moe_dtype dt,
+                                         const int32_t* idx, int T, int k, int h, int E, int align,
+                                         void* Xp, int64_t Rcap,
+                                         int32_t* row_of, int32_t* src_of, int32_t* offsets, int32_t* counts) {
+    char* err = moe_ctxless_error();  // this host thread's message buffer, read back with moe_last_error(NULL)
+    err[0] = 0;
+    const moe_status st = permute_check(err, X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts);
+    if (st != MOE_OK) return st;
+    const size_t need = moe_permute_ws_bytes((int64_t)T * k, E);
+    if (need > PERMUTE_STATIC_BYTES) {
+        snprintf(err, 512, "moe_permute_static: ceil(T*k/%d)*E*4 = %zu B exceeds the fixed scratch of %u B; use moe_permute",
+                 PERMUTE_CHUNK, need, PERMUTE_STATIC_BYTES);
+        return MOE_ERR_WORKSPACE;
+    }
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= PERMUTE_STATIC_MAX_DEVICES) {
+        snprintf(err, 512, "moe_permute_static: no current device below %d (%s)", PERMUTE_STATIC_MAX_DEVICES, hipGetErrorString(e));
+        return MOE_ERR_HIP;
+    }
+    // (two host threads racing here both look up the same address and store the same value)
+    void* ptr = __atomic_load_n(&scratch_ptr_of_device[dev], __ATOMIC_ACQUIRE);
+    if (!ptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            snprintf(err, 512, "moe_permute_static: hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+            return MOE_ERR_HIP;
+        }
+        __atomic_store_n(&scratch_ptr_of_device[dev], ptr, __ATOMIC_RELEASE);
+    }
+    permute_launch((hipStream_t)stream, X, dt, idx, T, k, h, E, align, Xp, Rcap, row_of, src_of, offsets, counts,
+                   (int32_t*)ptr);
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(err, 512, "launch moe_permute_static kernels: %s", hipGetErrorString(e));
+        return MOE_ERR_HIP;
+    }
     return MOE_OK;
 }
 
