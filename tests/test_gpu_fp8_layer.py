@@ -14,9 +14,26 @@ def _f64(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+def _checkers():
+    """(c8, c16): element-level checks of a one-byte GEMM's output against the full-precision oracle (6e-2 pooled; a
+    row on its own fluctuates around the format's noise, hence 3 x for rows: a wrong row is off by its whole norm) and of a bf16 result (2e-2 pooled and
+    per row, 6e-3 regression bound); dprob is a handful of dot products per row (sums with cancellation: the error
+    scales with the operands, not with the result), so its rows are checked against the typical row."""
+    from gpu_util import assert_close, BF16_TOL, FP8_TOL
+
+    def c8(key, got, ref):
+        return assert_close(got, ref, key, tol=FP8_TOL, reg=None, row_tol=3 * FP8_TOL, row_floor=0.3 if key == "dprob" else 1e-6)
+
+    def c16(key, got, ref):
+        return assert_close(got, ref, key, row_floor=0.05 if key == "dprob" else 1e-6)
+
+    return c8, c16
+
+
 @pytest.mark.parametrize("variant", [None, "zeros", "hot"])
 def test_fp8_layer_every_element(oracle, variant):
     from gpu_util import rel_fro, BF16_TOL, FP8_TOL
+    c8, c16 = _checkers()
     from paper_2603_07685_amd import layer as L
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS["C5S"]
@@ -46,26 +63,26 @@ def test_fp8_layer_every_element(oracle, variant):
     W1, W2, Ws1, Ws2 = hin["W1"], hin["W2"], hin["Ws1"][None], hin["Ws2"][None]
     e8, e16 = {}, {}
     Zref = oracle.grouped_gemm_nt(Xp, W1, off)
-    e8["Z"] = rel_fro(_f64(st.Z)[:R], Zref)
-    e8["A"] = rel_fro(_f64(st.A)[:R], oracle.swiglu(Zref))
-    e8["O"] = rel_fro(_f64(st.O)[:R], oracle.grouped_gemm_nt(_f64(st.A)[:R], W2, off))
+    e8["Z"] = c8("Z", _f64(st.Z)[:R], Zref)
+    e8["A"] = c8("A", _f64(st.A)[:R], oracle.swiglu(Zref))
+    e8["O"] = c8("O", _f64(st.O)[:R], oracle.grouped_gemm_nt(_f64(st.A)[:R], W2, off))
     o1 = np.array([0, T], np.int32)
-    e8["Zs"] = rel_fro(_f64(st.Zs), oracle.grouped_gemm_nt(hin["X"], Ws1, o1))
-    e8["S"] = rel_fro(_f64(st.S), oracle.grouped_gemm_nt(_f64(st.As), Ws2, o1))
+    e8["Zs"] = c8("Zs", _f64(st.Zs), oracle.grouped_gemm_nt(hin["X"], Ws1, o1))
+    e8["S"] = c8("S", _f64(st.S), oracle.grouped_gemm_nt(_f64(st.As), Ws2, o1))
     prob = st.topk_prob.cpu().numpy().astype(np.float64)
-    e16["Y"] = rel_fro(_f64(st.Y), oracle.combine(_f64(st.O)[:R], m.row_of, prob, _f64(st.S)))
+    e16["Y"] = c16("Y", _f64(st.Y), oracle.combine(_f64(st.O)[:R], m.row_of, prob, _f64(st.S)))
     dOref, dpref = oracle.combine_bwd(hin["dY"], _f64(st.O)[:R], m.row_of, prob, R)
-    e16["dO"] = rel_fro(_f64(st.dO)[:R], dOref)
+    e16["dO"] = c16("dO", _f64(st.dO)[:R], dOref)
     assert np.all(_f64(st.dO)[:R][m.src_of[:R] < 0] == 0)                 # padding rows of dO are exact zeros
-    e16["dprob"] = rel_fro(st.dprob.cpu().numpy(), dpref)
+    e16["dprob"] = c16("dprob", st.dprob.cpu().numpy(), dpref)
     dOg, Zg, dZg = _f64(st.dO)[:R], _f64(st.Z)[:R], _f64(st.dZ)[:R]
-    e16["dW2"] = rel_fro(_f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off))
-    e8["dZ"] = rel_fro(dZg, oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, off), Zg))
-    e16["dW1"] = rel_fro(_f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off))
-    e8["dXp"] = rel_fro(_f64(st.dXp)[:R], oracle.grouped_gemm_nn(dZg, W1, off))
-    e8["dZs"] = rel_fro(_f64(st.dZs), oracle.swiglu_bwd(oracle.grouped_gemm_nn(hin["dY"], Ws2, o1), _f64(st.Zs)))
-    e8["dXs"] = rel_fro(_f64(st.dXs), oracle.grouped_gemm_nn(_f64(st.dZs), Ws1, o1))
-    e16["dX"] = rel_fro(_f64(st.dX), oracle.combine(_f64(st.dXp)[:R], m.row_of, None, _f64(st.dXs)))
+    e16["dW2"] = c16("dW2", _f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off))
+    e8["dZ"] = c8("dZ", dZg, oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, off), Zg))
+    e16["dW1"] = c16("dW1", _f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off))
+    e8["dXp"] = c8("dXp", _f64(st.dXp)[:R], oracle.grouped_gemm_nn(dZg, W1, off))
+    e8["dZs"] = c8("dZs", _f64(st.dZs), oracle.swiglu_bwd(oracle.grouped_gemm_nn(hin["dY"], Ws2, o1), _f64(st.Zs)))
+    e8["dXs"] = c8("dXs", _f64(st.dXs), oracle.grouped_gemm_nn(_f64(st.dZs), Ws1, o1))
+    e16["dX"] = c16("dX", _f64(st.dX), oracle.combine(_f64(st.dXp)[:R], m.row_of, None, _f64(st.dXs)))
     for e in range(E):
         if m.counts[e] == 0:
             assert not st.dW1[e].any() and not st.dW2[e].any()
@@ -84,6 +101,7 @@ def test_fp8_layer_eq2_per_call(oracle):
     """C5S in the memory-efficient permutation form (eq. (2)) with the fp8 GEMMs: the calls that differ from the
     standard form, each against the oracle on the tensors the GPU actually fed it."""
     from gpu_util import rel_fro, BF16_TOL, FP8_TOL
+    c8, c16 = _checkers()
     from paper_2603_07685_amd import layer as L
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS["C5S"]
@@ -101,19 +119,19 @@ def test_fp8_layer_eq2_per_call(oracle):
     np.testing.assert_array_equal(st.row_prob.cpu().numpy()[:R], row_p.astype(np.float32))
     Xp = oracle.permute_rows(hin["X"], m.src_of[:R], k)
     Zref = oracle.grouped_gemm_nt(Xp, hin["W1"], off)
-    e8 = {"Z": rel_fro(_f64(st.Z)[:R], Zref),
-          "A": rel_fro(_f64(st.A)[:R], oracle.swiglu(Zref) * row_p[:, None])}
+    e8 = {"Z": c8("Z", _f64(st.Z)[:R], Zref),
+          "A": c8("A", _f64(st.A)[:R], oracle.swiglu(Zref) * row_p[:, None])}
     assert np.all(_f64(st.A)[:R][m.src_of[:R] < 0] == 0)                  # padding rows carry weight 0
     Y = oracle.combine(_f64(st.O)[:R], m.row_of, None, _f64(st.S))
-    e16 = {"Y": rel_fro(_f64(st.Y), Y)}
+    e16 = {"Y": c8("Y", _f64(st.Y), Y)}
     dOref = oracle.permute_rows(hin["dY"], m.src_of[:R], k)
     assert np.array_equal(_f64(st.dO)[:R], dOref)
     dA = oracle.grouped_gemm_nn(dOref, hin["W2"], off)
     Zg = _f64(st.Z)[:R]
-    e8["dZ"] = rel_fro(_f64(st.dZ)[:R], oracle.swiglu_bwd(dA, Zg) * row_p[:, None])
+    e8["dZ"] = c8("dZ", _f64(st.dZ)[:R], oracle.swiglu_bwd(dA, Zg) * row_p[:, None])
     dp_row = (dA * oracle.swiglu(Zg)).sum(axis=1)
     dp = np.where(m.row_of >= 0, dp_row[np.maximum(m.row_of, 0)], 0.0)
-    e8["dprob"] = rel_fro(st.dprob.cpu().numpy(), dp)
+    e8["dprob"] = c8("dprob", st.dprob.cpu().numpy(), dp)
     print("eq2 fp8:", {k_: f"{v:.2e}" for k_, v in e8.items()}, "bf16:", {k_: f"{v:.2e}" for k_, v in e16.items()})
     for k_, v in e8.items():
         assert v <= FP8_TOL, (k_, v)
@@ -125,6 +143,7 @@ def test_mxfp8_layer_per_call(oracle):
     """C6S: the layer with MXFP8 (1x32, E8M0) forward / data-gradient / weight-gradient GEMMs, every element, per call: each GPU
     result against the oracle applied to the tensors the GPU fed that call (bound 6e-2 for the fp8 calls)."""
     from gpu_util import rel_fro, BF16_TOL, FP8_TOL
+    c8, c16 = _checkers()
     from paper_2603_07685_amd import layer as L
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS["C6S"]
@@ -156,22 +175,22 @@ def test_mxfp8_layer_per_call(oracle):
     Zref = oracle.grouped_gemm_nt(Xp, W1, off)
     dOg, Zg, dZg = _f64(st.dO)[:R], _f64(st.Z)[:R], _f64(st.dZ)[:R]
     e8 = {
-        "Z": rel_fro(_f64(st.Z)[:R], Zref), "A": rel_fro(_f64(st.A)[:R], oracle.swiglu(Zref)),
-        "O": rel_fro(_f64(st.O)[:R], oracle.grouped_gemm_nt(_f64(st.A)[:R], W2, off)),
-        "Zs": rel_fro(_f64(st.Zs), oracle.grouped_gemm_nt(hin["X"], Ws1, o1)),
-        "S": rel_fro(_f64(st.S), oracle.grouped_gemm_nt(_f64(st.As), Ws2, o1)),
-        "dZ": rel_fro(dZg, oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, off), Zg)),
-        "dXp": rel_fro(_f64(st.dXp)[:R], oracle.grouped_gemm_nn(dZg, W1, off)),
-        "dZs": rel_fro(_f64(st.dZs), oracle.swiglu_bwd(oracle.grouped_gemm_nn(hin["dY"], Ws2, o1), _f64(st.Zs))),
-        "dXs": rel_fro(_f64(st.dXs), oracle.grouped_gemm_nn(_f64(st.dZs), Ws1, o1)),
-        "dW2": rel_fro(_f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off)),
-        "dW1": rel_fro(_f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off)),
-        "dWs2": rel_fro(_f64(st.dWs2), oracle.grouped_gemm_tn(hin["dY"], _f64(st.As), o1)[0]),
-        "dWs1": rel_fro(_f64(st.dWs1), oracle.grouped_gemm_tn(_f64(st.dZs), hin["X"], o1)[0]),
+        "Z": c8("Z", _f64(st.Z)[:R], Zref), "A": c8("A", _f64(st.A)[:R], oracle.swiglu(Zref)),
+        "O": c8("O", _f64(st.O)[:R], oracle.grouped_gemm_nt(_f64(st.A)[:R], W2, off)),
+        "Zs": c8("Zs", _f64(st.Zs), oracle.grouped_gemm_nt(hin["X"], Ws1, o1)),
+        "S": c8("S", _f64(st.S), oracle.grouped_gemm_nt(_f64(st.As), Ws2, o1)),
+        "dZ": c8("dZ", dZg, oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, off), Zg)),
+        "dXp": c8("dXp", _f64(st.dXp)[:R], oracle.grouped_gemm_nn(dZg, W1, off)),
+        "dZs": c8("dZs", _f64(st.dZs), oracle.swiglu_bwd(oracle.grouped_gemm_nn(hin["dY"], Ws2, o1), _f64(st.Zs))),
+        "dXs": c8("dXs", _f64(st.dXs), oracle.grouped_gemm_nn(_f64(st.dZs), Ws1, o1)),
+        "dW2": c8("dW2", _f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off)),
+        "dW1": c8("dW1", _f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off)),
+        "dWs2": c8("dWs2", _f64(st.dWs2), oracle.grouped_gemm_tn(hin["dY"], _f64(st.As), o1)[0]),
+        "dWs1": c8("dWs1", _f64(st.dWs1), oracle.grouped_gemm_tn(_f64(st.dZs), hin["X"], o1)[0]),
     }
     e16 = {
-        "Y": rel_fro(_f64(st.Y), oracle.combine(_f64(st.O)[:R], m.row_of, prob, _f64(st.S))),
-        "dX": rel_fro(_f64(st.dX), oracle.combine(_f64(st.dXp)[:R], m.row_of, None, _f64(st.dXs))),
+        "Y": c16("Y", _f64(st.Y), oracle.combine(_f64(st.O)[:R], m.row_of, prob, _f64(st.S))),
+        "dX": c16("dX", _f64(st.dX), oracle.combine(_f64(st.dXp)[:R], m.row_of, None, _f64(st.dXs))),
     }
     print("mxfp8:", {k_: f"{v:.2e}" for k_, v in e8.items()}, "bf16:", {k_: f"{v:.2e}" for k_, v in e16.items()})
     for k_, v in e8.items():

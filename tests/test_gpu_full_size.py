@@ -1,12 +1,19 @@
-"""GPU parity at the full benchmark sizes (C2, C3, C4 and the degenerate C4 load patterns), in the
-launch configuration bench.py times.
+"""GPU parity at the full benchmark sizes (C2, C3, C4 and the degenerate C4 load patterns, the fp8 and
+MXFP8 configs), in the launch configuration bench.py times.
 
 Integer results (routing indices, counts, row maps, offsets) are compared in full and bit-exactly.
-Floating-point results are checked per library call on sampled outputs the oracle computes one by
-one from the same bf16 input bits: rows of every forward / data-gradient tensor for a handful of
-experts (first / last / largest / smallest / two more, rows at tile boundaries and the ragged
-tail), 64x64 windows of every weight gradient contracted over all rows of the expert, and sampled
-tokens of the combine and its backward.  Bound: relative Frobenius error <= 2e-2 on the sample.
+Floating-point results are checked per library call on sampled outputs the oracle computes one by one
+from the same bf16 input bits, per expert (nothing is pooled across experts):
+  * rows of every forward / data-gradient tensor for EVERY live expert: at least 64 rows each (all rows of a
+    smaller expert): both ends, the rows on either side of the first and last 256-row tile boundary, the
+    ragged tail, random rows; for the largest expert, in addition one row in every 256-row band;
+  * one 64x64 window of every weight gradient per expert, contracted over all rows of the expert; under the
+    skewed loads (one expert with 40 % of the rows, Zipf) eight more windows in distinct 256x256 output tiles
+    of the largest expert, whose tiles the kernel hands out dynamically;
+  * the shared expert's tensors, including its activation and both weight gradients;
+  * sampled tokens of the combine, its backward and the permute backward.
+Bounds: per tensor and expert the relative Frobenius error (2e-2 bf16, 6e-2 one-byte operands against full
+precision) and the same bound for every sampled row on its own.
 """
 import numpy as np
 import pytest
@@ -17,23 +24,31 @@ torch = pytest.importorskip("torch")
 
 CASES = [("C2", None), ("C3", None), ("C4", None), ("C4", "zeros"), ("C4", "hot"),
          ("C5", None), ("C5", "zeros"), ("C5", "hot"), ("C6", None), ("C6", "zeros"), ("C6", "hot"), ("C4G", None)]
+ROWS_PER_EXPERT = 64
 
 
 def _f64(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def _sample_rows(lo, hi, g, n=10):
-    """Rows of [lo, hi): both ends, the 256-row tile boundaries near them, and a few random ones."""
+def _sample_rows(lo, hi, g, n=ROWS_PER_EXPERT, every_band=False):
+    """At least n rows of [lo, hi) (all of them if there are fewer): both ends, both sides of the first and the
+    last 256-row tile boundary, the middle, random ones; every_band adds a random row in each 256-row band."""
     m = hi - lo
-    cand = {lo, hi - 1, lo + min(255, m - 1), lo + min(256, m - 1), lo + (m - 1) // 256 * 256, lo + m // 2}
-    cand |= {int(lo + v) for v in g.integers(0, m, size=n)}
+    if m <= n:
+        return np.arange(lo, hi, dtype=np.int64)
+    last = (m - 1) // 256 * 256
+    cand = {lo, hi - 1, lo + min(255, m - 1), lo + min(256, m - 1), lo + last, lo + max(last - 1, 0), lo + m // 2}
+    if every_band:
+        cand |= {int(lo + b + g.integers(0, min(256, m - b))) for b in range(0, m, 256)}
+    while len(cand) < n:
+        cand |= {int(lo + v) for v in g.integers(0, m, size=n)}
     return np.array(sorted(c for c in cand if lo <= c < hi), dtype=np.int64)
 
 
 @pytest.mark.parametrize("name,variant", CASES)
 def test_full_size_sampled(oracle, name, variant):
-    from gpu_util import rel_fro, BF16_TOL, FP8_TOL, permuted_rows, combine_bwd_rows
+    from gpu_util import assert_close, BF16_TOL, FP8_TOL, BF16_REG, permuted_rows, combine_bwd_rows
     from paper_2603_07685_amd import layer as L
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS[name]
@@ -67,22 +82,42 @@ def test_full_size_sampled(oracle, name, variant):
         assert m.counts.max() >= 0.39 * T * k
     off = m.offsets
 
-    # ---- per-expert sampled rows and weight-gradient windows ----
+    one_byte = bool(cfg.fp8 or cfg.mx)
+    # bounds per key: one-byte GEMM outputs against the full-precision oracle sit at the format's noise (3.6e-2 per
+    # GEMM, 5e-2 behind the SwiGLU), so their regression bound is the contract bound itself; a row on its own
+    # fluctuates around that figure by its 1/sqrt(columns), hence the wider row bound
+    gemm_fwd_keys = {"Z", "A", "O", "dZ", "dXp", "Zs", "As", "S", "dZs", "dXs"}
+    wgrad_keys = {"dW1", "dW2", "dWs1", "dWs2"}
+    # which weight gradients run on one-byte operands: MXFP8 always, the blockwise recipe where the layer says so
+    fp8_wgrad = bool(cfg.mx) or bool(getattr(st, "fp8_wgrad", False))
+
+    def bounds(key):
+        if one_byte and (key in gemm_fwd_keys or (key in wgrad_keys and fp8_wgrad)):
+            return dict(tol=FP8_TOL, reg=None, row_tol=3 * FP8_TOL)
+        return dict(tol=BF16_TOL, reg=BF16_REG, row_tol=BF16_TOL)
+
+    worst = {}
+
+    def chk(key, got, ref, tag, **kw):
+        b = bounds(key)
+        b.update(kw)
+        e = assert_close(got, ref, f"{key} [{tag}]", **b)
+        worst[key] = max(worst.get(key, 0.0), e)
+
+    # ---- per-expert sampled rows and weight-gradient windows: every live expert ----
     live = [e for e in range(E) if m.counts[e] > 0]
-    pick = {live[0], live[-1], max(live, key=lambda e: m.counts[e]), min(live, key=lambda e: m.counts[e])}
-    pick |= {int(e) for e in g.choice(live, size=min(2, len(live)), replace=False)}
-    errs = {}
-
-    def acc(key, got, ref):
-        num, den = errs.get(key, (0.0, 0.0))
-        errs[key] = (num + float(((got - ref) ** 2).sum()), den + float((ref ** 2).sum()))
-
+    biggest = max(live, key=lambda e: m.counts[e])
+    skewed = variant == "hot" or cfg.load == "zipf"
     one = lambda n: np.array([0, n], np.int32)
-    for e in sorted(pick):
+    n_rows_checked = 0
+    for e in live:
         lo, hi = int(off[e]), int(off[e]) + int(m.counts[e])
-        rows = _sample_rows(lo, hi, g)
+        rows = _sample_rows(lo, hi, g, every_band=(e == biggest))
+        assert len(rows) >= min(ROWS_PER_EXPERT, hi - lo)
+        n_rows_checked += len(rows)
         rt = torch.from_numpy(rows).cuda()
         n = len(rows)
+        tag = f"expert {e}"
         W1 = _f64(st.W1[e])[None]
         W2 = _f64(st.W2[e])[None]
         src_tok = m.src_of[rows] // k
@@ -93,47 +128,63 @@ def test_full_size_sampled(oracle, name, variant):
             qo, eo = oracle.mx_quant_1x32(Xrows)
             assert np.array_equal(st.qXp[rt].cpu().numpy(), qo) and np.array_equal(st.sXp[rt].cpu().numpy(), eo)
         Zref = oracle.grouped_gemm_nt(Xrows, W1, one(n))
-        acc("Z", _f64(st.Z[rt]), Zref)
-        acc("A", _f64(st.A[rt]), oracle.swiglu(Zref))
+        chk("Z", _f64(st.Z[rt]), Zref, tag)
+        chk("A", _f64(st.A[rt]), oracle.swiglu(Zref), tag)
         Ag = _f64(st.A[rt])
-        acc("O", _f64(st.O[rt]), oracle.grouped_gemm_nt(Ag, W2, one(n)))
+        chk("O", _f64(st.O[rt]), oracle.grouped_gemm_nt(Ag, W2, one(n)), tag)
         dOg, Zg = _f64(combine_bwd_rows(st, rt)), _f64(st.Z[rt])
         if st.dO is None:
             qo, eo = oracle.mx_quant_1x32(dOg)
             assert np.array_equal(st.qdO[rt].cpu().numpy(), qo) and np.array_equal(st.sdO[rt].cpu().numpy(), eo)
-        acc("dZ", _f64(st.dZ[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, one(n)), Zg))
-        acc("dXp", _f64(st.dXp[rt]), oracle.grouped_gemm_nn(_f64(st.dZ[rt]), W1, one(n)))
+        chk("dZ", _f64(st.dZ[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, one(n)), Zg), tag)
+        chk("dXp", _f64(st.dXp[rt]), oracle.grouped_gemm_nn(_f64(st.dZ[rt]), W1, one(n)), tag)
+        del W1, W2
         # weight-gradient windows, contracted over every row of the expert
-        n0, k0 = int(g.integers(0, h - 63)), int(g.integers(0, f - 63))
-        allr = torch.arange(lo, hi, device="cuda")
-        ref = oracle.grouped_gemm_tn(_f64(combine_bwd_rows(st, allr, slice(n0, n0 + 64))), _f64(st.A[lo:hi, k0:k0 + 64]),
-                                     one(hi - lo))[0]
-        acc("dW2", _f64(st.dW2[e, n0:n0 + 64, k0:k0 + 64]), ref)
-        n1, k1 = int(g.integers(0, 2 * f - 63)), int(g.integers(0, h - 63))
-        ref = oracle.grouped_gemm_tn(_f64(st.dZ[lo:hi, n1:n1 + 64]), _f64(permuted_rows(st, allr, slice(k1, k1 + 64))),
-                                     one(hi - lo))[0]
-        acc("dW1", _f64(st.dW1[e, n1:n1 + 64, k1:k1 + 64]), ref)
+        hi_pad = hi
+        allr = torch.arange(lo, hi_pad, device="cuda")
+        wins2 = [(int(g.integers(0, h - 63)), int(g.integers(0, f - 63)))]
+        wins1 = [(int(g.integers(0, 2 * f - 63)), int(g.integers(0, h - 63)))]
+        if skewed and e == biggest:   # eight more windows, each in a different 256 x 256 output tile
+            t2 = g.choice((h // 256) * (f // 256), size=8, replace=False)
+            wins2 += [(int(t // (f // 256)) * 256 + int(g.integers(0, 193)), int(t % (f // 256)) * 256 + int(g.integers(0, 193))) for t in t2]
+            t1 = g.choice((2 * f // 256) * (h // 256), size=8, replace=False)
+            wins1 += [(int(t // (h // 256)) * 256 + int(g.integers(0, 193)), int(t % (h // 256)) * 256 + int(g.integers(0, 193))) for t in t1]
+        for n0, k0 in wins2:
+            ref = oracle.grouped_gemm_tn(_f64(combine_bwd_rows(st, allr, slice(n0, n0 + 64))), _f64(st.A[lo:hi_pad, k0:k0 + 64]),
+                                         one(hi_pad - lo))[0]
+            chk("dW2", _f64(st.dW2[e, n0:n0 + 64, k0:k0 + 64]), ref, f"{tag}, window ({n0}, {k0})")
+        for n1, k1 in wins1:
+            ref = oracle.grouped_gemm_tn(_f64(st.dZ[lo:hi_pad, n1:n1 + 64]), _f64(permuted_rows(st, allr, slice(k1, k1 + 64))),
+                                         one(hi_pad - lo))[0]
+            chk("dW1", _f64(st.dW1[e, n1:n1 + 64, k1:k1 + 64]), ref, f"{tag}, window ({n1}, {k1})")
+    assert n_rows_checked >= min(ROWS_PER_EXPERT, int(m.counts[live].min())) * len(live)
     for e in range(E):                                                       # zero-token experts: exact zero gradients
         if m.counts[e] == 0:
             assert not st.dW1[e].any() and not st.dW2[e].any()
 
     # ---- shared expert (one group of T rows on the unpermuted tokens) ----
     if st.sf:
-        rows = _sample_rows(0, T, g)
+        sf = st.sf
+        rows = _sample_rows(0, T, g, every_band=True)
         rt = torch.from_numpy(rows).cuda()
         n = len(rows)
         Ws1, Ws2 = _f64(st.Ws1)[None], _f64(st.Ws2)[None]
         Zs = oracle.grouped_gemm_nt(_f64(st.X[rt]), Ws1, one(n))
-        acc("Zs", _f64(st.Zs[rt]), Zs)
-        acc("S", _f64(st.S[rt]), oracle.grouped_gemm_nt(_f64(st.As[rt]), Ws2, one(n)))
-        acc("dZs", _f64(st.dZs[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(_f64(st.dY[rt]), Ws2, one(n)), _f64(st.Zs[rt])))
-        acc("dXs", _f64(st.dXs[rt]), oracle.grouped_gemm_nn(_f64(st.dZs[rt]), Ws1, one(n)))
-        n0, k0 = int(g.integers(0, h - 63)), int(g.integers(0, st.sf - 63))
-        acc("dWs2", _f64(st.dWs2[n0:n0 + 64, k0:k0 + 64]),
-            oracle.grouped_gemm_tn(_f64(st.dY[:, n0:n0 + 64]), _f64(st.As[:, k0:k0 + 64]), one(T))[0])
+        chk("Zs", _f64(st.Zs[rt]), Zs, "shared")
+        chk("As", _f64(st.As[rt]), oracle.swiglu(Zs), "shared")
+        chk("S", _f64(st.S[rt]), oracle.grouped_gemm_nt(_f64(st.As[rt]), Ws2, one(n)), "shared")
+        chk("dZs", _f64(st.dZs[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(_f64(st.dY[rt]), Ws2, one(n)), _f64(st.Zs[rt])), "shared")
+        chk("dXs", _f64(st.dXs[rt]), oracle.grouped_gemm_nn(_f64(st.dZs[rt]), Ws1, one(n)), "shared")
+        for _ in range(2):
+            n0, k0 = int(g.integers(0, h - 63)), int(g.integers(0, sf - 63))
+            chk("dWs2", _f64(st.dWs2[n0:n0 + 64, k0:k0 + 64]),
+                oracle.grouped_gemm_tn(_f64(st.dY[:, n0:n0 + 64]), _f64(st.As[:, k0:k0 + 64]), one(T))[0], f"shared, window ({n0}, {k0})")
+            n1, k1 = int(g.integers(0, 2 * sf - 63)), int(g.integers(0, h - 63))
+            chk("dWs1", _f64(st.dWs1[n1:n1 + 64, k1:k1 + 64]),
+                oracle.grouped_gemm_tn(_f64(st.dZs[:, n1:n1 + 64]), _f64(st.X[:, k1:k1 + 64]), one(T))[0], f"shared, window ({n1}, {k1})")
 
     # ---- combine, its backward and the permute backward on sampled tokens ----
-    toks = np.unique(np.concatenate([[0, T - 1], g.integers(0, T, size=64)]))
+    toks = np.unique(np.concatenate([[0, T - 1], g.integers(0, T, size=256)]))
     tt = torch.from_numpy(toks).cuda()
     r_of = m.row_of[toks]                                                    # [n, k]
     flat = torch.from_numpy(r_of.reshape(-1).astype(np.int64)).cuda()
@@ -142,16 +193,16 @@ def test_full_size_sampled(oracle, name, variant):
     local_rows = np.arange(len(toks) * k, dtype=np.int32).reshape(len(toks), k)
     prob = st.topk_prob.cpu().numpy().astype(np.float64)[toks]
     S = _f64(st.S[tt]) if st.sf else None
-    acc("Y", _f64(st.Y[tt]), oracle.combine(Osub, local_rows, prob, S))
+    chk("Y", _f64(st.Y[tt]), oracle.combine(Osub, local_rows, prob, S), "tokens")
     dOref, dpref = oracle.combine_bwd(_f64(st.dY[tt]), Osub, local_rows, prob, len(toks) * k)
-    acc("dO", _f64(combine_bwd_rows(st, flat)), dOref)
-    acc("dprob", st.dprob.cpu().numpy().astype(np.float64)[toks], dpref)
-    acc("dX", _f64(st.dX[tt]), oracle.combine(dXpsub, local_rows, None, _f64(st.dXs[tt]) if st.sf else None))
+    if st.dO is not None:
+        chk("dO", _f64(st.dO[flat]), dOref, "tokens")
+    else:
+        # only the quantised copies of dO exist: dequantise what the GPU wrote (row-wise copy, one E8M0 scale per 32
+        # elements) and compare that with the oracle's dO, at the format's bound
+        deq = oracle.mx_dequant(st.qdO[flat].cpu().numpy(), st.sdO[flat].cpu().numpy(), "1x32")
+        chk("dO", deq, dOref, "tokens, dequantised codes", tol=FP8_TOL, reg=None, row_tol=FP8_TOL)
+    chk("dprob", st.dprob.cpu().numpy().astype(np.float64)[toks], dpref, "tokens", row_floor=0.05)
+    chk("dX", _f64(st.dX[tt]), oracle.combine(dXpsub, local_rows, None, _f64(st.dXs[tt]) if st.sf else None), "tokens")
 
-    rel = {k_: (np.sqrt(n_ / d_) if d_ > 0 else (0.0 if n_ == 0 else np.inf)) for k_, (n_, d_) in errs.items()}
-    print(name, variant, {k_: f"{v:.2e}" for k_, v in rel.items()})
-    fp8_keys = {"Z", "A", "O", "dZ", "dXp", "Zs", "S", "dZs", "dXs"} if (cfg.fp8 or cfg.mx) else set()
-    if cfg.mx:  # MXFP8 runs the weight gradients on one-byte operands too
-        fp8_keys |= {"dW1", "dW2", "dWs2"}
-    for k_, v in rel.items():
-        assert v <= (FP8_TOL if k_ in fp8_keys else BF16_TOL), (k_, v)
+    print(name, variant, f"{len(live)} experts, {n_rows_checked} rows;", {k_: f"{v:.2e}" for k_, v in worst.items()})

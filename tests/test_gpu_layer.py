@@ -16,9 +16,17 @@ def _oracle_route(oracle, cfg, logits):
     return oracle.route_topk(logits, cfg.k, cfg.score, cfg.norm_topk, cfg.route_scale)
 
 
+def _chain_reg(name):
+    """Regression bound of a tensor of the whole-layer run against the oracle's own chain: BF16_REG per rounded
+    stage between the inputs and the tensor (Z: 1; A, O, Y: up to 4; the backward tensors: up to 8)."""
+    from gpu_util import BF16_REG
+    depth = {"Z": 1, "A": 2, "O": 3, "S": 3, "Y": 4, "dO": 1, "dprob": 4, "dW2": 3}.get(name, 8)
+    return min(2e-2, BF16_REG * max(1, depth) ** 0.5 * 1.5)
+
+
 @pytest.mark.parametrize("name,shared_f", [("C1", 0), ("C1", 64), ("MID", 0), ("C7S", None)])
 def test_layer_forward_backward_every_element(oracle, name, shared_f):
-    from gpu_util import host_f64, rel_fro, BF16_TOL
+    from gpu_util import host_f64, assert_close
     from paper_2603_07685_amd import workloads as wl
     from paper_2603_07685_amd import layer as L
     cfg = wl.CONFIGS[name]
@@ -45,31 +53,26 @@ def test_layer_forward_backward_every_element(oracle, name, shared_f):
     assert np.array_equal(st.counts.cpu().numpy(), m.counts)
     R = fw.R
     assert np.array_equal(host_f64(st.Xp)[:R], fw.Xp)
-    errs = {
-        "Z": rel_fro(host_f64(st.Z)[:R], fw.Z), "A": rel_fro(host_f64(st.A)[:R], fw.A),
-        "O": rel_fro(host_f64(st.O)[:R], fw.O), "Y": rel_fro(host_f64(st.Y), fw.Y),
-    }
     bw = oracle.layer_backward(fw, hin["X"], o_prob, hin["W1"], hin["W2"], hin["dY"], hin.get("Ws1"), hin.get("Ws2"))
-    errs.update({
-        "dO": rel_fro(host_f64(st.dO)[:R], bw.dO), "dprob": rel_fro(host_f64(st.dprob), bw.dprob),
-        "dW2": rel_fro(host_f64(st.dW2), bw.dW2), "dZ": rel_fro(host_f64(st.dZ)[:R], bw.dZ),
-        "dW1": rel_fro(host_f64(st.dW1), bw.dW1), "dXp": rel_fro(host_f64(st.dXp)[:R], bw.dXp),
-        "dX": rel_fro(host_f64(st.dX), bw.dX + (bw.dX_shared if shared_f else 0.0)),
-    })
+    pairs = [("Z", st.Z[:R], fw.Z), ("A", st.A[:R], fw.A), ("O", st.O[:R], fw.O), ("Y", st.Y, fw.Y),
+             ("dO", st.dO[:R], bw.dO), ("dprob", st.dprob, bw.dprob), ("dW2", st.dW2, bw.dW2), ("dZ", st.dZ[:R], bw.dZ),
+             ("dW1", st.dW1, bw.dW1), ("dXp", st.dXp[:R], bw.dXp),
+             ("dX", st.dX, bw.dX + (bw.dX_shared if shared_f else 0.0))]
     if shared_f:
-        errs.update({"S": rel_fro(host_f64(st.S), fw.S), "dWs1": rel_fro(host_f64(st.dWs1), bw.dWs1),
-                     "dWs2": rel_fro(host_f64(st.dWs2), bw.dWs2),
-                     "dX_shared": rel_fro(host_f64(st.dXs), bw.dX_shared)})
+        pairs += [("S", st.S, fw.S), ("dWs1", st.dWs1, bw.dWs1), ("dWs2", st.dWs2, bw.dWs2), ("dX_shared", st.dXs, bw.dX_shared)]
+    # every tensor: pooled bound (contract 2e-2, regression 6e-3 x the depth of the chain behind it) and every row on
+    # its own; errors accumulate along the chain (each stage consumes the rounded output of the one before), so the
+    # regression bound of the later tensors is a multiple of the single-call figure
+    errs = {n_: assert_close(host_f64(g_), r_, n_, reg=_chain_reg(n_), row_floor=0.05 if n_ == "dprob" else 1e-6)
+            for n_, g_, r_ in pairs}
     print(name, {k: f"{v:.2e}" for k, v in errs.items()})
-    for k, v in errs.items():
-        assert v <= BF16_TOL, (k, v)
 
 
 @pytest.mark.parametrize("name,shared_f", [("C1", 64), ("MID", 0)])
 def test_layer_eq2_every_element(oracle, name, shared_f):
     """The memory-efficient permutation variant (Sec. 4.1.2, eq. (2)) of the whole layer, every element:
     weights applied in the fc1 epilogue, plain-sum combine, dprob from the fused fc2 data gradient."""
-    from gpu_util import host_f64, rel_fro, BF16_TOL
+    from gpu_util import host_f64, assert_close
     from paper_2603_07685_amd import workloads as wl
     from paper_2603_07685_amd import layer as L
     cfg = wl.CONFIGS[name]
@@ -87,25 +90,21 @@ def test_layer_eq2_every_element(oracle, name, shared_f):
     R = fw.R
     assert np.array_equal(st.row_of.cpu().numpy(), fw.maps.row_of)
     np.testing.assert_allclose(st.row_prob.cpu().numpy()[:R], fw.row_prob, rtol=2e-6)
-    errs = {
-        "Z": rel_fro(host_f64(st.Z)[:R], fw.Z), "A": rel_fro(host_f64(st.A)[:R], fw.A),
-        "O": rel_fro(host_f64(st.O)[:R], fw.O), "Y": rel_fro(host_f64(st.Y), fw.Y),
-        "dO": rel_fro(host_f64(st.dO)[:R], bw.dO), "dprob": rel_fro(host_f64(st.dprob), bw.dprob),
-        "dW2": rel_fro(host_f64(st.dW2), bw.dW2), "dZ": rel_fro(host_f64(st.dZ)[:R], bw.dZ),
-        "dW1": rel_fro(host_f64(st.dW1), bw.dW1), "dXp": rel_fro(host_f64(st.dXp)[:R], bw.dXp),
-        "dX": rel_fro(host_f64(st.dX), bw.dX + (bw.dX_shared if shared_f else 0.0)),
-    }
+    pairs = [("Z", st.Z[:R], fw.Z), ("A", st.A[:R], fw.A), ("O", st.O[:R], fw.O), ("Y", st.Y, fw.Y),
+             ("dO", st.dO[:R], bw.dO), ("dprob", st.dprob, bw.dprob), ("dW2", st.dW2, bw.dW2), ("dZ", st.dZ[:R], bw.dZ),
+             ("dW1", st.dW1, bw.dW1), ("dXp", st.dXp[:R], bw.dXp),
+             ("dX", st.dX, bw.dX + (bw.dX_shared if shared_f else 0.0))]
+    errs = {n_: assert_close(host_f64(g_), r_, n_, reg=_chain_reg(n_), row_floor=0.05 if n_ == "dprob" else 1e-6)
+            for n_, g_, r_ in pairs}
     assert np.array_equal(host_f64(st.dO)[:R], bw.dO)      # plain copies of dY
     print(name, "eq2", {k: f"{v:.2e}" for k, v in errs.items()})
-    for k, v in errs.items():
-        assert v <= BF16_TOL, (k, v)
 
 
 @pytest.mark.parametrize("name,shared_f", [("C1", 0), ("C1", 64), ("MID", 0)])
 def test_layer_all_fp32_every_element(oracle, name, shared_f):
     """The tiny config is generated in fp32: the whole layer with fp32 tensors and the fp32 GEMM path (dt = MOE_F32)
     against the fp64 oracle at the 1e-5 level, every element of every tensor."""
-    from gpu_util import host_f64, rel_fro
+    from gpu_util import host_f64, assert_close
     from paper_2603_07685_amd import workloads as wl
     from paper_2603_07685_amd import layer as L
     TOL = 1e-5
@@ -123,17 +122,12 @@ def test_layer_all_fp32_every_element(oracle, name, shared_f):
     R = fw.R
     assert np.array_equal(st.row_of.cpu().numpy(), fw.maps.row_of)
     assert np.array_equal(host_f64(st.Xp)[:R], fw.Xp)
-    errs = {
-        "Z": rel_fro(host_f64(st.Z)[:R], fw.Z), "A": rel_fro(host_f64(st.A)[:R], fw.A),
-        "O": rel_fro(host_f64(st.O)[:R], fw.O), "Y": rel_fro(host_f64(st.Y), fw.Y),
-        "dO": rel_fro(host_f64(st.dO)[:R], bw.dO), "dprob": rel_fro(host_f64(st.dprob), bw.dprob),
-        "dW2": rel_fro(host_f64(st.dW2), bw.dW2), "dZ": rel_fro(host_f64(st.dZ)[:R], bw.dZ),
-        "dW1": rel_fro(host_f64(st.dW1), bw.dW1), "dXp": rel_fro(host_f64(st.dXp)[:R], bw.dXp),
-        "dX": rel_fro(host_f64(st.dX), bw.dX + (bw.dX_shared if shared_f else 0.0)),
-    }
+    pairs = [("Z", st.Z[:R], fw.Z), ("A", st.A[:R], fw.A), ("O", st.O[:R], fw.O), ("Y", st.Y, fw.Y),
+             ("dO", st.dO[:R], bw.dO), ("dprob", st.dprob, bw.dprob), ("dW2", st.dW2, bw.dW2), ("dZ", st.dZ[:R], bw.dZ),
+             ("dW1", st.dW1, bw.dW1), ("dXp", st.dXp[:R], bw.dXp),
+             ("dX", st.dX, bw.dX + (bw.dX_shared if shared_f else 0.0))]
     if shared_f:
-        errs.update({"S": rel_fro(host_f64(st.S), fw.S), "dWs1": rel_fro(host_f64(st.dWs1), bw.dWs1),
-                     "dWs2": rel_fro(host_f64(st.dWs2), bw.dWs2)})
+        pairs += [("S", st.S, fw.S), ("dWs1", st.dWs1, bw.dWs1), ("dWs2", st.dWs2, bw.dWs2)]
+    errs = {n_: assert_close(host_f64(g_), r_, n_, tol=TOL, reg=None, row_tol=1e-4, row_floor=1e-4 if n_ == "dprob" else 1e-6)
+            for n_, g_, r_ in pairs}
     print(name, "fp32", {k: f"{v:.2e}" for k, v in errs.items()})
-    for k, v in errs.items():
-        assert v <= TOL, (k, v)

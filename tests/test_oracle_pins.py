@@ -624,6 +624,60 @@ def test_fp8_block_quantisers(oracle):
     assert np.array_equal(qt.T, qc) and np.array_equal(st.T, sc)
 
 
+def test_fp8_blockwise_wgrad_emulation(oracle):
+    """The quantise-dequantise emulation of the blockwise weight gradient (Sec. 5.3.2 with the 1x128 tiles running
+    down the token dimension, Sec. 5.4.1): both operands quantised 128x1 inside an expert's 128-aligned row range,
+    dequantised, then dW_e = dC_e^T A_e.  Pinned three ways: exact when the quantisation is exact; equal to the
+    block-scaled form sum_b (s_dC[b, n] s_A[b, k]) (codes_dC_b^T codes_A_b) evaluated with numpy from the decoded
+    codes (a wrong scale index, a transposed operand or a block that straddles experts breaks the equality); and
+    within the format's error of the full-precision gradient."""
+    g = _rng(21)
+    counts = np.array([256, 0, 128, 384])
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R, N, K = int(off[-1]), 12, 20
+    vals = np.array([oracle.e4m3_decode(c) for c in range(256)])
+    finite = vals[np.isfinite(vals)]
+    # (a) exactly representable operands: codes times a power-of-two scale per (128-row block, column); every block
+    #     holds +-448, so amax / 448 is that power of two and the quantisation is the identity
+    def exact(cols, seed):
+        gg = _rng(seed)
+        v = gg.choice(finite, size=(R, cols))
+        v[::128] = 448.0 * gg.choice([-1.0, 1.0], size=(R // 128, cols))
+        sc = 2.0 ** gg.integers(-12, 5, size=(R // 128, cols))
+        return (v * np.repeat(sc, 128, axis=0)).astype(np.float32), sc
+    dC, sdc = exact(N, 1)
+    A, sa = exact(K, 2)
+    qd, sd = oracle.fp8_quant_128x1(dC)
+    qa, sA = oracle.fp8_quant_128x1(A)
+    np.testing.assert_array_equal(sd, sdc.astype(np.float32))
+    np.testing.assert_array_equal(sA, sa.astype(np.float32))
+    Dd, Ad = oracle.fp8_dequant(qd, sd, "128x1"), oracle.fp8_dequant(qa, sA, "128x1")
+    np.testing.assert_array_equal(Dd, dC.astype(np.float64))
+    emu = oracle.grouped_gemm_tn(Dd, Ad, off)
+    full = oracle.grouped_gemm_tn(dC, A, off)
+    np.testing.assert_allclose(emu, full, rtol=1e-13, atol=0)
+    assert not emu[1].any()                                            # the empty expert
+    # (b) Gaussian operands with a different magnitude per row block: the block-scaled form, written with numpy
+    mag = np.exp(g.uniform(-4, 4, (R // 128, 1)))
+    dC = (g.standard_normal((R, N)) * np.repeat(mag, 128, axis=0)).astype(np.float32)
+    A = (g.standard_normal((R, K)) * np.repeat(mag[::-1], 128, axis=0)).astype(np.float32)
+    dC[128:256] = 0.0                                                   # a block of zero rows (padding): scale 1, codes 0
+    qd, sd = oracle.fp8_quant_128x1(dC)
+    qa, sA = oracle.fp8_quant_128x1(A)
+    assert np.all(sd[1] == 1.0) and not qd[128:256].any()
+    emu = oracle.grouped_gemm_tn(oracle.fp8_dequant(qd, sd, "128x1"), oracle.fp8_dequant(qa, sA, "128x1"), off)
+    ref = np.zeros_like(emu)
+    for e in range(len(counts)):
+        for b in range(off[e] // 128, off[e + 1] // 128):
+            cd, ca = vals[qd[128 * b:128 * b + 128]], vals[qa[128 * b:128 * b + 128]]
+            ref[e] += np.outer(sd[b].astype(np.float64), sA[b].astype(np.float64)) * (cd.T @ ca)
+    np.testing.assert_allclose(emu, ref, rtol=1e-12, atol=1e-300)
+    # (c) against full precision: two quantised operands, each within 2^-4 per element
+    full = oracle.grouped_gemm_tn(dC, A, off)
+    err = np.linalg.norm(emu - full) / np.linalg.norm(full)
+    assert 5e-3 < err < 6e-2, err
+
+
 def test_mxfp8_quantisers(oracle):
     """MXFP8 (Sec. 5.3.3): E8M0 scale = smallest power of two that brings the block maximum inside +-448;
     1x32 blocks along the row (and along N for the column-wise weight copy)."""
@@ -678,3 +732,33 @@ def test_mxfp8_quantisers(oracle):
         assert np.array_equal(qc[gi], qt.T) and np.array_equal(ec[gi], et)
     np.testing.assert_array_equal(oracle.mx_dequant(qc, ec, "32x1")[1],
                                   oracle.mx_dequant(*oracle.mx_quant_1x32(np.ascontiguousarray(W[1].T)), "1x32").T)
+
+
+def test_assert_close_catches_a_wrong_row_that_a_pooled_norm_hides():
+    """The helper the GPU parity tests use: a single wrong row (or a row that lost half its contraction) in a tensor of
+    thousands passes a pooled 2e-2 Frobenius bound and must fail the per-row bound; the mistake is planted in a copy
+    of a reference, on the CPU."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from gpu_util import assert_close, rel_fro, BF16_TOL
+    g = np.random.default_rng(7)
+    A = g.standard_normal((8192, 256))
+    B = g.standard_normal((256, 256))
+    ref = A @ B.T
+    good = ref * (1.0 + 2e-3 * g.standard_normal(ref.shape))          # bf16-like rounding noise
+    assert_close(good, ref, "good")
+    half = good.copy()
+    half[1234] = A[1234, :128] @ B[:, :128].T                            # one row with half its contraction
+    assert rel_fro(half, ref) <= BF16_TOL                                # the pooled norm does not see it
+    with pytest.raises(AssertionError, match="rows above the per-row bound"):
+        assert_close(half, ref, "half a row", reg=None)
+    wrong = good.copy()
+    wrong[7] = good[8]                                                   # one row swapped for its neighbour
+    assert rel_fro(wrong, ref) <= BF16_TOL
+    with pytest.raises(AssertionError, match="rows above the per-row bound"):
+        assert_close(wrong, ref, "wrong row", reg=None)
+    drift = ref * (1.0 + 8e-3 * g.standard_normal(ref.shape))           # everywhere worse, still inside the contract
+    with pytest.raises(AssertionError, match="regression bound"):
+        assert_close(drift, ref, "drift")
+    z = np.zeros((4, 8))
+    assert_close(z, z, "zeros")                                          # empty experts: exact zeros pass
