@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--wgrad-f32", action="store_true", help="fp32 weight gradients (default bf16)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in a HIP graph and report the time of its replays (field 'graph')")
+    ap.add_argument("--bf16-wgrad", action="store_true",
+                    help="blockwise fp8 workloads: weight gradients from the bf16 tensors instead of the 128x1 E4M3 copies")
     ap.add_argument("--eq2", action="store_true",
                     help="memory-efficient permutation: routing weights applied in the fc1 epilogue, plain-sum combine")
     return ap.parse_args()
@@ -247,7 +249,8 @@ def main():
     cfg = wl.CONFIGS[args.workload]
     small = cfg.T * cfg.h <= 4 * 1024 * 1024
     hin = L.host_inputs(cfg) if small else None
-    st = L.LayerState(cfg, hin, variant=args.variant, wgrad_f32=args.wgrad_f32, eq2=args.eq2)
+    st = L.LayerState(cfg, hin, variant=args.variant, wgrad_f32=args.wgrad_f32, eq2=args.eq2,
+                      fp8_wgrad=False if args.bf16_wgrad else None)
 
     # one plain device copy of known size, outside the timed region: the reference dispatch the HBM byte
     # counters (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by
@@ -312,6 +315,7 @@ def main():
         "ms_per_step": round(ms, 4), "wall_ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("mxfp8_e4m3 (fwd/dgrad/wgrad GEMMs) + bf16 moves" if cfg.mx else
+                  "fp8_e4m3 (fwd/dgrad/wgrad GEMMs) + bf16 moves" if cfg.fp8 and st.fp8_wgrad else
                   "fp8_e4m3 (fwd/dgrad GEMMs) + bf16 (wgrad, moves)" if cfg.fp8 else "bf16"), "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} h={cfg.h} f={cfg.f} E_local={cfg.E} top{cfg.k} "
                                f"shared_f={cfg.shared_f} load={args.variant or cfg.load} "

@@ -227,9 +227,8 @@ moe_status moe_permute_static(void* stream, const void* X, moe_dtype dt,
  * return MOE_ERR_UNSUPPORTED and touch nothing.  dt = MOE_F32: every operand and result is fp32
  * (fp32 accumulation in increasing contraction index; wgrad needs out_dt = MOE_F32; any N, K >= 1);
  * a plain one-thread-per-output path for parity runs at the 1e-5 level on small layers, not tuned.
- * wgrad with dt = MOE_FP8_E4M3 is
- * not built and returns MOE_ERR_UNSUPPORTED.  dt = MOE_MXFP8_E4M3 (Sec. 5.3.3) is
- * described with moe_mx_quantize below; all three calls take it.
+ * dt = MOE_MXFP8_E4M3 (Sec. 5.3.3) is described with moe_mx_quantize below; all three calls take
+ * both one-byte types.
  *
  * fwd:   C[r,n] = sum_k A[r,k] * B[e(r),n,k]                    A [Rcap,K], C [Rcap,N]
  *        epi = MOE_EPI_SWIGLU (N = 2f): C holds the pre-activation Z = [gate | up]
@@ -263,9 +262,14 @@ moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const void* dC, co
  *        Under a skewed load the tiles are handed out through a counter in the context's
  *        reserved workspace (results are unaffected): wgrad calls on one context must not
  *        overlap in time.
- *        MXFP8: both operands are quantised in 32x1 blocks down the token dimension
- *        (see moe_mx_quantize); every offsets[e] must then be a multiple of 128
- *        (moe_permute with align = 128).  Blockwise fp8 is not built for this call.
+ *        One-byte operands are quantised down the token dimension, the contraction of this call
+ *        (Sec. 5.4.1): blockwise fp8 in 128x1 tiles (moe_fp8_quantize, MOE_Q_128x1),
+ *        a_scale [Rcap/128, K], dc_scale [Rcap/128, N] fp32; MXFP8 in 32x1 blocks (see
+ *        moe_mx_quantize).  A scale block must not straddle two experts: every offsets[e] must be a
+ *        multiple of 128 (moe_permute with align = 128), otherwise the error word is raised and dB is
+ *        left untouched.  Blockwise: the block scales of one operand row / column may differ from one
+ *        128-row block to the next by up to 2^100 (the accumulators are carried in units of the current
+ *        block's scales).
  */
 moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, const void* dC,
                                   const int32_t* offsets, int E, int N, int K, int64_t Rcap,

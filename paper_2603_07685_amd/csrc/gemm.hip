@@ -228,7 +228,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // fp8: the block scales of a stage travel with it, behind the P tile: 256 row scales (position
     // 4 * (row % 32) + row / 32 inside each 128-row half, so a lane finds its four rows in one 16-byte
     // read) and, from position 256 on, the two column-block scales (replicated)
-    constexpr int SC_BYTES = FP8 ? 2048 : 0;
+    // (blockwise weight gradient: both operands carry one scale per tile row / column and stage, and the rescaling
+    // needs the previous stage's too: 256 + 256 current, then 256 + 256 previous)
+    constexpr bool BW_WGRAD = F8 == 1 && MODE == GG_WGRAD;
+    constexpr int SC_BYTES = FP8 ? (BW_WGRAD ? 4096 : 2048) : 0;
     // One LDS array: [P0 | scales0 | Q0 | P1 | scales1 | Q1 | pad].  Buffer 1 (from P1 on) doubles as the
     // staging area of the epilogue: 64 tile rows x 260 floats.
     constexpr int BUF_BYTES = 2 * GG_STAGE_BYTES + SC_BYTES;
@@ -244,7 +247,6 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     __shared__ int tile_start[GG_MAX_E + 1];
     __shared__ int dyn_next;
 
-    static_assert(!(F8 == 1 && MODE == GG_WGRAD), "blockwise fp8 weight gradients are not built");
     constexpr bool P_CMAJ = (MODE == GG_WGRAD);
     constexpr bool Q_CMAJ = (MODE != GG_FWD);
     constexpr int ES = FP8 ? 1 : 2;            // operand element size
@@ -296,7 +298,8 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             const int rows = offs[e + 1] - offs[e];
             bad |= rows < 0;
             // MXFP8 wgrad: a 32-row scale block (and the 128-row stage) must not straddle two experts
-            if (MX && MODE == GG_WGRAD) bad |= (rows & 127) != 0 || (offs[e] & 127) != 0;
+            // (the same for the 128-row scale blocks of the blockwise recipe)
+            if (FP8 && MODE == GG_WGRAD) bad |= (rows & 127) != 0 || (offs[e] & 127) != 0;
             if (MODE == GG_WGRAD) run += tiles_i_w * tiles_j;
             else run += rows > 0 ? ((rows + GG_BM - 1) / GG_BM) * tiles_j : 0;
         }
@@ -319,7 +322,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // k-major tile: a 1 KB chunk = 8 rows x 128 B; lane -> (row l/8, slot l%8), slot ^= KM_SWZ(row)
     const int km_row = lane >> 3;
     // c-major tile: a 1 KB chunk = CM_ROWS rows; lane -> (row l / CM_SLOTS, slot l % CM_SLOTS)
-    //   bf16: slot ^= 4 * (row % 4);  fp8: slot ^= 2 * (row % 8)
+    //   bf16: slot ^= 4 * (row % 4) (four waves: and ^= 2 * (row / 16 % 2));  fp8: slot ^= 2 * (row % 8)
     const int cm_row = lane / CM_SLOTS;
     // ---- per-lane constants: fragment side ----
     const int fr_row = lane & 31;
@@ -345,18 +348,25 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // four waves: 16 x 16 blocks.  Row-major: lane -> (row l % 16, 16-byte slot l / 16 of the step's 64 bytes), one
     // slot offset per step (the swizzle depends on l % 16 only).  Contraction-major: lane group l / 16 covers the
     // contraction rows 8 (l / 16) .. + 7 of a step in two transposing reads of 4 rows.
+    // Which 8 of the 32 contraction elements of a step a lane group holds is free as long as both operands agree.
+    // With a contraction-major operand in play, group g takes the rows 16 (g % 2) + 8 (g / 2) .. + 7: the two groups
+    // that the LDS serves in one pass (lanes 0..31, then 32..63) then differ in bit 4 of the row, which the swizzle
+    // of these tiles turns into a different 32-byte half of a 64-byte bank segment (without it both groups of a pass
+    // read the same banks: SQ_LDS_BANK_CONFLICT was a third of the LDS cycles of the weight gradient).
     int p4[8], q4[8], km4[2];
     if (NW == 4) {
         const int l16 = lane & 15, kq = lane >> 4;
-        km4[0] = ((kq) ^ KM_SWZ(l16)) * 16;
-        km4[1] = ((4 + kq) ^ KM_SWZ(l16)) * 16;
-        const int cm_off = (8 * kq + (l16 >> 2)) * 512 + (l16 & 1) * 8;
+        const int kperm = Q_CMAJ ? 2 * (kq & 1) + (kq >> 1) : kq;
+        km4[0] = ((kperm) ^ KM_SWZ(l16)) * 16;
+        km4[1] = ((4 + kperm) ^ KM_SWZ(l16)) * 16;
+        const int cm_off = (8 * kperm + (l16 >> 2)) * 512 + (l16 & 1) * 8;
+        const int cm_xor = tr_xor ^ (2 * (kq & 1));   // bit 4 of the row = kq & 1
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int prow = wm * 128 + 16 * i;                             // tile row of P block i
             const int qrow = (i / 4) * 128 + wn * 64 + (i % 4) * 16;        // tile column of Q block i
-            p4[i] = P_CMAJ ? cm_off + (((prow / 8) ^ tr_xor) + ((l16 & 3) >> 1)) * 16 : (prow + l16) * GG_ROWB;
-            q4[i] = Q_CMAJ ? cm_off + (((qrow / 8) ^ tr_xor) + ((l16 & 3) >> 1)) * 16 : (qrow + l16) * GG_ROWB;
+            p4[i] = P_CMAJ ? cm_off + (((prow / 8) ^ cm_xor) + ((l16 & 3) >> 1)) * 16 : (prow + l16) * GG_ROWB;
+            q4[i] = Q_CMAJ ? cm_off + (((qrow / 8) ^ cm_xor) + ((l16 & 3) >> 1)) * 16 : (qrow + l16) * GG_ROWB;
         }
     }
     int p_rd[4], q_rd[NJ];
@@ -437,7 +447,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
 #pragma unroll
             for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
                 const int row = (wave * CH + i) * CM_ROWS + cm_row;
-                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
+                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3) ^ (NW == 4 ? 2 * ((row >> 4) & 1) : 0));
                 int col = i0 + slot * EPS;
                 col = col <= N - EPS ? col : N - EPS;
                 if (NW == 4) po2[i] = (uint32_t)((row * N + col) * ES);
@@ -466,7 +476,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
 #pragma unroll
             for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
                 const int row = (wave * CH + i) * CM_ROWS + cm_row;
-                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3));
+                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3) ^ (NW == 4 ? 2 * ((row >> 4) & 1) : 0));
                 int col = (slot < CM_SLOTS / 2 ? j0 : j1 - 128) + slot * EPS;
                 col = col <= K - EPS ? col : K - EPS;
                 if (NW == 4) qo2[i] = (uint32_t)((row * K + col) * ES);
@@ -539,6 +549,24 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     sc_step = K;
                 }
             }
+        } else if (BW_WGRAD) {
+            // 128x1 scales of both operands: [c / 128, columns] floats, one row of them per stage.  Waves 0..3 fetch the
+            // 256 scales of the tile's rows (= columns n of dC; position layout as in the forward kernel: a lane finds
+            // its four rows in one 16-byte read), waves 4..7 the 256 of the tile's columns (= columns k of A), in
+            // tile-column order.
+            if (wave < 4) {
+                const int pp = wave * 64 + lane;
+                int64_t r = (int64_t)i0 + (pp >> 7) * 128 + (pp & 3) * 32 + ((pp & 127) >> 2);
+                r = r < N ? r : N - 1;
+                sc_src = a.p_scale + (int64_t)(c_lo >> 7) * N + r;
+                sc_step = N;
+            } else {
+                const int c = (wave - 4) * 64 + lane;
+                int col = (c < 128 ? j0 : j1 - 128) + c;
+                col = col < K ? col : K - 1;
+                sc_src = a.q_scale + (int64_t)(c_lo >> 7) * K + col;
+                sc_step = K;
+            }
         } else if (FP8) {
             if (wave < 4) {  // row scales: LDS position p = 64 wave + lane holds tile row ...
                 const int pp = wave * 64 + lane;
@@ -566,7 +594,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             const uint32_t off = (idx & 1) ? qo[i] : po[i];
             const char* base = (idx & 1) ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
             const uint32_t dst_wave = wave * (CH * 1024), dst_const = lds_addr((idx & 1) ? sq : sp) + i * 1024;
-            if (MODE == GG_WGRAD && !MX) {  // contraction tail of the expert: feed zeros
+            if (MODE == GG_WGRAD && !FP8) {  // contraction tail of the expert: feed zeros (one-byte operands: whole stages only)
                 const int row = c_lo + kt * BKE + (wave * CH + i) * CM_ROWS + cm_row;
                 uint32_t o = off;
                 asm volatile("" : "+v"(o));  // opaque: keeps base + offset from being hoisted as 64-bit lane pointers
@@ -577,6 +605,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         };
 
         auto issue_scales = [&](int kb, float* ss) {
+            if (BW_WGRAD) {  // this stage's scales and, behind them, the previous stage's (stage 0: its own, ratio 1)
+                dma4(sc_src + kb * sc_step, wave * 256, lds_addr(ss));
+                dma4(sc_src + (kb > 0 ? kb - 1 : 0) * sc_step, wave * 256, lds_addr(ss) + 2048);
+                return;
+            }
             if (MX || wave <= 4) {
                 const float* src = sc_src + kb * sc_step;
                 dma4(src, wave * 256, lds_addr(ss));
@@ -851,6 +884,51 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 }
             };
 
+            // Blockwise weight gradient: the factor of an accumulator is a product, s = sP[n] * sQ[k] (128x1 scales of
+            // dC and A for this stage's 128 rows), different for every element of a block, so every element gets its
+            // own ratio s(kb-1) / s(kb) = rP[row] * rQ[column]: per lane 4 row ratios and 2 x 16 column ratios, formed
+            // from the current and previous scales in LDS, four columns at a time (no scale stays in registers).
+            // Two multiplies per accumulator and stage: the plain-ALU price of a scale that changes along the
+            // contraction on both operands.
+            auto scale_cols = [&](const float* ss, bool ratio, const float (&rp)[4]) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int c = 256 + blk_col(j) + 8 * g + 4 * fr_khalf;
+                        const f32x4_t qn4 = *(const f32x4_t*)(ss + c);
+                        f32x4_t q4 = qn4;
+                        if (ratio) {
+                            const f32x4_t qp4 = *(const f32x4_t*)(ss + 512 + c);
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) q4[x] = qp4[x] * __builtin_amdgcn_rcpf(qn4[x]);
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) acc[i][j][4 * g + x] *= rp[i] * q4[x];
+                        }
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    pin(acc[i][0]);
+                    pin(acc[i][1]);
+                }
+            };
+            auto rescale_w = [&](const float* ss) {
+                const f32x4_t pn4 = *(const f32x4_t*)(ss + wm * 128 + fr_row * 4);
+                const f32x4_t pp4 = *(const f32x4_t*)(ss + 512 + wm * 128 + fr_row * 4);
+                float rp[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rp[i] = pp4[i] * __builtin_amdgcn_rcpf(pn4[i]);
+                scale_cols(ss, true, rp);
+            };
+            auto final_scale_w = [&](const float* ss) {  // out of the last stage's units
+                const f32x4_t pn4 = *(const f32x4_t*)(ss + wm * 128 + fr_row * 4);
+                const float rp[4] = {pn4[0], pn4[1], pn4[2], pn4[3]};
+                scale_cols(ss, false, rp);
+            };
+
             // The two wave groups (wm = 0 / 1) run the same stages one slot apart: while one group issues
             // MFMAs the other reads fragments.  Each group has its own copy of the loop, so that every wait
             // is unconditional inside it (the compiler's own wait insertion then sees exactly which DMA is
@@ -864,13 +942,14 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             // group 0 issues its share of stage j+1 at the start of A(j,0), group 1 during B(j-1,1), both in
             // slot 1, and both wait for their share in slot 4.
             auto half_a = [&](int s, int half) {
-                if (FP8 && half == 0) {
+                if (FP8 && !BW_WGRAD && half == 0) {
                     read_scales(SS[s]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 fetch(SP[s], SQ[s], half);
                 __builtin_amdgcn_sched_barrier(0);
-                if (FP8 && !MX && half == 0) rescale();  // after the fragment reads in program order: overlaps them
+                if (BW_WGRAD && half == 0) rescale_w(SS[s]);
+                else if (FP8 && !MX && half == 0) rescale();  // after the fragment reads in program order: overlaps them
                 wait_lgkm0();
             };
             if (NW == 4) {
@@ -1034,6 +1113,13 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     stage1(j + 1, 1);
                 }
             }
+            if (BW_WGRAD) {
+                // the accumulators are in units of the last stage's scales, which sit in that stage's buffer until the
+                // next tile's first stage is issued: convert now, and let every wave finish before anyone issues
+                if (KT > 0) final_scale_w((const float*)(lds_buf + ((KT - 1) & 1) * BUF_BYTES + GG_STAGE_BYTES));
+                wait_lgkm0();
+                stage_barrier();
+            }
         }
 
         // ---- next tile: set it up and start its first stage, then write this tile out ----
@@ -1096,7 +1182,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
                         v[x] = acc[i][h2][4 * g + x];
-                        if (FP8 && !MX) v[x] *= ps_cur[i] * qs_cur[h2];
+                        if (FP8 && !MX && !BW_WGRAD) v[x] *= ps_cur[i] * qs_cur[h2];
                     }
                     *(f32x4_t*)(stg + (wm * 32 + fr_row) * STG_PITCH + blk_col(h2) + 8 * g + 4 * fr_khalf) = v;
                 }
@@ -1459,10 +1545,8 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     }
     moe_status st = gg_check_common(ctx, "moe_grouped_gemm_wgrad", dC, A, offsets, E, N, K, Rcap, dt);
     if (st != MOE_OK) return st;
-    if (dt == MOE_FP8_E4M3)
-        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wgrad: blockwise fp8 operands are not built; pass the bf16 tensors");
-    const bool mx = dt == MOE_MXFP8_E4M3;
-    if (mx && (!a_scale || !dc_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: MXFP8 needs a_scale and dc_scale");
+    const bool mx = dt == MOE_MXFP8_E4M3, bw = dt == MOE_FP8_E4M3;
+    if ((mx || bw) && (!a_scale || !dc_scale)) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: fp8 needs a_scale and dc_scale");
     if (!dB) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: dB is NULL");
     if (out_dt != MOE_BF16 && out_dt != MOE_F32) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: out_dt must be bf16 or f32");
     gg_args a = gg_make(ctx, dC, A, offsets, E, N, K, Rcap, dB);
@@ -1474,6 +1558,9 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     if (mx) {
         if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 2);
         else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 2);
+    } else if (bw) {
+        if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 1);
+        else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 1);
     } else {
         if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 0);
         else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 0);

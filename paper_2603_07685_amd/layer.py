@@ -42,7 +42,8 @@ class LayerState:
 
     def __init__(self, cfg: wl.MoEConfig, hin: dict | None = None, shared_f: int | None = None,
                  variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False,
-                 fused_quant: bool | None = None, epilogue_quant: bool | None = None, f32: bool = False):
+                 fused_quant: bool | None = None, epilogue_quant: bool | None = None, f32: bool = False,
+                 fp8_wgrad: bool | None = None):
         self.cfg = cfg
         self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.1.2): weights applied before fc2
         # MXFP8 only (default there): the permuted tokens and the combine's backward are quantised straight from
@@ -53,11 +54,17 @@ class LayerState:
         # output, the next GEMM's operand (Sec. 5.4.2); off = stand-alone quantiser launches
         self.epilogue_quant = bool(cfg.fp8) and not cfg.mx if epilogue_quant is None else bool(epilogue_quant)
         assert not self.epilogue_quant or (cfg.fp8 and not cfg.mx), "epilogue quantisation is built for the blockwise path"
+        # blockwise fp8 (default there): the weight gradients also run on E4M3 codes, quantised 128x1 down the token
+        # dimension inside each expert's 128-aligned row range (Sec. 5.3.2, 5.4.1); off = weight gradients from the
+        # bf16 tensors.  (MXFP8 always runs them on its 32x1 copies.)
+        self.fp8_wgrad = (bool(cfg.fp8) and not cfg.mx) if fp8_wgrad is None else bool(fp8_wgrad)
+        assert not self.fp8_wgrad or (cfg.fp8 and not cfg.mx and cfg.align % 128 == 0), \
+            "blockwise fp8 weight gradients need the blockwise config with experts padded to 128 rows"
         T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
         self.sf = sf = cfg.shared_f if shared_f is None else shared_f
         self.align = cfg.align
         Rcap = T * k + E * (cfg.align - 1)
-        if cfg.mx:  # the column-wise quantiser and the weight-gradient GEMM walk the rows in steps of 128
+        if cfg.mx or self.fp8_wgrad:  # the column-wise quantiser and the weight-gradient GEMM walk the rows in steps of 128
             Rcap = (Rcap + 127) // 128 * 128
         self.Rcap = Rcap
         self.ctx = B.Context(T, k, max(E, cfg.E_router), h, max(f, sf))
@@ -142,18 +149,19 @@ class LayerState:
                 return (torch.empty((g, rows, cols), dtype=u8, device=dev),
                         torch.empty((g * rows // 128, cols, 4), dtype=u8, device=dev))
 
-            def codes_col(rows, cols):  # MXFP8 only: the copy quantised down the rows for the weight gradient
-                if not mx:
+            def codes_col(rows, cols):  # the copy quantised down the rows for the weight gradient (32x1 E8M0 / 128x1 fp32)
+                if not mx and not self.fp8_wgrad:
                     return None, None
                 return (torch.empty((rows, cols), dtype=u8, device=dev),
-                        torch.empty((rows // 128, cols, 4), dtype=u8, device=dev))
+                        torch.empty((rows // 128, cols, 4), dtype=u8, device=dev) if mx else
+                        torch.empty((rows // 128, cols), dtype=f32, device=dev))
 
             self.qXp, self.sXp = codes(Rcap, h)
             self.qA, self.sA = codes(Rcap, f)
             self.qdO, self.sdO = codes(Rcap, h)
             self.qdZ, self.sdZ = codes(Rcap, 2 * f)
-            if mx:
-                assert Rcap % 128 == 0 and T % 128 == 0, "MXFP8 weight gradients walk the rows in steps of 128"
+            if mx or self.fp8_wgrad:
+                assert Rcap % 128 == 0 and T % 128 == 0, "fp8 weight gradients walk the rows in steps of 128"
             self.qXpc, self.sXpc = codes_col(Rcap, h)
             self.qAc, self.sAc = codes_col(Rcap, f)
             self.qdOc, self.sdOc = codes_col(Rcap, h)
@@ -195,6 +203,13 @@ class LayerState:
             B.moe_mx_quantize_rowcol(self.ctx, X, rows, cols, live, q, s, qc, sc)
         else:
             B.moe_fp8_quantize(self.ctx, X, B.Q_1x128, 1, rows, cols, live, q, s)
+            self._q_cols(X, qc, sc, rows, cols, live)
+
+    def _q_cols(self, X, qc, sc, rows, cols, live=None):
+        """Blockwise recipe: the weight-gradient copy of a row-indexed tensor, 128x1 tiles down the rows (a tensor that
+        two GEMMs read with different contraction dimensions is quantised once per direction, Sec. 5.3.3 / 5.4.1)."""
+        if self.fp8_wgrad and not self.mx:
+            B.moe_fp8_quantize(self.ctx, X, B.Q_128x1, 1, rows, cols, live, qc, sc)
 
     def _q_weight(self, W, q, s, qd=None, sd=None):
         """Quantise a weight stack for the forward GEMM (and, MXFP8, the second copy for the data gradient)."""
@@ -281,7 +296,7 @@ class LayerState:
     # ---- fp8 (blockwise, Sec. 5.3.2, or MXFP8, Sec. 5.3.3): forward and data-gradient GEMMs on E4M3 codes;
     # weights are re-quantised every step (MXFP8: in both directions, one pass); MXFP8 also runs the weight
     # gradients on one-byte operands, quantised down the token dimension in the same pass as the row-wise
-    # copy; blockwise weight gradients use the bf16 tensors ----
+    # copy; blockwise weight gradients run on 128x1 copies made by a second quantiser pass (fp8_wgrad off: on the bf16 tensors) ----
     def _forward_fp8(self):
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
@@ -307,6 +322,8 @@ class LayerState:
                                      self.qA if eq else None, self.sA if eq else None)
         if not eq:
             self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows, self.qAc, self.sAc)
+        else:
+            self._q_cols(self.A, self.qAc, self.sAc, Rcap, f, self.live_rows)
         B.moe_grouped_gemm_fwd(c, self.qA, self.qW2, self.offsets, E, h, f, Rcap, F8, B.EPI_NONE,
                                self.sA, self.sW2, self.O, None)
         if sf:
@@ -319,6 +336,8 @@ class LayerState:
                                          self.qAs if eq else None, self.sAs if eq else None)
             if not eq:
                 self._q_rows(self.As, self.qAs, self.sAs, T, sf, None, self.qAsc, self.sAsc)
+            else:
+                self._q_cols(self.As, self.qAsc, self.sAsc, T, sf)
             B.moe_grouped_gemm_fwd(c, self.qAs, self.qWs2, o1, 1, h, sf, T, F8, B.EPI_NONE,
                                    self.sAs, self.sWs2, self.S, None)
         B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, None if self.eq2 else self.topk_prob,
@@ -353,6 +372,8 @@ class LayerState:
             B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
         if not eq:
             self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows, self.qdZc, self.sdZc)
+        else:
+            self._q_cols(self.dZ, self.qdZc, self.sdZc, Rcap, 2 * f, self.live_rows)
         self._wgrad(self.Xp, self.dZ, self.qXpc, self.sXpc, self.qdZc, self.sdZc, self.offsets, E, 2 * f, h, Rcap, self.dW1)
         B.moe_grouped_gemm_dgrad(c, self.qdZ, self.qW1d, self.offsets, E, 2 * f, h, Rcap, F8, None, self.sdZ, self.sW1d,
                                  self.dXp)
@@ -364,16 +385,18 @@ class LayerState:
                                            None, self.dZs, None, self.qdZs if eq else None, self.sdZs if eq else None)
             if not eq:
                 self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf, None, self.qdZsc, self.sdZsc)
+            else:
+                self._q_cols(self.dZs, self.qdZsc, self.sdZsc, T, 2 * sf)
             self._wgrad(self.X, self.dZs, self.qXc, self.sXc, self.qdZsc, self.sdZsc, o1, 1, 2 * sf, h, T, self.dWs1)
             B.moe_grouped_gemm_dgrad(c, self.qdZs, self.qWs1d, o1, 1, 2 * sf, h, T, F8, None, self.sdZs, self.sWs1d,
                                      self.dXs)
         B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
 
     def _wgrad(self, A, dC, qA, sA, qdC, sdC, offsets, E, N, K, rows, dW):
-        """dW = dC^T A per expert: on the copies quantised down the rows (MXFP8) or on the bf16 tensors (the
-        blockwise recipe has no weight-gradient GEMM here)."""
-        if self.mx:
-            B.moe_grouped_gemm_wgrad(self.ctx, qA, qdC, offsets, E, N, K, rows, B.MXFP8_E4M3, sA, sdC, 0, self.wgrad_dt, dW)
+        """dW = dC^T A per expert: on the copies quantised down the rows (MXFP8: 32x1 blocks; blockwise: 128x1 tiles) or,
+        with fp8_wgrad off, on the bf16 tensors."""
+        if self.mx or self.fp8_wgrad:
+            B.moe_grouped_gemm_wgrad(self.ctx, qA, qdC, offsets, E, N, K, rows, self.f8dt, sA, sdC, 0, self.wgrad_dt, dW)
         else:
             B.moe_grouped_gemm_wgrad(self.ctx, A, dC, offsets, E, N, K, rows, B.BF16, None, None, 0, self.wgrad_dt, dW)
 

@@ -76,12 +76,16 @@ def test_fp8_layer_every_element(oracle, variant):
     assert np.all(_f64(st.dO)[:R][m.src_of[:R] < 0] == 0)                 # padding rows of dO are exact zeros
     e16["dprob"] = c16("dprob", st.dprob.cpu().numpy(), dpref)
     dOg, Zg, dZg = _f64(st.dO)[:R], _f64(st.Z)[:R], _f64(st.dZ)[:R]
-    e16["dW2"] = c16("dW2", _f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off))
+    cw = c8 if st.fp8_wgrad else c16                                       # the weight gradients run on E4M3 codes too
+    ew = e8 if st.fp8_wgrad else e16
+    ew["dW2"] = cw("dW2", _f64(st.dW2), oracle.grouped_gemm_tn(dOg, _f64(st.A)[:R], off))
+    ew["dWs2"] = cw("dWs2", _f64(st.dWs2), oracle.grouped_gemm_tn(hin["dY"], _f64(st.As), o1)[0])
     e8["dZ"] = c8("dZ", dZg, oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, off), Zg))
-    e16["dW1"] = c16("dW1", _f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off))
+    ew["dW1"] = cw("dW1", _f64(st.dW1), oracle.grouped_gemm_tn(dZg, Xp, off))
     e8["dXp"] = c8("dXp", _f64(st.dXp)[:R], oracle.grouped_gemm_nn(dZg, W1, off))
     e8["dZs"] = c8("dZs", _f64(st.dZs), oracle.swiglu_bwd(oracle.grouped_gemm_nn(hin["dY"], Ws2, o1), _f64(st.Zs)))
     e8["dXs"] = c8("dXs", _f64(st.dXs), oracle.grouped_gemm_nn(_f64(st.dZs), Ws1, o1))
+    ew["dWs1"] = cw("dWs1", _f64(st.dWs1), oracle.grouped_gemm_tn(_f64(st.dZs), hin["X"], o1)[0])
     e16["dX"] = c16("dX", _f64(st.dX), oracle.combine(_f64(st.dXp)[:R], m.row_of, None, _f64(st.dXs)))
     for e in range(E):
         if m.counts[e] == 0:

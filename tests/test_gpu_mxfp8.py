@@ -281,12 +281,3 @@ def test_mx_wgrad_rejects_ranges_off_the_block_grid(B, ctx):
     torch.cuda.synchronize()
     assert ctx.poll_error() != 0
     assert (dW == 3.0).all()
-
-
-def test_blockwise_fp8_wgrad_is_refused(B, ctx):
-    from gpu_util import dev
-    A = torch.zeros((128, 128), dtype=torch.uint8, device="cuda")
-    dW = torch.zeros((1, 128, 128), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(B.MoeError):
-        B.moe_grouped_gemm_wgrad(ctx, A, A, dev(np.array([0, 128], np.int32)), 1, 128, 128, 128, B.FP8_E4M3, None, None,
-                                 0, B.BF16, dW)
