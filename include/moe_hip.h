@@ -287,11 +287,13 @@ moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, con
  *                 not weighted.  row_prob = NULL is exactly moe_grouped_gemm_fwd.
  * dgrad_weighted: as moe_grouped_gemm_dgrad with Z_saved; the output is
  *                 dZ[r,:] = row_prob[r] * SwiGLU-backward(dA[r,:], Z_saved[r,:]) and, if
- *                 dprob_part != NULL (fp32 [Rcap, ceil(K/256)]), dprob_part[r,j] =
- *                 sum over the 256 columns c of column tile j of dA[r,c] * silu(gate)*up:
- *                 the partial sums of dL/d row_prob[r], in fp32, written once each (no
- *                 atomics; moe_scatter_row_dprob adds them in a fixed order).  Rows of
- *                 padding get a partial of 0; rows >= offsets[E] are not written.
+ *                 dprob_part != NULL (fp32 [Rcap, 2 * ceil(K/256)]), dprob_part[r, 2j] +
+ *                 dprob_part[r, 2j + 1] = sum over the 256 columns c of column tile j of
+ *                 dA[r,c] * silu(gate)*up (each entry covers 128 of the tile's columns; which
+ *                 ones is the kernel's business): the partial sums of dL/d row_prob[r], in
+ *                 fp32, written once each (no atomics; moe_scatter_row_dprob adds them in a
+ *                 fixed order).  Rows of padding get partials of 0; rows >= offsets[E] are
+ *                 not written.
  */
 moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, const void* A, const void* B,
                                          const int32_t* offsets, int E, int N, int K, int64_t Rcap,

@@ -196,7 +196,7 @@ struct gg_args {
     uint8_t* out_q;
     float* out_q_scale;
     int* tile_counter;     // wgrad: zeroed device counter for the dynamic tile order under skewed loads (see the kernel)
-    float* dprob_part;     // eq. (2), dgrad SWIGLU_BWD: [Rcap, ceil(K/256)] partial <dA, act(Z)> per row and column tile
+    float* dprob_part;     // eq. (2), dgrad SWIGLU_BWD: [Rcap, 2 ceil(K/256)] partial <dA, act(Z)> per row, two per column tile
 };
 
 // MODE: GG_FWD / GG_DGRAD / GG_WGRAD.  EPI: see enum.  OUT_F32: fp32 output (wgrad only).
@@ -403,6 +403,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     int KT_pf = 0;
     int e_hint = 0;
     auto setup_tile = [&](int t) __attribute__((always_inline)) {
+        // (four waves: the lane constants of the set-up are formed here from a lane id the compiler cannot see through;
+        // computed once at kernel start they would occupy registers through every stage loop, or spill)
+        int lane = threadIdx.x & 63;
+        if (NW == 4) asm volatile("" : "+v"(lane));
+        const int km_row = lane >> 3, cm_row = lane / CM_SLOTS;
         // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
         int u;
         if (MODE == GG_WGRAD) {
@@ -1127,7 +1132,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         // fragment reads of both groups)
         const int ep_e = e, ep_i0 = i0, ep_i_end = i_end, ep_j0 = j0, ep_j1 = j1;
         const int t_next = dyn ? publish(drawn) : tile_of(n_tile + 1);
-        if (t_next < total_tiles) {
+        // (four-wave SwiGLU backward: the registers that would hold the next tile's first stage carry the saved
+        // pre-activations instead, many units ahead; the next tile is set up behind the output phase)
+        constexpr bool LATE_SETUP = NW == 4 && EPI != GG_EPI_STORE;
+        if (!LATE_SETUP && t_next < total_tiles) {
             setup_tile(t_next);
             issue_stage0();
         }
@@ -1140,213 +1148,458 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         // instruction: lane l owns columns 4 l .. 4 l + 3 of the 256, so every global access is 256-512
         // contiguous bytes.  Buffer 1 is free here: the next tile's stage 0 went to buffer 0, its stage 1 is
         // issued after the barrier that follows this epilogue.
-        float* const stg = (float*)ldsP1;
-        const int cl = lane * 4;                                          // column inside the 256-wide tile
-        const int c = cl < 128 ? ep_j0 + cl : ep_j1 + cl - 128;           // output column of this lane
+        if constexpr (NW == 4) {
+            // Four waves: every wave writes out its own 128 x 128 share (two strips of 64 columns, 128 apart in the
+            // tile) with no help from the others, so the output phase has no barrier at all.  A lane holds one row and
+            // 4 columns of each 16 x 16 block; to leave as whole cache lines the values take a round trip through a
+            // private 16 KB of buffer 1, one 16-row x 64-column unit at a time (row pitch 68 floats: the 16 lanes of a
+            // store and of a load hit 64 different banks), and come back as 8 consecutive columns per lane: a store
+            // instruction is then 8 rows x 128 contiguous bytes (bf16).  The LDS executes a wave's instructions in
+            // order, so a unit is read back right behind its stores; three units rotate, the next one is already on
+            // its way through the LDS while the current one is converted and stored.  The SwiGLU is applied to the
+            // accumulators before the trip (gate and up of a feature sit in the same lane, blocks jq and jq + 4),
+            // its derivative behind it, on the saved pre-activations fetched three units ahead.
+            // (Buffer 1 is not written by anyone until every wave has passed the first barrier of the next tile.)
+            float* const wst = (float*)(ldsP1 + wave * 16384);
+            constexpr int UP = 68, UNIT = 16 * UP;
+            // (the lane constants of this phase are formed here, from a lane id the compiler cannot see through: hoisted
+            // out of the tile loop they would sit in registers for the whole stage loop, which has none to spare)
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int l16 = ln & 15, lq = ln >> 4;           // accumulator layout: row l16, columns 4 lq + 0..3 of a block
+            const int rr = ln >> 3, c8 = (ln & 7) * 8;       // row-major layout: rows rr and rr + 8, columns c8 .. c8 + 7
+            const int wr_off = l16 * UP + 4 * lq, rd_off = rr * UP + c8;
+            const int row0 = ep_i0 + wm * 128;               // first output row of this wave
+            const int col_lo = ep_j0 + wn * 64 + c8, col_hi = ep_j1 + wn * 64 + c8;   // this lane's columns in the two strips
+            struct unit_t { f32x4_t v[2][2]; };               // [row group][columns 0..3 / 4..7]
+            auto put = [&](int slot, const f32x4_t (&v)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // SwiGLU backward: the saved pre-activations of the first 8 rows this wave writes in this pass are requested
-            // before the accumulators go to LDS, so their latency overlaps the staging and its barrier
-            // (bf16 only: the one-byte variants have no registers to spare for it; with four waves a wave writes
-            // 16 rows per pass and has registers for half of them)
-            constexpr bool Z_EARLY = EPI == GG_EPI_SWIGLU_BWD && !FP8;
-            constexpr int ZE = 8;
-            u32x2_t zg[ZE], zu[ZE];
-            if (Z_EARLY) {
+                for (int j = 0; j < 4; ++j) *(f32x4_t*)(wst + slot * UNIT + wr_off + 16 * j) = v[j];
+            };
+            auto get = [&](int slot) __attribute__((always_inline)) {
+                unit_t u;
 #pragma unroll
-                for (int x8 = 0; x8 < ZE; ++x8) {
-                    const int rr = wave * RPW + x8;
-                    const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
-                    if (r < ep_i_end && c < K) {
-                        const int64_t zr = (int64_t)r * 2 * K;
-                        zg[x8] = *(const u32x2_t*)(a.Zsaved + zr + c);
-                        zu[x8] = *(const u32x2_t*)(a.Zsaved + zr + K + c);
+                for (int g = 0; g < 2; ++g) {
+                    u.v[g][0] = *(const f32x4_t*)(wst + slot * UNIT + rd_off + 8 * g * UP);
+                    u.v[g][1] = *(const f32x4_t*)(wst + slot * UNIT + rd_off + 8 * g * UP + 4);
+                }
+                return u;
+            };
+            auto pack8 = [](const f32x4_t& a, const f32x4_t& b) {
+                const u32x4_t w = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]), pack_bf16(b[2], b[3])};
+                return w;
+            };
+            if constexpr (EPI == GG_EPI_SWIGLU) {
+                // units of P block i: gate strip, up strip (the saved pre-activations, if wanted), activation
+                bf16_t* const C = (bf16_t*)a.out;
+                const bool feat_ok = ep_j0 + wn * 64 + c8 < half_cols;   // (N / 2 need not fill the last tile)
+                constexpr int NU = 24;
+                // (every accumulator is read once, into ordinary registers, when its block comes up: left to the
+                // compiler, the two uses of each value, as pre-activation and in the activation, ended in scratch)
+                f32x4_t g4[4], u4[4];
+                auto make = [&](int u, f32x4_t (&v)[4]) __attribute__((always_inline)) {
+                    const int i = u / 3, t = u % 3;
+                    if (t == 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            g4[j] = acc4[i][j];
+                            u4[j] = acc4[i][4 + j];
+                            asm volatile("" : "+v"(g4[j]), "+v"(u4[j]));
+                        }
                     }
+                    if (t < 2) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] = t == 0 ? g4[j] : u4[j];
+                    } else {
+                        float pr = 1.0f;
+                        if (a.row_prob) {
+                            const int r = row0 + 16 * i + l16;
+                            pr = r < ep_i_end ? a.row_prob[r] : 0.0f;
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) {
+                                const float gt = g4[j][x], up = u4[j][x];
+                                v[j][x] = pr * (gt * sigmoid_f(gt) * up);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);   // (four values at a time: interleaving all sixteen chains costs 60 registers)
+                        }
+                    }
+                };
+                // (addresses: a wave-uniform row base per unit plus one 32-bit lane offset per tensor and strip; whole
+                // 64-bit addresses per lane, formed ahead for all units, are what spilled)
+                const uint32_t vz_lo = (uint32_t)(rr * N + col_lo) * 2, vz_hi = (uint32_t)(rr * N + col_hi) * 2;
+                const uint32_t va = (uint32_t)(rr * half_cols + col_lo) * 2;
+                auto emit = [&](int u, const unit_t& o) __attribute__((always_inline)) {
+                    const int i = u / 3, t = u % 3;
+                    if (t < 2 && !C) return;
+                    if (!feat_ok) return;
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const int rb = row0 + 16 * i + 8 * g;   // wave-uniform
+                        if (rb + rr >= ep_i_end) continue;
+                        const u32x4_t w = pack8(o.v[g][0], o.v[g][1]);
+                        if (t == 2) *(u32x4_t*)((char*)a.out_act + (int64_t)rb * half_cols * 2 + va) = w;
+                        else *(u32x4_t*)((char*)C + (int64_t)rb * N * 2 + (t == 0 ? vz_lo : vz_hi)) = w;
+                    }
+                };
+                // (one unit at a time here: with the next unit already on its way, as in the other two output phases, the
+                // activation's temporaries no longer fit beside the operands in flight for the next tile)
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    f32x4_t v[4];
+                    make(u, v);
+                    put(u % 3, v);
+                    const unit_t cur = get(u % 3);
+                    emit(u, cur);
+                    __builtin_amdgcn_sched_barrier(0);   // (units in program order: left free, the scheduler starts them all at once and spills)
+                }
+            } else if constexpr (EPI == GG_EPI_SWIGLU_BWD) {
+                // units: (P block i, strip hf).  dZ[r, c] = dA up s (1 + g (1 - s)), dZ[r, K + c] = dA g s, s = sigmoid(g),
+                // from the saved [gate | up]; the row's share of dL/dp, <dA, silu(gate) up> over the wave's 128 columns,
+                // is one partial sum per row and wave (added in a fixed order: strip 0 then strip 1, lanes by xor 1, 2, 4)
+                bf16_t* const dZ = (bf16_t*)a.out;
+#ifndef GG_ZD
+#define GG_ZD 5
+#endif
+                constexpr int NU = 16, ZD = GG_ZD;   // saved pre-activations are requested ZD units ahead
+                u32x4_t zg[ZD][2], zu[ZD][2];
+                // (addresses: a wave-uniform row base per unit plus a 32-bit lane offset per strip)
+                const uint32_t vo_lo = (uint32_t)(rr * 2 * K + col_lo) * 2, vo_hi = (uint32_t)(rr * 2 * K + col_hi) * 2;
+                auto zload = [&](int u) __attribute__((always_inline)) {
+                    const int i = u / 2, hf = u % 2;
+                    const int c = hf == 0 ? col_lo : col_hi;
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const int rb = row0 + 16 * i + 8 * g;   // wave-uniform
+                        if (rb + rr < ep_i_end && c < K) {
+                            const char* zb = (const char*)a.Zsaved + (int64_t)rb * 2 * K * 2 + (hf == 0 ? vo_lo : vo_hi);
+                            zg[u % ZD][g] = *(const u32x4_t*)zb;
+                            zu[u % ZD][g] = *(const u32x4_t*)(zb + 2 * K);
+                        }
+                    }
+                };
+                float dots[2] = {0.f, 0.f};
+                auto emit = [&](int u, const unit_t& o) __attribute__((always_inline)) {
+                    const int i = u / 2, hf = u % 2;
+                    const int c = hf == 0 ? col_lo : col_hi;
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const int r = row0 + 16 * i + rr + 8 * g;
+                        float dot = 0.f;
+                        if (r < ep_i_end && c < K) {
+                            const u32x4_t zgv = zg[u % ZD][g], zuv = zu[u % ZD][g];
+                            const float gt[8] = {bf16_lo(zgv.x), bf16_hi(zgv.x), bf16_lo(zgv.y), bf16_hi(zgv.y),
+                                                 bf16_lo(zgv.z), bf16_hi(zgv.z), bf16_lo(zgv.w), bf16_hi(zgv.w)};
+                            const float up[8] = {bf16_lo(zuv.x), bf16_hi(zuv.x), bf16_lo(zuv.y), bf16_hi(zuv.y),
+                                                 bf16_lo(zuv.z), bf16_hi(zuv.z), bf16_lo(zuv.w), bf16_hi(zuv.w)};
+                            const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
+                            float dg[8], du[8];
+#pragma unroll
+                            for (int x = 0; x < 8; ++x) {
+                                const float da = o.v[g][x >> 2][x & 3];
+                                const float sg = sigmoid_f(gt[x]);
+                                dg[x] = pr * da * up[x] * sg * (1.0f + gt[x] * (1.0f - sg));
+                                du[x] = pr * da * gt[x] * sg;
+                                dot += da * (gt[x] * sg * up[x]);
+                            }
+                            const u32x4_t wg = {pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3]), pack_bf16(dg[4], dg[5]), pack_bf16(dg[6], dg[7])};
+                            const u32x4_t wu = {pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3]), pack_bf16(du[4], du[5]), pack_bf16(du[6], du[7])};
+                            char* ob = (char*)dZ + (int64_t)(r - rr) * 2 * K * 2 + (hf == 0 ? vo_lo : vo_hi);
+                            *(u32x4_t*)ob = wg;
+                            *(u32x4_t*)(ob + 2 * K) = wu;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);   // (one row group at a time: keeps the temporaries of the derivative at 8 values)
+                        if (a.dprob_part) {
+                            dot += __shfl_xor(dot, 1);
+                            dot += __shfl_xor(dot, 2);
+                            dot += __shfl_xor(dot, 4);
+                            dots[g] = hf == 0 ? dot : dots[g] + dot;
+                            if (hf == 1 && (ln & 7) == 0 && r < ep_i_end)
+                                a.dprob_part[(int64_t)r * (2 * tiles_j) + 2 * (ep_j0 / GG_BN) + wn] = dots[g];
+                        }
+                    }
+                };
+#pragma unroll
+                for (int u = 0; u < ZD; ++u) zload(u);
+                f32x4_t v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = acc4[0][j];
+                put(0, v);
+                unit_t cur = get(0);
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    unit_t nxt;
+                    if (u + 1 < NU) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] = acc4[(u + 1) / 2][4 * ((u + 1) % 2) + j];
+                        put((u + 1) % 3, v);
+                        nxt = get((u + 1) % 3);
+                    }
+                    emit(u, cur);
+                    if (u + ZD < NU) zload(u + ZD);
+                    if (u + 1 < NU) cur = nxt;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                // plain store (forward fc2, data gradients, weight gradients, the gate's fp32 logits)
+                constexpr int NU = 16;
+                const int ld = (MODE == GG_WGRAD) ? K : J;
+                constexpr int OB = OUT_F32 ? 4 : 2;
+                // (addresses: a wave-uniform row base per unit plus a 32-bit lane offset per strip)
+                const uint32_t vo_lo = (uint32_t)(rr * ld + col_lo) * OB, vo_hi = (uint32_t)(rr * ld + col_hi) * OB;
+                auto emit = [&](int u, const unit_t& o) __attribute__((always_inline)) {
+                    const int i = u / 2, hf = u % 2;
+                    const int c = hf == 0 ? col_lo : col_hi;
+                    if (c >= J) return;
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const int rb = row0 + 16 * i + 8 * g;   // wave-uniform
+                        if (rb + rr >= ep_i_end) continue;
+                        char* const at = (char*)a.out + ((MODE == GG_WGRAD) ? ((int64_t)ep_e * N + rb) : (int64_t)rb) * ld * OB +
+                                         (hf == 0 ? vo_lo : vo_hi);
+                        f32x4_t lo = o.v[g][0], hi = o.v[g][1];
+                        if (OUT_F32) {
+                            f32x4_t* q = (f32x4_t*)at;
+                            if (a.accumulate) {
+                                lo += q[0];
+                                hi += q[1];
+                            }
+                            q[0] = lo;
+                            q[1] = hi;
+                        } else {
+                            u32x4_t* q = (u32x4_t*)at;
+                            if (a.accumulate) {
+                                const u32x4_t w = *q;
+                                lo += f32x4_t{bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y)};
+                                hi += f32x4_t{bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+                            }
+                            *q = pack8(lo, hi);
+                        }
+                    }
+                };
+                f32x4_t v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = acc4[0][j];
+                put(0, v);
+                unit_t cur = get(0);
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    unit_t nxt;
+                    if (u + 1 < NU) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] = acc4[(u + 1) / 2][4 * ((u + 1) % 2) + j];
+                        put((u + 1) % 3, v);
+                        nxt = get((u + 1) % 3);
+                    }
+                    emit(u, cur);
+                    if (u + 1 < NU) cur = nxt;
+                    __builtin_amdgcn_sched_barrier(0);   // (units in program order: left free, the scheduler starts them all at once and spills)
                 }
             }
-            if (NW == 4) {
-                // a lane holds, per 16 x 16 block, one output row (l % 16) and 4 consecutive columns (4 (l / 16) + 0..3);
-                // pass i stages the P blocks 2 i and 2 i + 1 of both wave rows
+        } else {
+            float* const stg = (float*)ldsP1;
+            const int cl = lane * 4;                                          // column inside the 256-wide tile
+            const int c = cl < 128 ? ep_j0 + cl : ep_j1 + cl - 128;           // output column of this lane
 #pragma unroll
-                for (int ib = 0; ib < 2; ++ib)
+            for (int i = 0; i < 4; ++i) {
+                // SwiGLU backward: the saved pre-activations of the first 8 rows this wave writes in this pass are requested
+                // before the accumulators go to LDS, so their latency overlaps the staging and its barrier
+                // (bf16 in the eight-wave body only: the one-byte variants have no registers to spare for it)
+                constexpr bool Z_EARLY = EPI == GG_EPI_SWIGLU_BWD && !FP8;
+                constexpr int ZE = 8;
+                u32x2_t zg[ZE], zu[ZE];
+                if (Z_EARLY) {
 #pragma unroll
-                    for (int jq = 0; jq < 8; ++jq)
-                        *(f32x4_t*)(stg + (wm * 32 + 16 * ib + (lane & 15)) * STG_PITCH + (jq / 4) * 128 + wn * 64 + (jq % 4) * 16 +
-                                    4 * (lane >> 4)) = acc4[2 * i + ib][jq];
-            } else
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int h2 = 0; h2 < NJ; ++h2) {
-                    f32x4_t v;
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        v[x] = acc[i][h2][4 * g + x];
-                        if (FP8 && !MX && !BW_WGRAD) v[x] *= ps_cur[i] * qs_cur[h2];
-                    }
-                    *(f32x4_t*)(stg + (wm * 32 + fr_row) * STG_PITCH + blk_col(h2) + 8 * g + 4 * fr_khalf) = v;
-                }
-            wait_lgkm0();
-            stage_barrier();
-            auto out_row = [&](int x8, bool early, bool have, f32x4_t vin) {
-                const int rr = wave * RPW + x8;                           // staged row 0..63
-                const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
-                if (r >= ep_i_end) return;                                // wave-uniform
-                const f32x4_t v = have ? vin : *(const f32x4_t*)(stg + rr * STG_PITCH + cl);
-                if (EPI == GG_EPI_SWIGLU) {
-                    bf16_t* C = (bf16_t*)a.out;                           // [gate | up] pre-activations
-                    if (C && ep_j0 + (cl & 127) < half_cols) {
-                        const float t4[4] = {v[0], v[1], v[2], v[3]};
-                        st4_bf16(C + (int64_t)r * N + c, t4);
-                    }
-                } else if (EPI == GG_EPI_SWIGLU_BWD) {
-                    // dZ[r, c] = dA * up * s (1 + g (1 - s)),  dZ[r, K + c] = dA * g * s,  s = sigmoid(g)
-                    float dot = 0.f;
-                    if (c < K) {
-                        bf16_t* dZ = (bf16_t*)a.out;
-                        const int64_t zr = (int64_t)r * 2 * K;
-                        u32x2_t zgv, zuv;  // (not through the arrays when the row loop is rolled: no runtime index)
-                        if (Z_EARLY && early) {
-                            zgv = zg[x8 < ZE ? x8 : 0];
-                            zuv = zu[x8 < ZE ? x8 : 0];
-                        } else {
-                            zgv = *(const u32x2_t*)(a.Zsaved + zr + c);
-                            zuv = *(const u32x2_t*)(a.Zsaved + zr + K + c);
+                    for (int x8 = 0; x8 < ZE; ++x8) {
+                        const int rr = wave * RPW + x8;
+                        const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
+                        if (r < ep_i_end && c < K) {
+                            const int64_t zr = (int64_t)r * 2 * K;
+                            zg[x8] = *(const u32x2_t*)(a.Zsaved + zr + c);
+                            zu[x8] = *(const u32x2_t*)(a.Zsaved + zr + K + c);
                         }
-                        const float gt[4] = {bf16_lo(zgv.x), bf16_hi(zgv.x), bf16_lo(zgv.y), bf16_hi(zgv.y)};
-                        const float up[4] = {bf16_lo(zuv.x), bf16_hi(zuv.x), bf16_lo(zuv.y), bf16_hi(zuv.y)};
-                        float dg[4], du[4];
-                        const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int h2 = 0; h2 < NJ; ++h2) {
+                        f32x4_t v;
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
-                            const float sg = sigmoid_f(gt[x]);
-                            dg[x] = pr * v[x] * up[x] * sg * (1.0f + gt[x] * (1.0f - sg));
-                            du[x] = pr * v[x] * gt[x] * sg;
-                            dot += v[x] * (gt[x] * sg * up[x]);  // <dA, silu(gate) * up>: the row's share of dL/dp
+                            v[x] = acc[i][h2][4 * g + x];
+                            if (FP8 && !MX && !BW_WGRAD) v[x] *= ps_cur[i] * qs_cur[h2];
                         }
-                        st4_bf16(dZ + zr + c, dg);
-                        st4_bf16(dZ + zr + K + c, du);
-                        if (F8 == 1 && a.out_q) {
-                            // the 32 lanes of a half-wave hold one 1x128 block of the gate part and one of the up
-                            // part of this row (K % 128 == 0: a half is inside K or outside as a whole); quantise
-                            // the values as they were just stored (bf16), as the stand-alone quantiser would
-                            const uint32_t g01 = pack_bf16(dg[0], dg[1]), g23 = pack_bf16(dg[2], dg[3]);
-                            const uint32_t u01 = pack_bf16(du[0], du[1]), u23 = pack_bf16(du[2], du[3]);
-                            float mg = fmaxf(fmaxf(fabsf(bf16_lo(g01)), fabsf(bf16_hi(g01))), fmaxf(fabsf(bf16_lo(g23)), fabsf(bf16_hi(g23))));
-                            float mu = fmaxf(fmaxf(fabsf(bf16_lo(u01)), fabsf(bf16_hi(u01))), fmaxf(fabsf(bf16_lo(u23)), fabsf(bf16_hi(u23))));
-#pragma unroll
-                            for (int o = 16; o > 0; o >>= 1) {
-                                mg = fmaxf(mg, __shfl_xor(mg, o));
-                                mu = fmaxf(mu, __shfl_xor(mu, o));
-                            }
-                            const float sgs = block_scale(mg), sus = block_scale(mu);
-                            uint32_t* q = (uint32_t*)(a.out_q + zr);
-                            q[c >> 2] = cvt4_e4m3(bf16_lo(g01), bf16_hi(g01), bf16_lo(g23), bf16_hi(g23), sgs);
-                            q[(K + c) >> 2] = cvt4_e4m3(bf16_lo(u01), bf16_hi(u01), bf16_lo(u23), bf16_hi(u23), sus);
-                            if ((lane & 31) == 0) {
-                                float* sc = a.out_q_scale + (int64_t)r * (2 * K / 128);
-                                sc[c >> 7] = sgs;
-                                sc[(K + c) >> 7] = sus;
-                            }
+                        *(f32x4_t*)(stg + (wm * 32 + fr_row) * STG_PITCH + blk_col(h2) + 8 * g + 4 * fr_khalf) = v;
+                    }
+                wait_lgkm0();
+                stage_barrier();
+                auto out_row = [&](int x8, bool early, bool have, f32x4_t vin) {
+                    const int rr = wave * RPW + x8;                           // staged row 0..63
+                    const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
+                    if (r >= ep_i_end) return;                                // wave-uniform
+                    const f32x4_t v = have ? vin : *(const f32x4_t*)(stg + rr * STG_PITCH + cl);
+                    if (EPI == GG_EPI_SWIGLU) {
+                        bf16_t* C = (bf16_t*)a.out;                           // [gate | up] pre-activations
+                        if (C && ep_j0 + (cl & 127) < half_cols) {
+                            const float t4[4] = {v[0], v[1], v[2], v[3]};
+                            st4_bf16(C + (int64_t)r * N + c, t4);
                         }
-                    }
-                    if (a.dprob_part) {  // the wave holds the 256 columns of this row and tile: one partial sum
-#pragma unroll
-                        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
-                        if (lane == 0) a.dprob_part[(int64_t)r * tiles_j + ep_j0 / GG_BN] = dot;
-                    }
-                } else if (c < J) {
-                    const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r) * K : (int64_t)r * J;
-                    if (OUT_F32) {
-                        f32x4_t* o = (f32x4_t*)((float*)a.out + base + c);
-                        f32x4_t w = v;
-                        if (a.accumulate) w += *o;
-                        *o = w;
-                    } else {
-                        bf16_t* o = (bf16_t*)a.out + base + c;
-                        float t4[4] = {v[0], v[1], v[2], v[3]};
-                        if (a.accumulate) {
-                            float old[4];
-                            ld4_bf16(o, old);
-#pragma unroll
-                            for (int x = 0; x < 4; ++x) t4[x] += old[x];
-                        }
-                        st4_bf16(o, t4);
-                    }
-                }
-            };
-            // (the pass loop must unroll completely: the accumulators are indexed by it.  The compiler gives up on
-            // that above a size limit, so the row loops stay rolled where nothing is indexed by them)
-            const f32x4_t none = {0.f, 0.f, 0.f, 0.f};
-            if (FP8) {
-#pragma unroll 1
-                for (int x8 = 0; x8 < RPW; ++x8) out_row(x8, false, false, none);
-            } else {
-                // rows in batches of 8: all the staged values first (unconditional LDS reads, nothing between them),
-                // then the rows; read inside the rows, every LDS latency would be taken in turn
-#pragma unroll
-                for (int x0 = 0; x0 < RPW; x0 += 8) {
-                    f32x4_t vb[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) vb[u] = *(const f32x4_t*)(stg + (wave * RPW + x0 + u) * STG_PITCH + cl);
-                    // plain store of 8 whole rows (the common case): no test or branch per row, one address chain
-                    const int rr0 = wave * RPW + x0;
-                    const int r0 = ep_i0 + (rr0 >> 5) * 128 + i * 32 + (rr0 & 31);  // the 8 rows are consecutive
-                    if (EPI == GG_EPI_STORE && !a.accumulate && r0 + 8 <= ep_i_end) {
-                        if (c < J) {
-                            const int64_t ld = (MODE == GG_WGRAD) ? K : J;
-                            const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r0) * K : (int64_t)r0 * J;
-                            if (OUT_F32) {
-                                float* o = (float*)a.out + base + c;
-#pragma unroll
-                                for (int u = 0; u < 8; ++u) *(f32x4_t*)(o + u * ld) = vb[u];
+                    } else if (EPI == GG_EPI_SWIGLU_BWD) {
+                        // dZ[r, c] = dA * up * s (1 + g (1 - s)),  dZ[r, K + c] = dA * g * s,  s = sigmoid(g)
+                        float dot = 0.f;
+                        if (c < K) {
+                            bf16_t* dZ = (bf16_t*)a.out;
+                            const int64_t zr = (int64_t)r * 2 * K;
+                            u32x2_t zgv, zuv;  // (not through the arrays when the row loop is rolled: no runtime index)
+                            if (Z_EARLY && early) {
+                                zgv = zg[x8 < ZE ? x8 : 0];
+                                zuv = zu[x8 < ZE ? x8 : 0];
                             } else {
-                                bf16_t* o = (bf16_t*)a.out + base + c;
+                                zgv = *(const u32x2_t*)(a.Zsaved + zr + c);
+                                zuv = *(const u32x2_t*)(a.Zsaved + zr + K + c);
+                            }
+                            const float gt[4] = {bf16_lo(zgv.x), bf16_hi(zgv.x), bf16_lo(zgv.y), bf16_hi(zgv.y)};
+                            const float up[4] = {bf16_lo(zuv.x), bf16_hi(zuv.x), bf16_lo(zuv.y), bf16_hi(zuv.y)};
+                            float dg[4], du[4];
+                            const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
 #pragma unroll
-                                for (int u = 0; u < 8; ++u) {
-                                    const float t4[4] = {vb[u][0], vb[u][1], vb[u][2], vb[u][3]};
-                                    st4_bf16(o + u * ld, t4);
+                            for (int x = 0; x < 4; ++x) {
+                                const float sg = sigmoid_f(gt[x]);
+                                dg[x] = pr * v[x] * up[x] * sg * (1.0f + gt[x] * (1.0f - sg));
+                                du[x] = pr * v[x] * gt[x] * sg;
+                                dot += v[x] * (gt[x] * sg * up[x]);  // <dA, silu(gate) * up>: the row's share of dL/dp
+                            }
+                            st4_bf16(dZ + zr + c, dg);
+                            st4_bf16(dZ + zr + K + c, du);
+                            if (F8 == 1 && a.out_q) {
+                                // the 32 lanes of a half-wave hold one 1x128 block of the gate part and one of the up
+                                // part of this row (K % 128 == 0: a half is inside K or outside as a whole); quantise
+                                // the values as they were just stored (bf16), as the stand-alone quantiser would
+                                const uint32_t g01 = pack_bf16(dg[0], dg[1]), g23 = pack_bf16(dg[2], dg[3]);
+                                const uint32_t u01 = pack_bf16(du[0], du[1]), u23 = pack_bf16(du[2], du[3]);
+                                float mg = fmaxf(fmaxf(fabsf(bf16_lo(g01)), fabsf(bf16_hi(g01))), fmaxf(fabsf(bf16_lo(g23)), fabsf(bf16_hi(g23))));
+                                float mu = fmaxf(fmaxf(fabsf(bf16_lo(u01)), fabsf(bf16_hi(u01))), fmaxf(fabsf(bf16_lo(u23)), fabsf(bf16_hi(u23))));
+#pragma unroll
+                                for (int o = 16; o > 0; o >>= 1) {
+                                    mg = fmaxf(mg, __shfl_xor(mg, o));
+                                    mu = fmaxf(mu, __shfl_xor(mu, o));
+                                }
+                                const float sgs = block_scale(mg), sus = block_scale(mu);
+                                uint32_t* q = (uint32_t*)(a.out_q + zr);
+                                q[c >> 2] = cvt4_e4m3(bf16_lo(g01), bf16_hi(g01), bf16_lo(g23), bf16_hi(g23), sgs);
+                                q[(K + c) >> 2] = cvt4_e4m3(bf16_lo(u01), bf16_hi(u01), bf16_lo(u23), bf16_hi(u23), sus);
+                                if ((lane & 31) == 0) {
+                                    float* sc = a.out_q_scale + (int64_t)r * (2 * K / 128);
+                                    sc[c >> 7] = sgs;
+                                    sc[(K + c) >> 7] = sus;
                                 }
                             }
                         }
-                    } else {
+                        if (a.dprob_part) {  // a half-wave holds 128 of the 256 columns of this row and tile: two partial sums
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) out_row(x0 + u, Z_EARLY && x0 == 0, true, vb[u]);
+                            for (int o = 16; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+                            if ((lane & 31) == 0) a.dprob_part[(int64_t)r * (2 * tiles_j) + 2 * (ep_j0 / GG_BN) + (lane >> 5)] = dot;
+                        }
+                    } else if (c < J) {
+                        const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r) * K : (int64_t)r * J;
+                        if (OUT_F32) {
+                            f32x4_t* o = (f32x4_t*)((float*)a.out + base + c);
+                            f32x4_t w = v;
+                            if (a.accumulate) w += *o;
+                            *o = w;
+                        } else {
+                            bf16_t* o = (bf16_t*)a.out + base + c;
+                            float t4[4] = {v[0], v[1], v[2], v[3]};
+                            if (a.accumulate) {
+                                float old[4];
+                                ld4_bf16(o, old);
+#pragma unroll
+                                for (int x = 0; x < 4; ++x) t4[x] += old[x];
+                            }
+                            st4_bf16(o, t4);
+                        }
                     }
-                }
-            }
-            if (EPI == GG_EPI_SWIGLU) {
-                // activation: a lane pairs gate and up of 4 features; two tile rows per instruction
-                const int fl = (lane & 31) * 4;
-#pragma unroll(FP8 ? 1 : 4)
-                for (int x4 = 0; x4 < RPW / 2; ++x4) {
-                    const int rr = wave * RPW + 2 * x4 + (lane >> 5);
-                    const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
-                    if (r < ep_i_end && ep_j0 + fl < half_cols) {  // uniform over a half-wave when N % 256 == 0 (fp8)
-                        const f32x4_t gt = *(const f32x4_t*)(stg + rr * STG_PITCH + fl);
-                        const f32x4_t up = *(const f32x4_t*)(stg + rr * STG_PITCH + 128 + fl);
-                        float act[4];
-                        const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
+                };
+                // (the pass loop must unroll completely: the accumulators are indexed by it.  The compiler gives up on
+                // that above a size limit, so the row loops stay rolled where nothing is indexed by them)
+                const f32x4_t none = {0.f, 0.f, 0.f, 0.f};
+                if (FP8) {
+#pragma unroll 1
+                    for (int x8 = 0; x8 < RPW; ++x8) out_row(x8, false, false, none);
+                } else {
+                    // rows in batches of 8: all the staged values first (unconditional LDS reads, nothing between them),
+                    // then the rows; read inside the rows, every LDS latency would be taken in turn
 #pragma unroll
-                        for (int x = 0; x < 4; ++x) act[x] = pr * (gt[x] * sigmoid_f(gt[x]) * up[x]);
-                        st4_bf16(a.out_act + (int64_t)r * half_cols + ep_j0 + fl, act);
-                        if (F8 == 1 && a.out_q) {
-                            // the half-wave holds the row's 128 activations of this tile = one 1x128 block of fc2's
-                            // input: quantise the values as stored (bf16), as the stand-alone quantiser would
-                            const uint32_t a01 = pack_bf16(act[0], act[1]), a23 = pack_bf16(act[2], act[3]);
-                            float m = fmaxf(fmaxf(fabsf(bf16_lo(a01)), fabsf(bf16_hi(a01))), fmaxf(fabsf(bf16_lo(a23)), fabsf(bf16_hi(a23))));
+                    for (int x0 = 0; x0 < RPW; x0 += 8) {
+                        f32x4_t vb[8];
 #pragma unroll
-                            for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-                            const float sa = block_scale(m);
-                            ((uint32_t*)(a.out_q + (int64_t)r * half_cols))[(ep_j0 + fl) >> 2] =
-                                cvt4_e4m3(bf16_lo(a01), bf16_hi(a01), bf16_lo(a23), bf16_hi(a23), sa);
-                            if ((lane & 31) == 0) a.out_q_scale[(int64_t)r * (half_cols / 128) + ep_j0 / 128] = sa;
+                        for (int u = 0; u < 8; ++u) vb[u] = *(const f32x4_t*)(stg + (wave * RPW + x0 + u) * STG_PITCH + cl);
+                        // plain store of 8 whole rows (the common case): no test or branch per row, one address chain
+                        const int rr0 = wave * RPW + x0;
+                        const int r0 = ep_i0 + (rr0 >> 5) * 128 + i * 32 + (rr0 & 31);  // the 8 rows are consecutive
+                        if (EPI == GG_EPI_STORE && !a.accumulate && r0 + 8 <= ep_i_end) {
+                            if (c < J) {
+                                const int64_t ld = (MODE == GG_WGRAD) ? K : J;
+                                const int64_t base = (MODE == GG_WGRAD) ? ((int64_t)ep_e * N + r0) * K : (int64_t)r0 * J;
+                                if (OUT_F32) {
+                                    float* o = (float*)a.out + base + c;
+#pragma unroll
+                                    for (int u = 0; u < 8; ++u) *(f32x4_t*)(o + u * ld) = vb[u];
+                                } else {
+                                    bf16_t* o = (bf16_t*)a.out + base + c;
+#pragma unroll
+                                    for (int u = 0; u < 8; ++u) {
+                                        const float t4[4] = {vb[u][0], vb[u][1], vb[u][2], vb[u][3]};
+                                        st4_bf16(o + u * ld, t4);
+                                    }
+                                }
+                            }
+                        } else {
+#pragma unroll
+                            for (int u = 0; u < 8; ++u) out_row(x0 + u, Z_EARLY && x0 == 0, true, vb[u]);
                         }
                     }
                 }
+                if (EPI == GG_EPI_SWIGLU) {
+                    // activation: a lane pairs gate and up of 4 features; two tile rows per instruction
+                    const int fl = (lane & 31) * 4;
+#pragma unroll(FP8 ? 1 : 4)
+                    for (int x4 = 0; x4 < RPW / 2; ++x4) {
+                        const int rr = wave * RPW + 2 * x4 + (lane >> 5);
+                        const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
+                        if (r < ep_i_end && ep_j0 + fl < half_cols) {  // uniform over a half-wave when N % 256 == 0 (fp8)
+                            const f32x4_t gt = *(const f32x4_t*)(stg + rr * STG_PITCH + fl);
+                            const f32x4_t up = *(const f32x4_t*)(stg + rr * STG_PITCH + 128 + fl);
+                            float act[4];
+                            const float pr = a.row_prob ? a.row_prob[r] : 1.0f;
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) act[x] = pr * (gt[x] * sigmoid_f(gt[x]) * up[x]);
+                            st4_bf16(a.out_act + (int64_t)r * half_cols + ep_j0 + fl, act);
+                            if (F8 == 1 && a.out_q) {
+                                // the half-wave holds the row's 128 activations of this tile = one 1x128 block of fc2's
+                                // input: quantise the values as stored (bf16), as the stand-alone quantiser would
+                                const uint32_t a01 = pack_bf16(act[0], act[1]), a23 = pack_bf16(act[2], act[3]);
+                                float m = fmaxf(fmaxf(fabsf(bf16_lo(a01)), fabsf(bf16_hi(a01))), fmaxf(fabsf(bf16_lo(a23)), fabsf(bf16_hi(a23))));
+#pragma unroll
+                                for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+                                const float sa = block_scale(m);
+                                ((uint32_t*)(a.out_q + (int64_t)r * half_cols))[(ep_j0 + fl) >> 2] =
+                                    cvt4_e4m3(bf16_lo(a01), bf16_hi(a01), bf16_lo(a23), bf16_hi(a23), sa);
+                                if ((lane & 31) == 0) a.out_q_scale[(int64_t)r * (half_cols / 128) + ep_j0 / 128] = sa;
+                            }
+                        }
+                    }
+                }
+                wait_lgkm0();
+                stage_barrier();  // the staging rows are rewritten by the next pass (or the next tile's stage 1)
             }
-            wait_lgkm0();
-            stage_barrier();  // the staging rows are rewritten by the next pass (or the next tile's stage 1)
+        }
+        if (LATE_SETUP && t_next < total_tiles) {
+            setup_tile(t_next);
+            issue_stage0();
         }
         t = t_next;
     }

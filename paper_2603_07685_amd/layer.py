@@ -126,7 +126,7 @@ class LayerState:
         self.dW2 = torch.empty((E, h, f), dtype=wdt, device=dev)
         if self.eq2:
             self.row_prob = torch.empty(Rcap, dtype=f32, device=dev)
-            self.dprob_parts = (f + 255) // 256
+            self.dprob_parts = 2 * ((f + 255) // 256)   # two partial sums per 256-column tile of the fc2 data gradient
             self.dprob_part = torch.empty((Rcap, self.dprob_parts), dtype=f32, device=dev)
         self.mx = bool(cfg.mx)                    # MXFP8: 1x32 blocks, E8M0 scales, scaling by the matrix instruction
         self.fp8 = bool(cfg.fp8) or self.mx       # one-byte operands in the forward / data-gradient GEMMs
