@@ -125,6 +125,16 @@ def describe_call(name, args, st):
         n = R * cols
         src = "tokens" if args[1] is st.X else "dY"
         return f"mx_quantize_gather_{src}[{args[6]}x{cols}]", None, T * cols * 2 + n * 2 + n // 16 + R * 4
+    if name == "moe_fp8_quantize_rowcol":  # read bf16 once, write one or two one-byte copies and their scales
+        rows, cols, live = args[2], args[3], args[4]
+        n = (R if live is not None else rows) * cols
+        copies = (args[5] is not None) + (args[7] is not None)
+        return f"fp8_quantize_rowcol[{rows}x{cols},{copies}]", None, n * (2 + copies) + copies * (n // 128) * 4
+    if name == "moe_fp8_quantize_rowcol_gather":
+        cols = args[7]
+        n = R * cols
+        src = "tokens" if args[1] is st.X else "dY"
+        return f"fp8_quantize_gather_{src}[{args[6]}x{cols}]", None, T * cols * 2 + n * 2 + (n // 128) * 8 + R * 4
     if name == "moe_fp8_quantize":
         block, groups, rows, cols, live = args[2], args[3], args[4], args[5], args[6]
         rows_alg = R if live is not None else rows          # grouped row tensors: only the routed rows count
@@ -133,7 +143,7 @@ def describe_call(name, args, st):
     return name, None, None
 
 
-HOOKED = ["moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_mx_quantize_rowcol_gather", "moe_route_topk", "moe_route_topk_grouped", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
+HOOKED = ["moe_fp8_quantize_rowcol", "moe_fp8_quantize_rowcol_gather", "moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_mx_quantize_rowcol_gather", "moe_route_topk", "moe_route_topk_grouped", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
           "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
           "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted",
           "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gather_row_prob",

@@ -385,6 +385,28 @@ moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X, moe_qbloc
                             int groups, int64_t rows, int cols, const int32_t* rows_dev,
                             void* q, float* scale);
 
+/*
+ * Both copies of a row-indexed tensor in one pass over it (Sec. 5.3.3: a tensor that two GEMMs read with
+ * different contraction dimensions is quantised once per direction; Sec. 5.4.2: one grouped launch for all
+ * experts): (q_row, scale_row) as MOE_Q_1x128, (q_col, scale_col) as MOE_Q_128x1, bit for bit.  Either pair may
+ * be NULL to make only the other copy.  rows and cols must be multiples of 128; rows_dev as above (whole tiles
+ * of 128 rows that start below *rows_dev are quantised).
+ * _gather: the same for a tensor that is never stored in bf16 (quantisation fused into the permute, padding
+ * included, and into the backward of the combine: Sec. 5.4.1, 5.4.2):
+ *   V[r,:] = X[s / k, :] with s = src_of[r]                         (pair_scale == NULL: the permuted tokens)
+ *   V[r,:] = bf16(pair_scale[s] * X[s / k, :]), product in fp32     (pair_scale [T*k]: dO = p * dY)
+ *   V[r,:] = 0 where src_of[r] < 0 (padding rows)
+ * X [T,cols] bf16, src_of [rows] as moe_permute returns it (call it with X = Xp = NULL for the maps alone),
+ * rows = Rcap, k <= 32; `groups` (>= 1, normally E) only steers the order in which the row tiles are visited.
+ */
+moe_status moe_fp8_quantize_rowcol(moe_ctx* ctx, void* stream, const void* X, int64_t rows, int cols,
+                                   const int32_t* rows_dev, void* q_row, float* scale_row,
+                                   void* q_col, float* scale_col);
+moe_status moe_fp8_quantize_rowcol_gather(moe_ctx* ctx, void* stream, const void* X, const int32_t* src_of, int k,
+                                          const float* pair_scale, int groups, int64_t rows, int cols,
+                                          const int32_t* rows_dev, void* q_row, float* scale_row,
+                                          void* q_col, float* scale_col);
+
 /* ------------------------------------------------------------------------- */
 /* MXFP8 quantisation (Sec. 5.3.3): E4M3 elements, 1x32 blocks, E8M0 scales    */
 /* ------------------------------------------------------------------------- */

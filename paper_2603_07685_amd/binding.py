@@ -30,6 +30,7 @@ EXPORTS = [
     "moe_route_topk_bwd", "moe_mx_quantize", "moe_mx_quantize_rowcol",
     "moe_route_topk_grouped", "moe_aux_loss", "moe_mx_quantize_rowcol_gather",
     "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gate_gemm", "moe_permute_static",
+    "moe_fp8_quantize_rowcol", "moe_fp8_quantize_rowcol_gather",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -72,6 +73,8 @@ def lib() -> C.CDLL:
         L.moe_mx_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_fwd_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_dgrad_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.moe_fp8_quantize_rowcol.argtypes = [_vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _vp, _vp]
+        L.moe_fp8_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_gate_gemm.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
         L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
@@ -258,3 +261,15 @@ def moe_mx_quantize_rowcol_gather(ctx, X, src_of, k, pair_scale, groups, rows, c
 def moe_fp8_quantize(ctx, X, block, groups, rows, cols, rows_dev, q, scale):
     ctx.check(lib().moe_fp8_quantize(ctx.h, _stream(), _ptr(X), block, groups, rows, cols, _ptr(rows_dev), _ptr(q),
                                      _ptr(scale)), "moe_fp8_quantize")
+
+
+def moe_fp8_quantize_rowcol(ctx, X, rows, cols, rows_dev, q_row, scale_row, q_col, scale_col):
+    ctx.check(lib().moe_fp8_quantize_rowcol(ctx.h, _stream(), _ptr(X), rows, cols, _ptr(rows_dev), _ptr(q_row),
+                                            _ptr(scale_row), _ptr(q_col), _ptr(scale_col)), "moe_fp8_quantize_rowcol")
+
+
+def moe_fp8_quantize_rowcol_gather(ctx, X, src_of, k, pair_scale, groups, rows, cols, rows_dev, q_row, scale_row, q_col,
+                                   scale_col):
+    ctx.check(lib().moe_fp8_quantize_rowcol_gather(ctx.h, _stream(), _ptr(X), _ptr(src_of), k, _ptr(pair_scale), groups, rows,
+                                                   cols, _ptr(rows_dev), _ptr(q_row), _ptr(scale_row), _ptr(q_col),
+                                                   _ptr(scale_col)), "moe_fp8_quantize_rowcol_gather")

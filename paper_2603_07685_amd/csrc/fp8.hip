@@ -123,6 +123,10 @@ __global__ __launch_bounds__(256) void quant_128x128_kernel(const u32x4_t* __res
     for (int it = 0; it < 8; ++it) q[base + (int64_t)(it * 16 + tr) * vpr] = cvt8_e4m3(v[it], s);
 }
 
+static moe_status fp8_rowcol_launch(moe_ctx* ctx, hipStream_t s, const char* who, const void* X, int64_t rows, int cols,
+                                    const int32_t* rows_dev, void* q_row, float* s_row, void* q_col, float* s_col,
+                                    const int32_t* src_of, int k, const float* pair_scale, int groups);
+
 extern "C" moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X, moe_qblock block,
                                        int groups, int64_t rows, int cols, const int32_t* rows_dev,
                                        void* q, float* scale) {
@@ -147,6 +151,12 @@ extern "C" moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X
         case MOE_Q_128x1: {
             if (rows % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(128x1): rows %% 128 != 0");
             if (groups != 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize(128x1): groups must be 1");
+            if (cols % 128 == 0) {  // the tiled kernel below: the same bits at about twice the rate
+                moe_status st = fp8_rowcol_launch(ctx, s, "moe_fp8_quantize(128x1)", X, rows, cols, rows_dev, nullptr, nullptr, q, scale,
+                                                  nullptr, 1, nullptr, 1);
+                if (st != MOE_OK) return st;
+                break;
+            }
             const int64_t npanels = (rows / 128) * ceil_div64(cols / 8, 64);
             int64_t grid = ceil_div64(npanels, 4);
             if (grid > (int64_t)cu * 16) grid = (int64_t)cu * 16;
@@ -167,6 +177,169 @@ extern "C" moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X
             MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize: bad block kind");
     }
     MOE_LAUNCH_CHECK(ctx, "moe_fp8_quantize");
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Blockwise recipe, row- and column-wise copies in one pass (Sec. 5.3.3: a tensor that two GEMMs read with different
+// contraction dimensions is quantised once per direction; Sec. 5.4.2: one grouped launch; Sec. 5.4.1: padding and
+// the permutation fused in).  A 256-thread workgroup owns a tile of 128 rows x 128 columns: exactly one 1x128 block
+// of each of its rows and one 128x1 block of each of its columns.  Wave w owns rows 32 w .. 32 w + 31; a lane reads
+// eight 16-byte pieces: piece i is row 32 w + 4 i + lane / 16, columns 8 (lane % 16) .. + 7.
+//   row-wise : the block is the 16 lanes of one piece (four butterfly steps);
+//   col-wise : the block is the same element of the lane's 8 pieces, of the 4 lanes 16 apart and of the 4 waves
+//              (maxima meet in LDS).
+// Either copy may be switched off (q_row or q_col NULL).  GATHER: row r of the input is pair_scale[s] * X[s / k, :]
+// rounded to bf16 (no scale, no rounding when pair_scale is NULL) with s = src_of[r], zero where s < 0.
+// Scales and codes are formed exactly as in the single-direction kernels above (amax / 448, fp32 division,
+// hardware conversion), so both copies are bit-identical to theirs.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t scale2_bf16_bw(uint32_t w, float sc) { return pack_bf16(sc * bf16_lo(w), sc * bf16_hi(w)); }
+
+template <bool GATHER>
+__global__ __launch_bounds__(256) void fp8_quant_rowcol_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
+                                                               const int32_t* __restrict__ rows_dev,
+                                                               const int32_t* __restrict__ src_of, uint64_t k_magic,
+                                                               const float* __restrict__ pair_scale, int groups,
+                                                               u32x2_t* __restrict__ q_row, float* __restrict__ s_row,
+                                                               u32x2_t* __restrict__ q_col, float* __restrict__ s_col) {
+    __shared__ float cmax[4][128];
+    const int64_t live = rows_dev ? min((int64_t)*rows_dev, rows) : rows;
+    const int ctiles = cols / 128;
+    int64_t rt = blockIdx.x / ctiles;
+    const int ct = blockIdx.x % ctiles;
+    if (GATHER && groups > 1) {  // row tiles expert-interleaved: the k copies of a token are read close together in time
+        const int64_t S = (rows / 128 + groups - 1) / groups;
+        rt = (rt % groups) * S + rt / groups;
+    }
+    const int64_t row0 = rt * 128;
+    if (row0 >= live || row0 >= rows) return;  // uniform over the workgroup
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int vpr = cols / 8;
+    const int64_t v0 = (row0 + wave * 32 + (lane >> 4)) * vpr + ct * 16 + (lane & 15);
+    u32x4_t x[8];
+    if (GATHER) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int32_t sidx = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
+            x[i] = u32x4_t{0, 0, 0, 0};
+            if (sidx >= 0) {
+                const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx * k_magic) >> 40);  // sidx / k, exact below 2^31
+                x[i] = X[tok * vpr + ct * 16 + (lane & 15)];
+                if (pair_scale) {
+                    const float sc = pair_scale[sidx];
+                    x[i] = u32x4_t{scale2_bf16_bw(x[i].x, sc), scale2_bf16_bw(x[i].y, sc), scale2_bf16_bw(x[i].z, sc),
+                                   scale2_bf16_bw(x[i].w, sc)};
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = X[v0 + (int64_t)i * 4 * vpr];
+    }
+    if (q_col) {  // (first: the other waves' maxima are on their way while this wave converts its rows)
+        float m[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) m[c] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            m[0] = fmaxf(m[0], fabsf(bf16_lo(x[i].x))); m[1] = fmaxf(m[1], fabsf(bf16_hi(x[i].x)));
+            m[2] = fmaxf(m[2], fabsf(bf16_lo(x[i].y))); m[3] = fmaxf(m[3], fabsf(bf16_hi(x[i].y)));
+            m[4] = fmaxf(m[4], fabsf(bf16_lo(x[i].z))); m[5] = fmaxf(m[5], fabsf(bf16_hi(x[i].z)));
+            m[6] = fmaxf(m[6], fabsf(bf16_lo(x[i].w))); m[7] = fmaxf(m[7], fabsf(bf16_hi(x[i].w)));
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            m[c] = fmaxf(m[c], __shfl_xor(m[c], 16));
+            m[c] = fmaxf(m[c], __shfl_xor(m[c], 32));
+            if (lane < 16) cmax[wave][8 * lane + c] = m[c];
+        }
+    }
+    if (q_row) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float m = amax8(x[i]);
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+            const float sc = block_scale(m);
+            q_row[v0 + (int64_t)i * 4 * vpr] = cvt8_e4m3(x[i], sc);
+            if ((lane & 15) == 0) s_row[(row0 + wave * 32 + 4 * i + (lane >> 4)) * ctiles + ct] = sc;
+        }
+    }
+    if (q_col) {
+        __syncthreads();
+        float sc[8];
+        const int cb = 8 * (lane & 15);
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            sc[c] = block_scale(fmaxf(fmaxf(cmax[0][cb + c], cmax[1][cb + c]), fmaxf(cmax[2][cb + c], cmax[3][cb + c])));
+        if (wave == 0 && lane < 16) {
+            f32x4_t* sd = (f32x4_t*)(s_col + rt * cols + ct * 128 + cb);
+            sd[0] = f32x4_t{sc[0], sc[1], sc[2], sc[3]};
+            sd[1] = f32x4_t{sc[4], sc[5], sc[6], sc[7]};
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float v[8] = {bf16_lo(x[i].x), bf16_hi(x[i].x), bf16_lo(x[i].y), bf16_hi(x[i].y),
+                          bf16_lo(x[i].z), bf16_hi(x[i].z), bf16_lo(x[i].w), bf16_hi(x[i].w)};
+#pragma unroll
+            for (int c = 0; c < 8; ++c) v[c] = __builtin_fminf(__builtin_fmaxf(v[c] / sc[c], -448.0f), 448.0f);
+            int w0 = 0, w1 = 0;
+            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], w0, false);
+            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], w0, true);
+            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(v[4], v[5], w1, false);
+            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(v[6], v[7], w1, true);
+            q_col[v0 + (int64_t)i * 4 * vpr] = u32x2_t{(uint32_t)w0, (uint32_t)w1};
+        }
+    }
+}
+
+static moe_status fp8_rowcol_launch(moe_ctx* ctx, hipStream_t s, const char* who, const void* X, int64_t rows, int cols,
+                                    const int32_t* rows_dev, void* q_row, float* s_row, void* q_col, float* s_col,
+                                    const int32_t* src_of, int k, const float* pair_scale, int groups) {
+    if (rows % 128 || cols % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: rows and cols must be multiples of 128", who);
+    if ((q_row == nullptr) != (s_row == nullptr) || (q_col == nullptr) != (s_col == nullptr) || (!q_row && !q_col))
+        MOE_FAIL(ctx, MOE_ERR_ARG, "%s: codes and scales of a copy go together, and at least one copy is needed", who);
+    if (groups < 1) groups = 1;
+    const int64_t tiles_r = src_of ? (rows / 128 + groups - 1) / groups * groups : rows / 128;
+    const int64_t nblk = tiles_r * (cols / 128);
+    if (nblk > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: too many tiles", who);
+    if (src_of)
+        hipLaunchKernelGGL(fp8_quant_rowcol_kernel<true>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
+                           rows_dev, src_of, ((1ull << 40) + k - 1) / k, pair_scale, groups, (u32x2_t*)q_row, s_row,
+                           (u32x2_t*)q_col, s_col);
+    else
+        hipLaunchKernelGGL(fp8_quant_rowcol_kernel<false>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
+                           rows_dev, nullptr, 0, nullptr, 1, (u32x2_t*)q_row, s_row, (u32x2_t*)q_col, s_col);
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_fp8_quantize_rowcol(moe_ctx* ctx, void* stream, const void* X, int64_t rows, int cols,
+                                              const int32_t* rows_dev, void* q_row, float* scale_row,
+                                              void* q_col, float* scale_col) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!X) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize_rowcol: NULL pointer");
+    if (rows < 0 || cols < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize_rowcol: bad sizes");
+    if (rows == 0) return MOE_OK;
+    moe_status st = fp8_rowcol_launch(ctx, (hipStream_t)stream, "moe_fp8_quantize_rowcol", X, rows, cols, rows_dev, q_row,
+                                      scale_row, q_col, scale_col, nullptr, 1, nullptr, 1);
+    if (st != MOE_OK) return st;
+    MOE_LAUNCH_CHECK(ctx, "moe_fp8_quantize_rowcol");
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_fp8_quantize_rowcol_gather(moe_ctx* ctx, void* stream, const void* X, const int32_t* src_of, int k,
+                                                     const float* pair_scale, int groups, int64_t rows, int cols,
+                                                     const int32_t* rows_dev, void* q_row, float* scale_row,
+                                                     void* q_col, float* scale_col) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (!X || !src_of) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize_rowcol_gather: NULL pointer");
+    if (rows < 0 || cols < 1 || k < 1 || k > 32 || groups < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_fp8_quantize_rowcol_gather: bad sizes");
+    if (rows == 0) return MOE_OK;
+    moe_status st = fp8_rowcol_launch(ctx, (hipStream_t)stream, "moe_fp8_quantize_rowcol_gather", X, rows, cols, rows_dev,
+                                      q_row, scale_row, q_col, scale_col, src_of, k, pair_scale, groups);
+    if (st != MOE_OK) return st;
+    MOE_LAUNCH_CHECK(ctx, "moe_fp8_quantize_rowcol_gather");
     return MOE_OK;
 }
 

@@ -46,10 +46,7 @@ class LayerState:
                  fp8_wgrad: bool | None = None):
         self.cfg = cfg
         self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.1.2): weights applied before fc2
-        # MXFP8 only (default there): the permuted tokens and the combine's backward are quantised straight from
-        # X / dY through the row map, padding included (Sec. 5.4.1, 5.4.2); Xp and dO are never stored in bf16
-        self.fused_quant = bool(cfg.mx) if fused_quant is None else bool(fused_quant)
-        assert not self.fused_quant or cfg.mx, "fused quantisation is built for the MXFP8 path"
+        self.fused_quant = None if fused_quant is None else bool(fused_quant)   # (resolved below, once fp8_wgrad is known)
         # blockwise fp8 (default there): the SwiGLU / SwiGLU-backward epilogues also emit the 1x128 codes of their
         # output, the next GEMM's operand (Sec. 5.4.2); off = stand-alone quantiser launches
         self.epilogue_quant = bool(cfg.fp8) and not cfg.mx if epilogue_quant is None else bool(epilogue_quant)
@@ -60,6 +57,13 @@ class LayerState:
         self.fp8_wgrad = (bool(cfg.fp8) and not cfg.mx) if fp8_wgrad is None else bool(fp8_wgrad)
         assert not self.fp8_wgrad or (cfg.fp8 and not cfg.mx and cfg.align % 128 == 0), \
             "blockwise fp8 weight gradients need the blockwise config with experts padded to 128 rows"
+        # one-byte recipes whose weight gradients run on one-byte operands too: the permuted tokens and the combine's
+        # backward are quantised straight from X / dY through the row map, in both directions, padding included
+        # (Sec. 5.4.1, 5.4.2); Xp and dO are never stored in bf16
+        if self.fused_quant is None:
+            self.fused_quant = bool(cfg.mx) or self.fp8_wgrad
+        assert not self.fused_quant or cfg.mx or self.fp8_wgrad, \
+            "fused quantisation needs a recipe that keeps no bf16 copy for the weight gradients"
         T, k, E, h, f = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f
         self.sf = sf = cfg.shared_f if shared_f is None else shared_f
         self.align = cfg.align
@@ -201,15 +205,21 @@ class LayerState:
         same pass the second copy, quantised down the rows, for the weight gradient)."""
         if self.mx:
             B.moe_mx_quantize_rowcol(self.ctx, X, rows, cols, live, q, s, qc, sc)
+        elif self.fp8_wgrad:
+            B.moe_fp8_quantize_rowcol(self.ctx, X, rows, cols, live, q, s, qc, sc)
         else:
             B.moe_fp8_quantize(self.ctx, X, B.Q_1x128, 1, rows, cols, live, q, s)
-            self._q_cols(X, qc, sc, rows, cols, live)
+
+    def _q_gather(self, X, pair_scale, groups, rows, cols, q, s, qc, sc):
+        """Both quantised copies of X's rows taken through the row map (the permuted tokens, or p * dY)."""
+        fn = B.moe_mx_quantize_rowcol_gather if self.mx else B.moe_fp8_quantize_rowcol_gather
+        fn(self.ctx, X, self.src_of, self.cfg.k, pair_scale, groups, rows, cols, self.live_rows, q, s, qc, sc)
 
     def _q_cols(self, X, qc, sc, rows, cols, live=None):
         """Blockwise recipe: the weight-gradient copy of a row-indexed tensor, 128x1 tiles down the rows (a tensor that
         two GEMMs read with different contraction dimensions is quantised once per direction, Sec. 5.3.3 / 5.4.1)."""
         if self.fp8_wgrad and not self.mx:
-            B.moe_fp8_quantize(self.ctx, X, B.Q_128x1, 1, rows, cols, live, qc, sc)
+            B.moe_fp8_quantize_rowcol(self.ctx, X, rows, cols, live, None, None, qc, sc)
 
     def _q_weight(self, W, q, s, qd=None, sd=None):
         """Quantise a weight stack for the forward GEMM (and, MXFP8, the second copy for the data gradient)."""
@@ -308,8 +318,7 @@ class LayerState:
         self._q_weight(self.W1, self.qW1, self.sW1, self.qW1d, self.sW1d)
         self._q_weight(self.W2, self.qW2, self.sW2, self.qW2d, self.sW2d)
         if self.fused_quant:
-            B.moe_mx_quantize_rowcol_gather(c, self.X, self.src_of, k, None, E, Rcap, h, self.live_rows,
-                                            self.qXp, self.sXp, self.qXpc, self.sXpc)
+            self._q_gather(self.X, None, E, Rcap, h, self.qXp, self.sXp, self.qXpc, self.sXpc)
         else:
             self._q_rows(self.Xp, self.qXp, self.sXp, Rcap, h, self.live_rows, self.qXpc, self.sXpc)
         row_prob = None
@@ -352,8 +361,7 @@ class LayerState:
             if not self.eq2:
                 B.moe_unpermute_combine_bwd(c, self.dY, self.O, B.BF16, self.row_of, self.src_of, self.topk_prob,
                                             T, k, h, Rcap, None, self.dprob)
-            B.moe_mx_quantize_rowcol_gather(c, self.dY, self.src_of, k, None if self.eq2 else self.topk_prob, E, Rcap, h,
-                                            self.live_rows, self.qdO, self.sdO, self.qdOc, self.sdOc)
+            self._q_gather(self.dY, None if self.eq2 else self.topk_prob, E, Rcap, h, self.qdO, self.sdO, self.qdOc, self.sdOc)
         else:
             if self.eq2:
                 B.moe_unpermute_combine_bwd(c, self.dY, None, B.BF16, self.row_of, self.src_of, None,

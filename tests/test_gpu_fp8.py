@@ -75,6 +75,86 @@ def test_quantize_128x1_and_rows_dev(B, ctx, oracle):
     assert np.array_equal(s2.cpu().numpy()[:3], so[:3]) and (s2[3:] == -1.0).all()
 
 
+@pytest.mark.parametrize("rows,cols", [(256, 384), (640, 128), (1024, 2048)])
+def test_quantize_rowcol_bit_exact(B, ctx, oracle, rows, cols):
+    """Both blockwise copies from one pass over the input: each equal, bit for bit, to the oracle's separate 1x128 and
+    128x1 quantisers; either copy alone; with a live-row count on the device, whole 128-row tiles beyond it are left
+    alone; MOE_Q_128x1 through moe_fp8_quantize gives the same bits."""
+    from gpu_util import dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(rows * 7 + cols)
+    Xh = wl.bf16_round((g.standard_normal((rows, cols)) * np.exp(g.normal(size=(rows, cols)) * 2)).astype(np.float32))
+    Xh[3, :128] = 0.0                      # an all-zero 1x128 block: scale 1, codes 0
+    Xh[128:256, 5] = 0.0                   # an all-zero 128x1 block
+    Xh[70, 40] = 448.0
+    qr_o, sr_o = oracle.fp8_quant_1x128(Xh)
+    qc_o, sc_o = oracle.fp8_quant_128x1(Xh)
+    X = dev_bf16(Xh)
+    for live_rows in (None, (rows // 256) * 128):
+        qr = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+        sr = torch.zeros((rows, cols // 128), dtype=torch.float32, device="cuda")
+        qc = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+        sc = torch.zeros((rows // 128, cols), dtype=torch.float32, device="cuda")
+        live = None if live_rows is None else torch.tensor([live_rows], dtype=torch.int32, device="cuda")
+        B.moe_fp8_quantize_rowcol(ctx, X, rows, cols, live, qr, sr, qc, sc)
+        torch.cuda.synchronize()
+        n = rows if live_rows is None else live_rows
+        assert np.array_equal(qr.cpu().numpy()[:n], qr_o[:n]) and np.array_equal(sr.cpu().numpy()[:n], sr_o[:n])
+        assert np.array_equal(qc.cpu().numpy()[:n], qc_o[:n]) and np.array_equal(sc.cpu().numpy()[:n // 128], sc_o[:n // 128])
+        assert not qr[n:].any() and not qc[n:].any() and not sr[n:].any() and not sc[n // 128:].any()
+    # one copy at a time
+    qc = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+    sc = torch.zeros((rows // 128, cols), dtype=torch.float32, device="cuda")
+    B.moe_fp8_quantize_rowcol(ctx, X, rows, cols, None, None, None, qc, sc)
+    qr = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+    sr = torch.zeros((rows, cols // 128), dtype=torch.float32, device="cuda")
+    B.moe_fp8_quantize_rowcol(ctx, X, rows, cols, None, qr, sr, None, None)
+    q1, s1 = _quant(B, ctx, X, B.Q_128x1)
+    torch.cuda.synchronize()
+    assert np.array_equal(qc.cpu().numpy(), qc_o) and np.array_equal(sc.cpu().numpy(), sc_o)
+    assert np.array_equal(qr.cpu().numpy(), qr_o) and np.array_equal(sr.cpu().numpy(), sr_o)
+    assert np.array_equal(q1.cpu().numpy(), qc_o) and np.array_equal(s1.cpu().numpy(), sc_o)
+    with pytest.raises(B.MoeError):
+        B.moe_fp8_quantize_rowcol(ctx, X, rows, cols, None, qr, None, None, None)
+
+
+@pytest.mark.parametrize("with_scale", [False, True])
+def test_quantize_rowcol_gather_bit_exact(B, ctx, oracle, with_scale):
+    """Blockwise quantisation fused into the permute (padding rows included) and into the combine's backward: the
+    virtual tensor V[r] = (bf16(p[s] *)) X[s / k], s = src_of[r], zero where s < 0, quantised 1x128 and 128x1 without
+    being stored."""
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(21 + with_scale)
+    T, k, E, cols = 300, 3, 5, 384
+    idx = g.integers(0, E, size=(T, k)).astype(np.int32)
+    m = oracle.permute_maps(idx, E, 128, None)
+    Rcap = (T * k + E * 127 + 127) // 128 * 128
+    src = np.full(Rcap, -1, np.int32)
+    src[:len(m.src_of)] = m.src_of
+    R = int(m.offsets[-1])
+    Xh = wl.bf16_round((g.standard_normal((T, cols)) * np.exp(g.normal(size=(T, cols)))).astype(np.float32))
+    p = g.uniform(0.05, 1.0, size=T * k).astype(np.float32)
+    V = Xh[np.maximum(src, 0) // k]
+    if with_scale:
+        V = wl.bf16_round(p[np.maximum(src, 0)][:, None] * V)
+    V[src < 0] = 0
+    qr = torch.zeros((Rcap, cols), dtype=torch.uint8, device="cuda")
+    sr = torch.zeros((Rcap, cols // 128), dtype=torch.float32, device="cuda")
+    qc = torch.zeros((Rcap, cols), dtype=torch.uint8, device="cuda")
+    sc = torch.zeros((Rcap // 128, cols), dtype=torch.float32, device="cuda")
+    live = torch.tensor([R], dtype=torch.int32, device="cuda")
+    B.moe_fp8_quantize_rowcol_gather(ctx, dev_bf16(Xh), dev(src), k, dev(p) if with_scale else None, E if with_scale else 1,
+                                     Rcap, cols, live, qr, sr, qc, sc)
+    torch.cuda.synchronize()
+    qr_o, sr_o = oracle.fp8_quant_1x128(V)
+    qc_o, sc_o = oracle.fp8_quant_128x1(V)
+    assert np.array_equal(qr.cpu().numpy()[:R], qr_o[:R]) and np.array_equal(sr.cpu().numpy()[:R], sr_o[:R])
+    assert np.array_equal(qc.cpu().numpy()[:R], qc_o[:R]) and np.array_equal(sc.cpu().numpy()[:R // 128], sc_o[:R // 128])
+    assert (src[:R] < 0).any() and not qr.cpu().numpy()[:R][src[:R] < 0].any()      # padding rows: zero codes
+    assert not qr[R:].any() and not qc[R:].any()                                     # beyond the live rows: untouched
+
+
 def test_quantize_128x128_bit_exact(B, ctx, oracle):
     from gpu_util import dev_bf16
     from paper_2603_07685_amd import workloads as wl

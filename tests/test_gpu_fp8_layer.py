@@ -38,8 +38,8 @@ def test_fp8_layer_every_element(oracle, variant):
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS["C5S"]
     hin = L.host_inputs(cfg)
-    st = L.LayerState(cfg, hin, variant=variant)
-    assert st.fp8 and st.align == 128
+    st = L.LayerState(cfg, hin, variant=variant, fused_quant=False)      # (per-call checks read the bf16 Xp and dO)
+    assert st.fp8 and st.align == 128 and st.fp8_wgrad
     st.step()
     torch.cuda.synchronize()
     assert st.ctx.poll_error() == 0
@@ -110,7 +110,7 @@ def test_fp8_layer_eq2_per_call(oracle):
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS["C5S"]
     hin = L.host_inputs(cfg)
-    st = L.LayerState(cfg, hin, eq2=True)
+    st = L.LayerState(cfg, hin, eq2=True, fused_quant=False)
     st.step()
     torch.cuda.synchronize()
     assert st.ctx.poll_error() == 0
@@ -247,6 +247,49 @@ def test_mxfp8_fused_quantisation_is_bit_identical(oracle, eq2):
 
 
 @pytest.mark.parametrize("eq2", [False, True])
+def test_fp8_fused_quantisation_is_bit_identical(oracle, eq2):
+    """C5S, blockwise recipe: quantising the permuted tokens and the combine's backward straight from X / dY through
+    the row map, 1x128 and 128x1 in one pass, padding included (no bf16 Xp or dO), gives the GEMMs the very same codes
+    and scales, so every output of the step is bit-identical to the unfused path; the codes are checked against the
+    oracle's quantisers."""
+    from paper_2603_07685_amd import layer as L
+    from paper_2603_07685_amd import workloads as wl
+    cfg = wl.CONFIGS["C5S"]
+    hin = L.host_inputs(cfg)
+    a = L.LayerState(cfg, hin, eq2=eq2, fused_quant=False)
+    b = L.LayerState(cfg, hin, eq2=eq2)
+    assert b.fused_quant and b.fp8_wgrad and b.Xp is None and b.dO is None
+    for st in (a, b):
+        st.step()
+    torch.cuda.synchronize()
+    assert a.ctx.poll_error() == 0 and b.ctx.poll_error() == 0
+    R = int(a.offsets[-1].item())
+    for n in ["qXp", "sXp", "qXpc", "qdO", "sdO", "qdOc"]:
+        assert torch.equal(getattr(a, n)[:R], getattr(b, n)[:R]), n
+    for n in ["sXpc", "sdOc"]:
+        assert torch.equal(getattr(a, n)[:R // 128], getattr(b, n)[:R // 128]), n
+    for n in ["Y", "dX", "dW1", "dW2", "dprob", "dWs1", "dWs2", "Z", "dZ"]:
+        x, y = getattr(a, n), getattr(b, n)
+        assert torch.equal(x[:R] if n in ("Z", "dZ") else x, y[:R] if n in ("Z", "dZ") else y), n
+    idx = b.forced_idx.cpu().numpy()
+    m = oracle.permute_maps(idx, cfg.E, 128, b.Rcap)
+    Xp = oracle.permute_rows(hin["X"], m.src_of[:R], cfg.k)
+    qo, so = oracle.fp8_quant_1x128(Xp)
+    assert np.array_equal(b.qXp.cpu().numpy()[:R], qo) and np.array_equal(b.sXp.cpu().numpy()[:R], so)
+    qc, sc = oracle.fp8_quant_128x1(Xp)
+    assert np.array_equal(b.qXpc.cpu().numpy()[:R], qc) and np.array_equal(b.sXpc.cpu().numpy()[:R // 128], sc)
+    src = m.src_of[:R]
+    dO = hin["dY"].astype(np.float32)[np.maximum(src, 0) // cfg.k]
+    if not eq2:
+        dO = wl.bf16_round(dO * b.topk_prob.cpu().numpy().reshape(-1)[np.maximum(src, 0)][:, None])
+    dO[src < 0] = 0
+    qo, so = oracle.fp8_quant_1x128(dO)
+    assert np.array_equal(b.qdO.cpu().numpy()[:R], qo) and np.array_equal(b.sdO.cpu().numpy()[:R], so)
+    qc, sc = oracle.fp8_quant_128x1(dO)
+    assert np.array_equal(b.qdOc.cpu().numpy()[:R], qc) and np.array_equal(b.sdOc.cpu().numpy()[:R // 128], sc)
+
+
+@pytest.mark.parametrize("eq2", [False, True])
 def test_fp8_epilogue_quantisation_is_bit_identical(eq2):
     """C5S: the codes and scales the SwiGLU / SwiGLU-backward epilogues emit (routed and shared expert) equal those of
     the stand-alone 1x128 quantiser run on the stored bf16 tensor, so every output of the step is bit-identical."""
@@ -254,8 +297,8 @@ def test_fp8_epilogue_quantisation_is_bit_identical(eq2):
     from paper_2603_07685_amd import workloads as wl
     cfg = wl.CONFIGS["C5S"]
     hin = L.host_inputs(cfg)
-    a = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=False)
-    b = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=True)
+    a = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=False, fused_quant=False)
+    b = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=True, fused_quant=False)
     for st in (a, b):
         for n in ("qA", "sA", "qdZ", "sdZ", "qAs", "sAs", "qdZs", "sdZs"):
             getattr(st, n).zero_()

@@ -96,6 +96,9 @@ def test_full_size_sampled(oracle, name, variant):
             return dict(tol=FP8_TOL, reg=None, row_tol=3 * FP8_TOL)
         return dict(tol=BF16_TOL, reg=BF16_REG, row_tol=BF16_TOL)
 
+    # the row-wise quantiser of this config's recipe (for the layers that keep no bf16 copy of Xp and dO)
+    row_quant = oracle.mx_quant_1x32 if cfg.mx else oracle.fp8_quant_1x128
+    row_dequant = (lambda q, e: oracle.mx_dequant(q, e, "1x32")) if cfg.mx else (lambda q, e: oracle.fp8_dequant(q, e, "1x128"))
     worst = {}
 
     def chk(key, got, ref, tag, **kw):
@@ -125,7 +128,7 @@ def test_full_size_sampled(oracle, name, variant):
         if st.Xp is not None:
             assert np.array_equal(_f64(st.Xp[rt]), Xrows)                   # permuted rows are exact copies
         else:                                                               # quantised straight from X: the codes are exact
-            qo, eo = oracle.mx_quant_1x32(Xrows)
+            qo, eo = row_quant(Xrows)
             assert np.array_equal(st.qXp[rt].cpu().numpy(), qo) and np.array_equal(st.sXp[rt].cpu().numpy(), eo)
         Zref = oracle.grouped_gemm_nt(Xrows, W1, one(n))
         chk("Z", _f64(st.Z[rt]), Zref, tag)
@@ -134,7 +137,7 @@ def test_full_size_sampled(oracle, name, variant):
         chk("O", _f64(st.O[rt]), oracle.grouped_gemm_nt(Ag, W2, one(n)), tag)
         dOg, Zg = _f64(combine_bwd_rows(st, rt)), _f64(st.Z[rt])
         if st.dO is None:
-            qo, eo = oracle.mx_quant_1x32(dOg)
+            qo, eo = row_quant(dOg)
             assert np.array_equal(st.qdO[rt].cpu().numpy(), qo) and np.array_equal(st.sdO[rt].cpu().numpy(), eo)
         chk("dZ", _f64(st.dZ[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, one(n)), Zg), tag)
         chk("dXp", _f64(st.dXp[rt]), oracle.grouped_gemm_nn(_f64(st.dZ[rt]), W1, one(n)), tag)
@@ -198,9 +201,9 @@ def test_full_size_sampled(oracle, name, variant):
     if st.dO is not None:
         chk("dO", _f64(st.dO[flat]), dOref, "tokens")
     else:
-        # only the quantised copies of dO exist: dequantise what the GPU wrote (row-wise copy, one E8M0 scale per 32
-        # elements) and compare that with the oracle's dO, at the format's bound
-        deq = oracle.mx_dequant(st.qdO[flat].cpu().numpy(), st.sdO[flat].cpu().numpy(), "1x32")
+        # only the quantised copies of dO exist: dequantise what the GPU wrote (the row-wise copy) and compare that with
+        # the oracle's dO, at the format's bound
+        deq = row_dequant(st.qdO[flat].cpu().numpy(), st.sdO[flat].cpu().numpy())
         chk("dO", deq, dOref, "tokens, dequantised codes", tol=FP8_TOL, reg=None, row_tol=FP8_TOL)
     chk("dprob", st.dprob.cpu().numpy().astype(np.float64)[toks], dpref, "tokens", row_floor=0.05)
     chk("dX", _f64(st.dX[tt]), oracle.combine(dXpsub, local_rows, None, _f64(st.dXs[tt]) if st.sf else None), "tokens")
