@@ -18,11 +18,17 @@ void moe_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s) {
 }
 
 extern "C" size_t moe_workspace_bytes(int T, int k, int E, int h, int f_max) {
-    (void)h;
-    (void)f_max;
     if (T < 0 || k < 1 || E < 1) return 0;
-    size_t bytes = MOE_WS_RESERVED;
-    bytes += moe_permute_ws_bytes((int64_t)T * k, E);
+    // behind the reserved head the calls share one region (they are stream-ordered on a context): the row-ID map's
+    // per-chunk histograms, or the fp32 partial tiles of a weight gradient whose contraction is split under a skewed
+    // load: MOE_WS_SPLIT_SLICES copies of the larger of one expert's two weight gradients, in whole 256 x 256 tiles
+    size_t bytes = moe_permute_ws_bytes((int64_t)T * k, E);
+    if (h > 0 && f_max > 0) {
+        const size_t t1 = (size_t)((2 * (int64_t)f_max + 255) / 256) * (size_t)((h + 255) / 256);   // fc1: [2f, h]
+        const size_t split = (size_t)MOE_WS_SPLIT_SLICES * t1 * 256 * 256 * sizeof(float);
+        if (split > bytes) bytes = split;
+    }
+    bytes += MOE_WS_RESERVED;
     return (bytes + 255) / 256 * 256;
 }
 

@@ -63,6 +63,8 @@
 #endif
 #define GG_THREADS 512
 #define GG_MAX_E 1024
+#define GG_MAX_SPLIT 8          // most slices of partial tiles a weight-gradient call uses (workspace: that many fp32 copies of one expert's dW)
+#define GG_MAX_SPLIT_EXPERTS 4  // an expert is split into at least two pieces
 #define GG_ROWB 128                     // bytes of a k-major tile row per stage: one cache line
 #define GG_STAGE_BYTES (GG_BM * GG_ROWB)  // one operand tile per stage: 32 KB
 // k-major swizzle: two 128-byte rows share a 256-byte bank line; slot ^= bits 1..3 of the row makes
@@ -196,6 +198,10 @@ struct gg_args {
     uint8_t* out_q;
     float* out_q_scale;
     int* tile_counter;     // wgrad: zeroed device counter for the dynamic tile order under skewed loads (see the kernel)
+    // wgrad, bf16: deterministic split of the contraction for experts far above the mean load (see the kernel)
+    int split_cap;         // how many expert-sized slices of fp32 partial tiles `partials` can hold (0: never split)
+    float* partials;       // [split_cap][tiles per expert][256 x 256] fp32
+    int* split_info;       // [1 + 3 * GG_MAX_SPLIT_EXPERTS]: count, then (expert, pieces, first slice) for the reduce kernel
     float* dprob_part;     // eq. (2), dgrad SWIGLU_BWD: [Rcap, 2 ceil(K/256)] partial <dA, act(Z)> per row, two per column tile
 };
 
@@ -246,6 +252,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     __shared__ int offs[GG_MAX_E + 1];
     __shared__ int tile_start[GG_MAX_E + 1];
     __shared__ int dyn_next;
+    // weight gradient with a split contraction: sorted position -> first work item, and (pieces | first slice << 8)
+    __shared__ int item_start[(MODE == GG_WGRAD && NW == 4) ? GG_MAX_E + 1 : 1];
+    __shared__ int split_of[(MODE == GG_WGRAD && NW == 4) ? GG_MAX_E : 1];
+    constexpr bool SPLITK = MODE == GG_WGRAD && NW == 4;
 
     constexpr bool P_CMAJ = (MODE == GG_WGRAD);
     constexpr bool Q_CMAJ = (MODE != GG_FWD);
@@ -290,6 +300,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             tile_start[rank] = e;
         }
     }
+    if (SPLITK) __syncthreads();  // (thread 0 walks the sorted experts below)
     if (tid == 0) {
         int run = 0;
         bool bad = offs[0] < 0 || offs[E] > a.Rcap;
@@ -304,9 +315,51 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             else run += rows > 0 ? ((rows + GG_BM - 1) / GG_BM) * tiles_j : 0;
         }
         tile_start[E] = run;
+        if (SPLITK) {
+            // Deterministic split of the contraction (Sec. 4.3.1 names the imbalance it answers).  Under a skewed load
+            // one tile of the largest expert can be most of a workgroup's share; such experts are cut into pieces of
+            // about the mean expert's row count (whole stages), each piece is a work item of its own that leaves its
+            // 256 x 256 result as an fp32 partial tile in the workspace, and a second kernel adds the pieces of a tile
+            // in increasing order: the same sums in the same order whatever the timing.  Decided here, from the
+            // offsets alone and identically in every workgroup: experts in descending size, pieces = rows / mean
+            // rounded up for experts above twice the mean, while the workspace has slices left.
+            const int tpe = tiles_i_w * tiles_j;
+            const int64_t rows_all = offs[E] - offs[0];
+            const int emax = tile_start[0];
+            const bool skew = !bad && a.split_cap >= 2 && (int64_t)(offs[emax + 1] - offs[emax]) * E > 2 * rows_all;
+            const int mean = (int)((rows_all / E + 127) / 128 * 128);
+            int used = 0, nsplit = 0, items = 0;
+            for (int i = 0; i < E; ++i) {
+                const int ee = tile_start[i];
+                const int rows = offs[ee + 1] - offs[ee];
+                int pieces = 1;
+                if (skew && mean > 0 && rows > 2 * mean && nsplit < GG_MAX_SPLIT_EXPERTS) {
+                    pieces = min((rows + mean - 1) / mean, a.split_cap - used);
+                    if (pieces < 2) pieces = 1;
+                }
+                item_start[i] = items;
+                split_of[i] = pieces | (used << 8);
+                if (pieces > 1) {
+                    if (blockIdx.x == 0) {
+                        a.split_info[1 + 3 * nsplit] = ee;
+                        a.split_info[2 + 3 * nsplit] = pieces;
+                        a.split_info[3 + 3 * nsplit] = used;
+                    }
+                    used += pieces;
+                    ++nsplit;
+                }
+                items += pieces * tpe;
+            }
+            item_start[E] = items;
+            if (blockIdx.x == 0) a.split_info[0] = nsplit;
+            tile_start[E] = items;
+        }
         if (bad) {  // inconsistent offsets: touch no tensor memory, raise the error word
             tile_start[E] = 0;
-            if (blockIdx.x == 0) atomicExch(a.dev_err, 1);
+            if (blockIdx.x == 0) {
+                atomicExch(a.dev_err, 1);
+                if (SPLITK) a.split_info[0] = 0;
+            }
         }
     }
     __syncthreads();
@@ -402,6 +455,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     bool pf_on = false, pf_q = false;
     int KT_pf = 0;
     int e_hint = 0;
+    int part_slot = -1, part_tile = 0;  // split contraction: slice and tile of the partial result (-1: the result itself)
     auto setup_tile = [&](int t) __attribute__((always_inline)) {
         // (four waves: the lane constants of the set-up are formed here from a lane id the compiler cannot see through;
         // computed once at kernel start they would occupy registers through every stage loop, or spill)
@@ -410,7 +464,22 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         const int km_row = lane >> 3, cm_row = lane / CM_SLOTS;
         // ---- locate the tile: bands of GG_BAND row-tiles, column-major inside a band ----
         int u;
-        if (MODE == GG_WGRAD) {
+        int piece = 0, pieces = 1;
+        if (SPLITK) {
+            // work item -> (sorted position, piece, tile); a workgroup's items come in increasing order
+            const int tpe = tiles_i_w * tiles_j;
+            int es = e_hint;
+            while (es + 1 < E && t >= __builtin_amdgcn_readfirstlane(item_start[es + 1])) ++es;
+            e_hint = es;
+            e = __builtin_amdgcn_readfirstlane(tile_start[es]);
+            const int sp = __builtin_amdgcn_readfirstlane(split_of[es]);
+            pieces = sp & 255;
+            u = t - __builtin_amdgcn_readfirstlane(item_start[es]);
+            piece = u / tpe;
+            u -= piece * tpe;
+            part_slot = pieces > 1 ? (sp >> 8) + piece : -1;
+            part_tile = u;
+        } else if (MODE == GG_WGRAD) {
             const int tpe = tiles_i_w * tiles_j;
             const int es = t / tpe;
             e = __builtin_amdgcn_readfirstlane(tile_start[es]);
@@ -440,6 +509,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         // contraction range
         c_lo = (MODE == GG_WGRAD) ? row_lo : 0;
         c_hi = (MODE == GG_WGRAD) ? row_hi : (MODE == GG_FWD ? K : N);
+        if (SPLITK && pieces > 1) {  // this piece's share of the expert's rows, in whole stages
+            const int len = ((row_hi - row_lo + pieces - 1) / pieces + BKE - 1) / BKE * BKE;
+            c_lo = min(row_lo + piece * len, row_hi);
+            c_hi = min(c_lo + len, row_hi);
+        }
         KT = (c_hi - c_lo + BKE - 1) / BKE;
 
         // ---- DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus
@@ -1131,6 +1205,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         // (every wave is past its last LDS read here: the stage loop ends with a barrier after the last
         // fragment reads of both groups)
         const int ep_e = e, ep_i0 = i0, ep_i_end = i_end, ep_j0 = j0, ep_j1 = j1;
+        const int ep_part = part_slot, ep_ptile = part_tile;
         const int t_next = dyn ? publish(drawn) : tile_of(n_tile + 1);
         // (four-wave SwiGLU backward: the registers that would hold the next tile's first stage carry the saved
         // pre-activations instead, many units ahead; the next tile is set up behind the output phase)
@@ -1349,8 +1424,23 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 constexpr int OB = OUT_F32 ? 4 : 2;
                 // (addresses: a wave-uniform row base per unit plus a 32-bit lane offset per strip)
                 const uint32_t vo_lo = (uint32_t)(rr * ld + col_lo) * OB, vo_hi = (uint32_t)(rr * ld + col_hi) * OB;
+                // (a piece of a split contraction: the whole 256 x 256 tile goes to its slice of the workspace in fp32,
+                // row pitch 256; the reduce kernel knows which part of it is inside the matrix)
+                float* const part = (SPLITK && ep_part >= 0)
+                                        ? a.partials + ((int64_t)ep_part * (tiles_i_w * tiles_j) + ep_ptile) * (GG_BM * GG_BN) +
+                                              (wm * 128 + rr) * GG_BN + wn * 64 + c8
+                                        : nullptr;
                 auto emit = [&](int u, const unit_t& o) __attribute__((always_inline)) {
                     const int i = u / 2, hf = u % 2;
+                    if (SPLITK && part) {
+#pragma unroll
+                        for (int g = 0; g < 2; ++g) {
+                            f32x4_t* q = (f32x4_t*)(part + (16 * i + 8 * g) * GG_BN + hf * 128);
+                            q[0] = o.v[g][0];
+                            q[1] = o.v[g][1];
+                        }
+                        return;
+                    }
                     const int c = hf == 0 ? col_lo : col_hi;
                     if (c >= J) return;
 #pragma unroll
@@ -1639,6 +1729,50 @@ static gg_args gg_make(moe_ctx* ctx, const void* P, const void* Q, const int32_t
 }
 
 #define MOE_WS_TILE_COUNTER 48  // byte offset of the wgrad tile counter in the reserved head of the workspace
+#define MOE_WS_SPLIT_INFO 64    // ... of the list of split experts (1 + 3 * GG_MAX_SPLIT_EXPERTS ints)
+
+// Second step of a weight gradient with a split contraction: dW tile = sum of its pieces' partial tiles, piece 0
+// first, then the ordinary output step (type, accumulate, matrix edges).  grid = (tiles per expert,
+// GG_MAX_SPLIT_EXPERTS); the list of split experts was written by the first kernel.
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) void gg_split_reduce_kernel(const float* __restrict__ partials, const int* __restrict__ info,
+                                                              int N, int K, int accumulate, void* __restrict__ out) {
+    const int j = blockIdx.y;
+    if (j >= info[0]) return;
+    const int e = info[1 + 3 * j], pieces = info[2 + 3 * j], slice0 = info[3 + 3 * j];
+    const int tiles_j = (K + GG_BN - 1) / GG_BN, tiles_i = (N + GG_BM - 1) / GG_BM, tpe = tiles_i * tiles_j;
+    const int u = blockIdx.x;
+    // the tile order of the first kernel: bands of GG_BAND row tiles, column-major inside a band
+    const int band_sz = GG_BAND * tiles_j, band = u / band_sz, in_band = u - band * band_sz;
+    const int band_rows = min(GG_BAND, tiles_i - band * GG_BAND);
+    const int ti = band * GG_BAND + in_band % band_rows, tj = in_band / band_rows;
+    const int c = (threadIdx.x & 63) * 4, r0 = threadIdx.x >> 6;
+    const int col = tj * GG_BN + c;
+    if (col >= K) return;
+    for (int r = r0; r < GG_BM; r += 4) {
+        const int row = ti * GG_BM + r;
+        if (row >= N) break;
+        f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < pieces; ++p)
+            v += *(const f32x4_t*)(partials + ((int64_t)(slice0 + p) * tpe + u) * (GG_BM * GG_BN) + r * GG_BN + c);
+        const int64_t at = ((int64_t)e * N + row) * K + col;
+        if (OUT_F32) {
+            f32x4_t* o = (f32x4_t*)((float*)out + at);
+            if (accumulate) v += *o;
+            *o = v;
+        } else {
+            bf16_t* o = (bf16_t*)out + at;
+            float t4[4] = {v[0], v[1], v[2], v[3]};
+            if (accumulate) {
+                float old[4];
+                ld4_bf16(o, old);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) t4[x] += old[x];
+            }
+            st4_bf16(o, t4);
+        }
+    }
+}
 
 #ifndef GG_BF16_NW
 #define GG_BF16_NW 4  // waves per workgroup of the bf16 variants (see the kernel)
@@ -1808,6 +1942,12 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     moe_launch_fill_i32(a.tile_counter, 1, 0, (hipStream_t)stream);
     a.p_scale = dc_scale;
     a.q_scale = a_scale;
+    // split contraction (bf16 operands): as many slices of partial tiles as the workspace holds behind its reserved head
+    const size_t slice_bytes = (size_t)ceil_div64(N, GG_BM) * ceil_div64(K, GG_BN) * GG_BM * GG_BN * sizeof(float);
+    const size_t ws_free = ctx->ws_bytes > MOE_WS_RESERVED ? ctx->ws_bytes - MOE_WS_RESERVED : 0;
+    a.split_info = (int*)((char*)ctx->ws + MOE_WS_SPLIT_INFO);
+    a.partials = (float*)((char*)ctx->ws + MOE_WS_RESERVED);
+    a.split_cap = (!mx && !bw && GG_BF16_NW == 4) ? (int)(ws_free / slice_bytes < GG_MAX_SPLIT ? ws_free / slice_bytes : GG_MAX_SPLIT) : 0;
     if (mx) {
         if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 2);
         else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 2);
@@ -1817,6 +1957,15 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     } else {
         if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 0);
         else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 0);
+    }
+    if (a.split_cap >= 2) {
+        const dim3 grid((unsigned)(ceil_div64(N, GG_BM) * ceil_div64(K, GG_BN)), GG_MAX_SPLIT_EXPERTS);
+        if (out_dt == MOE_F32)
+            hipLaunchKernelGGL(gg_split_reduce_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, a.partials, a.split_info, N, K,
+                               a.accumulate, dB);
+        else
+            hipLaunchKernelGGL(gg_split_reduce_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, a.partials, a.split_info, N, K,
+                               a.accumulate, dB);
     }
     MOE_LAUNCH_CHECK(ctx, "gg_kernel<wgrad>");
     return MOE_OK;

@@ -263,6 +263,46 @@ def test_grouped_gemm_wgrad(B, ctx, oracle, counts, N, K, out_f32):
     assert_close(host_f64(dB), 2 * ref, "dB accumulated", **kw)
 
 
+@pytest.mark.parametrize("counts", [[6000, 300, 257, 0, 700, 64, 1, 130], [9000, 5000, 100, 100, 100, 100, 100, 100, 100, 100]])
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_grouped_gemm_wgrad_split_contraction(B, oracle, counts, out_f32):
+    """Skewed loads: the contraction of experts far above the mean is split into pieces whose fp32 partial tiles are
+    added in a fixed order by a second kernel.  Against the oracle (every element, every row), bit-identical from run
+    to run, accumulate on top, and the same call on a context whose workspace has no room for partial tiles (no
+    split) must agree with the oracle as well."""
+    from gpu_util import dev, dev_bf16, host_f64, assert_close, F32_REG
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets(counts)
+    R = int(off[-1])
+    N, K = 320, 264                                        # ragged output tiles in both directions
+    dCh = wl.gaussian_bf16((R, N), 1.0, 81, E)
+    Ah = wl.gaussian_bf16((R, K), 1.0, 82, E)
+    A, dC, doff = dev_bf16(Ah), dev_bf16(dCh), dev(off)
+    ref = oracle.grouped_gemm_tn(dCh, Ah, off)
+    tdt = torch.float32 if out_f32 else torch.bfloat16
+    odt = B.F32 if out_f32 else B.BF16
+    kw = dict(tol=1e-5, reg=F32_REG) if out_f32 else {}
+    big = B.Context(T=16384, k=8, E=E, h=512, f_max=256)    # room for 8 slices of partial tiles
+    small = B.Context(T=16, k=1, E=E, h=0, f_max=0)         # none
+    assert big.bytes >= 8 * 4 * 256 * 256 * 4 > small.bytes
+    outs = []
+    for ctx in (big, big, small):
+        dB = torch.full((E, N, K), float("nan"), dtype=tdt, device="cuda")
+        B.moe_grouped_gemm_wgrad(ctx, A, dC, doff, E, N, K, R, B.BF16, None, None, 0, odt, dB)
+        torch.cuda.synchronize()
+        assert ctx.poll_error() == 0
+        assert_close(host_f64(dB), ref, "dB", **kw)
+        outs.append(dB)
+    assert torch.equal(outs[0].view(torch.int32 if out_f32 else torch.int16), outs[1].view(torch.int32 if out_f32 else torch.int16))
+    assert not outs[0][counts.index(0)].any() if 0 in counts else True
+    B.moe_grouped_gemm_wgrad(big, A, dC, doff, E, N, K, R, B.BF16, None, None, 1, odt, outs[0])
+    torch.cuda.synchronize()
+    assert_close(host_f64(outs[0]), 2 * ref, "dB accumulated", **kw)
+    big.close()
+    small.close()
+
+
 @pytest.mark.parametrize("T,E,h", [(16384, 256, 7168), (1000, 8, 128), (300, 128, 4096), (1, 40, 64)])
 def test_gate_gemm_and_router_on_its_logits(B, ctx, oracle, T, E, h):
     """logits = X Wr^T in fp32 from bf16 operands against the fp64 oracle; the router then selects on those logits
