@@ -406,14 +406,17 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // that the LDS serves in one pass (lanes 0..31, then 32..63) then differ in bit 4 of the row, which the swizzle
     // of these tiles turns into a different 32-byte half of a 64-byte bank segment (without it both groups of a pass
     // read the same banks: SQ_LDS_BANK_CONFLICT was a third of the LDS cycles of the weight gradient).
+    // (Data gradient: its row-major operand is read 16 bytes per lane, conflict-free only with group g on the g-th
+    // 16 bytes of a step; so there the groups keep rows 8 g .. + 7 and the swizzle uses bit 3 of the row instead.)
+    constexpr bool SWZ3 = NW == 4 && MODE == GG_DGRAD;   // which row bit separates the two groups of a pass: 3, else 4
     int p4[8], q4[8], km4[2];
     if (NW == 4) {
         const int l16 = lane & 15, kq = lane >> 4;
-        const int kperm = Q_CMAJ ? 2 * (kq & 1) + (kq >> 1) : kq;
+        const int kperm = (Q_CMAJ && !SWZ3) ? 2 * (kq & 1) + (kq >> 1) : kq;
         km4[0] = ((kperm) ^ KM_SWZ(l16)) * 16;
         km4[1] = ((4 + kperm) ^ KM_SWZ(l16)) * 16;
         const int cm_off = (8 * kperm + (l16 >> 2)) * 512 + (l16 & 1) * 8;
-        const int cm_xor = tr_xor ^ (2 * (kq & 1));   // bit 4 of the row = kq & 1
+        const int cm_xor = tr_xor ^ (2 * (kq & 1));   // the separating row bit = kq & 1 in both assignments
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int prow = wm * 128 + 16 * i;                             // tile row of P block i
@@ -445,7 +448,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // four waves: chunk i of a wave sits (i / 2) x a fixed stride behind chunk i % 2 (the swizzle alternates with the
     // parity of the chunk), so two lane offsets and a wave-uniform stride per operand replace 2 x 8 registers; rows are
     // not clamped here, the record count of the buffer descriptor covers the end of the tensor
-    uint32_t po2[2] = {0, 0}, qo2[2] = {0, 0};
+    uint32_t po2[2] = {0, 0}, qo2[4] = {0, 0, 0, 0};   // (qo2[2..3]: data gradient only, chunks 4..7 of a wave, see SWZ3)
     uint32_t p_cstride = 0, q_cstride = 0;
     int64_t p_step = 0, q_step = 0;  // byte advance per stage
     const float* sc_src = nullptr;   // fp8: this lane's scale for block 0
@@ -553,9 +556,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             q_base = (MODE == GG_DGRAD ? (const char*)a.Q + (int64_t)e * N * K * ES : (const char*)a.Q) + (int64_t)c_lo * K * ES;
             q_cstride = (uint32_t)(2 * CM_ROWS * K * ES);
 #pragma unroll
-            for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
-                const int row = (wave * CH + i) * CM_ROWS + cm_row;
-                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3) ^ (NW == 4 ? 2 * ((row >> 4) & 1) : 0));
+            for (int i = 0; i < (NW == 4 ? (SWZ3 ? 4 : 2) : CH); ++i) {
+                // (SWZ3: entries 2, 3 are chunks 4, 5 of the wave, whose rows have bit 3 set)
+                const int row = (wave * CH + (SWZ3 ? (i & 1) + 4 * (i >> 1) : i)) * CM_ROWS + cm_row;
+                const int sep = SWZ3 ? (row >> 3) & 1 : (row >> 4) & 1;
+                const int slot = (lane & (CM_SLOTS - 1)) ^ (FP8 ? 2 * (row & 7) : 4 * (row & 3) ^ (NW == 4 ? 2 * sep : 0));
                 int col = (slot < CM_SLOTS / 2 ? j0 : j1 - 128) + slot * EPS;
                 col = col <= K - EPS ? col : K - EPS;
                 if (NW == 4) qo2[i] = (uint32_t)((row * K + col) * ES);
@@ -709,7 +714,8 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     auto load_one = [&](int kt, int idx) __attribute__((always_inline)) {
         const int i = idx >> 1;
         const bool isq = idx & 1;
-        const uint32_t off = (isq ? qo2[i & 1] : po2[i & 1]) + (uint32_t)(i >> 1) * (isq ? q_cstride : p_cstride);
+        const uint32_t off = (isq && SWZ3) ? qo2[(i & 1) + 2 * (i >> 2)] + (uint32_t)((i >> 1) & 1) * q_cstride
+                                           : (isq ? qo2[i & 1] : po2[i & 1]) + (uint32_t)(i >> 1) * (isq ? q_cstride : p_cstride);
         const char* base = isq ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
         const bool cmaj = isq ? Q_CMAJ : P_CMAJ;
         int64_t bytes;  // from the base to the end of what may be read
@@ -1131,6 +1137,12 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     // (the MFMAs are inline assembly: the compiler does not know that their results need 18 more cycles
                     // before ordinary instructions may read them)
                     asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+                    // (and every later read of an accumulator depends on a statement behind those nops: volatile asm
+                    // statements keep their order, so no read can be scheduled ahead of the wait)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+#pragma unroll
+                        for (int jq = 0; jq < 8; ++jq) asm volatile("" : "+a"(acc4[i][jq]));
                 }
             } else if (KT > 0 && wm == 0) {
                 wait_vm0();  // stage 0, issued before the previous tile's epilogue
