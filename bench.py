@@ -23,19 +23,22 @@ FP8_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 CAL_COPY_BYTES = 1 << 30    # size of the calibration copy (read 1 GiB, write 1 GiB)
 
-# HBM-side bytes per launch (GB read, GB written) of the grouped-GEMM call sites, from two rocprofv3 counter
-# passes over this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same
-# counter read for the 1 GiB calibration copy above (FETCH_SIZE 0.5 x, WRITE_SIZE 1.0 x of the known size).
-# Summaries and commands: profiles/gg_kernel_c4_hbm_traffic.txt, ..._c5_..., ..._c6_....
-# Offline measurements: they describe the committed kernels at the default load pattern, not this run.
-MEASURED_TRAFFIC_GB = {
-    "C4": {"fc1_fwd_swiglu_bf16": (13.76, 1.61), "fc2_fwd_bf16": (6.75, 1.88), "fc2_wgrad_bf16": (5.65, 0.94),
-           "fc2_dgrad_swiglu_bwd_bf16": (10.14, 1.07), "fc1_wgrad_bf16": (11.81, 1.88), "fc1_dgrad_bf16": (13.29, 1.88)},
-    "C5": {"fc1_fwd_swiglu_fp8": (7.13, 1.93), "fc2_fwd_fp8": (3.86, 1.92), "fc2_wgrad_bf16": (6.14, 0.94),
-           "fc2_dgrad_swiglu_bwd_fp8": (5.05, 1.66), "fc1_wgrad_bf16": (12.01, 1.88), "fc1_dgrad_fp8": (7.31, 1.91)},
-    "C6": {"fc1_fwd_swiglu_mxfp8": (7.38, 1.64), "fc2_fwd_mxfp8": (3.71, 1.91), "fc2_wgrad_mxfp8": (4.65, 0.94),
-           "fc2_dgrad_swiglu_bwd_mxfp8": (5.00, 1.09), "fc1_wgrad_mxfp8": (9.64, 1.88), "fc1_dgrad_mxfp8": (7.19, 1.91)},
-}
+def measured_traffic(workload: str, label: str):
+    """(GB read, GB written) per launch of one grouped-GEMM call site, from the tracked summary of the two rocprofv3
+    counter passes over this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, each scaled by what the same
+    counter read for the 1 GiB calibration copy below): profiles/gg_kernel_<workload>_hbm_traffic.txt, written by
+    paper_2603_07685_amd.profile_summary.  Offline measurements: they describe the committed kernels at the default
+    load pattern, not this run.  None when the workload has no summary."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"gg_kernel_{workload.lower()}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        for line in fh:
+            m = re.match(r"\s+(\S+)\s+gg_kernel<[^>]*>\s+read\s+([0-9.]+)\s+write\s+([0-9.]+)", line)
+            if m and m.group(1) == label:
+                return float(m.group(2)), float(m.group(3))
+    return None
 
 
 def parse():
@@ -306,8 +309,8 @@ def main():
     gemm = [(t, lab, fl) for lab, fl, by, t in calls if fl]
     t_dom, n_dom, fl_dom = max(gemm)
     by_dom = next(by for lab, fl, by, t in calls if lab == n_dom)
-    rw = MEASURED_TRAFFIC_GB.get(args.workload, {}).get(n_dom) if args.variant is None else None
-    traffic = round(sum(rw), 2) if rw else None
+    rw = measured_traffic(args.workload, n_dom) if args.variant is None else None
+    traffic = round(sum(rw), 3) if rw else None
     achieved = fl_dom / t_dom / 1e9
     gemm_ms = sum(t for t, _, _ in gemm)
     gemm_fl = sum(fl for _, _, fl in gemm)
@@ -337,7 +340,7 @@ def main():
                       "pct_peak": round(100.0 * gemm_fl / gemm_ms / 1e9 / BF16_PEAK_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "kernel": f"gg_kernel ({n_dom})", "achieved": round(achieved, 1),
                      "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": traffic, "traffic_unit": "GB per launch (HBM-side read + write, offline counters)",
+                     "traffic": traffic, "traffic_unit": "GB per launch (HBM-side read + write, offline counters: profiles/gg_kernel_<workload>_hbm_traffic.txt)",
                      "traffic_read_write_gb": list(rw) if rw else None,
                      "algorithmic_gb": round(by_dom / 1e9, 2) if by_dom else None},
         "kernels": breakdown,

@@ -22,7 +22,11 @@
  *   - Return value: MOE_OK or a negative moe_status.  Argument errors are found
  *     on the host before anything is launched; nothing is written then.
  *     moe_last_error gives a host string describing the last failure on a context.
- *   - Calls on one context from several host threads at once are not supported.
+ *   - Calls on one context from several host threads at once are not supported, and all calls on one
+ *     context must be stream-ordered with respect to each other (use one context per stream): several calls
+ *     keep device-side state in the context workspace (the row-ID map's histograms, the auxiliary loss's
+ *     partial sums, the gate GEMM's offsets, the weight gradient's tile counter and partial tiles), and two such
+ *     calls running at the same time on different streams would race silently.
  *   - Same inputs give bit-identical outputs from run to run (no floating-point
  *     atomics anywhere; integer atomics only where the result is order-free).
  */
@@ -220,7 +224,10 @@ moe_status moe_permute_static(void* stream, const void* X, moe_dtype dt,
  * an expert's Linear weight), no bias (Sec. 4.1.2 needs bias-free experts).
  * dt is the operand type: MOE_BF16 (fp32 accumulation, bf16 result) or
  * MOE_FP8_E4M3 (blockwise recipe of Sec. 5.3.2: operands are E4M3 codes with
- * fp32 scales, fp32 accumulation, bf16 result).  N and K must be multiples of
+ * fp32 scales, fp32 accumulation, bf16 result; the accumulators are carried in units of
+ * the current 128-wide block's scales, so the scales met along one contraction must be
+ * normal numbers within 2^100 of each other, which amax / 448 of bf16 data always is
+ * unless a block's amax is below 2^-117).  N and K must be multiples of
  * 128 (fp8) / 16 (bf16); in bf16 the contraction dimension of fwd (K) and of
  * dgrad (N) must also be a multiple of 64 (one 128-byte operand row per stage);
  * wgrad contracts over the expert's rows, any count.  Sizes outside these limits
