@@ -57,6 +57,8 @@ def parse():
                     help="also capture the step in a HIP graph and report the time of its replays (field 'graph')")
     ap.add_argument("--bf16-wgrad", action="store_true",
                     help="blockwise fp8 workloads: weight gradients from the bf16 tensors instead of the 128x1 E4M3 copies")
+    ap.add_argument("--no-epilogue-quant", action="store_true",
+                    help="one-byte recipes: quantise A and dZ with stand-alone quantiser launches instead of in the GEMM epilogues")
     ap.add_argument("--eq2", action="store_true",
                     help="memory-efficient permutation: routing weights applied in the fc1 epilogue, plain-sum combine")
     return ap.parse_args()
@@ -73,6 +75,12 @@ def describe_call(name, args, st):
         return "gather_row_prob", None, args[3] * 12
     if name == "moe_scatter_row_dprob":
         return "scatter_row_dprob", None, T * k * (8 + 4 * args[2])
+    q_out = 0   # quantised copies a quantising epilogue writes besides its bf16 output (bytes per output element)
+    if name.endswith("_quant_mx"):   # (ctx, P, W, offsets, E, N, K, Rcap, [Z_saved,] scales ...): MXFP8 implied
+        fwd = "fwd" in name
+        q_out = 1 + (args[-2] is not None)
+        args = list(args[:8]) + [3, 1 if fwd else args[8]]
+        name = "moe_grouped_gemm_" + ("fwd" if fwd else "dgrad")
     for sfx in ("_weighted", "_quant"):
         if name.endswith(sfx):
             name = name[:-len(sfx)]
@@ -91,9 +99,9 @@ def describe_call(name, args, st):
         label = f"{'shared_' if E == 1 else ''}{which}_{kind}{extra}_{tag}"
         es = 1 if dt in (1, 3) else 2
         if kind == "fwd":      # read A and the weights once, write C (SwiGLU: pre-activations + activation)
-            by = rows * K * es + E * N * K * es + rows * N * 2 + (rows * (N // 2) * 2 if extra else 0)
+            by = rows * K * es + E * N * K * es + rows * N * 2 + (rows * (N // 2) * (2 + q_out) if extra else 0)
         elif kind == "dgrad":  # read dC and the weights once, write dA (SwiGLU-bwd: read Z, write dZ, both [rows, 2K])
-            by = rows * N * es + E * N * K * es + (rows * 2 * K * 2 * 2 if extra else rows * K * 2)
+            by = rows * N * es + E * N * K * es + (rows * 2 * K * (2 * 2 + q_out) if extra else rows * K * 2)
         else:                  # read A and dC once, write the weight gradients
             by = rows * (N + K) * es + E * N * K * (4 if args[12] == 2 else 2)
         return label, 2.0 * rows * N * K, by
@@ -149,7 +157,8 @@ def describe_call(name, args, st):
 HOOKED = ["moe_fp8_quantize_rowcol", "moe_fp8_quantize_rowcol_gather", "moe_mx_quantize", "moe_mx_quantize_rowcol", "moe_mx_quantize_rowcol_gather", "moe_route_topk", "moe_route_topk_grouped", "moe_permute", "moe_grouped_gemm_fwd", "moe_grouped_gemm_dgrad", "moe_grouped_gemm_wgrad",
           "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_fp8_quantize",
           "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted",
-          "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gather_row_prob",
+          "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_grouped_gemm_fwd_quant_mx",
+          "moe_grouped_gemm_dgrad_quant_mx", "moe_gather_row_prob",
           "moe_scatter_row_dprob"]
 
 
@@ -263,7 +272,8 @@ def main():
     small = cfg.T * cfg.h <= 4 * 1024 * 1024
     hin = L.host_inputs(cfg) if small else None
     st = L.LayerState(cfg, hin, variant=args.variant, wgrad_f32=args.wgrad_f32, eq2=args.eq2,
-                      fp8_wgrad=False if args.bf16_wgrad else None)
+                      fp8_wgrad=False if args.bf16_wgrad else None,
+                      epilogue_quant=False if args.no_epilogue_quant else None)
 
     # one plain device copy of known size, outside the timed region: the reference dispatch the HBM byte
     # counters (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by

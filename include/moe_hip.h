@@ -336,6 +336,30 @@ moe_status moe_grouped_gemm_dgrad_quant(moe_ctx* ctx, void* stream, const void* 
                                         void* dz_q, float* dz_q_scale);
 
 /*
+ * The same fusion for the MXFP8 recipe (Sec. 5.3.3, 5.4.2; dt = MOE_MXFP8_E4M3 implied, operands and scales as
+ * for the plain MXFP8 calls): the SwiGLU epilogue of fc1 / the SwiGLU-backward epilogue of the fc2 data gradient
+ * also emit the quantised copies of the bf16 tensor they store (C_act [Rcap, N/2] / dZ [Rcap, 2K]; "cols" below is
+ * that tensor's width), bit for bit what moe_mx_quantize_rowcol would make of it:
+ *   q_row [Rcap, cols] codes, e8_row [Rcap, cols/32] E8M0 bytes: the 1x32 copy (operand of the next forward /
+ *         data-gradient GEMM); required.
+ *   q_col [Rcap, cols] codes, e8_col [Rcap/128, cols, 4] E8M0 bytes: the 32x1 copy (operand of the weight
+ *         gradients); both NULL = not made.  Needs Rcap % 128 == 0 and every expert's range to start and end on a
+ *         multiple of 128 rows (moe_permute with align = 128); otherwise the device error word is raised
+ *         (moe_ctx_poll_error) and the outputs are undefined.
+ * Rows >= offsets[E] are not written.  All device pointers; nothing is allocated.
+ */
+moe_status moe_grouped_gemm_fwd_quant_mx(moe_ctx* ctx, void* stream, const void* A, const void* B,
+                                         const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                         const void* a_scale, const void* b_scale, const float* row_prob,
+                                         void* C, void* C_act, void* act_q_row, uint8_t* act_e8_row,
+                                         void* act_q_col, uint8_t* act_e8_col);
+moe_status moe_grouped_gemm_dgrad_quant_mx(moe_ctx* ctx, void* stream, const void* dC, const void* B,
+                                           const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                           const void* Z_saved, const void* dc_scale, const void* b_scale,
+                                           const float* row_prob, void* dZ, float* dprob_part,
+                                           void* dz_q_row, uint8_t* dz_e8_row, void* dz_q_col, uint8_t* dz_e8_col);
+
+/*
  * Row-indexed view of the routing weights for eq. (2) and its inverse:
  *   gather:  row_prob[r] = prob[src_of[r]] for r < Rcap, 0 where src_of[r] < 0 (padding).
  *   scatter: dprob[t,s] = sum_j dprob_part[row_of[t,s], j], j = 0..parts-1 in increasing

@@ -29,7 +29,8 @@ EXPORTS = [
     "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted", "moe_gather_row_prob", "moe_scatter_row_dprob",
     "moe_route_topk_bwd", "moe_mx_quantize", "moe_mx_quantize_rowcol",
     "moe_route_topk_grouped", "moe_aux_loss", "moe_mx_quantize_rowcol_gather",
-    "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_gate_gemm", "moe_permute_static",
+    "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant",
+    "moe_grouped_gemm_fwd_quant_mx", "moe_grouped_gemm_dgrad_quant_mx", "moe_gate_gemm", "moe_permute_static",
     "moe_fp8_quantize_rowcol", "moe_fp8_quantize_rowcol_gather",
 ]
 
@@ -73,6 +74,8 @@ def lib() -> C.CDLL:
         L.moe_mx_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_fwd_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.moe_grouped_gemm_dgrad_quant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_fwd_quant_mx.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64] + [_vp] * 9
+        L.moe_grouped_gemm_dgrad_quant_mx.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i64] + [_vp] * 10
         L.moe_fp8_quantize_rowcol.argtypes = [_vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_fp8_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_gate_gemm.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
@@ -203,6 +206,22 @@ def moe_grouped_gemm_dgrad_quant(ctx, dC, B, offsets, E, N, K, Rcap, dt, Z_saved
                                                  _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(row_prob), _ptr(dA),
                                                  _ptr(dprob_part), _ptr(dz_q), _ptr(dz_q_scale)),
               "moe_grouped_gemm_dgrad_quant")
+
+
+def moe_grouped_gemm_fwd_quant_mx(ctx, A, B, offsets, E, N, K, Rcap, a_scale, b_scale, row_prob, Cout, C_act,
+                                  act_q_row, act_e8_row, act_q_col, act_e8_col):
+    ctx.check(lib().moe_grouped_gemm_fwd_quant_mx(ctx.h, _stream(), _ptr(A), _ptr(B), _ptr(offsets), E, N, K, Rcap,
+                                                  _ptr(a_scale), _ptr(b_scale), _ptr(row_prob), _ptr(Cout), _ptr(C_act),
+                                                  _ptr(act_q_row), _ptr(act_e8_row), _ptr(act_q_col), _ptr(act_e8_col)),
+              "moe_grouped_gemm_fwd_quant_mx")
+
+
+def moe_grouped_gemm_dgrad_quant_mx(ctx, dC, B, offsets, E, N, K, Rcap, Z_saved, dc_scale, b_scale, row_prob, dZ,
+                                    dprob_part, dz_q_row, dz_e8_row, dz_q_col, dz_e8_col):
+    ctx.check(lib().moe_grouped_gemm_dgrad_quant_mx(ctx.h, _stream(), _ptr(dC), _ptr(B), _ptr(offsets), E, N, K, Rcap,
+                                                    _ptr(Z_saved), _ptr(dc_scale), _ptr(b_scale), _ptr(row_prob), _ptr(dZ),
+                                                    _ptr(dprob_part), _ptr(dz_q_row), _ptr(dz_e8_row), _ptr(dz_q_col),
+                                                    _ptr(dz_e8_col)), "moe_grouped_gemm_dgrad_quant_mx")
 
 
 def moe_gate_gemm(ctx, X, Wr, T, E, h, logits):

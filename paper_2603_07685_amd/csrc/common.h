@@ -76,6 +76,46 @@ __device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d
     return (uint32_t)w;
 }
 
+// MXFP8 (Sec. 5.3.3): the E8M0 exponent of a block from its largest magnitude, e = ceil(log2(amax / 448)) taken from
+// the bits of amax (clamped to +-127, 0 for an all-zero block), and the E4M3 codes of x * 2^-e (exact scaling, RNE).
+// One copy for every kernel that quantises (stand-alone quantisers and GEMM epilogues): identical bits everywhere.
+__device__ __forceinline__ int mx_exponent(float amax) {
+    if (!(amax > 0.0f)) return 0;
+    const uint32_t b = __float_as_uint(amax);
+    int e = (int)((b >> 23) & 0xFF) - 127 - 8 + ((b & 0x7FFFFFu) > 0x600000u ? 1 : 0);
+    if (((b >> 23) & 0xFF) == 0) e = -127;  // subnormal maximum: far below the clamp
+    return e < -127 ? -127 : (e > 127 ? 127 : e);
+}
+// Four bf16 values (two packed pairs) -> four E4M3 codes of x / 2^e, with the hardware's scaled conversion
+// (v_cvt_scalef32_pk_fp8_bf16 divides by the power of two in the scale operand's exponent field, round to nearest
+// even); one exponent for all four, or one per element (two conversions per pair, one byte kept of each).
+typedef short s16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float mx_scale_f32(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }  // 2^e
+__device__ __forceinline__ uint32_t mx_cvt4_bf16(uint32_t w01, uint32_t w23, float scale) {
+    s16x2_t o = {0, 0};
+    o = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(o, __builtin_bit_cast(bf16x2_t, w01), scale, false);
+    o = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(o, __builtin_bit_cast(bf16x2_t, w23), scale, true);
+    return __builtin_bit_cast(uint32_t, o);
+}
+__device__ __forceinline__ uint32_t mx_cvt4_bf16_each(uint32_t w01, uint32_t w23, float s0, float s1, float s2, float s3) {
+    s16x2_t ev = {0, 0}, od = {0, 0};
+    ev = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(ev, __builtin_bit_cast(bf16x2_t, w01), s0, false);
+    ev = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(ev, __builtin_bit_cast(bf16x2_t, w23), s2, true);
+    od = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(od, __builtin_bit_cast(bf16x2_t, w01), s1, false);
+    od = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(od, __builtin_bit_cast(bf16x2_t, w23), s3, true);
+    return (__builtin_bit_cast(uint32_t, ev) & 0x00FF00FFu) | (__builtin_bit_cast(uint32_t, od) & 0xFF00FF00u);
+}
+// largest magnitude of the eight bf16 values of a 16-byte piece, as fp32 (the bits of |x| order like unsigned integers)
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_absmax_bits(uint32_t m, uint32_t w) {   // both halves at once
+    const u16x2_t a = __builtin_bit_cast(u16x2_t, m), b = __builtin_bit_cast(u16x2_t, w & 0x7FFF7FFFu);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
+}
+__device__ __forceinline__ float bf16_absmax_finish(uint32_t m) {
+    const uint32_t hi = m >> 16, lo = m & 0xFFFFu;
+    return __uint_as_float((hi > lo ? hi : lo) << 16);
+}
+
 // all-fp32 grouped GEMMs (gemm_f32.hip), reached from the public entry points with dt = MOE_F32
 moe_status moe_gg_f32_fwd(moe_ctx* ctx, hipStream_t s, const void* A, const void* B, const int32_t* offsets, int E, int N,
                           int K, int64_t Rcap, int swiglu, const float* row_prob, void* C, void* C_act);

@@ -352,20 +352,6 @@ extern "C" moe_status moe_fp8_quantize_rowcol_gather(moe_ctx* ctx, void* stream,
 //          (weights in the data gradient, both operands of the weight gradient); made alone or together with
 //          the 1x32 copy in one pass over the input (mx_quant_rowcol_kernel).
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ int mx_exponent(float amax) {
-    if (!(amax > 0.0f)) return 0;
-    const uint32_t b = __float_as_uint(amax);
-    int e = (int)((b >> 23) & 0xFF) - 127 - 8 + ((b & 0x7FFFFFu) > 0x600000u ? 1 : 0);
-    if (((b >> 23) & 0xFF) == 0) e = -127;  // subnormal maximum: far below the clamp
-    return e < -127 ? -127 : (e > 127 ? 127 : e);
-}
-__device__ __forceinline__ uint32_t mx_cvt4(float a, float b, float c, float d, int e) {
-    int w = 0;
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(a, -e), ldexpf(b, -e), w, false);
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(c, -e), ldexpf(d, -e), w, true);
-    return (uint32_t)w;
-}
-
 __global__ __launch_bounds__(256) void mx_quant_1x32_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
                                                             const int32_t* __restrict__ rows_dev,
                                                             u32x2_t* __restrict__ q, uint8_t* __restrict__ e8) {
@@ -382,8 +368,8 @@ __global__ __launch_bounds__(256) void mx_quant_1x32_kernel(const u32x4_t* __res
         const int e = mx_exponent(m);
         if (in) {
             u32x2_t o;
-            o.x = mx_cvt4(bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y), e);
-            o.y = mx_cvt4(bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w), e);
+            o.x = mx_cvt4_bf16(x.x, x.y, mx_scale_f32(e));
+            o.y = mx_cvt4_bf16(x.z, x.w, mx_scale_f32(e));
             q[v] = o;
             if ((v & 3) == 0) e8[v >> 2] = (uint8_t)(e + 127);
         }
@@ -456,8 +442,8 @@ __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __r
             m = fmaxf(m, __shfl_xor(m, 2));
             const int e = mx_exponent(m);
             u32x2_t o;
-            o.x = mx_cvt4(bf16_lo(x[i].x), bf16_hi(x[i].x), bf16_lo(x[i].y), bf16_hi(x[i].y), e);
-            o.y = mx_cvt4(bf16_lo(x[i].z), bf16_hi(x[i].z), bf16_lo(x[i].w), bf16_hi(x[i].w), e);
+            o.x = mx_cvt4_bf16(x[i].x, x[i].y, mx_scale_f32(e));
+            o.y = mx_cvt4_bf16(x[i].z, x[i].w, mx_scale_f32(e));
             q_row[v0 + (int64_t)i * 4 * vpr] = o;
             // the row's four block bytes of this tile, gathered into the first of its 16 lanes
             const int b = e + 127, base = lane & 48;
@@ -485,14 +471,13 @@ __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __r
             e[c] = mx_exponent(m[c]);
             if (lane < 16) sc[wave][8 * lane + c] = (uint8_t)(e[c] + 127);
         }
+        float sf[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) sf[c] = mx_scale_f32(e[c]);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            int w0 = 0, w1 = 0;
-            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].x), -e[0]), ldexpf(bf16_hi(x[i].x), -e[1]), w0, false);
-            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].y), -e[2]), ldexpf(bf16_hi(x[i].y), -e[3]), w0, true);
-            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].z), -e[4]), ldexpf(bf16_hi(x[i].z), -e[5]), w1, false);
-            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(bf16_lo(x[i].w), -e[6]), ldexpf(bf16_hi(x[i].w), -e[7]), w1, true);
-            u32x2_t o = {(uint32_t)w0, (uint32_t)w1};
+            const u32x2_t o = {mx_cvt4_bf16_each(x[i].x, x[i].y, sf[0], sf[1], sf[2], sf[3]),
+                               mx_cvt4_bf16_each(x[i].z, x[i].w, sf[4], sf[5], sf[6], sf[7])};
             q_col[v0 + (int64_t)i * 4 * vpr] = o;
         }
         __syncthreads();

@@ -197,6 +197,11 @@ struct gg_args {
     // activation [rows, N/2]; dgrad SWIGLU_BWD: of dZ [rows, 2K]), the operand of the next GEMM (Sec. 5.4.2)
     uint8_t* out_q;
     float* out_q_scale;
+    // MXFP8: the same tensors as 1x32 codes + E8M0 bytes [rows, cols/32] (out_q, out_q_e8) and, optionally, as the
+    // 32x1 copy for the weight gradient (out_qc, scales [rows/128, cols, 4]: one dword = the four 32-row blocks)
+    uint8_t* out_q_e8;
+    uint8_t* out_qc;
+    uint8_t* out_qc_e8;
     int* tile_counter;     // wgrad: zeroed device counter for the dynamic tile order under skewed loads (see the kernel)
     // wgrad, bf16: deterministic split of the contraction for experts far above the mean load (see the kernel)
     int split_cap;         // how many expert-sized slices of fp32 partial tiles `partials` can hold (0: never split)
@@ -249,6 +254,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     char* const ldsQ0 = lds_buf + GG_STAGE_BYTES + SC_BYTES;
     char* const ldsP1 = lds_buf + BUF_BYTES;
     char* const ldsQ1 = ldsP1 + GG_STAGE_BYTES + SC_BYTES;
+    // MXFP8 quantising epilogues: column maxima of the four waves that share a 32-row block meet here
+    constexpr bool MXQ = F8 == 2 && NW == 8 && EPI != GG_EPI_STORE;
+    __shared__ __attribute__((aligned(16))) uint32_t qx[MXQ ? 8 * 64 * 4 : 4];
+    __shared__ __attribute__((aligned(16))) float qe[MXQ ? 2 * 512 : 4];  // per tile half: the block scale 2^e of every column
     __shared__ int offs[GG_MAX_E + 1];
     __shared__ int tile_start[GG_MAX_E + 1];
     __shared__ int dyn_next;
@@ -311,6 +320,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             // MXFP8 wgrad: a 32-row scale block (and the 128-row stage) must not straddle two experts
             // (the same for the 128-row scale blocks of the blockwise recipe)
             if (FP8 && MODE == GG_WGRAD) bad |= (rows & 127) != 0 || (offs[e] & 127) != 0;
+            if (MXQ && a.out_qc) bad |= (rows & 127) != 0 || (offs[e] & 127) != 0;  // 32-row blocks inside one expert
             if (MODE == GG_WGRAD) run += tiles_i_w * tiles_j;
             else run += rows > 0 ? ((rows + GG_BM - 1) / GG_BM) * tiles_j : 0;
         }
@@ -1538,6 +1548,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     }
                 wait_lgkm0();
                 stage_barrier();
+                float cmx[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // MXFP8 column copy: column maxima of this wave's rows
                 auto out_row = [&](int x8, bool early, bool have, f32x4_t vin) {
                     const int rr = wave * RPW + x8;                           // staged row 0..63
                     const int r = ep_i0 + (rr >> 5) * 128 + i * 32 + (rr & 31);
@@ -1597,6 +1608,22 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                                     float* sc = a.out_q_scale + (int64_t)r * (2 * K / 128);
                                     sc[c >> 7] = sgs;
                                     sc[(K + c) >> 7] = sus;
+                                }
+                            }
+                            if (MXQ && a.out_q) {
+                                // MXFP8 copies of dZ: the values as stored (bf16) replace the row's consumed staging
+                                // words -- gate part at byte 8 * lane, up part 512 bytes further, i.e. the row in column
+                                // order -- and are quantised 16 columns per lane once the whole pass is there (below)
+                                const uint32_t g01 = pack_bf16(dg[0], dg[1]), g23 = pack_bf16(dg[2], dg[3]);
+                                const uint32_t u01 = pack_bf16(du[0], du[1]), u23 = pack_bf16(du[2], du[3]);
+                                uint32_t* srow = (uint32_t*)(stg + rr * STG_PITCH);
+                                *(u32x2_t*)(srow + 2 * lane) = u32x2_t{g01, g23};
+                                *(u32x2_t*)(srow + 128 + 2 * lane) = u32x2_t{u01, u23};
+                                if (a.out_qc) {
+                                    cmx[0] = fmaxf(cmx[0], fabsf(bf16_lo(g01))); cmx[1] = fmaxf(cmx[1], fabsf(bf16_hi(g01)));
+                                    cmx[2] = fmaxf(cmx[2], fabsf(bf16_lo(g23))); cmx[3] = fmaxf(cmx[3], fabsf(bf16_hi(g23)));
+                                    cmx[4] = fmaxf(cmx[4], fabsf(bf16_lo(u01))); cmx[5] = fmaxf(cmx[5], fabsf(bf16_hi(u01)));
+                                    cmx[6] = fmaxf(cmx[6], fabsf(bf16_lo(u23))); cmx[7] = fmaxf(cmx[7], fabsf(bf16_hi(u23)));
                                 }
                             }
                         }
@@ -1692,6 +1719,126 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                                     cvt4_e4m3(bf16_lo(a01), bf16_hi(a01), bf16_lo(a23), bf16_hi(a23), sa);
                                 if ((lane & 31) == 0) a.out_q_scale[(int64_t)r * (half_cols / 128) + ep_j0 / 128] = sa;
                             }
+                            if (MXQ && a.out_q) {
+                                // MXFP8 copies of A: the values as stored (bf16) go over the row's consumed gate words, in
+                                // feature order, and are quantised 16 features per lane once the pass is complete (below)
+                                const uint32_t a01 = pack_bf16(act[0], act[1]), a23 = pack_bf16(act[2], act[3]);
+                                *(u32x2_t*)((uint32_t*)(stg + rr * STG_PITCH) + 2 * (lane & 31)) = u32x2_t{a01, a23};
+                                if (a.out_qc) {
+                                    cmx[0] = fmaxf(cmx[0], fabsf(bf16_lo(a01))); cmx[1] = fmaxf(cmx[1], fabsf(bf16_hi(a01)));
+                                    cmx[2] = fmaxf(cmx[2], fabsf(bf16_lo(a23))); cmx[3] = fmaxf(cmx[3], fabsf(bf16_hi(a23)));
+                                }
+                            }
+                        }
+                    }
+                }
+                // MXFP8 quantising epilogue (Sec. 5.4.2), second half.  The pass's rows of this wave (eight) now lie in
+                // the staging area as bf16 in column order.  A lane takes 16 consecutive columns of one row (16 codes =
+                // one 16-byte store): the 1x32 copy needs the maximum of two neighbouring lanes; for the 32x1 copy the
+                // 32 rows of a block are this pass's rows of one tile half, eight per wave, so the four waves of the
+                // half first exchange their column maxima through LDS and each keeps the exponents of its columns as a
+                // byte table of its own.
+                if (MXQ && a.out_q) {
+                    const bool colq = a.out_qc != nullptr;                     // uniform over the grid
+                    const int hb = wave & 4;                                   // first wave of this wave's tile half
+                    const int r_blk = ep_i0 + (wave >> 2) * 128 + i * 32;      // first row of the 32-row block
+                    constexpr int HALVES = EPI == GG_EPI_SWIGLU ? 1 : 2;       // column parts per row (A: one; dZ: gate, up)
+                    const int width = HALVES == 1 ? half_cols : 2 * K;         // row length of the quantised tensor
+                    if (colq) {
+                        if (EPI == GG_EPI_SWIGLU) {
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) cmx[x] = fmaxf(cmx[x], __shfl_xor(cmx[x], 32));  // the two rows of a lane pair
+                            if (lane < 32) *(f32x4_t*)(qx + (wave * 64 + lane) * 4) = f32x4_t{cmx[0], cmx[1], cmx[2], cmx[3]};
+                        } else {
+                            // (maxima of bf16 values are bf16 values: packed without loss)
+                            *(u32x4_t*)(qx + (wave * 64 + lane) * 4) = u32x4_t{pack_bf16(cmx[0], cmx[1]), pack_bf16(cmx[2], cmx[3]),
+                                                                                pack_bf16(cmx[4], cmx[5]), pack_bf16(cmx[6], cmx[7])};
+                        }
+                        wait_lgkm0();
+                        stage_barrier();
+                        int ex[8];
+                        if (EPI == GG_EPI_SWIGLU) {
+                            f32x4_t m = *(const f32x4_t*)(qx + (hb * 64 + (lane & 31)) * 4);
+#pragma unroll
+                            for (int w2 = 1; w2 < 4; ++w2) {
+                                const f32x4_t o = *(const f32x4_t*)(qx + ((hb + w2) * 64 + (lane & 31)) * 4);
+#pragma unroll
+                                for (int x = 0; x < 4; ++x) m[x] = fmaxf(m[x], o[x]);
+                            }
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) ex[x] = mx_exponent(m[x]);
+                        } else {
+                            u32x4_t pm = *(const u32x4_t*)(qx + (hb * 64 + lane) * 4);
+                            float m[8] = {bf16_lo(pm.x), bf16_hi(pm.x), bf16_lo(pm.y), bf16_hi(pm.y),
+                                          bf16_lo(pm.z), bf16_hi(pm.z), bf16_lo(pm.w), bf16_hi(pm.w)};
+#pragma unroll
+                            for (int w2 = 1; w2 < 4; ++w2) {
+                                const u32x4_t o = *(const u32x4_t*)(qx + ((hb + w2) * 64 + lane) * 4);
+                                const float of[8] = {bf16_lo(o.x), bf16_hi(o.x), bf16_lo(o.y), bf16_hi(o.y),
+                                                     bf16_lo(o.z), bf16_hi(o.z), bf16_lo(o.w), bf16_hi(o.w)};
+#pragma unroll
+                                for (int x = 0; x < 8; ++x) m[x] = fmaxf(m[x], of[x]);
+                            }
+#pragma unroll
+                            for (int x = 0; x < 8; ++x) ex[x] = mx_exponent(m[x]);
+                        }
+                        // the half's table of column scales 2^e (part p of the row at 256 p; its four waves write the same
+                        // values and each reads behind its own writes), and, from the first wave of each half, the E8M0
+                        // bytes: byte i of the dword of (128-row group, column)
+                        float* qh = qe + (wave >> 2) * 512;
+#pragma unroll
+                        for (int p2 = 0; p2 < HALVES; ++p2) {
+                            const int* e4 = ex + 4 * p2;
+                            const f32x4_t w = {mx_scale_f32(e4[0]), mx_scale_f32(e4[1]), mx_scale_f32(e4[2]), mx_scale_f32(e4[3])};
+                            if (HALVES == 2 || lane < 32) *(f32x4_t*)(qh + 256 * p2 + 4 * (HALVES == 2 ? lane : (lane & 31))) = w;
+                        }
+                        if ((wave & 3) == 0 && r_blk < ep_i_end) {
+                            if (EPI == GG_EPI_SWIGLU) {
+                                if (lane < 32) {
+                                    uint8_t* sc = a.out_qc_e8 + ((int64_t)(r_blk >> 7) * width + ep_j0 + lane * 4) * 4 + i;
+#pragma unroll
+                                    for (int x = 0; x < 4; ++x) sc[4 * x] = (uint8_t)(ex[x] + 127);
+                                }
+                            } else if (c < K) {
+                                uint8_t* sc = a.out_qc_e8 + ((int64_t)(r_blk >> 7) * width + c) * 4 + i;
+#pragma unroll
+                                for (int x = 0; x < 4; ++x) {
+                                    sc[4 * x] = (uint8_t)(ex[x] + 127);
+                                    sc[4 * (K + x)] = (uint8_t)(ex[4 + x] + 127);
+                                }
+                            }
+                        }
+                    }
+                    const int row = lane >> 3, rr = wave * RPW + row;             // RPW = 8 rows per wave and pass
+                    const int r = r_blk + (rr & 31);
+#pragma unroll
+                    for (int t2 = 0; t2 < 2 * HALVES; ++t2) {
+                        const int p2 = t2 >> 1;                                    // part of the row (dZ: gate / up)
+                        const int sc16 = ((lane & 7) + 8 * (t2 & 1)) * 16;         // first of the lane's 16 columns in the tile
+                        if (HALVES == 1 && t2 == 1) break;                         // (A: 128 columns per tile row, one task)
+                        const int colt = HALVES == 1 ? ep_j0 + sc16 : (sc16 < 128 ? ep_j0 + sc16 : ep_j1 + sc16 - 128);
+                        if (r >= ep_i_end || colt >= (HALVES == 1 ? half_cols : K)) continue;
+                        const u32x4_t* sp = (const u32x4_t*)((const uint32_t*)(stg + rr * STG_PITCH) + 128 * p2 + sc16 / 2);
+                        const u32x4_t v0 = sp[0], v1 = sp[1];
+                        uint32_t mb = 0;
+                        mb = bf16_absmax_bits(mb, v0.x); mb = bf16_absmax_bits(mb, v0.y); mb = bf16_absmax_bits(mb, v0.z);
+                        mb = bf16_absmax_bits(mb, v0.w); mb = bf16_absmax_bits(mb, v1.x); mb = bf16_absmax_bits(mb, v1.y);
+                        mb = bf16_absmax_bits(mb, v1.z); mb = bf16_absmax_bits(mb, v1.w);
+                        float m = bf16_absmax_finish(mb);
+                        m = fmaxf(m, __shfl_xor(m, 1));                            // a 1x32 block = two neighbouring lanes
+                        const int er = mx_exponent(m);
+                        const float sr = mx_scale_f32(er);
+                        const int64_t at = (int64_t)r * width + (int64_t)p2 * K + colt;
+                        *(u32x4_t*)(a.out_q + at) = u32x4_t{mx_cvt4_bf16(v0.x, v0.y, sr), mx_cvt4_bf16(v0.z, v0.w, sr),
+                                                            mx_cvt4_bf16(v1.x, v1.y, sr), mx_cvt4_bf16(v1.z, v1.w, sr)};
+                        if ((lane & 1) == 0) a.out_q_e8[at >> 5] = (uint8_t)(er + 127);
+                        if (colq) {
+                            const f32x4_t* sp4 = (const f32x4_t*)(qe + (wave >> 2) * 512 + 256 * p2 + sc16);
+                            const f32x4_t s0 = sp4[0], s1 = sp4[1], s2 = sp4[2], s3 = sp4[3];
+                            *(u32x4_t*)(a.out_qc + at) = u32x4_t{mx_cvt4_bf16_each(v0.x, v0.y, s0[0], s0[1], s0[2], s0[3]),
+                                                                 mx_cvt4_bf16_each(v0.z, v0.w, s1[0], s1[1], s1[2], s1[3]),
+                                                                 mx_cvt4_bf16_each(v1.x, v1.y, s2[0], s2[1], s2[2], s2[3]),
+                                                                 mx_cvt4_bf16_each(v1.z, v1.w, s3[0], s3[1], s3[2], s3[3])};
                         }
                     }
                 }
@@ -1813,17 +1960,61 @@ extern "C" moe_status moe_grouped_gemm_fwd_weighted(moe_ctx* ctx, void* stream, 
                                       C_act, nullptr, nullptr);
 }
 
+// the MXFP8 outputs of a quantising epilogue: 1x32 copy (q_row, e8_row), optional 32x1 copy (q_col, e8_col)
+struct gg_mx_out {
+    void* q_row;
+    uint8_t* e8_row;
+    void* q_col;
+    uint8_t* e8_col;
+};
+static moe_status gg_mx_out_check(moe_ctx* ctx, const char* who, const gg_mx_out& o, moe_dtype dt, bool epi_ok, int64_t Rcap) {
+    if (!o.q_row || !o.e8_row) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: q_row and e8_row are required", who);
+    if ((o.q_col == nullptr) != (o.e8_col == nullptr)) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: q_col and e8_col go together", who);
+    if (dt != MOE_MXFP8_E4M3 || !epi_ok)
+        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "%s: needs dt = MOE_MXFP8_E4M3 and the SwiGLU (forward) / SwiGLU-backward (Z_saved) epilogue", who);
+    if (o.q_col && Rcap % 128) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: the 32x1 copy needs Rcap %% 128 == 0 (and 128-aligned experts)", who);
+    return MOE_OK;
+}
+
+static moe_status gg_fwd_all(moe_ctx* ctx, void* stream, const void* A, const void* B, const int32_t* offsets, int E, int N,
+                             int K, int64_t Rcap, moe_dtype dt, moe_epilogue epi, const float* a_scale, const float* b_scale,
+                             const float* row_prob, void* C, void* C_act, void* act_q, float* act_q_scale,
+                             const gg_mx_out* mxo);
+
 extern "C" moe_status moe_grouped_gemm_fwd_quant(moe_ctx* ctx, void* stream, const void* A, const void* B,
                                                  const int32_t* offsets, int E, int N, int K, int64_t Rcap,
                                                  moe_dtype dt, moe_epilogue epi,
                                                  const float* a_scale, const float* b_scale,
                                                  const float* row_prob, void* C, void* C_act,
                                                  void* act_q, float* act_q_scale) {
+    return gg_fwd_all(ctx, stream, A, B, offsets, E, N, K, Rcap, dt, epi, a_scale, b_scale, row_prob, C, C_act, act_q,
+                      act_q_scale, nullptr);
+}
+
+extern "C" moe_status moe_grouped_gemm_fwd_quant_mx(moe_ctx* ctx, void* stream, const void* A, const void* B,
+                                                    const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                                    const void* a_scale, const void* b_scale, const float* row_prob,
+                                                    void* C, void* C_act, void* act_q_row, uint8_t* act_e8_row,
+                                                    void* act_q_col, uint8_t* act_e8_col) {
+    if (!ctx) return MOE_ERR_ARG;
+    const gg_mx_out o = {act_q_row, act_e8_row, act_q_col, act_e8_col};
+    return gg_fwd_all(ctx, stream, A, B, offsets, E, N, K, Rcap, MOE_MXFP8_E4M3, MOE_EPI_SWIGLU, (const float*)a_scale,
+                      (const float*)b_scale, row_prob, C, C_act, nullptr, nullptr, &o);
+}
+
+static moe_status gg_fwd_all(moe_ctx* ctx, void* stream, const void* A, const void* B, const int32_t* offsets, int E, int N,
+                             int K, int64_t Rcap, moe_dtype dt, moe_epilogue epi, const float* a_scale, const float* b_scale,
+                             const float* row_prob, void* C, void* C_act, void* act_q, float* act_q_scale,
+                             const gg_mx_out* mxo) {
     if (!ctx) return MOE_ERR_ARG;
     if ((act_q == nullptr) != (act_q_scale == nullptr))
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_quant: act_q and act_q_scale go together");
     if (act_q && (dt != MOE_FP8_E4M3 || epi != MOE_EPI_SWIGLU))
         MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd_quant: quantised output needs dt = MOE_FP8_E4M3 and the SwiGLU epilogue");
+    if (mxo) {
+        moe_status stq = gg_mx_out_check(ctx, "moe_grouped_gemm_fwd_quant_mx", *mxo, dt, epi == MOE_EPI_SWIGLU, Rcap);
+        if (stq != MOE_OK) return stq;
+    }
     if (dt == MOE_F32) {  // all-fp32 path (gemm_f32.hip)
         if (!A || !B || !offsets) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: NULL pointer");
         if (E < 1 || N < 1 || K < 1 || Rcap < 1 || Rcap > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd: bad sizes");
@@ -1854,6 +2045,12 @@ extern "C" moe_status moe_grouped_gemm_fwd_quant(moe_ctx* ctx, void* stream, con
     a.row_prob = row_prob;
     a.out_q = (uint8_t*)act_q;
     a.out_q_scale = act_q_scale;
+    if (mxo) {
+        a.out_q = (uint8_t*)mxo->q_row;
+        a.out_q_e8 = mxo->e8_row;
+        a.out_qc = (uint8_t*)mxo->q_col;
+        a.out_qc_e8 = mxo->e8_col;
+    }
     if (epi == MOE_EPI_SWIGLU) {
         if (mx) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, 2);
         else if (fp8) GG_LAUNCH(GG_FWD, GG_EPI_SWIGLU, false, 1);
@@ -1884,13 +2081,41 @@ extern "C" moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream
                                         dA, dprob_part, nullptr, nullptr);
 }
 
+static moe_status gg_dgrad_all(moe_ctx* ctx, void* stream, const void* dC, const void* B, const int32_t* offsets, int E,
+                               int N, int K, int64_t Rcap, moe_dtype dt, const void* Z_saved, const float* dc_scale,
+                               const float* b_scale, const float* row_prob, void* dA, float* dprob_part, void* dz_q,
+                               float* dz_q_scale, const gg_mx_out* mxo);
+
 extern "C" moe_status moe_grouped_gemm_dgrad_quant(moe_ctx* ctx, void* stream, const void* dC, const void* B,
                                                    const int32_t* offsets, int E, int N, int K, int64_t Rcap,
                                                    moe_dtype dt, const void* Z_saved,
                                                    const float* dc_scale, const float* b_scale,
                                                    const float* row_prob, void* dA, float* dprob_part,
                                                    void* dz_q, float* dz_q_scale) {
+    return gg_dgrad_all(ctx, stream, dC, B, offsets, E, N, K, Rcap, dt, Z_saved, dc_scale, b_scale, row_prob, dA, dprob_part,
+                        dz_q, dz_q_scale, nullptr);
+}
+
+extern "C" moe_status moe_grouped_gemm_dgrad_quant_mx(moe_ctx* ctx, void* stream, const void* dC, const void* B,
+                                                      const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                                      const void* Z_saved, const void* dc_scale, const void* b_scale,
+                                                      const float* row_prob, void* dZ, float* dprob_part,
+                                                      void* dz_q_row, uint8_t* dz_e8_row, void* dz_q_col, uint8_t* dz_e8_col) {
     if (!ctx) return MOE_ERR_ARG;
+    const gg_mx_out o = {dz_q_row, dz_e8_row, dz_q_col, dz_e8_col};
+    return gg_dgrad_all(ctx, stream, dC, B, offsets, E, N, K, Rcap, MOE_MXFP8_E4M3, Z_saved, (const float*)dc_scale,
+                        (const float*)b_scale, row_prob, dZ, dprob_part, nullptr, nullptr, &o);
+}
+
+static moe_status gg_dgrad_all(moe_ctx* ctx, void* stream, const void* dC, const void* B, const int32_t* offsets, int E,
+                               int N, int K, int64_t Rcap, moe_dtype dt, const void* Z_saved, const float* dc_scale,
+                               const float* b_scale, const float* row_prob, void* dA, float* dprob_part, void* dz_q,
+                               float* dz_q_scale, const gg_mx_out* mxo) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (mxo) {
+        moe_status stq = gg_mx_out_check(ctx, "moe_grouped_gemm_dgrad_quant_mx", *mxo, dt, Z_saved != nullptr, Rcap);
+        if (stq != MOE_OK) return stq;
+    }
     if ((dz_q == nullptr) != (dz_q_scale == nullptr))
         MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_quant: dz_q and dz_q_scale go together");
     if (dz_q && (dt != MOE_FP8_E4M3 || !Z_saved))
@@ -1918,6 +2143,12 @@ extern "C" moe_status moe_grouped_gemm_dgrad_quant(moe_ctx* ctx, void* stream, c
     a.dprob_part = dprob_part;
     a.out_q = (uint8_t*)dz_q;
     a.out_q_scale = dz_q_scale;
+    if (mxo) {
+        a.out_q = (uint8_t*)mxo->q_row;
+        a.out_q_e8 = mxo->e8_row;
+        a.out_qc = (uint8_t*)mxo->q_col;
+        a.out_qc_e8 = mxo->e8_col;
+    }
     if (Z_saved) {
         if (mx) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 2);
         else if (fp8) GG_LAUNCH(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 1);

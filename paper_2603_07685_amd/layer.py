@@ -49,8 +49,9 @@ class LayerState:
         self.fused_quant = None if fused_quant is None else bool(fused_quant)   # (resolved below, once fp8_wgrad is known)
         # blockwise fp8 (default there): the SwiGLU / SwiGLU-backward epilogues also emit the 1x128 codes of their
         # output, the next GEMM's operand (Sec. 5.4.2); off = stand-alone quantiser launches
-        self.epilogue_quant = bool(cfg.fp8) and not cfg.mx if epilogue_quant is None else bool(epilogue_quant)
-        assert not self.epilogue_quant or (cfg.fp8 and not cfg.mx), "epilogue quantisation is built for the blockwise path"
+        # (MXFP8: the 1x32 codes and the 32x1 copy for the weight gradients; row counts are on the 128-row grid there)
+        self.epilogue_quant = bool(cfg.fp8 or cfg.mx) if epilogue_quant is None else bool(epilogue_quant)
+        assert not self.epilogue_quant or cfg.fp8 or cfg.mx, "epilogue quantisation belongs to the one-byte recipes"
         # blockwise fp8 (default there): the weight gradients also run on E4M3 codes, quantised 128x1 down the token
         # dimension inside each expert's 128-aligned row range (Sec. 5.3.2, 5.4.1); off = weight gradients from the
         # bf16 tensors.  (MXFP8 always runs them on its 32x1 copies.)
@@ -326,13 +327,8 @@ class LayerState:
             B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
             row_prob = self.row_prob
         eq = self.epilogue_quant
-        B.moe_grouped_gemm_fwd_quant(c, self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, F8, B.EPI_SWIGLU,
-                                     self.sXp, self.sW1, row_prob, self.Z, self.A,
-                                     self.qA if eq else None, self.sA if eq else None)
-        if not eq:
-            self._q_rows(self.A, self.qA, self.sA, Rcap, f, self.live_rows, self.qAc, self.sAc)
-        else:
-            self._q_cols(self.A, self.qAc, self.sAc, Rcap, f, self.live_rows)
+        self._fc1_fwd(self.qXp, self.qW1, self.offsets, E, 2 * f, h, Rcap, self.sXp, self.sW1, row_prob, self.Z, self.A,
+                      self.qA, self.sA, self.qAc, self.sAc, self.live_rows)
         B.moe_grouped_gemm_fwd(c, self.qA, self.qW2, self.offsets, E, h, f, Rcap, F8, B.EPI_NONE,
                                self.sA, self.sW2, self.O, None)
         if sf:
@@ -340,13 +336,8 @@ class LayerState:
             self._q_weight(self.Ws1.view(1, 2 * sf, h), self.qWs1, self.sWs1, self.qWs1d, self.sWs1d)
             self._q_weight(self.Ws2.view(1, h, sf), self.qWs2, self.sWs2, self.qWs2d, self.sWs2d)
             self._q_rows(self.X, self.qX, self.sX, T, h, None, self.qXc, self.sXc)
-            B.moe_grouped_gemm_fwd_quant(c, self.qX, self.qWs1, o1, 1, 2 * sf, h, T, F8, B.EPI_SWIGLU,
-                                         self.sX, self.sWs1, None, self.Zs, self.As,
-                                         self.qAs if eq else None, self.sAs if eq else None)
-            if not eq:
-                self._q_rows(self.As, self.qAs, self.sAs, T, sf, None, self.qAsc, self.sAsc)
-            else:
-                self._q_cols(self.As, self.qAsc, self.sAsc, T, sf)
+            self._fc1_fwd(self.qX, self.qWs1, o1, 1, 2 * sf, h, T, self.sX, self.sWs1, None, self.Zs, self.As,
+                          self.qAs, self.sAs, self.qAsc, self.sAsc, None)
             B.moe_grouped_gemm_fwd(c, self.qAs, self.qWs2, o1, 1, h, sf, T, F8, B.EPI_NONE,
                                    self.sAs, self.sWs2, self.S, None)
         B.moe_unpermute_combine(c, self.O, B.BF16, self.row_of, None if self.eq2 else self.topk_prob,
@@ -371,17 +362,11 @@ class LayerState:
                                             T, k, h, Rcap, self.dO, self.dprob)
             self._q_rows(self.dO, self.qdO, self.sdO, Rcap, h, self.live_rows, self.qdOc, self.sdOc)
         self._wgrad(self.A, self.dO, self.qAc, self.sAc, self.qdOc, self.sdOc, self.offsets, E, h, f, Rcap, self.dW2)
-        eq = self.epilogue_quant
-        B.moe_grouped_gemm_dgrad_quant(c, self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, F8, self.Z, self.sdO,
-                                       self.sW2d, self.row_prob if self.eq2 else None, self.dZ,
-                                       self.dprob_part if self.eq2 else None,
-                                       self.qdZ if eq else None, self.sdZ if eq else None)
+        self._fc2_dgrad(self.qdO, self.qW2d, self.offsets, E, h, f, Rcap, self.Z, self.sdO, self.sW2d,
+                        self.row_prob if self.eq2 else None, self.dZ, self.dprob_part if self.eq2 else None,
+                        self.qdZ, self.sdZ, self.qdZc, self.sdZc, self.live_rows)
         if self.eq2:
             B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
-        if not eq:
-            self._q_rows(self.dZ, self.qdZ, self.sdZ, Rcap, 2 * f, self.live_rows, self.qdZc, self.sdZc)
-        else:
-            self._q_cols(self.dZ, self.qdZc, self.sdZc, Rcap, 2 * f, self.live_rows)
         self._wgrad(self.Xp, self.dZ, self.qXpc, self.sXpc, self.qdZc, self.sdZc, self.offsets, E, 2 * f, h, Rcap, self.dW1)
         B.moe_grouped_gemm_dgrad(c, self.qdZ, self.qW1d, self.offsets, E, 2 * f, h, Rcap, F8, None, self.sdZ, self.sW1d,
                                  self.dXp)
@@ -389,16 +374,40 @@ class LayerState:
             o1 = self.off_shared
             self._q_rows(self.dY, self.qdY, self.sdY, T, h, None, self.qdYc, self.sdYc)
             self._wgrad(self.As, self.dY, self.qAsc, self.sAsc, self.qdYc, self.sdYc, o1, 1, h, sf, T, self.dWs2)
-            B.moe_grouped_gemm_dgrad_quant(c, self.qdY, self.qWs2d, o1, 1, h, sf, T, F8, self.Zs, self.sdY, self.sWs2d,
-                                           None, self.dZs, None, self.qdZs if eq else None, self.sdZs if eq else None)
-            if not eq:
-                self._q_rows(self.dZs, self.qdZs, self.sdZs, T, 2 * sf, None, self.qdZsc, self.sdZsc)
-            else:
-                self._q_cols(self.dZs, self.qdZsc, self.sdZsc, T, 2 * sf)
+            self._fc2_dgrad(self.qdY, self.qWs2d, o1, 1, h, sf, T, self.Zs, self.sdY, self.sWs2d, None, self.dZs, None,
+                            self.qdZs, self.sdZs, self.qdZsc, self.sdZsc, None)
             self._wgrad(self.X, self.dZs, self.qXc, self.sXc, self.qdZsc, self.sdZsc, o1, 1, 2 * sf, h, T, self.dWs1)
             B.moe_grouped_gemm_dgrad(c, self.qdZs, self.qWs1d, o1, 1, 2 * sf, h, T, F8, None, self.sdZs, self.sWs1d,
                                      self.dXs)
         B.moe_unpermute_combine(c, self.dXp, B.BF16, self.row_of, None, self.dXs if sf else None, T, k, h, self.dX)
+
+    def _fc1_fwd(self, qX, qW, offsets, E, N, K, rows, sX, sW, row_prob, Z, A, qA, sA, qAc, sAc, live):
+        """fc1 + SwiGLU and the quantised copies of the activation fc2 and its weight gradient read: from the GEMM's own
+        epilogue (Sec. 5.4.2) where that is built and switched on, else by quantiser launches."""
+        c, eq = self.ctx, self.epilogue_quant
+        if eq and self.mx:
+            B.moe_grouped_gemm_fwd_quant_mx(c, qX, qW, offsets, E, N, K, rows, sX, sW, row_prob, Z, A, qA, sA, qAc, sAc)
+            return
+        B.moe_grouped_gemm_fwd_quant(c, qX, qW, offsets, E, N, K, rows, self.f8dt, B.EPI_SWIGLU, sX, sW, row_prob, Z, A,
+                                     qA if eq else None, sA if eq else None)
+        if not eq:
+            self._q_rows(A, qA, sA, rows, N // 2, live, qAc, sAc)
+        else:
+            self._q_cols(A, qAc, sAc, rows, N // 2, live)
+
+    def _fc2_dgrad(self, qdO, qW, offsets, E, N, K, rows, Z, sdO, sW, row_prob, dZ, dprob_part, qdZ, sdZ, qdZc, sdZc, live):
+        """fc2 data gradient + SwiGLU backward and the quantised copies of dZ, as in _fc1_fwd."""
+        c, eq = self.ctx, self.epilogue_quant
+        if eq and self.mx:
+            B.moe_grouped_gemm_dgrad_quant_mx(c, qdO, qW, offsets, E, N, K, rows, Z, sdO, sW, row_prob, dZ, dprob_part,
+                                              qdZ, sdZ, qdZc, sdZc)
+            return
+        B.moe_grouped_gemm_dgrad_quant(c, qdO, qW, offsets, E, N, K, rows, self.f8dt, Z, sdO, sW, row_prob, dZ, dprob_part,
+                                       qdZ if eq else None, sdZ if eq else None)
+        if not eq:
+            self._q_rows(dZ, qdZ, sdZ, rows, 2 * K, live, qdZc, sdZc)
+        else:
+            self._q_cols(dZ, qdZc, sdZc, rows, 2 * K, live)
 
     def _wgrad(self, A, dC, qA, sA, qdC, sdC, offsets, E, N, K, rows, dW):
         """dW = dC^T A per expert: on the copies quantised down the rows (MXFP8: 32x1 blocks; blockwise: 128x1 tiles) or,

@@ -311,3 +311,31 @@ def test_fp8_epilogue_quantisation_is_bit_identical(eq2):
     for n in ("qAs", "sAs", "qdZs", "sdZs", "Y", "dX", "dW1", "dW2", "dprob", "dWs1", "dWs2"):
         assert torch.equal(getattr(a, n), getattr(b, n)), n
     assert not b.qA[R:].any() and not b.qdZ[R:].any()          # rows beyond the live ones are not written
+
+
+@pytest.mark.parametrize("eq2", [False, True])
+def test_mxfp8_epilogue_quantisation_is_bit_identical(eq2):
+    """C6S: the 1x32 and 32x1 copies of A and dZ (routed and shared expert) that the SwiGLU / SwiGLU-backward
+    epilogues emit equal those of the stand-alone row+column quantiser run on the stored bf16 tensor, so every
+    output of the step is bit-identical."""
+    from paper_2603_07685_amd import layer as L
+    from paper_2603_07685_amd import workloads as wl
+    cfg = wl.CONFIGS["C6S"]
+    hin = L.host_inputs(cfg)
+    a = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=False)
+    b = L.LayerState(cfg, hin, eq2=eq2, epilogue_quant=True)
+    names = ("qA", "sA", "qAc", "sAc", "qdZ", "sdZ", "qdZc", "sdZc", "qAs", "sAs", "qAsc", "sAsc", "qdZs", "sdZs", "qdZsc", "sdZsc")
+    for st in (a, b):
+        for n in names:
+            getattr(st, n).zero_()
+        st.step()
+    torch.cuda.synchronize()
+    assert a.ctx.poll_error() == 0 and b.ctx.poll_error() == 0
+    R = int(a.offsets[-1].item())
+    for n in ("qA", "sA", "qAc", "qdZ", "sdZ", "qdZc"):
+        assert torch.equal(getattr(a, n)[:R], getattr(b, n)[:R]), n
+    for n in ("sAc", "sdZc"):
+        assert torch.equal(getattr(a, n)[:R // 128], getattr(b, n)[:R // 128]), n
+    for n in ("qAs", "sAs", "qAsc", "sAsc", "qdZs", "sdZs", "qdZsc", "sdZsc", "Y", "dX", "dW1", "dW2", "dprob", "dWs1", "dWs2"):
+        assert torch.equal(getattr(a, n), getattr(b, n)), n
+    assert not b.qA[R:].any() and not b.qdZ[R:].any() and not b.qAc[R:].any() and not b.qdZc[R:].any()

@@ -281,3 +281,128 @@ def test_mx_wgrad_rejects_ranges_off_the_block_grid(B, ctx):
     torch.cuda.synchronize()
     assert ctx.poll_error() != 0
     assert (dW == 3.0).all()
+
+
+@pytest.mark.parametrize("counts,N,K,weighted,col", [
+    ([300, 0, 257, 1, 700], 512, 256, False, True),
+    ([513, 128, 5], 768, 384, True, True),
+    ([130, 90], 256, 128, True, False),
+])
+def test_mx_quantising_epilogue_fwd_bit_exact(B, ctx, oracle, counts, N, K, weighted, col):
+    """fc1 with the SwiGLU epilogue that also quantises (Sec. 5.4.2): Z and A are the plain call's bits, and the
+    1x32 / 32x1 copies are the oracle's quantisers applied to the stored A, bit for bit; rows beyond offsets[E]
+    are left alone."""
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets128(counts)
+    R = int(off[-1])
+    Rcap = R + 128
+    g = np.random.default_rng(N + K + 1)
+    Ah = wl.bf16_round((g.standard_normal((Rcap, K)) * np.exp(g.uniform(-2, 2, (Rcap, K // 32)).repeat(32, axis=1))).astype(np.float32))
+    for e, c in enumerate(counts):
+        Ah[off[e] + c: off[e + 1]] = 0.0
+    Wh = wl.bf16_round((g.standard_normal((E, N, K)) * 0.05 * np.exp(g.uniform(-2, 2, (E, N, K // 32)).repeat(32, axis=2))).astype(np.float32))
+    qa, ea = _mxq(B, ctx, dev_bf16(Ah), B.MX_1x32)
+    qw, ew = _mxq(B, ctx, dev_bf16(Wh.reshape(E * N, K)), B.MX_1x32)
+    rp = dev(g.uniform(0.05, 1.0, Rcap).astype(np.float32)) if weighted else None
+    f = N // 2
+    C0 = torch.zeros((Rcap, N), dtype=torch.bfloat16, device="cuda")
+    A0 = torch.zeros((Rcap, f), dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_fwd_weighted(ctx, qa, qw, dev(off), E, N, K, Rcap, B.MXFP8_E4M3, B.EPI_SWIGLU, ea, ew, rp, C0, A0)
+    C1, A1 = torch.zeros_like(C0), torch.zeros_like(A0)
+    qr = torch.full((Rcap, f), 7, dtype=torch.uint8, device="cuda")
+    er = torch.full((Rcap, f // 32), 7, dtype=torch.uint8, device="cuda")
+    qc = torch.full((Rcap, f), 7, dtype=torch.uint8, device="cuda") if col else None
+    ec = torch.full((Rcap // 128, f, 4), 7, dtype=torch.uint8, device="cuda") if col else None
+    B.moe_grouped_gemm_fwd_quant_mx(ctx, qa, qw, dev(off), E, N, K, Rcap, ea, ew, rp, C1, A1, qr, er, qc, ec)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    assert torch.equal(C0.view(torch.int16), C1.view(torch.int16)) and torch.equal(A0.view(torch.int16), A1.view(torch.int16))
+    Ast = A1.float().cpu().numpy()
+    qr_o, er_o = oracle.mx_quant_1x32(Ast)
+    assert np.array_equal(er.cpu().numpy()[:R], er_o[:R]) and np.array_equal(qr.cpu().numpy()[:R], qr_o[:R])
+    assert (qr[R:] == 7).all() and (er[R:] == 7).all()
+    if col:
+        qc_o, ec_o = oracle.mx_quant_32x1(Ast[None])
+        assert np.array_equal(_col_scales(ec, 1, Rcap, f)[0, :, :R // 32], ec_o[0, :, :R // 32])
+        assert np.array_equal(qc.cpu().numpy()[:R], qc_o[0, :R])
+        assert (qc[R:] == 7).all() and (ec[R // 128:] == 7).all()
+
+
+@pytest.mark.parametrize("counts,N,K,weighted,col", [
+    ([300, 0, 257, 1, 700], 256, 512, False, True),
+    ([513, 128, 5], 384, 384, True, True),
+    ([130, 90], 128, 256, True, False),
+])
+def test_mx_quantising_epilogue_dgrad_bit_exact(B, ctx, oracle, counts, N, K, weighted, col):
+    """fc2 data gradient with the SwiGLU-backward epilogue that also quantises dZ: dZ and the dprob partials are
+    the plain call's bits, the two quantised copies the oracle's quantisers applied to the stored dZ."""
+    from gpu_util import dev, dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    E = len(counts)
+    off = _offsets128(counts)
+    R = int(off[-1])
+    Rcap = R + 128
+    g = np.random.default_rng(N * 3 + K + 1)
+    dCh = wl.bf16_round((g.standard_normal((Rcap, N)) * np.exp(g.uniform(-2, 2, (Rcap, N // 32)).repeat(32, axis=1))).astype(np.float32))
+    for e, c in enumerate(counts):
+        dCh[off[e] + c: off[e + 1]] = 0.0
+    Wh = wl.bf16_round((g.standard_normal((E, N, K)) * 0.05 * np.exp(g.uniform(-2, 2, (E, N // 32, K)).repeat(32, axis=1))).astype(np.float32))
+    qd, ed = _mxq(B, ctx, dev_bf16(dCh), B.MX_1x32)
+    qw, ew = _mxq(B, ctx, dev_bf16(Wh), B.MX_32x1)
+    Z = dev_bf16(wl.gaussian_bf16((Rcap, 2 * K), 1.5, 35, K))
+    rp = dev(g.uniform(0.05, 1.0, Rcap).astype(np.float32)) if weighted else None
+    parts = 2 * ((K + 255) // 256)
+    dZ0 = torch.zeros((Rcap, 2 * K), dtype=torch.bfloat16, device="cuda")
+    dp0 = torch.zeros((Rcap, parts), dtype=torch.float32, device="cuda") if weighted else None
+    B.moe_grouped_gemm_dgrad_weighted(ctx, qd, qw, dev(off), E, N, K, Rcap, B.MXFP8_E4M3, Z, ed, ew, rp, dZ0, dp0)
+    dZ1 = torch.zeros_like(dZ0)
+    dp1 = torch.zeros_like(dp0) if weighted else None
+    qr = torch.full((Rcap, 2 * K), 7, dtype=torch.uint8, device="cuda")
+    er = torch.full((Rcap, 2 * K // 32), 7, dtype=torch.uint8, device="cuda")
+    qc = torch.full((Rcap, 2 * K), 7, dtype=torch.uint8, device="cuda") if col else None
+    ec = torch.full((Rcap // 128, 2 * K, 4), 7, dtype=torch.uint8, device="cuda") if col else None
+    B.moe_grouped_gemm_dgrad_quant_mx(ctx, qd, qw, dev(off), E, N, K, Rcap, Z, ed, ew, rp, dZ1, dp1, qr, er, qc, ec)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    assert torch.equal(dZ0.view(torch.int16), dZ1.view(torch.int16))
+    if weighted:
+        assert torch.equal(dp0, dp1)
+    Zst = dZ1.float().cpu().numpy()
+    qr_o, er_o = oracle.mx_quant_1x32(Zst)
+    assert np.array_equal(er.cpu().numpy()[:R], er_o[:R]) and np.array_equal(qr.cpu().numpy()[:R], qr_o[:R])
+    assert (qr[R:] == 7).all() and (er[R:] == 7).all()
+    if col:
+        qc_o, ec_o = oracle.mx_quant_32x1(Zst[None])
+        assert np.array_equal(_col_scales(ec, 1, Rcap, 2 * K)[0, :, :R // 32], ec_o[0, :, :R // 32])
+        assert np.array_equal(qc.cpu().numpy()[:R], qc_o[0, :R])
+        assert (qc[R:] == 7).all() and (ec[R // 128:] == 7).all()
+
+
+def test_mx_quantising_epilogue_rejects_bad_requests(B, ctx):
+    """No row-wise outputs, the wrong epilogue, or a capacity off the 128-row grid with the 32x1 copy: refused on the
+    host; expert ranges off the grid with the 32x1 copy: the device error word."""
+    from gpu_util import dev
+    R, N, K = 512, 256, 128
+    q = torch.zeros((R, K), dtype=torch.uint8, device="cuda")
+    e = torch.full((R, K // 32), 127, dtype=torch.uint8, device="cuda")
+    qw = torch.zeros((2 * N, K), dtype=torch.uint8, device="cuda")
+    ew = torch.full((2 * N, K // 32), 127, dtype=torch.uint8, device="cuda")
+    A = torch.zeros((R, N // 2), dtype=torch.bfloat16, device="cuda")
+    qr = torch.zeros((R, N // 2), dtype=torch.uint8, device="cuda")
+    er = torch.zeros((R, N // 64), dtype=torch.uint8, device="cuda")
+    ec = torch.zeros((R // 128, N // 2, 4), dtype=torch.uint8, device="cuda")
+    off = dev(np.array([0, 256, 512], np.int32))
+    with pytest.raises(B.MoeError):
+        B.moe_grouped_gemm_fwd_quant_mx(ctx, q, qw, off, 2, N, K, R, e, ew, None, None, A, None, None, None, None)
+    with pytest.raises(B.MoeError):
+        B.moe_grouped_gemm_fwd_quant_mx(ctx, q, qw, off, 2, N, K, R, e, ew, None, None, A, qr, er, qr, None)
+    with pytest.raises(B.MoeError):
+        B.moe_grouped_gemm_fwd_quant_mx(ctx, q, qw, off, 2, N, K, R - 64, e, ew, None, None, A, qr, er, qr, ec)
+    with pytest.raises(B.MoeError):   # the data gradient without saved pre-activations has nothing to quantise
+        B.moe_grouped_gemm_dgrad_quant_mx(ctx, qr, qw, off, 2, N // 2, K, R, None, er, ew, None, A, None, qr, er, None, None)
+    B.moe_grouped_gemm_fwd_quant_mx(ctx, q, qw, dev(np.array([0, 200, 512], np.int32)), 2, N, K, R, e, ew, None, None, A,
+                                    qr, er, torch.zeros_like(qr), ec)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() != 0
