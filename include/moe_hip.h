@@ -225,9 +225,10 @@ moe_status moe_permute_static(void* stream, const void* X, moe_dtype dt,
  * dt is the operand type: MOE_BF16 (fp32 accumulation, bf16 result) or
  * MOE_FP8_E4M3 (blockwise recipe of Sec. 5.3.2: operands are E4M3 codes with
  * fp32 scales, fp32 accumulation, bf16 result; the accumulators are carried in units of
- * the current 128-wide block's scales, so the scales met along one contraction must be
- * normal numbers within 2^100 of each other, which amax / 448 of bf16 data always is
- * unless a block's amax is below 2^-117).  N and K must be multiples of
+ * the current 128-wide block's scales, so every scale must be a normal number and the product
+ * of the two operands' scales may change from one block of a contraction to the next by a
+ * factor of at most 2^100 either way; amax / 448 of bf16 data meets that unless blocks with
+ * amax below 2^-60 alternate with blocks near the top of the bf16 range).  N and K must be multiples of
  * 128 (fp8) / 16 (bf16); in bf16 the contraction dimension of fwd (K) and of
  * dgrad (N) must also be a multiple of 64 (one 128-byte operand row per stage);
  * wgrad contracts over the expert's rows, any count.  Sizes outside these limits
@@ -274,9 +275,9 @@ moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const void* dC, co
  *        a_scale [Rcap/128, K], dc_scale [Rcap/128, N] fp32; MXFP8 in 32x1 blocks (see
  *        moe_mx_quantize).  A scale block must not straddle two experts: every offsets[e] must be a
  *        multiple of 128 (moe_permute with align = 128), otherwise the error word is raised and dB is
- *        left untouched.  Blockwise: the block scales of one operand row / column may differ from one
- *        128-row block to the next by up to 2^100 (the accumulators are carried in units of the current
- *        block's scales).
+ *        left untouched.  Blockwise: the product of a row's and a column's block scales may change from
+ *        one 128-row block to the next by a factor of at most 2^100 either way (the accumulators are
+ *        carried in units of the current block's scales).
  */
 moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, const void* dC,
                                   const int32_t* offsets, int E, int N, int K, int64_t Rcap,

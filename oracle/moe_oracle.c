@@ -10,8 +10,12 @@
  * The file is compiled twice, with -DREAL=double -DSFX=f64 (the parity
  * authority) and -DREAL=float -DSFX=f32 (the "plain fp32 CPU implementation"
  * whose time is reported beside the GPU's).  Integer steps do not depend on REAL.
- * OpenMP is used only across independent rows / experts; there is no blocking,
- * fusion or reordering of the arithmetic.
+ * OpenMP threads split only independent rows / experts; there is no blocking or
+ * fusion.  One reordering exists: the dot-product loop of grouped_gemm_nt
+ * carries "omp simd reduction(+)", so the compiler may add a dot product's terms in
+ * several partial sums (vector lanes) instead of strictly left to right.  In the
+ * fp64 build, the parity authority, that moves results by a few 1e-16 relative,
+ * far below every bound used; the fp32 build is the timed baseline only.
  *
  * What each function follows:
  *   route_topk        Sec. 1.1 (p = Softmax(W_r x), sum over TopK) and Sec. 2.1.2

@@ -313,3 +313,43 @@ def test_fp8_wgrad_needs_aligned_experts_and_scales(B, ctx):
     with pytest.raises(B.MoeError):
         B.moe_grouped_gemm_wgrad(ctx, qa, qd, dev(np.array([0, 128, 256], np.int32)), 2, 128, 128, 256, B.FP8_E4M3, None,
                                  None, 0, B.BF16, dW)
+
+
+def test_fp8_block_scales_24_decades_apart(B, ctx, oracle):
+    """The accumulators of the blockwise GEMMs are carried in units of the current block's scales: consecutive
+    blocks whose scale products differ by 1e24 in either direction (the documented limit is 2^100) must neither
+    overflow nor lose the large blocks.  Forward (row scale x weight-block scale) and weight gradient (row scale x
+    column scale of the two 128x1-quantised operands), against the oracle's quantise-dequantise emulation."""
+    from gpu_util import dev, dev_bf16, host_f64, assert_close
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(2024)
+    E, R, N, K = 2, 512, 256, 512
+    off = np.array([0, 256, 512], np.int32)
+    # forward: contraction blocks alternate between 1e6 and 1e-6 in both operands; some rows start small, some big
+    kmag = np.where(np.arange(K // 128) % 2 == 0, 1e6, 1e-6).repeat(128)
+    flip = np.where(np.arange(R) % 3 == 0, 1.0, 0.0)[:, None]
+    amag = np.where(flip > 0, kmag[::-1][None, :], kmag[None, :])
+    Ah = wl.bf16_round((g.standard_normal((R, K)) * amag).astype(np.float32))
+    Wh = wl.bf16_round((g.standard_normal((E, N, K)) * kmag[None, None, :]).astype(np.float32))
+    qa, sa = _quant(B, ctx, dev_bf16(Ah), B.Q_1x128)
+    qw, sw = _quant(B, ctx, dev_bf16(Wh), B.Q_128x128)
+    C = torch.full((R, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.moe_grouped_gemm_fwd(ctx, qa, qw, dev(off), E, N, K, R, B.FP8_E4M3, B.EPI_NONE, sa, sw, C, None)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    emu = oracle.grouped_gemm_nt(oracle.fp8_dequant(qa.cpu().numpy(), sa.cpu().numpy(), "1x128"),
+                                 oracle.fp8_dequant(qw.cpu().numpy(), sw.cpu().numpy(), "128x128"), off)
+    assert_close(host_f64(C), emu, "forward, 1e24 between blocks", tol=EMU_TOL, reg=None, row_tol=2e-2)
+    # weight gradient: 128-row blocks alternate between 1e6 and 1e-6 in both operands
+    rmag = np.where(np.arange(R // 128) % 2 == 0, 1e6, 1e-6).repeat(128)[:, None]
+    dCh = wl.bf16_round((g.standard_normal((R, N)) * rmag).astype(np.float32))
+    A2 = wl.bf16_round((g.standard_normal((R, K)) * rmag).astype(np.float32))
+    qd, sd = _quant(B, ctx, dev_bf16(dCh), B.Q_128x1)
+    q2, s2 = _quant(B, ctx, dev_bf16(A2), B.Q_128x1)
+    dW = torch.full((E, N, K), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_grouped_gemm_wgrad(ctx, q2, qd, dev(off), E, N, K, R, B.FP8_E4M3, s2, sd, 0, B.F32, dW)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    emu = oracle.grouped_gemm_tn(oracle.fp8_dequant(qd.cpu().numpy(), sd.cpu().numpy(), "128x1"),
+                                 oracle.fp8_dequant(q2.cpu().numpy(), s2.cpu().numpy(), "128x1"), off)
+    assert_close(host_f64(dW), emu, "weight gradient, 1e24 between blocks", tol=1e-4, reg=None, row_tol=1e-3)

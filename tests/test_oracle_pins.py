@@ -762,3 +762,31 @@ def test_assert_close_catches_a_wrong_row_that_a_pooled_norm_hides():
         assert_close(drift, ref, "drift")
     z = np.zeros((4, 8))
     assert_close(z, z, "zeros")                                          # empty experts: exact zeros pass
+
+
+def test_fp8_blockwise_scales_far_apart(oracle):
+    """Blocks 24 decades apart along one contraction: the oracle's quantise-dequantise has no dynamic-range limit
+    of its own (each block is scaled by its own fp32 amax / 448): every element comes back within the format's
+    half-ulp (2^-4 relative for normal codes), and the emulated product equals the block-scaled form
+    sum_b s_A[r, b] s_W[b] (codes_A_b . codes_W_b) evaluated in exact rational arithmetic on a small case."""
+    from fractions import Fraction
+    g = _rng(77)
+    R, K = 6, 512
+    kmag = np.where(np.arange(K // 128) % 2 == 0, 1e12, 1e-12).repeat(128)
+    A = (g.standard_normal((R, K)) * kmag).astype(np.float32)
+    q, s = oracle.fp8_quant_1x128(A)
+    assert s.shape == (R, K // 128) and np.all(s[:, 0] > 1e9) and np.all(s[:, 1] < 1e-13)
+    Ad = oracle.fp8_dequant(q, s, "1x128")
+    big = np.abs(A) >= (np.repeat(s, 128, axis=1) * 2.0 ** -6)           # normal codes only
+    assert np.all(np.abs(Ad - A)[big] <= 2.0 ** -4 * np.abs(A)[big] * (1 + 1e-6))
+    w = (g.standard_normal(K) * kmag).astype(np.float32)
+    qw, sw = oracle.fp8_quant_1x128(w[None])
+    wd = oracle.fp8_dequant(qw, sw, "1x128")[0]
+    emu = Ad @ wd
+    for r in range(R):
+        tot = Fraction(0)
+        for b in range(K // 128):
+            blk = sum(Fraction(float(oracle.e4m3_decode(int(q[r, b * 128 + i])))) * Fraction(float(oracle.e4m3_decode(int(qw[0, b * 128 + i]))))
+                      for i in range(128))
+            tot += Fraction(float(s[r, b])) * Fraction(float(sw[0, b])) * blk
+        assert abs(float(tot) - emu[r]) <= 1e-12 * abs(float(tot))
