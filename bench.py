@@ -41,6 +41,25 @@ def measured_traffic(workload: str, label: str):
     return None
 
 
+def mfma_ceiling():
+    """Context only: what the matrix pipes of this box sustain with every operand in registers (no LDS, no memory),
+    measured by paper_2603_07685_amd/csrc/mfma_ceiling.hip for the two MFMA shapes the grouped GEMMs use, on zeros
+    (nominal rate) and on random operands (the power-limited rate a kernel on real data can approach).  None if the
+    probe library is not built."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2603_07685_amd", "libmfma_ceiling.so")
+    if not os.path.exists(path):
+        return None
+    lib = ctypes.CDLL(path)
+    lib.mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
+    res = {"what": "register-resident MFMA loop, TFLOP/s: v_mfma_f32_16x16x32_bf16 / v_mfma_scale_f32_32x32x64_f8f6f4 (E4M3)"}
+    for name, fp8, rnd in (("bf16_zeros", 0, 0), ("bf16_random", 0, 1), ("fp8_zeros", 1, 0), ("fp8_random", 1, 1)):
+        v = ctypes.c_float(0.0)
+        rc = lib.mfma_ceiling(fp8, rnd, 300, ctypes.byref(v))
+        res[name] = round(v.value, 1) if rc == 0 else None
+    return res
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -391,6 +410,7 @@ def main():
                             "tflops": round(2.0 * m_ref * 4096 * cfg.h * 10 / r0.elapsed_time(r1) / 1e9, 1)}
     del o_ref
     del a_ref, b_ref
+    out["box_reference"]["mfma_ceiling"] = mfma_ceiling()
     if not args.no_cpu_baseline:
         v, cores, desc = cpu_baseline(st, torch)
         out["cpu_baseline"] = {"value": round(v, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle", "sample": desc}

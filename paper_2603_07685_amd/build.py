@@ -50,7 +50,21 @@ def build_library(verbose: bool = False, jobs: int = 8, extra_flags=(), out: str
     lib = out or LIB
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     subprocess.check_call(cmd)
+    if out is None:
+        build_ceiling_probe(hipcc)
     return lib
+
+
+CEILING_LIB = os.path.join(PKG, "libmfma_ceiling.so")
+
+
+def build_ceiling_probe(hipcc: str) -> str:
+    """The register-resident MFMA rate probe bench.py reports beside its numbers: a library of its own (one exported
+    function, no part of the layer's C ABI)."""
+    flags = [f for f in HIPCC_FLAGS if f != "-Rpass-analysis=kernel-resource-usage"]
+    subprocess.check_call([hipcc, *flags, "-shared", os.path.join(CSRC, "mfma_ceiling.hip"), "-o", CEILING_LIB],
+                          stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    return CEILING_LIB
 
 
 def _max_scratch(log: str):
