@@ -71,7 +71,10 @@ def trace(d: str, bench_path: str | None = None):
         a = agg.setdefault(_short(r["Kernel_Name"]), [0, 0.0])
         a[0] += 1
         a[1] += (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
-    tot = sum(v[1] for v in agg.values())
+    # (bench.py's context measurements -- the vendor GEMM and the register-resident MFMA loop -- are listed but left
+    # out of the percentages)
+    context = lambda n: "ceiling_kernel" in n or "Cijk" in n
+    tot = sum(v[1] for n, v in agg.items() if not context(n))
     if bench_path:
         b = _bench(bench_path)
         print(f"# bench.py reported in the same run: {b['ms_per_step']} ms per fwd+bwd step, {b['value']} {b['unit']}; "
@@ -79,8 +82,9 @@ def trace(d: str, bench_path: str | None = None):
     print("# " + LEGEND)
     print("# durations in microseconds")
     print(f"{'kernel':72s} {'calls':>6s} {'total_us':>12s} {'avg_us':>10s} {'pct':>6s}")
-    for n, (cnt, t) in sorted(agg.items(), key=lambda kv: -kv[1][1])[:20]:
-        print(f"{n:72s} {cnt:6d} {t:12.1f} {t / cnt:10.1f} {100 * t / tot:6.2f}")
+    for n, (cnt, t) in sorted(agg.items(), key=lambda kv: -kv[1][1])[:22]:
+        pct = "   ctx" if context(n) else f"{100 * t / tot:6.2f}"
+        print(f"{n:72s} {cnt:6d} {t:12.1f} {t / cnt:10.1f} {pct}")
     steps, cur = [], None
     for r in rows:
         sn = _short(r["Kernel_Name"])
