@@ -60,7 +60,10 @@ typedef enum { MOE_EPI_NONE = 0, MOE_EPI_SWIGLU = 1 } moe_epilogue;
 
 /* Bytes of workspace the calls below need for problems up to the given sizes
  * (host, pure function).  T tokens, k slots per token, E experts, h hidden,
- * f_max the largest expert width used with this context. */
+ * f_max the largest expert width used with this context.  The largest part is
+ * the room for the weight gradient's split contraction (see
+ * moe_grouped_gemm_wgrad): 8 fp32 copies of one expert's largest weight gradient,
+ * 8 * 2 f_max * h * 4 bytes rounded up to whole 256 x 256 tiles. */
 size_t moe_workspace_bytes(int T, int k, int E, int h, int f_max);
 
 /* Create a context on `device` and allocate `workspace_bytes` of device memory
@@ -267,9 +270,13 @@ moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const void* dC, co
  *        The contraction length is the expert's (padded) row count, read from
  *        `offsets`; an expert with no rows gets dB_e = 0 (accumulate = 0) or is
  *        left as it is (accumulate != 0: dB += ...).  out_dt: MOE_BF16 or MOE_F32.
- *        Under a skewed load the tiles are handed out through a counter in the context's
- *        reserved workspace (results are unaffected): wgrad calls on one context must not
- *        overlap in time.
+ *        Under a skewed load (largest expert above twice the mean; decided on the device from
+ *        `offsets`) the tiles are handed out through a counter in the context's reserved workspace
+ *        and, for bf16 operands, the contraction of every expert above twice the mean is split into
+ *        up to 8 pieces whose fp32 partial tiles go to the workspace and are added in piece order by
+ *        a second kernel of the same call.  Which workgroup computes what varies from run to run,
+ *        what is added to what, and in which order, does not: results are bit-identical run to
+ *        run.  wgrad calls on one context must not overlap in time.
  *        One-byte operands are quantised down the token dimension, the contraction of this call
  *        (Sec. 5.4.1): blockwise fp8 in 128x1 tiles (moe_fp8_quantize, MOE_Q_128x1),
  *        a_scale [Rcap/128, K], dc_scale [Rcap/128, N] fp32; MXFP8 in 32x1 blocks (see
