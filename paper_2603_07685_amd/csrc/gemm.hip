@@ -35,10 +35,11 @@
 //   per stage s:  A(s,0) | B(s,0) | A(s,1) | B(s,1)    A: LDS -> registers,  B: MFMAs,  '|' = barrier
 //   group 1 (waves 4-7) takes one extra barrier up front, group 0 one at the end; in time:
 //     group 0:  A(s,0)*   B(s,0)   A(s,1)   B(s,1)   A(s+1,0)* ...
-//     group 1:  B(s-1,1)* A(s,0)   B(s,0)   A(s,1)   B(s,1)*   ...      (* = issues its half of stage s+1)
+//     group 1:  B(s-1,1)* A(s,0)   B(s,0)   A(s,1)   B(s,1)*   ...      (* = issues its half of stage s+1; group 1: or at A(s,0))
 // Buffer (s+1)%2 was last read in A(s-1,1); group 1 finishes that phase one barrier before group 0
-// enters A(s,0), so group 0 refills it at the start of A(s,0) and group 1, in the same slot, between
-// the MFMAs of its B(s-1,1).  Each wave waits for its own loads of stage s+1 before the barrier that
+// enters A(s,0), so group 0 refills it at the start of A(s,0) and group 1 either in the same slot, between
+// the MFMAs of its B(s-1,1) (weight gradients), or one slot later at the start of its own A(s,0) (forward,
+// data gradient: see the stage loop).  Each wave waits for its own loads of stage s+1 before the barrier that
 // precedes group 0's A(s+1,0): group 0 at the end of B(s,1), group 1 at the end of A(s,1).
 // The first stage of a tile is issued before the epilogue of the tile before it.
 //
@@ -1187,7 +1188,13 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             } else if (KT > 0) {
                 wait_vm0();
                 stage_barrier();
-                if (KT > 1) {  // slot 1: group 0 reads stage 0, both groups issue their share of stage 1
+                // Where group 1 issues its share of a stage.  Weight gradients: between the MFMAs of its B(j,1), in the
+                // same slot as group 0 (the first slot the buffer is free).  Forward and data gradient: one slot later, at
+                // the start of its A(j+1,0), like group 0 in its own: the memory pipe then takes the two groups' 32 KB in
+                // two slots instead of 64 KB in one, where the second group's issue blocked for ~1200 cycles per
+                // stage (per-slot timestamps); 1-2 % per call, the weight gradients lose as much and keep the old place.
+                constexpr bool DMA_IN_B = MODE == GG_WGRAD;
+                if (DMA_IN_B && KT > 1) {  // slot 1: group 0 reads stage 0, both groups issue their share of stage 1
 #pragma unroll
                     for (int x = 0; x < 2 * CH; ++x) issue_one(1, SP[1], SQ[1], x);
                     if (FP8) issue_scales(1, SS[1]);
@@ -1195,6 +1202,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 if (PF && 2 < KT_pf) prefetch(2);
                 stage_barrier();  // group 0's first slot
                 auto stage1 = [&](int j, int s) {
+                    if (!DMA_IN_B && j + 1 < KT) {
+#pragma unroll
+                        for (int x = 0; x < 2 * CH; ++x) issue_one(j + 1, SP[s ^ 1], SQ[s ^ 1], x);
+                        if (FP8) issue_scales(j + 1, SS[s ^ 1]);
+                    }
                     half_a(s, 0);
                     stage_barrier();
                     mma(false, 0, nullptr, nullptr, 0);
@@ -1203,8 +1215,8 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     if (PF && j + 2 < KT_pf) wait_vm1();  // stage j+1 landed (issued before the warm-up load of stage j+2)
                     else wait_vm0();
                     stage_barrier();
-                    mma(j + 2 < KT, j + 2, SP[s], SQ[s], 1);
-                    if (FP8 && j + 2 < KT) issue_scales(j + 2, SS[s]);
+                    mma(DMA_IN_B && j + 2 < KT, j + 2, SP[s], SQ[s], 1);
+                    if (DMA_IN_B && FP8 && j + 2 < KT) issue_scales(j + 2, SS[s]);
                     if (PF && j + 3 < KT_pf) prefetch(j + 3);
                     stage_barrier();
                 };

@@ -126,10 +126,11 @@ def _calibration(F, W):
 
 def _traffic_rows(fd: str, wd: str):
     F, W = _pmc(fd), _pmc(wd)
-    assert len(F) == len(W), (len(F), len(W))
     cal = _calibration(F, W)
     kf, kw = GIB / cal[1], GIB / cal[2]
     Fs, Ws = _last_step(F, lambda r: r["name"]), _last_step(W, lambda r: r["name"])
+    # (the two passes are two runs: what bench.py launches after its timed steps may differ in count, a step may not)
+    assert [r["name"] for r in Fs] == [r["name"] for r in Ws], (len(Fs), len(Ws))
     rows = [(_short(f["name"]), f["FETCH_SIZE"] * 1024 * kf / 1e9, w["WRITE_SIZE"] * 1024 * kw / 1e9)
             for f, w in zip(Fs, Ws) if _is_site(f["name"])]
     return cal, rows
