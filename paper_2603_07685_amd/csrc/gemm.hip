@@ -1174,8 +1174,14 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             } else if (KT > 0 && wm == 0) {
                 wait_vm0();  // stage 0, issued before the previous tile's epilogue
                 stage_barrier();
+                // Where group 0 issues its share of stage j+1: at the top of A(j,0), in one run (the first moment the buffer
+                // is free), or -- blockwise weight gradient -- between the MFMAs of B(j,0), one slot after group 1 has
+                // done the same in its B(j-1,1): the memory pipe then sees 32 KB per slot, each run hidden behind a
+                // group's MFMAs (7-9 % per call there; the other variants pay for the address registers that must
+                // then live beside the fragments with spills inside the loop, or simply do not gain).
+                constexpr bool G0_DMA_IN_B = BW_WGRAD;
                 auto stage0 = [&](int j, int s) {
-                    if (j + 1 < KT) {
+                    if (!G0_DMA_IN_B && j + 1 < KT) {
 #pragma unroll
                         for (int x = 0; x < 2 * CH; ++x) issue_one(j + 1, SP[s ^ 1], SQ[s ^ 1], x);
                         if (FP8) issue_scales(j + 1, SS[s ^ 1]);
@@ -1184,7 +1190,8 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     if (pf) prefetch(j + 2);
                     half_a(s, 0);
                     stage_barrier();
-                    mma(false, 0, nullptr, nullptr, 0);
+                    mma(G0_DMA_IN_B && j + 1 < KT, j + 1, SP[s ^ 1], SQ[s ^ 1], 0);
+                    if (G0_DMA_IN_B && FP8 && j + 1 < KT) issue_scales(j + 1, SS[s ^ 1]);
                     stage_barrier();
                     half_a(s, 1);
                     stage_barrier();
