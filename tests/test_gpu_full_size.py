@@ -142,6 +142,34 @@ def test_full_size_sampled(oracle, name, variant):
         chk("dZ", _f64(st.dZ[rt]), oracle.swiglu_bwd(oracle.grouped_gemm_nn(dOg, W2, one(n)), Zg), tag)
         chk("dXp", _f64(st.dXp[rt]), oracle.grouped_gemm_nn(_f64(st.dZ[rt]), W1, one(n)), tag)
         del W1, W2
+        if one_byte:
+            # the quantised copies the GEMMs read (made by quantiser launches or by the GEMM epilogues): bit for bit the
+            # oracle's quantisers applied to the stored bf16 tensor -- the row-wise copies on the sampled rows, the
+            # column-wise copies (the weight gradients' operands) on one 128-row group of the expert
+            for nm, qn, sn in (("A", "qA", "sA"), ("dZ", "qdZ", "sdZ")):
+                qo, eo = row_quant(_f64(getattr(st, nm)[rt]))
+                assert np.array_equal(getattr(st, qn)[rt].cpu().numpy(), qo), (nm, tag, "row-wise codes")
+                assert np.array_equal(getattr(st, sn)[rt].cpu().numpy(), eo), (nm, tag, "row-wise scales")
+            if fp8_wgrad and cfg.align % 128 == 0:
+                gi = int(g.integers(0, (int(off[e + 1]) - lo) // 128))
+                r0 = lo + 128 * gi
+                grp = torch.arange(r0, r0 + 128, device="cuda")
+                # (256 columns of each tensor: a column's blocks do not depend on the other columns, and the oracle's
+                # nearest-code search is slow)
+                wcol = {"A": f, "dZ": 2 * f, "Xp": h, "dO": h}
+                for nm, qn, sn in (("A", "qAc", "sAc"), ("dZ", "qdZc", "sdZc"), ("Xp", "qXpc", "sXpc"), ("dO", "qdOc", "sdOc")):
+                    c0 = int(g.integers(0, wcol[nm] // 256)) * 256
+                    cs = slice(c0, c0 + 256)
+                    blk = {"A": lambda: st.A[grp, cs], "dZ": lambda: st.dZ[grp, cs], "Xp": lambda: permuted_rows(st, grp, cs),
+                           "dO": lambda: combine_bwd_rows(st, grp, cs)}[nm]()
+                    if cfg.mx:
+                        qo, eo = oracle.mx_quant_32x1(_f64(blk)[None])
+                        qo, eo = qo[0], eo[0]                  # [128, 256] codes, [256, 4] E8M0 bytes of the group
+                    else:
+                        qo, eo = oracle.fp8_quant_128x1(_f64(blk))
+                        eo = eo[0]                             # [256] fp32 scales of the group
+                    assert np.array_equal(getattr(st, qn)[grp, cs].cpu().numpy(), qo), (nm, tag, "column-wise codes")
+                    assert np.array_equal(getattr(st, sn)[r0 // 128, cs].cpu().numpy(), eo), (nm, tag, "column-wise scales")
         # weight-gradient windows, contracted over every row of the expert
         hi_pad = hi
         allr = torch.arange(lo, hi_pad, device="cuda")
