@@ -78,6 +78,9 @@ def parse():
                     help="blockwise fp8 workloads: weight gradients from the bf16 tensors instead of the 128x1 E4M3 copies")
     ap.add_argument("--no-epilogue-quant", action="store_true",
                     help="one-byte recipes: quantise A and dZ with stand-alone quantiser launches instead of in the GEMM epilogues")
+    ap.add_argument("--gather", action="store_true",
+                    help="bf16 workloads: no permuted copy of the tokens (with --eq2: nor of dY); the GEMMs that would read it "
+                         "fetch the rows of X / dY through the row map")
     ap.add_argument("--eq2", action="store_true",
                     help="memory-efficient permutation: routing weights applied in the fc1 epilogue, plain-sum combine")
     return ap.parse_args()
@@ -95,6 +98,18 @@ def describe_call(name, args, st):
     if name == "moe_scatter_row_dprob":
         return "scatter_row_dprob", None, T * k * (8 + 4 * args[2])
     q_out = 0   # quantised copies a quantising epilogue writes besides its bf16 output (bytes per output element)
+    gath = ""
+    if name.startswith("moe_grouped_gemm_") and name.endswith("_gather"):
+        # one operand fetched through the row map: the same algorithmic work as the plain call (a row per permuted row,
+        # plus the map); arguments brought into the plain call's order
+        gath = "_gather"
+        if "fwd" in name:      # (ctx, X, T, src_of, k, B, offsets, E, N, K, Rcap, epi, ...)
+            args = [args[0], args[1], args[5], args[6], args[7], args[8], args[9], args[10], 0, args[11]]
+        elif "dgrad" in name:  # (ctx, G, T, src_of, k, B, offsets, E, N, K, Rcap, Z_saved, ...)
+            args = [args[0], args[1], args[5], args[6], args[7], args[8], args[9], args[10], 0, args[11]]
+        else:                  # (ctx, A, dC, which, T, src_of, k, offsets, E, N, K, Rcap, accumulate, out_dt, dB)
+            args = [args[0], args[1], args[2], args[7], args[8], args[9], args[10], args[11], 0, None, None, args[12], args[13]]
+        name = name[:-len("_gather")]
     if name.endswith("_quant_mx"):   # (ctx, P, W, offsets, E, N, K, Rcap, [Z_saved,] scales ...): MXFP8 implied
         fwd = "fwd" in name
         q_out = 1 + (args[-2] is not None)
@@ -115,7 +130,7 @@ def describe_call(name, args, st):
         else:
             extra = ""
         which = ("fc1" if (kind == "fwd" and K == cfg.h) or (kind != "fwd" and K == cfg.h) else "fc2")
-        label = f"{'shared_' if E == 1 else ''}{which}_{kind}{extra}_{tag}"
+        label = f"{'shared_' if E == 1 else ''}{which}_{kind}{extra}_{tag}{gath}"
         es = 1 if dt in (1, 3) else 2
         if kind == "fwd":      # read A and the weights once, write C (SwiGLU: pre-activations + activation)
             by = rows * K * es + E * N * K * es + rows * N * 2 + (rows * (N // 2) * (2 + q_out) if extra else 0)
@@ -123,6 +138,8 @@ def describe_call(name, args, st):
             by = rows * N * es + E * N * K * es + (rows * 2 * K * (2 * 2 + q_out) if extra else rows * K * 2)
         else:                  # read A and dC once, write the weight gradients
             by = rows * (N + K) * es + E * N * K * (4 if args[12] == 2 else 2)
+        if gath:
+            by += rows * 4
         return label, 2.0 * rows * N * K, by
     if name == "moe_route_topk_grouped":
         Tn, E = args[3], args[4]
@@ -132,6 +149,8 @@ def describe_call(name, args, st):
         return "route_topk", None, Tn * E * 4 + Tn * args[4] * 8 + E * 4
     if name == "moe_permute":
         h = args[6]
+        if args[1] is None:   # the maps alone: read the expert ids, write row_of and src_of
+            return "permute_maps", None, T * k * 8 + R * 4
         return "permute", None, (T + R) * h * 2 + T * k * 12
     if name == "moe_unpermute_combine":
         h = args[8]
@@ -178,7 +197,8 @@ HOOKED = ["moe_fp8_quantize_rowcol", "moe_fp8_quantize_rowcol_gather", "moe_mx_q
           "moe_grouped_gemm_fwd_weighted", "moe_grouped_gemm_dgrad_weighted",
           "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant", "moe_grouped_gemm_fwd_quant_mx",
           "moe_grouped_gemm_dgrad_quant_mx", "moe_gather_row_prob",
-          "moe_scatter_row_dprob"]
+          "moe_scatter_row_dprob", "moe_grouped_gemm_fwd_gather", "moe_grouped_gemm_dgrad_gather",
+          "moe_grouped_gemm_wgrad_gather"]
 
 
 def timed_step_with_events(st, torch, sync=True):
@@ -292,7 +312,7 @@ def main():
     hin = L.host_inputs(cfg) if small else None
     st = L.LayerState(cfg, hin, variant=args.variant, wgrad_f32=args.wgrad_f32, eq2=args.eq2,
                       fp8_wgrad=False if args.bf16_wgrad else None,
-                      epilogue_quant=False if args.no_epilogue_quant else None)
+                      epilogue_quant=False if args.no_epilogue_quant else None, gather=args.gather)
 
     # one plain device copy of known size, outside the timed region: the reference dispatch the HBM byte
     # counters (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled by
@@ -362,7 +382,8 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} h={cfg.h} f={cfg.f} E_local={cfg.E} top{cfg.k} "
                                f"shared_f={cfg.shared_f} load={args.variant or cfg.load} "
                                f"wgrad_out={'f32' if args.wgrad_f32 else 'bf16'}"
-                               f"{' weights-in-fc1 (eq. 2)' if args.eq2 else ''}",
+                               f"{' weights-in-fc1 (eq. 2)' if args.eq2 else ''}"
+                               f"{' gathered-operands' if args.gather else ''}",
                    "model_tflop_per_step": round(flops / 1e12, 3)},
         "pct_bf16_mfma_peak": round(100.0 * flops / ms / 1e9 / BF16_PEAK_TFLOPS, 2),
         "gemm_only": {"tflops": round(gemm_fl / gemm_ms / 1e9, 1),
@@ -392,6 +413,25 @@ def main():
         gms = g0.elapsed_time(g1) / args.steps
         assert st.ctx.poll_error() == 0
         out["graph"] = {"ms_per_step": round(gms, 4), "tflops": round(flops / gms / 1e9, 2)}
+    if not (cfg.fp8 or cfg.mx) and not args.gather and not args.variant:
+        # the same step with the permute's row move fused into the GEMMs that read the permuted tokens (no bf16 Xp; with
+        # --eq2 no dO either): bit-identical results (tests/test_gpu_layer.py), reported beside the figure above, which
+        # keeps the stand-alone permute kernel in the timed step
+        sg = L.LayerState(cfg, hin, wgrad_f32=args.wgrad_f32, eq2=args.eq2, gather=True)
+        for _ in range(max(args.warmup, 1)):
+            sg.step()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(args.steps):
+            sg.step()
+        g1.record()
+        torch.cuda.synchronize()
+        gms = g0.elapsed_time(g1) / args.steps
+        assert sg.ctx.poll_error() == 0
+        out["gathered_operands"] = {"ms_per_step": round(gms, 4), "tflops": round(flops / gms / 1e9, 2)}
+        sg.ctx.close()
+        del sg
     # context only: the vendor dense bf16 GEMM through torch on this very box, at the size of one fc1 call of this
     # workload (rows = routed tokens, capped), same operand distribution, output preallocated
     m_ref = min(cfg.T * cfg.k, 131072)

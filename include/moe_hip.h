@@ -322,6 +322,37 @@ moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream, const voi
                                            const float* row_prob, void* dA, float* dprob_part);
 
 /*
+ * The permute's row move fused into the GEMMs that read the permuted tensor (Permutation Fusion, Sec. 4.3.3,
+ * taken one step further: the move disappears).  bf16 only.  An operand indexed by permuted rows is never
+ * stored: its row r is row src_of[r] / k of an unpermuted tensor of T rows, and all zeros where src_of[r] < 0
+ * (padding rows, rows >= offsets[E]); src_of is moe_permute's map, which can be had without the move
+ * (moe_permute with X = NULL).  Results are bit for bit those of the plain calls on the permuted copy.
+ *
+ * fwd_gather:   moe_grouped_gemm_fwd_weighted(dt = MOE_BF16) with A[r,:] = X[src_of[r]/k,:], X [T,K].
+ * dgrad_gather: moe_grouped_gemm_dgrad_weighted(dt = MOE_BF16) with dC[r,:] = G[src_of[r]/k,:], G [T,N]
+ *               (under eq. (2) the combine's backward is a plain copy of dY rows, so G = dY).
+ * wgrad_gather: moe_grouped_gemm_wgrad(dt = MOE_BF16) with one operand gathered: which = MOE_GATHER_A:
+ *               `A` points to X [T,K] and A[r,:] = X[src_of[r]/k,:]; which = MOE_GATHER_DC: `dC` points to
+ *               G [T,N] and dC[r,:] = G[src_of[r]/k,:].  The other operand is read as it lies, [Rcap, .].
+ * Limits (MOE_ERR_UNSUPPORTED otherwise): T * row bytes <= 0xE0000000, Rcap < 2^29, T*k*k < 2^30 (32-bit
+ * offsets inside the gathered tensor; the division by k is a multiplication).  Every src_of[r] >= 0 must be
+ * below T*k (moe_permute's are); larger entries read zeros.
+ */
+typedef enum { MOE_GATHER_A = 0, MOE_GATHER_DC = 1 } moe_gather;
+moe_status moe_grouped_gemm_fwd_gather(moe_ctx* ctx, void* stream, const void* X, int T, const int32_t* src_of,
+                                       int k, const void* B, const int32_t* offsets, int E, int N, int K,
+                                       int64_t Rcap, moe_epilogue epi, const float* row_prob, void* C,
+                                       void* C_act);
+moe_status moe_grouped_gemm_dgrad_gather(moe_ctx* ctx, void* stream, const void* G, int T, const int32_t* src_of,
+                                         int k, const void* B, const int32_t* offsets, int E, int N, int K,
+                                         int64_t Rcap, const void* Z_saved, const float* row_prob, void* dA,
+                                         float* dprob_part);
+moe_status moe_grouped_gemm_wgrad_gather(moe_ctx* ctx, void* stream, const void* A, const void* dC,
+                                         moe_gather which, int T, const int32_t* src_of, int k,
+                                         const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                         int accumulate, moe_dtype out_dt, void* dB);
+
+/*
  * Quantisation of a GEMM's output fused into its epilogue (Sec. 5.4.2; the activation + quantisation
  * epilogue of Sec. 4.3.2), blockwise recipe (dt = MOE_FP8_E4M3) only.  The calls are the _weighted ones
  * with two more outputs, which receive the 1x128 codes and scales of the bf16 tensor the epilogue

@@ -21,6 +21,7 @@ SOFTMAX, SIGMOID = 0, 1
 EPI_NONE, EPI_SWIGLU = 0, 1
 Q_1x128, Q_128x1, Q_128x128 = 0, 1, 2
 MX_1x32, MX_32x1 = 0, 1
+GATHER_A, GATHER_DC = 0, 1
 
 EXPORTS = [
     "moe_workspace_bytes", "moe_ctx_create", "moe_ctx_destroy", "moe_last_error", "moe_ctx_poll_error",
@@ -32,6 +33,7 @@ EXPORTS = [
     "moe_grouped_gemm_fwd_quant", "moe_grouped_gemm_dgrad_quant",
     "moe_grouped_gemm_fwd_quant_mx", "moe_grouped_gemm_dgrad_quant_mx", "moe_gate_gemm", "moe_permute_static",
     "moe_fp8_quantize_rowcol", "moe_fp8_quantize_rowcol_gather",
+    "moe_grouped_gemm_fwd_gather", "moe_grouped_gemm_dgrad_gather", "moe_grouped_gemm_wgrad_gather",
 ]
 
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
@@ -79,6 +81,9 @@ def lib() -> C.CDLL:
         L.moe_fp8_quantize_rowcol.argtypes = [_vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_fp8_quantize_rowcol_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]
         L.moe_gate_gemm.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
+        L.moe_grouped_gemm_fwd_gather.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _vp]
+        L.moe_grouped_gemm_dgrad_gather.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp, _vp]
+        L.moe_grouped_gemm_wgrad_gather.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _vp, _i, _vp, _i, _i, _i, _i64, _i, _i, _vp]
         L.moe_route_topk_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]
         L.moe_gather_row_prob.argtypes = [_vp, _vp, _vp, _vp, _i64, _vp]
         L.moe_scatter_row_dprob.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _i, _vp]
@@ -247,6 +252,24 @@ def moe_grouped_gemm_wgrad(ctx, A, dC, offsets, E, N, K, Rcap, dt, a_scale, dc_s
     ctx.check(lib().moe_grouped_gemm_wgrad(ctx.h, _stream(), _ptr(A), _ptr(dC), _ptr(offsets), E, N, K, Rcap, dt,
                                            _ptr(a_scale), _ptr(dc_scale), int(accumulate), out_dt, _ptr(dB)),
               "moe_grouped_gemm_wgrad")
+
+
+def moe_grouped_gemm_fwd_gather(ctx, X, T, src_of, k, B, offsets, E, N, K, Rcap, epi, row_prob, Cout, C_act):
+    ctx.check(lib().moe_grouped_gemm_fwd_gather(ctx.h, _stream(), _ptr(X), T, _ptr(src_of), k, _ptr(B), _ptr(offsets),
+                                                E, N, K, Rcap, epi, _ptr(row_prob), _ptr(Cout), _ptr(C_act)),
+              "moe_grouped_gemm_fwd_gather")
+
+
+def moe_grouped_gemm_dgrad_gather(ctx, G, T, src_of, k, B, offsets, E, N, K, Rcap, Z_saved, row_prob, dA, dprob_part):
+    ctx.check(lib().moe_grouped_gemm_dgrad_gather(ctx.h, _stream(), _ptr(G), T, _ptr(src_of), k, _ptr(B), _ptr(offsets),
+                                                  E, N, K, Rcap, _ptr(Z_saved), _ptr(row_prob), _ptr(dA),
+                                                  _ptr(dprob_part)), "moe_grouped_gemm_dgrad_gather")
+
+
+def moe_grouped_gemm_wgrad_gather(ctx, A, dC, which, T, src_of, k, offsets, E, N, K, Rcap, accumulate, out_dt, dB):
+    ctx.check(lib().moe_grouped_gemm_wgrad_gather(ctx.h, _stream(), _ptr(A), _ptr(dC), which, T, _ptr(src_of), k,
+                                                  _ptr(offsets), E, N, K, Rcap, int(accumulate), out_dt, _ptr(dB)),
+              "moe_grouped_gemm_wgrad_gather")
 
 
 def moe_unpermute_combine(ctx, O, dt, row_of, prob, residual, T, k, h, Y):

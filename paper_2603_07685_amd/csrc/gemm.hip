@@ -209,7 +209,17 @@ struct gg_args {
     float* partials;       // [split_cap][tiles per expert][256 x 256] fp32
     int* split_info;       // [1 + 3 * GG_MAX_SPLIT_EXPERTS]: count, then (expert, pieces, first slice) for the reduce kernel
     float* dprob_part;     // eq. (2), dgrad SWIGLU_BWD: [Rcap, 2 ceil(K/256)] partial <dA, act(Z)> per row, two per column tile
+    // Permutation fused into the operand fetch (Sec. 4.3.3; GATH variants): the gathered operand (P or Q) points to
+    // the unpermuted tensor [g_T, row length], and row r of the operand is its row g_src_of[r] / g_k, or zeros where
+    // g_src_of[r] < 0 (padding, rows behind offsets[E])
+    const int32_t* g_src_of;
+    uint32_t g_magic;      // ceil(2^31 / g_k): ((2 s + 1) * g_magic) >> 32 == s / g_k for every 0 <= s with s * g_k < 2^30
+    int g_k;
+    int g_T;
 };
+// offset of a gathered row that has no source: behind every record count a gathered operand can have (checked on the
+// host), and far enough from 2^32 that a column offset added to it cannot wrap
+#define GG_NO_ROW 0xF0000000u
 
 // MODE: GG_FWD / GG_DGRAD / GG_WGRAD.  EPI: see enum.  OUT_F32: fp32 output (wgrad only).
 // F8: 0 = bf16 operands; 1 = E4M3 codes with fp32 block scales applied in software
@@ -219,11 +229,15 @@ struct gg_args {
 // and MFMAs, operands by global -> LDS DMA; 4 = one wave per SIMD with 512 registers (wave tile 128 x 128 as 8 x 8
 // blocks of the 16x16x32 MFMA), operands staged through registers one stage ahead, fragment reads pipelined inside
 // the wave (bf16 only).
-template <int MODE, int EPI, bool OUT_F32, int F8, int NW>
+// GATH: 0 = both operands as they lie in memory; 1 / 2 = the rows of P / Q are fetched through the row map from the
+// unpermuted tensor (four-wave body only; Q only in the weight gradient, whose two operands are both indexed by
+// permuted rows).
+template <int MODE, int EPI, bool OUT_F32, int F8, int NW, int GATH = 0>
 __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, NW == 4 ? 1 : 2))) void gg_kernel(const gg_args a) {
     constexpr bool FP8 = F8 != 0;  // one-byte operands
     constexpr bool MX = F8 == 2;   // hardware block scales
     static_assert(NW == 8 || (NW == 4 && !FP8), "four-wave workgroups are built for bf16 operands only");
+    static_assert(GATH == 0 || (NW == 4 && (GATH == 1 || (GATH == 2 && MODE == GG_WGRAD))), "gathered operands: four-wave body; Q only in the weight gradient");
     constexpr int THREADS = NW * 64;
     constexpr int HW = NW / 2;     // waves per 128-row half of the tile
     constexpr int NJ = 16 / NW;    // 32-column blocks per wave: NJ / 2 in each 128-column half
@@ -274,6 +288,17 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     constexpr int CM_ROWS = 1024 / (256 * ES);  // c-major rows per 1 KB DMA chunk: 2 bf16 / 4 fp8
     constexpr int CM_SLOTS = 256 * ES / 16;     // 16-byte slots per c-major row: 32 bf16 / 16 fp8
     constexpr int EPS = 16 / ES;                // elements per 16-byte slot
+    // Gathered operand (GATH).  Row-major (forward, data gradient): the rows of a tile are fixed, eight lane offsets
+    // hold their places in the unpermuted tensor for the whole tile.  Contraction-major (weight gradient): every
+    // stage brings 64 new rows, 16 per wave; a wave fetches the 16 map entries of a stage three stages ahead (one
+    // 4-byte load per lane), turns them into byte offsets, and passes them through a few LDS words of its own to the
+    // lanes that need them: chunk c of a lane (rows 2 c + lane / 32) finds the offsets of its eight chunks in two
+    // 16-byte reads, a stage before the loads that use them (gfetch / gconv / gput / gread below).  Rows without a
+    // source, rows behind the contraction range and stages behind the last get GG_NO_ROW, which the buffer
+    // descriptor turns into zeros.
+    constexpr bool G_ROW = GATH == 1 && !P_CMAJ;
+    constexpr bool G_CM = GATH != 0 && MODE == GG_WGRAD;
+    __shared__ __attribute__((aligned(16))) uint32_t gring[G_CM ? 3 * 4 * 16 : 4];  // [slot][wave][row parity][chunk]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -283,6 +308,27 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // tile column of the wave's jb-th 32-column block
     auto blk_col = [&](int jb) { return (jb / (NJ / 2)) * 128 + wn * (16 * NJ) + (jb % (NJ / 2)) * 32; };
     const int E = a.E, N = a.N, K = a.K;
+    // gathered operand: bytes per row of the unpermuted tensor; this lane's row among the 64 of a stage when it
+    // fetches map entries, and where it reads offsets back (contraction-major chunks hold rows 2 i + lane / 32)
+    const uint32_t g_rowb = (uint32_t)(((GATH == 2 || MODE == GG_FWD) ? K : N) * ES);
+    const int g_row16 = 16 * wave + (lane & 15);
+    const uint32_t gl_rd = lds_addr(gring) + wave * 64 + (lane >> 5) * 32;
+    const uint32_t gl_wr = lds_addr(gring) + wave * 64 + ((lane & 1) * 8 + ((lane & 15) >> 1)) * 4;
+    // map entry -> source row -> its byte offset, in two steps (each holds one quarter-rate multiplication; inside the
+    // stage loop they sit behind different MFMAs).  No branches: every lane computes, the select comes last (left alone,
+    // the compiler predicates the multiplications and puts a branch between the MFMAs).
+    auto g_tok_of = [&](int s) -> uint32_t {
+        uint32_t tok = __umulhi(2u * (uint32_t)s + 1u, a.g_magic);   // s / g_k
+        asm volatile("" : "+v"(tok));
+        return tok;
+    };
+    auto g_off_at = [&](int s, uint32_t tok, bool live) -> uint32_t {
+        uint32_t off = tok * g_rowb;
+        asm volatile("" : "+v"(off));
+        const bool ok = (s >= 0) & live;
+        return ok ? off : GG_NO_ROW;
+    };
+    auto g_off_of = [&](int s, bool live) -> uint32_t { return g_off_at(s, g_tok_of(s), live); };
 
     // Output geometry.  J = extent of j (output columns).
     //   fwd:   J = N (with SWIGLU the column tiles pair gate/up: N/2 features in tiles of 128)
@@ -460,6 +506,8 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     // parity of the chunk), so two lane offsets and a wave-uniform stride per operand replace 2 x 8 registers; rows are
     // not clamped here, the record count of the buffer descriptor covers the end of the tensor
     uint32_t po2[2] = {0, 0}, qo2[4] = {0, 0, 0, 0};   // (qo2[2..3]: data gradient only, chunks 4..7 of a wave, see SWZ3)
+    uint32_t po8[G_ROW ? 8 : 1] = {};   // gathered row-major P: one offset per chunk
+    uint32_t gv[G_CM ? 8 : 1] = {};     // gathered contraction-major operand: the row offsets of the chunks about to be loaded
     uint32_t p_cstride = 0, q_cstride = 0;
     int64_t p_step = 0, q_step = 0;  // byte advance per stage
     const float* sc_src = nullptr;   // fp8: this lane's scale for block 0
@@ -470,6 +518,31 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     int KT_pf = 0;
     int e_hint = 0;
     int part_slot = -1, part_tile = 0;  // split contraction: slice and tile of the partial result (-1: the result itself)
+    // contraction-major gather: the map entry of this lane's row of stage kt (rows behind the map read 0 and are
+    // masked by the range test in gconv), its byte offset, the ring slot it is parked in, and the read-back of the
+    // row of chunk c
+    auto gfetch = [&](int kt) __attribute__((always_inline)) -> int {
+        const __amdgpu_buffer_rsrc_t rs =
+            __builtin_amdgcn_make_buffer_rsrc((void*)a.g_src_of, 0, (int)((uint32_t)a.Rcap * 4u), 0x00020000);
+        // (the stage's first row through readfirstlane: otherwise the loop counter is strength-reduced into this
+        // lane-dependent row number and the stage loop becomes a divergent loop on an exec mask)
+        return (int)__builtin_amdgcn_raw_buffer_load_b32(rs, (__builtin_amdgcn_readfirstlane(c_lo + kt * BKE) + g_row16) * 4, 0, 0);
+    };
+    auto gconv = [&](int kt, int s) __attribute__((always_inline)) -> uint32_t {
+        return g_off_of(s, (__builtin_amdgcn_readfirstlane(c_lo + kt * BKE) + g_row16) < c_hi);
+    };
+    typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
+    auto gput = [&](int slot, uint32_t v) __attribute__((always_inline)) {
+        *(lds_u32_t*)(uintptr_t)(gl_wr + slot * 256) = v;
+    };
+    typedef __attribute__((address_space(3))) u32x4_t lds_u32x4_t;
+    auto gread = [&](int slot, int half) __attribute__((always_inline)) {  // the offsets of chunks 4 half .. 4 half + 3
+        const u32x4_t v = *(const lds_u32x4_t*)(uintptr_t)(gl_rd + slot * 256 + half * 16);
+        gv[4 * half] = v[0];
+        gv[4 * half + 1] = v[1];
+        gv[4 * half + 2] = v[2];
+        gv[4 * half + 3] = v[3];
+    };
     auto setup_tile = [&](int t) __attribute__((always_inline)) {
         // (four waves: the lane constants of the set-up are formed here from a lane id the compiler cannot see through;
         // computed once at kernel start they would occupy registers through every stage loop, or spill)
@@ -489,13 +562,13 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             const int sp = __builtin_amdgcn_readfirstlane(split_of[es]);
             pieces = sp & 255;
             u = t - __builtin_amdgcn_readfirstlane(item_start[es]);
-            piece = u / tpe;
+            piece = __builtin_amdgcn_readfirstlane(u / tpe);
             u -= piece * tpe;
             part_slot = pieces > 1 ? (sp >> 8) + piece : -1;
             part_tile = u;
         } else if (MODE == GG_WGRAD) {
             const int tpe = tiles_i_w * tiles_j;
-            const int es = t / tpe;
+            const int es = __builtin_amdgcn_readfirstlane(t / tpe);
             e = __builtin_amdgcn_readfirstlane(tile_start[es]);
             u = t - es * tpe;
         } else {
@@ -512,8 +585,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             const int band = u / band_sz;
             const int in_band = u - band * band_sz;
             const int band_rows = min(GG_BAND, tiles_i - band * GG_BAND);
-            ti = band * GG_BAND + in_band % band_rows;
-            tj = in_band / band_rows;
+            // (integer divisions run on the vector unit: without the readfirstlanes their uniform results, and the
+            // operand bases, record counts and trip count derived from them, live in vector registers, and the stage
+            // loop rebuilds every buffer descriptor with 64-bit vector arithmetic between its MFMAs)
+            ti = __builtin_amdgcn_readfirstlane(band * GG_BAND + in_band % band_rows);
+            tj = __builtin_amdgcn_readfirstlane(in_band / band_rows);
         }
         // output row/column origin of the two 128-column halves
         i0 = (MODE == GG_WGRAD) ? ti * GG_BM : row_lo + ti * GG_BM;
@@ -524,11 +600,13 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         c_lo = (MODE == GG_WGRAD) ? row_lo : 0;
         c_hi = (MODE == GG_WGRAD) ? row_hi : (MODE == GG_FWD ? K : N);
         if (SPLITK && pieces > 1) {  // this piece's share of the expert's rows, in whole stages
-            const int len = ((row_hi - row_lo + pieces - 1) / pieces + BKE - 1) / BKE * BKE;
+            const int len = __builtin_amdgcn_readfirstlane(((row_hi - row_lo + pieces - 1) / pieces + BKE - 1) / BKE * BKE);
             c_lo = min(row_lo + piece * len, row_hi);
             c_hi = min(c_lo + len, row_hi);
         }
-        KT = (c_hi - c_lo + BKE - 1) / BKE;
+        c_lo = __builtin_amdgcn_readfirstlane(c_lo);
+        c_hi = __builtin_amdgcn_readfirstlane(c_hi);
+        KT = __builtin_amdgcn_readfirstlane((c_hi - c_lo + BKE - 1) / BKE);
 
         // ---- DMA sources: a wave-uniform 64-bit base per operand (advances with the stage) plus
         //      CH 32-bit per-lane offsets; offsets stay below 2^32 because they are tile-relative ----
@@ -545,6 +623,27 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 col = col <= N - EPS ? col : N - EPS;
                 if (NW == 4) po2[i] = (uint32_t)((row * N + col) * ES);
                 else po[i] = (uint32_t)((row * N + col) * ES);
+                if (GATH == 1) po2[i] = (uint32_t)(col * ES);  // the row comes from the map
+            }
+            if (GATH == 1) {
+                p_step = 0;
+                p_base = (const char*)a.P;
+            }
+        } else if (G_ROW) {
+            const int ldp = (MODE == GG_FWD) ? K : N;
+            (void)ldp;
+            p_step = GG_ROWB;
+            p_base = (const char*)a.P;
+            int sidx[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t r = (int64_t)i0 + (wave * CH + i) * 8 + km_row;
+                sidx[i] = r < a.Rcap ? a.g_src_of[r] : -1;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int p = (wave * CH + i) * 8 + km_row;  // tile row 0..255
+                po8[i] = g_off_of(sidx[i], true) + (uint32_t)(((lane & 7) ^ KM_SWZ(p)) * 16);
             }
         } else {
             const int ldp = (MODE == GG_FWD) ? K : N;
@@ -576,6 +675,11 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 col = col <= K - EPS ? col : K - EPS;
                 if (NW == 4) qo2[i] = (uint32_t)((row * K + col) * ES);
                 else qo[i] = (uint32_t)((row * K + col) * ES);
+                if (GATH == 2) qo2[i] = (uint32_t)(col * ES);  // the row comes from the map
+            }
+            if (GATH == 2) {
+                q_step = 0;
+                q_base = (const char*)a.Q;
             }
         } else {
             q_step = GG_ROWB;
@@ -681,6 +785,12 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                 }
             }
         }
+        if (G_CM) {  // the row offsets of the first three stages, one slot each (inside the stage loop: slot 0 only)
+            const int s0 = gfetch(0), s1 = gfetch(1), s2 = gfetch(2);
+            gput(0, gconv(0, s0));
+            gput(1, gconv(1, s1));
+            gput(2, gconv(2, s2));
+        }
     };
 
         // one of the 2 CH DMA instructions of stage kt (idx: operand = idx & 1, chunk = idx >> 1)
@@ -725,12 +835,20 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     auto load_one = [&](int kt, int idx) __attribute__((always_inline)) {
         const int i = idx >> 1;
         const bool isq = idx & 1;
-        const uint32_t off = (isq && SWZ3) ? qo2[(i & 1) + 2 * (i >> 2)] + (uint32_t)((i >> 1) & 1) * q_cstride
-                                           : (isq ? qo2[i & 1] : po2[i & 1]) + (uint32_t)(i >> 1) * (isq ? q_cstride : p_cstride);
+        const bool g_cm = G_CM && (isq ? GATH == 2 : GATH == 1);  // this operand's rows come through the ring
+        const bool g_row = G_ROW && !isq;                          // ... or from the tile's eight row offsets
+        const uint32_t off = g_cm    ? gv[i] + (isq ? qo2[i & 1] : po2[i & 1])
+                             : g_row ? po8[i]
+                             : (isq && SWZ3) ? qo2[(i & 1) + 2 * (i >> 2)] + (uint32_t)((i >> 1) & 1) * q_cstride
+                                             : (isq ? qo2[i & 1] : po2[i & 1]) + (uint32_t)(i >> 1) * (isq ? q_cstride : p_cstride);
         const char* base = isq ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
         const bool cmaj = isq ? Q_CMAJ : P_CMAJ;
         int64_t bytes;  // from the base to the end of what may be read
-        if (cmaj) {
+        if (g_cm) {
+            bytes = (int64_t)a.g_T * g_rowb;
+        } else if (g_row) {
+            bytes = kt >= KT ? 0 : (int64_t)a.g_T * g_rowb - kt * GG_ROWB;
+        } else if (cmaj) {
             const int ld = (isq || MODE == GG_DGRAD) ? K : N;  // row length of the contraction-major operand
             bytes = (int64_t)max(c_hi - c_lo - kt * BKE, 0) * ld * ES;
         } else if (kt >= KT) {
@@ -779,6 +897,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     auto issue_stage0 = [&]() __attribute__((always_inline)) {
         if (NW == 4) {  // into the registers
             if (KT > 0) {
+                if (G_CM) {
+                    gread(0, 0);
+                    gread(0, 1);
+                }
 #pragma unroll
                 for (int x = 0; x < 2 * CH; ++x) load_one(0, x);
             }
@@ -824,6 +946,7 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     };
     int t_first = tile_of(0);
     if (dyn) t_first = publish(draw());
+    t_first = __builtin_amdgcn_readfirstlane(t_first);
     if (t_first < total_tiles) {
         setup_tile(t_first);
         issue_stage0();
@@ -1102,6 +1225,8 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                         if (Q_CMAJ) qr[set][jq] = lds_read_tr16x8(sq + ks * 16384, sq + ks * 16384 + 2048);
                         else qr[set][jq] = *(const lds_bf16x8_t*)(uintptr_t)(vbq[sb][ks] + ((jq / 4) * 128 + (jq % 4) * 16) * GG_ROWB);
                     };
+                    int g_ent = 0;
+                    uint32_t g_tok = 0, g_cnv = 0;
                     auto stage4 = [&](int j, int s) __attribute__((always_inline)) {
                         // (nothing here is conditional: behind the last stage the moves and reads go on, unused)
                         static_assert(NW != 4 || CH == 8, "the gap assignment below is for 16 chunks per stage");
@@ -1114,6 +1239,24 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                             const int b = 8 * ks + i, M = 8 * b + jq, off = jq;
                             asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc4[i][jq]) : "v"(qr[ks][jq]), "v"(pr[b & 3]));
                             __builtin_amdgcn_sched_barrier(0);
+                            if (G_CM) {
+                                // gathered operand: the map entries of stage j + 3 are requested early in the stage,
+                                // become offsets late in it and are stored to the wave's LDS words ahead of the
+                                // stage's barrier; the lanes that will load with them in stage j + 1 read them back
+                                // behind the barrier and behind the last load of this stage (read ahead of the
+                                // barrier they would make its wait for outstanding LDS reads a real one)
+                                if (M == 2) g_ent = gfetch(j + 3);
+                                if (M == 100) {
+                                    // (opaque up to here: the compiler otherwise starts on the entry, and waits for its
+                                    // load together with half of the stage's operand loads, forty MFMAs earlier)
+                                    asm volatile("" : "+v"(g_ent));
+                                    g_tok = g_tok_of(g_ent);
+                                }
+                                if (M == 104) g_cnv = g_off_at(g_ent, g_tok, (__builtin_amdgcn_readfirstlane(c_lo + (j + 3) * BKE) + g_row16) < c_hi);
+                                if (M == 106) gput(0, g_cnv);
+                                if (M == 126) gread(0, 0);
+                                if (M == 127) gread(0, 1);
+                            }
                             int mv = -1;  // move slot: 2 x chunk = store, 2 x chunk + 1 = load
                             if (b < 8) {
                                 if (off == 5) mv = 2 * b;
@@ -1143,8 +1286,16 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                     // stage 1 into the freed registers, the first fragments
 #pragma unroll
                     for (int x = 0; x < 2 * CH; ++x) store_one(SP[0], SQ[0], x);
+                    if (G_CM) {
+                        gread(1, 0);
+                        gread(1, 1);
+                    }
 #pragma unroll
                     for (int x = 0; x < 2 * CH; ++x) load_one(1, x);
+                    if (G_CM) {  // the offsets the loads of the first stage of the loop (those of stage 2) will use
+                        gread(2, 0);
+                        gread(2, 1);
+                    }
                     wait_lgkm0();
                     stage_barrier();
 #pragma unroll
@@ -1263,7 +1414,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         // fragment reads of both groups)
         const int ep_e = e, ep_i0 = i0, ep_i_end = i_end, ep_j0 = j0, ep_j1 = j1;
         const int ep_part = part_slot, ep_ptile = part_tile;
-        const int t_next = dyn ? publish(drawn) : tile_of(n_tile + 1);
+        // (readfirstlane: the choice between a drawn and a dealt tile otherwise counts as lane-dependent, and with it the
+        // whole geometry of the next tile: its operand bases and trip count then live in vector registers and the stage
+        // loop of the weight gradient rebuilds its buffer descriptors with 64-bit vector arithmetic between MFMAs)
+        const int t_next = __builtin_amdgcn_readfirstlane(dyn ? publish(drawn) : tile_of(n_tile + 1));
         // (four-wave SwiGLU backward: the registers that would hold the next tile's first stage carry the saved
         // pre-activations instead, many units ahead; the next tile is set up behind the output phase)
         constexpr bool LATE_SETUP = NW == 4 && EPI != GG_EPI_STORE;
@@ -1978,6 +2132,58 @@ __global__ __launch_bounds__(256) void gg_split_reduce_kernel(const float* __res
                        dim3(ctx->num_cu > 0 ? ctx->num_cu : 256), dim3(GG_NW_OF(MODE, FP8) * 64),               \
                        0, (hipStream_t)stream, a)
 
+// the four-wave bf16 kernel with operand P (GATH = 1) or Q (2) fetched through the row map
+#define GG_LAUNCH_G(MODE, EPI, F32, GATH)                                                                       \
+    hipLaunchKernelGGL((gg_kernel<MODE, EPI, F32, 0, 4, GATH>), dim3(ctx->num_cu > 0 ? ctx->num_cu : 256),      \
+                       dim3(256), 0, (hipStream_t)stream, a)
+
+// Arguments of a gathered operand: `ld` = its row length.  Limits: every byte offset into the unpermuted tensor, and
+// GG_NO_ROW plus a column offset, must fit 32 bits; the map is read through a 32-bit record count; the division by k
+// is a multiplication: with m = ceil(2^31 / k), (2 s + 1) m / 2^32 = (s + 1/2) / k + (2 s + 1) e / 2^32, 0 <= e < 1,
+// whose first term lies at least 1 / (2 k) below the next integer, so the floor is s / k while (2 s + 1) 2 k < 2^32.
+static moe_status gg_gather_args(moe_ctx* ctx, const char* who, gg_args& a, int T, const int32_t* src_of, int k, int ld,
+                                 int64_t Rcap) {
+    if (!src_of) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: src_of is NULL", who);
+    if (T < 1 || k < 1) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: need T >= 1 and k >= 1", who);
+    if ((int64_t)T * ld * 2 > 0xE0000000LL || Rcap >= (1LL << 29) || (int64_t)T * k * k >= (1LL << 30))
+        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "%s: T=%d rows of %d elements (or T*k*k, or Rcap) exceed the 32-bit offsets of the gathered fetch", who, T, ld);
+    a.g_src_of = src_of;
+    a.g_k = k;
+    a.g_T = T;
+    a.g_magic = (uint32_t)(((1ULL << 31) + (uint64_t)k - 1) / (uint64_t)k);
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_grouped_gemm_fwd_gather(moe_ctx* ctx, void* stream, const void* X, int T, const int32_t* src_of,
+                                                  int k, const void* B, const int32_t* offsets, int E, int N, int K,
+                                                  int64_t Rcap, moe_epilogue epi, const float* row_prob, void* C,
+                                                  void* C_act) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (GG_BF16_NW != 4) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd_gather: needs the four-wave bf16 body");
+    if (row_prob && epi != MOE_EPI_SWIGLU)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_gather: row weights go with the SwiGLU epilogue");
+    moe_status st = gg_check_common(ctx, "moe_grouped_gemm_fwd_gather", X, B, offsets, E, N, K, Rcap, MOE_BF16);
+    if (st != MOE_OK) return st;
+    if (epi == MOE_EPI_SWIGLU) {
+        if (!C_act) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_gather: SWIGLU needs C_act");
+        if (N % 16) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_gather: SWIGLU needs N %% 16 == 0");
+    } else if (epi == MOE_EPI_NONE) {
+        if (!C) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_gather: C is NULL");
+    } else {
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_fwd_gather: bad epilogue");
+    }
+    if (K % 64) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_fwd_gather: K=%d must be a multiple of 64", K);
+    gg_args a = gg_make(ctx, X, B, offsets, E, N, K, Rcap, C);
+    st = gg_gather_args(ctx, "moe_grouped_gemm_fwd_gather", a, T, src_of, k, K, Rcap);
+    if (st != MOE_OK) return st;
+    a.out_act = (bf16_t*)C_act;
+    a.row_prob = row_prob;
+    if (epi == MOE_EPI_SWIGLU) GG_LAUNCH_G(GG_FWD, GG_EPI_SWIGLU, false, 1);
+    else GG_LAUNCH_G(GG_FWD, GG_EPI_STORE, false, 1);
+    MOE_LAUNCH_CHECK(ctx, "gg_kernel<fwd, gather>");
+    return MOE_OK;
+}
+
 extern "C" moe_status moe_grouped_gemm_fwd(moe_ctx* ctx, void* stream, const void* A, const void* B,
                                            const int32_t* offsets, int E, int N, int K, int64_t Rcap,
                                            moe_dtype dt, moe_epilogue epi,
@@ -2100,6 +2306,30 @@ static moe_status gg_fwd_all(moe_ctx* ctx, void* stream, const void* A, const vo
     return MOE_OK;
 }
 
+extern "C" moe_status moe_grouped_gemm_dgrad_gather(moe_ctx* ctx, void* stream, const void* G, int T, const int32_t* src_of,
+                                                    int k, const void* B, const int32_t* offsets, int E, int N, int K,
+                                                    int64_t Rcap, const void* Z_saved, const float* row_prob, void* dA,
+                                                    float* dprob_part) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (GG_BF16_NW != 4) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad_gather: needs the four-wave bf16 body");
+    if ((row_prob || dprob_part) && !Z_saved)
+        MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_gather: row weights / dprob_part need Z_saved");
+    moe_status st = gg_check_common(ctx, "moe_grouped_gemm_dgrad_gather", G, B, offsets, E, N, K, Rcap, MOE_BF16);
+    if (st != MOE_OK) return st;
+    if (!dA) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_dgrad_gather: dA is NULL");
+    if (N % 64) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_dgrad_gather: N=%d must be a multiple of 64", N);
+    gg_args a = gg_make(ctx, G, B, offsets, E, N, K, Rcap, dA);
+    st = gg_gather_args(ctx, "moe_grouped_gemm_dgrad_gather", a, T, src_of, k, N, Rcap);
+    if (st != MOE_OK) return st;
+    a.Zsaved = (const bf16_t*)Z_saved;
+    a.row_prob = row_prob;
+    a.dprob_part = dprob_part;
+    if (Z_saved) GG_LAUNCH_G(GG_DGRAD, GG_EPI_SWIGLU_BWD, false, 1);
+    else GG_LAUNCH_G(GG_DGRAD, GG_EPI_STORE, false, 1);
+    MOE_LAUNCH_CHECK(ctx, "gg_kernel<dgrad, gather>");
+    return MOE_OK;
+}
+
 extern "C" moe_status moe_grouped_gemm_dgrad(moe_ctx* ctx, void* stream, const void* dC, const void* B,
                                              const int32_t* offsets, int E, int N, int K, int64_t Rcap,
                                              moe_dtype dt, const void* Z_saved,
@@ -2198,10 +2428,32 @@ static moe_status gg_dgrad_all(moe_ctx* ctx, void* stream, const void* dC, const
     return MOE_OK;
 }
 
+static moe_status gg_wgrad_all(moe_ctx* ctx, void* stream, const void* A, const void* dC, const int32_t* offsets, int E,
+                               int N, int K, int64_t Rcap, moe_dtype dt, const float* a_scale, const float* dc_scale,
+                               int accumulate, moe_dtype out_dt, void* dB, int gath, int T, const int32_t* src_of, int k);
+
 extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const void* A, const void* dC,
                                              const int32_t* offsets, int E, int N, int K, int64_t Rcap,
                                              moe_dtype dt, const float* a_scale, const float* dc_scale,
                                              int accumulate, moe_dtype out_dt, void* dB) {
+    return gg_wgrad_all(ctx, stream, A, dC, offsets, E, N, K, Rcap, dt, a_scale, dc_scale, accumulate, out_dt, dB, 0, 0,
+                        nullptr, 0);
+}
+
+extern "C" moe_status moe_grouped_gemm_wgrad_gather(moe_ctx* ctx, void* stream, const void* A, const void* dC,
+                                                    moe_gather which, int T, const int32_t* src_of, int k,
+                                                    const int32_t* offsets, int E, int N, int K, int64_t Rcap,
+                                                    int accumulate, moe_dtype out_dt, void* dB) {
+    if (!ctx) return MOE_ERR_ARG;
+    if (which != MOE_GATHER_A && which != MOE_GATHER_DC) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad_gather: bad `which`");
+    if (GG_BF16_NW != 4) MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wgrad_gather: needs the four-wave bf16 body");
+    return gg_wgrad_all(ctx, stream, A, dC, offsets, E, N, K, Rcap, MOE_BF16, nullptr, nullptr, accumulate, out_dt, dB,
+                        which == MOE_GATHER_A ? 2 : 1, T, src_of, k);
+}
+
+static moe_status gg_wgrad_all(moe_ctx* ctx, void* stream, const void* A, const void* dC, const int32_t* offsets, int E,
+                               int N, int K, int64_t Rcap, moe_dtype dt, const float* a_scale, const float* dc_scale,
+                               int accumulate, moe_dtype out_dt, void* dB, int gath, int T, const int32_t* src_of, int k) {
     if (!ctx) return MOE_ERR_ARG;
     if (dt == MOE_F32) {  // all-fp32 path (gemm_f32.hip)
         if (!A || !dC || !offsets || !dB) MOE_FAIL(ctx, MOE_ERR_ARG, "moe_grouped_gemm_wgrad: NULL pointer");
@@ -2227,7 +2479,17 @@ extern "C" moe_status moe_grouped_gemm_wgrad(moe_ctx* ctx, void* stream, const v
     a.split_info = (int*)((char*)ctx->ws + MOE_WS_SPLIT_INFO);
     a.partials = (float*)((char*)ctx->ws + MOE_WS_RESERVED);
     a.split_cap = (!mx && !bw && GG_BF16_NW == 4) ? (int)(ws_free / slice_bytes < GG_MAX_SPLIT ? ws_free / slice_bytes : GG_MAX_SPLIT) : 0;
-    if (mx) {
+    if (gath) {  // (bf16 operands; P = dC, Q = A)
+        st = gg_gather_args(ctx, "moe_grouped_gemm_wgrad_gather", a, T, src_of, k, gath == 2 ? K : N, Rcap);
+        if (st != MOE_OK) return st;
+    }
+    if (gath == 2) {
+        if (out_dt == MOE_F32) GG_LAUNCH_G(GG_WGRAD, GG_EPI_STORE, true, 2);
+        else GG_LAUNCH_G(GG_WGRAD, GG_EPI_STORE, false, 2);
+    } else if (gath == 1) {
+        if (out_dt == MOE_F32) GG_LAUNCH_G(GG_WGRAD, GG_EPI_STORE, true, 1);
+        else GG_LAUNCH_G(GG_WGRAD, GG_EPI_STORE, false, 1);
+    } else if (mx) {
         if (out_dt == MOE_F32) GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, true, 2);
         else GG_LAUNCH(GG_WGRAD, GG_EPI_STORE, false, 2);
     } else if (bw) {

@@ -43,8 +43,13 @@ class LayerState:
     def __init__(self, cfg: wl.MoEConfig, hin: dict | None = None, shared_f: int | None = None,
                  variant: str | None = None, wgrad_f32: bool = False, eq2: bool = False,
                  fused_quant: bool | None = None, epilogue_quant: bool | None = None, f32: bool = False,
-                 fp8_wgrad: bool | None = None):
+                 fp8_wgrad: bool | None = None, gather: bool = False):
         self.cfg = cfg
+        # bf16 only: the permute's row move fused into the GEMMs that read the permuted tensor (Sec. 4.3.3): fc1 and its
+        # weight gradient fetch the rows of X through the row map, and under eq. (2), where the combine's backward is a
+        # plain copy, fc2's two gradients fetch the rows of dY the same way; Xp (and then dO) are never stored
+        self.gather = bool(gather)
+        assert not self.gather or not (cfg.fp8 or cfg.mx or f32), "the gathered GEMMs are bf16 kernels"
         self.eq2 = bool(eq2)  # memory-efficient permutation (Sec. 4.1.2): weights applied before fc2
         self.fused_quant = None if fused_quant is None else bool(fused_quant)   # (resolved below, once fp8_wgrad is known)
         # blockwise fp8 (default there): the SwiGLU / SwiGLU-backward epilogues also emit the 1x128 codes of their
@@ -114,7 +119,7 @@ class LayerState:
         self.src_of = torch.empty(Rcap, dtype=i32, device=dev)
         self.offsets = torch.empty(E + 1, dtype=i32, device=dev)
         self.counts = torch.empty(E, dtype=i32, device=dev)
-        self.Xp = None if self.fused_quant else torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.Xp = None if (self.fused_quant or self.gather) else torch.empty((Rcap, h), dtype=bf, device=dev)
         self.Z = torch.empty((Rcap, 2 * f), dtype=bf, device=dev)
         self.A = torch.empty((Rcap, f), dtype=bf, device=dev)
         self.O = torch.empty((Rcap, h), dtype=bf, device=dev)
@@ -122,7 +127,7 @@ class LayerState:
         # backward
         wdt = f32 if wgrad_f32 else bf
         self.wgrad_dt = B.F32 if wgrad_f32 else B.BF16
-        self.dO = None if self.fused_quant else torch.empty((Rcap, h), dtype=bf, device=dev)
+        self.dO = None if (self.fused_quant or (self.gather and self.eq2)) else torch.empty((Rcap, h), dtype=bf, device=dev)
         self.dprob = torch.empty((T, k), dtype=f32, device=dev)
         self.dZ = torch.empty((Rcap, 2 * f), dtype=bf, device=dev)
         self.dXp = torch.empty((Rcap, h), dtype=bf, device=dev)
@@ -252,14 +257,18 @@ class LayerState:
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         self._route()
         idx = self.topk_idx if self.forced_idx is None else self.forced_idx
-        B.moe_permute(c, self.X, self.dt, idx, T, k, h, E, self.align, self.Xp, Rcap,
+        B.moe_permute(c, None if self.gather else self.X, self.dt, idx, T, k, h, E, self.align, self.Xp, Rcap,
                       self.row_of, self.src_of, self.offsets, self.counts)
         row_prob = None
         if self.eq2:  # eq. (2): A = p * silu(gate) * up, plain-sum combine
             B.moe_gather_row_prob(c, self.topk_prob, self.src_of, Rcap, self.row_prob)
             row_prob = self.row_prob
-        B.moe_grouped_gemm_fwd_weighted(c, self.Xp, self.W1, self.offsets, E, 2 * f, h, Rcap, self.dt, B.EPI_SWIGLU,
-                                        None, None, row_prob, self.Z, self.A)
+        if self.gather:
+            B.moe_grouped_gemm_fwd_gather(c, self.X, T, self.src_of, k, self.W1, self.offsets, E, 2 * f, h, Rcap,
+                                          B.EPI_SWIGLU, row_prob, self.Z, self.A)
+        else:
+            B.moe_grouped_gemm_fwd_weighted(c, self.Xp, self.W1, self.offsets, E, 2 * f, h, Rcap, self.dt, B.EPI_SWIGLU,
+                                            None, None, row_prob, self.Z, self.A)
         B.moe_grouped_gemm_fwd(c, self.A, self.W2, self.offsets, E, h, f, Rcap, self.dt, B.EPI_NONE,
                                None, None, self.O, None)
         if sf:
@@ -275,7 +284,14 @@ class LayerState:
         c, cfg = self.ctx, self.cfg
         T, k, E, h, f, sf, Rcap = cfg.T, cfg.k, cfg.E, cfg.h, cfg.f, self.sf, self.Rcap
         wdt = self.wgrad_dt
-        if self.eq2:
+        if self.eq2 and self.gather:
+            # dO would be plain copies of dY: both fc2 gradients fetch the rows of dY through the map instead
+            B.moe_grouped_gemm_wgrad_gather(c, self.A, self.dY, B.GATHER_DC, T, self.src_of, k, self.offsets, E, h, f, Rcap,
+                                            0, wdt, self.dW2)
+            B.moe_grouped_gemm_dgrad_gather(c, self.dY, T, self.src_of, k, self.W2, self.offsets, E, h, f, Rcap, self.Z,
+                                            self.row_prob, self.dZ, self.dprob_part)
+            B.moe_scatter_row_dprob(c, self.dprob_part, self.dprob_parts, self.row_of, T, k, self.dprob)
+        elif self.eq2:
             # dO = plain copies of dY (no weight, O is not read); dprob comes out of the fc2 data gradient
             B.moe_unpermute_combine_bwd(c, self.dY, None, self.dt, self.row_of, self.src_of, None,
                                         T, k, h, Rcap, self.dO, None)
@@ -291,8 +307,12 @@ class LayerState:
                                      self.dW2)
             B.moe_grouped_gemm_dgrad(c, self.dO, self.W2, self.offsets, E, h, f, Rcap, self.dt, self.Z, None, None,
                                      self.dZ)
-        B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, self.dt, None, None, 0, wdt,
-                                 self.dW1)
+        if self.gather:
+            B.moe_grouped_gemm_wgrad_gather(c, self.X, self.dZ, B.GATHER_A, T, self.src_of, k, self.offsets, E, 2 * f, h,
+                                            Rcap, 0, wdt, self.dW1)
+        else:
+            B.moe_grouped_gemm_wgrad(c, self.Xp, self.dZ, self.offsets, E, 2 * f, h, Rcap, self.dt, None, None, 0, wdt,
+                                     self.dW1)
         B.moe_grouped_gemm_dgrad(c, self.dZ, self.W1, self.offsets, E, 2 * f, h, Rcap, self.dt, None, None, None,
                                  self.dXp)
         if sf:

@@ -190,13 +190,20 @@ def moves(td: str, fd: str, wd: str, bench_path: str):
     _, rows = _traffic_rows(fd, wd)
     meas = [(n, rd + wr) for n, rd, wr in rows if any(t in n for t in ("combine", "permute_rows"))]
     alg = {k: v for k, v in b["kernels"].items() if k in ("permute", "combine", "combine_bwd", "unpermute_sum_dx")}
-    names = ["permute", "combine", "combine_bwd", "unpermute_sum_dx"]
+
+    def label_of(i):   # call site of the i-th move kernel of a step, by kernel and order (a step without a bf16 permuted
+        name = steps[-1][i][0]   # copy launches no permute_rows kernel, one whose dO is quantised on the fly no full combine backward)
+        if "permute_rows" in name:
+            return "permute"
+        if "combine_bwd" in name:
+            return "combine_bwd"
+        return "combine" if not any("combine_kernel" in steps[-1][j][0] for j in range(i)) else "unpermute_sum_dx"
     print("# durations: rocprofv3 --kernel-trace averages per call site; bytes: FETCH_SIZE / WRITE_SIZE passes scaled by the calibration copy;")
     print("# algorithmic bytes: bench.py's figures for the same calls (its GB/s x its ms).  Peak 8000 GB/s.")
     print(f"{'call site':20s} {'kernel':30s} {'avg_us':>8s} {'alg_GB':>8s} {'meas_GB':>8s} {'alg_GB/s':>9s} {'% of peak':>9s} {'meas_GB/s':>10s}")
     for i, (name, _) in enumerate(steps[-1]):
         avg = sum(s[i][1] for s in steps) / len(steps)
-        lab = names[i] if i < len(names) else "-"
+        lab = label_of(i)
         a = alg.get(lab)
         alg_gb = a["gbs"] * a["ms"] / 1e3 if a else float("nan")
         m = meas[i][1] if i < len(meas) else float("nan")

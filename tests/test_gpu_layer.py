@@ -131,3 +131,40 @@ def test_layer_all_fp32_every_element(oracle, name, shared_f):
     errs = {n_: assert_close(host_f64(g_), r_, n_, tol=TOL, reg=None, row_tol=1e-4, row_floor=1e-4 if n_ == "dprob" else 1e-6)
             for n_, g_, r_ in pairs}
     print(name, "fp32", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+@pytest.mark.parametrize("name,shared_f,variant", [("C1", 64, None), ("MID", 0, None), ("C7S", 0, None)])
+@pytest.mark.parametrize("eq2", [False, True])
+def test_layer_gathered_operands_are_bit_identical(oracle, name, shared_f, variant, eq2):
+    """The permute's row move fused into the GEMMs (Sec. 4.3.3): fc1 and its weight gradient read X through the row
+    map, under eq. (2) fc2's two gradients read dY the same way; Xp (and dO) do not exist.  Every tensor of the step
+    is bit-identical to the path that stores them, which the tests above hold against the oracle element by element;
+    Z, dW1 and dW2 are compared with the oracle here again, directly."""
+    from gpu_util import host_f64, assert_close
+    from paper_2603_07685_amd import workloads as wl
+    from paper_2603_07685_amd import layer as L
+    cfg = wl.CONFIGS[name]
+    hin = L.host_inputs(cfg, shared_f=shared_f)
+    a = L.LayerState(cfg, hin, shared_f=shared_f, eq2=eq2, variant=variant)
+    b = L.LayerState(cfg, hin, shared_f=shared_f, eq2=eq2, variant=variant, gather=True)
+    assert b.Xp is None and (b.dO is None) == eq2
+    for st in (a, b):
+        st.step()
+    torch.cuda.synchronize()
+    assert a.ctx.poll_error() == 0 and b.ctx.poll_error() == 0
+    R = int(a.offsets[-1].item())
+    for n in ["row_of", "src_of", "offsets", "counts"]:
+        assert torch.equal(getattr(a, n), getattr(b, n)), n
+    for n in ["Z", "A", "O", "dZ", "dXp"]:
+        assert torch.equal(getattr(a, n)[:R].view(torch.int16), getattr(b, n)[:R].view(torch.int16)), n
+    for n in ["Y", "dX", "dW1", "dW2"]:
+        assert torch.equal(getattr(a, n).view(torch.int16), getattr(b, n).view(torch.int16)), n
+    assert torch.equal(a.dprob.view(torch.int32), b.dprob.view(torch.int32))
+    o_idx, o_prob, _ = _oracle_route(oracle, cfg, hin["logits"])
+    fwd, bwd = (oracle.layer_forward_eq2, oracle.layer_backward_eq2) if eq2 else (oracle.layer_forward, oracle.layer_backward)
+    fw = fwd(hin["X"], o_idx, o_prob, hin["W1"], hin["W2"], cfg.E, cfg.align, hin.get("Ws1"), hin.get("Ws2"))
+    bw = bwd(fw, hin["X"], o_prob, hin["W1"], hin["W2"], hin["dY"], hin.get("Ws1"), hin.get("Ws2"))
+    assert fw.R == R
+    assert_close(host_f64(b.Z[:R]), fw.Z, "Z")
+    assert_close(host_f64(b.dW1), bw.dW1, "dW1", reg=_chain_reg("dW1"))
+    assert_close(host_f64(b.dW2), bw.dW2, "dW2", reg=_chain_reg("dW2"))
