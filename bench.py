@@ -81,6 +81,8 @@ def parse():
     ap.add_argument("--gather", action="store_true",
                     help="bf16 workloads: no permuted copy of the tokens (with --eq2: nor of dY); the GEMMs that would read it "
                          "fetch the rows of X / dY through the row map")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed step and the box reference (profiler runs: no second pass with gathered operands)")
     ap.add_argument("--eq2", action="store_true",
                     help="memory-efficient permutation: routing weights applied in the fc1 epilogue, plain-sum combine")
     return ap.parse_args()
@@ -413,7 +415,7 @@ def main():
         gms = g0.elapsed_time(g1) / args.steps
         assert st.ctx.poll_error() == 0
         out["graph"] = {"ms_per_step": round(gms, 4), "tflops": round(flops / gms / 1e9, 2)}
-    if not (cfg.fp8 or cfg.mx) and not args.gather and not args.variant:
+    if not (cfg.fp8 or cfg.mx) and not args.gather and not args.variant and not args.no_extras:
         # the same step with the permute's row move fused into the GEMMs that read the permuted tokens (no bf16 Xp; with
         # --eq2 no dO either): bit-identical results (tests/test_gpu_layer.py), reported beside the figure above, which
         # keeps the stand-alone permute kernel in the timed step
