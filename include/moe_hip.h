@@ -234,7 +234,8 @@ moe_status moe_permute_static(void* stream, const void* X, moe_dtype dt,
  * amax below 2^-60 alternate with blocks near the top of the bf16 range).  N and K must be multiples of
  * 128 (fp8) / 16 (bf16); in bf16 the contraction dimension of fwd (K) and of
  * dgrad (N) must also be a multiple of 64 (one 128-byte operand row per stage);
- * wgrad contracts over the expert's rows, any count.  Sizes outside these limits
+ * wgrad contracts over the expert's rows, any count.  N, K <= 2^24 and N*K <= 2^31 elements per
+ * expert (32-bit offsets inside one expert's weights).  Sizes outside these limits
  * return MOE_ERR_UNSUPPORTED and touch nothing.  dt = MOE_F32: every operand and result is fp32
  * (fp32 accumulation in increasing contraction index; wgrad needs out_dt = MOE_F32; any N, K >= 1);
  * a plain one-thread-per-output path for parity runs at the 1e-5 level on small layers, not tuned.

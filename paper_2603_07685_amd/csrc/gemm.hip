@@ -509,6 +509,16 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
     uint32_t po8[G_ROW ? 8 : 1] = {};   // gathered row-major P: one offset per chunk
     uint32_t gv[G_CM ? 8 : 1] = {};     // gathered contraction-major operand: the row offsets of the chunks about to be loaded
     uint32_t p_cstride = 0, q_cstride = 0;
+    // the buffer descriptor of each operand at the stage being loaded (set by the stage's first chunk, see load_one),
+    // and what it is made from: bytes per row and the largest whole-row count below 4 GB (contraction-major operands),
+    // the byte count of the tile's tensor from its stage-0 base on, clamped (row-major operands; set with the tile),
+    // the size of a gathered tensor
+    uint32_t d_lo[2] = {0, 0}, d_hi[2] = {0, 0}, d_rec[2] = {0, 0};
+    const uint32_t p_rowb = (uint32_t)(((MODE == GG_FWD) ? K : N) * ES), q_rowb = (uint32_t)(K * ES);
+    const uint32_t p_rowcap = __builtin_amdgcn_readfirstlane(0xffffffffu / p_rowb);
+    const uint32_t q_rowcap = __builtin_amdgcn_readfirstlane(0xffffffffu / q_rowb);
+    const uint32_t g_total = (uint32_t)a.g_T * g_rowb;
+    uint32_t p_rec0 = 0, q_rec0 = 0;
     int64_t p_step = 0, q_step = 0;  // byte advance per stage
     const float* sc_src = nullptr;   // fp8: this lane's scale for block 0
     int64_t sc_step = 0;             // fp8: element advance per block
@@ -649,6 +659,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
             const int ldp = (MODE == GG_FWD) ? K : N;
             p_step = GG_ROWB;
             p_base = (const char*)a.P + (int64_t)i0 * ldp * ES;
+            {   // rows of the activation tensor from the tile's first row up to its capacity
+                const int64_t tot = (a.Rcap - i0) * (int64_t)ldp * ES;
+                p_rec0 = __builtin_amdgcn_readfirstlane(tot > 0xffffffffLL ? 0xffffffffu : (uint32_t)tot);
+            }
             p_cstride = (uint32_t)(16 * ldp * ES);
 #pragma unroll
             for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
@@ -684,6 +698,10 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
         } else {
             q_step = GG_ROWB;
             q_base = (const char*)a.Q + (int64_t)e * N * K * ES;
+            {   // the weights of this expert
+                const int64_t tot = (int64_t)N * K * ES;
+                q_rec0 = __builtin_amdgcn_readfirstlane(tot > 0xffffffffLL ? 0xffffffffu : (uint32_t)tot);
+            }
             q_cstride = (uint32_t)(16 * K * ES);
 #pragma unroll
             for (int i = 0; i < (NW == 4 ? 2 : CH); ++i) {
@@ -841,30 +859,37 @@ __global__ __launch_bounds__(NW * 64, 1) __attribute__((amdgpu_waves_per_eu(1, N
                              : g_row ? po8[i]
                              : (isq && SWZ3) ? qo2[(i & 1) + 2 * (i >> 2)] + (uint32_t)((i >> 1) & 1) * q_cstride
                                              : (isq ? qo2[i & 1] : po2[i & 1]) + (uint32_t)(i >> 1) * (isq ? q_cstride : p_cstride);
-        const char* base = isq ? q_base + kt * q_step : p_base + kt * p_step;  // wave-uniform
-        const bool cmaj = isq ? Q_CMAJ : P_CMAJ;
-        int64_t bytes;  // from the base to the end of what may be read
-        if (g_cm) {
-            bytes = (int64_t)a.g_T * g_rowb;
-        } else if (g_row) {
-            bytes = kt >= KT ? 0 : (int64_t)a.g_T * g_rowb - kt * GG_ROWB;
-        } else if (cmaj) {
-            const int ld = (isq || MODE == GG_DGRAD) ? K : N;  // row length of the contraction-major operand
-            bytes = (int64_t)max(c_hi - c_lo - kt * BKE, 0) * ld * ES;
-        } else if (kt >= KT) {
-            bytes = 0;
-        } else if (isq) {  // weights of this expert: rows (output columns) up to N
-            bytes = (int64_t)N * K * ES - kt * GG_ROWB;
-        } else {           // rows of the activation tensor up to its capacity
-            bytes = (a.Rcap - i0) * (int64_t)((MODE == GG_FWD) ? K : N) * ES - kt * GG_ROWB;
+        if (i == 0) {
+            // The first chunk of an operand in a stage builds the descriptor the other seven share: base = the operand
+            // at this stage; record count = the bytes from there to the end of what may be read, in 32-bit scalar
+            // arithmetic (counts above 4 GB are clamped: lane offsets are tile-relative and far below that).  The stage
+            // number passes through an empty asm so that this arithmetic stays in the MFMA gap of this chunk: hoisted
+            // to the top of the loop body, the descriptors of two stages were some fifty scalar and 64-bit vector
+            // compare instructions in front of a single MFMA.
+            int ks = kt;
+            asm volatile("" : "+s"(ks));
+            // (wave-uniform; the byte advance per stage fits 32 bits, so the product is one 32 x 32 -> 64 multiplication)
+            const char* base = isq ? q_base + (uint64_t)(uint32_t)ks * (uint32_t)q_step : p_base + (uint64_t)(uint32_t)ks * (uint32_t)p_step;
+            const bool cmaj = isq ? Q_CMAJ : P_CMAJ;
+            uint32_t records;
+            if (g_cm) {
+                records = g_total;
+            } else if (g_row) {
+                records = ks >= KT ? 0u : g_total - (uint32_t)ks * GG_ROWB;
+            } else if (cmaj) {   // whole rows up to the end of the contraction range
+                const uint32_t left = (uint32_t)max(c_hi - c_lo - ks * BKE, 0);
+                records = min(left, isq ? q_rowcap : p_rowcap) * (isq ? q_rowb : p_rowb);
+            } else {             // row-major: the tensor from this stage's first byte on; nothing behind the last stage
+                records = ks >= KT ? 0u : (isq ? q_rec0 : p_rec0) - (uint32_t)ks * GG_ROWB;
+            }
+            // (readfirstlane: free for values already in scalar registers, and the promise of uniformity the descriptor needs)
+            const uint64_t b = (uint64_t)base;
+            d_lo[isq] = __builtin_amdgcn_readfirstlane((uint32_t)b);
+            d_hi[isq] = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+            d_rec[isq] = __builtin_amdgcn_readfirstlane(records);
         }
-        uint32_t records = bytes > 0xffffffffLL ? 0xffffffffu : (uint32_t)bytes;
-        // (readfirstlane: free for values already in scalar registers, and the promise of uniformity the descriptor needs)
-        const uint64_t b = (uint64_t)base;
-        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-        records = __builtin_amdgcn_readfirstlane(records);
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, (int)records, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(((uint64_t)d_hi[isq] << 32) | d_lo[isq]), 0, (int)d_rec[isq], 0x00020000);
         R[idx] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
     };
     auto store_one = [&](char* sp, char* sq, int idx) __attribute__((always_inline)) {
@@ -2057,6 +2082,10 @@ static moe_status gg_check_common(moe_ctx* ctx, const char* who, const void* p, 
     if (dt != MOE_BF16 && (N % 128 || K % 128))
         MOE_FAIL(ctx, MOE_ERR_ARG, "%s: fp8 needs N and K to be multiples of 128 (block scales)", who);
     if (N % 8 || K % 8) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: N and K must be multiples of 8 (16-byte rows)", who);
+    // (the kernels advance their operands by 128 rows of N or K elements per stage in 32-bit arithmetic, and address
+    // one expert's weights with 32-bit offsets)
+    if (N > (1 << 24) || K > (1 << 24) || (int64_t)N * K * 2 > 0xffffffffLL)
+        MOE_FAIL(ctx, MOE_ERR_UNSUPPORTED, "%s: N, K up to 2^24 and N*K up to 2^31 elements per expert", who);
     return MOE_OK;
 }
 
