@@ -337,7 +337,8 @@ moe_status moe_grouped_gemm_dgrad_weighted(moe_ctx* ctx, void* stream, const voi
  *               G [T,N] and dC[r,:] = G[src_of[r]/k,:].  The other operand is read as it lies, [Rcap, .].
  * Limits (MOE_ERR_UNSUPPORTED otherwise): T * row bytes <= 0xE0000000, Rcap < 2^29, T*k*k < 2^30 (32-bit
  * offsets inside the gathered tensor; the division by k is a multiplication).  Every src_of[r] >= 0 must be
- * below T*k (moe_permute's are); larger entries read zeros.
+ * below T*k, as moe_permute's are (the fetch is bounds-checked against the T rows, so a larger entry cannot
+ * fault, but what it reads is unspecified).
  */
 typedef enum { MOE_GATHER_A = 0, MOE_GATHER_DC = 1 } moe_gather;
 moe_status moe_grouped_gemm_fwd_gather(moe_ctx* ctx, void* stream, const void* X, int T, const int32_t* src_of,
