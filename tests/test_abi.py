@@ -63,3 +63,21 @@ def test_header_is_plain_c_and_cxx():
     hdr = os.path.join(ROOT, "include", "moe_hip.h")
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr])
     subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", hdr])
+
+
+def test_row_map_division_by_multiplication():
+    """The gathered GEMMs turn a map entry s = t*k + slot into its token t = s / k with one multiplication,
+    t = ((2 s + 1) * ceil(2^31 / k)) >> 32, and the host admits only T*k*k < 2^30.  The identity, checked in exact
+    integer arithmetic for every k up to 64 (and a few large ones) on the extremes of the admitted range and on random
+    entries: a wrong rounding of the constant, or a bound that is too generous, fails here."""
+    import random
+    rnd = random.Random(7)
+    for k in list(range(1, 65)) + [100, 127, 128, 255, 1000, 4096]:
+        m = ((1 << 31) + k - 1) // k
+        assert m < (1 << 32)
+        top = ((1 << 30) - 1) // k            # s * k < 2^30 at most (s < T*k and T*k*k < 2^30)
+        cases = {0, 1, k - 1, k, k + 1, top, top - 1, max(top - k, 0), (top // k) * k, max((top // k) * k - 1, 0)}
+        cases |= {rnd.randrange(0, top + 1) for _ in range(2000)}
+        for s in cases:
+            assert 2 * s + 1 < (1 << 32)
+            assert ((2 * s + 1) * m) >> 32 == s // k, (k, s)
