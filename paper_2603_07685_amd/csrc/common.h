@@ -65,11 +65,42 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // (fp32 division, clamp to +-448, hardware round-to-nearest-even conversion).  Shared by the quantiser kernels and
 // the GEMM epilogues that quantise their own output, so both produce the same bits.
 __device__ __forceinline__ float block_scale(float amax) { return amax > 0.0f ? amax / 448.0f : 1.0f; }
+// x / scale without a division per element.  The quantisers are bound by vector arithmetic when every element pays the
+// dozen instructions of a correctly rounded fp32 division, so the division is done once per block, r = 1 / scale, and
+// an element costs a product and two fused multiply-adds: q0 = x r, q = fma(fma(-q0, scale, x), r, q0).  With r the
+// correctly rounded reciprocal, q0 is a faithful quotient, the inner fma is the exact residual x - q0 scale, and the
+// corrected q is the correctly rounded quotient (Markstein's division theorem), i.e. bit for bit what x / scale gives,
+// as long as nothing under- or overflows on the way.  That holds for scales in [2^-40, 2^120] (block maxima from about
+// 2^-31 up to the top of the bf16 range): r is normal; the residual of an element of magnitude 2^-77 or more is exact
+// and a normal number whenever it matters (a residual below 2^-126 means q0 was already the correctly rounded
+// quotient, so it would not matter even if denormals were flushed); a smaller element has a quotient below 2^-37, and
+// whatever fp32 value comes out near that converts to the code 0 like the exact one (E4M3's smallest step is 2^-9).
+// A wave in which any lane holds a scale outside the range takes the plain division for that piece (quant_fast_ok +
+// a ballot: a uniform branch).
+__device__ __forceinline__ bool quant_fast_ok(float scale) { return scale >= 0x1p-40f && scale <= 0x1p120f; }
+__device__ __forceinline__ bool quant_fast_all(bool ok) { return __builtin_amdgcn_ballot_w64(!ok) == 0; }
+__device__ __forceinline__ float quant_div(float x, float scale, float rcp) {
+    const float q0 = x * rcp;
+    // (the sign is x's: the scale is positive, and for x = -0 the sum of the two zeros would come out positive)
+    return __builtin_copysignf(__builtin_fmaf(__builtin_fmaf(-q0, scale, x), rcp, q0), x);
+}
 __device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d, float scale) {
-    a = __builtin_fminf(__builtin_fmaxf(a / scale, -448.0f), 448.0f);
-    b = __builtin_fminf(__builtin_fmaxf(b / scale, -448.0f), 448.0f);
-    c = __builtin_fminf(__builtin_fmaxf(c / scale, -448.0f), 448.0f);
-    d = __builtin_fminf(__builtin_fmaxf(d / scale, -448.0f), 448.0f);
+    const float rcp = 1.0f / scale;
+    if (quant_fast_all(quant_fast_ok(scale))) {
+        a = quant_div(a, scale, rcp);
+        b = quant_div(b, scale, rcp);
+        c = quant_div(c, scale, rcp);
+        d = quant_div(d, scale, rcp);
+    } else {
+        a = a / scale;
+        b = b / scale;
+        c = c / scale;
+        d = d / scale;
+    }
+    a = __builtin_fminf(__builtin_fmaxf(a, -448.0f), 448.0f);
+    b = __builtin_fminf(__builtin_fmaxf(b, -448.0f), 448.0f);
+    c = __builtin_fminf(__builtin_fmaxf(c, -448.0f), 448.0f);
+    d = __builtin_fminf(__builtin_fmaxf(d, -448.0f), 448.0f);
     int w = 0;
     w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, w, false);
     w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);

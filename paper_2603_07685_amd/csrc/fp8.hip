@@ -78,12 +78,27 @@ __global__ __launch_bounds__(256) void quant_128x1_kernel(const u32x4_t* __restr
         sd[0] = f32x4_t{s[0], s[1], s[2], s[3]};
         sd[1] = f32x4_t{s[4], s[5], s[6], s[7]};
         u32x2_t* dst = q + rb * 128 * vpr + vc;
+        float rc[8];   // (one division per column block, then a product and two fmas per element: see quant_div)
+        bool fast = true;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            rc[i] = 1.0f / s[i];
+            fast &= quant_fast_ok(s[i]);
+        }
+        fast = quant_fast_all(fast);
         for (int r = 0; r < 128; ++r) {
             const u32x4_t v = src[(int64_t)r * vpr];
             float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
                           bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+            if (fast) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = __builtin_fminf(__builtin_fmaxf(x[i] / s[i], -448.0f), 448.0f);
+                for (int i = 0; i < 8; ++i) x[i] = quant_div(x[i], s[i], rc[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] = x[i] / s[i];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = __builtin_fminf(__builtin_fmaxf(x[i], -448.0f), 448.0f);
             int w0 = 0, w1 = 0;
             w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w0, false);
             w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w0, true);
@@ -268,11 +283,16 @@ __global__ __launch_bounds__(256) void fp8_quant_rowcol_kernel(const u32x4_t* __
     }
     if (q_col) {
         __syncthreads();
-        float sc[8];
+        float sc[8], rc[8];
+        bool fast = true;
         const int cb = 8 * (lane & 15);
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
+        for (int c = 0; c < 8; ++c) {
             sc[c] = block_scale(fmaxf(fmaxf(cmax[0][cb + c], cmax[1][cb + c]), fmaxf(cmax[2][cb + c], cmax[3][cb + c])));
+            rc[c] = 1.0f / sc[c];
+            fast &= quant_fast_ok(sc[c]);
+        }
+        fast = quant_fast_all(fast);   // (see quant_div: one division per column block instead of one per element)
         if (wave == 0 && lane < 16) {
             f32x4_t* sd = (f32x4_t*)(s_col + rt * cols + ct * 128 + cb);
             sd[0] = f32x4_t{sc[0], sc[1], sc[2], sc[3]};
@@ -282,8 +302,15 @@ __global__ __launch_bounds__(256) void fp8_quant_rowcol_kernel(const u32x4_t* __
         for (int i = 0; i < 8; ++i) {
             float v[8] = {bf16_lo(x[i].x), bf16_hi(x[i].x), bf16_lo(x[i].y), bf16_hi(x[i].y),
                           bf16_lo(x[i].z), bf16_hi(x[i].z), bf16_lo(x[i].w), bf16_hi(x[i].w)};
+            if (fast) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) v[c] = __builtin_fminf(__builtin_fmaxf(v[c] / sc[c], -448.0f), 448.0f);
+                for (int c = 0; c < 8; ++c) v[c] = quant_div(v[c], sc[c], rc[c]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) v[c] = v[c] / sc[c];
+            }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) v[c] = __builtin_fminf(__builtin_fmaxf(v[c], -448.0f), 448.0f);
             int w0 = 0, w1 = 0;
             w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], w0, false);
             w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], w0, true);

@@ -155,6 +155,56 @@ def test_quantize_rowcol_gather_bit_exact(B, ctx, oracle, with_scale):
     assert not qr[R:].any() and not qc[R:].any()                                     # beyond the live rows: untouched
 
 
+def test_quantisers_one_division_per_block_bit_exact(B, ctx, oracle):
+    """The quantisers divide once per block (r = 1 / scale) and correct the product x r with the exact residual; that
+    must give the bits of the fp32 division x / scale the recipe is defined with.  Inputs chosen against it: block
+    maxima from far below the range in which the short form is used (those blocks must take the plain division, also
+    when they share a wave with ordinary ones) up to the top of the bf16 range; elements on and next to the halfway
+    points between neighbouring E4M3 values (where one unit in the last place of the quotient changes the code);
+    denormal elements inside ordinary blocks; all four kernels (1x128, 128x1, both in one pass, 128x128)."""
+    from gpu_util import dev_bf16
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(99)
+    rows, cols = 1024, 1024
+    # E4M3 values and the midpoints between neighbours, as multiples of amax / 448
+    e4 = np.array(sorted({(1 + m / 8) * 2.0 ** e for e in range(-6, 9) for m in range(8)} | {m / 8 * 2.0 ** -6 for m in range(8)}))
+    e4 = e4[e4 <= 448]
+    mids = (e4[1:] + e4[:-1]) / 2
+    pts = np.concatenate([e4, mids, mids * (1 + 2.0 ** -8), mids * (1 - 2.0 ** -8)])
+    X = g.choice(pts, size=(rows, cols)) * g.choice([-1.0, 1.0], size=(rows, cols)) / 448.0
+    X = X * (1 + g.uniform(-1, 1, size=(rows, cols)) * 2.0 ** g.integers(-20, -6, size=(rows, cols)))   # small nudges
+    # per 128x128 tile a magnitude: 2^-120 .. 2^126 (the short form is used from about 2^-31 up)
+    mag = 2.0 ** g.choice([-120.0, -60.0, -41.0, -32.0, -31.0, -30.0, -10.0, 0.0, 3.0, 40.0, 100.0, 126.0], size=(rows // 128, cols // 128))
+    X = X * np.kron(mag, np.ones((128, 128)))
+    X[:, ::7] *= 448.0                                   # most rows and columns reach their block maximum somewhere
+    X[5::64, 3::32] = 1e-40                              # denormal elements inside ordinary blocks
+    X[256:384, 128:256] = 0.0                            # an all-zero tile
+    with np.errstate(over="ignore"):
+        Xh = wl.bf16_round(np.clip(X, -3e38, 3e38).astype(np.float32))
+    Xd = dev_bf16(Xh)
+    q, s = _quant(B, ctx, Xd, B.Q_1x128)
+    qo, so = oracle.fp8_quant_1x128(Xh)
+    assert np.array_equal(s.cpu().numpy(), so) and np.array_equal(q.cpu().numpy(), qo)
+    q, s = _quant(B, ctx, Xd, B.Q_128x1)
+    qc_o, sc_o = oracle.fp8_quant_128x1(Xh)
+    assert np.array_equal(s.cpu().numpy(), sc_o) and np.array_equal(q.cpu().numpy(), qc_o)
+    qr = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+    sr = torch.zeros((rows, cols // 128), dtype=torch.float32, device="cuda")
+    qc = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+    sc = torch.zeros((rows // 128, cols), dtype=torch.float32, device="cuda")
+    B.moe_fp8_quantize_rowcol(ctx, Xd, rows, cols, None, qr, sr, qc, sc)
+    torch.cuda.synchronize()
+    assert np.array_equal(qr.cpu().numpy(), qo) and np.array_equal(sr.cpu().numpy(), so)
+    assert np.array_equal(qc.cpu().numpy(), qc_o) and np.array_equal(sc.cpu().numpy(), sc_o)
+    W = Xh.reshape(1, rows, cols)
+    q, s = _quant(B, ctx, dev_bf16(W), B.Q_128x128)
+    torch.cuda.synchronize()
+    qw_o, sw_o = oracle.fp8_quant_128x128(W)
+    assert np.array_equal(s.cpu().numpy(), sw_o) and np.array_equal(q.cpu().numpy(), qw_o)
+    # the inputs do what they were made for: codes of every magnitude class, blocks on both sides of the range
+    assert len(np.unique(qo)) > 200 and (so < 2.0 ** -40).any() and (so > 2.0 ** 100).any()
+
+
 def test_quantize_128x128_bit_exact(B, ctx, oracle):
     from gpu_util import dev_bf16
     from paper_2603_07685_amd import workloads as wl
