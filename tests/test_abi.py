@@ -81,3 +81,13 @@ def test_row_map_division_by_multiplication():
         for s in cases:
             assert 2 * s + 1 < (1 << 32)
             assert ((2 * s + 1) * m) >> 32 == s // k, (k, s)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is the one-GPU path: bench.py --gpus N with N > 1 exits with a message that says so, before anything
+    touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one-GPU" in r.stderr and "--gpus 1" in r.stderr and r.stdout.strip() == ""
