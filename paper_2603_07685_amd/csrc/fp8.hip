@@ -234,20 +234,33 @@ __global__ __launch_bounds__(256) void fp8_quant_rowcol_kernel(const u32x4_t* __
     const int64_t v0 = (row0 + wave * 32 + (lane >> 4)) * vpr + ct * 16 + (lane & 15);
     u32x4_t x[8];
     if (GATHER) {
+        // Three passes, so that the eight map entries, then the eight rows, then the eight weights are each in
+        // flight together (one pass per piece would chain sixteen memory latencies per lane), and no branch: a lane
+        // whose row is padding reads the first 16 bytes of this tile's map entries instead, which always exist,
+        // and drops them.
+        const void* const spare = src_of + row0;
+        int32_t sidx[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sidx[i] = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int32_t sidx = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
-            x[i] = u32x4_t{0, 0, 0, 0};
-            if (sidx >= 0) {
-                const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx * k_magic) >> 40);  // sidx / k, exact below 2^31
-                x[i] = X[tok * vpr + ct * 16 + (lane & 15)];
-                if (pair_scale) {
-                    const float sc = pair_scale[sidx];
-                    x[i] = u32x4_t{scale2_bf16_bw(x[i].x, sc), scale2_bf16_bw(x[i].y, sc), scale2_bf16_bw(x[i].z, sc),
-                                   scale2_bf16_bw(x[i].w, sc)};
-                }
-            }
+            const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx[i] * k_magic) >> 40);  // sidx / k, exact below 2^31
+            uint64_t live_at = (uint64_t)(X + (tok * vpr + ct * 16 + (lane & 15)));
+            asm volatile("" : "+v"(live_at));  // (formed for every lane: a select then, not a branch around the multiplications)
+            x[i] = *(const u32x4_t*)(sidx[i] >= 0 ? live_at : (uint64_t)spare);
         }
+        if (pair_scale) {
+            float psc[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) psc[i] = *(sidx[i] >= 0 ? pair_scale + sidx[i] : (const float*)spare);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                x[i] = u32x4_t{scale2_bf16_bw(x[i].x, psc[i]), scale2_bf16_bw(x[i].y, psc[i]), scale2_bf16_bw(x[i].z, psc[i]),
+                               scale2_bf16_bw(x[i].w, psc[i])};
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (sidx[i] < 0) x[i] = u32x4_t{0, 0, 0, 0};
     } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i) x[i] = X[v0 + (int64_t)i * 4 * vpr];
@@ -443,20 +456,33 @@ __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __r
     const int64_t v0 = (row0 + wave * 32 + (lane >> 4)) * vpr + ct * 16 + (lane & 15);
     u32x4_t x[8];
     if (GATHER) {
+        // Three passes, so that the eight map entries, then the eight rows, then the eight weights are each in
+        // flight together (one pass per piece would chain sixteen memory latencies per lane), and no branch: a lane
+        // whose row is padding reads the first 16 bytes of this tile's map entries instead, which always exist,
+        // and drops them.
+        const void* const spare = src_of + row0;
+        int32_t sidx[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sidx[i] = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int32_t sidx = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
-            x[i] = u32x4_t{0, 0, 0, 0};
-            if (sidx >= 0) {
-                const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx * k_magic) >> 40);  // sidx / k, exact below 2^31
-                x[i] = X[tok * vpr + ct * 16 + (lane & 15)];
-                if (pair_scale) {
-                    const float sc = pair_scale[sidx];
-                    x[i] = u32x4_t{scale2_bf16(x[i].x, sc), scale2_bf16(x[i].y, sc), scale2_bf16(x[i].z, sc),
-                                   scale2_bf16(x[i].w, sc)};
-                }
-            }
+            const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx[i] * k_magic) >> 40);  // sidx / k, exact below 2^31
+            uint64_t live_at = (uint64_t)(X + (tok * vpr + ct * 16 + (lane & 15)));
+            asm volatile("" : "+v"(live_at));  // (formed for every lane: a select then, not a branch around the multiplications)
+            x[i] = *(const u32x4_t*)(sidx[i] >= 0 ? live_at : (uint64_t)spare);
         }
+        if (pair_scale) {
+            float psc[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) psc[i] = *(sidx[i] >= 0 ? pair_scale + sidx[i] : (const float*)spare);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                x[i] = u32x4_t{scale2_bf16(x[i].x, psc[i]), scale2_bf16(x[i].y, psc[i]), scale2_bf16(x[i].z, psc[i]),
+                               scale2_bf16(x[i].w, psc[i])};
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (sidx[i] < 0) x[i] = u32x4_t{0, 0, 0, 0};
     } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i) x[i] = X[v0 + (int64_t)i * 4 * vpr];
