@@ -236,9 +236,9 @@ __global__ __launch_bounds__(256) void fp8_quant_rowcol_kernel(const u32x4_t* __
     if (GATHER) {
         // Three passes, so that the eight map entries, then the eight rows, then the eight weights are each in
         // flight together (one pass per piece would chain sixteen memory latencies per lane), and no branch: a lane
-        // whose row is padding reads the first 16 bytes of this tile's map entries instead, which always exist,
-        // and drops them.
-        const void* const spare = src_of + row0;
+        // whose row is padding reads 16 aligned bytes of this tile's 512 bytes of map entries instead, which always
+        // exist, and drops them.
+        const void* const spare = (const void*)(((uintptr_t)(src_of + row0) + 15) & ~(uintptr_t)15);
         int32_t sidx[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) sidx[i] = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
@@ -458,9 +458,9 @@ __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __r
     if (GATHER) {
         // Three passes, so that the eight map entries, then the eight rows, then the eight weights are each in
         // flight together (one pass per piece would chain sixteen memory latencies per lane), and no branch: a lane
-        // whose row is padding reads the first 16 bytes of this tile's map entries instead, which always exist,
-        // and drops them.
-        const void* const spare = src_of + row0;
+        // whose row is padding reads 16 aligned bytes of this tile's 512 bytes of map entries instead, which always
+        // exist, and drops them.
+        const void* const spare = (const void*)(((uintptr_t)(src_of + row0) + 15) & ~(uintptr_t)15);
         int32_t sidx[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) sidx[i] = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];

@@ -132,7 +132,12 @@ def test_mx_quantize_rowcol_gather_bit_exact(B, ctx, oracle, with_scale):
     qc = torch.zeros((Rcap, cols), dtype=torch.uint8, device="cuda")
     ec = torch.zeros((Rcap // 128, cols, 4), dtype=torch.uint8, device="cuda")
     live = torch.tensor([R], dtype=torch.int32, device="cuda")
-    B.moe_mx_quantize_rowcol_gather(ctx, dev_bf16(Xh), dev(src), k, dev(p) if with_scale else None, E if with_scale else 1,
+    src_dev = dev(src)
+    if with_scale:  # the map as a view that starts 4 bytes off a 16-byte boundary (padding lanes read spare map bytes)
+        buf = torch.empty(Rcap + 1, dtype=torch.int32, device="cuda")
+        buf[1:].copy_(src_dev)
+        src_dev = buf[1:]
+    B.moe_mx_quantize_rowcol_gather(ctx, dev_bf16(Xh), src_dev, k, dev(p) if with_scale else None, E if with_scale else 1,
                                     Rcap, cols, live, qr, er, qc, ec)
     torch.cuda.synchronize()
     qr_o, er_o = oracle.mx_quant_1x32(V)
