@@ -83,6 +83,22 @@ def test_row_map_division_by_multiplication():
             assert ((2 * s + 1) * m) >> 32 == s // k, (k, s)
 
 
+def test_quantiser_row_map_division_by_multiplication():
+    """The gathering quantisers divide a map entry by k (k <= 32 admitted) as (s * ceil(2^40 / k)) >> 40 in 64-bit
+    arithmetic, for any non-negative 32-bit entry: exact on the extremes and on random entries, and the product
+    stays below 2^64."""
+    import random
+    rnd = random.Random(11)
+    for k in range(1, 33):
+        m = ((1 << 40) + k - 1) // k
+        top = (1 << 31) - 1
+        cases = {0, 1, k - 1, k, k + 1, top, top - 1, top - k, (top // k) * k, (top // k) * k - 1}
+        cases |= {rnd.randrange(0, top + 1) for _ in range(2000)}
+        for s in cases:
+            assert s * m < (1 << 64)
+            assert (s * m) >> 40 == s // k, (k, s)
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build is the one-GPU path: bench.py --gpus N with N > 1 exits with a message that says so, before anything
     touches a GPU."""
