@@ -209,12 +209,22 @@ extern "C" moe_status moe_fp8_quantize(moe_ctx* ctx, void* stream, const void* X
 // Scales and codes are formed exactly as in the single-direction kernels above (amax / 448, fp32 division,
 // hardware conversion), so both copies are bit-identical to theirs.
 // ---------------------------------------------------------------------------
+// floor(s / k) for a map entry 0 <= s < 2^31 as one widening multiplication (division by an invariant integer,
+// rounded-up constant): with l = ceil(log2 k) and m = ceil(2^(31 + l) / k) <= 2^32 - 1, (s * m) >> (31 + l) == s / k
+// for every such s, and the product stays below 2^63.
+struct gather_div_t { uint32_t m; int sh; };
+static inline gather_div_t gather_div(int k) {
+    int l = 0;
+    while ((1 << l) < k) ++l;
+    return gather_div_t{(uint32_t)(((1ull << (31 + l)) + (uint64_t)k - 1) / (uint64_t)k), 31 + l};
+}
+
 __device__ __forceinline__ uint32_t scale2_bf16_bw(uint32_t w, float sc) { return pack_bf16(sc * bf16_lo(w), sc * bf16_hi(w)); }
 
 template <bool GATHER>
 __global__ __launch_bounds__(256) void fp8_quant_rowcol_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
                                                                const int32_t* __restrict__ rows_dev,
-                                                               const int32_t* __restrict__ src_of, uint64_t k_magic,
+                                                               const int32_t* __restrict__ src_of, uint32_t k_magic, int k_shift,
                                                                const float* __restrict__ pair_scale, int groups,
                                                                u32x2_t* __restrict__ q_row, float* __restrict__ s_row,
                                                                u32x2_t* __restrict__ q_col, float* __restrict__ s_col) {
@@ -244,7 +254,7 @@ __global__ __launch_bounds__(256) void fp8_quant_rowcol_kernel(const u32x4_t* __
         for (int i = 0; i < 8; ++i) sidx[i] = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx[i] * k_magic) >> 40);  // sidx / k, exact below 2^31
+            const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx[i] * k_magic) >> k_shift);  // sidx / k (gather_div)
             uint64_t live_at = (uint64_t)(X + (tok * vpr + ct * 16 + (lane & 15)));
             asm volatile("" : "+v"(live_at));  // (formed for every lane: a select then, not a branch around the multiplications)
             x[i] = *(const u32x4_t*)(sidx[i] >= 0 ? live_at : (uint64_t)spare);
@@ -346,11 +356,11 @@ static moe_status fp8_rowcol_launch(moe_ctx* ctx, hipStream_t s, const char* who
     if (nblk > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: too many tiles", who);
     if (src_of)
         hipLaunchKernelGGL(fp8_quant_rowcol_kernel<true>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
-                           rows_dev, src_of, ((1ull << 40) + k - 1) / k, pair_scale, groups, (u32x2_t*)q_row, s_row,
+                           rows_dev, src_of, gather_div(k).m, gather_div(k).sh, pair_scale, groups, (u32x2_t*)q_row, s_row,
                            (u32x2_t*)q_col, s_col);
     else
         hipLaunchKernelGGL(fp8_quant_rowcol_kernel<false>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
-                           rows_dev, nullptr, 0, nullptr, 1, (u32x2_t*)q_row, s_row, (u32x2_t*)q_col, s_col);
+                           rows_dev, nullptr, 0, 0, nullptr, 1, (u32x2_t*)q_row, s_row, (u32x2_t*)q_col, s_col);
     return MOE_OK;
 }
 
@@ -432,7 +442,7 @@ __device__ __forceinline__ uint32_t scale2_bf16(uint32_t w, float sc) { return p
 template <bool GATHER>
 __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __restrict__ X, int64_t rows, int cols,
                                                               const int32_t* __restrict__ rows_dev,
-                                                              const int32_t* __restrict__ src_of, uint64_t k_magic,
+                                                              const int32_t* __restrict__ src_of, uint32_t k_magic, int k_shift,
                                                               const float* __restrict__ pair_scale, int groups,
                                                               u32x2_t* __restrict__ q_row, uint32_t* __restrict__ e8_row,
                                                               u32x2_t* __restrict__ q_col, uint32_t* __restrict__ e8_col) {
@@ -466,7 +476,7 @@ __global__ __launch_bounds__(256) void mx_quant_rowcol_kernel(const u32x4_t* __r
         for (int i = 0; i < 8; ++i) sidx[i] = src_of[row0 + wave * 32 + 4 * i + (lane >> 4)];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx[i] * k_magic) >> 40);  // sidx / k, exact below 2^31
+            const int64_t tok = (int64_t)(((uint64_t)(uint32_t)sidx[i] * k_magic) >> k_shift);  // sidx / k (gather_div)
             uint64_t live_at = (uint64_t)(X + (tok * vpr + ct * 16 + (lane & 15)));
             asm volatile("" : "+v"(live_at));  // (formed for every lane: a select then, not a branch around the multiplications)
             x[i] = *(const u32x4_t*)(sidx[i] >= 0 ? live_at : (uint64_t)spare);
@@ -553,11 +563,11 @@ static moe_status mx_rowcol_launch(moe_ctx* ctx, hipStream_t s, const char* who,
     if (nblk > 0x7fffffffLL) MOE_FAIL(ctx, MOE_ERR_ARG, "%s: too many tiles", who);
     if (src_of)
         hipLaunchKernelGGL(mx_quant_rowcol_kernel<true>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
-                           rows_dev, src_of, ((1ull << 40) + k - 1) / k, pair_scale, groups, (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col,
+                           rows_dev, src_of, gather_div(k).m, gather_div(k).sh, pair_scale, groups, (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col,
                            (uint32_t*)e8_col);
     else
         hipLaunchKernelGGL(mx_quant_rowcol_kernel<false>, dim3((unsigned)nblk), dim3(256), 0, s, (const u32x4_t*)X, rows, cols,
-                           rows_dev, nullptr, 0, nullptr, 1, (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col,
+                           rows_dev, nullptr, 0, 0, nullptr, 1, (u32x2_t*)q_row, (uint32_t*)e8_row, (u32x2_t*)q_col,
                            (uint32_t*)e8_col);
     return MOE_OK;
 }

@@ -84,19 +84,25 @@ def test_row_map_division_by_multiplication():
 
 
 def test_quantiser_row_map_division_by_multiplication():
-    """The gathering quantisers divide a map entry by k (k <= 32 admitted) as (s * ceil(2^40 / k)) >> 40 in 64-bit
-    arithmetic, for any non-negative 32-bit entry: exact on the extremes and on random entries, and the product
-    stays below 2^64."""
+    """The gathering quantisers divide a map entry 0 <= s < 2^31 by k (k <= 32 admitted) as (s * m) >> (31 + l) with
+    l = ceil(log2 k), m = ceil(2^(31 + l) / k): exact on the extremes and on random entries, m fits 32 bits and the
+    product 64 (a constant of the form ceil(2^40 / k) would overflow 64 bits from s = 2^24 k on)."""
     import random
     rnd = random.Random(11)
-    for k in range(1, 33):
-        m = ((1 << 40) + k - 1) // k
+    for k in list(range(1, 33)) + [33, 63, 64, 65, 100, 1000]:
+        l = (k - 1).bit_length()
+        assert (1 << l) >= k and (l == 0 or (1 << (l - 1)) < k)
+        m = ((1 << (31 + l)) + k - 1) // k
+        assert m < (1 << 32)
         top = (1 << 31) - 1
-        cases = {0, 1, k - 1, k, k + 1, top, top - 1, top - k, (top // k) * k, (top // k) * k - 1}
+        cases = {0, 1, k - 1, k, k + 1, top, top - 1, top - k, (top // k) * k, (top // k) * k - 1, 1 << 24, (1 << 24) * k,
+                 (1 << 24) * k - 1}
         cases |= {rnd.randrange(0, top + 1) for _ in range(2000)}
         for s in cases:
+            if s > top:
+                continue
             assert s * m < (1 << 64)
-            assert (s * m) >> 40 == s // k, (k, s)
+            assert (s * m) >> (31 + l) == s // k, (k, s)
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -411,3 +411,33 @@ def test_mx_quantising_epilogue_rejects_bad_requests(B, ctx):
                                     qr, er, torch.zeros_like(qr), ec)
     torch.cuda.synchronize()
     assert ctx.poll_error() != 0
+
+
+def test_mx_quantize_gather_source_rows_beyond_2_pow_24(B, ctx, oracle):
+    """Map entries of 2^24 k and more (a source tensor of more than 16.7 million rows): the division of the entry by k
+    must still be exact (a 2^40 / k constant would wrap around 64 bits there).  k = 1 and k = 3, 128 gathered rows."""
+    from gpu_util import dev
+    from paper_2603_07685_amd import workloads as wl
+    g = np.random.default_rng(77)
+    cols, Rcap = 128, 128
+    for k in (1, 3):
+        T = (1 << 24) + 4096
+        toks = np.sort(g.choice(np.arange((1 << 24) - 64, T), size=100, replace=False)).astype(np.int64)
+        src = np.full(Rcap, -1, np.int32)
+        src[:100] = (toks * k + g.integers(0, k, size=100)).astype(np.int32)
+        rows = wl.bf16_round(g.standard_normal((100, cols)).astype(np.float32))
+        X = torch.zeros((T, cols), dtype=torch.bfloat16, device="cuda")
+        X[torch.from_numpy(toks).cuda()] = torch.from_numpy(rows).cuda().to(torch.bfloat16)
+        V = np.zeros((Rcap, cols), np.float32)
+        V[:100] = rows
+        qr = torch.zeros((Rcap, cols), dtype=torch.uint8, device="cuda")
+        er = torch.zeros((Rcap, cols // 32), dtype=torch.uint8, device="cuda")
+        qc = torch.zeros((Rcap, cols), dtype=torch.uint8, device="cuda")
+        ec = torch.zeros((Rcap // 128, cols, 4), dtype=torch.uint8, device="cuda")
+        B.moe_mx_quantize_rowcol_gather(ctx, X, dev(src), k, None, 1, Rcap, cols, None, qr, er, qc, ec)
+        torch.cuda.synchronize()
+        qr_o, er_o = oracle.mx_quant_1x32(V)
+        qc_o, _ = oracle.mx_quant_32x1(V[None])
+        assert np.array_equal(qr.cpu().numpy(), qr_o) and np.array_equal(er.cpu().numpy(), er_o), k
+        assert np.array_equal(qc.cpu().numpy(), qc_o[0]), k
+        del X
